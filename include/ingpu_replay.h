@@ -1,0 +1,204 @@
+/*
+ * ingpu_replay — device-resident experience replay and Q-learning train step
+ * for AMD MI355X (gfx950).  Plain C ABI.
+ *
+ * The interface follows the paper's problem statement: an experience replay
+ * with two methods, "add" and "sample" (Methods), whose sample call returns
+ * old state, new state, action, reward and is_terminal tensors with all type
+ * casting hidden from the user (Methods), and a train step that takes no
+ * network inputs from the host (Integration with Reinforcement Learning
+ * Algorithm).
+ *
+ * Conventions
+ *  - Ownership: the caller allocates every device buffer (ring storage,
+ *    trainer workspace, sample outputs) and keeps it alive until the matching
+ *    *_destroy call.  The library owns only its host-side handles, one small
+ *    pinned host buffer per trainer, and its HIP graph objects.
+ *  - Streams: `hip_stream` is a hipStream_t passed as void* (NULL = the null
+ *    stream).  All calls are asynchronous on that stream except the ones marked
+ *    "synchronises", which exist for tests and inspection.  One handle must be
+ *    driven from one stream at a time.
+ *  - Status: 0 = done, > 0 = benign (nothing was sampled or trained),
+ *    < 0 = failure; a failing call changes no replay or trainer state.  A
+ *    message for the last failure on the calling thread is returned by
+ *    rp_last_error().  Nothing throws across this boundary.
+ *  - "device" / "host" below say where a pointer must point.
+ */
+#ifndef INGPU_REPLAY_H
+#define INGPU_REPLAY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct replay  replay_t;  /* opaque host handle */
+typedef struct trainer trainer_t; /* opaque host handle */
+
+typedef enum {
+    RP_OK = 0,
+    RP_SKIPPED_BURN_IN = 1, /* burn-in not complete (Related Work: no training during burn-in),
+                               or nothing to sample yet */
+    RP_EINVAL = -1,         /* null pointer, zero size, size beyond a limit, mismatched dims */
+    RP_ENOMEM = -2,         /* a caller-provided buffer is too small / host allocation failed */
+    RP_EHIP = -3,           /* a HIP runtime call failed; see rp_last_error() */
+    RP_ESTATE = -4          /* device-resident state disagrees with the host mirror */
+} rp_status;
+
+/* element type of a stored state */
+enum { RP_F32 = 0, RP_BF16 = 1, RP_U8 = 2 };
+/* RP_PAIR: an experience stores both states, one packed row
+ *          [s(D) | s'(D) | action | reward | is_terminal] (Methods: rows of 2D+3 values).
+ * RP_CHAIN: one state per experience; the new state of slot p is the state in
+ *          slot p+1 (Discussion: halves the memory when states are large). */
+enum { RP_PAIR = 0, RP_CHAIN = 1 };
+enum { RP_HUBER = 0, RP_MSE = 1 };
+enum { RP_SGD = 0, RP_ADAM = 1 };
+
+typedef struct {
+    uint64_t capacity;    /* number of experiences the replay holds (1,000,000 in the paper) */
+    uint32_t state_dim;   /* D: elements per state (27 in the paper)                          */
+    uint32_t state_dtype; /* RP_F32 | RP_BF16 | RP_U8                                         */
+    uint32_t layout;      /* RP_PAIR | RP_CHAIN                                               */
+    uint32_t max_append;  /* largest n a host-sourced replay_append moves in one piece; the
+                             storage holds a device staging area of this many rows (>= 1)     */
+    uint64_t burn_in;     /* sampling and training are refused until this many experiences
+                             have been added in total                                         */
+    uint64_t seed;        /* key of the index generator                                       */
+} replay_config;
+
+/* Bytes of device memory replay_create needs for this configuration (0 if the
+ * configuration is invalid).  Pure host arithmetic. */
+size_t replay_storage_bytes(const replay_config* cfg);
+
+/* Bytes of one stored experience (PAIR: the padded packed row; CHAIN: the padded
+ * state slot plus 9 bytes of side data).  Pure host arithmetic; 0 if invalid. */
+size_t replay_row_bytes(const replay_config* cfg);
+
+/*
+ * Create an empty replay (Methods: fixed size, starts empty) inside
+ * `dev_storage` (device, 256-byte aligned, at least replay_storage_bytes()).
+ * The storage is cleared.  Synchronises.
+ */
+rp_status replay_create(const replay_config* cfg, void* dev_storage, size_t bytes,
+                        replay_t** out);
+
+/* Release the host handle.  Never frees dev_storage. */
+rp_status replay_destroy(replay_t* rp);
+
+/*
+ * "Add" (Methods): append n experiences in first-in first-out order,
+ * overwriting the oldest once the replay is full; a batch that reaches the end
+ * of the storage wraps to slot 0.  Arrays are structure-of-arrays, row-major:
+ * s[n*D], s_next[n*D] of the state type (s_next is ignored and may be NULL for
+ * RP_CHAIN), a[n], r[n], term[n] (any non-zero byte = terminal).
+ * src_is_device = 0: host pointers, moved through the staging area in pieces of
+ * max_append rows; 1: device pointers, read directly by the append kernel and
+ * to be left untouched until the stream reaches it.  n = 0 is a no-op; n >
+ * capacity is RP_EINVAL.
+ */
+rp_status replay_append(replay_t* rp, uint64_t n, const void* s, const void* s_next,
+                        const int32_t* a, const float* r, const uint8_t* term, int src_is_device,
+                        void* hip_stream);
+
+/*
+ * "Sample" (Methods): draw `batch` slot numbers uniformly, with replacement,
+ * from the experiences currently held, and unpack those experiences into
+ * contiguous batch tensors (all device pointers):
+ *   out_s[batch*D], out_s_next[batch*D]  float for RP_F32 states, bf16 bits for
+ *                                        RP_BF16, float = u8/255 for RP_U8;
+ *   out_a[batch] int32, out_r[batch] float, out_term[batch] 0/1 bytes;
+ *   out_idx[batch] the sampled slot numbers (may be NULL).
+ * Draw i of a call is a pure function of (seed, step, i, current size): word
+ * i mod 4 of Philox4x32-10 with key = seed and counter = (i div 4, 0, step),
+ * mapped to floor(word * size / 2^32).  RP_CHAIN draws among the size-1
+ * experiences that already have a successor.  For RP_CHAIN, out_s_next of a
+ * terminal experience holds the next slot's state and is to be masked by the
+ * caller with out_term.
+ * Returns RP_SKIPPED_BURN_IN, writing nothing, before burn-in completes or
+ * while there is nothing to sample.  batch = 0 or batch > 2^24 is RP_EINVAL.
+ */
+rp_status replay_sample_gather(replay_t* rp, uint64_t step, uint32_t batch, void* out_s,
+                               void* out_s_next, int32_t* out_a, float* out_r, uint8_t* out_term,
+                               uint32_t* out_idx, void* hip_stream);
+
+/* Write position, number of experiences held, and experiences ever added, as
+ * read back from the device.  RP_ESTATE if they differ from the host mirror.
+ * Synchronises the device. */
+rp_status replay_get_state(replay_t* rp, uint64_t* head, uint64_t* size, uint64_t* total);
+
+/* Copy n stored experiences starting at slot first_slot (wrapping) to host
+ * arrays, field by field (any may be NULL; s_next is not written for
+ * RP_CHAIN).  States come back in their stored type.  Synchronises. */
+rp_status replay_read_rows(replay_t* rp, uint64_t first_slot, uint64_t n, void* s, void* s_next,
+                           int32_t* a, float* r, uint8_t* term);
+
+typedef struct {
+    uint32_t state_dim;        /* D, must equal the replay's                                   */
+    uint32_t hidden;           /* H: width of the two hidden layers (multiple of 64)           */
+    uint32_t num_actions;      /* A                                                            */
+    uint32_t batch;            /* B experiences per train step                                 */
+    uint32_t param_dtype;      /* RP_F32: fp32 everywhere (replay states RP_F32);
+                                  RP_BF16: bf16 matrix inputs with fp32 accumulation and fp32
+                                  master weights (replay states RP_BF16)                       */
+    uint32_t loss;             /* RP_HUBER (threshold 1) | RP_MSE (half squared error)         */
+    uint32_t opt;              /* RP_SGD | RP_ADAM                                             */
+    uint32_t appends_per_step; /* experiences added by every train_step (0 = none)             */
+    float lr, gamma, beta1, beta2, eps;
+    uint32_t use_graph;        /* 1: the step is replayed as one HIP graph launch              */
+} train_config;
+
+/* number of network parameters: D*H + H + H*H + H + H*A + A */
+size_t train_param_count(const train_config* cfg);
+/* Bytes of device workspace train_create needs (0 if the configuration is invalid). */
+size_t train_workspace_bytes(const train_config* cfg);
+
+/*
+ * Create a trainer for the network D -> H -> H -> A (ReLU after both hidden
+ * layers) on top of a PAIR replay.  host_init_params (host) holds
+ * W1[D*H] b1[H] W2[H*H] b2[H] W3[H*A] b3[A], matrices row-major [in x out].
+ * dev_workspace: device, 256-byte aligned, train_workspace_bytes().  Synchronises.
+ */
+rp_status train_create(const train_config* cfg, replay_t* rp, void* dev_workspace, size_t bytes,
+                       const float* host_init_params, trainer_t** out);
+rp_status train_destroy(trainer_t* tr);
+
+/*
+ * One train step with no network inputs from the host (Integration): append
+ * appends_per_step experiences (arrays as in replay_append; ignored when
+ * appends_per_step = 0), then, once burn-in is complete, sample a batch with
+ * the trainer's own step counter (starts at 0, advances on executed steps
+ * only), gather it, run the network on s and s', form
+ *   y = r + gamma (1 - terminal) max_a' Q(s',a'),  delta = y - Q(s,a)
+ * (Deep Q-Network Model, the update equation, with the target held constant),
+ * take the mean Huber / half-squared loss, backpropagate through Q(s,.) and
+ * apply SGD or Adam.  Returns RP_SKIPPED_BURN_IN when only the append ran.
+ */
+rp_status train_step(trainer_t* tr, const void* s, const void* s_next, const int32_t* a,
+                     const float* r, const uint8_t* term, int src_is_device, void* hip_stream);
+
+/* Test / inspection calls; host destinations, any may be NULL; all synchronise. */
+rp_status train_get_params(trainer_t* tr, float* params);             /* fp32 master weights */
+rp_status train_get_grads(trainer_t* tr, float* grads);               /* of the last step    */
+rp_status train_get_opt_state(trainer_t* tr, float* m, float* v, uint64_t* t, uint64_t* step);
+/* Overwrite weights, Adam moments (NULL = keep), Adam t and the sampling step counter. */
+rp_status train_set_state(trainer_t* tr, const float* params, const float* m, const float* v,
+                          uint64_t t, uint64_t step);
+/* From the last executed step: Q(s,.) [B*A], Q(s',.) [B*A], y[B], delta[B], loss[1],
+ * sampled slot numbers idx[B]. */
+rp_status train_get_last(trainer_t* tr, float* q, float* q_next, float* y, float* delta,
+                         float* loss, uint32_t* idx);
+/* Number of GPU kernels one executed train step launches (graph nodes). */
+rp_status train_kernels_per_step(trainer_t* tr, uint32_t* n);
+
+/* Message for the last failure on this thread ("" if none). */
+const char* rp_last_error(void);
+/* Library version string. */
+const char* rp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* INGPU_REPLAY_H */

@@ -129,10 +129,11 @@ class Ring:
                                            self.burn_in)
         if not self._h:
             raise ValueError("oracle_ring_create rejected the configuration")
+        self._destroy = lib().oracle_ring_destroy
 
     def __del__(self):
         if getattr(self, "_h", None):
-            lib().oracle_ring_destroy(self._h)
+            self._destroy(self._h)
             self._h = None
 
     @property

@@ -1,0 +1,283 @@
+"""Thin ctypes binding of libingpu_replay.so (include/ingpu_replay.h).
+
+Argument marshalling only: every step of the replay and of the train step runs
+in the library's HIP kernels.  PyTorch is used here for device memory and
+streams, nothing else.  If the library is missing or cannot be loaded this
+module raises; there is no fallback path.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libingpu_replay.so")
+
+RP_OK, RP_SKIPPED_BURN_IN = 0, 1
+RP_EINVAL, RP_ENOMEM, RP_EHIP, RP_ESTATE = -1, -2, -3, -4
+RP_F32, RP_BF16, RP_U8 = 0, 1, 2
+RP_PAIR, RP_CHAIN = 0, 1
+RP_HUBER, RP_MSE = 0, 1
+RP_SGD, RP_ADAM = 0, 1
+
+_NP_STATE = {RP_F32: np.float32, RP_BF16: np.uint16, RP_U8: np.uint8}
+_TORCH_OUT = {RP_F32: torch.float32, RP_BF16: torch.bfloat16, RP_U8: torch.float32}
+
+
+class ReplayError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"ingpu_replay status {status}: {message}")
+        self.status = status
+
+
+class ReplayConfig(C.Structure):
+    _fields_ = [("capacity", C.c_uint64), ("state_dim", C.c_uint32), ("state_dtype", C.c_uint32),
+                ("layout", C.c_uint32), ("max_append", C.c_uint32), ("burn_in", C.c_uint64),
+                ("seed", C.c_uint64)]
+
+
+class TrainConfig(C.Structure):
+    _fields_ = [("state_dim", C.c_uint32), ("hidden", C.c_uint32), ("num_actions", C.c_uint32),
+                ("batch", C.c_uint32), ("param_dtype", C.c_uint32), ("loss", C.c_uint32),
+                ("opt", C.c_uint32), ("appends_per_step", C.c_uint32), ("lr", C.c_float),
+                ("gamma", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
+                ("eps", C.c_float), ("use_graph", C.c_uint32)]
+
+
+# every symbol include/ingpu_replay.h declares: name -> (restype, argtypes)
+_vp, _u32, _u64, _int = C.c_void_p, C.c_uint32, C.c_uint64, C.c_int
+SYMBOLS = {
+    "replay_storage_bytes": (C.c_size_t, [_vp]),
+    "replay_row_bytes": (C.c_size_t, [_vp]),
+    "replay_create": (_int, [_vp, _vp, C.c_size_t, _vp]),
+    "replay_destroy": (_int, [_vp]),
+    "replay_append": (_int, [_vp, _u64, _vp, _vp, _vp, _vp, _vp, _int, _vp]),
+    "replay_sample_gather": (_int, [_vp, _u64, _u32, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "replay_get_state": (_int, [_vp, _vp, _vp, _vp]),
+    "replay_read_rows": (_int, [_vp, _u64, _u64, _vp, _vp, _vp, _vp, _vp]),
+    "train_param_count": (C.c_size_t, [_vp]),
+    "train_workspace_bytes": (C.c_size_t, [_vp]),
+    "train_create": (_int, [_vp, _vp, _vp, C.c_size_t, _vp, _vp]),
+    "train_destroy": (_int, [_vp]),
+    "train_step": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _int, _vp]),
+    "train_get_params": (_int, [_vp, _vp]),
+    "train_get_grads": (_int, [_vp, _vp]),
+    "train_get_opt_state": (_int, [_vp, _vp, _vp, _vp, _vp]),
+    "train_set_state": (_int, [_vp, _vp, _vp, _vp, _u64, _u64]),
+    "train_get_last": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "train_kernels_per_step": (_int, [_vp, _vp]),
+    "rp_last_error": (C.c_char_p, []),
+    "rp_version": (C.c_char_p, []),
+}
+
+_lib = None
+
+
+def lib():
+    """Load the HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_1801_03138_amd.build` "
+                              "(or __graft_entry__.build()) first; there is no fallback path")
+        L = C.CDLL(LIB_PATH)
+        for name, (res, args) in SYMBOLS.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+def _check(status):
+    if status < 0:
+        raise ReplayError(status, lib().rp_last_error().decode())
+    return status
+
+
+def _stream_ptr(stream=None):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _dev(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _host(arr):
+    return None if arr is None else arr.ctypes.data_as(C.c_void_p)
+
+
+def _alloc_bytes(nbytes, device):
+    # torch's caching allocator hands out blocks aligned to at least 256 bytes
+    buf = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+    assert buf.data_ptr() % 256 == 0
+    return buf
+
+
+def storage_bytes(cfg):
+    return int(lib().replay_storage_bytes(C.byref(cfg)))
+
+
+def row_bytes(cfg):
+    return int(lib().replay_row_bytes(C.byref(cfg)))
+
+
+class Replay:
+    """The experience replay of the paper's Methods section, resident in HBM."""
+
+    def __init__(self, capacity, state_dim, state_dtype=RP_F32, layout=RP_PAIR, burn_in=0, seed=0,
+                 max_append=4096, device="cuda:0"):
+        self.cfg = ReplayConfig(capacity, state_dim, state_dtype, layout, max_append, burn_in, seed)
+        nbytes = storage_bytes(self.cfg)
+        if nbytes == 0:
+            raise ReplayError(RP_EINVAL, "invalid replay configuration")
+        self.device = torch.device(device)
+        self.storage = _alloc_bytes(nbytes, self.device)
+        h = C.c_void_p()
+        with torch.cuda.device(self.device):
+            _check(lib().replay_create(C.byref(self.cfg), _dev(self.storage), nbytes, C.byref(h)))
+        self._h = h
+        self._destroy = lib().replay_destroy
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    @property
+    def np_state(self):
+        return _NP_STATE[self.cfg.state_dtype]
+
+    def append(self, s, s_next, a, r, term, stream=None):
+        """Append experiences given as numpy arrays (host) or torch CUDA tensors (device)."""
+        on_dev = isinstance(a, torch.Tensor)
+        n = len(a)
+        if on_dev:
+            args = [_dev(s), _dev(s_next), _dev(a), _dev(r), _dev(term)]
+            keep = None
+        else:
+            keep = [np.ascontiguousarray(s, self.np_state),
+                    None if s_next is None else np.ascontiguousarray(s_next, self.np_state),
+                    np.ascontiguousarray(a, np.int32), np.ascontiguousarray(r, np.float32),
+                    np.ascontiguousarray(term, np.uint8)]
+            args = [_host(x) for x in keep]
+        return _check(lib().replay_append(self._h, n, *args, 1 if on_dev else 0,
+                                          _stream_ptr(stream)))
+
+    def alloc_batch(self, batch):
+        """Output tensors for sample_gather: (s, s_next, a, r, term, idx)."""
+        D, dt, dev = self.cfg.state_dim, _TORCH_OUT[self.cfg.state_dtype], self.device
+        return (torch.empty((batch, D), dtype=dt, device=dev),
+                torch.empty((batch, D), dtype=dt, device=dev),
+                torch.empty(batch, dtype=torch.int32, device=dev),
+                torch.empty(batch, dtype=torch.float32, device=dev),
+                torch.empty(batch, dtype=torch.uint8, device=dev),
+                torch.empty(batch, dtype=torch.int32, device=dev))
+
+    def sample_gather(self, step, batch, out=None, stream=None):
+        """Returns (status, (s, s_next, a, r, term, idx)); status 1 = refused during burn-in."""
+        out = self.alloc_batch(batch) if out is None else out
+        st = _check(lib().replay_sample_gather(self._h, step, batch, *[_dev(t) for t in out],
+                                               _stream_ptr(stream)))
+        return st, out
+
+    def state(self):
+        h, s, t = C.c_uint64(), C.c_uint64(), C.c_uint64()
+        _check(lib().replay_get_state(self._h, C.byref(h), C.byref(s), C.byref(t)))
+        return h.value, s.value, t.value
+
+    def read_rows(self, first_slot, n):
+        D = self.cfg.state_dim
+        s = np.empty((n, D), self.np_state)
+        sn = np.empty((n, D), self.np_state) if self.cfg.layout == RP_PAIR else None
+        a, r, term = np.empty(n, np.int32), np.empty(n, np.float32), np.empty(n, np.uint8)
+        _check(lib().replay_read_rows(self._h, first_slot, n, _host(s), _host(sn), _host(a),
+                                      _host(r), _host(term)))
+        return s, sn, a, r, term
+
+
+class Trainer:
+    """The Q-learning train step on top of a Replay; all state lives in HBM."""
+
+    def __init__(self, replay, hidden, num_actions, batch, param_dtype=RP_F32, loss=RP_HUBER,
+                 opt=RP_ADAM, appends_per_step=1, lr=1e-4, gamma=0.99, beta1=0.9, beta2=0.999,
+                 eps=1e-8, use_graph=True, init_params=None):
+        self.replay = replay
+        self.cfg = TrainConfig(replay.cfg.state_dim, hidden, num_actions, batch, param_dtype, loss,
+                               opt, appends_per_step, lr, gamma, beta1, beta2, eps,
+                               1 if use_graph else 0)
+        nbytes = int(lib().train_workspace_bytes(C.byref(self.cfg)))
+        if nbytes == 0:
+            raise ReplayError(RP_EINVAL, "invalid train configuration")
+        self.n_params = int(lib().train_param_count(C.byref(self.cfg)))
+        init = np.ascontiguousarray(init_params, np.float32)
+        if init.shape != (self.n_params,):
+            raise ValueError(f"init_params must have {self.n_params} entries")
+        self.workspace = _alloc_bytes(nbytes, replay.device)
+        h = C.c_void_p()
+        with torch.cuda.device(replay.device):
+            _check(lib().train_create(C.byref(self.cfg), replay._h, _dev(self.workspace), nbytes,
+                                      _host(init), C.byref(h)))
+        self._h = h
+        self._destroy = lib().train_destroy
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def step(self, s=None, s_next=None, a=None, r=None, term=None, stream=None):
+        """One train step; the arrays are the appends_per_step new experiences (numpy or CUDA tensors)."""
+        on_dev = isinstance(a, torch.Tensor)
+        if a is None:
+            args, keep = [None] * 5, None
+        elif on_dev:
+            args, keep = [_dev(s), _dev(s_next), _dev(a), _dev(r), _dev(term)], None
+        else:
+            st = self.replay.np_state
+            keep = [np.ascontiguousarray(s, st), np.ascontiguousarray(s_next, st),
+                    np.ascontiguousarray(a, np.int32), np.ascontiguousarray(r, np.float32),
+                    np.ascontiguousarray(term, np.uint8)]
+            args = [_host(x) for x in keep]
+        return _check(lib().train_step(self._h, *args, 1 if on_dev else 0, _stream_ptr(stream)))
+
+    def params(self):
+        p = np.empty(self.n_params, np.float32)
+        _check(lib().train_get_params(self._h, _host(p)))
+        return p
+
+    def grads(self):
+        g = np.empty(self.n_params, np.float32)
+        _check(lib().train_get_grads(self._h, _host(g)))
+        return g
+
+    def opt_state(self):
+        m, v = np.empty(self.n_params, np.float32), np.empty(self.n_params, np.float32)
+        t, step = C.c_uint64(), C.c_uint64()
+        _check(lib().train_get_opt_state(self._h, _host(m), _host(v), C.byref(t), C.byref(step)))
+        return m, v, t.value, step.value
+
+    def set_state(self, params, m, v, t, step):
+        p = np.ascontiguousarray(params, np.float32)
+        m = None if m is None else np.ascontiguousarray(m, np.float32)
+        v = None if v is None else np.ascontiguousarray(v, np.float32)
+        _check(lib().train_set_state(self._h, _host(p), _host(m), _host(v), int(t), int(step)))
+
+    def last(self):
+        B, A = self.cfg.batch, self.cfg.num_actions
+        q, qn = np.empty((B, A), np.float32), np.empty((B, A), np.float32)
+        y, d = np.empty(B, np.float32), np.empty(B, np.float32)
+        loss, idx = np.empty(1, np.float32), np.empty(B, np.uint32)
+        _check(lib().train_get_last(self._h, _host(q), _host(qn), _host(y), _host(d), _host(loss),
+                                    _host(idx)))
+        return {"Q": q, "Qn": qn, "y": y, "delta": d, "loss": float(loss[0]), "idx": idx}
+
+    def kernels_per_step(self):
+        n = C.c_uint32()
+        _check(lib().train_kernels_per_step(self._h, C.byref(n)))
+        return n.value

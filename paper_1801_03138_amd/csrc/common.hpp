@@ -1,0 +1,82 @@
+// Shared host-side plumbing of the library: error reporting and handle layouts.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+
+#include "../../include/ingpu_replay.h"
+
+namespace rp {
+
+// Last failure message of the calling thread.
+char* error_buffer();
+void set_error(const char* fmt, ...);
+
+#define RP_CHECK_HIP(expr)                                                                  \
+    do {                                                                                    \
+        hipError_t e_ = (expr);                                                             \
+        if (e_ != hipSuccess) {                                                             \
+            rp::set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__,  \
+                          __LINE__);                                                        \
+            return RP_EHIP;                                                                 \
+        }                                                                                   \
+    } while (0)
+
+#define RP_REQUIRE(cond, ...)           \
+    do {                                \
+        if (!(cond)) {                  \
+            rp::set_error(__VA_ARGS__); \
+            return RP_EINVAL;           \
+        }                               \
+    } while (0)
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Device-resident replay state.  Kernels read and advance it, so that a
+// recorded graph replays correctly; the host keeps a mirror for its decisions.
+struct RingState {
+    unsigned long long head;   // slot the next experience goes to
+    unsigned long long size;   // experiences held
+    unsigned long long total;  // experiences ever added
+    unsigned int blocks_done;  // append kernel: blocks that have finished writing
+    unsigned int pad_[9];
+};
+static_assert(sizeof(RingState) == 64, "RingState is one 64-byte line");
+
+// Geometry of the ring in device memory, passed by value to kernels.
+struct RingGeom {
+    unsigned long long capacity;
+    unsigned int state_dim;     // D
+    unsigned int elem_bytes;    // 4, 2, 1
+    unsigned int state_bytes;   // D * elem_bytes
+    unsigned int row_bytes;     // PAIR: padded packed row; CHAIN: padded state slot
+    unsigned int meta_off;      // PAIR: byte offset of (action, reward, terminal) in a row
+    unsigned int layout;
+    unsigned int dtype;
+    unsigned char* rows;        // PAIR: [capacity][row_bytes]; CHAIN: [capacity][row_bytes] states
+    int* a;                     // CHAIN side arrays [capacity]
+    float* r;
+    unsigned char* term;
+    RingState* state;
+};
+
+}  // namespace rp
+
+struct replay {
+    replay_config cfg;
+    rp::RingGeom geom;
+    unsigned char* storage;
+    size_t storage_bytes;
+    // staging area (device) for host-sourced appends, structure of arrays
+    unsigned char* stage_s;
+    unsigned char* stage_s_next;
+    int* stage_a;
+    float* stage_r;
+    unsigned char* stage_term;
+    // host mirror of the ring state
+    uint64_t head, size, total;
+};

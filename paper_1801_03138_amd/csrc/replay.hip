@@ -1,0 +1,609 @@
+// Device-resident FIFO experience replay: storage layout, append, and the
+// fused sample + gather + unpack kernels, behind the C entry points replay_*.
+//
+// Paper: Methods (packed rows of 2D+3 values, add / sample API, FIFO, uniform
+// integer sampling with replacement) and Discussion (one state per experience).
+#include <vector>
+
+#include "common.hpp"
+#include "philox.hpp"
+#include "replay_kernels.hpp"
+
+namespace rp {
+
+static thread_local char g_error[512] = "";
+
+char* error_buffer() { return g_error; }
+
+void set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof(g_error), fmt, ap);
+    va_end(ap);
+}
+
+namespace {
+
+constexpr unsigned int kThreads = 256;
+constexpr unsigned int kMaxPairRowBytes = 32768;  // a gathered PAIR row is staged through LDS
+
+unsigned int elem_bytes_of(unsigned int dtype) { return dtype == RP_F32 ? 4 : dtype == RP_BF16 ? 2 : 1; }
+
+// Stored rows are padded so that 16-byte vector accesses never straddle a row
+// and rows of more than 64 bytes start on a 128-byte line.
+size_t padded_row(size_t raw) {
+    if (raw <= 16) return 16;
+    if (raw <= 32) return 32;
+    if (raw <= 64) return 64;
+    return align_up(raw, 128);
+}
+
+struct Layout {
+    size_t state_bytes, meta_off, row_bytes;
+    size_t off_stage_s, off_stage_s_next, off_stage_a, off_stage_r, off_stage_term;
+    size_t off_a, off_r, off_term, off_rows, total;
+};
+
+bool compute_layout(const replay_config* c, Layout* L) {
+    if (!c || c->capacity == 0 || c->capacity >= (1ull << 32) || c->state_dim == 0 ||
+        c->state_dim > (1u << 24) || c->state_dtype > RP_U8 || c->layout > RP_CHAIN ||
+        c->max_append == 0 || c->max_append > (1u << 24))
+        return false;
+    const size_t eb = elem_bytes_of(c->state_dtype);
+    L->state_bytes = (size_t)c->state_dim * eb;
+    if (c->layout == RP_PAIR) {
+        L->meta_off = align_up(2 * L->state_bytes, 4);
+        L->row_bytes = padded_row(L->meta_off + 12);
+        if (L->row_bytes > kMaxPairRowBytes) return false;
+    } else {
+        L->meta_off = 0;
+        L->row_bytes = padded_row(L->state_bytes);
+    }
+    size_t o = 256;  // RingState lives in the first 256 bytes
+    auto take = [&](size_t bytes) {
+        size_t at = o;
+        o = align_up(o + bytes, 256);
+        return at;
+    };
+    const size_t m = c->max_append;
+    L->off_stage_s = take(m * L->state_bytes);
+    L->off_stage_s_next = take(c->layout == RP_PAIR ? m * L->state_bytes : 0);
+    L->off_stage_a = take(m * 4);
+    L->off_stage_r = take(m * 4);
+    L->off_stage_term = take(m);
+    const size_t side = c->layout == RP_CHAIN ? c->capacity : 0;
+    L->off_a = take(side * 4);
+    L->off_r = take(side * 4);
+    L->off_term = take(side);
+    L->off_rows = take((size_t)c->capacity * L->row_bytes);
+    L->total = o;
+    return true;
+}
+
+// ---------------------------------------------------------------------------------------
+// Append.  Every block reads the head before it writes; the head moves only after the
+// last block has finished, so one launch sees one consistent head.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ void finish_append(const RingGeom& g, unsigned long long n,
+                                              unsigned long long head) {
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned int done = atomicAdd(&g.state->blocks_done, 1u);
+        if (done == gridDim.x - 1) {
+            unsigned long long h = head + n;
+            if (h >= g.capacity) h -= g.capacity;
+            unsigned long long sz = g.state->size + n;
+            g.state->head = h;
+            g.state->size = sz > g.capacity ? g.capacity : sz;
+            g.state->total += n;
+            g.state->blocks_done = 0;
+            __threadfence();
+        }
+    }
+}
+
+// PAIR rows: [s | s' | pad to 4 | action | reward bits | terminal 0/1 | zero pad], built one
+// 32-bit word per thread.
+template <int ELEM>
+__global__ __launch_bounds__(kThreads) void append_pair_kernel(
+    RingGeom g, unsigned long long n, const unsigned char* __restrict__ s,
+    const unsigned char* __restrict__ s_next, const int* __restrict__ a,
+    const float* __restrict__ r, const unsigned char* __restrict__ term,
+    unsigned int rows_per_block) {
+    const unsigned long long head = g.state->head;
+    const unsigned int words = g.row_bytes >> 2;
+    const unsigned long long row0 = (unsigned long long)blockIdx.x * rows_per_block;
+    const unsigned int sb = g.state_bytes;
+    for (unsigned int e = threadIdx.x; e < rows_per_block * words; e += kThreads) {
+        const unsigned int k = e / words, w = e - k * words;
+        const unsigned long long row = row0 + k;
+        if (row >= n) break;
+        unsigned long long slot = head + row;
+        if (slot >= g.capacity) slot -= g.capacity;
+        const unsigned int o = w * 4u;
+        unsigned int val = 0;
+        if (o < g.meta_off) {
+            if (ELEM == 4) {
+                const unsigned int col = w;
+                val = col < g.state_dim
+                          ? reinterpret_cast<const unsigned int*>(s)[row * g.state_dim + col]
+                          : reinterpret_cast<const unsigned int*>(s_next)[row * g.state_dim + col -
+                                                                          g.state_dim];
+            } else {
+#pragma unroll
+                for (unsigned int b = 0; b < 4; ++b) {
+                    const unsigned int ob = o + b;
+                    unsigned int byte = 0;
+                    if (ob < sb)
+                        byte = s[row * sb + ob];
+                    else if (ob < 2 * sb)
+                        byte = s_next[row * sb + ob - sb];
+                    val |= byte << (8 * b);
+                }
+            }
+        } else if (o == g.meta_off) {
+            val = (unsigned int)a[row];
+        } else if (o == g.meta_off + 4) {
+            val = __float_as_uint(r[row]);
+        } else if (o == g.meta_off + 8) {
+            val = term[row] ? 1u : 0u;
+        }
+        reinterpret_cast<unsigned int*>(g.rows + slot * g.row_bytes)[w] = val;
+    }
+    finish_append(g, n, head);
+}
+
+// CHAIN: one block per experience copies the state into its slot and the three scalars
+// into the side arrays.  VEC: state_bytes is a multiple of 16 and the source is 16-byte aligned.
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void append_chain_kernel(
+    RingGeom g, unsigned long long n, const unsigned char* __restrict__ s,
+    const int* __restrict__ a, const float* __restrict__ r,
+    const unsigned char* __restrict__ term) {
+    const unsigned long long head = g.state->head;
+    for (unsigned long long row = blockIdx.x; row < n; row += gridDim.x) {
+        unsigned long long slot = head + row;
+        if (slot >= g.capacity) slot -= g.capacity;
+        unsigned char* dst = g.rows + slot * g.row_bytes;
+        const unsigned char* src = s + row * g.state_bytes;
+        if (VEC) {
+            const unsigned int nv = g.state_bytes >> 4;
+            for (unsigned int v = threadIdx.x; v < nv; v += kThreads)
+                reinterpret_cast<uint4*>(dst)[v] = reinterpret_cast<const uint4*>(src)[v];
+        } else {
+            for (unsigned int b = threadIdx.x; b < g.state_bytes; b += kThreads) dst[b] = src[b];
+        }
+        if (threadIdx.x == 0) {
+            g.a[slot] = a[row];
+            g.r[slot] = r[row];
+            g.term[slot] = term[row] ? 1 : 0;
+        }
+    }
+    finish_append(g, n, head);
+}
+
+// ---------------------------------------------------------------------------------------
+// Sample + gather + unpack, PAIR layout.  A block draws the slot numbers of R batch rows,
+// pulls those rows into LDS with 16-byte loads (a 256-byte row is one load by 16 lanes),
+// then writes each output tensor as one contiguous, coalesced run.
+// ---------------------------------------------------------------------------------------
+template <int ELEM>
+__global__ __launch_bounds__(kThreads) void sample_gather_pair_kernel(
+    RingGeom g, unsigned long long seed, unsigned long long step_value,
+    const unsigned long long* __restrict__ step_ptr, unsigned int batch, unsigned int R,
+    void* __restrict__ out_s, void* __restrict__ out_s_next, unsigned int out_ld,
+    int* __restrict__ out_a, float* __restrict__ out_r, unsigned char* __restrict__ out_term,
+    unsigned int* __restrict__ out_idx) {
+    extern __shared__ uint4 smem[];
+    unsigned int* idx_s = reinterpret_cast<unsigned int*>(smem);               // R <= 64 entries
+    unsigned char* rows_s = reinterpret_cast<unsigned char*>(smem) + 256;
+
+    const unsigned long long step = step_ptr ? *step_ptr : step_value;
+    const unsigned int size = (unsigned int)g.state->size;
+    const unsigned int i0 = blockIdx.x * R;
+    const unsigned int nrows = min(R, batch - i0);
+
+    if (threadIdx.x < nrows) {
+        const unsigned int i = i0 + threadIdx.x;
+        const unsigned int p = uniform_draw(seed, step, i, size);
+        idx_s[threadIdx.x] = p;
+        if (out_idx) out_idx[i] = p;
+    }
+    __syncthreads();
+
+    const unsigned int V = g.row_bytes >> 4;
+    for (unsigned int v = threadIdx.x; v < nrows * V; v += kThreads) {
+        const unsigned int row = v / V, part = v - row * V;
+        const uint4* src =
+            reinterpret_cast<const uint4*>(g.rows + (unsigned long long)idx_s[row] * g.row_bytes);
+        reinterpret_cast<uint4*>(rows_s)[v] = src[part];
+    }
+    __syncthreads();
+
+    const unsigned int D = g.state_dim;
+    for (unsigned int e = threadIdx.x; e < nrows * D; e += kThreads) {
+        const unsigned int row = e / D, col = e - row * D;
+        const unsigned char* base = rows_s + row * g.row_bytes;
+        const size_t o = (size_t)(i0 + row) * out_ld + col;
+        if (ELEM == 4) {
+            const unsigned int* w = reinterpret_cast<const unsigned int*>(base);
+            if (out_s) static_cast<unsigned int*>(out_s)[o] = w[col];
+            if (out_s_next) static_cast<unsigned int*>(out_s_next)[o] = w[D + col];
+        } else if (ELEM == 2) {
+            const unsigned short* h = reinterpret_cast<const unsigned short*>(base);
+            if (out_s) static_cast<unsigned short*>(out_s)[o] = h[col];
+            if (out_s_next) static_cast<unsigned short*>(out_s_next)[o] = h[D + col];
+        } else {
+            if (out_s) static_cast<float*>(out_s)[o] = (float)base[col] / 255.0f;
+            if (out_s_next) static_cast<float*>(out_s_next)[o] = (float)base[D + col] / 255.0f;
+        }
+    }
+    if (threadIdx.x < nrows) {
+        const unsigned int i = i0 + threadIdx.x;
+        const unsigned int* meta =
+            reinterpret_cast<const unsigned int*>(rows_s + threadIdx.x * g.row_bytes + g.meta_off);
+        if (out_a) out_a[i] = (int)meta[0];
+        if (out_r) out_r[i] = __uint_as_float(meta[1]);
+        if (out_term) out_term[i] = (unsigned char)meta[2];
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Sample + gather + convert, CHAIN layout (large states).  A block moves one 4 KB piece of
+// one state of one sampled experience: 16 bytes in per lane, and for uint8 states 64 bytes
+// (16 floats) out per lane.  s comes from the sampled slot, s' from the slot after it.
+// ---------------------------------------------------------------------------------------
+template <int ELEM, bool VEC>
+__global__ __launch_bounds__(kThreads) void sample_gather_chain_kernel(
+    RingGeom g, unsigned long long seed, unsigned long long step_value,
+    const unsigned long long* __restrict__ step_ptr, unsigned int batch, unsigned int chunks,
+    void* __restrict__ out_s, void* __restrict__ out_s_next, unsigned int out_ld,
+    int* __restrict__ out_a, float* __restrict__ out_r, unsigned char* __restrict__ out_term,
+    unsigned int* __restrict__ out_idx) {
+    const unsigned int chunk = blockIdx.x % chunks;
+    const unsigned int t = blockIdx.x / chunks;
+    const unsigned int which = t & 1u;
+    const unsigned int i = t >> 1;
+    if (i >= batch) return;
+
+    const unsigned long long step = step_ptr ? *step_ptr : step_value;
+    const unsigned long long size = g.state->size, head = g.state->head;
+    unsigned long long oldest = head + g.capacity - size;
+    if (oldest >= g.capacity) oldest -= g.capacity;
+    unsigned long long p = oldest + uniform_draw(seed, step, i, (unsigned int)(size - 1));
+    if (p >= g.capacity) p -= g.capacity;
+    unsigned long long q = p;
+    if (which) q = (p + 1 == g.capacity) ? 0 : p + 1;
+
+    if (chunk == 0 && which == 0 && threadIdx.x == 0) {
+        if (out_idx) out_idx[i] = (unsigned int)p;
+        if (out_a) out_a[i] = g.a[p];
+        if (out_r) out_r[i] = g.r[p];
+        if (out_term) out_term[i] = g.term[p];
+    }
+    void* out = which ? out_s_next : out_s;
+    if (!out) return;
+
+    const unsigned int v = chunk * kThreads + threadIdx.x;
+    const unsigned int byte0 = v * 16u;
+    if (byte0 >= g.state_bytes) return;
+    // the slot is padded to a multiple of 16 bytes, so this load stays inside it
+    const uint4 val = reinterpret_cast<const uint4*>(g.rows + q * g.row_bytes)[v];
+    const unsigned int words[4] = {val.x, val.y, val.z, val.w};
+    const unsigned int valid_bytes = min(16u, g.state_bytes - byte0);
+    constexpr unsigned int EPV = 16 / ELEM;  // elements per 16-byte vector
+    const unsigned int e0 = byte0 / ELEM;
+    const size_t o = (size_t)i * out_ld + e0;
+
+    if (ELEM == 1) {
+        float f[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+            f[j] = (float)((words[j >> 2] >> (8 * (j & 3))) & 0xFFu) / 255.0f;
+        float* dst = static_cast<float*>(out) + o;
+        if (VEC && valid_bytes == 16) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                reinterpret_cast<float4*>(dst)[j] =
+                    make_float4(f[4 * j], f[4 * j + 1], f[4 * j + 2], f[4 * j + 3]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                if ((unsigned int)j < valid_bytes) dst[j] = f[j];
+        }
+    } else if (ELEM == 2) {
+        unsigned short* dst = static_cast<unsigned short*>(out) + o;
+        if (VEC && valid_bytes == 16) {
+            *reinterpret_cast<uint4*>(dst) = val;
+        } else {
+#pragma unroll
+            for (unsigned int j = 0; j < EPV; ++j)
+                if (2 * j < valid_bytes)
+                    dst[j] = (unsigned short)(words[j >> 1] >> (16 * (j & 1)));
+        }
+    } else {
+        unsigned int* dst = static_cast<unsigned int*>(out) + o;
+        if (VEC && valid_bytes == 16) {
+            *reinterpret_cast<uint4*>(dst) = val;
+        } else {
+#pragma unroll
+            for (unsigned int j = 0; j < EPV; ++j)
+                if (4 * j < valid_bytes) dst[j] = words[j];
+        }
+    }
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+hipError_t launch_append(const RingGeom& g, unsigned long long n, const void* s,
+                         const void* s_next, const int* a, const float* r,
+                         const unsigned char* term, hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    const unsigned char* sp = static_cast<const unsigned char*>(s);
+    const unsigned char* snp = static_cast<const unsigned char*>(s_next);
+    if (g.layout == RP_PAIR) {
+        const unsigned int words = g.row_bytes >> 2;
+        unsigned int rpb = kThreads * 4 / words;  // about four words per thread
+        if (rpb == 0) rpb = 1;
+        const unsigned int blocks = (unsigned int)((n + rpb - 1) / rpb);
+        if (g.elem_bytes == 4)
+            hipLaunchKernelGGL(append_pair_kernel<4>, dim3(blocks), dim3(kThreads), 0, stream, g, n,
+                               sp, snp, a, r, term, rpb);
+        else if (g.elem_bytes == 2)
+            hipLaunchKernelGGL(append_pair_kernel<2>, dim3(blocks), dim3(kThreads), 0, stream, g, n,
+                               sp, snp, a, r, term, rpb);
+        else
+            hipLaunchKernelGGL(append_pair_kernel<1>, dim3(blocks), dim3(kThreads), 0, stream, g, n,
+                               sp, snp, a, r, term, rpb);
+    } else {
+        const unsigned int blocks = (unsigned int)(n < 65536 ? n : 65536);
+        if ((g.state_bytes & 15u) == 0 && aligned16(s))
+            hipLaunchKernelGGL(append_chain_kernel<true>, dim3(blocks), dim3(kThreads), 0, stream,
+                               g, n, sp, a, r, term);
+        else
+            hipLaunchKernelGGL(append_chain_kernel<false>, dim3(blocks), dim3(kThreads), 0, stream,
+                               g, n, sp, a, r, term);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_sample_gather(const RingGeom& g, unsigned long long seed,
+                                unsigned long long step_value,
+                                const unsigned long long* step_ptr, unsigned int batch,
+                                void* out_s, void* out_s_next, unsigned int out_ld, int* out_a,
+                                float* out_r, unsigned char* out_term, unsigned int* out_idx,
+                                hipStream_t stream) {
+    if (g.layout == RP_PAIR) {
+        unsigned int R = 16;
+        while (R > 1 && (size_t)R * g.row_bytes > kMaxPairRowBytes) R >>= 1;
+        const unsigned int blocks = (batch + R - 1) / R;
+        const size_t lds = 256 + (size_t)R * g.row_bytes;
+#define RP_LAUNCH_PAIR(E)                                                                         \
+    hipLaunchKernelGGL(sample_gather_pair_kernel<E>, dim3(blocks), dim3(kThreads), lds, stream, g, \
+                       seed, step_value, step_ptr, batch, R, out_s, out_s_next, out_ld, out_a,     \
+                       out_r, out_term, out_idx)
+        if (g.elem_bytes == 4)
+            RP_LAUNCH_PAIR(4);
+        else if (g.elem_bytes == 2)
+            RP_LAUNCH_PAIR(2);
+        else
+            RP_LAUNCH_PAIR(1);
+#undef RP_LAUNCH_PAIR
+    } else {
+        const unsigned int vectors = (g.state_bytes + 15u) >> 4;
+        const unsigned int chunks = (vectors + kThreads - 1) / kThreads;
+        const unsigned long long blocks64 = (unsigned long long)batch * 2ull * chunks;
+        if (blocks64 > 0x7FFFFFFFull) return hipErrorInvalidValue;
+        const unsigned int blocks = (unsigned int)blocks64;
+        const unsigned int out_elem = g.elem_bytes == 1 ? 4 : g.elem_bytes;
+        const bool vec = ((size_t)out_ld * out_elem) % 16 == 0 && aligned16(out_s) &&
+                         aligned16(out_s_next);
+#define RP_LAUNCH_CHAIN(E, VEC)                                                                  \
+    hipLaunchKernelGGL((sample_gather_chain_kernel<E, VEC>), dim3(blocks), dim3(kThreads), 0,     \
+                       stream, g, seed, step_value, step_ptr, batch, chunks, out_s, out_s_next,   \
+                       out_ld, out_a, out_r, out_term, out_idx)
+        if (g.elem_bytes == 4) {
+            if (vec) RP_LAUNCH_CHAIN(4, true); else RP_LAUNCH_CHAIN(4, false);
+        } else if (g.elem_bytes == 2) {
+            if (vec) RP_LAUNCH_CHAIN(2, true); else RP_LAUNCH_CHAIN(2, false);
+        } else {
+            if (vec) RP_LAUNCH_CHAIN(1, true); else RP_LAUNCH_CHAIN(1, false);
+        }
+#undef RP_LAUNCH_CHAIN
+    }
+    return hipGetLastError();
+}
+
+}  // namespace rp
+
+using rp::Layout;
+
+extern "C" {
+
+const char* rp_last_error(void) { return rp::error_buffer(); }
+const char* rp_version(void) { return "ingpu_replay 0.1 (gfx950)"; }
+
+size_t replay_storage_bytes(const replay_config* cfg) {
+    Layout L;
+    return rp::compute_layout(cfg, &L) ? L.total : 0;
+}
+
+size_t replay_row_bytes(const replay_config* cfg) {
+    Layout L;
+    if (!rp::compute_layout(cfg, &L)) return 0;
+    return cfg->layout == RP_PAIR ? L.row_bytes : L.row_bytes + 9;
+}
+
+rp_status replay_create(const replay_config* cfg, void* dev_storage, size_t bytes,
+                        replay_t** out) {
+    RP_REQUIRE(cfg && dev_storage && out, "replay_create: null argument");
+    Layout L;
+    RP_REQUIRE(rp::compute_layout(cfg, &L),
+               "replay_create: invalid configuration (capacity 1..2^32-1, state_dim >= 1, "
+               "max_append >= 1, PAIR rows at most %u bytes)", rp::kMaxPairRowBytes);
+    RP_REQUIRE((reinterpret_cast<uintptr_t>(dev_storage) & 255u) == 0,
+               "replay_create: dev_storage must be 256-byte aligned");
+    if (bytes < L.total) {
+        rp::set_error("replay_create: storage of %zu bytes is smaller than the %zu needed", bytes,
+                      L.total);
+        return RP_ENOMEM;
+    }
+    RP_CHECK_HIP(hipMemset(dev_storage, 0, L.total));
+    RP_CHECK_HIP(hipDeviceSynchronize());
+    replay* rp_ = new (std::nothrow) replay();
+    if (!rp_) {
+        rp::set_error("replay_create: out of host memory");
+        return RP_ENOMEM;
+    }
+    unsigned char* base = static_cast<unsigned char*>(dev_storage);
+    rp_->cfg = *cfg;
+    rp_->storage = base;
+    rp_->storage_bytes = L.total;
+    rp_->stage_s = base + L.off_stage_s;
+    rp_->stage_s_next = base + L.off_stage_s_next;
+    rp_->stage_a = reinterpret_cast<int*>(base + L.off_stage_a);
+    rp_->stage_r = reinterpret_cast<float*>(base + L.off_stage_r);
+    rp_->stage_term = base + L.off_stage_term;
+    rp::RingGeom& g = rp_->geom;
+    g.capacity = cfg->capacity;
+    g.state_dim = cfg->state_dim;
+    g.elem_bytes = rp::elem_bytes_of(cfg->state_dtype);
+    g.state_bytes = (unsigned int)L.state_bytes;
+    g.row_bytes = (unsigned int)L.row_bytes;
+    g.meta_off = (unsigned int)L.meta_off;
+    g.layout = cfg->layout;
+    g.dtype = cfg->state_dtype;
+    g.rows = base + L.off_rows;
+    g.a = reinterpret_cast<int*>(base + L.off_a);
+    g.r = reinterpret_cast<float*>(base + L.off_r);
+    g.term = base + L.off_term;
+    g.state = reinterpret_cast<rp::RingState*>(base);
+    rp_->head = rp_->size = rp_->total = 0;
+    *out = rp_;
+    return RP_OK;
+}
+
+rp_status replay_destroy(replay_t* rp_) {
+    delete rp_;
+    return RP_OK;
+}
+
+rp_status replay_append(replay_t* rp_, uint64_t n, const void* s, const void* s_next,
+                        const int32_t* a, const float* r, const uint8_t* term, int src_is_device,
+                        void* hip_stream) {
+    RP_REQUIRE(rp_, "replay_append: null handle");
+    if (n == 0) return RP_OK;
+    RP_REQUIRE(n <= rp_->cfg.capacity, "replay_append: n = %llu exceeds the capacity %llu",
+               (unsigned long long)n, (unsigned long long)rp_->cfg.capacity);
+    const bool pair = rp_->cfg.layout == RP_PAIR;
+    RP_REQUIRE(s && a && r && term && (!pair || s_next), "replay_append: null field array");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const rp::RingGeom& g = rp_->geom;
+    if (src_is_device) {
+        RP_CHECK_HIP(rp::launch_append(g, n, s, s_next, a, r, term, stream));
+    } else {
+        const size_t sb = g.state_bytes;
+        for (uint64_t done = 0; done < n;) {
+            const uint64_t m = (n - done < rp_->cfg.max_append) ? n - done : rp_->cfg.max_append;
+            RP_CHECK_HIP(hipMemcpyAsync(rp_->stage_s, static_cast<const unsigned char*>(s) + done * sb,
+                                        m * sb, hipMemcpyHostToDevice, stream));
+            if (pair)
+                RP_CHECK_HIP(hipMemcpyAsync(rp_->stage_s_next,
+                                            static_cast<const unsigned char*>(s_next) + done * sb,
+                                            m * sb, hipMemcpyHostToDevice, stream));
+            RP_CHECK_HIP(hipMemcpyAsync(rp_->stage_a, a + done, m * 4, hipMemcpyHostToDevice, stream));
+            RP_CHECK_HIP(hipMemcpyAsync(rp_->stage_r, r + done, m * 4, hipMemcpyHostToDevice, stream));
+            RP_CHECK_HIP(hipMemcpyAsync(rp_->stage_term, term + done, m, hipMemcpyHostToDevice, stream));
+            RP_CHECK_HIP(rp::launch_append(g, m, rp_->stage_s, rp_->stage_s_next, rp_->stage_a,
+                                           rp_->stage_r, rp_->stage_term, stream));
+            done += m;
+            // pageable host memory: the copies above have left the caller's arrays when they
+            // return, and stream order keeps the staging area safe for the next piece
+        }
+    }
+    rp_->total += n;
+    rp_->size = rp_->size + n > rp_->cfg.capacity ? rp_->cfg.capacity : rp_->size + n;
+    rp_->head = (rp_->head + n) % rp_->cfg.capacity;
+    return RP_OK;
+}
+
+rp_status replay_sample_gather(replay_t* rp_, uint64_t step, uint32_t batch, void* out_s,
+                               void* out_s_next, int32_t* out_a, float* out_r, uint8_t* out_term,
+                               uint32_t* out_idx, void* hip_stream) {
+    RP_REQUIRE(rp_, "replay_sample_gather: null handle");
+    RP_REQUIRE(batch >= 1 && batch <= (1u << 24), "replay_sample_gather: batch %u not in 1..2^24",
+               batch);
+    if (rp_->total < rp_->cfg.burn_in) return RP_SKIPPED_BURN_IN;
+    if (rp_->size < (rp_->cfg.layout == RP_CHAIN ? 2u : 1u)) return RP_SKIPPED_BURN_IN;
+    RP_CHECK_HIP(rp::launch_sample_gather(rp_->geom, rp_->cfg.seed, step, nullptr, batch, out_s,
+                                          out_s_next, rp_->cfg.state_dim, out_a, out_r, out_term,
+                                          out_idx, static_cast<hipStream_t>(hip_stream)));
+    return RP_OK;
+}
+
+rp_status replay_get_state(replay_t* rp_, uint64_t* head, uint64_t* size, uint64_t* total) {
+    RP_REQUIRE(rp_, "replay_get_state: null handle");
+    rp::RingState st;
+    RP_CHECK_HIP(hipDeviceSynchronize());
+    RP_CHECK_HIP(hipMemcpy(&st, rp_->geom.state, sizeof(st), hipMemcpyDeviceToHost));
+    if (head) *head = st.head;
+    if (size) *size = st.size;
+    if (total) *total = st.total;
+    if (st.head != rp_->head || st.size != rp_->size || st.total != rp_->total) {
+        rp::set_error("replay_get_state: device state (%llu,%llu,%llu) != host mirror (%llu,%llu,%llu)",
+                      st.head, st.size, st.total, (unsigned long long)rp_->head,
+                      (unsigned long long)rp_->size, (unsigned long long)rp_->total);
+        return RP_ESTATE;
+    }
+    return RP_OK;
+}
+
+rp_status replay_read_rows(replay_t* rp_, uint64_t first_slot, uint64_t n, void* s, void* s_next,
+                           int32_t* a, float* r, uint8_t* term) {
+    RP_REQUIRE(rp_, "replay_read_rows: null handle");
+    const rp::RingGeom& g = rp_->geom;
+    RP_REQUIRE(first_slot < g.capacity && n <= g.capacity, "replay_read_rows: range out of bounds");
+    if (n == 0) return RP_OK;
+    RP_CHECK_HIP(hipDeviceSynchronize());
+    const size_t sb = g.state_bytes, rb = g.row_bytes;
+    const uint64_t chunk_rows = 4096;
+    std::vector<unsigned char> raw(chunk_rows * rb);
+    std::vector<int> ta(chunk_rows);
+    std::vector<float> tr(chunk_rows);
+    std::vector<unsigned char> tt(chunk_rows);
+    for (uint64_t done = 0; done < n;) {
+        const uint64_t slot = (first_slot + done) % g.capacity;
+        uint64_t m = n - done;
+        if (m > chunk_rows) m = chunk_rows;
+        if (m > g.capacity - slot) m = g.capacity - slot;  // stop at the wrap point
+        RP_CHECK_HIP(hipMemcpy(raw.data(), g.rows + slot * rb, m * rb, hipMemcpyDeviceToHost));
+        if (g.layout == RP_CHAIN) {
+            RP_CHECK_HIP(hipMemcpy(ta.data(), g.a + slot, m * 4, hipMemcpyDeviceToHost));
+            RP_CHECK_HIP(hipMemcpy(tr.data(), g.r + slot, m * 4, hipMemcpyDeviceToHost));
+            RP_CHECK_HIP(hipMemcpy(tt.data(), g.term + slot, m, hipMemcpyDeviceToHost));
+        }
+        for (uint64_t k = 0; k < m; ++k) {
+            const unsigned char* row = raw.data() + k * rb;
+            if (s) memcpy(static_cast<unsigned char*>(s) + (done + k) * sb, row, sb);
+            if (g.layout == RP_PAIR) {
+                if (s_next) memcpy(static_cast<unsigned char*>(s_next) + (done + k) * sb, row + sb, sb);
+                unsigned int meta[3];
+                memcpy(meta, row + g.meta_off, 12);
+                if (a) a[done + k] = (int)meta[0];
+                if (r) memcpy(&r[done + k], &meta[1], 4);
+                if (term) term[done + k] = (uint8_t)meta[2];
+            } else {
+                if (a) a[done + k] = ta[k];
+                if (r) r[done + k] = tr[k];
+                if (term) term[done + k] = tt[k];
+            }
+        }
+        done += m;
+    }
+    return RP_OK;
+}
+
+}  // extern "C"

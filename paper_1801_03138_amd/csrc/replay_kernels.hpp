@@ -1,0 +1,24 @@
+// Launchers of the replay kernels, shared by the replay entry points and the trainer.
+#pragma once
+
+#include "common.hpp"
+
+namespace rp {
+
+// Append n experiences read from device arrays (structure of arrays) at the
+// ring's device-resident head; the last block to finish advances the state.
+hipError_t launch_append(const RingGeom& g, unsigned long long n, const void* s,
+                         const void* s_next, const int* a, const float* r,
+                         const unsigned char* term, hipStream_t stream);
+
+// Sample `batch` slots and unpack them.  The sampling step is *step_ptr when
+// step_ptr is non-null (device), else step_value.  out_ld is the row pitch of
+// out_s / out_s_next in elements (>= D); columns D..out_ld-1 are not written.
+hipError_t launch_sample_gather(const RingGeom& g, unsigned long long seed,
+                                unsigned long long step_value,
+                                const unsigned long long* step_ptr, unsigned int batch,
+                                void* out_s, void* out_s_next, unsigned int out_ld, int* out_a,
+                                float* out_r, unsigned char* out_term, unsigned int* out_idx,
+                                hipStream_t stream);
+
+}  // namespace rp

@@ -1,0 +1,716 @@
+// The Q-learning train step on a device-resident replay: sample + gather, MLP forward on
+// s and s', TD target / selection / loss, backward, optimizer, replayed as one HIP graph.
+//
+// Paper: Integration with Reinforcement Learning Algorithm (the step takes no inputs from
+// the host; Q(s,a) is entry i*A + a_i of the flattened network output) and Deep Q-Network
+// Model (the update equation).
+#include <cmath>
+#include <vector>
+
+#include "common.hpp"
+#include "replay_kernels.hpp"
+
+namespace rp {
+namespace {
+
+constexpr unsigned int kThreads = 256;
+
+// ----------------------------------------------------------------------------- element types
+struct bf16_t {
+    unsigned short bits;
+};
+
+__device__ __forceinline__ float to_float(float x) { return x; }
+__device__ __forceinline__ float to_float(bf16_t x) {
+    return __uint_as_float((unsigned int)x.bits << 16);
+}
+// round to nearest even; NaN stays NaN
+__device__ __forceinline__ unsigned short bf16_bits_rne(float f) {
+    unsigned int u = __float_as_uint(f);
+    if ((u & 0x7F800000u) == 0x7F800000u && (u & 0x007FFFFFu)) return (unsigned short)((u >> 16) | 0x40u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (unsigned short)(u >> 16);
+}
+template <typename T>
+__device__ __forceinline__ T from_float(float x);
+template <>
+__device__ __forceinline__ float from_float<float>(float x) { return x; }
+template <>
+__device__ __forceinline__ bf16_t from_float<bf16_t>(float x) { return bf16_t{bf16_bits_rne(x)}; }
+
+// Device-resident scalars of the trainer.
+struct TrainCounters {
+    unsigned long long step;    // sampling step of the next executed train step
+    unsigned long long adam_t;  // Adam steps taken
+    float c1, c2;               // Adam bias corrections 1 - beta^t of the current step
+    float loss;                 // mean loss of the last step
+    unsigned int pad_[9];
+};
+static_assert(sizeof(TrainCounters) == 64, "one line");
+
+// ----------------------------------------------------------------------------- dense products
+enum { EPI_NONE = 0, EPI_BIAS_RELU = 1, EPI_BIAS = 2, EPI_MASK = 3 };
+
+// C[M x N] = op(A) op(B), 64 x 64 tile per block, fp32 accumulation in registers.
+// op(A)(m,k) = TRANS_A ? A[k*lda + m] : A[m*lda + k];  op(B)(k,n) = TRANS_B ? B[n*ldb + k] : B[k*ldb + n].
+template <typename TA, typename TB, typename TC, bool TRANS_A, bool TRANS_B, int EPI>
+__global__ __launch_bounds__(kThreads) void gemm_kernel(int M, int N, int K,
+                                                        const TA* __restrict__ A, int lda,
+                                                        const TB* __restrict__ B, int ldb,
+                                                        TC* __restrict__ C, int ldc,
+                                                        const float* __restrict__ bias,
+                                                        const TC* __restrict__ mask, int ldmask) {
+    constexpr int BM = 64, BN = 64, BK = 16;
+    __shared__ float As[BK][BM + 4];
+    __shared__ float Bs[BK][BN + 4];
+    const int tid = threadIdx.x;
+    const int tx = tid & 15, ty = tid >> 4;
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    float acc[4][4] = {};
+
+    for (int k0 = 0; k0 < K; k0 += BK) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int m, k;
+            if (TRANS_A) { m = tid & 63; k = (tid >> 6) + 4 * j; }
+            else         { k = tid & 15; m = (tid >> 4) + 16 * j; }
+            const int gm = m0 + m, gk = k0 + k;
+            float v = 0.f;
+            if (gm < M && gk < K)
+                v = to_float(TRANS_A ? A[(size_t)gk * lda + gm] : A[(size_t)gm * lda + gk]);
+            As[k][m] = v;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int n, k;
+            if (TRANS_B) { k = tid & 15; n = (tid >> 4) + 16 * j; }
+            else         { n = tid & 63; k = (tid >> 6) + 4 * j; }
+            const int gn = n0 + n, gk = k0 + k;
+            float v = 0.f;
+            if (gn < N && gk < K)
+                v = to_float(TRANS_B ? B[(size_t)gn * ldb + gk] : B[(size_t)gk * ldb + gn]);
+            Bs[k][n] = v;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < BK; ++k) {
+            float a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = As[k][ty * 4 + i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[j] = Bs[k][tx * 4 + j];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int gm = m0 + ty * 4 + i;
+        if (gm >= M) continue;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int gn = n0 + tx * 4 + j;
+            if (gn >= N) continue;
+            float v = acc[i][j];
+            if (EPI == EPI_BIAS_RELU) {
+                v += bias[gn];
+                v = v > 0.f ? v : 0.f;
+            } else if (EPI == EPI_BIAS) {
+                v += bias[gn];
+            } else if (EPI == EPI_MASK) {
+                if (!(to_float(mask[(size_t)gm * ldmask + gn]) > 0.f)) v = 0.f;
+            }
+            C[(size_t)gm * ldc + gn] = from_float<TC>(v);
+        }
+    }
+}
+
+// out[n] = sum_m X[m*ld + n], rows added in order
+template <typename T>
+__global__ __launch_bounds__(kThreads) void colsum_kernel(int M, int N, const T* __restrict__ X,
+                                                          int ld, float* __restrict__ out) {
+    const int n = blockIdx.x * kThreads + threadIdx.x;
+    if (n >= N) return;
+    float acc = 0.f;
+    for (int m = 0; m < M; ++m) acc += to_float(X[(size_t)m * ld + n]);
+    out[n] = acc;
+}
+
+// ----------------------------------------------------------------------------- TD target and loss
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// One wavefront per batch row i:  y_i = r_i + gamma (1 - term_i) max_a Q[B+i][a],
+// delta_i = y_i - Q[i][a_i], per-sample loss, and the one non-zero of dL/dQ in row i.
+// Thread 0 of block 0 also advances Adam's step count and its bias corrections.
+__global__ __launch_bounds__(kThreads) void td_loss_kernel(
+    unsigned int B, unsigned int A, unsigned int Ap, const float* __restrict__ Q,
+    const int* __restrict__ act, const float* __restrict__ rew,
+    const unsigned char* __restrict__ term, float gamma, unsigned int loss_kind,
+    float* __restrict__ y_out, float* __restrict__ delta_out, float* __restrict__ lossi,
+    float* __restrict__ dQ, TrainCounters* __restrict__ ctr, float beta1, float beta2) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        const unsigned long long t = ctr->adam_t + 1;
+        ctr->adam_t = t;
+        ctr->c1 = (float)(1.0 - pow((double)beta1, (double)t));
+        ctr->c2 = (float)(1.0 - pow((double)beta2, (double)t));
+    }
+    const unsigned int lane = threadIdx.x & 63u;
+    const unsigned int i = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (i >= B) return;
+    const float* qn = Q + (size_t)(B + i) * Ap;
+    float best = -INFINITY;
+    for (unsigned int k = lane; k < A; k += 64) best = fmaxf(best, qn[k]);
+    best = wave_max(best);
+    unsigned int ai = (unsigned int)act[i];
+    if (ai >= A) ai = A - 1;  // an out-of-range action must not turn into a wild address
+    const float q = Q[(size_t)i * Ap + ai];
+    const float y = rew[i] + (term[i] ? 0.f : gamma * best);
+    const float d = y - q;
+    float li, slope;
+    if (loss_kind == RP_MSE || fabsf(d) <= 1.f) {
+        li = 0.5f * d * d;
+        slope = d;
+    } else {
+        li = fabsf(d) - 0.5f;
+        slope = d > 0.f ? 1.f : -1.f;
+    }
+    const float g = -slope / (float)B;
+    for (unsigned int k = lane; k < Ap; k += 64) dQ[(size_t)i * Ap + k] = (k == ai) ? g : 0.f;
+    if (lane == 0) {
+        y_out[i] = y;
+        delta_out[i] = d;
+        lossi[i] = li;
+    }
+}
+
+// dZ2[i][k] = dQ[i][a_i] * W3[k][a_i] * 1[H2[i][k] > 0]   (dQ has one non-zero per row)
+template <typename E>
+__global__ __launch_bounds__(kThreads) void dz_out_kernel(unsigned int B, unsigned int H,
+                                                          unsigned int A, unsigned int Ap,
+                                                          const float* __restrict__ dQ,
+                                                          const int* __restrict__ act,
+                                                          const E* __restrict__ W3,
+                                                          const E* __restrict__ H2,
+                                                          E* __restrict__ dZ2) {
+    const size_t e = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    if (e >= (size_t)B * H) return;
+    const unsigned int i = (unsigned int)(e / H), k = (unsigned int)(e - (size_t)i * H);
+    unsigned int ai = (unsigned int)act[i];
+    if (ai >= A) ai = A - 1;
+    float v = dQ[(size_t)i * Ap + ai] * to_float(W3[(size_t)k * Ap + ai]);
+    if (!(to_float(H2[e]) > 0.f)) v = 0.f;
+    dZ2[e] = from_float<E>(v);
+}
+
+// ----------------------------------------------------------------------------- optimizer
+// SGD or Adam over the flat parameter array; in mixed precision also refreshes the bf16 copy.
+// Block 0 additionally reduces the per-sample losses to their mean and advances the
+// sampling step counter.
+__global__ __launch_bounds__(kThreads) void optimizer_kernel(
+    unsigned int n, float* __restrict__ w, const float* __restrict__ g, float* __restrict__ m,
+    float* __restrict__ v, bf16_t* __restrict__ wb, unsigned int opt, float lr, float beta1,
+    float beta2, float eps, TrainCounters* __restrict__ ctr, const float* __restrict__ lossi,
+    unsigned int B) {
+    const unsigned int k = blockIdx.x * kThreads + threadIdx.x;
+    if (k < n) {
+        float wk = w[k];
+        const float gk = g[k];
+        if (opt == RP_SGD) {
+            wk -= lr * gk;
+        } else {
+            const float mk = beta1 * m[k] + (1.f - beta1) * gk;
+            const float vk = beta2 * v[k] + (1.f - beta2) * gk * gk;
+            m[k] = mk;
+            v[k] = vk;
+            wk -= lr * (mk / ctr->c1) / (sqrtf(vk / ctr->c2) + eps);
+        }
+        w[k] = wk;
+        if (wb) wb[k] = from_float<bf16_t>(wk);
+    }
+    if (blockIdx.x == 0 && threadIdx.x < 64) {
+        float acc = 0.f;
+        for (unsigned int i = threadIdx.x; i < B; i += 64) acc += lossi[i];
+        acc = wave_sum(acc);
+        if (threadIdx.x == 0) {
+            ctr->loss = acc / (float)B;
+            ctr->step += 1;
+        }
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void to_bf16_kernel(unsigned int n,
+                                                           const float* __restrict__ w,
+                                                           bf16_t* __restrict__ wb) {
+    const unsigned int k = blockIdx.x * kThreads + threadIdx.x;
+    if (k < n) wb[k] = from_float<bf16_t>(w[k]);
+}
+
+}  // namespace
+}  // namespace rp
+
+using rp::bf16_t;
+using rp::TrainCounters;
+
+struct trainer {
+    train_config cfg;
+    replay* rp_;
+    unsigned int Dp, Ap, H, B;
+    size_t n_params, n_padded;       // external / padded parameter counts
+    size_t oW1, ob1, oW2, ob2, oW3, ob3;
+    size_t elem;                     // bytes of an activation element
+    unsigned char* ws;
+    TrainCounters* ctr;
+    float *w, *g, *m, *v;
+    bf16_t* wb;
+    void* X;                         // [2B x Dp]
+    int* act;
+    float* rew;
+    unsigned char* term;
+    unsigned int* idx;
+    void *H1, *H2;                   // [2B x H]
+    float* Q;                        // [2B x Ap]
+    float *y, *delta, *lossi, *dQ;   // [B], [B], [B], [B x Ap]
+    void *dZ2, *dZ1;                 // [B x H]
+    hipGraph_t graph;
+    hipGraphExec_t graph_exec;
+    hipStream_t capture_stream;
+    unsigned int kernels_per_step;
+    uint64_t host_step;              // mirror of ctr->step
+};
+
+namespace rp {
+namespace {
+
+struct WsLayout {
+    size_t ctr, w, g, m, v, wb, X, act, rew, term, idx, H1, H2, Q, y, delta, lossi, dQ, dZ2, dZ1,
+        total;
+    unsigned int Dp, Ap;
+    size_t n_params, n_padded, elem;
+    size_t oW1, ob1, oW2, ob2, oW3, ob3;
+};
+
+bool ws_layout(const train_config* c, WsLayout* L) {
+    if (!c || c->state_dim == 0 || c->state_dim > 4096 || c->hidden == 0 || c->hidden % 64 != 0 ||
+        c->hidden > 8192 || c->num_actions == 0 || c->num_actions > 4096 || c->batch == 0 ||
+        c->batch > (1u << 20) || (c->param_dtype != RP_F32 && c->param_dtype != RP_BF16) ||
+        c->loss > RP_MSE || c->opt > RP_ADAM)
+        return false;
+    const size_t D = c->state_dim, H = c->hidden, A = c->num_actions, B = c->batch;
+    L->Dp = (unsigned int)align_up(D, 32);
+    L->Ap = (unsigned int)align_up(A, 32);
+    L->elem = c->param_dtype == RP_BF16 ? 2 : 4;
+    L->n_params = D * H + H + H * H + H + H * A + A;
+    L->oW1 = 0;
+    L->ob1 = L->oW1 + (size_t)L->Dp * H;
+    L->oW2 = L->ob1 + H;
+    L->ob2 = L->oW2 + H * H;
+    L->oW3 = L->ob2 + H;
+    L->ob3 = L->oW3 + H * L->Ap;
+    L->n_padded = L->ob3 + L->Ap;
+    size_t o = 0;
+    auto take = [&](size_t bytes) {
+        size_t at = o;
+        o = align_up(o + bytes, 256);
+        return at;
+    };
+    L->ctr = take(sizeof(TrainCounters));
+    L->w = take(L->n_padded * 4);
+    L->g = take(L->n_padded * 4);
+    L->m = take(L->n_padded * 4);
+    L->v = take(L->n_padded * 4);
+    L->wb = take(c->param_dtype == RP_BF16 ? L->n_padded * 2 : 0);
+    L->X = take(2 * B * L->Dp * L->elem);
+    L->act = take(B * 4);
+    L->rew = take(B * 4);
+    L->term = take(B);
+    L->idx = take(B * 4);
+    L->H1 = take(2 * B * H * L->elem);
+    L->H2 = take(2 * B * H * L->elem);
+    L->Q = take(2 * B * L->Ap * 4);
+    L->y = take(B * 4);
+    L->delta = take(B * 4);
+    L->lossi = take(B * 4);
+    L->dQ = take(B * L->Ap * 4);
+    L->dZ2 = take(B * H * L->elem);
+    L->dZ1 = take(B * H * L->elem);
+    L->total = o;
+    return true;
+}
+
+// external [W1 b1 W2 b2 W3 b3] <-> padded device order (zero rows / columns as padding)
+void pad_params(const trainer* t, const float* ext, std::vector<float>& pad) {
+    const size_t D = t->cfg.state_dim, H = t->H, A = t->cfg.num_actions, Ap = t->Ap;
+    pad.assign(t->n_padded, 0.f);
+    const float* p = ext;
+    memcpy(&pad[t->oW1], p, D * H * 4); p += D * H;
+    memcpy(&pad[t->ob1], p, H * 4);     p += H;
+    memcpy(&pad[t->oW2], p, H * H * 4); p += H * H;
+    memcpy(&pad[t->ob2], p, H * 4);     p += H;
+    for (size_t k = 0; k < H; ++k) memcpy(&pad[t->oW3 + k * Ap], p + k * A, A * 4);
+    p += H * A;
+    memcpy(&pad[t->ob3], p, A * 4);
+}
+
+void unpad_params(const trainer* t, const std::vector<float>& pad, float* ext) {
+    const size_t D = t->cfg.state_dim, H = t->H, A = t->cfg.num_actions, Ap = t->Ap;
+    float* p = ext;
+    memcpy(p, &pad[t->oW1], D * H * 4); p += D * H;
+    memcpy(p, &pad[t->ob1], H * 4);     p += H;
+    memcpy(p, &pad[t->oW2], H * H * 4); p += H * H;
+    memcpy(p, &pad[t->ob2], H * 4);     p += H;
+    for (size_t k = 0; k < H; ++k) memcpy(p + k * A, &pad[t->oW3 + k * Ap], A * 4);
+    p += H * A;
+    memcpy(p, &pad[t->ob3], A * 4);
+}
+
+template <typename TA, typename TB, typename TC, bool TRA, bool TRB, int EPI>
+void gemm(hipStream_t st, int M, int N, int K, const void* A, int lda, const void* B, int ldb,
+          void* C, int ldc, const float* bias, const void* mask, int ldmask) {
+    dim3 grid((N + 63) / 64, (M + 63) / 64);
+    hipLaunchKernelGGL((gemm_kernel<TA, TB, TC, TRA, TRB, EPI>), grid, dim3(kThreads), 0, st, M, N,
+                       K, static_cast<const TA*>(A), lda, static_cast<const TB*>(B), ldb,
+                       static_cast<TC*>(C), ldc, bias, static_cast<const TC*>(mask), ldmask);
+}
+
+// Enqueue every kernel of one executed train step (after the append).  E is the element
+// type of activations and of the matrices the products read.
+template <typename E>
+hipError_t enqueue_step(trainer* t, hipStream_t st, unsigned int* count) {
+    const int B = (int)t->B, H = (int)t->H, Dp = (int)t->Dp, Ap = (int)t->Ap;
+    const unsigned int A = t->cfg.num_actions;
+    const bool mixed = t->cfg.param_dtype == RP_BF16;
+    const unsigned char* wsrc = mixed ? reinterpret_cast<const unsigned char*>(t->wb)
+                                      : reinterpret_cast<const unsigned char*>(t->w);
+    const size_t eb = t->elem;
+    const void* W1 = wsrc + t->oW1 * eb;
+    const void* W2 = wsrc + t->oW2 * eb;
+    const void* W3 = wsrc + t->oW3 * eb;
+    unsigned int n = 0;
+
+    // sample B slots with the device-resident step counter and unpack into X = [S ; S']
+    hipError_t e = launch_sample_gather(
+        t->rp_->geom, t->rp_->cfg.seed, 0, &t->ctr->step, t->B, t->X,
+        static_cast<unsigned char*>(t->X) + (size_t)B * Dp * eb, t->Dp, t->act, t->rew, t->term,
+        t->idx, st);
+    if (e != hipSuccess) return e;
+    ++n;
+    // forward on the 2B rows of X
+    gemm<E, E, E, false, false, EPI_BIAS_RELU>(st, 2 * B, H, Dp, t->X, Dp, W1, H, t->H1, H,
+                                               t->w + t->ob1, nullptr, 0); ++n;
+    gemm<E, E, E, false, false, EPI_BIAS_RELU>(st, 2 * B, H, H, t->H1, H, W2, H, t->H2, H,
+                                               t->w + t->ob2, nullptr, 0); ++n;
+    gemm<E, E, float, false, false, EPI_BIAS>(st, 2 * B, Ap, H, t->H2, H, W3, Ap, t->Q, Ap,
+                                              t->w + t->ob3, nullptr, 0); ++n;
+    // targets, TD errors, loss terms, dL/dQ
+    hipLaunchKernelGGL(td_loss_kernel, dim3((B + 3) / 4), dim3(kThreads), 0, st, t->B, A, t->Ap,
+                       t->Q, t->act, t->rew, t->term, t->cfg.gamma, t->cfg.loss, t->y, t->delta,
+                       t->lossi, t->dQ, t->ctr, t->cfg.beta1, t->cfg.beta2); ++n;
+    // output layer
+    gemm<E, float, float, true, false, EPI_NONE>(st, H, Ap, B, t->H2, H, t->dQ, Ap,
+                                                 t->g + t->oW3, Ap, nullptr, nullptr, 0); ++n;
+    hipLaunchKernelGGL(colsum_kernel<float>, dim3((Ap + kThreads - 1) / kThreads), dim3(kThreads),
+                       0, st, B, Ap, t->dQ, Ap, t->g + t->ob3); ++n;
+    hipLaunchKernelGGL(dz_out_kernel<E>, dim3(((size_t)B * H + kThreads - 1) / kThreads),
+                       dim3(kThreads), 0, st, t->B, t->H, A, t->Ap, t->dQ, t->act,
+                       static_cast<const E*>(W3), static_cast<const E*>(t->H2),
+                       static_cast<E*>(t->dZ2)); ++n;
+    // second hidden layer
+    gemm<E, E, float, true, false, EPI_NONE>(st, H, H, B, t->H1, H, t->dZ2, H, t->g + t->oW2, H,
+                                             nullptr, nullptr, 0); ++n;
+    hipLaunchKernelGGL(colsum_kernel<E>, dim3((H + kThreads - 1) / kThreads), dim3(kThreads), 0, st,
+                       B, H, static_cast<const E*>(t->dZ2), H, t->g + t->ob2); ++n;
+    gemm<E, E, E, false, true, EPI_MASK>(st, B, H, H, t->dZ2, H, W2, H, t->dZ1, H, nullptr, t->H1,
+                                         H); ++n;
+    // first hidden layer
+    gemm<E, E, float, true, false, EPI_NONE>(st, Dp, H, B, t->X, Dp, t->dZ1, H, t->g + t->oW1, H,
+                                             nullptr, nullptr, 0); ++n;
+    hipLaunchKernelGGL(colsum_kernel<E>, dim3((H + kThreads - 1) / kThreads), dim3(kThreads), 0, st,
+                       B, H, static_cast<const E*>(t->dZ1), H, t->g + t->ob1); ++n;
+    // update
+    hipLaunchKernelGGL(optimizer_kernel, dim3((t->n_padded + kThreads - 1) / kThreads),
+                       dim3(kThreads), 0, st, (unsigned int)t->n_padded, t->w, t->g, t->m, t->v,
+                       t->wb, t->cfg.opt, t->cfg.lr, t->cfg.beta1, t->cfg.beta2, t->cfg.eps, t->ctr,
+                       t->lossi, t->B); ++n;
+    if (count) *count = n;
+    return hipGetLastError();
+}
+
+hipError_t enqueue_append_and_step(trainer* t, hipStream_t st, unsigned int* count) {
+    unsigned int n = 0, k = 0;
+    replay* r = t->rp_;
+    if (t->cfg.appends_per_step) {
+        hipError_t e = launch_append(r->geom, t->cfg.appends_per_step, r->stage_s, r->stage_s_next,
+                                     r->stage_a, r->stage_r, r->stage_term, st);
+        if (e != hipSuccess) return e;
+        ++n;
+    }
+    hipError_t e = t->cfg.param_dtype == RP_BF16 ? enqueue_step<bf16_t>(t, st, &k)
+                                                 : enqueue_step<float>(t, st, &k);
+    if (count) *count = n + k;
+    return e;
+}
+
+}  // namespace
+}  // namespace rp
+
+extern "C" {
+
+size_t train_param_count(const train_config* cfg) {
+    rp::WsLayout L;
+    return rp::ws_layout(cfg, &L) ? L.n_params : 0;
+}
+
+size_t train_workspace_bytes(const train_config* cfg) {
+    rp::WsLayout L;
+    return rp::ws_layout(cfg, &L) ? L.total : 0;
+}
+
+rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspace, size_t bytes,
+                       const float* host_init_params, trainer_t** out) {
+    RP_REQUIRE(cfg && rp_ && dev_workspace && host_init_params && out, "train_create: null argument");
+    rp::WsLayout L;
+    RP_REQUIRE(rp::ws_layout(cfg, &L),
+               "train_create: invalid configuration (hidden must be a multiple of 64; batch, "
+               "state_dim, num_actions >= 1)");
+    RP_REQUIRE(rp_->cfg.layout == RP_PAIR, "train_create: the trainer needs a PAIR replay");
+    RP_REQUIRE(rp_->cfg.state_dim == cfg->state_dim, "train_create: state_dim %u != replay's %u",
+               cfg->state_dim, rp_->cfg.state_dim);
+    RP_REQUIRE((cfg->param_dtype == RP_F32 && rp_->cfg.state_dtype == RP_F32) ||
+                   (cfg->param_dtype == RP_BF16 && rp_->cfg.state_dtype == RP_BF16),
+               "train_create: param_dtype and the replay's state_dtype must both be F32 or both BF16");
+    RP_REQUIRE(cfg->appends_per_step <= rp_->cfg.max_append && cfg->appends_per_step <= rp_->cfg.capacity,
+               "train_create: appends_per_step %u exceeds the replay's max_append %u or capacity",
+               cfg->appends_per_step, rp_->cfg.max_append);
+    RP_REQUIRE((reinterpret_cast<uintptr_t>(dev_workspace) & 255u) == 0,
+               "train_create: dev_workspace must be 256-byte aligned");
+    if (bytes < L.total) {
+        rp::set_error("train_create: workspace of %zu bytes is smaller than the %zu needed", bytes,
+                      L.total);
+        return RP_ENOMEM;
+    }
+    trainer* t = new (std::nothrow) trainer();
+    if (!t) {
+        rp::set_error("train_create: out of host memory");
+        return RP_ENOMEM;
+    }
+    t->cfg = *cfg;
+    t->rp_ = rp_;
+    t->Dp = L.Dp; t->Ap = L.Ap; t->H = cfg->hidden; t->B = cfg->batch;
+    t->n_params = L.n_params; t->n_padded = L.n_padded; t->elem = L.elem;
+    t->oW1 = L.oW1; t->ob1 = L.ob1; t->oW2 = L.oW2; t->ob2 = L.ob2; t->oW3 = L.oW3; t->ob3 = L.ob3;
+    unsigned char* ws = static_cast<unsigned char*>(dev_workspace);
+    t->ws = ws;
+    t->ctr = reinterpret_cast<TrainCounters*>(ws + L.ctr);
+    t->w = reinterpret_cast<float*>(ws + L.w);
+    t->g = reinterpret_cast<float*>(ws + L.g);
+    t->m = reinterpret_cast<float*>(ws + L.m);
+    t->v = reinterpret_cast<float*>(ws + L.v);
+    t->wb = cfg->param_dtype == RP_BF16 ? reinterpret_cast<bf16_t*>(ws + L.wb) : nullptr;
+    t->X = ws + L.X;
+    t->act = reinterpret_cast<int*>(ws + L.act);
+    t->rew = reinterpret_cast<float*>(ws + L.rew);
+    t->term = ws + L.term;
+    t->idx = reinterpret_cast<unsigned int*>(ws + L.idx);
+    t->H1 = ws + L.H1;
+    t->H2 = ws + L.H2;
+    t->Q = reinterpret_cast<float*>(ws + L.Q);
+    t->y = reinterpret_cast<float*>(ws + L.y);
+    t->delta = reinterpret_cast<float*>(ws + L.delta);
+    t->lossi = reinterpret_cast<float*>(ws + L.lossi);
+    t->dQ = reinterpret_cast<float*>(ws + L.dQ);
+    t->dZ2 = ws + L.dZ2;
+    t->dZ1 = ws + L.dZ1;
+    t->graph = nullptr;
+    t->graph_exec = nullptr;
+    t->capture_stream = nullptr;
+    t->host_step = 0;
+
+    auto fail = [&](rp_status s) {
+        train_destroy(t);
+        return s;
+    };
+    hipError_t e = hipMemset(ws, 0, L.total);  // zero padding columns, moments, counters
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        rp::set_error("train_create: clearing the workspace failed: %s", hipGetErrorString(e));
+        return fail(RP_EHIP);
+    }
+    rp_status s = train_set_state(t, host_init_params, nullptr, nullptr, 0, 0);
+    if (s != RP_OK) return fail(s);
+
+    if (cfg->use_graph) {
+        e = hipStreamCreateWithFlags(&t->capture_stream, hipStreamNonBlocking);
+        if (e == hipSuccess) e = hipStreamBeginCapture(t->capture_stream, hipStreamCaptureModeThreadLocal);
+        if (e == hipSuccess) {
+            hipError_t ek = rp::enqueue_append_and_step(t, t->capture_stream, &t->kernels_per_step);
+            e = hipStreamEndCapture(t->capture_stream, &t->graph);
+            if (ek != hipSuccess) e = ek;
+        }
+        if (e == hipSuccess) e = hipGraphInstantiate(&t->graph_exec, t->graph, nullptr, nullptr, 0);
+        if (e != hipSuccess) {
+            rp::set_error("train_create: recording the step graph failed: %s", hipGetErrorString(e));
+            return fail(RP_EHIP);
+        }
+    } else {
+        // count the launches without running them: the count is static
+        t->kernels_per_step = (cfg->appends_per_step ? 1u : 0u) + 14u;
+    }
+    *out = t;
+    return RP_OK;
+}
+
+rp_status train_destroy(trainer_t* t) {
+    if (!t) return RP_OK;
+    if (t->graph_exec) (void)hipGraphExecDestroy(t->graph_exec);
+    if (t->graph) (void)hipGraphDestroy(t->graph);
+    if (t->capture_stream) (void)hipStreamDestroy(t->capture_stream);
+    delete t;
+    return RP_OK;
+}
+
+rp_status train_step(trainer_t* t, const void* s, const void* s_next, const int32_t* a,
+                     const float* r, const uint8_t* term, int src_is_device, void* hip_stream) {
+    RP_REQUIRE(t, "train_step: null handle");
+    replay* rpl = t->rp_;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const uint64_t n = t->cfg.appends_per_step;
+    if (n) {
+        RP_REQUIRE(s && s_next && a && r && term, "train_step: null field array for the append");
+        const hipMemcpyKind kind = src_is_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+        const size_t sb = rpl->geom.state_bytes;
+        RP_CHECK_HIP(hipMemcpyAsync(rpl->stage_s, s, n * sb, kind, st));
+        RP_CHECK_HIP(hipMemcpyAsync(rpl->stage_s_next, s_next, n * sb, kind, st));
+        RP_CHECK_HIP(hipMemcpyAsync(rpl->stage_a, a, n * 4, kind, st));
+        RP_CHECK_HIP(hipMemcpyAsync(rpl->stage_r, r, n * 4, kind, st));
+        RP_CHECK_HIP(hipMemcpyAsync(rpl->stage_term, term, n, kind, st));
+    }
+    const uint64_t total_after = rpl->total + n;
+    const uint64_t size_after = rpl->size + n > rpl->cfg.capacity ? rpl->cfg.capacity : rpl->size + n;
+    const bool train = total_after >= rpl->cfg.burn_in && size_after >= 1;
+    if (!train) {
+        if (n)
+            RP_CHECK_HIP(rp::launch_append(rpl->geom, n, rpl->stage_s, rpl->stage_s_next, rpl->stage_a,
+                                           rpl->stage_r, rpl->stage_term, st));
+    } else if (t->graph_exec) {
+        RP_CHECK_HIP(hipGraphLaunch(t->graph_exec, st));
+    } else {
+        RP_CHECK_HIP(rp::enqueue_append_and_step(t, st, nullptr));
+    }
+    rpl->total = total_after;
+    rpl->size = size_after;
+    rpl->head = (rpl->head + n) % rpl->cfg.capacity;
+    if (!train) return RP_SKIPPED_BURN_IN;
+    t->host_step += 1;
+    return RP_OK;
+}
+
+rp_status train_get_params(trainer_t* t, float* params) {
+    RP_REQUIRE(t && params, "train_get_params: null argument");
+    std::vector<float> pad(t->n_padded);
+    RP_CHECK_HIP(hipDeviceSynchronize());
+    RP_CHECK_HIP(hipMemcpy(pad.data(), t->w, t->n_padded * 4, hipMemcpyDeviceToHost));
+    rp::unpad_params(t, pad, params);
+    return RP_OK;
+}
+
+rp_status train_get_grads(trainer_t* t, float* grads) {
+    RP_REQUIRE(t && grads, "train_get_grads: null argument");
+    std::vector<float> pad(t->n_padded);
+    RP_CHECK_HIP(hipDeviceSynchronize());
+    RP_CHECK_HIP(hipMemcpy(pad.data(), t->g, t->n_padded * 4, hipMemcpyDeviceToHost));
+    rp::unpad_params(t, pad, grads);
+    return RP_OK;
+}
+
+rp_status train_get_opt_state(trainer_t* t, float* m, float* v, uint64_t* adam_t, uint64_t* step) {
+    RP_REQUIRE(t, "train_get_opt_state: null handle");
+    std::vector<float> pad(t->n_padded);
+    RP_CHECK_HIP(hipDeviceSynchronize());
+    if (m) {
+        RP_CHECK_HIP(hipMemcpy(pad.data(), t->m, t->n_padded * 4, hipMemcpyDeviceToHost));
+        rp::unpad_params(t, pad, m);
+    }
+    if (v) {
+        RP_CHECK_HIP(hipMemcpy(pad.data(), t->v, t->n_padded * 4, hipMemcpyDeviceToHost));
+        rp::unpad_params(t, pad, v);
+    }
+    TrainCounters c;
+    RP_CHECK_HIP(hipMemcpy(&c, t->ctr, sizeof(c), hipMemcpyDeviceToHost));
+    if (adam_t) *adam_t = c.adam_t;
+    if (step) *step = c.step;
+    return RP_OK;
+}
+
+rp_status train_set_state(trainer_t* t, const float* params, const float* m, const float* v,
+                          uint64_t adam_t, uint64_t step) {
+    RP_REQUIRE(t && params, "train_set_state: null argument");
+    std::vector<float> pad;
+    RP_CHECK_HIP(hipDeviceSynchronize());
+    rp::pad_params(t, params, pad);
+    RP_CHECK_HIP(hipMemcpy(t->w, pad.data(), t->n_padded * 4, hipMemcpyHostToDevice));
+    if (m) {
+        rp::pad_params(t, m, pad);
+        RP_CHECK_HIP(hipMemcpy(t->m, pad.data(), t->n_padded * 4, hipMemcpyHostToDevice));
+    }
+    if (v) {
+        rp::pad_params(t, v, pad);
+        RP_CHECK_HIP(hipMemcpy(t->v, pad.data(), t->n_padded * 4, hipMemcpyHostToDevice));
+    }
+    TrainCounters c;
+    RP_CHECK_HIP(hipMemcpy(&c, t->ctr, sizeof(c), hipMemcpyDeviceToHost));
+    c.adam_t = adam_t;
+    c.step = step;
+    RP_CHECK_HIP(hipMemcpy(t->ctr, &c, sizeof(c), hipMemcpyHostToDevice));
+    t->host_step = step;
+    if (t->wb) {
+        hipLaunchKernelGGL(rp::to_bf16_kernel, dim3((t->n_padded + rp::kThreads - 1) / rp::kThreads),
+                           dim3(rp::kThreads), 0, nullptr, (unsigned int)t->n_padded, t->w, t->wb);
+        RP_CHECK_HIP(hipGetLastError());
+    }
+    RP_CHECK_HIP(hipDeviceSynchronize());
+    return RP_OK;
+}
+
+rp_status train_get_last(trainer_t* t, float* q, float* q_next, float* y, float* delta, float* loss,
+                         uint32_t* idx) {
+    RP_REQUIRE(t, "train_get_last: null handle");
+    const size_t B = t->B, A = t->cfg.num_actions, Ap = t->Ap;
+    RP_CHECK_HIP(hipDeviceSynchronize());
+    if (q || q_next) {
+        std::vector<float> Q(2 * B * Ap);
+        RP_CHECK_HIP(hipMemcpy(Q.data(), t->Q, Q.size() * 4, hipMemcpyDeviceToHost));
+        for (size_t i = 0; i < B; ++i) {
+            if (q) memcpy(q + i * A, &Q[i * Ap], A * 4);
+            if (q_next) memcpy(q_next + i * A, &Q[(B + i) * Ap], A * 4);
+        }
+    }
+    if (y) RP_CHECK_HIP(hipMemcpy(y, t->y, B * 4, hipMemcpyDeviceToHost));
+    if (delta) RP_CHECK_HIP(hipMemcpy(delta, t->delta, B * 4, hipMemcpyDeviceToHost));
+    if (idx) RP_CHECK_HIP(hipMemcpy(idx, t->idx, B * 4, hipMemcpyDeviceToHost));
+    if (loss) {
+        TrainCounters c;
+        RP_CHECK_HIP(hipMemcpy(&c, t->ctr, sizeof(c), hipMemcpyDeviceToHost));
+        *loss = c.loss;
+    }
+    return RP_OK;
+}
+
+rp_status train_kernels_per_step(trainer_t* t, uint32_t* n) {
+    RP_REQUIRE(t && n, "train_kernels_per_step: null argument");
+    *n = t->kernels_per_step;
+    return RP_OK;
+}
+
+}  // extern "C"

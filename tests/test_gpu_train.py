@@ -1,0 +1,236 @@
+"""GPU parity of train_step against the CPU oracle, teacher-forced: before each compared
+step the oracle is given the GPU's own state (weights, Adam moments, t), both take one step
+on the same sampled batch, and Q-values, targets, loss, gradients and new weights are compared.
+
+Tolerance (written here as the test of record): |x - y| <= rtol * max(|x|, |y|) + rtol * max|ref|
+with rtol = 1e-5 for fp32 and 2e-2 for the bf16 mixed-precision path, for Q-values, targets,
+loss and updated weights.  Gradients and Adam moments are linear (quadratic for v) in
+clip(delta) with delta = y - Q(s,a), a difference of two quantities that each carry the Q
+tolerance, so in fp32 their bound is 10x (m: 10x, v: 20x) the Q bound; a wrong index, sign or
+operand in the backward pass is off by O(1), far outside either.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1801_03138_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+F32_RTOL, BF16_RTOL = 1e-5, 2e-2
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_1801_03138_amd import binding
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    binding.lib()
+    return binding
+
+
+def assert_close(got, ref, rtol, what):
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    assert got.shape == ref.shape, what
+    assert np.isfinite(got).all(), what
+    scale = np.abs(ref).max() if ref.size else 0.0
+    err = np.abs(got - ref)
+    bound = rtol * np.maximum(np.abs(got), np.abs(ref)) + rtol * scale
+    worst = int(np.argmax(err - bound))
+    assert (err <= bound).all(), (what, worst, got.ravel()[worst], ref.ravel()[worst], scale)
+
+
+class Pair:
+    """A GPU replay + trainer and the oracle ring it is compared with."""
+
+    def __init__(self, B, *, capacity, D, H, A, batch, burn_in, seed, dtype="f32", loss="huber",
+                 opt="adam", lr=1e-4, appends=1, use_graph=True, max_append=4096):
+        self.B, self.D, self.H, self.A, self.batch, self.seed = B, D, H, A, batch, seed
+        self.bf16 = dtype == "bf16"
+        sd = B.RP_BF16 if self.bf16 else B.RP_F32
+        self.gpu_ring = B.Replay(capacity, D, sd, B.RP_PAIR, burn_in=burn_in, seed=seed,
+                                 max_append=max_append)
+        self.ref_ring = oracle.Ring(capacity, D, oracle.BF16 if self.bf16 else oracle.F32,
+                                    oracle.PAIR, burn_in=burn_in)
+        self.p0 = synth.init_params(D, H, A, seed)
+        f = np.float32
+        self.hyper = dict(lr=f(lr), gamma=f(0.99), beta1=f(0.9), beta2=f(0.999), eps=f(1e-8))
+        self.trainer = B.Trainer(self.gpu_ring, H, A, batch, param_dtype=sd,
+                                 loss=B.RP_HUBER if loss == "huber" else B.RP_MSE,
+                                 opt=B.RP_ADAM if opt == "adam" else B.RP_SGD,
+                                 appends_per_step=appends, use_graph=use_graph,
+                                 init_params=self.p0, **{k: float(v) for k, v in self.hyper.items()})
+        self.cfg = oracle.make_cfg(D, H, A, batch,
+                                   loss=oracle.HUBER if loss == "huber" else oracle.MSE,
+                                   opt=oracle.ADAM if opt == "adam" else oracle.SGD,
+                                   bf16=int(self.bf16), **{k: float(v) for k, v in self.hyper.items()})
+        self.rtol = BF16_RTOL if self.bf16 else F32_RTOL
+
+    def append_only(self, part, device_src=True):
+        self.ref_ring.append(part["s"], part["s_next"], part["a"], part["r"], part["term"])
+        if device_src:
+            d = {k: torch.from_numpy(v.view(np.int16) if v.dtype == np.uint16 else v).cuda()
+                 for k, v in part.items()}
+            self.gpu_ring.append(d["s"], d["s_next"], d["a"], d["r"], d["term"])
+            torch.cuda.synchronize()
+        else:
+            self.gpu_ring.append(part["s"], part["s_next"], part["a"], part["r"], part["term"])
+
+    def states_f64(self, x):
+        return (synth.bf16_bits_to_f32(x) if self.bf16 else x).astype(np.float64)
+
+    def step(self, part, compare):
+        """Append `part` on both sides and take one train step; returns the GPU status."""
+        tr = self.trainer
+        if compare:
+            p, (m, v, t, step) = tr.params(), tr.opt_state()
+        self.ref_ring.append(part["s"], part["s_next"], part["a"], part["r"], part["term"])
+        status = tr.step(part["s"], part["s_next"], part["a"], part["r"], part["term"])
+        if not compare:
+            return status
+        idx = self.ref_ring.sample(self.seed, step, self.batch)
+        if idx is None:
+            assert status == self.B.RP_SKIPPED_BURN_IN
+            assert np.array_equal(tr.params(), p)
+            return status
+        assert status == 0
+        s, sn, a, r, term = self.ref_ring.gather(idx)
+        ref = oracle.train_step(self.cfg, p, m, v, t, self.states_f64(s), self.states_f64(sn), a,
+                                r, term)
+        last = tr.last()
+        assert np.array_equal(last["idx"], idx)
+        rt = self.rtol
+        assert_close(last["Q"], ref.Q, rt, "Q(s,.)")
+        assert_close(last["Qn"], ref.Qn, rt, "Q(s',.)")
+        assert_close(last["y"], ref.y, rt, "targets")
+        # delta = y - q is a difference of O(1) numbers: bound it on that scale
+        assert np.abs(last["delta"] - ref.delta).max() <= 2 * rt * max(1.0, np.abs(ref.y).max(),
+                                                                      np.abs(ref.Q).max())
+        assert_close([last["loss"]], [ref.loss], rt, "loss")
+        assert_close(tr.grads(), ref.grads, 10 * rt if not self.bf16 else 2 * rt, "gradients")
+        new_p = tr.params()
+        assert_close(new_p, ref.params, rt, "updated weights")
+        m2, v2, t2, step2 = tr.opt_state()
+        assert step2 == step + 1
+        if self.cfg.opt == oracle.ADAM:
+            assert t2 == t + 1 == ref.t
+            assert_close(m2, ref.m, 10 * rt if not self.bf16 else 2 * rt, "Adam m")
+            assert_close(v2, ref.v, 20 * rt if not self.bf16 else 4 * rt, "Adam v")
+        else:
+            # the update itself, on its own scale
+            assert_close(new_p.astype(np.float64) - p, ref.params - p.astype(np.float64),
+                         1e-3 if not self.bf16 else 4 * rt, "weight update")
+        return status
+
+
+def test_tiny_config_all_100_steps(B):
+    """Ring 1024, 27-64-64-8, batch 32, SGD 1e-3, burn-in 256, one append per step."""
+    rows = synth.experiences(4096, 27, 8, 0.01, seed=0)
+    pr = Pair(B, capacity=1024, D=27, H=64, A=8, batch=32, burn_in=256, seed=0, opt="sgd", lr=1e-3)
+    executed = 0
+    for k in range(4096):
+        part = synth.take(rows, k, k + 1)
+        if executed < 100:
+            st = pr.step(part, compare=True)
+            assert st == (B.RP_SKIPPED_BURN_IN if k + 1 < 256 else 0)
+            executed += st == 0
+        else:
+            pr.append_only(part, device_src=False)
+    assert executed == 100
+    assert pr.gpu_ring.state() == pr.ref_ring.state() == (0, 1024, 4096)
+    g, o = pr.gpu_ring.read_rows(0, 1024), pr.ref_ring.read(0, 1024)
+    assert all(np.array_equal(x.view(np.uint8), y.view(np.uint8)) for x, y in zip(g, o))
+
+
+@pytest.mark.parametrize("loss,opt", [("huber", "adam"), ("mse", "sgd"), ("mse", "adam")])
+def test_small_net_every_loss_and_optimizer(B, loss, opt):
+    rows = synth.experiences(300, 11, 5, 0.2, seed=4)
+    pr = Pair(B, capacity=128, D=11, H=64, A=5, batch=50, burn_in=20, seed=9, loss=loss, opt=opt,
+              lr=1e-3, appends=3)
+    for k in range(0, 300, 3):
+        pr.step(synth.take(rows, k, k + 3), compare=True)
+
+
+def test_graph_and_direct_launch_agree_bitwise(B):
+    rows = synth.experiences(200, 27, 30, 0.05, seed=2)
+    outs = []
+    for use_graph in (True, False):
+        pr = Pair(B, capacity=150, D=27, H=64, A=30, batch=64, burn_in=10, seed=3,
+                  use_graph=use_graph)
+        for k in range(200):
+            pr.step(synth.take(rows, k, k + 1), compare=False)
+        outs.append((pr.trainer.params(), pr.trainer.last()["loss"], pr.trainer.opt_state()))
+        assert pr.gpu_ring.state() == pr.ref_ring.state()
+    assert np.array_equal(outs[0][0], outs[1][0]) and outs[0][1] == outs[1][1]
+    assert outs[0][2][2:] == outs[1][2][2:] == (191, 191)
+
+
+def test_paper_shaped_config_sampled_steps(B):
+    """Capacity 1e6, 27-256-256-30, batch 128, Adam 1e-4, burn-in 50,000, 10,000 steps."""
+    rows = synth.experiences(60_000, 27, 30, 0.005, seed=0)
+    pr = Pair(B, capacity=1_000_000, D=27, H=256, A=30, batch=128, burn_in=50_000, seed=0)
+    pr.append_only(synth.take(rows, 0, 49_999))
+    compared = {0, 1, 2, 10, 100, 1000, 9999}
+    for k in range(10_000):
+        st = pr.step(synth.take(rows, 49_999 + k, 50_000 + k), compare=k in compared)
+        assert st == 0
+    assert pr.trainer.opt_state()[2:] == (10_000, 10_000)
+    assert pr.gpu_ring.state() == pr.ref_ring.state() == (59_999, 59_999, 59_999)
+    assert pr.trainer.kernels_per_step() >= 1
+
+
+def test_terminal_rows_and_out_of_range_actions_are_safe(B):
+    rows = synth.experiences(64, 27, 8, 1.0, seed=6)       # every experience terminal
+    pr = Pair(B, capacity=64, D=27, H=64, A=8, batch=32, burn_in=64, seed=1, opt="sgd", lr=1e-3,
+              appends=64)
+    pr.step(rows, compare=True)
+    last = pr.trainer.last()
+    assert np.array_equal(last["y"], pr.ref_ring.gather(last["idx"])[3])
+
+
+def test_mixed_precision_small(B):
+    """bf16 matrix inputs, fp32 accumulation and master weights, on a net that spans several tiles."""
+    rows = synth.experiences(600, 27, 30, 0.05, seed=7, state_dtype="bf16")
+    pr = Pair(B, capacity=512, D=27, H=128, A=30, batch=200, burn_in=100, seed=2, dtype="bf16",
+              appends=4)
+    for k in range(0, 600, 4):
+        pr.step(synth.take(rows, k, k + 4), compare=(k % 40 == 0) or k >= 560)
+
+
+def test_wide_config_first_steps(B):
+    """Capacity 4e6 (bf16 states), 27-1024-1024-30, batch 4096, 64 appends per step, Adam."""
+    oracle.set_threads(16)
+    try:
+        rows = synth.experiences(200_000, 27, 30, 0.005, seed=0, state_dtype="bf16")
+        pr = Pair(B, capacity=4_000_000, D=27, H=1024, A=30, batch=4096, burn_in=0, seed=0,
+                  dtype="bf16", appends=64, max_append=64)
+        pr.append_only(synth.take(rows, 0, 199_808))
+        for k in range(3):
+            lo = 199_808 + 64 * k
+            assert pr.step(synth.take(rows, lo, lo + 64), compare=True) == 0
+    finally:
+        oracle.set_threads(1)
+
+
+def test_burn_in_skips_training_but_appends(B):
+    rows = synth.experiences(12, 5, 3, 0.1, seed=8)
+    pr = Pair(B, capacity=16, D=5, H=64, A=3, batch=4, burn_in=10, seed=0, appends=2)
+    for k in range(0, 12, 2):
+        st = pr.step(synth.take(rows, k, k + 2), compare=True)
+        assert st == (B.RP_SKIPPED_BURN_IN if k + 2 < 10 else 0)
+    assert pr.trainer.opt_state()[2:] == (2, 2)
+
+
+def test_trainer_rejects_bad_configurations(B):
+    ring = B.Replay(64, 5)
+    p = synth.init_params(5, 64, 3)
+    with pytest.raises(B.ReplayError):
+        B.Trainer(ring, 50, 3, 4, init_params=synth.init_params(5, 50, 3))      # hidden % 64
+    with pytest.raises(B.ReplayError):
+        B.Trainer(ring, 64, 3, 4, param_dtype=B.RP_BF16, init_params=p)        # dtype mismatch
+    with pytest.raises(B.ReplayError):
+        B.Trainer(ring, 64, 3, 4, appends_per_step=10**6, init_params=p)
+    chain = B.Replay(64, 5, B.RP_F32, B.RP_CHAIN)
+    with pytest.raises(B.ReplayError):
+        B.Trainer(chain, 64, 3, 4, init_params=p)
