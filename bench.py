@@ -1,0 +1,292 @@
+#!/usr/bin/env python3
+"""Benchmark of the device-resident replay train step on one MI355X.
+
+A "step" is one pass of the whole hot path: append the new experience(s), sample a
+batch on the device, gather it, forward on s and s', TD target and loss, backward,
+optimizer.  The headline value is train steps/s on the paper-shaped workload
+(capacity 1,000,000, 27 floats per state, 30 actions, batch 128, MLP 27-256-256-30,
+Adam) with every input already in HBM.  The same JSON line carries the gather kernel's
+HBM roofline (measured live with events), the other workloads, and the CPU oracle
+timed on this machine's host cores.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--legs p,gather,large,wide,cpu]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+BF16_MFMA_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA, published
+FP32_VALU_PEAK_TFLOPS = 157.3
+
+P_CFG = dict(capacity=1_000_000, D=27, A=30, B=128, H=256, burn_in=50_000, p_term=0.005,
+             lr=1e-4, appends=1)
+W_CFG = dict(capacity=4_000_000, D=27, A=30, B=4096, H=1024, p_term=0.005, lr=1e-4, appends=64)
+L_CFG = dict(capacity=200_000, D=84 * 84 * 4, p_term=0.001)
+GATHER_BATCHES = [32, 128, 512, 2048, 8192, 65536]
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def dev_rows(rows):
+    import torch
+    return {k: (None if v is None else
+                torch.from_numpy(v.view(np.int16) if v.dtype == np.uint16 else v).cuda())
+            for k, v in rows.items()}
+
+
+def event_time_ms(fn, reps):
+    """Average milliseconds per call of fn over `reps` back-to-back calls on the current stream."""
+    import torch
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for k in range(reps):
+        fn(k)
+    stop.record()
+    stop.synchronize()
+    return start.elapsed_time(stop) / reps
+
+
+def prefill(ring, rows, n_total):
+    """Append n_total experiences by cycling through the device copy of `rows` in large pieces."""
+    d = dev_rows(rows)
+    n = len(rows["a"])
+    done = 0
+    while done < n_total:
+        m = min(n, n_total - done)
+        ring.append(d["s"][:m], None if d["s_next"] is None else d["s_next"][:m], d["a"][:m],
+                    d["r"][:m], d["term"][:m])
+        done += m
+    import torch
+    torch.cuda.synchronize()
+
+
+# ----------------------------------------------------------------------------- legs
+def leg_paper_shaped(B, synth, steps, warmup, full_ring, host_payload=False):
+    import torch
+    c = P_CFG
+    ring = B.Replay(c["capacity"], c["D"], burn_in=c["burn_in"], seed=0, max_append=4096)
+    base = synth.experiences(100_000, c["D"], c["A"], c["p_term"], seed=0)
+    prefill(ring, base, c["capacity"] if full_ring else c["burn_in"])
+    tr = B.Trainer(ring, c["H"], c["A"], c["B"], opt=B.RP_ADAM, loss=B.RP_HUBER, lr=c["lr"],
+                   appends_per_step=c["appends"], init_params=synth.init_params(c["D"], c["H"], c["A"], 0))
+    stream_rows = synth.experiences(steps + warmup, c["D"], c["A"], c["p_term"], seed=1)
+    src = stream_rows if host_payload else dev_rows(stream_rows)
+    w = {k: v[:warmup] for k, v in src.items()}
+    t = {k: v[warmup:] for k, v in src.items()}
+    assert tr.steps(warmup, w["s"], w["s_next"], w["a"], w["r"], w["term"]) == warmup
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    done = tr.steps(steps, t["s"], t["s_next"], t["a"], t["r"], t["term"])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    assert done == steps
+    loss = tr.last()["loss"]
+    assert np.isfinite(loss)
+    return {"steps_per_s": steps / dt, "ms_per_step": 1e3 * dt / steps,
+            "kernels_per_step": tr.kernels_per_step(), "final_loss": loss,
+            "ring_rows": ring.state()[1]}
+
+
+def leg_gather_sweep(B, synth, reps):
+    import torch
+    c = P_CFG
+    ring = B.Replay(c["capacity"], c["D"], seed=0, max_append=4096)
+    prefill(ring, synth.experiences(100_000, c["D"], c["A"], c["p_term"], seed=0), c["capacity"])
+    out = []
+    for batch in GATHER_BATCHES:
+        bufs = ring.alloc_batch(batch)
+        for k in range(10):
+            ring.sample_gather(k, batch, out=bufs)
+        ms = event_time_ms(lambda k: ring.sample_gather(k, batch, out=bufs), reps)
+        alg = batch * 2 * (2 * c["D"] + 3) * 4      # 228 B read + 228 B written per sampled row
+        out.append({"batch": batch, "us_per_call": 1e3 * ms, "alg_bytes": alg,
+                    "GBps": alg / (ms * 1e-3) / 1e9})
+    return out
+
+
+def leg_large_state(B, reps):
+    import torch
+    c = L_CFG
+    ring = B.Replay(c["capacity"], c["D"], B.RP_U8, B.RP_CHAIN, seed=0, max_append=64)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(0)
+    chunk = 10_000
+    for lo in range(0, c["capacity"], chunk):
+        s = torch.randint(0, 256, (chunk, c["D"]), dtype=torch.uint8, device="cuda", generator=g)
+        a = torch.randint(0, 18, (chunk,), dtype=torch.int32, device="cuda", generator=g)
+        r = torch.randn(chunk, device="cuda", generator=g)
+        term = (torch.rand(chunk, device="cuda", generator=g) < c["p_term"]).to(torch.uint8)
+        ring.append(s, None, a, r, term)
+    torch.cuda.synchronize()
+    out = []
+    for batch in (32, 256):
+        bufs = ring.alloc_batch(batch)
+        for k in range(5):
+            ring.sample_gather(k, batch, out=bufs)
+        ms = event_time_ms(lambda k: ring.sample_gather(k, batch, out=bufs), reps)
+        alg = batch * (2 * c["D"] + 2 * c["D"] * 4)   # two u8 states read, two fp32 states written
+        out.append({"batch": batch, "us_per_call": 1e3 * ms, "alg_bytes": alg,
+                    "GBps": alg / (ms * 1e-3) / 1e9})
+    return out
+
+
+def leg_wide(B, synth, steps, warmup):
+    import torch
+    c = W_CFG
+    ring = B.Replay(c["capacity"], c["D"], B.RP_BF16, B.RP_PAIR, seed=0, max_append=64)
+    prefill(ring, synth.experiences(250_000, c["D"], c["A"], c["p_term"], seed=0, state_dtype="bf16"),
+            c["capacity"])
+    tr = B.Trainer(ring, c["H"], c["A"], c["B"], param_dtype=B.RP_BF16, opt=B.RP_ADAM, lr=c["lr"],
+                   appends_per_step=c["appends"],
+                   init_params=synth.init_params(c["D"], c["H"], c["A"], 0))
+    n = (steps + warmup) * c["appends"]
+    pool = dev_rows(synth.experiences(n, c["D"], c["A"], c["p_term"], seed=1, state_dtype="bf16"))
+    cut = warmup * c["appends"]
+    w = {k: v[:cut] for k, v in pool.items()}
+    t = {k: v[cut:] for k, v in pool.items()}
+    tr.steps(warmup, w["s"], w["s_next"], w["a"], w["r"], w["term"])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    done = tr.steps(steps, t["s"], t["s_next"], t["a"], t["r"], t["term"])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    assert done == steps and np.isfinite(tr.last()["loss"])
+    D, H, A, Bt = c["D"], c["H"], c["A"], c["B"]
+    flops = 4 * 2 * (D * H + H * H + H * A) * Bt    # forward on s and s', backward ~ 2 forwards on s
+    return {"steps_per_s": steps / dt, "ms_per_step": 1e3 * dt / steps, "alg_flops": flops,
+            "TFLOPs": flops * steps / dt / 1e12, "kernels_per_step": tr.kernels_per_step()}
+
+
+def leg_cpu_oracle(synth, seconds_budget):
+    """The oracle's own append + sample + gather + train step on the paper-shaped workload."""
+    import oracle
+    c = P_CFG
+    rows = synth.experiences(c["burn_in"] + 4096, c["D"], c["A"], c["p_term"], seed=0)
+    cfg = oracle.make_cfg(c["D"], c["H"], c["A"], c["B"], loss=oracle.HUBER, opt=oracle.ADAM,
+                          lr=c["lr"])
+    res = {}
+    for label, threads in (("all", os.cpu_count() if (os.cpu_count() or 1) <= 16 else 16), ("one", 1)):
+        oracle.set_threads(threads)
+        ring = oracle.Ring(c["capacity"], c["D"], burn_in=c["burn_in"])
+        ring.append(rows["s"][:c["burn_in"] - 1], rows["s_next"][:c["burn_in"] - 1],
+                    rows["a"][:c["burn_in"] - 1], rows["r"][:c["burn_in"] - 1],
+                    rows["term"][:c["burn_in"] - 1])
+        p = synth.init_params(c["D"], c["H"], c["A"], 0).astype(np.float64)
+        m, v, t = np.zeros_like(p), np.zeros_like(p), 0
+        k, t0 = 0, time.perf_counter()
+        while True:
+            j = c["burn_in"] - 1 + k
+            ring.append(rows["s"][j:j + 1], rows["s_next"][j:j + 1], rows["a"][j:j + 1],
+                        rows["r"][j:j + 1], rows["term"][j:j + 1])
+            s, sn, a, r, term = ring.gather(ring.sample(0, k, c["B"]))
+            o = oracle.train_step(cfg, p, m, v, t, s, sn, a, r, term)
+            p, m, v, t = o.params, o.m, o.v, o.t
+            k += 1
+            if time.perf_counter() - t0 > seconds_budget / 2 or k >= 4096:
+                break
+        dt = time.perf_counter() - t0
+        res[label] = {"steps": k, "steps_per_s": k / dt, "threads": oracle.get_threads()}
+    oracle.set_threads(1)
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10_000)
+    ap.add_argument("--warmup", type=int, default=500)
+    ap.add_argument("--legs", default="p,pfull,phost,gather,large,wide,cpu")
+    ap.add_argument("--gather-reps", type=int, default=1000)
+    ap.add_argument("--wide-steps", type=int, default=200)
+    ap.add_argument("--cpu-seconds", type=float, default=20.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only; --gpus %d is not supported "
+                 "(no collectives or multi-GPU sharding are part of it)" % args.gpus)
+    legs = set(args.legs.split(","))
+
+    import torch
+    from paper_1801_03138_amd import binding as B
+    from paper_1801_03138_amd import synth
+    B.lib()   # raises if the HIP library is missing: there is no fallback
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    torch.cuda.set_device(0)
+
+    out = {}
+    log("[bench] paper-shaped train steps (burn-in ring) ...")
+    p = leg_paper_shaped(B, synth, args.steps, args.warmup, full_ring=False)
+    log("[bench]   %.0f steps/s, %d kernels/step" % (p["steps_per_s"], p["kernels_per_step"]))
+    if "pfull" in legs:
+        log("[bench] paper-shaped train steps (full 1M-row ring) ...")
+        out["paper_shaped_full_ring"] = leg_paper_shaped(B, synth, args.steps, args.warmup, True)
+        log("[bench]   %.0f steps/s" % out["paper_shaped_full_ring"]["steps_per_s"])
+    if "phost" in legs:
+        log("[bench] paper-shaped train steps, append payload from host memory ...")
+        out["paper_shaped_host_payload"] = leg_paper_shaped(B, synth, args.steps, args.warmup,
+                                                            False, host_payload=True)
+        log("[bench]   %.0f steps/s" % out["paper_shaped_host_payload"]["steps_per_s"])
+    roofline = None
+    if "gather" in legs:
+        log("[bench] gather sweep on the full 1M-row ring ...")
+        out["gather_sweep"] = leg_gather_sweep(B, synth, args.gather_reps)
+        for g in out["gather_sweep"]:
+            log("[bench]   B=%-6d %8.2f us  %8.1f GB/s" % (g["batch"], g["us_per_call"], g["GBps"]))
+        g = out["gather_sweep"][-1]
+        roofline = {"kernel": "sample_gather_pair_kernel<4>", "workload": "gather sweep, batch %d, "
+                    "capacity 1,000,000, 27 fp32 per state" % g["batch"], "bound": "hbm",
+                    "achieved": g["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": g["GBps"] / HBM_PEAK_GBS, "traffic": None,
+                    "alg_bytes_per_launch": g["alg_bytes"], "us_per_launch": g["us_per_call"]}
+    if "large" in legs:
+        log("[bench] large-state gather (200,000 x 84x84x4 uint8, one state per slot) ...")
+        out["large_state_gather"] = leg_large_state(B, max(50, args.gather_reps // 5))
+        for g in out["large_state_gather"]:
+            g["frac_hbm"] = g["GBps"] / HBM_PEAK_GBS
+            log("[bench]   B=%-6d %8.2f us  %8.1f GB/s" % (g["batch"], g["us_per_call"], g["GBps"]))
+    if "wide" in legs:
+        log("[bench] wide fused step (bf16, batch 4096, 27-1024-1024-30) ...")
+        w = leg_wide(B, synth, args.wide_steps, 10)
+        w["frac_mfma"] = w["TFLOPs"] / BF16_MFMA_PEAK_TFLOPS
+        out["wide_step"] = w
+        log("[bench]   %.1f steps/s, %.1f TFLOP/s" % (w["steps_per_s"], w["TFLOPs"]))
+    cpu = None
+    if "cpu" in legs:
+        log("[bench] CPU oracle on the paper-shaped workload ...")
+        o = leg_cpu_oracle(synth, args.cpu_seconds)
+        cpu = {"value": o["all"]["steps_per_s"], "unit": "steps/s", "cores": o["all"]["threads"],
+               "kind": "oracle",
+               "sample": "%d paper-shaped train steps (append 1, sample+gather 128, 27-256-256-30 "
+                         "step, Adam) after a 50,000-row burn-in" % o["all"]["steps"],
+               "value_1thread": o["one"]["steps_per_s"], "host_cpus": os.cpu_count()}
+        log("[bench]   %.1f steps/s on %d threads, %.1f on one" %
+            (cpu["value"], cpu["cores"], cpu["value_1thread"]))
+
+    line = {
+        "metric": "replay train steps/sec at B=128, cap 1M; gather GB/s vs HBM peak",
+        "value": p["steps_per_s"], "unit": "steps/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": p["ms_per_step"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "paper-shaped: capacity 1,000,000, state 27 fp32, 30 actions, "
+                               "burn-in 50,000, 1 append/step from HBM, batch 128, MLP 27-256-256-30, "
+                               "Huber, Adam 1e-4, one HIP graph per step",
+                   "kernels_per_step": p["kernels_per_step"]},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    line.update(out)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

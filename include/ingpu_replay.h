@@ -179,6 +179,16 @@ rp_status train_destroy(trainer_t* tr);
 rp_status train_step(trainer_t* tr, const void* s, const void* s_next, const int32_t* a,
                      const float* r, const uint8_t* term, int src_is_device, void* hip_stream);
 
+/*
+ * `count` consecutive train steps in one call: step k consumes experiences
+ * k*appends_per_step .. (k+1)*appends_per_step - 1 of the given arrays (which hold
+ * count*appends_per_step experiences).  Same semantics as calling train_step `count`
+ * times; *executed (may be NULL) receives the number of steps that trained.
+ */
+rp_status train_steps(trainer_t* tr, uint64_t count, const void* s, const void* s_next,
+                      const int32_t* a, const float* r, const uint8_t* term, int src_is_device,
+                      void* hip_stream, uint64_t* executed);
+
 /* Test / inspection calls; host destinations, any may be NULL; all synchronise. */
 rp_status train_get_params(trainer_t* tr, float* params);             /* fp32 master weights */
 rp_status train_get_grads(trainer_t* tr, float* grads);               /* of the last step    */

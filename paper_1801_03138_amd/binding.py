@@ -61,6 +61,7 @@ SYMBOLS = {
     "train_create": (_int, [_vp, _vp, _vp, C.c_size_t, _vp, _vp]),
     "train_destroy": (_int, [_vp]),
     "train_step": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _int, _vp]),
+    "train_steps": (_int, [_vp, _u64, _vp, _vp, _vp, _vp, _vp, _int, _vp, _vp]),
     "train_get_params": (_int, [_vp, _vp]),
     "train_get_grads": (_int, [_vp, _vp]),
     "train_get_opt_state": (_int, [_vp, _vp, _vp, _vp, _vp]),
@@ -245,6 +246,27 @@ class Trainer:
                     np.ascontiguousarray(term, np.uint8)]
             args = [_host(x) for x in keep]
         return _check(lib().train_step(self._h, *args, 1 if on_dev else 0, _stream_ptr(stream)))
+
+    def steps(self, count, s=None, s_next=None, a=None, r=None, term=None, stream=None):
+        """`count` train steps in one call; the arrays hold count*appends_per_step experiences.
+        Returns the number of steps that trained (the others only appended, during burn-in)."""
+        on_dev = isinstance(a, torch.Tensor)
+        if a is None:
+            args, keep = [None] * 5, None
+        elif on_dev:
+            args, keep = [_dev(s), _dev(s_next), _dev(a), _dev(r), _dev(term)], None
+        else:
+            st = self.replay.np_state
+            keep = [np.ascontiguousarray(s, st), np.ascontiguousarray(s_next, st),
+                    np.ascontiguousarray(a, np.int32), np.ascontiguousarray(r, np.float32),
+                    np.ascontiguousarray(term, np.uint8)]
+            args = [_host(x) for x in keep]
+        if a is not None and len(a) < count * self.cfg.appends_per_step:
+            raise ValueError("not enough experiences for that many steps")
+        done = C.c_uint64()
+        _check(lib().train_steps(self._h, count, *args, 1 if on_dev else 0, _stream_ptr(stream),
+                                 C.byref(done)))
+        return done.value
 
     def params(self):
         p = np.empty(self.n_params, np.float32)

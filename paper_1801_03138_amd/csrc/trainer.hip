@@ -616,6 +616,30 @@ rp_status train_step(trainer_t* t, const void* s, const void* s_next, const int3
     return RP_OK;
 }
 
+rp_status train_steps(trainer_t* t, uint64_t count, const void* s, const void* s_next,
+                      const int32_t* a, const float* r, const uint8_t* term, int src_is_device,
+                      void* hip_stream, uint64_t* executed) {
+    RP_REQUIRE(t, "train_steps: null handle");
+    const uint64_t n = t->cfg.appends_per_step;
+    const size_t sb = t->rp_->geom.state_bytes;
+    uint64_t done = 0;
+    for (uint64_t k = 0; k < count; ++k) {
+        const uint64_t o = k * n;
+        const rp_status st =
+            n ? train_step(t, static_cast<const unsigned char*>(s) + o * sb,
+                           static_cast<const unsigned char*>(s_next) + o * sb, a + o, r + o,
+                           term + o, src_is_device, hip_stream)
+              : train_step(t, nullptr, nullptr, nullptr, nullptr, nullptr, 0, hip_stream);
+        if (st < 0) {
+            if (executed) *executed = done;
+            return st;
+        }
+        done += st == RP_OK;
+    }
+    if (executed) *executed = done;
+    return RP_OK;
+}
+
 rp_status train_get_params(trainer_t* t, float* params) {
     RP_REQUIRE(t && params, "train_get_params: null argument");
     std::vector<float> pad(t->n_padded);
