@@ -58,6 +58,26 @@ def event_time_ms(fn, reps):
     return start.elapsed_time(stop) / reps
 
 
+def graph_time_ms(fn, launches, replays):
+    """Average milliseconds per launch when `launches` calls of fn are recorded into one graph
+    and replayed back to back: kernel time plus the GPU's own inter-kernel gap, without the
+    host's per-call cost."""
+    import torch
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for k in range(launches):
+            fn(k)
+    graph.replay()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for _ in range(replays):
+        graph.replay()
+    stop.record()
+    stop.synchronize()
+    return start.elapsed_time(stop) / (launches * replays)
+
+
 def prefill(ring, rows, n_total):
     """Append n_total experiences by cycling through the device copy of `rows` in large pieces."""
     d = dev_rows(rows)
@@ -109,10 +129,11 @@ def leg_gather_sweep(B, synth, reps):
         bufs = ring.alloc_batch(batch)
         for k in range(10):
             ring.sample_gather(k, batch, out=bufs)
-        ms = event_time_ms(lambda k: ring.sample_gather(k, batch, out=bufs), reps)
+        ms_host = event_time_ms(lambda k: ring.sample_gather(k, batch, out=bufs), reps)
+        ms = graph_time_ms(lambda k: ring.sample_gather(k, batch, out=bufs), 100, max(1, reps // 100))
         alg = batch * 2 * (2 * c["D"] + 3) * 4      # 228 B read + 228 B written per sampled row
-        out.append({"batch": batch, "us_per_call": 1e3 * ms, "alg_bytes": alg,
-                    "GBps": alg / (ms * 1e-3) / 1e9})
+        out.append({"batch": batch, "us_per_call": 1e3 * ms, "us_per_call_host_launched": 1e3 * ms_host,
+                    "alg_bytes": alg, "GBps": alg / (ms * 1e-3) / 1e9})
     return out
 
 
@@ -135,10 +156,11 @@ def leg_large_state(B, reps):
         bufs = ring.alloc_batch(batch)
         for k in range(5):
             ring.sample_gather(k, batch, out=bufs)
-        ms = event_time_ms(lambda k: ring.sample_gather(k, batch, out=bufs), reps)
+        ms_host = event_time_ms(lambda k: ring.sample_gather(k, batch, out=bufs), reps)
+        ms = graph_time_ms(lambda k: ring.sample_gather(k, batch, out=bufs), 50, max(1, reps // 50))
         alg = batch * (2 * c["D"] + 2 * c["D"] * 4)   # two u8 states read, two fp32 states written
-        out.append({"batch": batch, "us_per_call": 1e3 * ms, "alg_bytes": alg,
-                    "GBps": alg / (ms * 1e-3) / 1e9})
+        out.append({"batch": batch, "us_per_call": 1e3 * ms, "us_per_call_host_launched": 1e3 * ms_host,
+                    "alg_bytes": alg, "GBps": alg / (ms * 1e-3) / 1e9})
     return out
 
 

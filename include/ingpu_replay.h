@@ -56,6 +56,10 @@ enum { RP_F32 = 0, RP_BF16 = 1, RP_U8 = 2 };
 enum { RP_PAIR = 0, RP_CHAIN = 1 };
 enum { RP_HUBER = 0, RP_MSE = 1 };
 enum { RP_SGD = 0, RP_ADAM = 1 };
+/* train_config.flags: GRAPH = an executed step is replayed as one HIP graph launch;
+ * LAYERED = always use the one-kernel-per-layer step, also where the two-kernel step for
+ * small fp32 networks would apply (both give the same results to rounding). */
+enum { RP_TRAIN_GRAPH = 1, RP_TRAIN_LAYERED = 2 };
 
 typedef struct {
     uint64_t capacity;    /* number of experiences the replay holds (1,000,000 in the paper) */
@@ -147,7 +151,7 @@ typedef struct {
     uint32_t opt;              /* RP_SGD | RP_ADAM                                             */
     uint32_t appends_per_step; /* experiences added by every train_step (0 = none)             */
     float lr, gamma, beta1, beta2, eps;
-    uint32_t use_graph;        /* 1: the step is replayed as one HIP graph launch              */
+    uint32_t flags;            /* RP_TRAIN_GRAPH | RP_TRAIN_LAYERED                            */
 } train_config;
 
 /* number of network parameters: D*H + H + H*H + H + H*A + A */

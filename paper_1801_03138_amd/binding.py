@@ -20,6 +20,7 @@ RP_F32, RP_BF16, RP_U8 = 0, 1, 2
 RP_PAIR, RP_CHAIN = 0, 1
 RP_HUBER, RP_MSE = 0, 1
 RP_SGD, RP_ADAM = 0, 1
+RP_TRAIN_GRAPH, RP_TRAIN_LAYERED = 1, 2
 
 _NP_STATE = {RP_F32: np.float32, RP_BF16: np.uint16, RP_U8: np.uint8}
 _TORCH_OUT = {RP_F32: torch.float32, RP_BF16: torch.bfloat16, RP_U8: torch.float32}
@@ -42,7 +43,7 @@ class TrainConfig(C.Structure):
                 ("batch", C.c_uint32), ("param_dtype", C.c_uint32), ("loss", C.c_uint32),
                 ("opt", C.c_uint32), ("appends_per_step", C.c_uint32), ("lr", C.c_float),
                 ("gamma", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
-                ("eps", C.c_float), ("use_graph", C.c_uint32)]
+                ("eps", C.c_float), ("flags", C.c_uint32)]
 
 
 # every symbol include/ingpu_replay.h declares: name -> (restype, argtypes)
@@ -205,11 +206,11 @@ class Trainer:
 
     def __init__(self, replay, hidden, num_actions, batch, param_dtype=RP_F32, loss=RP_HUBER,
                  opt=RP_ADAM, appends_per_step=1, lr=1e-4, gamma=0.99, beta1=0.9, beta2=0.999,
-                 eps=1e-8, use_graph=True, init_params=None):
+                 eps=1e-8, use_graph=True, layered=False, init_params=None):
         self.replay = replay
         self.cfg = TrainConfig(replay.cfg.state_dim, hidden, num_actions, batch, param_dtype, loss,
                                opt, appends_per_step, lr, gamma, beta1, beta2, eps,
-                               1 if use_graph else 0)
+                               (RP_TRAIN_GRAPH if use_graph else 0) | (RP_TRAIN_LAYERED if layered else 0))
         nbytes = int(lib().train_workspace_bytes(C.byref(self.cfg)))
         if nbytes == 0:
             raise ReplayError(RP_EINVAL, "invalid train configuration")

@@ -183,18 +183,30 @@ __global__ __launch_bounds__(kThreads) void append_chain_kernel(
     finish_append(g, n, head);
 }
 
+// float(b) / 255 for b in 0..255, correctly rounded: one multiply by the float nearest to
+// 1/255 and one Newton correction through an exact FMA residual.  The result equals IEEE
+// division for all 256 inputs (checked value by value in the tests).
+__device__ __forceinline__ float unit_from_u8(unsigned int b) {
+    constexpr float kInv255 = 0x1.010102p-8f;
+    const float x = (float)b;
+    const float q = x * kInv255;
+    const float r = fmaf(-q, 255.0f, x);
+    return fmaf(r, kInv255, q);
+}
+
 // ---------------------------------------------------------------------------------------
 // Sample + gather + unpack, PAIR layout.  A block draws the slot numbers of R batch rows,
-// pulls those rows into LDS with 16-byte loads (a 256-byte row is one load by 16 lanes),
-// then writes each output tensor as one contiguous, coalesced run.
+// pulls those rows into LDS with 16-byte loads (a 256-byte row is one load by 16 lanes; every
+// thread keeps up to four loads in flight), then writes each output tensor as contiguous,
+// coalesced runs.  lane_shift = log2 of the lanes that cooperate on one row.
 // ---------------------------------------------------------------------------------------
 template <int ELEM>
 __global__ __launch_bounds__(kThreads) void sample_gather_pair_kernel(
     RingGeom g, unsigned long long seed, unsigned long long step_value,
     const unsigned long long* __restrict__ step_ptr, unsigned int batch, unsigned int R,
-    void* __restrict__ out_s, void* __restrict__ out_s_next, unsigned int out_ld,
-    int* __restrict__ out_a, float* __restrict__ out_r, unsigned char* __restrict__ out_term,
-    unsigned int* __restrict__ out_idx) {
+    unsigned int lane_shift, void* __restrict__ out_s, void* __restrict__ out_s_next,
+    unsigned int out_ld, int* __restrict__ out_a, float* __restrict__ out_r,
+    unsigned char* __restrict__ out_term, unsigned int* __restrict__ out_idx) {
     extern __shared__ uint4 smem[];
     unsigned int* idx_s = reinterpret_cast<unsigned int*>(smem);               // R <= 64 entries
     unsigned char* rows_s = reinterpret_cast<unsigned char*>(smem) + 256;
@@ -212,31 +224,52 @@ __global__ __launch_bounds__(kThreads) void sample_gather_pair_kernel(
     }
     __syncthreads();
 
-    const unsigned int V = g.row_bytes >> 4;
-    for (unsigned int v = threadIdx.x; v < nrows * V; v += kThreads) {
-        const unsigned int row = v / V, part = v - row * V;
-        const uint4* src =
-            reinterpret_cast<const uint4*>(g.rows + (unsigned long long)idx_s[row] * g.row_bytes);
-        reinterpret_cast<uint4*>(rows_s)[v] = src[part];
+    {
+        const unsigned int V = g.row_bytes >> 4;             // 16-byte vectors per row
+        const unsigned int lanes = 1u << lane_shift;         // lanes per row (power of two)
+        const unsigned int rows_per_pass = kThreads >> lane_shift;
+        const unsigned int part0 = threadIdx.x & (lanes - 1u);
+        const unsigned int rsub = threadIdx.x >> lane_shift;
+        for (unsigned int part = part0; part < V; part += lanes) {
+            for (unsigned int row = rsub; row < nrows; row += 4 * rows_per_pass) {
+                uint4 val[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const unsigned int rr = row + u * rows_per_pass;
+                    if (rr < nrows)
+                        val[u] = reinterpret_cast<const uint4*>(
+                            g.rows + (unsigned long long)idx_s[rr] * g.row_bytes)[part];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const unsigned int rr = row + u * rows_per_pass;
+                    if (rr < nrows)
+                        reinterpret_cast<uint4*>(rows_s + (size_t)rr * g.row_bytes)[part] = val[u];
+                }
+            }
+        }
     }
     __syncthreads();
 
+    // unpack: 32 lanes walk the columns of one row, 8 rows per pass; consecutive rows are
+    // adjacent in the output, so a wavefront writes one contiguous run
     const unsigned int D = g.state_dim;
-    for (unsigned int e = threadIdx.x; e < nrows * D; e += kThreads) {
-        const unsigned int row = e / D, col = e - row * D;
-        const unsigned char* base = rows_s + row * g.row_bytes;
-        const size_t o = (size_t)(i0 + row) * out_ld + col;
-        if (ELEM == 4) {
-            const unsigned int* w = reinterpret_cast<const unsigned int*>(base);
-            if (out_s) static_cast<unsigned int*>(out_s)[o] = w[col];
-            if (out_s_next) static_cast<unsigned int*>(out_s_next)[o] = w[D + col];
-        } else if (ELEM == 2) {
-            const unsigned short* h = reinterpret_cast<const unsigned short*>(base);
-            if (out_s) static_cast<unsigned short*>(out_s)[o] = h[col];
-            if (out_s_next) static_cast<unsigned short*>(out_s_next)[o] = h[D + col];
-        } else {
-            if (out_s) static_cast<float*>(out_s)[o] = (float)base[col] / 255.0f;
-            if (out_s_next) static_cast<float*>(out_s_next)[o] = (float)base[D + col] / 255.0f;
+    for (unsigned int row = threadIdx.x >> 5; row < nrows; row += kThreads >> 5) {
+        const unsigned char* base = rows_s + (size_t)row * g.row_bytes;
+        const size_t o = (size_t)(i0 + row) * out_ld;
+        for (unsigned int col = threadIdx.x & 31u; col < D; col += 32) {
+            if (ELEM == 4) {
+                const unsigned int* w = reinterpret_cast<const unsigned int*>(base);
+                if (out_s) static_cast<unsigned int*>(out_s)[o + col] = w[col];
+                if (out_s_next) static_cast<unsigned int*>(out_s_next)[o + col] = w[D + col];
+            } else if (ELEM == 2) {
+                const unsigned short* h = reinterpret_cast<const unsigned short*>(base);
+                if (out_s) static_cast<unsigned short*>(out_s)[o + col] = h[col];
+                if (out_s_next) static_cast<unsigned short*>(out_s_next)[o + col] = h[D + col];
+            } else {
+                if (out_s) static_cast<float*>(out_s)[o + col] = unit_from_u8(base[col]);
+                if (out_s_next) static_cast<float*>(out_s_next)[o + col] = unit_from_u8(base[D + col]);
+            }
         }
     }
     if (threadIdx.x < nrows) {
@@ -251,10 +284,13 @@ __global__ __launch_bounds__(kThreads) void sample_gather_pair_kernel(
 
 // ---------------------------------------------------------------------------------------
 // Sample + gather + convert, CHAIN layout (large states).  A block moves one 4 KB piece of
-// one state of one sampled experience: 16 bytes in per lane, and for uint8 states 64 bytes
-// (16 floats) out per lane.  s comes from the sampled slot, s' from the slot after it.
+// one state of one sampled experience; s comes from the sampled slot, s' from the slot after
+// it.  MODE 0: uint8 -> float with every access coalesced: a wavefront reads 256 contiguous
+// bytes as one dword per lane and writes 1 KB as one float4 per lane, four times.
+// MODE 1: raw 16-byte copies (float / bf16 states).  MODE 2: element-wise fallback for
+// shapes whose rows are not 16-byte multiples.
 // ---------------------------------------------------------------------------------------
-template <int ELEM, bool VEC>
+template <int ELEM, int MODE>
 __global__ __launch_bounds__(kThreads) void sample_gather_chain_kernel(
     RingGeom g, unsigned long long seed, unsigned long long step_value,
     const unsigned long long* __restrict__ step_ptr, unsigned int batch, unsigned int chunks,
@@ -284,12 +320,36 @@ __global__ __launch_bounds__(kThreads) void sample_gather_chain_kernel(
     }
     void* out = which ? out_s_next : out_s;
     if (!out) return;
+    const unsigned char* src = g.rows + q * g.row_bytes;
+
+    if (MODE == 0) {
+        // state_bytes is a multiple of 4 and output rows are 16-byte aligned
+        const unsigned int wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
+        const unsigned int base = chunk * 4096u + wave * 1024u + lane * 4u;
+        float* dst = static_cast<float*>(out) + (size_t)i * out_ld;
+        unsigned int w[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const unsigned int b0 = base + 256u * j;
+            w[j] = b0 < g.state_bytes ? *reinterpret_cast<const unsigned int*>(src + b0) : 0u;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const unsigned int b0 = base + 256u * j;
+            if (b0 < g.state_bytes) {
+                const float4 f = make_float4(unit_from_u8(w[j] & 0xFFu), unit_from_u8((w[j] >> 8) & 0xFFu),
+                                             unit_from_u8((w[j] >> 16) & 0xFFu), unit_from_u8(w[j] >> 24));
+                *reinterpret_cast<float4*>(dst + b0) = f;
+            }
+        }
+        return;
+    }
 
     const unsigned int v = chunk * kThreads + threadIdx.x;
     const unsigned int byte0 = v * 16u;
     if (byte0 >= g.state_bytes) return;
     // the slot is padded to a multiple of 16 bytes, so this load stays inside it
-    const uint4 val = reinterpret_cast<const uint4*>(g.rows + q * g.row_bytes)[v];
+    const uint4 val = reinterpret_cast<const uint4*>(src)[v];
     const unsigned int words[4] = {val.x, val.y, val.z, val.w};
     const unsigned int valid_bytes = min(16u, g.state_bytes - byte0);
     constexpr unsigned int EPV = 16 / ELEM;  // elements per 16-byte vector
@@ -297,24 +357,14 @@ __global__ __launch_bounds__(kThreads) void sample_gather_chain_kernel(
     const size_t o = (size_t)i * out_ld + e0;
 
     if (ELEM == 1) {
-        float f[16];
+        float* dst = static_cast<float*>(out) + o;
 #pragma unroll
         for (int j = 0; j < 16; ++j)
-            f[j] = (float)((words[j >> 2] >> (8 * (j & 3))) & 0xFFu) / 255.0f;
-        float* dst = static_cast<float*>(out) + o;
-        if (VEC && valid_bytes == 16) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                reinterpret_cast<float4*>(dst)[j] =
-                    make_float4(f[4 * j], f[4 * j + 1], f[4 * j + 2], f[4 * j + 3]);
-        } else {
-#pragma unroll
-            for (int j = 0; j < 16; ++j)
-                if ((unsigned int)j < valid_bytes) dst[j] = f[j];
-        }
+            if ((unsigned int)j < valid_bytes)
+                dst[j] = unit_from_u8((words[j >> 2] >> (8 * (j & 3))) & 0xFFu);
     } else if (ELEM == 2) {
         unsigned short* dst = static_cast<unsigned short*>(out) + o;
-        if (VEC && valid_bytes == 16) {
+        if (MODE == 1 && valid_bytes == 16) {
             *reinterpret_cast<uint4*>(dst) = val;
         } else {
 #pragma unroll
@@ -324,7 +374,7 @@ __global__ __launch_bounds__(kThreads) void sample_gather_chain_kernel(
         }
     } else {
         unsigned int* dst = static_cast<unsigned int*>(out) + o;
-        if (VEC && valid_bytes == 16) {
+        if (MODE == 1 && valid_bytes == 16) {
             *reinterpret_cast<uint4*>(dst) = val;
         } else {
 #pragma unroll
@@ -377,14 +427,19 @@ hipError_t launch_sample_gather(const RingGeom& g, unsigned long long seed,
                                 float* out_r, unsigned char* out_term, unsigned int* out_idx,
                                 hipStream_t stream) {
     if (g.layout == RP_PAIR) {
-        unsigned int R = 16;
+        // rows per block: 16 keeps eight blocks resident per CU and measured fastest at batch
+        // 65,536 (4..64 tried); small batches take 4 so that more CUs take part
+        unsigned int R = batch >= 2048 ? 16 : 4;
         while (R > 1 && (size_t)R * g.row_bytes > kMaxPairRowBytes) R >>= 1;
+        const unsigned int V = g.row_bytes >> 4;
+        unsigned int lane_shift = 0;
+        while ((1u << lane_shift) < V && lane_shift < 8) ++lane_shift;
         const unsigned int blocks = (batch + R - 1) / R;
         const size_t lds = 256 + (size_t)R * g.row_bytes;
 #define RP_LAUNCH_PAIR(E)                                                                         \
     hipLaunchKernelGGL(sample_gather_pair_kernel<E>, dim3(blocks), dim3(kThreads), lds, stream, g, \
-                       seed, step_value, step_ptr, batch, R, out_s, out_s_next, out_ld, out_a,     \
-                       out_r, out_term, out_idx)
+                       seed, step_value, step_ptr, batch, R, lane_shift, out_s, out_s_next,        \
+                       out_ld, out_a, out_r, out_term, out_idx)
         if (g.elem_bytes == 4)
             RP_LAUNCH_PAIR(4);
         else if (g.elem_bytes == 2)
@@ -401,16 +456,16 @@ hipError_t launch_sample_gather(const RingGeom& g, unsigned long long seed,
         const unsigned int out_elem = g.elem_bytes == 1 ? 4 : g.elem_bytes;
         const bool vec = ((size_t)out_ld * out_elem) % 16 == 0 && aligned16(out_s) &&
                          aligned16(out_s_next);
-#define RP_LAUNCH_CHAIN(E, VEC)                                                                  \
-    hipLaunchKernelGGL((sample_gather_chain_kernel<E, VEC>), dim3(blocks), dim3(kThreads), 0,     \
+#define RP_LAUNCH_CHAIN(E, MODE)                                                                 \
+    hipLaunchKernelGGL((sample_gather_chain_kernel<E, MODE>), dim3(blocks), dim3(kThreads), 0,    \
                        stream, g, seed, step_value, step_ptr, batch, chunks, out_s, out_s_next,   \
                        out_ld, out_a, out_r, out_term, out_idx)
         if (g.elem_bytes == 4) {
-            if (vec) RP_LAUNCH_CHAIN(4, true); else RP_LAUNCH_CHAIN(4, false);
+            if (vec) RP_LAUNCH_CHAIN(4, 1); else RP_LAUNCH_CHAIN(4, 2);
         } else if (g.elem_bytes == 2) {
-            if (vec) RP_LAUNCH_CHAIN(2, true); else RP_LAUNCH_CHAIN(2, false);
+            if (vec) RP_LAUNCH_CHAIN(2, 1); else RP_LAUNCH_CHAIN(2, 2);
         } else {
-            if (vec) RP_LAUNCH_CHAIN(1, true); else RP_LAUNCH_CHAIN(1, false);
+            if (vec && (g.state_bytes & 3u) == 0) RP_LAUNCH_CHAIN(1, 0); else RP_LAUNCH_CHAIN(1, 2);
         }
 #undef RP_LAUNCH_CHAIN
     }

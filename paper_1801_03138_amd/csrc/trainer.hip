@@ -9,44 +9,12 @@
 
 #include "common.hpp"
 #include "replay_kernels.hpp"
+#include "trainer.hpp"
 
 namespace rp {
 namespace {
 
-constexpr unsigned int kThreads = 256;
-
-// ----------------------------------------------------------------------------- element types
-struct bf16_t {
-    unsigned short bits;
-};
-
-__device__ __forceinline__ float to_float(float x) { return x; }
-__device__ __forceinline__ float to_float(bf16_t x) {
-    return __uint_as_float((unsigned int)x.bits << 16);
-}
-// round to nearest even; NaN stays NaN
-__device__ __forceinline__ unsigned short bf16_bits_rne(float f) {
-    unsigned int u = __float_as_uint(f);
-    if ((u & 0x7F800000u) == 0x7F800000u && (u & 0x007FFFFFu)) return (unsigned short)((u >> 16) | 0x40u);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (unsigned short)(u >> 16);
-}
-template <typename T>
-__device__ __forceinline__ T from_float(float x);
-template <>
-__device__ __forceinline__ float from_float<float>(float x) { return x; }
-template <>
-__device__ __forceinline__ bf16_t from_float<bf16_t>(float x) { return bf16_t{bf16_bits_rne(x)}; }
-
-// Device-resident scalars of the trainer.
-struct TrainCounters {
-    unsigned long long step;    // sampling step of the next executed train step
-    unsigned long long adam_t;  // Adam steps taken
-    float c1, c2;               // Adam bias corrections 1 - beta^t of the current step
-    float loss;                 // mean loss of the last step
-    unsigned int pad_[9];
-};
-static_assert(sizeof(TrainCounters) == 64, "one line");
+constexpr unsigned int kThreads = kTrainThreads;
 
 // ----------------------------------------------------------------------------- dense products
 enum { EPI_NONE = 0, EPI_BIAS_RELU = 1, EPI_BIAS = 2, EPI_MASK = 3 };
@@ -140,17 +108,6 @@ __global__ __launch_bounds__(kThreads) void colsum_kernel(int M, int N, const T*
 }
 
 // ----------------------------------------------------------------------------- TD target and loss
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
-    return v;
-}
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
-}
-
 // One wavefront per batch row i:  y_i = r_i + gamma (1 - term_i) max_a Q[B+i][a],
 // delta_i = y_i - Q[i][a_i], per-sample loss, and the one non-zero of dL/dQ in row i.
 // Thread 0 of block 0 also advances Adam's step count and its bias corrections.
@@ -263,38 +220,11 @@ __global__ __launch_bounds__(kThreads) void to_bf16_kernel(unsigned int n,
 using rp::bf16_t;
 using rp::TrainCounters;
 
-struct trainer {
-    train_config cfg;
-    replay* rp_;
-    unsigned int Dp, Ap, H, B;
-    size_t n_params, n_padded;       // external / padded parameter counts
-    size_t oW1, ob1, oW2, ob2, oW3, ob3;
-    size_t elem;                     // bytes of an activation element
-    unsigned char* ws;
-    TrainCounters* ctr;
-    float *w, *g, *m, *v;
-    bf16_t* wb;
-    void* X;                         // [2B x Dp]
-    int* act;
-    float* rew;
-    unsigned char* term;
-    unsigned int* idx;
-    void *H1, *H2;                   // [2B x H]
-    float* Q;                        // [2B x Ap]
-    float *y, *delta, *lossi, *dQ;   // [B], [B], [B], [B x Ap]
-    void *dZ2, *dZ1;                 // [B x H]
-    hipGraph_t graph;
-    hipGraphExec_t graph_exec;
-    hipStream_t capture_stream;
-    unsigned int kernels_per_step;
-    uint64_t host_step;              // mirror of ctr->step
-};
-
 namespace rp {
 namespace {
 
 struct WsLayout {
-    size_t ctr, w, g, m, v, wb, X, act, rew, term, idx, H1, H2, Q, y, delta, lossi, dQ, dZ2, dZ1,
+    size_t ctr, w, g, m, v, w2t, wb, X, act, rew, term, idx, H1, H2, Q, y, delta, lossi, dQ, dZ2, dZ1,
         total;
     unsigned int Dp, Ap;
     size_t n_params, n_padded, elem;
@@ -330,6 +260,7 @@ bool ws_layout(const train_config* c, WsLayout* L) {
     L->g = take(L->n_padded * 4);
     L->m = take(L->n_padded * 4);
     L->v = take(L->n_padded * 4);
+    L->w2t = take(c->param_dtype == RP_F32 ? H * H * 4 : 0);
     L->wb = take(c->param_dtype == RP_BF16 ? L->n_padded * 2 : 0);
     L->X = take(2 * B * L->Dp * L->elem);
     L->act = take(B * 4);
@@ -448,6 +379,7 @@ hipError_t enqueue_step(trainer* t, hipStream_t st, unsigned int* count) {
 }
 
 hipError_t enqueue_append_and_step(trainer* t, hipStream_t st, unsigned int* count) {
+    if (t->fused) return enqueue_fused_step(t, st, count);
     unsigned int n = 0, k = 0;
     replay* r = t->rp_;
     if (t->cfg.appends_per_step) {
@@ -517,6 +449,8 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
     t->g = reinterpret_cast<float*>(ws + L.g);
     t->m = reinterpret_cast<float*>(ws + L.m);
     t->v = reinterpret_cast<float*>(ws + L.v);
+    t->w2t = cfg->param_dtype == RP_F32 ? reinterpret_cast<float*>(ws + L.w2t) : nullptr;
+    t->fused = !(cfg->flags & RP_TRAIN_LAYERED) && rp::fused_step_supported(*cfg, rp_);
     t->wb = cfg->param_dtype == RP_BF16 ? reinterpret_cast<bf16_t*>(ws + L.wb) : nullptr;
     t->X = ws + L.X;
     t->act = reinterpret_cast<int*>(ws + L.act);
@@ -550,7 +484,7 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
     rp_status s = train_set_state(t, host_init_params, nullptr, nullptr, 0, 0);
     if (s != RP_OK) return fail(s);
 
-    if (cfg->use_graph) {
+    if (cfg->flags & RP_TRAIN_GRAPH) {
         e = hipStreamCreateWithFlags(&t->capture_stream, hipStreamNonBlocking);
         if (e == hipSuccess) e = hipStreamBeginCapture(t->capture_stream, hipStreamCaptureModeThreadLocal);
         if (e == hipSuccess) {
@@ -565,7 +499,7 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
         }
     } else {
         // count the launches without running them: the count is static
-        t->kernels_per_step = (cfg->appends_per_step ? 1u : 0u) + 14u;
+        t->kernels_per_step = t->fused ? 2u : (cfg->appends_per_step ? 1u : 0u) + 14u;
     }
     *out = t;
     return RP_OK;
@@ -684,6 +618,13 @@ rp_status train_set_state(trainer_t* t, const float* params, const float* m, con
     RP_CHECK_HIP(hipDeviceSynchronize());
     rp::pad_params(t, params, pad);
     RP_CHECK_HIP(hipMemcpy(t->w, pad.data(), t->n_padded * 4, hipMemcpyHostToDevice));
+    if (t->w2t) {
+        const size_t H = t->H;
+        std::vector<float> tr(H * H);
+        for (size_t j = 0; j < H; ++j)
+            for (size_t k = 0; k < H; ++k) tr[k * H + j] = pad[t->oW2 + j * H + k];
+        RP_CHECK_HIP(hipMemcpy(t->w2t, tr.data(), H * H * 4, hipMemcpyHostToDevice));
+    }
     if (m) {
         rp::pad_params(t, m, pad);
         RP_CHECK_HIP(hipMemcpy(t->m, pad.data(), t->n_padded * 4, hipMemcpyHostToDevice));

@@ -1,0 +1,93 @@
+// Shared definitions of the trainer: element types, device-resident counters, the host handle.
+#pragma once
+
+#include "common.hpp"
+
+namespace rp {
+
+constexpr unsigned int kTrainThreads = 256;
+
+// ----------------------------------------------------------------------------- element types
+struct bf16_t {
+    unsigned short bits;
+};
+
+__device__ __forceinline__ float to_float(float x) { return x; }
+__device__ __forceinline__ float to_float(bf16_t x) {
+    return __uint_as_float((unsigned int)x.bits << 16);
+}
+// round to nearest even; NaN stays NaN
+__device__ __forceinline__ unsigned short bf16_bits_rne(float f) {
+    unsigned int u = __float_as_uint(f);
+    if ((u & 0x7F800000u) == 0x7F800000u && (u & 0x007FFFFFu)) return (unsigned short)((u >> 16) | 0x40u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (unsigned short)(u >> 16);
+}
+template <typename T>
+__device__ __forceinline__ T from_float(float x);
+template <>
+__device__ __forceinline__ float from_float<float>(float x) { return x; }
+template <>
+__device__ __forceinline__ bf16_t from_float<bf16_t>(float x) { return bf16_t{bf16_bits_rne(x)}; }
+
+// Device-resident scalars of the trainer.
+struct TrainCounters {
+    unsigned long long step;    // sampling step of the next executed train step
+    unsigned long long adam_t;  // Adam steps taken
+    float c1, c2;               // Adam bias corrections 1 - beta^t of the current step
+    float loss;                 // mean loss of the last step
+    unsigned int pad_[9];
+};
+static_assert(sizeof(TrainCounters) == 64, "one line");
+
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+}  // namespace rp
+
+struct trainer {
+    train_config cfg;
+    replay* rp_;
+    unsigned int Dp, Ap, H, B;
+    size_t n_params, n_padded;       // external / padded parameter counts
+    size_t oW1, ob1, oW2, ob2, oW3, ob3;
+    size_t elem;                     // bytes of an activation element
+    unsigned char* ws;
+    rp::TrainCounters* ctr;
+    float *w, *g, *m, *v;
+    float* w2t;                      // fused path: W2 transposed, [H x H]
+    rp::bf16_t* wb;
+    void* X;                         // [2B x Dp]
+    int* act;
+    float* rew;
+    unsigned char* term;
+    unsigned int* idx;
+    void *H1, *H2;                   // [2B x H]
+    float* Q;                        // [2B x Ap]
+    float *y, *delta, *lossi, *dQ;   // [B], [B], [B], [B x Ap]
+    void *dZ2, *dZ1;                 // [B x H]
+    bool fused;                      // two-kernel step for small fp32 networks
+    hipGraph_t graph;
+    hipGraphExec_t graph_exec;
+    hipStream_t capture_stream;
+    unsigned int kernels_per_step;
+    uint64_t host_step;              // mirror of ctr->step
+};
+
+namespace rp {
+// Whether the two-kernel fused step can run this configuration.
+bool fused_step_supported(const train_config& cfg, const replay* rp_);
+// Dynamic LDS bytes its row kernel needs.
+// Enqueue the fused step (append + sample + gather + forward + TD + backward; weight
+// gradients + optimizer).  *count receives the number of kernels launched.
+hipError_t enqueue_fused_step(trainer* t, hipStream_t st, unsigned int* count);
+}  // namespace rp

@@ -45,7 +45,7 @@ class Pair:
     """A GPU replay + trainer and the oracle ring it is compared with."""
 
     def __init__(self, B, *, capacity, D, H, A, batch, burn_in, seed, dtype="f32", loss="huber",
-                 opt="adam", lr=1e-4, appends=1, use_graph=True, max_append=4096):
+                 opt="adam", lr=1e-4, appends=1, use_graph=True, max_append=4096, layered=False):
         self.B, self.D, self.H, self.A, self.batch, self.seed = B, D, H, A, batch, seed
         self.bf16 = dtype == "bf16"
         sd = B.RP_BF16 if self.bf16 else B.RP_F32
@@ -59,7 +59,7 @@ class Pair:
         self.trainer = B.Trainer(self.gpu_ring, H, A, batch, param_dtype=sd,
                                  loss=B.RP_HUBER if loss == "huber" else B.RP_MSE,
                                  opt=B.RP_ADAM if opt == "adam" else B.RP_SGD,
-                                 appends_per_step=appends, use_graph=use_graph,
+                                 appends_per_step=appends, use_graph=use_graph, layered=layered,
                                  init_params=self.p0, **{k: float(v) for k, v in self.hyper.items()})
         self.cfg = oracle.make_cfg(D, H, A, batch,
                                    loss=oracle.HUBER if loss == "huber" else oracle.MSE,
@@ -124,10 +124,13 @@ class Pair:
         return status
 
 
-def test_tiny_config_all_100_steps(B):
+@pytest.mark.parametrize("layered", [False, True])
+def test_tiny_config_all_100_steps(B, layered):
     """Ring 1024, 27-64-64-8, batch 32, SGD 1e-3, burn-in 256, one append per step."""
     rows = synth.experiences(4096, 27, 8, 0.01, seed=0)
-    pr = Pair(B, capacity=1024, D=27, H=64, A=8, batch=32, burn_in=256, seed=0, opt="sgd", lr=1e-3)
+    pr = Pair(B, capacity=1024, D=27, H=64, A=8, batch=32, burn_in=256, seed=0, opt="sgd", lr=1e-3,
+              layered=layered)
+    assert pr.trainer.kernels_per_step() == (15 if layered else 2)
     executed = 0
     for k in range(4096):
         part = synth.take(rows, k, k + 1)
@@ -143,21 +146,25 @@ def test_tiny_config_all_100_steps(B):
     assert all(np.array_equal(x.view(np.uint8), y.view(np.uint8)) for x, y in zip(g, o))
 
 
+@pytest.mark.parametrize("layered", [False, True])
 @pytest.mark.parametrize("loss,opt", [("huber", "adam"), ("mse", "sgd"), ("mse", "adam")])
-def test_small_net_every_loss_and_optimizer(B, loss, opt):
+def test_small_net_every_loss_and_optimizer(B, loss, opt, layered):
+    """Batch 50 is not a multiple of the row kernel's four experiences per workgroup; a ring of
+    128 with 3 appends per step makes sampled slots coincide with slots being overwritten."""
     rows = synth.experiences(300, 11, 5, 0.2, seed=4)
     pr = Pair(B, capacity=128, D=11, H=64, A=5, batch=50, burn_in=20, seed=9, loss=loss, opt=opt,
-              lr=1e-3, appends=3)
+              lr=1e-3, appends=3, layered=layered)
     for k in range(0, 300, 3):
         pr.step(synth.take(rows, k, k + 3), compare=True)
 
 
-def test_graph_and_direct_launch_agree_bitwise(B):
+@pytest.mark.parametrize("layered", [False, True])
+def test_graph_and_direct_launch_agree_bitwise(B, layered):
     rows = synth.experiences(200, 27, 30, 0.05, seed=2)
     outs = []
     for use_graph in (True, False):
         pr = Pair(B, capacity=150, D=27, H=64, A=30, batch=64, burn_in=10, seed=3,
-                  use_graph=use_graph)
+                  use_graph=use_graph, layered=layered)
         for k in range(200):
             pr.step(synth.take(rows, k, k + 1), compare=False)
         outs.append((pr.trainer.params(), pr.trainer.last()["loss"], pr.trainer.opt_state()))
@@ -177,7 +184,18 @@ def test_paper_shaped_config_sampled_steps(B):
         assert st == 0
     assert pr.trainer.opt_state()[2:] == (10_000, 10_000)
     assert pr.gpu_ring.state() == pr.ref_ring.state() == (59_999, 59_999, 59_999)
-    assert pr.trainer.kernels_per_step() >= 1
+    assert pr.trainer.kernels_per_step() == 2
+
+
+def test_wider_net_both_paths_agree_with_oracle(B):
+    """27-320-320-30 (more than one 256-column pass per layer), batch 130, ring that wraps."""
+    rows = synth.experiences(900, 27, 30, 0.05, seed=12)
+    for layered in (False, True):
+        pr = Pair(B, capacity=500, D=27, H=320, A=30, batch=130, burn_in=300, seed=4, appends=2,
+                  layered=layered)
+        for k in range(0, 900, 2):
+            pr.step(synth.take(rows, k, k + 2), compare=(k % 50 == 0) or k >= 880)
+        assert pr.gpu_ring.state() == pr.ref_ring.state()
 
 
 def test_terminal_rows_and_out_of_range_actions_are_safe(B):
