@@ -64,6 +64,24 @@ struct RingGeom {
     RingState* state;
 };
 
+// New experiences handed to a kernel, structure of arrays (device-readable memory).
+struct Payload {
+    const unsigned char* s;
+    const unsigned char* s_next;
+    const int* a;
+    const float* r;
+    const unsigned char* term;
+};
+
+// Argument block of the PAIR append kernel (one struct, so that a recorded graph node can be
+// pointed at another payload by replacing a single kernel argument).
+struct AppendArgs {
+    RingGeom g;
+    unsigned long long n;
+    Payload src;
+    unsigned int rows_per_block;
+};
+
 }  // namespace rp
 
 struct replay {

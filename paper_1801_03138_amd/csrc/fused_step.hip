@@ -18,150 +18,92 @@
 namespace rp {
 namespace {
 
-constexpr unsigned int kThreads = kTrainThreads;
+constexpr unsigned int kThreads = kTrainThreads;   // weight kernel
+constexpr unsigned int kRowThreads = 1024;         // row kernel: 16 wavefronts
 constexpr unsigned int kRows = 4;          // experiences per workgroup of the row kernel
-constexpr unsigned int kChunk = 256;       // output columns one wavefront covers per pass
+constexpr unsigned int kChunk = 256;       // output columns the workgroup covers per pass
 constexpr unsigned int kPadK = 4;          // LDS row padding (floats) against bank conflicts
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-struct RowArgs {
-    RingGeom g;
-    unsigned long long seed;
-    unsigned int n_append;
-    const unsigned char* st_s;
-    const unsigned char* st_s_next;
-    const int* st_a;
-    const float* st_r;
-    const unsigned char* st_term;
-    TrainCounters* ctr;
-    const float* w;       // padded parameters
-    const float* w2t;     // W2 transposed
-    unsigned int B, D, Dp, H, A, Ap;
-    unsigned int oW1, ob1, oW2, ob2, oW3, ob3;
-    float gamma, beta1, beta2;
-    unsigned int loss_kind;
-    float *X, *H1, *H2, *Q, *y, *delta, *lossi, *dQ, *dZ2, *dZ1;
-    int* act;
-    float* rew;
-    unsigned char* term;
-    unsigned int* idx;
-};
 
 // One 32-bit word of the packed row of a new experience, taken from the staging arrays.
 __device__ __forceinline__ unsigned int staged_word(const RowArgs& p, unsigned long long k,
                                                     unsigned int w) {
     const unsigned int D = p.D;
-    if (w < D) return reinterpret_cast<const unsigned int*>(p.st_s)[k * D + w];
-    if (w < 2 * D) return reinterpret_cast<const unsigned int*>(p.st_s_next)[k * D + w - D];
-    if (w == 2 * D) return (unsigned int)p.st_a[k];
-    if (w == 2 * D + 1) return __float_as_uint(p.st_r[k]);
-    if (w == 2 * D + 2) return p.st_term[k] ? 1u : 0u;
+    if (w < D) return reinterpret_cast<const unsigned int*>(p.src.s)[k * D + w];
+    if (w < 2 * D) return reinterpret_cast<const unsigned int*>(p.src.s_next)[k * D + w - D];
+    if (w == 2 * D) return (unsigned int)p.src.a[k];
+    if (w == 2 * D + 1) return __float_as_uint(p.src.r[k]);
+    if (w == 2 * D + 2) return p.src.term[k] ? 1u : 0u;
     return 0u;
 }
 
-// part[wave][row][col] = sum over this wavefront's quarter of K of act[row][k] * W[k][col]
-// for MG*4 rows and the 256 columns of `chunk`.  act: LDS, row pitch ldk floats.  W: global,
-// row-major [K x N], N a multiple of 4, K a multiple of 16.  Each lane loads a float4 of
-// four adjacent columns per k (1 KB per wavefront, fully coalesced) and feeds one column
-// group per MFMA; the activations come in as the broadcast A operand.
-template <int MG>
-__device__ __forceinline__ void mm_rows(const float* act, unsigned int ldk, unsigned int K,
-                                        const float* __restrict__ W, unsigned int N,
-                                        unsigned int chunk, float* part) {
-    const unsigned int lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-    const unsigned int col = chunk * kChunk + 4u * lane;
+// ----------------------------------------------------------------------------------------
+// Products of a few activation rows (LDS) with a weight matrix (global, row-major [K x N]).
+// On this machine a global load that misses the local L2 takes about 2 us, longer than all
+// the arithmetic of a layer, so the row kernel never computes right after loading: a lane
+// fetches its whole share of a weight matrix into registers (load_*) one or two phases before
+// the matching mma_* consumes it.  A lane owns one output column and the MFMA takes the
+// activations of four rows as its broadcast A operand.
+//
+// "wide" split (N up to 256): wavefront w covers columns 64*(w&3).. and the K quarter w>>2.
+// "narrow" split (N up to 64): every wavefront covers columns 0..63 and K sixteenth w.
+// ----------------------------------------------------------------------------------------
+template <int NR>
+__device__ __forceinline__ void load_cols(float (&wr)[NR], const float* __restrict__ W,
+                                          unsigned int N, unsigned int col, unsigned int kbeg,
+                                          unsigned int kcount) {
     const bool active = col < N;
-    const unsigned int Kq = K >> 2;
-    const unsigned int kbeg = wave * Kq, kend = kbeg + Kq;
-    const float* wp = W + col;
-    const float* ap = act + (lane & 3u) * ldk;
-
-    f32x4 acc[MG][4];
+    const float* wp = W + (size_t)kbeg * N + col;
 #pragma unroll
-    for (int mg = 0; mg < MG; ++mg)
-#pragma unroll
-        for (int gq = 0; gq < 4; ++gq) acc[mg][gq] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    constexpr int U = 16;  // k rows per pipeline stage
-    f32x4 cur[U], nxt[U];
-    auto load_stage = [&](f32x4* dst, unsigned int k0) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const unsigned int k = k0 + u;
-            dst[u] = (active && k < kend)
-                         ? *reinterpret_cast<const f32x4*>(wp + (size_t)k * N)
-                         : f32x4{0.f, 0.f, 0.f, 0.f};
-        }
-    };
-    load_stage(cur, kbeg);
-    for (unsigned int k0 = kbeg; k0 < kend; k0 += U) {
-        if (k0 + U < kend) load_stage(nxt, k0 + U);
-#pragma unroll
-        for (int u4 = 0; u4 < U; u4 += 4) {
-            if (k0 + u4 < kend) {  // Kq is a multiple of 4, so a group of four is all in or all out
-#pragma unroll
-                for (int mg = 0; mg < MG; ++mg) {
-                    const f32x4 a = *reinterpret_cast<const f32x4*>(ap + (size_t)mg * 4 * ldk + k0 + u4);
-#pragma unroll
-                    for (int u = 0; u < 4; ++u)
-#pragma unroll
-                        for (int gq = 0; gq < 4; ++gq)
-                            acc[mg][gq] = __builtin_amdgcn_mfma_f32_4x4x1f32(
-                                a[u], cur[u4 + u][gq], acc[mg][gq], 0, 0, 0);
-                }
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) cur[u] = nxt[u];
-    }
-    // lane holds, for column group gq, rows v = 0..3 of column 4*lane + gq
-#pragma unroll
-    for (int mg = 0; mg < MG; ++mg)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            float* dst = part + ((size_t)(wave * (MG * 4) + mg * 4 + v)) * kChunk + 4u * lane;
-            *reinterpret_cast<f32x4*>(dst) =
-                f32x4{acc[mg][0][v], acc[mg][1][v], acc[mg][2][v], acc[mg][3][v]};
-        }
+    for (int u = 0; u < NR; ++u) wr[u] = (active && (unsigned int)u < kcount) ? wp[(size_t)u * N] : 0.f;
 }
 
-// sum of the four wavefronts' partial products for (row, col of the current chunk)
+// acc[mg][v] += sum_{u < kcount} act[mg*4 + v][kbeg + u] * wr[u]   (kcount a multiple of 4)
+template <int MG, int NR>
+__device__ __forceinline__ void mma_cols(f32x4 (&acc)[MG], const float* act, unsigned int ldk,
+                                         unsigned int kbeg, unsigned int kcount,
+                                         const float (&wr)[NR]) {
+    const float* ap = act + (threadIdx.x & 3u) * ldk + kbeg;
+#pragma unroll
+    for (int mg = 0; mg < MG; ++mg) acc[mg] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u4 = 0; u4 < NR; u4 += 4) {
+        if ((unsigned int)u4 < kcount) {
+#pragma unroll
+            for (int mg = 0; mg < MG; ++mg) {
+                const f32x4 a = *reinterpret_cast<const f32x4*>(ap + (size_t)mg * 4 * ldk + u4);
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    acc[mg] = __builtin_amdgcn_mfma_f32_4x4x1f32(a[u], wr[u4 + u], acc[mg], 0, 0, 0);
+            }
+        }
+    }
+}
+
+// part[slice][row][cc] = acc; the lane holds rows v = 0..3 of its column cc
 template <int MG>
-__device__ __forceinline__ float part_sum(const float* part, unsigned int row, unsigned int c) {
-    float v = part[(size_t)(0 * MG * 4 + row) * kChunk + c];
-    v += part[(size_t)(1 * MG * 4 + row) * kChunk + c];
-    v += part[(size_t)(2 * MG * 4 + row) * kChunk + c];
-    v += part[(size_t)(3 * MG * 4 + row) * kChunk + c];
+__device__ __forceinline__ void store_part(float* part, unsigned int slice, unsigned int pitch,
+                                           unsigned int cc, const f32x4 (&acc)[MG]) {
+#pragma unroll
+    for (int mg = 0; mg < MG; ++mg)
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            part[((size_t)(slice * (MG * 4) + mg * 4 + v)) * pitch + cc] = acc[mg][v];
+}
+
+__device__ __forceinline__ float sum_part(const float* part, unsigned int slices,
+                                          unsigned int rows, unsigned int pitch, unsigned int row,
+                                          unsigned int c) {
+    float v = 0.f;
+    for (unsigned int s = 0; s < slices; ++s) v += part[((size_t)(s * rows + row)) * pitch + c];
     return v;
 }
 
-// out[row][col] = relu?(in[row][:] . W[:, col] + bias[col]) for the 8 rows (4 of s, 4 of s').
-// Rows 0..3 are also written to the global activation array `glob` (row pitch N) when given.
-__device__ __forceinline__ void dense_rows8(const float* in, unsigned int ldk, unsigned int K,
-                                            const float* __restrict__ W,
-                                            const float* __restrict__ bias, unsigned int N,
-                                            bool relu, float* out, unsigned int ldo, float* part,
-                                            float* __restrict__ glob, unsigned int i0,
-                                            unsigned int nrows) {
-    for (unsigned int chunk = 0; chunk * kChunk < N; ++chunk) {
-        mm_rows<2>(in, ldk, K, W, N, chunk, part);
-        __syncthreads();
-        const unsigned int ncol = min(kChunk, N - chunk * kChunk);
-        for (unsigned int e = threadIdx.x; e < 8 * ncol; e += kThreads) {
-            const unsigned int row = e / ncol, c = e - row * ncol, col = chunk * kChunk + c;
-            float v = part_sum<2>(part, row, c) + bias[col];
-            if (relu) v = v > 0.f ? v : 0.f;
-            out[(size_t)row * ldo + col] = v;
-            if (glob && row < nrows) glob[(size_t)(i0 + row) * N + col] = v;
-        }
-        __syncthreads();
-    }
-}
-
-__global__ __launch_bounds__(kThreads) void fused_rows_kernel(RowArgs p) {
+__global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     extern __shared__ float lds[];
-    const unsigned int tid = threadIdx.x;
+    const unsigned int tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const unsigned int D = p.D, Dp = p.Dp, H = p.H, A = p.A, Ap = p.Ap;
     const unsigned int ldx = Dp + kPadK, ldh = H + kPadK, ldq = Ap + kPadK;
     float* Xs = lds;                      // [8][ldx]  rows 0..3 = s, 4..7 = s'
@@ -169,9 +111,29 @@ __global__ __launch_bounds__(kThreads) void fused_rows_kernel(RowArgs p) {
     float* H2s = H1s + 8 * ldh;           // [8][ldh]
     float* Qs = H2s + 8 * ldh;            // [8][ldq]
     float* dZs = Qs + 8 * ldq;            // [4][ldh]
-    float* part = dZs + 4 * ldh;          // [4 waves][8][256]
-    unsigned int* meta = reinterpret_cast<unsigned int*>(part + 4 * 8 * kChunk);  // [4][4]
-    float* gs = reinterpret_cast<float*>(meta + 16);                              // [4]
+    float* part = dZs + 4 * ldh;          // [4][8][256] or [16][8][64]
+    float* b1s = part + 4 * 8 * kChunk;   // [H]
+    float* b2s = b1s + H;                 // [H]
+    float* b3s = b2s + H;                 // [Ap]
+    unsigned int* meta = reinterpret_cast<unsigned int*>(b3s + Ap);  // [4][4]
+    float* gs = reinterpret_cast<float*>(meta + 16);                 // [4]
+
+    const float* W1 = p.w + p.oW1;
+    const float* W2 = p.w + p.oW2;
+    const float* W3 = p.w + p.oW3;
+    // wide split
+    const unsigned int cc = 64u * (wave & 3u) + lane, ks = wave >> 2;
+    const unsigned int q1 = Dp >> 2, q2 = H >> 2;   // K quarter of layer 1 / layers 2 and backward
+    // narrow split
+    const unsigned int s3 = H >> 4;                 // K sixteenth of layer 3
+
+    // ---- phase 0: everything that does not depend on the sample is requested first
+    float w1r[16], w2r[64];
+    load_cols<16>(w1r, W1, H, cc, ks * q1, q1);
+    load_cols<64>(w2r, W2, H, cc, ks * q2, q2);
+    const float b1v = tid < H ? p.w[p.ob1 + tid] : 0.f;
+    const float b2v = tid < H ? p.w[p.ob2 + tid] : 0.f;
+    const float b3v = tid < Ap ? p.w[p.ob3 + tid] : 0.f;
 
     // ring and trainer state as they stand before this step's append
     const unsigned long long cap = p.g.capacity;
@@ -183,21 +145,14 @@ __global__ __launch_bounds__(kThreads) void fused_rows_kernel(RowArgs p) {
     const unsigned int i0 = blockIdx.x * kRows;
     const unsigned int nrows = min(kRows, p.B - i0);
 
-    if (blockIdx.x == 0 && tid == 0) {
-        const unsigned long long t = p.ctr->adam_t + 1;
-        p.ctr->adam_t = t;
-        p.ctr->c1 = (float)(1.0 - pow((double)p.beta1, (double)t));
-        p.ctr->c2 = (float)(1.0 - pow((double)p.beta2, (double)t));
-    }
-
-    for (unsigned int e = tid; e < 8 * ldx; e += kThreads) Xs[e] = 0.f;
+    for (unsigned int e = tid; e < 8 * ldx; e += kRowThreads) Xs[e] = 0.f;
     if (tid < 16) meta[tid] = 0;
     __syncthreads();
 
-    // sample and gather: one 32-bit word per thread.  A drawn slot that this step's append is
-    // about to overwrite is read from the staging arrays, which hold its new content.
+    // ---- sample and gather: one 32-bit word per thread.  A drawn slot that this step's append
+    // is about to overwrite is read from the payload arrays, which hold its new content.
     const unsigned int words = 2 * D + 3;
-    for (unsigned int e = tid; e < nrows * words; e += kThreads) {
+    for (unsigned int e = tid; e < nrows * words; e += kRowThreads) {
         const unsigned int r = e / words, w = e - r * words;
         const unsigned int i = i0 + r;
         const unsigned int slot = uniform_draw(p.seed, step, i, size);
@@ -223,28 +178,73 @@ __global__ __launch_bounds__(kThreads) void fused_rows_kernel(RowArgs p) {
             }
         }
     }
+    if (tid < H) {
+        b1s[tid] = b1v;
+        b2s[tid] = b2v;
+    }
+    if (tid < Ap) b3s[tid] = b3v;
     __syncthreads();
 
-    // forward on the eight rows
-    const float* W1 = p.w + p.oW1;
-    const float* W2 = p.w + p.oW2;
-    const float* W3 = p.w + p.oW3;
-    dense_rows8(Xs, ldx, Dp, W1, p.w + p.ob1, H, true, H1s, ldh, part, p.H1, i0, nrows);
-    dense_rows8(H1s, ldh, H, W2, p.w + p.ob2, H, true, H2s, ldh, part, p.H2, i0, nrows);
-    dense_rows8(H2s, ldh, H, W3, p.w + p.ob3, Ap, false, Qs, ldq, part, nullptr, i0, nrows);
-
-    // Q values out (rows i and B+i of the [2B x Ap] array), then TD target, loss term, dL/dQ
-    for (unsigned int e = tid; e < 8 * Ap; e += kThreads) {
-        const unsigned int row = e / Ap, c = e - row * Ap, r = row & 3u;
-        if (r < nrows)
-            p.Q[((size_t)(row < 4 ? 0 : p.B) + i0 + r) * Ap + c] = Qs[row * ldq + c];
+    // the column of W3 that the backward pass of each row needs: W3[k][a_r], one per thread
+    float w3sel = 0.f;
+    {
+        const unsigned int r = tid / H, k = tid - r * H;
+        if (r < nrows) {
+            unsigned int ai = meta[r * 4 + 0];
+            if (ai >= A) ai = A - 1;  // an out-of-range action must not turn into a wild address
+            w3sel = W3[(size_t)k * Ap + ai];
+        }
     }
+
+    // ---- layer 1
+    f32x4 acc2[2];
+    mma_cols<2, 16>(acc2, Xs, ldx, ks * q1, q1, w1r);
+    store_part<2>(part, ks, kChunk, cc, acc2);
+    __syncthreads();
+    for (unsigned int e = tid; e < 8 * H; e += kRowThreads) {
+        const unsigned int row = e / H, c = e - row * H;
+        float v = sum_part(part, 4, 8, kChunk, row, c) + b1s[c];
+        v = v > 0.f ? v : 0.f;
+        H1s[row * ldh + c] = v;
+        if (row < nrows) p.H1[(size_t)(i0 + row) * H + c] = v;
+    }
+    __syncthreads();
+
+    // ---- layer 2; its registers are then refilled with W2^T (backward) and W3 is requested
+    mma_cols<2, 64>(acc2, H1s, ldh, ks * q2, q2, w2r);
+    float w3r[16];
+    load_cols<16>(w3r, W3, Ap, lane, wave * s3, s3);
+    load_cols<64>(w2r, p.w2t, H, cc, ks * q2, q2);
+    store_part<2>(part, ks, kChunk, cc, acc2);
+    __syncthreads();
+    for (unsigned int e = tid; e < 8 * H; e += kRowThreads) {
+        const unsigned int row = e / H, c = e - row * H;
+        float v = sum_part(part, 4, 8, kChunk, row, c) + b2s[c];
+        v = v > 0.f ? v : 0.f;
+        H2s[row * ldh + c] = v;
+        if (row < nrows) p.H2[(size_t)(i0 + row) * H + c] = v;
+    }
+    __syncthreads();
+
+    // ---- layer 3 (narrow split: 16 K slices, columns 0..63)
+    mma_cols<2, 16>(acc2, H2s, ldh, wave * s3, s3, w3r);
+    store_part<2>(part, wave, 64, lane, acc2);
+    __syncthreads();
+    for (unsigned int e = tid; e < 8 * Ap; e += kRowThreads) {
+        const unsigned int row = e / Ap, c = e - row * Ap, r = row & 3u;
+        const float v = sum_part(part, 16, 8, 64, row, c) + b3s[c];
+        Qs[row * ldq + c] = v;
+        if (r < nrows) p.Q[((size_t)(row < 4 ? 0 : p.B) + i0 + r) * Ap + c] = v;
+    }
+    __syncthreads();
+
+    // ---- TD target, loss term, dL/dQ
     if (tid < nrows) {
         const unsigned int r = tid, i = i0 + r;
         float best = -INFINITY;
         for (unsigned int k = 0; k < A; ++k) best = fmaxf(best, Qs[(4 + r) * ldq + k]);
         unsigned int ai = meta[r * 4 + 0];
-        if (ai >= A) ai = A - 1;  // an out-of-range action must not turn into a wild address
+        if (ai >= A) ai = A - 1;
         meta[r * 4 + 3] = ai;
         const float q = Qs[r * ldq + ai];
         const float y = __uint_as_float(meta[r * 4 + 1]) + (meta[r * 4 + 2] ? 0.f : p.gamma * best);
@@ -264,39 +264,38 @@ __global__ __launch_bounds__(kThreads) void fused_rows_kernel(RowArgs p) {
         p.lossi[i] = li;
     }
     __syncthreads();
-    for (unsigned int e = tid; e < nrows * Ap; e += kThreads) {
+    for (unsigned int e = tid; e < nrows * Ap; e += kRowThreads) {
         const unsigned int r = e / Ap, c = e - r * Ap;
         p.dQ[(size_t)(i0 + r) * Ap + c] = (c == meta[r * 4 + 3]) ? gs[r] : 0.f;
     }
-
     // dZ2[r][k] = dQ[r][a_r] * W3[k][a_r] * 1[H2[r][k] > 0]
-    for (unsigned int e = tid; e < 4 * H; e += kThreads) {
-        const unsigned int r = e / H, k = e - r * H;
-        float v = 0.f;
-        if (r < nrows && H2s[r * ldh + k] > 0.f) v = gs[r] * W3[(size_t)k * Ap + meta[r * 4 + 3]];
-        dZs[r * ldh + k] = v;
-        if (r < nrows) p.dZ2[(size_t)(i0 + r) * H + k] = v;
+    {
+        const unsigned int r = tid / H, k = tid - r * H;
+        if (r < 4) {
+            float v = 0.f;
+            if (r < nrows && H2s[r * ldh + k] > 0.f) v = gs[r] * w3sel;
+            dZs[r * ldh + k] = v;
+            if (r < nrows) p.dZ2[(size_t)(i0 + r) * H + k] = v;
+        }
     }
     __syncthreads();
 
-    // dZ1 = (dZ2 W2^T) masked by the first ReLU, through the transposed copy of W2
-    for (unsigned int chunk = 0; chunk * kChunk < H; ++chunk) {
-        mm_rows<1>(dZs, ldh, H, p.w2t, H, chunk, part);
-        __syncthreads();
-        const unsigned int ncol = min(kChunk, H - chunk * kChunk);
-        for (unsigned int e = tid; e < nrows * ncol; e += kThreads) {
-            const unsigned int r = e / ncol, c = e - r * ncol, col = chunk * kChunk + c;
-            float v = part_sum<1>(part, r, c);
-            if (!(H1s[r * ldh + col] > 0.f)) v = 0.f;
-            p.dZ1[(size_t)(i0 + r) * H + col] = v;
-        }
-        __syncthreads();
+    // ---- dZ1 = (dZ2 W2^T) masked by the first ReLU
+    f32x4 acc1[1];
+    mma_cols<1, 64>(acc1, dZs, ldh, ks * q2, q2, w2r);
+    store_part<1>(part, ks, kChunk, cc, acc1);
+    __syncthreads();
+    for (unsigned int e = tid; e < nrows * H; e += kRowThreads) {
+        const unsigned int r = e / H, c = e - r * H;
+        float v = sum_part(part, 4, 4, kChunk, r, c);
+        if (!(H1s[r * ldh + c] > 0.f)) v = 0.f;
+        p.dZ1[(size_t)(i0 + r) * H + c] = v;
     }
 
-    // the last workgroup writes the new experiences into the ring
+    // ---- the last workgroup writes the new experiences into the ring
     if (blockIdx.x == gridDim.x - 1 && n) {
         const unsigned int rw = p.g.row_bytes >> 2;
-        for (unsigned long long e = tid; e < n * rw; e += kThreads) {
+        for (unsigned long long e = tid; e < n * rw; e += kRowThreads) {
             const unsigned long long k = e / rw;
             const unsigned int w = (unsigned int)(e - k * rw);
             unsigned long long slot = head + k;
@@ -304,11 +303,12 @@ __global__ __launch_bounds__(kThreads) void fused_rows_kernel(RowArgs p) {
             reinterpret_cast<unsigned int*>(p.g.rows + slot * p.g.row_bytes)[w] = staged_word(p, k, w);
         }
     }
-    // every workgroup read the ring state before this point; the last one to arrive advances it
-    __threadfence();
-    __syncthreads();
+    // Every workgroup read the ring state and the counters at its start; the last one to arrive
+    // advances them.  Nothing written here is read again inside this launch, so no fence is
+    // needed: the end of the kernel publishes it to the next one.
     if (tid == 0) {
-        const unsigned int done = atomicAdd(&p.g.state->blocks_done, 1u);
+        const unsigned int done = __hip_atomic_fetch_add(&p.g.state->blocks_done, 1u, __ATOMIC_RELAXED,
+                                                         __HIP_MEMORY_SCOPE_AGENT);
         if (done == gridDim.x - 1) {
             unsigned long long h = head + n;
             if (h >= cap) h -= cap;
@@ -316,7 +316,10 @@ __global__ __launch_bounds__(kThreads) void fused_rows_kernel(RowArgs p) {
             p.g.state->size = size;
             p.g.state->total += n;
             p.g.state->blocks_done = 0;
-            __threadfence();
+            const unsigned long long t = p.ctr->adam_t + 1;
+            p.ctr->adam_t = t;
+            p.ctr->c1 = (float)(1.0 - pow((double)p.beta1, (double)t));
+            p.ctr->c2 = (float)(1.0 - pow((double)p.beta2, (double)t));
         }
     }
 }
@@ -346,17 +349,17 @@ struct WArgs {
     const float* lossi;
 };
 
-constexpr unsigned int kTM = 32, kTN = 64, kTK = 64;
+constexpr unsigned int kTM = 32, kTN = 64, kTK = 128;
 
-__device__ __forceinline__ float opt_update(const WArgs& p, unsigned int k, float gk, float c1,
-                                            float c2) {
-    float wk = p.w[k];
+// One optimizer update of parameter k with gradient gk, from values loaded earlier.
+__device__ __forceinline__ float opt_apply(const WArgs& p, unsigned int k, float gk, float wk,
+                                           float mk, float vk, float c1, float c2) {
     p.g[k] = gk;
     if (p.opt == RP_SGD) {
         wk -= p.lr * gk;
     } else {
-        const float mk = p.beta1 * p.m[k] + (1.f - p.beta1) * gk;
-        const float vk = p.beta2 * p.v[k] + (1.f - p.beta2) * gk * gk;
+        mk = p.beta1 * mk + (1.f - p.beta1) * gk;
+        vk = p.beta2 * vk + (1.f - p.beta2) * gk * gk;
         p.m[k] = mk;
         p.v[k] = vk;
         wk -= p.lr * (mk / c1) / (sqrtf(vk / c2) + p.eps);
@@ -365,49 +368,97 @@ __device__ __forceinline__ float opt_update(const WArgs& p, unsigned int k, floa
     return wk;
 }
 
+// A workgroup owns a 32 x 64 tile of one layer's weight matrix: it reduces the outer products
+// over the batch (128 rows per LDS pass, every global load of a pass issued before the first
+// use), adds the bias gradient when it sits on the tile row 0, and applies the optimizer.
 __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
-    __shared__ float As[kTK][kTM + 1];
+    __shared__ float As[kTK][kTM + 4];
     __shared__ float Bs[kTK][kTN + 4];
     const unsigned int tid = threadIdx.x;
     unsigned int j = 0;
     if (blockIdx.x >= p.job[1].tile_begin) j = 1;
     if (blockIdx.x >= p.job[2].tile_begin) j = 2;
-    const WJob& jb = p.job[j];
+    // copy the job out of the kernel arguments with uniform selects
+    const WJob jb = j == 0 ? p.job[0] : j == 1 ? p.job[1] : p.job[2];
     const unsigned int tile = blockIdx.x - jb.tile_begin;
     const unsigned int m0 = (tile / jb.tiles_n) * kTM, n0 = (tile % jb.tiles_n) * kTN;
     const unsigned int ty = tid >> 4, tx = tid & 15u;  // rows 2*ty.., columns 4*tx..
-    float acc[2][4] = {};
-    float bsum[4] = {};
     const bool do_bias = m0 == 0 && ty == 0;
 
-    for (unsigned int b0 = 0; b0 < p.B; b0 += kTK) {
-        for (unsigned int e = tid; e < kTK * kTM; e += kThreads) {
-            const unsigned int i = e / kTM, c = e % kTM;
-            const unsigned int bi = b0 + i, m = m0 + c;
-            As[i][c] = (bi < p.B && m < jb.M) ? jb.act[(size_t)bi * jb.lda + m] : 0.f;
+    // optimizer state of this thread's 2 x 4 outputs (+ 4 bias entries), fetched early so that
+    // its latency overlaps the product
+    float w_old[2][4], m_old[2][4], v_old[2][4], wb_old[4], mb_old[4], vb_old[4];
+    const bool adam = p.opt != RP_SGD;
+#pragma unroll
+    for (int r = 0; r < 2; ++r)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const unsigned int m = m0 + 2 * ty + r, nn = n0 + 4 * tx + c;
+            const bool ok = m < jb.M && nn < jb.N;
+            const unsigned int k = jb.w_off + m * jb.ldw + nn;
+            w_old[r][c] = ok ? p.w[k] : 0.f;
+            m_old[r][c] = ok && adam ? p.m[k] : 0.f;
+            v_old[r][c] = ok && adam ? p.v[k] : 0.f;
         }
-        for (unsigned int e = tid; e < kTK * kTN; e += kThreads) {
-            const unsigned int i = e / kTN, c = e % kTN;
-            const unsigned int bi = b0 + i, nn = n0 + c;
-            Bs[i][c] = (bi < p.B && nn < jb.N) ? jb.err[(size_t)bi * jb.ldb + nn] : 0.f;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const unsigned int nn = n0 + 4 * tx + c;
+        const bool ok = do_bias && nn < jb.N;
+        wb_old[c] = ok ? p.w[jb.b_off + nn] : 0.f;
+        mb_old[c] = ok && adam ? p.m[jb.b_off + nn] : 0.f;
+        vb_old[c] = ok && adam ? p.v[jb.b_off + nn] : 0.f;
+    }
+
+    const float c1 = p.ctr->c1, c2 = p.ctr->c2;
+    float acc[2][4] = {};
+    float bsum[4] = {};
+    for (unsigned int b0 = 0; b0 < p.B; b0 += kTK) {
+        // M is a multiple of 32 and N of 32, so float4 pieces are all in or all out
+        float4 av[4], bv[8];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const unsigned int e = tid + u * kThreads;          // 128 rows x 8 float4
+            const unsigned int i = e >> 3, c4 = (e & 7u) * 4u;
+            const unsigned int bi = b0 + i, m = m0 + c4;
+            av[u] = (bi < p.B && m < jb.M)
+                        ? *reinterpret_cast<const float4*>(jb.act + (size_t)bi * jb.lda + m)
+                        : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const unsigned int e = tid + u * kThreads;          // 128 rows x 16 float4
+            const unsigned int i = e >> 4, c4 = (e & 15u) * 4u;
+            const unsigned int bi = b0 + i, nn = n0 + c4;
+            bv[u] = (bi < p.B && nn < jb.N)
+                        ? *reinterpret_cast<const float4*>(jb.err + (size_t)bi * jb.ldb + nn)
+                        : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        if (b0) __syncthreads();
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const unsigned int e = tid + u * kThreads;
+            *reinterpret_cast<float4*>(&As[e >> 3][(e & 7u) * 4u]) = av[u];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const unsigned int e = tid + u * kThreads;
+            *reinterpret_cast<float4*>(&Bs[e >> 4][(e & 15u) * 4u]) = bv[u];
         }
         __syncthreads();
 #pragma unroll 8
         for (unsigned int i = 0; i < kTK; ++i) {
-            const float a0 = As[i][2 * ty], a1 = As[i][2 * ty + 1];
+            const float2 a = *reinterpret_cast<const float2*>(&As[i][2 * ty]);
             const float4 b = *reinterpret_cast<const float4*>(&Bs[i][4 * tx]);
-            acc[0][0] = fmaf(a0, b.x, acc[0][0]); acc[0][1] = fmaf(a0, b.y, acc[0][1]);
-            acc[0][2] = fmaf(a0, b.z, acc[0][2]); acc[0][3] = fmaf(a0, b.w, acc[0][3]);
-            acc[1][0] = fmaf(a1, b.x, acc[1][0]); acc[1][1] = fmaf(a1, b.y, acc[1][1]);
-            acc[1][2] = fmaf(a1, b.z, acc[1][2]); acc[1][3] = fmaf(a1, b.w, acc[1][3]);
+            acc[0][0] = fmaf(a.x, b.x, acc[0][0]); acc[0][1] = fmaf(a.x, b.y, acc[0][1]);
+            acc[0][2] = fmaf(a.x, b.z, acc[0][2]); acc[0][3] = fmaf(a.x, b.w, acc[0][3]);
+            acc[1][0] = fmaf(a.y, b.x, acc[1][0]); acc[1][1] = fmaf(a.y, b.y, acc[1][1]);
+            acc[1][2] = fmaf(a.y, b.z, acc[1][2]); acc[1][3] = fmaf(a.y, b.w, acc[1][3]);
             if (do_bias) {
                 bsum[0] += b.x; bsum[1] += b.y; bsum[2] += b.z; bsum[3] += b.w;
             }
         }
-        __syncthreads();
     }
 
-    const float c1 = p.ctr->c1, c2 = p.ctr->c2;
 #pragma unroll
     for (int r = 0; r < 2; ++r) {
         const unsigned int m = m0 + 2 * ty + r;
@@ -416,7 +467,8 @@ __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
         for (int c = 0; c < 4; ++c) {
             const unsigned int nn = n0 + 4 * tx + c;
             if (nn >= jb.N) continue;
-            const float wk = opt_update(p, jb.w_off + m * jb.ldw + nn, acc[r][c], c1, c2);
+            const float wk = opt_apply(p, jb.w_off + m * jb.ldw + nn, acc[r][c], w_old[r][c],
+                                       m_old[r][c], v_old[r][c], c1, c2);
             if (jb.wT) jb.wT[(size_t)nn * jb.M + m] = wk;
         }
     }
@@ -424,7 +476,8 @@ __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const unsigned int nn = n0 + 4 * tx + c;
-            if (nn < jb.N) opt_update(p, jb.b_off + nn, bsum[c], c1, c2);
+            if (nn < jb.N)
+                opt_apply(p, jb.b_off + nn, bsum[c], wb_old[c], mb_old[c], vb_old[c], c1, c2);
         }
     }
     if (blockIdx.x == 0 && tid < 64) {
@@ -440,7 +493,8 @@ __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
 
 size_t row_kernel_lds(unsigned int Dp, unsigned int H, unsigned int Ap) {
     const size_t ldx = Dp + kPadK, ldh = H + kPadK, ldq = Ap + kPadK;
-    return (8 * ldx + 8 * ldh * 2 + 8 * ldq + 4 * ldh + 4 * 8 * kChunk + 16 + 4) * sizeof(float);
+    return (8 * ldx + 8 * ldh * 2 + 8 * ldq + 4 * ldh + 4 * 8 * kChunk + 2 * H + Ap + 16 + 4) *
+           sizeof(float);
 }
 
 }  // namespace
@@ -448,7 +502,9 @@ size_t row_kernel_lds(unsigned int Dp, unsigned int H, unsigned int Ap) {
 bool fused_step_supported(const train_config& cfg, const replay* rp_) {
     if (cfg.param_dtype != RP_F32 || rp_->cfg.state_dtype != RP_F32 || rp_->cfg.layout != RP_PAIR)
         return false;
-    if (cfg.hidden % 64 != 0 || cfg.hidden > 512 || cfg.state_dim > 224 || cfg.num_actions > 224)
+    // one lane owns one column of a layer and holds its share of the weights in registers:
+    // hidden width up to 256, states and action sets up to 64 wide
+    if (cfg.hidden % 64 != 0 || cfg.hidden > 256 || cfg.state_dim > 64 || cfg.num_actions > 64)
         return false;
     if (cfg.batch > 8192 || cfg.appends_per_step > 8192) return false;
     const unsigned int Dp = (unsigned int)align_up(cfg.state_dim, 32);
@@ -456,17 +512,15 @@ bool fused_step_supported(const train_config& cfg, const replay* rp_) {
     return row_kernel_lds(Dp, cfg.hidden, Ap) <= 64 * 1024;
 }
 
-hipError_t enqueue_fused_step(trainer* t, hipStream_t st, unsigned int* count) {
+void* fused_rows_func() { return reinterpret_cast<void*>(fused_rows_kernel); }
+
+hipError_t enqueue_fused_step(trainer* t, const Payload& src, hipStream_t st, unsigned int* count) {
     replay* r = t->rp_;
-    RowArgs a;
+    RowArgs& a = t->row_args;
     a.g = r->geom;
     a.seed = r->cfg.seed;
     a.n_append = t->cfg.appends_per_step;
-    a.st_s = r->stage_s;
-    a.st_s_next = r->stage_s_next;
-    a.st_a = r->stage_a;
-    a.st_r = r->stage_r;
-    a.st_term = r->stage_term;
+    a.src = src;
     a.ctr = t->ctr;
     a.w = t->w;
     a.w2t = t->w2t;
@@ -481,9 +535,9 @@ hipError_t enqueue_fused_step(trainer* t, hipStream_t st, unsigned int* count) {
     a.dZ1 = static_cast<float*>(t->dZ1);
     a.act = t->act; a.rew = t->rew; a.term = t->term; a.idx = t->idx;
     const unsigned int blocks = (t->B + kRows - 1) / kRows;
-    hipLaunchKernelGGL(fused_rows_kernel, dim3(blocks), dim3(kThreads),
-                       row_kernel_lds(t->Dp, t->H, t->Ap), st, a);
-    hipError_t e = hipGetLastError();
+    void* kargs[] = {&a};
+    hipError_t e = hipLaunchKernel(fused_rows_func(), dim3(blocks), dim3(kRowThreads), kargs,
+                                   row_kernel_lds(t->Dp, t->H, t->Ap), st);
     if (e != hipSuccess) return e;
 
     WArgs w;

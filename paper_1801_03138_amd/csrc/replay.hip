@@ -86,10 +86,12 @@ bool compute_layout(const replay_config* c, Layout* L) {
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ void finish_append(const RingGeom& g, unsigned long long n,
                                               unsigned long long head) {
-    __threadfence();
+    // No fence: nothing written by this launch is read again inside it; the counter only
+    // establishes that every block has read the head it was going to use.
     __syncthreads();
     if (threadIdx.x == 0) {
-        const unsigned int done = atomicAdd(&g.state->blocks_done, 1u);
+        const unsigned int done = __hip_atomic_fetch_add(&g.state->blocks_done, 1u, __ATOMIC_RELAXED,
+                                                         __HIP_MEMORY_SCOPE_AGENT);
         if (done == gridDim.x - 1) {
             unsigned long long h = head + n;
             if (h >= g.capacity) h -= g.capacity;
@@ -98,7 +100,6 @@ __device__ __forceinline__ void finish_append(const RingGeom& g, unsigned long l
             g.state->size = sz > g.capacity ? g.capacity : sz;
             g.state->total += n;
             g.state->blocks_done = 0;
-            __threadfence();
         }
     }
 }
@@ -106,11 +107,15 @@ __device__ __forceinline__ void finish_append(const RingGeom& g, unsigned long l
 // PAIR rows: [s | s' | pad to 4 | action | reward bits | terminal 0/1 | zero pad], built one
 // 32-bit word per thread.
 template <int ELEM>
-__global__ __launch_bounds__(kThreads) void append_pair_kernel(
-    RingGeom g, unsigned long long n, const unsigned char* __restrict__ s,
-    const unsigned char* __restrict__ s_next, const int* __restrict__ a,
-    const float* __restrict__ r, const unsigned char* __restrict__ term,
-    unsigned int rows_per_block) {
+__global__ __launch_bounds__(kThreads) void append_pair_kernel(AppendArgs p) {
+    const RingGeom& g = p.g;
+    const unsigned long long n = p.n;
+    const unsigned char* __restrict__ s = p.src.s;
+    const unsigned char* __restrict__ s_next = p.src.s_next;
+    const int* __restrict__ a = p.src.a;
+    const float* __restrict__ r = p.src.r;
+    const unsigned char* __restrict__ term = p.src.term;
+    const unsigned int rows_per_block = p.rows_per_block;
     const unsigned long long head = g.state->head;
     const unsigned int words = g.row_bytes >> 2;
     const unsigned long long row0 = (unsigned long long)blockIdx.x * rows_per_block;
@@ -388,6 +393,27 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 }  // namespace
 
+AppendArgs make_append_args(const RingGeom& g, unsigned long long n, const Payload& src) {
+    AppendArgs a;
+    a.g = g;
+    a.n = n;
+    a.src = src;
+    const unsigned int words = g.row_bytes >> 2;
+    a.rows_per_block = kThreads * 4 / words;  // about four words per thread
+    if (a.rows_per_block == 0) a.rows_per_block = 1;
+    return a;
+}
+
+unsigned int append_blocks(const AppendArgs& a) {
+    return (unsigned int)((a.n + a.rows_per_block - 1) / a.rows_per_block);
+}
+
+void* append_pair_func(const RingGeom& g) {
+    if (g.elem_bytes == 4) return reinterpret_cast<void*>(append_pair_kernel<4>);
+    if (g.elem_bytes == 2) return reinterpret_cast<void*>(append_pair_kernel<2>);
+    return reinterpret_cast<void*>(append_pair_kernel<1>);
+}
+
 hipError_t launch_append(const RingGeom& g, unsigned long long n, const void* s,
                          const void* s_next, const int* a, const float* r,
                          const unsigned char* term, hipStream_t stream) {
@@ -395,19 +421,12 @@ hipError_t launch_append(const RingGeom& g, unsigned long long n, const void* s,
     const unsigned char* sp = static_cast<const unsigned char*>(s);
     const unsigned char* snp = static_cast<const unsigned char*>(s_next);
     if (g.layout == RP_PAIR) {
-        const unsigned int words = g.row_bytes >> 2;
-        unsigned int rpb = kThreads * 4 / words;  // about four words per thread
-        if (rpb == 0) rpb = 1;
-        const unsigned int blocks = (unsigned int)((n + rpb - 1) / rpb);
-        if (g.elem_bytes == 4)
-            hipLaunchKernelGGL(append_pair_kernel<4>, dim3(blocks), dim3(kThreads), 0, stream, g, n,
-                               sp, snp, a, r, term, rpb);
-        else if (g.elem_bytes == 2)
-            hipLaunchKernelGGL(append_pair_kernel<2>, dim3(blocks), dim3(kThreads), 0, stream, g, n,
-                               sp, snp, a, r, term, rpb);
-        else
-            hipLaunchKernelGGL(append_pair_kernel<1>, dim3(blocks), dim3(kThreads), 0, stream, g, n,
-                               sp, snp, a, r, term, rpb);
+        AppendArgs args = make_append_args(g, n, Payload{sp, snp, a, r, term});
+        const unsigned int blocks = append_blocks(args);
+        void* kargs[] = {&args};
+        hipError_t e = hipLaunchKernel(append_pair_func(g), dim3(blocks), dim3(kThreads), kargs, 0,
+                                       stream);
+        if (e != hipSuccess) return e;
     } else {
         const unsigned int blocks = (unsigned int)(n < 65536 ? n : 65536);
         if ((g.state_bytes & 15u) == 0 && aligned16(s))

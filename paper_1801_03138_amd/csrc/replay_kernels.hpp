@@ -11,6 +11,11 @@ hipError_t launch_append(const RingGeom& g, unsigned long long n, const void* s,
                          const void* s_next, const int* a, const float* r,
                          const unsigned char* term, hipStream_t stream);
 
+// Pieces of the PAIR append launch, for callers that record it into a graph themselves.
+AppendArgs make_append_args(const RingGeom& g, unsigned long long n, const Payload& src);
+unsigned int append_blocks(const AppendArgs& a);
+void* append_pair_func(const RingGeom& g);   // the __global__ function, as hipLaunchKernel takes it
+
 // Sample `batch` slots and unpack them.  The sampling step is *step_ptr when
 // step_ptr is non-null (device), else step_value.  out_ld is the row pitch of
 // out_s / out_s_next in elements (>= D); columns D..out_ld-1 are not written.

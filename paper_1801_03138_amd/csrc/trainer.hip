@@ -378,13 +378,17 @@ hipError_t enqueue_step(trainer* t, hipStream_t st, unsigned int* count) {
     return hipGetLastError();
 }
 
-hipError_t enqueue_append_and_step(trainer* t, hipStream_t st, unsigned int* count) {
-    if (t->fused) return enqueue_fused_step(t, st, count);
+// Enqueue one executed step: the kernel that consumes the new experiences first.
+hipError_t enqueue_append_and_step(trainer* t, const Payload& src, hipStream_t st,
+                                   unsigned int* count) {
+    if (t->fused) return enqueue_fused_step(t, src, st, count);
     unsigned int n = 0, k = 0;
     replay* r = t->rp_;
     if (t->cfg.appends_per_step) {
-        hipError_t e = launch_append(r->geom, t->cfg.appends_per_step, r->stage_s, r->stage_s_next,
-                                     r->stage_a, r->stage_r, r->stage_term, st);
+        t->append_args = make_append_args(r->geom, t->cfg.appends_per_step, src);
+        void* kargs[] = {&t->append_args};
+        hipError_t e = hipLaunchKernel(append_pair_func(r->geom), dim3(append_blocks(t->append_args)),
+                                       dim3(kThreads), kargs, 0, st);
         if (e != hipSuccess) return e;
         ++n;
     }
@@ -392,6 +396,33 @@ hipError_t enqueue_append_and_step(trainer* t, hipStream_t st, unsigned int* cou
                                                  : enqueue_step<float>(t, st, &k);
     if (count) *count = n + k;
     return e;
+}
+
+// Find the payload-consuming kernel's node in the recorded graph.
+hipError_t find_payload_node(trainer* t) {
+    t->payload_node = nullptr;
+    if (!t->cfg.appends_per_step) return hipSuccess;
+    size_t n = 0;
+    hipError_t e = hipGraphGetNodes(t->graph, nullptr, &n);
+    if (e != hipSuccess) return e;
+    std::vector<hipGraphNode_t> nodes(n);
+    e = hipGraphGetNodes(t->graph, nodes.data(), &n);
+    if (e != hipSuccess) return e;
+    for (size_t i = 0; i < n; ++i) {
+        hipGraphNodeType type;
+        if (hipGraphNodeGetType(nodes[i], &type) != hipSuccess || type != hipGraphNodeTypeKernel)
+            continue;
+        hipKernelNodeParams np;
+        if (hipGraphKernelNodeGetParams(nodes[i], &np) != hipSuccess) continue;
+        if (np.func == t->payload_func) {
+            t->payload_node = nodes[i];
+            t->payload_np = np;
+            t->payload_np.kernelParams = t->payload_kargs;
+            t->payload_np.extra = nullptr;
+            return hipSuccess;
+        }
+    }
+    return hipErrorNotFound;
 }
 
 }  // namespace
@@ -484,21 +515,61 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
     rp_status s = train_set_state(t, host_init_params, nullptr, nullptr, 0, 0);
     if (s != RP_OK) return fail(s);
 
+    // pinned host slots for host-sourced payloads
+    const size_t n_app = cfg->appends_per_step, sb = rp_->geom.state_bytes;
+    t->pin_host = t->pin_dev = nullptr;
+    t->pin_next = 0;
+    for (auto& ev : t->pin_event) ev = nullptr;
+    for (auto& live : t->pin_event_live) live = false;
+    if (n_app) {
+        size_t o = 0;
+        auto take = [&](size_t bytes) { size_t at = o; o = rp::align_up(o + bytes, 16); return at; };
+        take(n_app * sb);
+        t->pin_off_s_next = take(n_app * sb);
+        t->pin_off_a = take(n_app * 4);
+        t->pin_off_r = take(n_app * 4);
+        t->pin_off_term = take(n_app);
+        t->pin_slot_bytes = rp::align_up(o, 128);
+        void* hp = nullptr;
+        void* dp = nullptr;
+        e = hipHostMalloc(&hp, t->pin_slot_bytes * rp::kPinSlots, hipHostMallocMapped);
+        if (e == hipSuccess) {
+            t->pin_host = static_cast<unsigned char*>(hp);
+            e = hipHostGetDevicePointer(&dp, hp, 0);
+        }
+        for (auto& ev : t->pin_event)
+            if (e == hipSuccess) e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+        if (e != hipSuccess) {
+            rp::set_error("train_create: pinned payload slots: %s", hipGetErrorString(e));
+            return fail(RP_EHIP);
+        }
+        t->pin_dev = static_cast<unsigned char*>(dp);
+    }
+    t->payload_func = t->fused ? rp::fused_rows_func() : rp::append_pair_func(rp_->geom);
+    t->payload_kargs[0] = t->fused ? static_cast<void*>(&t->row_args) : static_cast<void*>(&t->append_args);
+    t->payload_node = nullptr;
+
     if (cfg->flags & RP_TRAIN_GRAPH) {
+        // recorded once with the replay's staging area as a stand-in payload; the payload
+        // kernel's argument is replaced before every launch
+        const rp::Payload stand_in{rp_->stage_s, rp_->stage_s_next, rp_->stage_a, rp_->stage_r,
+                                   rp_->stage_term};
         e = hipStreamCreateWithFlags(&t->capture_stream, hipStreamNonBlocking);
         if (e == hipSuccess) e = hipStreamBeginCapture(t->capture_stream, hipStreamCaptureModeThreadLocal);
         if (e == hipSuccess) {
-            hipError_t ek = rp::enqueue_append_and_step(t, t->capture_stream, &t->kernels_per_step);
+            hipError_t ek = rp::enqueue_append_and_step(t, stand_in, t->capture_stream,
+                                                        &t->kernels_per_step);
             e = hipStreamEndCapture(t->capture_stream, &t->graph);
             if (ek != hipSuccess) e = ek;
         }
+        if (e == hipSuccess) e = rp::find_payload_node(t);
         if (e == hipSuccess) e = hipGraphInstantiate(&t->graph_exec, t->graph, nullptr, nullptr, 0);
         if (e != hipSuccess) {
             rp::set_error("train_create: recording the step graph failed: %s", hipGetErrorString(e));
             return fail(RP_EHIP);
         }
     } else {
-        // count the launches without running them: the count is static
+        // the launch count is static
         t->kernels_per_step = t->fused ? 2u : (cfg->appends_per_step ? 1u : 0u) + 14u;
     }
     *out = t;
@@ -510,6 +581,9 @@ rp_status train_destroy(trainer_t* t) {
     if (t->graph_exec) (void)hipGraphExecDestroy(t->graph_exec);
     if (t->graph) (void)hipGraphDestroy(t->graph);
     if (t->capture_stream) (void)hipStreamDestroy(t->capture_stream);
+    for (auto& ev : t->pin_event)
+        if (ev) (void)hipEventDestroy(ev);
+    if (t->pin_host) (void)hipHostFree(t->pin_host);
     delete t;
     return RP_OK;
 }
@@ -520,27 +594,54 @@ rp_status train_step(trainer_t* t, const void* s, const void* s_next, const int3
     replay* rpl = t->rp_;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const uint64_t n = t->cfg.appends_per_step;
+    rp::Payload src{nullptr, nullptr, nullptr, nullptr, nullptr};
+    unsigned int slot = 0;
+    const bool host_src = n && !src_is_device;
     if (n) {
         RP_REQUIRE(s && s_next && a && r && term, "train_step: null field array for the append");
-        const hipMemcpyKind kind = src_is_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
-        const size_t sb = rpl->geom.state_bytes;
-        RP_CHECK_HIP(hipMemcpyAsync(rpl->stage_s, s, n * sb, kind, st));
-        RP_CHECK_HIP(hipMemcpyAsync(rpl->stage_s_next, s_next, n * sb, kind, st));
-        RP_CHECK_HIP(hipMemcpyAsync(rpl->stage_a, a, n * 4, kind, st));
-        RP_CHECK_HIP(hipMemcpyAsync(rpl->stage_r, r, n * 4, kind, st));
-        RP_CHECK_HIP(hipMemcpyAsync(rpl->stage_term, term, n, kind, st));
+        if (src_is_device) {
+            src = rp::Payload{static_cast<const unsigned char*>(s), static_cast<const unsigned char*>(s_next),
+                              a, r, term};
+        } else {
+            // copy into the next pinned slot; the kernel reads it in place over the host link
+            slot = (unsigned int)(t->pin_next % rp::kPinSlots);
+            const unsigned int grp = slot / rp::kPinGroup;
+            if (slot % rp::kPinGroup == 0 && t->pin_event_live[grp])
+                RP_CHECK_HIP(hipEventSynchronize(t->pin_event[grp]));
+            const size_t sb = rpl->geom.state_bytes, base = (size_t)slot * t->pin_slot_bytes;
+            unsigned char* h = t->pin_host + base;
+            memcpy(h, s, n * sb);
+            memcpy(h + t->pin_off_s_next, s_next, n * sb);
+            memcpy(h + t->pin_off_a, a, n * 4);
+            memcpy(h + t->pin_off_r, r, n * 4);
+            memcpy(h + t->pin_off_term, term, n);
+            const unsigned char* d = t->pin_dev + base;
+            src = rp::Payload{d, d + t->pin_off_s_next, reinterpret_cast<const int*>(d + t->pin_off_a),
+                              reinterpret_cast<const float*>(d + t->pin_off_r), d + t->pin_off_term};
+        }
     }
     const uint64_t total_after = rpl->total + n;
     const uint64_t size_after = rpl->size + n > rpl->cfg.capacity ? rpl->cfg.capacity : rpl->size + n;
     const bool train = total_after >= rpl->cfg.burn_in && size_after >= 1;
     if (!train) {
         if (n)
-            RP_CHECK_HIP(rp::launch_append(rpl->geom, n, rpl->stage_s, rpl->stage_s_next, rpl->stage_a,
-                                           rpl->stage_r, rpl->stage_term, st));
+            RP_CHECK_HIP(rp::launch_append(rpl->geom, n, src.s, src.s_next, src.a, src.r, src.term, st));
     } else if (t->graph_exec) {
+        if (t->payload_node) {
+            if (t->fused) t->row_args.src = src; else t->append_args.src = src;
+            RP_CHECK_HIP(hipGraphExecKernelNodeSetParams(t->graph_exec, t->payload_node, &t->payload_np));
+        }
         RP_CHECK_HIP(hipGraphLaunch(t->graph_exec, st));
     } else {
-        RP_CHECK_HIP(rp::enqueue_append_and_step(t, st, nullptr));
+        RP_CHECK_HIP(rp::enqueue_append_and_step(t, src, st, nullptr));
+    }
+    if (host_src) {
+        if (slot % rp::kPinGroup == rp::kPinGroup - 1) {
+            const unsigned int grp = slot / rp::kPinGroup;
+            RP_CHECK_HIP(hipEventRecord(t->pin_event[grp], st));
+            t->pin_event_live[grp] = true;
+        }
+        t->pin_next += 1;
     }
     rpl->total = total_after;
     rpl->size = size_after;

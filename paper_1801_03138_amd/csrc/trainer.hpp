@@ -52,6 +52,29 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
+// Argument block of the fused row kernel.
+struct RowArgs {
+    RingGeom g;
+    unsigned long long seed;
+    unsigned int n_append;
+    Payload src;          // this step's new experiences
+    TrainCounters* ctr;
+    const float* w;       // padded parameters
+    const float* w2t;     // W2 transposed
+    unsigned int B, D, Dp, H, A, Ap;
+    unsigned int oW1, ob1, oW2, ob2, oW3, ob3;
+    float gamma, beta1, beta2;
+    unsigned int loss_kind;
+    float *X, *H1, *H2, *Q, *y, *delta, *lossi, *dQ, *dZ2, *dZ1;
+    int* act;
+    float* rew;
+    unsigned char* term;
+    unsigned int* idx;
+};
+
+constexpr unsigned int kPinSlots = 64;       // pinned host slots for host-sourced payloads
+constexpr unsigned int kPinGroup = 16;       // slots per completion event
+
 }  // namespace rp
 
 struct trainer {
@@ -81,6 +104,23 @@ struct trainer {
     hipStream_t capture_stream;
     unsigned int kernels_per_step;
     uint64_t host_step;              // mirror of ctr->step
+    // The kernel that consumes the step's new experiences (fused row kernel, or the append
+    // kernel of the layered step): host copy of its argument block, and its node in the graph,
+    // whose argument is replaced before every launch.
+    rp::RowArgs row_args;
+    rp::AppendArgs append_args;
+    void* payload_func;
+    void* payload_kargs[1];
+    hipGraphNode_t payload_node;
+    hipKernelNodeParams payload_np;
+    // Host-sourced payloads are copied into a ring of pinned, device-mapped host slots that the
+    // kernel reads directly; an event per group of slots tells when a group may be reused.
+    unsigned char* pin_host;
+    unsigned char* pin_dev;
+    size_t pin_slot_bytes, pin_off_s_next, pin_off_a, pin_off_r, pin_off_term;
+    uint64_t pin_next;
+    hipEvent_t pin_event[rp::kPinSlots / rp::kPinGroup];
+    bool pin_event_live[rp::kPinSlots / rp::kPinGroup];
 };
 
 namespace rp {
@@ -89,5 +129,6 @@ bool fused_step_supported(const train_config& cfg, const replay* rp_);
 // Dynamic LDS bytes its row kernel needs.
 // Enqueue the fused step (append + sample + gather + forward + TD + backward; weight
 // gradients + optimizer).  *count receives the number of kernels launched.
-hipError_t enqueue_fused_step(trainer* t, hipStream_t st, unsigned int* count);
+hipError_t enqueue_fused_step(trainer* t, const Payload& src, hipStream_t st, unsigned int* count);
+void* fused_rows_func();
 }  // namespace rp

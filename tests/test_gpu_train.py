@@ -185,17 +185,55 @@ def test_paper_shaped_config_sampled_steps(B):
     assert pr.trainer.opt_state()[2:] == (10_000, 10_000)
     assert pr.gpu_ring.state() == pr.ref_ring.state() == (59_999, 59_999, 59_999)
     assert pr.trainer.kernels_per_step() == 2
+    # every streamed experience landed in its slot although thousands of steps were in flight
+    g, o = pr.gpu_ring.read_rows(49_000, 10_999), pr.ref_ring.read(49_000, 10_999)
+    assert all(np.array_equal(x.view(np.uint8), y.view(np.uint8)) for x, y in zip(g, o))
 
 
-def test_wider_net_both_paths_agree_with_oracle(B):
-    """27-320-320-30 (more than one 256-column pass per layer), batch 130, ring that wraps."""
+@pytest.mark.parametrize("layered", [False, True])
+def test_many_steps_in_flight_with_device_payload(B, layered):
+    """train_steps with device arrays: 3000 steps queued without a sync, 2 appends each, into a
+    ring that wraps; the ring must end up exactly as the oracle's and the counters must add up."""
+    n_steps, per = 3000, 2
+    rows = synth.experiences(n_steps * per, 27, 30, 0.05, seed=21)
+    pr = Pair(B, capacity=4096, D=27, H=64, A=30, batch=64, burn_in=100, seed=5, appends=per,
+              layered=layered)
+    d = {k: torch.from_numpy(v).cuda() for k, v in rows.items()}
+    done = pr.trainer.steps(n_steps, d["s"], d["s_next"], d["a"], d["r"], d["term"])
+    for lo in range(0, n_steps * per, 4096):
+        part = synth.take(rows, lo, min(lo + 4096, n_steps * per))
+        pr.ref_ring.append(part["s"], part["s_next"], part["a"], part["r"], part["term"])
+    assert done == n_steps - 49          # the first 49 steps end below the burn-in of 100
+    assert pr.trainer.opt_state()[2:] == (done, done)
+    assert pr.gpu_ring.state() == pr.ref_ring.state()
+    g, o = pr.gpu_ring.read_rows(0, 4096), pr.ref_ring.read(0, 4096)
+    assert all(np.array_equal(x.view(np.uint8), y.view(np.uint8)) for x, y in zip(g, o))
+    # and the next step still matches the oracle
+    extra = synth.experiences(per, 27, 30, 0.05, seed=22)
+    assert pr.step(extra, compare=True) == 0
+
+
+@pytest.mark.parametrize("H,layered,kernels", [(192, False, 2), (320, False, 15), (320, True, 15)])
+def test_other_widths_agree_with_oracle(B, H, layered, kernels):
+    """Widths that leave lanes idle in the row kernel (192) or exceed it (320, one kernel per
+    layer, tiles with ragged edges); batch 130, ring that wraps."""
     rows = synth.experiences(900, 27, 30, 0.05, seed=12)
-    for layered in (False, True):
-        pr = Pair(B, capacity=500, D=27, H=320, A=30, batch=130, burn_in=300, seed=4, appends=2,
-                  layered=layered)
-        for k in range(0, 900, 2):
-            pr.step(synth.take(rows, k, k + 2), compare=(k % 50 == 0) or k >= 880)
-        assert pr.gpu_ring.state() == pr.ref_ring.state()
+    pr = Pair(B, capacity=500, D=27, H=H, A=30, batch=130, burn_in=300, seed=4, appends=2,
+              layered=layered)
+    assert pr.trainer.kernels_per_step() == kernels
+    for k in range(0, 900, 2):
+        pr.step(synth.take(rows, k, k + 2), compare=(k % 50 == 0) or k >= 880)
+    assert pr.gpu_ring.state() == pr.ref_ring.state()
+
+
+def test_wide_state_and_action_sets(B):
+    """D = 60 and A = 64 fill the row kernel's 64-wide limits; D = 70 goes layer by layer."""
+    for D, A, kernels in ((60, 64, 2), (70, 40, 15)):
+        rows = synth.experiences(400, D, A, 0.05, seed=13)
+        pr = Pair(B, capacity=300, D=D, H=128, A=A, batch=37, burn_in=50, seed=6, appends=1)
+        assert pr.trainer.kernels_per_step() == kernels
+        for k in range(400):
+            pr.step(synth.take(rows, k, k + 1), compare=(k % 40 == 0) or k >= 395)
 
 
 def test_terminal_rows_and_out_of_range_actions_are_safe(B):
