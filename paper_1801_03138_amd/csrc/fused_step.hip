@@ -26,6 +26,13 @@ constexpr unsigned int kPadK = 4;          // LDS row padding (floats) against b
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
+// outstanding global load of the wavefront, which would cancel the register prefetch of the
+// weights; the row kernel exchanges data between wavefronts through LDS alone.
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 
 // One 32-bit word of the packed row of a new experience, taken from the staging arrays.
 __device__ __forceinline__ unsigned int staged_word(const RowArgs& p, unsigned long long k,
@@ -127,19 +134,18 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     // narrow split
     const unsigned int s3 = H >> 4;                 // K sixteenth of layer 3
 
-    // ---- phase 0: everything that does not depend on the sample is requested first
+    // ---- phase 0: the ring and trainer state as they stand before this step's append, then
+    // everything else that does not depend on the sample, all requested before the first use
+    const unsigned long long cap = p.g.capacity;
+    const unsigned long long head = p.g.state->head;
+    const unsigned long long size0 = p.g.state->size;
+    const unsigned long long step = p.ctr->step;
     float w1r[16], w2r[64];
     load_cols<16>(w1r, W1, H, cc, ks * q1, q1);
     load_cols<64>(w2r, W2, H, cc, ks * q2, q2);
     const float b1v = tid < H ? p.w[p.ob1 + tid] : 0.f;
     const float b2v = tid < H ? p.w[p.ob2 + tid] : 0.f;
     const float b3v = tid < Ap ? p.w[p.ob3 + tid] : 0.f;
-
-    // ring and trainer state as they stand before this step's append
-    const unsigned long long cap = p.g.capacity;
-    const unsigned long long head = p.g.state->head;
-    const unsigned long long size0 = p.g.state->size;
-    const unsigned long long step = p.ctr->step;
     const unsigned long long n = p.n_append;
     const unsigned int size = (unsigned int)(size0 + n > cap ? cap : size0 + n);
     const unsigned int i0 = blockIdx.x * kRows;
@@ -147,7 +153,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
 
     for (unsigned int e = tid; e < 8 * ldx; e += kRowThreads) Xs[e] = 0.f;
     if (tid < 16) meta[tid] = 0;
-    __syncthreads();
+    lds_barrier();
 
     // ---- sample and gather: one 32-bit word per thread.  A drawn slot that this step's append
     // is about to overwrite is read from the payload arrays, which hold its new content.
@@ -183,7 +189,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
         b2s[tid] = b2v;
     }
     if (tid < Ap) b3s[tid] = b3v;
-    __syncthreads();
+    lds_barrier();
 
     // the column of W3 that the backward pass of each row needs: W3[k][a_r], one per thread
     float w3sel = 0.f;
@@ -200,7 +206,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     f32x4 acc2[2];
     mma_cols<2, 16>(acc2, Xs, ldx, ks * q1, q1, w1r);
     store_part<2>(part, ks, kChunk, cc, acc2);
-    __syncthreads();
+    lds_barrier();
     for (unsigned int e = tid; e < 8 * H; e += kRowThreads) {
         const unsigned int row = e / H, c = e - row * H;
         float v = sum_part(part, 4, 8, kChunk, row, c) + b1s[c];
@@ -208,7 +214,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
         H1s[row * ldh + c] = v;
         if (row < nrows) p.H1[(size_t)(i0 + row) * H + c] = v;
     }
-    __syncthreads();
+    lds_barrier();
 
     // ---- layer 2; its registers are then refilled with W2^T (backward) and W3 is requested
     mma_cols<2, 64>(acc2, H1s, ldh, ks * q2, q2, w2r);
@@ -216,7 +222,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     load_cols<16>(w3r, W3, Ap, lane, wave * s3, s3);
     load_cols<64>(w2r, p.w2t, H, cc, ks * q2, q2);
     store_part<2>(part, ks, kChunk, cc, acc2);
-    __syncthreads();
+    lds_barrier();
     for (unsigned int e = tid; e < 8 * H; e += kRowThreads) {
         const unsigned int row = e / H, c = e - row * H;
         float v = sum_part(part, 4, 8, kChunk, row, c) + b2s[c];
@@ -224,19 +230,19 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
         H2s[row * ldh + c] = v;
         if (row < nrows) p.H2[(size_t)(i0 + row) * H + c] = v;
     }
-    __syncthreads();
+    lds_barrier();
 
     // ---- layer 3 (narrow split: 16 K slices, columns 0..63)
     mma_cols<2, 16>(acc2, H2s, ldh, wave * s3, s3, w3r);
     store_part<2>(part, wave, 64, lane, acc2);
-    __syncthreads();
+    lds_barrier();
     for (unsigned int e = tid; e < 8 * Ap; e += kRowThreads) {
         const unsigned int row = e / Ap, c = e - row * Ap, r = row & 3u;
         const float v = sum_part(part, 16, 8, 64, row, c) + b3s[c];
         Qs[row * ldq + c] = v;
         if (r < nrows) p.Q[((size_t)(row < 4 ? 0 : p.B) + i0 + r) * Ap + c] = v;
     }
-    __syncthreads();
+    lds_barrier();
 
     // ---- TD target, loss term, dL/dQ
     if (tid < nrows) {
@@ -263,7 +269,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
         p.delta[i] = d;
         p.lossi[i] = li;
     }
-    __syncthreads();
+    lds_barrier();
     for (unsigned int e = tid; e < nrows * Ap; e += kRowThreads) {
         const unsigned int r = e / Ap, c = e - r * Ap;
         p.dQ[(size_t)(i0 + r) * Ap + c] = (c == meta[r * 4 + 3]) ? gs[r] : 0.f;
@@ -278,13 +284,13 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
             if (r < nrows) p.dZ2[(size_t)(i0 + r) * H + k] = v;
         }
     }
-    __syncthreads();
+    lds_barrier();
 
     // ---- dZ1 = (dZ2 W2^T) masked by the first ReLU
     f32x4 acc1[1];
     mma_cols<1, 64>(acc1, dZs, ldh, ks * q2, q2, w2r);
     store_part<1>(part, ks, kChunk, cc, acc1);
-    __syncthreads();
+    lds_barrier();
     for (unsigned int e = tid; e < nrows * H; e += kRowThreads) {
         const unsigned int r = e / H, c = e - r * H;
         float v = sum_part(part, 4, 4, kChunk, r, c);
@@ -352,8 +358,9 @@ struct WArgs {
 constexpr unsigned int kTM = 32, kTN = 64, kTK = 128;
 
 // One optimizer update of parameter k with gradient gk, from values loaded earlier.
+// r1 = 1 / (1 - beta1^t), r2 = 1 / (1 - beta2^t).
 __device__ __forceinline__ float opt_apply(const WArgs& p, unsigned int k, float gk, float wk,
-                                           float mk, float vk, float c1, float c2) {
+                                           float mk, float vk, float r1, float r2) {
     p.g[k] = gk;
     if (p.opt == RP_SGD) {
         wk -= p.lr * gk;
@@ -362,7 +369,7 @@ __device__ __forceinline__ float opt_apply(const WArgs& p, unsigned int k, float
         vk = p.beta2 * vk + (1.f - p.beta2) * gk * gk;
         p.m[k] = mk;
         p.v[k] = vk;
-        wk -= p.lr * (mk / c1) / (sqrtf(vk / c2) + p.eps);
+        wk -= p.lr * (mk * r1) / (sqrtf(vk * r2) + p.eps);
     }
     p.w[k] = wk;
     return wk;
@@ -370,50 +377,50 @@ __device__ __forceinline__ float opt_apply(const WArgs& p, unsigned int k, float
 
 // A workgroup owns a 32 x 64 tile of one layer's weight matrix: it reduces the outer products
 // over the batch (128 rows per LDS pass, every global load of a pass issued before the first
-// use), adds the bias gradient when it sits on the tile row 0, and applies the optimizer.
+// use) with 16x16x4 fp32 MFMA -- wavefront w takes columns 16w..16w+15 and both 16-row halves --
+// adds the bias gradient when it sits on tile row 0 (a third MFMA with an all-ones A operand
+// gives the column sums), and applies the optimizer to what it holds.
 __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
     __shared__ float As[kTK][kTM + 4];
     __shared__ float Bs[kTK][kTN + 4];
-    const unsigned int tid = threadIdx.x;
+    const unsigned int tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const unsigned int l16 = lane & 15u, lq = lane >> 4;
     unsigned int j = 0;
     if (blockIdx.x >= p.job[1].tile_begin) j = 1;
     if (blockIdx.x >= p.job[2].tile_begin) j = 2;
-    // copy the job out of the kernel arguments with uniform selects
     const WJob jb = j == 0 ? p.job[0] : j == 1 ? p.job[1] : p.job[2];
     const unsigned int tile = blockIdx.x - jb.tile_begin;
     const unsigned int m0 = (tile / jb.tiles_n) * kTM, n0 = (tile % jb.tiles_n) * kTN;
-    const unsigned int ty = tid >> 4, tx = tid & 15u;  // rows 2*ty.., columns 4*tx..
-    const bool do_bias = m0 == 0 && ty == 0;
+    const bool bias_tile = m0 == 0;
+    // this lane's outputs: rows m0 + 16 rt + 4 lq + v (rt = 0,1; v = 0..3), column nn
+    const unsigned int nn = n0 + 16u * wave + l16;
+    const bool col_ok = nn < jb.N;
+    const bool do_bias = bias_tile && lq == 0 && col_ok;
 
-    // optimizer state of this thread's 2 x 4 outputs (+ 4 bias entries), fetched early so that
-    // its latency overlaps the product
-    float w_old[2][4], m_old[2][4], v_old[2][4], wb_old[4], mb_old[4], vb_old[4];
-    const bool adam = p.opt != RP_SGD;
-#pragma unroll
-    for (int r = 0; r < 2; ++r)
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const unsigned int m = m0 + 2 * ty + r, nn = n0 + 4 * tx + c;
-            const bool ok = m < jb.M && nn < jb.N;
-            const unsigned int k = jb.w_off + m * jb.ldw + nn;
-            w_old[r][c] = ok ? p.w[k] : 0.f;
-            m_old[r][c] = ok && adam ? p.m[k] : 0.f;
-            v_old[r][c] = ok && adam ? p.v[k] : 0.f;
-        }
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        const unsigned int nn = n0 + 4 * tx + c;
-        const bool ok = do_bias && nn < jb.N;
-        wb_old[c] = ok ? p.w[jb.b_off + nn] : 0.f;
-        mb_old[c] = ok && adam ? p.m[jb.b_off + nn] : 0.f;
-        vb_old[c] = ok && adam ? p.v[jb.b_off + nn] : 0.f;
-    }
-
+    // bias corrections and the optimizer state of this lane's outputs, fetched early so that
+    // their latency overlaps the product
     const float c1 = p.ctr->c1, c2 = p.ctr->c2;
-    float acc[2][4] = {};
-    float bsum[4] = {};
+    const bool adam = p.opt != RP_SGD;
+    float w_old[2][4], m_old[2][4], v_old[2][4];
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const unsigned int m = m0 + 16u * rt + 4u * lq + v;
+            const bool ok = col_ok && m < jb.M;
+            const unsigned int k = jb.w_off + m * jb.ldw + nn;
+            w_old[rt][v] = ok ? p.w[k] : 0.f;
+            m_old[rt][v] = ok && adam ? p.m[k] : 0.f;
+            v_old[rt][v] = ok && adam ? p.v[k] : 0.f;
+        }
+    const float wb_old = do_bias ? p.w[jb.b_off + nn] : 0.f;
+    const float mb_old = do_bias && adam ? p.m[jb.b_off + nn] : 0.f;
+    const float vb_old = do_bias && adam ? p.v[jb.b_off + nn] : 0.f;
+
+    f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+    f32x4 accb = f32x4{0.f, 0.f, 0.f, 0.f};
     for (unsigned int b0 = 0; b0 < p.B; b0 += kTK) {
-        // M is a multiple of 32 and N of 32, so float4 pieces are all in or all out
+        // M and N are multiples of 32, so float4 pieces are all in or all out
         float4 av[4], bv[8];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -428,9 +435,9 @@ __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
         for (int u = 0; u < 8; ++u) {
             const unsigned int e = tid + u * kThreads;          // 128 rows x 16 float4
             const unsigned int i = e >> 4, c4 = (e & 15u) * 4u;
-            const unsigned int bi = b0 + i, nn = n0 + c4;
-            bv[u] = (bi < p.B && nn < jb.N)
-                        ? *reinterpret_cast<const float4*>(jb.err + (size_t)bi * jb.ldb + nn)
+            const unsigned int bi = b0 + i, nc = n0 + c4;
+            bv[u] = (bi < p.B && nc < jb.N)
+                        ? *reinterpret_cast<const float4*>(jb.err + (size_t)bi * jb.ldb + nc)
                         : make_float4(0.f, 0.f, 0.f, 0.f);
         }
         if (b0) __syncthreads();
@@ -445,41 +452,29 @@ __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
             *reinterpret_cast<float4*>(&Bs[e >> 4][(e & 15u) * 4u]) = bv[u];
         }
         __syncthreads();
+        // A fragment: lane holds Act[k4 + lq][row l16]; B fragment: Err[k4 + lq][column l16]
 #pragma unroll 8
-        for (unsigned int i = 0; i < kTK; ++i) {
-            const float2 a = *reinterpret_cast<const float2*>(&As[i][2 * ty]);
-            const float4 b = *reinterpret_cast<const float4*>(&Bs[i][4 * tx]);
-            acc[0][0] = fmaf(a.x, b.x, acc[0][0]); acc[0][1] = fmaf(a.x, b.y, acc[0][1]);
-            acc[0][2] = fmaf(a.x, b.z, acc[0][2]); acc[0][3] = fmaf(a.x, b.w, acc[0][3]);
-            acc[1][0] = fmaf(a.y, b.x, acc[1][0]); acc[1][1] = fmaf(a.y, b.y, acc[1][1]);
-            acc[1][2] = fmaf(a.y, b.z, acc[1][2]); acc[1][3] = fmaf(a.y, b.w, acc[1][3]);
-            if (do_bias) {
-                bsum[0] += b.x; bsum[1] += b.y; bsum[2] += b.z; bsum[3] += b.w;
-            }
+        for (unsigned int k4 = 0; k4 < kTK; k4 += 4) {
+            const float b = Bs[k4 + lq][16u * wave + l16];
+            const float a0 = As[k4 + lq][l16], a1 = As[k4 + lq][16u + l16];
+            acc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b, acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b, acc[1], 0, 0, 0);
+            if (bias_tile) accb = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, b, accb, 0, 0, 0);
         }
     }
 
+    const float r1 = 1.f / c1, r2 = 1.f / c2;
 #pragma unroll
-    for (int r = 0; r < 2; ++r) {
-        const unsigned int m = m0 + 2 * ty + r;
-        if (m >= jb.M) continue;
+    for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const unsigned int nn = n0 + 4 * tx + c;
-            if (nn >= jb.N) continue;
-            const float wk = opt_apply(p, jb.w_off + m * jb.ldw + nn, acc[r][c], w_old[r][c],
-                                       m_old[r][c], v_old[r][c], c1, c2);
+        for (int v = 0; v < 4; ++v) {
+            const unsigned int m = m0 + 16u * rt + 4u * lq + v;
+            if (!col_ok || m >= jb.M) continue;
+            const float wk = opt_apply(p, jb.w_off + m * jb.ldw + nn, acc[rt][v], w_old[rt][v],
+                                       m_old[rt][v], v_old[rt][v], r1, r2);
             if (jb.wT) jb.wT[(size_t)nn * jb.M + m] = wk;
         }
-    }
-    if (do_bias) {
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const unsigned int nn = n0 + 4 * tx + c;
-            if (nn < jb.N)
-                opt_apply(p, jb.b_off + nn, bsum[c], wb_old[c], mb_old[c], vb_old[c], c1, c2);
-        }
-    }
+    if (do_bias) opt_apply(p, jb.b_off + nn, accb[0], wb_old, mb_old, vb_old, r1, r2);
     if (blockIdx.x == 0 && tid < 64) {
         float s = 0.f;
         for (unsigned int i = tid; i < p.B; i += 64) s += p.lossi[i];
