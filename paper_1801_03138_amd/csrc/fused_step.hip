@@ -89,6 +89,38 @@ __device__ __forceinline__ void mma_cols(f32x4 (&acc)[MG], const float* act, uns
     }
 }
 
+// The same product, and as soon as a group of four weight registers has been consumed it is
+// refilled from the next matrix (Wn, [.. x Nn], rows kbeg_n..): the loads of the next layer's
+// weights overlap this layer's MFMAs instead of queueing up behind them.
+template <int MG, int NR>
+__device__ __forceinline__ void mma_cols_reload(f32x4 (&acc)[MG], const float* act,
+                                                unsigned int ldk, unsigned int kbeg,
+                                                unsigned int kcount, float (&wr)[NR],
+                                                const float* __restrict__ Wn, unsigned int Nn,
+                                                unsigned int col_n, unsigned int kbeg_n,
+                                                unsigned int kcount_n) {
+    const float* ap = act + (threadIdx.x & 3u) * ldk + kbeg;
+    const bool active_n = col_n < Nn;
+    const float* wp = Wn + (size_t)kbeg_n * Nn + col_n;
+#pragma unroll
+    for (int mg = 0; mg < MG; ++mg) acc[mg] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u4 = 0; u4 < NR; u4 += 4) {
+        if ((unsigned int)u4 < kcount) {
+#pragma unroll
+            for (int mg = 0; mg < MG; ++mg) {
+                const f32x4 a = *reinterpret_cast<const f32x4*>(ap + (size_t)mg * 4 * ldk + u4);
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    acc[mg] = __builtin_amdgcn_mfma_f32_4x4x1f32(a[u], wr[u4 + u], acc[mg], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            wr[u4 + u] = (active_n && (unsigned int)(u4 + u) < kcount_n) ? wp[(size_t)(u4 + u) * Nn] : 0.f;
+    }
+}
+
 // part[slice][row][cc] = acc; the lane holds rows v = 0..3 of its column cc
 template <int MG>
 __device__ __forceinline__ void store_part(float* part, unsigned int slice, unsigned int pitch,
@@ -134,53 +166,69 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     // narrow split
     const unsigned int s3 = H >> 4;                 // K sixteenth of layer 3
 
-    // ---- phase 0: the ring and trainer state as they stand before this step's append, then
-    // everything else that does not depend on the sample, all requested before the first use
+    // ---- phase 0.  The ring and trainer state before this step come as arguments (the host
+    // mirrors them exactly), so the slot draw and the row fetch go out first; then everything
+    // that does not depend on the sample is requested, long before its first use.
     const unsigned long long cap = p.g.capacity;
-    const unsigned long long head = p.g.state->head;
-    const unsigned long long size0 = p.g.state->size;
-    const unsigned long long step = p.ctr->step;
+    const unsigned long long head = p.head;
+    const unsigned long long step = p.step;
+    const unsigned long long n = p.n_append;
+    const unsigned int size = p.size_after;
+    const unsigned int i0 = blockIdx.x * kRows;
+    const unsigned int nrows = min(kRows, p.B - i0);
+    const unsigned int words = 2 * D + 3;
+
+    // sample and gather: one 32-bit word per thread (two passes at most, D <= 64).  A drawn
+    // slot that this step's append is about to overwrite is read from the payload arrays,
+    // which hold its new content.
+    unsigned int gval[2] = {0u, 0u}, gslot[2] = {0u, 0u};
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const unsigned int e = tid + pass * kRowThreads;
+        if (e < nrows * words) {
+            const unsigned int r = e / words, w = e - r * words;
+            const unsigned int slot = uniform_draw(p.seed, step, i0 + r, size);
+            unsigned long long off = (unsigned long long)slot + cap - head;
+            if (off >= cap) off -= cap;
+            gslot[pass] = slot;
+            gval[pass] = off < n ? staged_word(p, off, w)
+                                 : reinterpret_cast<const unsigned int*>(
+                                       p.g.rows + (unsigned long long)slot * p.g.row_bytes)[w];
+        }
+    }
     float w1r[16], w2r[64];
     load_cols<16>(w1r, W1, H, cc, ks * q1, q1);
     load_cols<64>(w2r, W2, H, cc, ks * q2, q2);
     const float b1v = tid < H ? p.w[p.ob1 + tid] : 0.f;
     const float b2v = tid < H ? p.w[p.ob2 + tid] : 0.f;
     const float b3v = tid < Ap ? p.w[p.ob3 + tid] : 0.f;
-    const unsigned long long n = p.n_append;
-    const unsigned int size = (unsigned int)(size0 + n > cap ? cap : size0 + n);
-    const unsigned int i0 = blockIdx.x * kRows;
-    const unsigned int nrows = min(kRows, p.B - i0);
 
     for (unsigned int e = tid; e < 8 * ldx; e += kRowThreads) Xs[e] = 0.f;
     if (tid < 16) meta[tid] = 0;
     lds_barrier();
 
-    // ---- sample and gather: one 32-bit word per thread.  A drawn slot that this step's append
-    // is about to overwrite is read from the payload arrays, which hold its new content.
-    const unsigned int words = 2 * D + 3;
-    for (unsigned int e = tid; e < nrows * words; e += kRowThreads) {
-        const unsigned int r = e / words, w = e - r * words;
-        const unsigned int i = i0 + r;
-        const unsigned int slot = uniform_draw(p.seed, step, i, size);
-        unsigned long long off = (unsigned long long)slot + cap - head;
-        if (off >= cap) off -= cap;
-        const unsigned int val =
-            off < n ? staged_word(p, off, w)
-                    : reinterpret_cast<const unsigned int*>(p.g.rows + (unsigned long long)slot * p.g.row_bytes)[w];
-        if (w < D) {
-            Xs[r * ldx + w] = __uint_as_float(val);
-            p.X[(size_t)i * Dp + w] = __uint_as_float(val);
-        } else if (w < 2 * D) {
-            Xs[(4 + r) * ldx + w - D] = __uint_as_float(val);
-        } else {
-            meta[r * 4 + (w - 2 * D)] = val;
-            if (w == 2 * D) {
-                p.act[i] = (int)val;
-                p.idx[i] = slot;
-            } else if (w == 2 * D + 1) {
-                p.rew[i] = __uint_as_float(val);
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const unsigned int e = tid + pass * kRowThreads;
+        if (e < nrows * words) {
+            const unsigned int r = e / words, w = e - r * words;
+            const unsigned int i = i0 + r;
+            const unsigned int val = gval[pass];
+            if (w < D) {
+                Xs[r * ldx + w] = __uint_as_float(val);
+                p.X[(size_t)i * Dp + w] = __uint_as_float(val);
+            } else if (w < 2 * D) {
+                Xs[(4 + r) * ldx + w - D] = __uint_as_float(val);
             } else {
-                p.term[i] = (unsigned char)val;
+                meta[r * 4 + (w - 2 * D)] = val;
+                if (w == 2 * D) {
+                    p.act[i] = (int)val;
+                    p.idx[i] = gslot[pass];
+                } else if (w == 2 * D + 1) {
+                    p.rew[i] = __uint_as_float(val);
+                } else {
+                    p.term[i] = (unsigned char)val;
+                }
             }
         }
     }
@@ -205,6 +253,8 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     // ---- layer 1
     f32x4 acc2[2];
     mma_cols<2, 16>(acc2, Xs, ldx, ks * q1, q1, w1r);
+    float w3r[16];   // layer 1's registers are free: request layer 3's weights
+    load_cols<16>(w3r, W3, Ap, lane, wave * s3, s3);
     store_part<2>(part, ks, kChunk, cc, acc2);
     lds_barrier();
     for (unsigned int e = tid; e < 8 * H; e += kRowThreads) {
@@ -217,10 +267,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     lds_barrier();
 
     // ---- layer 2; its registers are then refilled with W2^T (backward) and W3 is requested
-    mma_cols<2, 64>(acc2, H1s, ldh, ks * q2, q2, w2r);
-    float w3r[16];
-    load_cols<16>(w3r, W3, Ap, lane, wave * s3, s3);
-    load_cols<64>(w2r, p.w2t, H, cc, ks * q2, q2);
+    mma_cols_reload<2, 64>(acc2, H1s, ldh, ks * q2, q2, w2r, p.w2t, H, cc, ks * q2, q2);
     store_part<2>(part, ks, kChunk, cc, acc2);
     lds_barrier();
     for (unsigned int e = tid; e < 8 * H; e += kRowThreads) {
@@ -318,7 +365,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
         if (done == gridDim.x - 1) {
             unsigned long long h = head + n;
             if (h >= cap) h -= cap;
-            p.g.state->head = h;
+            p.g.state->head = h;            // the device copy of the ring state follows
             p.g.state->size = size;
             p.g.state->total += n;
             p.g.state->blocks_done = 0;
@@ -417,6 +464,11 @@ __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
     const float mb_old = do_bias && adam ? p.m[jb.b_off + nn] : 0.f;
     const float vb_old = do_bias && adam ? p.v[jb.b_off + nn] : 0.f;
 
+    // workgroup 0 also reduces the per-sample losses: fetch them now
+    float loss_part = 0.f;
+    if (blockIdx.x == 0 && tid < 64)
+        for (unsigned int i = tid; i < p.B; i += 64) loss_part += p.lossi[i];
+
     f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
     f32x4 accb = f32x4{0.f, 0.f, 0.f, 0.f};
     for (unsigned int b0 = 0; b0 < p.B; b0 += kTK) {
@@ -476,9 +528,7 @@ __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
         }
     if (do_bias) opt_apply(p, jb.b_off + nn, accb[0], wb_old, mb_old, vb_old, r1, r2);
     if (blockIdx.x == 0 && tid < 64) {
-        float s = 0.f;
-        for (unsigned int i = tid; i < p.B; i += 64) s += p.lossi[i];
-        s = wave_sum(s);
+        const float s = wave_sum(loss_part);
         if (tid == 0) {
             p.ctr->loss = s / (float)p.B;
             p.ctr->step += 1;
@@ -516,6 +566,13 @@ hipError_t enqueue_fused_step(trainer* t, const Payload& src, hipStream_t st, un
     a.seed = r->cfg.seed;
     a.n_append = t->cfg.appends_per_step;
     a.src = src;
+    {
+        // state before this step, from the host mirrors (train_step has not advanced them yet)
+        const unsigned long long cap = r->cfg.capacity, after = r->size + a.n_append;
+        a.head = r->head;
+        a.step = t->host_step;
+        a.size_after = (unsigned int)(after > cap ? cap : after);
+    }
     a.ctr = t->ctr;
     a.w = t->w;
     a.w2t = t->w2t;

@@ -401,7 +401,7 @@ hipError_t enqueue_append_and_step(trainer* t, const Payload& src, hipStream_t s
 // Find the payload-consuming kernel's node in the recorded graph.
 hipError_t find_payload_node(trainer* t) {
     t->payload_node = nullptr;
-    if (!t->cfg.appends_per_step) return hipSuccess;
+    if (!t->cfg.appends_per_step && !t->fused) return hipSuccess;
     size_t n = 0;
     hipError_t e = hipGraphGetNodes(t->graph, nullptr, &n);
     if (e != hipSuccess) return e;
@@ -628,7 +628,14 @@ rp_status train_step(trainer_t* t, const void* s, const void* s_next, const int3
             RP_CHECK_HIP(rp::launch_append(rpl->geom, n, src.s, src.s_next, src.a, src.r, src.term, st));
     } else if (t->graph_exec) {
         if (t->payload_node) {
-            if (t->fused) t->row_args.src = src; else t->append_args.src = src;
+            if (t->fused) {
+                t->row_args.src = src;
+                t->row_args.head = rpl->head;
+                t->row_args.step = t->host_step;
+                t->row_args.size_after = (unsigned int)size_after;
+            } else {
+                t->append_args.src = src;
+            }
             RP_CHECK_HIP(hipGraphExecKernelNodeSetParams(t->graph_exec, t->payload_node, &t->payload_np));
         }
         RP_CHECK_HIP(hipGraphLaunch(t->graph_exec, st));

@@ -58,6 +58,10 @@ struct RowArgs {
     unsigned long long seed;
     unsigned int n_append;
     Payload src;          // this step's new experiences
+    // ring and trainer state before this step, from the host mirror (set before every launch,
+    // so the kernel can start drawing without a dependent load)
+    unsigned long long head, step;
+    unsigned int size_after;     // experiences held once this step's append is in
     TrainCounters* ctr;
     const float* w;       // padded parameters
     const float* w2t;     // W2 transposed
