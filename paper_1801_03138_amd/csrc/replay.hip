@@ -26,6 +26,7 @@ namespace {
 
 constexpr unsigned int kThreads = 256;
 constexpr unsigned int kMaxPairRowBytes = 32768;  // a gathered PAIR row is staged through LDS
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 unsigned int elem_bytes_of(unsigned int dtype) { return dtype == RP_F32 ? 4 : dtype == RP_BF16 ? 2 : 1; }
 
@@ -211,7 +212,8 @@ __global__ __launch_bounds__(kThreads) void sample_gather_pair_kernel(
     const unsigned long long* __restrict__ step_ptr, unsigned int batch, unsigned int R,
     unsigned int lane_shift, void* __restrict__ out_s, void* __restrict__ out_s_next,
     unsigned int out_ld, int* __restrict__ out_a, float* __restrict__ out_r,
-    unsigned char* __restrict__ out_term, unsigned int* __restrict__ out_idx) {
+    unsigned char* __restrict__ out_term, unsigned int* __restrict__ out_idx,
+    void* __restrict__ out_s_t, unsigned int out_t_ld) {
     extern __shared__ uint4 smem[];
     unsigned int* idx_s = reinterpret_cast<unsigned int*>(smem);               // R <= 64 entries
     unsigned char* rows_s = reinterpret_cast<unsigned char*>(smem) + 256;
@@ -237,19 +239,20 @@ __global__ __launch_bounds__(kThreads) void sample_gather_pair_kernel(
         const unsigned int rsub = threadIdx.x >> lane_shift;
         for (unsigned int part = part0; part < V; part += lanes) {
             for (unsigned int row = rsub; row < nrows; row += 4 * rows_per_pass) {
-                uint4 val[4];
+                // (a native vector type: an array of HIP's uint4 struct would live in scratch memory)
+                u32x4 val[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    const unsigned int rr = row + u * rows_per_pass;
-                    if (rr < nrows)
-                        val[u] = reinterpret_cast<const uint4*>(
-                            g.rows + (unsigned long long)idx_s[rr] * g.row_bytes)[part];
+                    unsigned int rr = row + u * rows_per_pass;
+                    rr = rr < nrows ? rr : row;   // a row past the end re-reads `row`; not stored
+                    val[u] = reinterpret_cast<const u32x4*>(
+                        g.rows + (unsigned long long)idx_s[rr] * g.row_bytes)[part];
                 }
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const unsigned int rr = row + u * rows_per_pass;
                     if (rr < nrows)
-                        reinterpret_cast<uint4*>(rows_s + (size_t)rr * g.row_bytes)[part] = val[u];
+                        reinterpret_cast<u32x4*>(rows_s + (size_t)rr * g.row_bytes)[part] = val[u];
                 }
             }
         }
@@ -267,10 +270,12 @@ __global__ __launch_bounds__(kThreads) void sample_gather_pair_kernel(
                 const unsigned int* w = reinterpret_cast<const unsigned int*>(base);
                 if (out_s) static_cast<unsigned int*>(out_s)[o + col] = w[col];
                 if (out_s_next) static_cast<unsigned int*>(out_s_next)[o + col] = w[D + col];
+                if (out_s_t) static_cast<unsigned int*>(out_s_t)[(size_t)col * out_t_ld + i0 + row] = w[col];
             } else if (ELEM == 2) {
                 const unsigned short* h = reinterpret_cast<const unsigned short*>(base);
                 if (out_s) static_cast<unsigned short*>(out_s)[o + col] = h[col];
                 if (out_s_next) static_cast<unsigned short*>(out_s_next)[o + col] = h[D + col];
+                if (out_s_t) static_cast<unsigned short*>(out_s_t)[(size_t)col * out_t_ld + i0 + row] = h[col];
             } else {
                 if (out_s) static_cast<float*>(out_s)[o + col] = unit_from_u8(base[col]);
                 if (out_s_next) static_cast<float*>(out_s_next)[o + col] = unit_from_u8(base[D + col]);
@@ -444,7 +449,8 @@ hipError_t launch_sample_gather(const RingGeom& g, unsigned long long seed,
                                 const unsigned long long* step_ptr, unsigned int batch,
                                 void* out_s, void* out_s_next, unsigned int out_ld, int* out_a,
                                 float* out_r, unsigned char* out_term, unsigned int* out_idx,
-                                hipStream_t stream) {
+                                hipStream_t stream, void* out_s_t, unsigned int out_t_ld) {
+    if (out_s_t && (g.layout != RP_PAIR || g.elem_bytes == 1)) return hipErrorInvalidValue;
     if (g.layout == RP_PAIR) {
         // rows per block: 16 keeps eight blocks resident per CU and measured fastest at batch
         // 65,536 (4..64 tried); small batches take 4 so that more CUs take part
@@ -458,7 +464,7 @@ hipError_t launch_sample_gather(const RingGeom& g, unsigned long long seed,
 #define RP_LAUNCH_PAIR(E)                                                                         \
     hipLaunchKernelGGL(sample_gather_pair_kernel<E>, dim3(blocks), dim3(kThreads), lds, stream, g, \
                        seed, step_value, step_ptr, batch, R, lane_shift, out_s, out_s_next,        \
-                       out_ld, out_a, out_r, out_term, out_idx)
+                       out_ld, out_a, out_r, out_term, out_idx, out_s_t, out_t_ld)
         if (g.elem_bytes == 4)
             RP_LAUNCH_PAIR(4);
         else if (g.elem_bytes == 2)

@@ -4,6 +4,7 @@
 // Paper: Integration with Reinforcement Learning Algorithm (the step takes no inputs from
 // the host; Q(s,a) is entry i*A + a_i of the flattened network output) and Deep Q-Network
 // Model (the update equation).
+#include <algorithm>
 #include <cmath>
 #include <vector>
 
@@ -226,7 +227,9 @@ namespace {
 struct WsLayout {
     size_t ctr, w, g, m, v, w2t, wb, X, act, rew, term, idx, H1, H2, Q, y, delta, lossi, dQ, dZ2, dZ1,
         total;
-    unsigned int Dp, Ap;
+    // mixed-precision step on MFMA
+    size_t W1T, W2b, W2T, W3T, XT, H1T, H2T, dQTh, dQTl, dZ2T, dZ1T, part3, part1;
+    unsigned int Dp, Ap, Bp;
     size_t n_params, n_padded, elem;
     size_t oW1, ob1, oW2, ob2, oW3, ob3;
 };
@@ -276,6 +279,23 @@ bool ws_layout(const train_config* c, WsLayout* L) {
     L->dQ = take(B * L->Ap * 4);
     L->dZ2 = take(B * H * L->elem);
     L->dZ1 = take(B * H * L->elem);
+    const bool mixed = c->param_dtype == RP_BF16;
+    const size_t Bp = align_up(B, 128), Dx = align_up(D + 1, 32);
+    L->Bp = (unsigned int)Bp;
+    L->W1T = take(mixed ? H * L->Dp * 2 : 0);
+    L->W2b = take(mixed ? H * H * 2 : 0);
+    L->W2T = take(mixed ? H * H * 2 : 0);
+    L->W3T = take(mixed ? L->Ap * H * 2 : 0);
+    L->XT = take(mixed ? Dx * Bp * 2 : 0);
+    L->H1T = take(mixed ? (H + 1) * Bp * 2 : 0);
+    L->H2T = take(mixed ? (H + 1) * Bp * 2 : 0);
+    L->dQTh = take(mixed ? 2 * L->Ap * Bp * 2 : 0);   // high part, then low part
+    L->dQTl = L->dQTh + L->Ap * Bp * 2;
+    L->dZ2T = take(mixed ? H * Bp * 2 : 0);
+    L->dZ1T = take(mixed ? H * Bp * 2 : 0);
+    // K-split partial products of the narrow layers' gradients (at most 16 splits)
+    L->part3 = take(mixed ? 16 * (H + 1) * 2 * L->Ap * 4 : 0);
+    L->part1 = take(mixed ? 16 * H * Dx * 4 : 0);
     L->total = o;
     return true;
 }
@@ -392,8 +412,9 @@ hipError_t enqueue_append_and_step(trainer* t, const Payload& src, hipStream_t s
         if (e != hipSuccess) return e;
         ++n;
     }
-    hipError_t e = t->cfg.param_dtype == RP_BF16 ? enqueue_step<bf16_t>(t, st, &k)
-                                                 : enqueue_step<float>(t, st, &k);
+    hipError_t e = t->wide ? enqueue_wide_step(t, st, &k)
+                   : t->cfg.param_dtype == RP_BF16 ? enqueue_step<bf16_t>(t, st, &k)
+                                                   : enqueue_step<float>(t, st, &k);
     if (count) *count = n + k;
     return e;
 }
@@ -470,7 +491,7 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
     }
     t->cfg = *cfg;
     t->rp_ = rp_;
-    t->Dp = L.Dp; t->Ap = L.Ap; t->H = cfg->hidden; t->B = cfg->batch;
+    t->Dp = L.Dp; t->Ap = L.Ap; t->H = cfg->hidden; t->B = cfg->batch; t->Bp = L.Bp;
     t->n_params = L.n_params; t->n_padded = L.n_padded; t->elem = L.elem;
     t->oW1 = L.oW1; t->ob1 = L.ob1; t->oW2 = L.oW2; t->ob2 = L.ob2; t->oW3 = L.oW3; t->ob3 = L.ob3;
     unsigned char* ws = static_cast<unsigned char*>(dev_workspace);
@@ -482,6 +503,14 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
     t->v = reinterpret_cast<float*>(ws + L.v);
     t->w2t = cfg->param_dtype == RP_F32 ? reinterpret_cast<float*>(ws + L.w2t) : nullptr;
     t->fused = !(cfg->flags & RP_TRAIN_LAYERED) && rp::fused_step_supported(*cfg, rp_);
+    t->wide = !(cfg->flags & RP_TRAIN_LAYERED) && rp::wide_step_supported(*cfg, rp_);
+    {
+        auto at = [&](size_t off) { return reinterpret_cast<unsigned short*>(ws + off); };
+        t->wd = rp::WideBuffers{at(L.W1T), at(L.W2b), at(L.W2T), at(L.W3T), at(L.XT), at(L.H1T),
+                                at(L.H2T), at(L.dQTh), at(L.dQTl), at(L.dZ2T), at(L.dZ1T),
+                                reinterpret_cast<float*>(ws + L.part3),
+                                reinterpret_cast<float*>(ws + L.part1)};
+    }
     t->wb = cfg->param_dtype == RP_BF16 ? reinterpret_cast<bf16_t*>(ws + L.wb) : nullptr;
     t->X = ws + L.X;
     t->act = reinterpret_cast<int*>(ws + L.act);
@@ -511,6 +540,13 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
     if (e != hipSuccess) {
         rp::set_error("train_create: clearing the workspace failed: %s", hipGetErrorString(e));
         return fail(RP_EHIP);
+    }
+    if (t->wide) {
+        e = rp::wide_init_buffers(t);
+        if (e != hipSuccess) {
+            rp::set_error("train_create: preparing the transposed buffers failed: %s", hipGetErrorString(e));
+            return fail(RP_EHIP);
+        }
     }
     rp_status s = train_set_state(t, host_init_params, nullptr, nullptr, 0, 0);
     if (s != RP_OK) return fail(s);
@@ -570,7 +606,8 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
         }
     } else {
         // the launch count is static
-        t->kernels_per_step = t->fused ? 2u : (cfg->appends_per_step ? 1u : 0u) + 14u;
+        t->kernels_per_step =
+            t->fused ? 2u : (cfg->appends_per_step ? 1u : 0u) + (t->wide ? 10u : 14u);
     }
     *out = t;
     return RP_OK;
@@ -726,6 +763,7 @@ rp_status train_set_state(trainer_t* t, const float* params, const float* m, con
     RP_CHECK_HIP(hipDeviceSynchronize());
     rp::pad_params(t, params, pad);
     RP_CHECK_HIP(hipMemcpy(t->w, pad.data(), t->n_padded * 4, hipMemcpyHostToDevice));
+    if (t->wide) RP_CHECK_HIP(rp::wide_set_weights(t, pad.data()));
     if (t->w2t) {
         const size_t H = t->H;
         std::vector<float> tr(H * H);

@@ -76,6 +76,18 @@ struct RowArgs {
     unsigned int* idx;
 };
 
+// Buffers of the mixed-precision step on MFMA (bf16 bit patterns).  "T" = transposed: the
+// batch index is the contiguous one, rows are padded to Bp (a multiple of 128) with zeros.
+struct WideBuffers {
+    unsigned short *W1T, *W2, *W2T, *W3T;   // [H x Dp], [H x H], [H x H] transposed, [Ap x H]
+    unsigned short* XT;                      // [>= D+1 x Bp], row D all ones
+    unsigned short *H1T, *H2T;               // [H+1 x Bp], row H all ones
+    unsigned short *dQT_hi, *dQT_lo;         // [Ap x Bp] each, dQT_lo right after dQT_hi
+    unsigned short *dZ2T, *dZ1T;             // [H x Bp]
+    float* part3;                            // K-split partials [splits][H+1][2 Ap] of [dW3 ; db3]
+    float* part1;                            // K-split partials [splits][H][Dx] of [dW1^T | db1]
+};
+
 constexpr unsigned int kPinSlots = 64;       // pinned host slots for host-sourced payloads
 constexpr unsigned int kPinGroup = 16;       // slots per completion event
 
@@ -84,7 +96,7 @@ constexpr unsigned int kPinGroup = 16;       // slots per completion event
 struct trainer {
     train_config cfg;
     replay* rp_;
-    unsigned int Dp, Ap, H, B;
+    unsigned int Dp, Ap, H, B, Bp;
     size_t n_params, n_padded;       // external / padded parameter counts
     size_t oW1, ob1, oW2, ob2, oW3, ob3;
     size_t elem;                     // bytes of an activation element
@@ -103,6 +115,8 @@ struct trainer {
     float *y, *delta, *lossi, *dQ;   // [B], [B], [B], [B x Ap]
     void *dZ2, *dZ1;                 // [B x H]
     bool fused;                      // two-kernel step for small fp32 networks
+    bool wide;                       // mixed-precision step on MFMA
+    rp::WideBuffers wd;
     hipGraph_t graph;
     hipGraphExec_t graph_exec;
     hipStream_t capture_stream;
@@ -135,4 +149,9 @@ bool fused_step_supported(const train_config& cfg, const replay* rp_);
 // gradients + optimizer).  *count receives the number of kernels launched.
 hipError_t enqueue_fused_step(trainer* t, const Payload& src, hipStream_t st, unsigned int* count);
 void* fused_rows_func();
+// Mixed-precision step on MFMA (bf16 replay states and matrix operands).
+bool wide_step_supported(const train_config& cfg, const replay* rp_);
+hipError_t wide_init_buffers(trainer* t);                       // once, after the workspace is cleared
+hipError_t wide_set_weights(trainer* t, const float* padded);   // bf16 operand copies from fp32 (host)
+hipError_t enqueue_wide_step(trainer* t, hipStream_t st, unsigned int* count);  // after the append
 }  // namespace rp

@@ -1,0 +1,829 @@
+// Mixed-precision train step for wide networks, where the step is bound by the dense products:
+// bf16 operands, fp32 accumulation on 32x32x16 MFMA, fp32 master weights and Adam moments.
+//
+// Every product is brought to one form, C[m][n] = sum_k A[m][k] * Bt[n][k] with both operands
+// stored K-contiguous, which is the form the MFMA lane layout reads with 16-byte loads.  The
+// forward layers therefore read transposed bf16 copies of the weights, and the weight
+// gradients, which contract over the batch, read transposed copies of the activations and of
+// the pre-activation gradients; the kernels that produce those tensors write both orientations.
+// A bias gradient is the product of the error with a vector of ones: the transposed activation
+// buffers carry one extra row of ones, so the bias gradient falls out of the weight-gradient
+// product as one more output row, and the optimizer runs in the epilogue of that product.
+//
+// Paper: Integration with Reinforcement Learning Algorithm (train step with no host inputs),
+// Deep Q-Network Model (update equation).
+#include <vector>
+
+#include "replay_kernels.hpp"
+#include "trainer.hpp"
+
+namespace rp {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned short bf16_bits;
+// 16 bytes in flight between a load and its use.  A native vector type: arrays of HIP's uint4
+// struct are not promoted to registers by the compiler and end up in scratch memory.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr unsigned int kGemmThreads = 256;
+
+__device__ __forceinline__ float bits_to_float(bf16_bits b) {
+    return __uint_as_float((unsigned int)b << 16);
+}
+
+__device__ __forceinline__ bf16x8 as_bf16x8(const u32x4& v) {
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+// Row (0..31 within the 32x32 tile) of accumulator element v held by `lane`; its column is lane % 32.
+__device__ __forceinline__ unsigned int acc_row(unsigned int v, unsigned int lane) {
+    return 8u * (v >> 2) + 4u * (lane >> 5) + (v & 3u);
+}
+
+// ----------------------------------------------------------------------------------------
+// Optimizer applied to one parameter from inside a product's epilogue.
+// ----------------------------------------------------------------------------------------
+struct OptState {
+    float *w, *g, *m, *v;
+    unsigned int opt;
+    float lr, beta1, beta2, eps;
+    const TrainCounters* ctr;
+};
+
+// c1, c2: Adam's bias corrections 1 - beta^t of this step
+__device__ __forceinline__ float opt_update(const OptState& o, size_t k, float gk, float c1,
+                                            float c2) {
+    float wk = o.w[k];
+    o.g[k] = gk;
+    if (o.opt == RP_SGD) {
+        wk -= o.lr * gk;
+    } else {
+        const float mk = o.beta1 * o.m[k] + (1.f - o.beta1) * gk;
+        const float vk = o.beta2 * o.v[k] + (1.f - o.beta2) * gk * gk;
+        o.m[k] = mk;
+        o.v[k] = vk;
+        wk -= o.lr * (mk / c1) / (sqrtf(vk / c2) + o.eps);
+    }
+    o.w[k] = wk;
+    return wk;
+}
+
+// ----------------------------------------------------------------------------------------
+// Epilogues of the tiled product.
+// "Staged" epilogues (bf16 output in the product's own orientation): the product is formed with
+// the MFMA operands exchanged, so a lane holds four consecutive columns of one output row; it
+// passes each value through pre(), rounds to bf16 and parks the wavefront's tile in LDS, from
+// where it leaves in 16-byte pieces -- eight lanes write one 128-byte run of a row -- through
+// store().  Other epilogues get the raw 32x32 accumulator tiles.
+// ----------------------------------------------------------------------------------------
+// out[m][n] = bf16(relu(acc + bias[n]))
+struct EpiForward {
+    static constexpr bool kStaged = true;
+    const float* bias;
+    bf16_bits* out;
+    unsigned int ldo;
+    unsigned int M, N;
+    __device__ __forceinline__ float pre(unsigned int n, float x) const {
+        x += bias[n < N ? n : 0u];
+        return x > 0.f ? x : 0.f;
+    }
+    // eight consecutive columns n..n+7 of row m (N is a multiple of 8)
+    __device__ __forceinline__ void store(unsigned int m, unsigned int n, const u32x4& v) const {
+        if (m < M && n < N) *reinterpret_cast<u32x4*>(out + (size_t)m * ldo + n) = v;
+    }
+};
+
+// out[m][n] = bf16(acc) where mask[m][n] > 0, else 0  (the ReLU derivative; both [M x ld]).
+// Columns from N up to the next multiple of 8 are written as zeros.
+struct EpiMask {
+    static constexpr bool kStaged = true;
+    const bf16_bits* mask;
+    bf16_bits* out;
+    unsigned int ld;
+    unsigned int M, N;
+    __device__ __forceinline__ float pre(unsigned int, float x) const { return x; }
+    __device__ __forceinline__ void store(unsigned int m, unsigned int n, const u32x4& v) const {
+        if (m >= M || n >= N) return;
+        const size_t at = (size_t)m * ld + n;
+        const u32x4 k = *reinterpret_cast<const u32x4*>(mask + at);
+        u32x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            // a bf16 is positive when it is non-zero with the sign bit clear (NaN counts as not)
+            const unsigned int lo = k[e] & 0xFFFFu, hi = k[e] >> 16;
+            const bool lo_on = lo != 0u && lo <= 0x7F80u && n + 2u * e < N;
+            const bool hi_on = hi != 0u && hi <= 0x7F80u && n + 2u * e + 1u < N;
+            o[e] = (lo_on ? v[e] & 0xFFFFu : 0u) | (hi_on ? v[e] & 0xFFFF0000u : 0u);
+        }
+        *reinterpret_cast<u32x4*>(out + at) = o;
+    }
+};
+
+// acc is the gradient of W[m][n] (rows below R) or of bias[n] (row R): optimizer step, then the
+// bf16 copies of the new weight in both orientations.
+struct EpiOptSquare {
+    static constexpr bool kStaged = false;
+    OptState o;
+    unsigned int R, N;          // weight matrix [R x N], row-major at w_off; bias [N] at b_off
+    size_t w_off, b_off;
+    bf16_bits* wb;              // [R x N]
+    bf16_bits* wbT;             // [N x R]
+    __device__ __forceinline__ void tile(unsigned int mb, unsigned int nb, const f32x16& c,
+                                         unsigned int lane, unsigned int) const {
+        const unsigned int n = nb + (lane & 31u);
+        if (n >= N) return;
+        const float c1 = o.ctr->c1, c2 = o.ctr->c2;
+#pragma unroll
+        for (unsigned int v = 0; v < 16; ++v) {
+            const unsigned int m = mb + acc_row(v, lane);
+            if (m < R) {
+                const float wk = opt_update(o, w_off + (size_t)m * N + n, c[v], c1, c2);
+                const bf16_bits h = bf16_bits_rne(wk);
+                wb[(size_t)m * N + n] = h;
+                wbT[(size_t)n * R + m] = h;
+            } else if (m == R) {
+                opt_update(o, b_off + n, c[v], c1, c2);
+            }
+        }
+    }
+};
+
+// part[split][m][n] = acc: the partial product of one K split, added up by a later kernel
+struct EpiPartial {
+    static constexpr bool kStaged = false;
+    float* part;
+    unsigned int M, N;
+    __device__ __forceinline__ void tile(unsigned int mb, unsigned int nb, const f32x16& c,
+                                         unsigned int lane, unsigned int split) const {
+        const unsigned int n = nb + (lane & 31u);
+        if (n >= N) return;
+#pragma unroll
+        for (unsigned int v = 0; v < 16; ++v) {
+            const unsigned int m = mb + acc_row(v, lane);
+            if (m < M) part[((size_t)split * M + m) * N + n] = c[v];
+        }
+    }
+};
+
+// ----------------------------------------------------------------------------------------
+// Tiled product C = A Bt^T: a workgroup of four wavefronts owns a BM x BN tile, streams BK-wide
+// slices of both operands through LDS (two stages; the next slice is fetched into registers
+// while the current one is multiplied) and keeps the accumulators in registers.  The
+// wavefronts split the tile WGM x WGN ways and the slice WGK ways; with WGK > 1 the partial
+// accumulators are added through LDS before the epilogue.  LDS rows are padded by 16 bytes,
+// which spreads the 16-byte operand reads of 8 consecutive rows over all banks.
+// The contraction may also be split over `splits` workgroups per tile, each taking K / splits
+// consecutive columns and handing its split number to the epilogue.
+// K / splits must be a multiple of BK.  Loads of rows beyond M / N are redirected to the last valid row:
+// such rows only feed accumulator rows / columns that the epilogue never stores.
+// ----------------------------------------------------------------------------------------
+struct GemmArgs {
+    const bf16_bits* A;
+    unsigned int lda;
+    const bf16_bits* Bt;
+    unsigned int ldb;
+    unsigned int M, N, K;          // K: columns one workgroup contracts over
+    unsigned int tiles_m, tiles_n, splits;
+};
+
+template <int BM, int BN, int BK, int WGK>
+constexpr size_t gemm_lds_bytes() {
+    const size_t stage = (size_t)(BM + BN) * (BK * 2 + 16);
+    const size_t red = WGK > 1 ? 4 * 4 * 16 * 64 * sizeof(float) : 0;  // 4 waves x 4 tiles
+    return 2 * stage > red ? 2 * stage : red;
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN, int WGK, class Epi>
+__global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(GemmArgs p, Epi epi) {
+    static_assert(WGM * WGN * WGK == 4, "four wavefronts");
+    constexpr int STRIDE = BK * 2 + 16;                    // bytes per LDS row
+    constexpr int A_BYTES = BM * STRIDE, STAGE = (BM + BN) * STRIDE;
+    constexpr int CPR = BK / 8;                            // 16-byte pieces per row of a slice
+    constexpr int RPP = kGemmThreads / CPR;                // rows one pass of the workgroup covers
+    constexpr int PA = BM / RPP, PB = BN / RPP;
+    static_assert(PA >= 1 && PB >= 1 && BM % RPP == 0 && BN % RPP == 0, "loader shape");
+    constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;  // 32x32 tiles per wavefront
+    constexpr int KSW = BK / 16 / WGK;                     // 16-deep MFMA steps per wavefront and slice
+    static_assert(TM >= 1 && TN >= 1 && KSW >= 1, "wavefront shape");
+    static_assert(WGK == 1 || (WGM == 1 && WGN == 1 && TM * TN == 4), "K split reduces 4 tiles");
+
+    extern __shared__ uint4 gemm_smem[];
+    unsigned char* smem = reinterpret_cast<unsigned char*>(gemm_smem);
+
+    // Workgroups are dealt to the eight XCDs round-robin; each XCD gets a contiguous range of
+    // tiles (N fastest), so the workgroups that share an L2 also share operand panels.
+    const unsigned int per_split = p.tiles_m * p.tiles_n, n_tiles = per_split * p.splits;
+    const unsigned int per_xcd = (n_tiles + 7u) / 8u;
+    const unsigned int tile_s = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+    if (tile_s >= n_tiles) return;
+    const unsigned int split = tile_s / per_split, tile = tile_s % per_split;
+    const unsigned int m0 = (tile / p.tiles_n) * BM, n0 = (tile % p.tiles_n) * BN;
+    const unsigned int k_base = split * p.K;
+
+    const unsigned int tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const unsigned int wk = wave % WGK, wn = (wave / WGK) % WGN, wm = wave / (WGK * WGN);
+    const unsigned int lrow = tid / CPR, lpiece = tid % CPR;
+
+    const bf16_bits* a_ptr[PA];
+    const bf16_bits* b_ptr[PB];
+#pragma unroll
+    for (int u = 0; u < PA; ++u) {
+        unsigned int gm = m0 + lrow + u * RPP;
+        gm = gm < p.M ? gm : p.M - 1;
+        a_ptr[u] = p.A + (size_t)gm * p.lda + k_base + lpiece * 8u;
+    }
+#pragma unroll
+    for (int u = 0; u < PB; ++u) {
+        unsigned int gn = n0 + lrow + u * RPP;
+        gn = gn < p.N ? gn : p.N - 1;
+        b_ptr[u] = p.Bt + (size_t)gn * p.ldb + k_base + lpiece * 8u;
+    }
+    u32x4 ra[PA], rb[PB];
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const unsigned int a_row = (wm * TM * 32u + (lane & 31u)) * STRIDE + (lane >> 5) * 16u;
+    const unsigned int b_row = (wn * TN * 32u + (lane & 31u)) * STRIDE + (lane >> 5) * 16u;
+    auto multiply = [&](unsigned int buf) {
+        const unsigned char* as = smem + buf * STAGE + a_row;
+        const unsigned char* bs = smem + buf * STAGE + A_BYTES + b_row;
+#pragma unroll
+        for (int s = 0; s < KSW; ++s) {
+            const unsigned int ko = (wk * KSW + s) * 32u;   // byte offset of this 16-deep step
+            bf16x8 a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                a[i] = as_bf16x8(*reinterpret_cast<const u32x4*>(as + i * 32 * STRIDE + ko));
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                b[j] = as_bf16x8(*reinterpret_cast<const u32x4*>(bs + j * 32 * STRIDE + ko));
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = Epi::kStaged
+                                    ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0)
+                                    : __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+    };
+
+    // The loop is written without branches between a slice's loads and its LDS stores, so
+    // that the loads stay in flight across the multiply.
+    const unsigned int nk = p.K / BK;
+    unsigned char* const st_a = smem + lrow * STRIDE + lpiece * 16u;
+    unsigned char* const st_b = st_a + A_BYTES;
+#pragma unroll
+    for (int u = 0; u < PA; ++u) ra[u] = *reinterpret_cast<const u32x4*>(a_ptr[u]);
+#pragma unroll
+    for (int u = 0; u < PB; ++u) rb[u] = *reinterpret_cast<const u32x4*>(b_ptr[u]);
+#pragma unroll
+    for (int u = 0; u < PA; ++u) *reinterpret_cast<u32x4*>(st_a + u * RPP * STRIDE) = ra[u];
+#pragma unroll
+    for (int u = 0; u < PB; ++u) *reinterpret_cast<u32x4*>(st_b + u * RPP * STRIDE) = rb[u];
+    __syncthreads();
+    for (unsigned int kt = 0; kt + 1 < nk; ++kt) {
+        const unsigned int k1 = (kt + 1) * BK;
+#pragma unroll
+        for (int u = 0; u < PA; ++u) ra[u] = *reinterpret_cast<const u32x4*>(a_ptr[u] + k1);
+#pragma unroll
+        for (int u = 0; u < PB; ++u) rb[u] = *reinterpret_cast<const u32x4*>(b_ptr[u] + k1);
+        multiply(kt & 1u);
+        const unsigned int nb = ((kt + 1) & 1u) * STAGE;
+#pragma unroll
+        for (int u = 0; u < PA; ++u) *reinterpret_cast<u32x4*>(st_a + nb + u * RPP * STRIDE) = ra[u];
+#pragma unroll
+        for (int u = 0; u < PB; ++u) *reinterpret_cast<u32x4*>(st_b + nb + u * RPP * STRIDE) = rb[u];
+        __syncthreads();
+    }
+    multiply((nk - 1) & 1u);
+
+    if constexpr (Epi::kStaged) {
+        static_assert(WGK == 1, "staged epilogues take whole accumulators");
+        // The accumulator of tile (i, j) is transposed: element v of a lane is output row
+        // lane % 32, column acc_row(v, lane).  Park the wavefront's (TM*32) x (TN*32) tile as
+        // bf16 in its own LDS region (the operand slices are no longer needed).
+        constexpr int TSTRIDE = TN * 64 + 16;                // bytes per parked row
+        constexpr int CR = TN * 4;                           // 16-byte pieces per row
+        constexpr int RP = 64 / CR;                          // rows per pass of the wavefront
+        static_assert(4 * TM * 32 * TSTRIDE <= 2 * STAGE, "parked tiles fit in the slice buffers");
+        __syncthreads();
+        unsigned char* park = smem + wave * (TM * 32 * TSTRIDE);
+        const unsigned int wm0 = m0 + wm * TM * 32u, wn0 = n0 + wn * TN * 32u;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (unsigned int grp = 0; grp < 4; ++grp) {
+                    const unsigned int nl = j * 32u + 8u * grp + 4u * (lane >> 5);
+                    bf16_bits h[4];
+#pragma unroll
+                    for (unsigned int e = 0; e < 4; ++e)
+                        h[e] = bf16_bits_rne(epi.pre(wn0 + nl + e, acc[i][j][4 * grp + e]));
+                    uint2 pk;
+                    pk.x = (unsigned int)h[0] | ((unsigned int)h[1] << 16);
+                    pk.y = (unsigned int)h[2] | ((unsigned int)h[3] << 16);
+                    *reinterpret_cast<uint2*>(park + (i * 32u + (lane & 31u)) * TSTRIDE + nl * 2u) = pk;
+                }
+        // same wavefront reads what it wrote: LDS operations of a wavefront complete in order
+#pragma unroll
+        for (int pass = 0; pass < TM * 32 / RP; ++pass) {
+            const unsigned int row = pass * RP + lane / CR, piece = lane % CR;
+            const u32x4 v = *reinterpret_cast<const u32x4*>(park + row * TSTRIDE + piece * 16u);
+            epi.store(wm0 + row, wn0 + piece * 8u, v);
+        }
+    } else if constexpr (WGK == 1) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                epi.tile(m0 + (wm * TM + i) * 32u, n0 + (wn * TN + j) * 32u, acc[i][j], lane, split);
+    } else {
+        // every wavefront holds a partial sum of all four tiles; wavefront w finishes tile w
+        __syncthreads();                                   // the slices in LDS are no longer needed
+        float* red = reinterpret_cast<float*>(smem);       // [wave][tile][v][lane]
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    red[((wave * 4u + (i * TN + j)) * 16u + v) * 64u + lane] = acc[i][j][v];
+        __syncthreads();
+        f32x16 sum;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            float s = 0.f;
+#pragma unroll
+            for (unsigned int src = 0; src < 4; ++src) s += red[((src * 4u + wave) * 16u + v) * 64u + lane];
+            sum[v] = s;
+        }
+        epi.tile(m0 + (wave / TN) * 32u, n0 + (wave % TN) * 32u, sum, lane, split);
+    }
+}
+
+// Workgroups of these kernels use more than 64 KB of dynamic LDS, which has to be allowed per
+// kernel before the first launch (done at trainer creation, outside any stream capture).
+template <int BM, int BN, int BK, int WGM, int WGN, int WGK, class Epi>
+hipError_t configure_gemm() {
+    auto kernel = gemm_nt_kernel<BM, BN, BK, WGM, WGN, WGK, Epi>;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize,
+                               (int)gemm_lds_bytes<BM, BN, BK, WGK>());
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN, int WGK, class Epi>
+hipError_t launch_gemm(hipStream_t st, const bf16_bits* A, unsigned int lda, const bf16_bits* Bt,
+                       unsigned int ldb, unsigned int M, unsigned int N, unsigned int K,
+                       const Epi& epi, unsigned int splits = 1) {
+    if (K == 0 || splits == 0 || K % (splits * BK) != 0 || lda % 8 != 0 || ldb % 8 != 0)
+        return hipErrorInvalidValue;
+    GemmArgs a;
+    a.A = A; a.lda = lda; a.Bt = Bt; a.ldb = ldb; a.M = M; a.N = N; a.K = K / splits;
+    a.tiles_m = (M + BM - 1) / BM;
+    a.tiles_n = (N + BN - 1) / BN;
+    a.splits = splits;
+    const unsigned int n_tiles = a.tiles_m * a.tiles_n * splits;
+    const unsigned int blocks = 8u * ((n_tiles + 7u) / 8u);
+    constexpr size_t lds = gemm_lds_bytes<BM, BN, BK, WGK>();
+    hipLaunchKernelGGL((gemm_nt_kernel<BM, BN, BK, WGM, WGN, WGK, Epi>), dim3(blocks),
+                       dim3(kGemmThreads), lds, st, a, epi);
+    return hipGetLastError();
+}
+
+// ----------------------------------------------------------------------------------------
+// Skinny product for the output layer, Q = H2 W3 + b3 (a few 32-wide column tiles, many rows):
+// one 32x32 output tile per workgroup; the wavefronts split K, each loading its MFMA operands
+// straight from global memory (eight 16-deep steps requested before the first multiply), and
+// add their accumulators through LDS.  K is a multiple of 16.  Rows beyond M / N read row 0
+// instead: they only reach accumulator elements that are not stored.
+// ----------------------------------------------------------------------------------------
+struct SkinnyArgs {
+    const bf16_bits* A;
+    unsigned int lda;
+    const bf16_bits* Bt;
+    unsigned int ldb;
+    unsigned int M, N, K;
+    const float* bias;   // [N]
+    float* out;          // [M x ldo], fp32
+    unsigned int ldo;
+};
+
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void skinny_nt_kernel(SkinnyArgs p) {
+    __shared__ float red[NW * 16 * 64];
+    const unsigned int tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const unsigned int m0 = blockIdx.x * 32u, n0 = blockIdx.y * 32u;
+    const unsigned int am = m0 + (lane & 31u), bn = n0 + (lane & 31u);
+    const bf16_bits* ap = p.A + (size_t)(am < p.M ? am : 0u) * p.lda + 8u * (lane >> 5);
+    const bf16_bits* bp = p.Bt + (size_t)(bn < p.N ? bn : 0u) * p.ldb + 8u * (lane >> 5);
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    f32x16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    for (unsigned int kc = wave * 128u; kc < p.K; kc += NW * 128u) {
+        u32x4 a[8], b[8];
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            const unsigned int k = kc + s * 16u;
+            const bool in = k < p.K;
+            a[s] = in ? *reinterpret_cast<const u32x4*>(ap + k) : zero4;
+            b[s] = in ? *reinterpret_cast<const u32x4*>(bp + k) : zero4;
+        }
+#pragma unroll
+        for (int s = 0; s < 8; ++s)
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a[s]), as_bf16x8(b[s]), acc, 0, 0, 0);
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) red[(wave * 16u + v) * 64u + lane] = acc[v];
+    __syncthreads();
+    for (unsigned int e = tid; e < 1024u; e += 64u * NW) {
+        const unsigned int v = e >> 6, l = e & 63u;
+        float s = 0.f;
+#pragma unroll
+        for (unsigned int w = 0; w < (unsigned int)NW; ++w) s += red[(w * 16u + v) * 64u + l];
+        const unsigned int m = m0 + acc_row(v, l), n = n0 + (l & 31u);
+        if (m < p.M && n < p.N) p.out[(size_t)m * p.ldo + n] = s + p.bias[n];
+    }
+}
+
+// ----------------------------------------------------------------------------------------
+// TD target, loss and the gradient at the second hidden layer's pre-activation.
+// A workgroup owns 64 batch rows x 64 hidden units.  It first repeats, for its 64 rows, the
+// per-row part: y_i = r_i + gamma (1 - term_i) max_a Q(s'_i, a), delta_i = y_i - Q(s_i, a_i),
+// the loss term and g_i = dL/dQ(s_i, a_i)  (four lanes per row share the max).  Workgroups of
+// the first hidden-unit stripe store those and dL/dQ transposed, split into a bf16 high and
+// low part so that the output-layer weight gradient keeps fp32 accuracy.  Then
+//   dZ2[i][k] = g_i * W3[k][a_i] * 1[H2[i][k] > 0]
+// goes out in both orientations (the transposed one through an LDS tile), and so do the
+// transposed copies of this tile of H1 and H2 that the weight-gradient products read.
+// ----------------------------------------------------------------------------------------
+struct TdArgs {
+    unsigned int B, Bp, H, A, Ap;
+    const float* Q;              // [2B x Ap]
+    const int* act;
+    const float* rew;
+    const unsigned char* term;
+    float gamma;
+    unsigned int loss_kind;
+    float beta1, beta2;
+    float *y, *delta, *lossi;
+    bf16_bits *dQT_hi, *dQT_lo;  // [Ap x Bp]
+    const bf16_bits* W3T;        // [Ap x H]
+    const bf16_bits* H1;         // [2B x H]
+    const bf16_bits* H2;         // [2B x H]
+    bf16_bits* dZ2;              // [B x H]
+    bf16_bits* dZ2T;             // [H x Bp]
+    bf16_bits *H1T, *H2T;        // [H+1 x Bp]: transposed copies of the first B rows of H1, H2
+    TrainCounters* ctr;
+};
+
+__global__ __launch_bounds__(256) void td_dz_kernel(TdArgs p) {
+    __shared__ float gs[64];
+    __shared__ unsigned int as_[64];
+    // [k][row] tiles, padded: dZ2, H2 and H1 on their way to the transposed buffers
+    __shared__ __attribute__((aligned(16))) bf16_bits tileT[3][64][72];
+    const unsigned int tid = threadIdx.x;
+    const unsigned int i0 = blockIdx.x * 64u, k0 = blockIdx.y * 64u;
+    if (blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) {
+        const unsigned long long t = p.ctr->adam_t + 1;
+        p.ctr->adam_t = t;
+        p.ctr->c1 = (float)(1.0 - pow((double)p.beta1, (double)t));
+        p.ctr->c2 = (float)(1.0 - pow((double)p.beta2, (double)t));
+    }
+    {
+        const unsigned int r = tid >> 2, part = tid & 3u, i = i0 + r;
+        const bool live = i < p.B;
+        float best = -INFINITY;
+        if (live) {
+            const float* qn = p.Q + (size_t)(p.B + i) * p.Ap;
+            for (unsigned int a = part; a < p.A; a += 4) best = fmaxf(best, qn[a]);
+        }
+        best = fmaxf(best, __shfl_xor(best, 1, 64));
+        best = fmaxf(best, __shfl_xor(best, 2, 64));
+        if (part == 0) {
+            float g = 0.f;
+            unsigned int ai = 0;
+            if (live) {
+                ai = (unsigned int)p.act[i];
+                if (ai >= p.A) ai = p.A - 1;  // an out-of-range action must not turn into a wild address
+                const float q = p.Q[(size_t)i * p.Ap + ai];
+                const float y = p.rew[i] + (p.term[i] ? 0.f : p.gamma * best);
+                const float d = y - q;
+                float li, slope;
+                if (p.loss_kind == RP_MSE || fabsf(d) <= 1.f) {
+                    li = 0.5f * d * d;
+                    slope = d;
+                } else {
+                    li = fabsf(d) - 0.5f;
+                    slope = d > 0.f ? 1.f : -1.f;
+                }
+                g = -slope / (float)p.B;
+                if (blockIdx.y == 0) {
+                    p.y[i] = y;
+                    p.delta[i] = d;
+                    p.lossi[i] = li;
+                }
+            }
+            gs[r] = g;
+            as_[r] = ai;
+        }
+    }
+    __syncthreads();
+    if (blockIdx.y == 0) {
+        for (unsigned int e = tid; e < p.Ap * 64u; e += 256u) {
+            const unsigned int a = e >> 6, r = e & 63u;
+            const float g = (a == as_[r]) ? gs[r] : 0.f;
+            const bf16_bits hi = bf16_bits_rne(g);
+            const bf16_bits lo = bf16_bits_rne(g - bits_to_float(hi));
+            p.dQT_hi[(size_t)a * p.Bp + i0 + r] = hi;
+            p.dQT_lo[(size_t)a * p.Bp + i0 + r] = lo;
+        }
+    }
+    {
+        // 16 consecutive hidden units of one row per thread
+        const unsigned int r = tid >> 2, ks = (tid & 3u) * 16u, i = i0 + r;
+        const bool live = i < p.B;
+        bf16_bits out[16], h2[16], h1[16];
+        if (live) {
+            const float g = gs[r];
+            const u32x4* hp = reinterpret_cast<const u32x4*>(p.H2 + (size_t)i * p.H + k0 + ks);
+            const u32x4* gp = reinterpret_cast<const u32x4*>(p.H1 + (size_t)i * p.H + k0 + ks);
+            const u32x4* wp = reinterpret_cast<const u32x4*>(p.W3T + (size_t)as_[r] * p.H + k0 + ks);
+            const u32x4 hv0 = hp[0], hv1 = hp[1], gv0 = gp[0], gv1 = gp[1], wv0 = wp[0], wv1 = wp[1];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const unsigned int hw = e < 8 ? hv0[e >> 1] : hv1[(e - 8) >> 1];
+                const unsigned int gw = e < 8 ? gv0[e >> 1] : gv1[(e - 8) >> 1];
+                const unsigned int ww = e < 8 ? wv0[e >> 1] : wv1[(e - 8) >> 1];
+                h2[e] = (bf16_bits)(hw >> (16 * (e & 1)));
+                h1[e] = (bf16_bits)(gw >> (16 * (e & 1)));
+                const bf16_bits wb = (bf16_bits)(ww >> (16 * (e & 1)));
+                const float x = bits_to_float(h2[e]) > 0.f ? g * bits_to_float(wb) : 0.f;
+                out[e] = bf16_bits_rne(x);
+            }
+            u32x4 o0, o1;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                o0[e] = out[2 * e] | ((unsigned int)out[2 * e + 1] << 16);
+                o1[e] = out[8 + 2 * e] | ((unsigned int)out[8 + 2 * e + 1] << 16);
+            }
+            u32x4* dp = reinterpret_cast<u32x4*>(p.dZ2 + (size_t)i * p.H + k0 + ks);
+            dp[0] = o0;
+            dp[1] = o1;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) out[e] = h2[e] = h1[e] = 0;
+        }
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            tileT[0][ks + e][r] = out[e];
+            tileT[1][ks + e][r] = h2[e];
+            tileT[2][ks + e][r] = h1[e];
+        }
+    }
+    __syncthreads();
+    {
+        // 16 consecutive batch rows of one hidden unit per thread
+        const unsigned int k = tid >> 2, rs = (tid & 3u) * 16u;
+        const size_t at = (size_t)(k0 + k) * p.Bp + i0 + rs;
+        bf16_bits* const dst[3] = {p.dZ2T, p.H2T, p.H1T};
+#pragma unroll
+        for (int w = 0; w < 3; ++w) {
+            const u32x4* sp = reinterpret_cast<const u32x4*>(&tileT[w][k][rs]);
+            u32x4* dp = reinterpret_cast<u32x4*>(dst[w] + at);
+            dp[0] = sp[0];
+            dp[1] = sp[1];
+        }
+    }
+}
+
+// The two narrow layers' update, from the K-split partial products of their gradients:
+//   part3[z][m][c]: m <= H (row H = bias), c < 2*Ap; gradient of W3[m][a] = sum_z part3[z][m][a]
+//                   + part3[z][m][Ap + a]  (dL/dQ was split into a bf16 high and low part)
+//   part1[z][j][d]: j < H, d <= D (column D = bias); gradient of W1[d][j] = sum_z part1[z][j][d]
+// One thread per parameter; splits are added in order.  Workgroup 0 also reduces the
+// per-sample losses to their mean and advances the sampling step counter.
+struct SmallOptArgs {
+    OptState o;
+    unsigned int splits, H, D, Dp, Dx, Ap, B;
+    const float* part3;
+    const float* part1;
+    size_t oW1, ob1, oW3, ob3;
+    bf16_bits* W1T;   // [H x Dp]
+    bf16_bits* W3T;   // [Ap x H]
+    TrainCounters* ctr;
+    const float* lossi;
+};
+
+__global__ __launch_bounds__(256) void small_opt_kernel(SmallOptArgs p) {
+    const unsigned int n3 = (p.H + 1u) * p.Ap, n1 = p.H * (p.D + 1u);
+    const unsigned int e = blockIdx.x * 256u + threadIdx.x;
+    const float c1 = p.o.ctr->c1, c2 = p.o.ctr->c2;
+    if (e < n3) {
+        const unsigned int m = e / p.Ap, a = e - m * p.Ap;
+        const size_t stride = (size_t)(p.H + 1u) * 2u * p.Ap;
+        const float* src = p.part3 + (size_t)m * 2u * p.Ap + a;
+        float g = 0.f;
+        for (unsigned int z = 0; z < p.splits; ++z) g += src[z * stride] + src[z * stride + p.Ap];
+        if (m < p.H) {
+            const float wk = opt_update(p.o, p.oW3 + (size_t)m * p.Ap + a, g, c1, c2);
+            p.W3T[(size_t)a * p.H + m] = bf16_bits_rne(wk);
+        } else {
+            opt_update(p.o, p.ob3 + a, g, c1, c2);
+        }
+    } else if (e < n3 + n1) {
+        const unsigned int f = e - n3, j = f / (p.D + 1u), d = f - j * (p.D + 1u);
+        const size_t stride = (size_t)p.H * p.Dx;
+        const float* src = p.part1 + (size_t)j * p.Dx + d;
+        float g = 0.f;
+        for (unsigned int z = 0; z < p.splits; ++z) g += src[z * stride];
+        if (d < p.D) {
+            const float wk = opt_update(p.o, p.oW1 + (size_t)d * p.H + j, g, c1, c2);
+            p.W1T[(size_t)j * p.Dp + d] = bf16_bits_rne(wk);
+        } else {
+            opt_update(p.o, p.ob1 + j, g, c1, c2);
+        }
+    }
+    if (blockIdx.x == 0) {
+        __shared__ float part[4];
+        float acc = 0.f;
+        for (unsigned int i = threadIdx.x; i < p.B; i += 256) acc += p.lossi[i];
+        acc = wave_sum(acc);
+        if ((threadIdx.x & 63u) == 0) part[threadIdx.x >> 6] = acc;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            p.ctr->loss = (part[0] + part[1] + part[2] + part[3]) / (float)p.B;
+            p.ctr->step += 1;
+        }
+    }
+}
+
+// K splits of the narrow layers' gradient products (contraction over the padded batch): as
+// many as leave every workgroup at least 256 columns, in whole 64-wide slices, at most 16.
+unsigned int batch_splits(unsigned int Bp) {
+    unsigned int best = 1;
+    for (unsigned int s = 2; s <= 16; ++s)
+        if (Bp % (s * 64u) == 0 && Bp / s >= 256u) best = s;
+    return best;
+}
+
+bf16_bits host_bf16(float f) {
+    unsigned int u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7F800000u) == 0x7F800000u && (u & 0x007FFFFFu)) return (bf16_bits)((u >> 16) | 0x40u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_bits)(u >> 16);
+}
+
+}  // namespace
+
+bool wide_step_supported(const train_config& cfg, const replay* rp_) {
+    return cfg.param_dtype == RP_BF16 && rp_->cfg.state_dtype == RP_BF16 &&
+           rp_->cfg.layout == RP_PAIR && cfg.hidden % 64 == 0;
+}
+
+// Allow the products' LDS sizes and fill the ones rows of the transposed activation buffers
+// (once, at creation).
+hipError_t wide_init_buffers(trainer* t) {
+    hipError_t ec = configure_gemm<128, 128, 32, 2, 2, 1, EpiForward>();
+    if (ec == hipSuccess) ec = configure_gemm<128, 128, 64, 2, 2, 1, EpiForward>();
+    if (ec == hipSuccess) ec = configure_gemm<128, 128, 64, 2, 2, 1, EpiMask>();
+    if (ec == hipSuccess) ec = configure_gemm<64, 64, 128, 1, 1, 4, EpiOptSquare>();
+    if (ec == hipSuccess) ec = configure_gemm<128, 64, 64, 4, 1, 1, EpiPartial>();
+    if (ec == hipSuccess) ec = configure_gemm<128, 32, 64, 4, 1, 1, EpiPartial>();
+    if (ec == hipSuccess) ec = configure_gemm<128, 128, 64, 2, 2, 1, EpiPartial>();
+    if (ec != hipSuccess) return ec;
+    std::vector<bf16_bits> ones(t->Bp, (bf16_bits)0x3F80u);
+    const size_t bytes = (size_t)t->Bp * sizeof(bf16_bits);
+    hipError_t e = hipMemcpy(t->wd.H1T + (size_t)t->H * t->Bp, ones.data(), bytes, hipMemcpyHostToDevice);
+    if (e == hipSuccess)
+        e = hipMemcpy(t->wd.H2T + (size_t)t->H * t->Bp, ones.data(), bytes, hipMemcpyHostToDevice);
+    if (e == hipSuccess)
+        e = hipMemcpy(t->wd.XT + (size_t)t->cfg.state_dim * t->Bp, ones.data(), bytes,
+                      hipMemcpyHostToDevice);
+    return e;
+}
+
+// Refresh the bf16 operand copies of the weights from padded fp32 parameters (host array).
+hipError_t wide_set_weights(trainer* t, const float* padded) {
+    const size_t H = t->H, Dp = t->Dp, Ap = t->Ap;
+    std::vector<bf16_bits> w1t(H * Dp), w2(H * H), w2t(H * H), w3t(Ap * H);
+    for (size_t d = 0; d < Dp; ++d)
+        for (size_t j = 0; j < H; ++j) w1t[j * Dp + d] = host_bf16(padded[t->oW1 + d * H + j]);
+    for (size_t j = 0; j < H; ++j)
+        for (size_t k = 0; k < H; ++k) {
+            const bf16_bits h = host_bf16(padded[t->oW2 + j * H + k]);
+            w2[j * H + k] = h;
+            w2t[k * H + j] = h;
+        }
+    for (size_t k = 0; k < H; ++k)
+        for (size_t a = 0; a < Ap; ++a) w3t[a * H + k] = host_bf16(padded[t->oW3 + k * Ap + a]);
+    hipError_t e = hipMemcpy(t->wd.W1T, w1t.data(), w1t.size() * 2, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(t->wd.W2, w2.data(), w2.size() * 2, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(t->wd.W2T, w2t.data(), w2t.size() * 2, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(t->wd.W3T, w3t.data(), w3t.size() * 2, hipMemcpyHostToDevice);
+    return e;
+}
+
+// Enqueue every kernel of one executed step after the append.
+hipError_t enqueue_wide_step(trainer* t, hipStream_t st, unsigned int* count) {
+    const unsigned int B = t->B, Bp = t->Bp, H = t->H, Dp = t->Dp, Ap = t->Ap;
+    const unsigned int D = t->cfg.state_dim, A = t->cfg.num_actions;
+    WideBuffers& w = t->wd;
+    bf16_bits* X = static_cast<bf16_bits*>(t->X);
+    bf16_bits* H1 = static_cast<bf16_bits*>(t->H1);
+    bf16_bits* H2 = static_cast<bf16_bits*>(t->H2);
+    bf16_bits* dZ2 = static_cast<bf16_bits*>(t->dZ2);
+    unsigned int n = 0;
+    OptState o{t->w, t->g, t->m, t->v, t->cfg.opt, t->cfg.lr, t->cfg.beta1, t->cfg.beta2, t->cfg.eps, t->ctr};
+
+    // sample B slots and unpack into X = [S ; S'] and the transposed copy of S
+    hipError_t e = launch_sample_gather(t->rp_->geom, t->rp_->cfg.seed, 0, &t->ctr->step, B, X,
+                                        X + (size_t)B * Dp, Dp, t->act, t->rew, t->term, t->idx, st,
+                                        w.XT, Bp);
+    if (e != hipSuccess) return e;
+    ++n;
+    // forward on the 2B rows
+    e = launch_gemm<128, 128, 32, 2, 2, 1>(st, X, Dp, w.W1T, Dp, 2 * B, H, Dp,
+                                           EpiForward{t->w + t->ob1, H1, H, 2 * B, H});
+    if (e != hipSuccess) return e;
+    ++n;
+    e = launch_gemm<128, 128, 64, 2, 2, 1>(st, H1, H, w.W2T, H, 2 * B, H, H,
+                                           EpiForward{t->w + t->ob2, H2, H, 2 * B, H});
+    if (e != hipSuccess) return e;
+    ++n;
+    {
+        SkinnyArgs a;
+        a.A = H2; a.lda = H; a.Bt = w.W3T; a.ldb = H; a.M = 2 * B; a.N = Ap; a.K = H;
+        a.bias = t->w + t->ob3; a.out = t->Q; a.ldo = Ap;
+        hipLaunchKernelGGL(skinny_nt_kernel<4>, dim3((2 * B + 31) / 32, Ap / 32), dim3(256), 0, st, a);
+        e = hipGetLastError();
+    }
+    if (e != hipSuccess) return e;
+    ++n;
+    // targets, TD errors, loss terms, dL/dQ and dZ2
+    {
+        TdArgs a;
+        a.B = B; a.Bp = Bp; a.H = H; a.A = A; a.Ap = Ap;
+        a.Q = t->Q; a.act = t->act; a.rew = t->rew; a.term = t->term;
+        a.gamma = t->cfg.gamma; a.loss_kind = t->cfg.loss; a.beta1 = t->cfg.beta1; a.beta2 = t->cfg.beta2;
+        a.y = t->y; a.delta = t->delta; a.lossi = t->lossi;
+        a.dQT_hi = w.dQT_hi; a.dQT_lo = w.dQT_lo; a.W3T = w.W3T; a.H1 = H1; a.H2 = H2; a.dZ2 = dZ2;
+        a.dZ2T = w.dZ2T; a.H1T = w.H1T; a.H2T = w.H2T;
+        a.ctr = t->ctr;
+        hipLaunchKernelGGL(td_dz_kernel, dim3(Bp / 64, H / 64), dim3(256), 0, st, a);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        ++n;
+    }
+    // output layer: partial products of [dW3 ; db3] (row H), high and low part of dL/dQ side by side
+    const unsigned int splits = batch_splits(Bp);
+    const unsigned int Dx = (D + 1 + 31) / 32 * 32;
+    e = Ap == 32 ? launch_gemm<128, 64, 64, 4, 1, 1>(st, w.H2T, Bp, w.dQT_hi, Bp, H + 1, 2 * Ap, Bp,
+                                                     EpiPartial{w.part3, H + 1, 2 * Ap}, splits)
+                 : launch_gemm<128, 128, 64, 2, 2, 1>(st, w.H2T, Bp, w.dQT_hi, Bp, H + 1, 2 * Ap, Bp,
+                                                      EpiPartial{w.part3, H + 1, 2 * Ap}, splits);
+    if (e != hipSuccess) return e;
+    ++n;
+    // dZ1^T = (W2 dZ2^T) masked by the first ReLU; uses W2 before its update
+    e = launch_gemm<128, 128, 64, 2, 2, 1>(st, w.W2, H, dZ2, H, H, B, H,
+                                           EpiMask{w.H1T, w.dZ1T, Bp, H, B});
+    if (e != hipSuccess) return e;
+    ++n;
+    // second hidden layer: W2 and b2
+    e = launch_gemm<64, 64, 128, 1, 1, 4>(st, w.H1T, Bp, w.dZ2T, Bp, H + 1, H, Bp,
+                                          EpiOptSquare{o, H, H, t->oW2, t->ob2, w.W2, w.W2T});
+    if (e != hipSuccess) return e;
+    ++n;
+    // first hidden layer: partial products of [dW1^T | db1] (column D)
+    e = Dx == 32 ? launch_gemm<128, 32, 64, 4, 1, 1>(st, w.dZ1T, Bp, w.XT, Bp, H, Dx, Bp,
+                                                     EpiPartial{w.part1, H, Dx}, splits)
+                 : launch_gemm<128, 128, 64, 2, 2, 1>(st, w.dZ1T, Bp, w.XT, Bp, H, Dx, Bp,
+                                                      EpiPartial{w.part1, H, Dx}, splits);
+    if (e != hipSuccess) return e;
+    ++n;
+    // both narrow layers' update, mean loss, step counter
+    {
+        SmallOptArgs a;
+        a.o = o; a.splits = splits; a.H = H; a.D = D; a.Dp = Dp; a.Dx = Dx; a.Ap = Ap; a.B = B;
+        a.part3 = w.part3; a.part1 = w.part1;
+        a.oW1 = t->oW1; a.ob1 = t->ob1; a.oW3 = t->oW3; a.ob3 = t->ob3;
+        a.W1T = w.W1T; a.W3T = w.W3T; a.ctr = t->ctr; a.lossi = t->lossi;
+        const unsigned int elems = (H + 1) * Ap + H * (D + 1);
+        hipLaunchKernelGGL(small_opt_kernel, dim3((elems + 255) / 256), dim3(256), 0, st, a);
+        ++n;
+    }
+    if (count) *count = n;
+    return hipGetLastError();
+}
+
+}  // namespace rp
