@@ -42,7 +42,7 @@ struct RingState {
     unsigned long long head;   // slot the next experience goes to
     unsigned long long size;   // experiences held
     unsigned long long total;  // experiences ever added
-    unsigned int blocks_done;  // append kernel: blocks that have finished writing
+    unsigned int blocks_done;  // fused train step: workgroups that have finished
     unsigned int pad_[9];
 };
 static_assert(sizeof(RingState) == 64, "RingState is one 64-byte line");
@@ -73,6 +73,12 @@ struct Payload {
     const unsigned char* term;
 };
 
+// Ring state before an operation, as the host mirrors it: kernels take it by value, so they
+// start without a dependent load, and write the state that follows back to device memory.
+struct RingPos {
+    unsigned long long head, size, total;
+};
+
 // Argument block of the PAIR append kernel (one struct, so that a recorded graph node can be
 // pointed at another payload by replacing a single kernel argument).
 struct AppendArgs {
@@ -80,6 +86,7 @@ struct AppendArgs {
     unsigned long long n;
     Payload src;
     unsigned int rows_per_block;
+    RingPos pos;               // ring state before this append
 };
 
 }  // namespace rp

@@ -82,26 +82,19 @@ bool compute_layout(const replay_config* c, Layout* L) {
 }
 
 // ---------------------------------------------------------------------------------------
-// Append.  Every block reads the head before it writes; the head moves only after the
-// last block has finished, so one launch sees one consistent head.
+// Append.  The ring state before the append comes as an argument (the host mirrors it exactly);
+// one thread stores the state that follows.  Kernels that read the state run later in stream
+// order.
 // ---------------------------------------------------------------------------------------
-__device__ __forceinline__ void finish_append(const RingGeom& g, unsigned long long n,
-                                              unsigned long long head) {
-    // No fence: nothing written by this launch is read again inside it; the counter only
-    // establishes that every block has read the head it was going to use.
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const unsigned int done = __hip_atomic_fetch_add(&g.state->blocks_done, 1u, __ATOMIC_RELAXED,
-                                                         __HIP_MEMORY_SCOPE_AGENT);
-        if (done == gridDim.x - 1) {
-            unsigned long long h = head + n;
-            if (h >= g.capacity) h -= g.capacity;
-            unsigned long long sz = g.state->size + n;
-            g.state->head = h;
-            g.state->size = sz > g.capacity ? g.capacity : sz;
-            g.state->total += n;
-            g.state->blocks_done = 0;
-        }
+__device__ __forceinline__ void store_state_after(const RingGeom& g, const RingPos& pos,
+                                                  unsigned long long n) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        unsigned long long h = pos.head + n;
+        if (h >= g.capacity) h -= g.capacity;
+        const unsigned long long sz = pos.size + n;
+        g.state->head = h;
+        g.state->size = sz > g.capacity ? g.capacity : sz;
+        g.state->total = pos.total + n;
     }
 }
 
@@ -117,7 +110,8 @@ __global__ __launch_bounds__(kThreads) void append_pair_kernel(AppendArgs p) {
     const float* __restrict__ r = p.src.r;
     const unsigned char* __restrict__ term = p.src.term;
     const unsigned int rows_per_block = p.rows_per_block;
-    const unsigned long long head = g.state->head;
+    const unsigned long long head = p.pos.head;
+    store_state_after(g, p.pos, n);
     const unsigned int words = g.row_bytes >> 2;
     const unsigned long long row0 = (unsigned long long)blockIdx.x * rows_per_block;
     const unsigned int sb = g.state_bytes;
@@ -136,6 +130,18 @@ __global__ __launch_bounds__(kThreads) void append_pair_kernel(AppendArgs p) {
                           ? reinterpret_cast<const unsigned int*>(s)[row * g.state_dim + col]
                           : reinterpret_cast<const unsigned int*>(s_next)[row * g.state_dim + col -
                                                                           g.state_dim];
+            } else if (ELEM == 2) {
+#pragma unroll
+                for (unsigned int h = 0; h < 2; ++h) {
+                    const unsigned int col = 2u * w + h;
+                    unsigned int half = 0;
+                    if (col < g.state_dim)
+                        half = reinterpret_cast<const unsigned short*>(s)[row * g.state_dim + col];
+                    else if (col < 2u * g.state_dim)
+                        half = reinterpret_cast<const unsigned short*>(s_next)[row * g.state_dim + col -
+                                                                               g.state_dim];
+                    val |= half << (16 * h);
+                }
             } else {
 #pragma unroll
                 for (unsigned int b = 0; b < 4; ++b) {
@@ -157,17 +163,17 @@ __global__ __launch_bounds__(kThreads) void append_pair_kernel(AppendArgs p) {
         }
         reinterpret_cast<unsigned int*>(g.rows + slot * g.row_bytes)[w] = val;
     }
-    finish_append(g, n, head);
 }
 
 // CHAIN: one block per experience copies the state into its slot and the three scalars
 // into the side arrays.  VEC: state_bytes is a multiple of 16 and the source is 16-byte aligned.
 template <bool VEC>
 __global__ __launch_bounds__(kThreads) void append_chain_kernel(
-    RingGeom g, unsigned long long n, const unsigned char* __restrict__ s,
+    RingGeom g, RingPos pos, unsigned long long n, const unsigned char* __restrict__ s,
     const int* __restrict__ a, const float* __restrict__ r,
     const unsigned char* __restrict__ term) {
-    const unsigned long long head = g.state->head;
+    const unsigned long long head = pos.head;
+    store_state_after(g, pos, n);
     for (unsigned long long row = blockIdx.x; row < n; row += gridDim.x) {
         unsigned long long slot = head + row;
         if (slot >= g.capacity) slot -= g.capacity;
@@ -186,7 +192,6 @@ __global__ __launch_bounds__(kThreads) void append_chain_kernel(
             g.term[slot] = term[row] ? 1 : 0;
         }
     }
-    finish_append(g, n, head);
 }
 
 // float(b) / 255 for b in 0..255, correctly rounded: one multiply by the float nearest to
@@ -398,9 +403,11 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 }  // namespace
 
-AppendArgs make_append_args(const RingGeom& g, unsigned long long n, const Payload& src) {
+AppendArgs make_append_args(const RingGeom& g, const RingPos& pos, unsigned long long n,
+                            const Payload& src) {
     AppendArgs a;
     a.g = g;
+    a.pos = pos;
     a.n = n;
     a.src = src;
     const unsigned int words = g.row_bytes >> 2;
@@ -419,14 +426,14 @@ void* append_pair_func(const RingGeom& g) {
     return reinterpret_cast<void*>(append_pair_kernel<1>);
 }
 
-hipError_t launch_append(const RingGeom& g, unsigned long long n, const void* s,
-                         const void* s_next, const int* a, const float* r,
+hipError_t launch_append(const RingGeom& g, const RingPos& pos, unsigned long long n,
+                         const void* s, const void* s_next, const int* a, const float* r,
                          const unsigned char* term, hipStream_t stream) {
     if (n == 0) return hipSuccess;
     const unsigned char* sp = static_cast<const unsigned char*>(s);
     const unsigned char* snp = static_cast<const unsigned char*>(s_next);
     if (g.layout == RP_PAIR) {
-        AppendArgs args = make_append_args(g, n, Payload{sp, snp, a, r, term});
+        AppendArgs args = make_append_args(g, pos, n, Payload{sp, snp, a, r, term});
         const unsigned int blocks = append_blocks(args);
         void* kargs[] = {&args};
         hipError_t e = hipLaunchKernel(append_pair_func(g), dim3(blocks), dim3(kThreads), kargs, 0,
@@ -436,10 +443,10 @@ hipError_t launch_append(const RingGeom& g, unsigned long long n, const void* s,
         const unsigned int blocks = (unsigned int)(n < 65536 ? n : 65536);
         if ((g.state_bytes & 15u) == 0 && aligned16(s))
             hipLaunchKernelGGL(append_chain_kernel<true>, dim3(blocks), dim3(kThreads), 0, stream,
-                               g, n, sp, a, r, term);
+                               g, pos, n, sp, a, r, term);
         else
             hipLaunchKernelGGL(append_chain_kernel<false>, dim3(blocks), dim3(kThreads), 0, stream,
-                               g, n, sp, a, r, term);
+                               g, pos, n, sp, a, r, term);
     }
     return hipGetLastError();
 }
@@ -583,7 +590,8 @@ rp_status replay_append(replay_t* rp_, uint64_t n, const void* s, const void* s_
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const rp::RingGeom& g = rp_->geom;
     if (src_is_device) {
-        RP_CHECK_HIP(rp::launch_append(g, n, s, s_next, a, r, term, stream));
+        RP_CHECK_HIP(rp::launch_append(g, rp::RingPos{rp_->head, rp_->size, rp_->total}, n, s, s_next, a,
+                                       r, term, stream));
     } else {
         const size_t sb = g.state_bytes;
         for (uint64_t done = 0; done < n;) {
@@ -597,7 +605,10 @@ rp_status replay_append(replay_t* rp_, uint64_t n, const void* s, const void* s_
             RP_CHECK_HIP(hipMemcpyAsync(rp_->stage_a, a + done, m * 4, hipMemcpyHostToDevice, stream));
             RP_CHECK_HIP(hipMemcpyAsync(rp_->stage_r, r + done, m * 4, hipMemcpyHostToDevice, stream));
             RP_CHECK_HIP(hipMemcpyAsync(rp_->stage_term, term + done, m, hipMemcpyHostToDevice, stream));
-            RP_CHECK_HIP(rp::launch_append(g, m, rp_->stage_s, rp_->stage_s_next, rp_->stage_a,
+            const uint64_t cap = rp_->cfg.capacity;
+            const rp::RingPos pos{(rp_->head + done) % cap,
+                                  rp_->size + done > cap ? cap : rp_->size + done, rp_->total + done};
+            RP_CHECK_HIP(rp::launch_append(g, pos, m, rp_->stage_s, rp_->stage_s_next, rp_->stage_a,
                                            rp_->stage_r, rp_->stage_term, stream));
             done += m;
             // pageable host memory: the copies above have left the caller's arrays when they

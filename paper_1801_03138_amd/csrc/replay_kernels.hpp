@@ -5,14 +5,15 @@
 
 namespace rp {
 
-// Append n experiences read from device arrays (structure of arrays) at the
-// ring's device-resident head; the last block to finish advances the state.
-hipError_t launch_append(const RingGeom& g, unsigned long long n, const void* s,
-                         const void* s_next, const int* a, const float* r,
+// Append n experiences read from device arrays (structure of arrays) to a ring in state
+// `pos` (the host mirror's); the kernel also stores the state that follows in device memory.
+hipError_t launch_append(const RingGeom& g, const RingPos& pos, unsigned long long n,
+                         const void* s, const void* s_next, const int* a, const float* r,
                          const unsigned char* term, hipStream_t stream);
 
 // Pieces of the PAIR append launch, for callers that record it into a graph themselves.
-AppendArgs make_append_args(const RingGeom& g, unsigned long long n, const Payload& src);
+AppendArgs make_append_args(const RingGeom& g, const RingPos& pos, unsigned long long n,
+                            const Payload& src);
 unsigned int append_blocks(const AppendArgs& a);
 void* append_pair_func(const RingGeom& g);   // the __global__ function, as hipLaunchKernel takes it
 

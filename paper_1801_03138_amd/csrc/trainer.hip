@@ -405,7 +405,8 @@ hipError_t enqueue_append_and_step(trainer* t, const Payload& src, hipStream_t s
     unsigned int n = 0, k = 0;
     replay* r = t->rp_;
     if (t->cfg.appends_per_step) {
-        t->append_args = make_append_args(r->geom, t->cfg.appends_per_step, src);
+        t->append_args = make_append_args(r->geom, RingPos{r->head, r->size, r->total},
+                                          t->cfg.appends_per_step, src);
         void* kargs[] = {&t->append_args};
         hipError_t e = hipLaunchKernel(append_pair_func(r->geom), dim3(append_blocks(t->append_args)),
                                        dim3(kThreads), kargs, 0, st);
@@ -662,7 +663,8 @@ rp_status train_step(trainer_t* t, const void* s, const void* s_next, const int3
     const bool train = total_after >= rpl->cfg.burn_in && size_after >= 1;
     if (!train) {
         if (n)
-            RP_CHECK_HIP(rp::launch_append(rpl->geom, n, src.s, src.s_next, src.a, src.r, src.term, st));
+            RP_CHECK_HIP(rp::launch_append(rpl->geom, rp::RingPos{rpl->head, rpl->size, rpl->total}, n,
+                                           src.s, src.s_next, src.a, src.r, src.term, st));
     } else if (t->graph_exec) {
         if (t->payload_node) {
             if (t->fused) {
@@ -672,6 +674,7 @@ rp_status train_step(trainer_t* t, const void* s, const void* s_next, const int3
                 t->row_args.size_after = (unsigned int)size_after;
             } else {
                 t->append_args.src = src;
+                t->append_args.pos = rp::RingPos{rpl->head, rpl->size, rpl->total};
             }
             RP_CHECK_HIP(hipGraphExecKernelNodeSetParams(t->graph_exec, t->payload_node, &t->payload_np));
         }

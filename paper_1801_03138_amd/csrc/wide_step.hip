@@ -610,7 +610,7 @@ __global__ __launch_bounds__(256) void td_dz_kernel(TdArgs p) {
 //   part3[z][m][c]: m <= H (row H = bias), c < 2*Ap; gradient of W3[m][a] = sum_z part3[z][m][a]
 //                   + part3[z][m][Ap + a]  (dL/dQ was split into a bf16 high and low part)
 //   part1[z][j][d]: j < H, d <= D (column D = bias); gradient of W1[d][j] = sum_z part1[z][j][d]
-// One thread per parameter; splits are added in order.  Workgroup 0 also reduces the
+// One thread per parameter; splits (at most 16) are added in order.  Workgroup 0 also reduces the
 // per-sample losses to their mean and advances the sampling step counter.
 struct SmallOptArgs {
     OptState o;
@@ -632,8 +632,15 @@ __global__ __launch_bounds__(256) void small_opt_kernel(SmallOptArgs p) {
         const unsigned int m = e / p.Ap, a = e - m * p.Ap;
         const size_t stride = (size_t)(p.H + 1u) * 2u * p.Ap;
         const float* src = p.part3 + (size_t)m * 2u * p.Ap + a;
+        float hi[16], lo[16];
+#pragma unroll
+        for (unsigned int z = 0; z < 16; ++z) {
+            hi[z] = z < p.splits ? src[z * stride] : 0.f;
+            lo[z] = z < p.splits ? src[z * stride + p.Ap] : 0.f;
+        }
         float g = 0.f;
-        for (unsigned int z = 0; z < p.splits; ++z) g += src[z * stride] + src[z * stride + p.Ap];
+#pragma unroll
+        for (unsigned int z = 0; z < 16; ++z) g += hi[z] + lo[z];
         if (m < p.H) {
             const float wk = opt_update(p.o, p.oW3 + (size_t)m * p.Ap + a, g, c1, c2);
             p.W3T[(size_t)a * p.H + m] = bf16_bits_rne(wk);
@@ -644,8 +651,12 @@ __global__ __launch_bounds__(256) void small_opt_kernel(SmallOptArgs p) {
         const unsigned int f = e - n3, j = f / (p.D + 1u), d = f - j * (p.D + 1u);
         const size_t stride = (size_t)p.H * p.Dx;
         const float* src = p.part1 + (size_t)j * p.Dx + d;
+        float part[16];
+#pragma unroll
+        for (unsigned int z = 0; z < 16; ++z) part[z] = z < p.splits ? src[z * stride] : 0.f;
         float g = 0.f;
-        for (unsigned int z = 0; z < p.splits; ++z) g += src[z * stride];
+#pragma unroll
+        for (unsigned int z = 0; z < 16; ++z) g += part[z];
         if (d < p.D) {
             const float wk = opt_update(p.o, p.oW1 + (size_t)d * p.H + j, g, c1, c2);
             p.W1T[(size_t)j * p.Dp + d] = bf16_bits_rne(wk);
@@ -654,14 +665,14 @@ __global__ __launch_bounds__(256) void small_opt_kernel(SmallOptArgs p) {
         }
     }
     if (blockIdx.x == 0) {
-        __shared__ float part[4];
+        __shared__ float wsum[4];
         float acc = 0.f;
         for (unsigned int i = threadIdx.x; i < p.B; i += 256) acc += p.lossi[i];
         acc = wave_sum(acc);
-        if ((threadIdx.x & 63u) == 0) part[threadIdx.x >> 6] = acc;
+        if ((threadIdx.x & 63u) == 0) wsum[threadIdx.x >> 6] = acc;
         __syncthreads();
         if (threadIdx.x == 0) {
-            p.ctr->loss = (part[0] + part[1] + part[2] + part[3]) / (float)p.B;
+            p.ctr->loss = (wsum[0] + wsum[1] + wsum[2] + wsum[3]) / (float)p.B;
             p.ctr->step += 1;
         }
     }
@@ -696,7 +707,7 @@ bool wide_step_supported(const train_config& cfg, const replay* rp_) {
 hipError_t wide_init_buffers(trainer* t) {
     hipError_t ec = configure_gemm<128, 128, 32, 2, 2, 1, EpiForward>();
     if (ec == hipSuccess) ec = configure_gemm<128, 128, 64, 2, 2, 1, EpiForward>();
-    if (ec == hipSuccess) ec = configure_gemm<128, 128, 64, 2, 2, 1, EpiMask>();
+    if (ec == hipSuccess) ec = configure_gemm<128, 64, 64, 2, 2, 1, EpiMask>();
     if (ec == hipSuccess) ec = configure_gemm<64, 64, 128, 1, 1, 4, EpiOptSquare>();
     if (ec == hipSuccess) ec = configure_gemm<128, 64, 64, 4, 1, 1, EpiPartial>();
     if (ec == hipSuccess) ec = configure_gemm<128, 32, 64, 4, 1, 1, EpiPartial>();
@@ -795,8 +806,8 @@ hipError_t enqueue_wide_step(trainer* t, hipStream_t st, unsigned int* count) {
     if (e != hipSuccess) return e;
     ++n;
     // dZ1^T = (W2 dZ2^T) masked by the first ReLU; uses W2 before its update
-    e = launch_gemm<128, 128, 64, 2, 2, 1>(st, w.W2, H, dZ2, H, H, B, H,
-                                           EpiMask{w.H1T, w.dZ1T, Bp, H, B});
+    e = launch_gemm<128, 64, 64, 2, 2, 1>(st, w.W2, H, dZ2, H, H, B, H,
+                                          EpiMask{w.H1T, w.dZ1T, Bp, H, B});
     if (e != hipSuccess) return e;
     ++n;
     // second hidden layer: W2 and b2

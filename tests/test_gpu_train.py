@@ -254,6 +254,30 @@ def test_mixed_precision_small(B):
         pr.step(synth.take(rows, k, k + 4), compare=(k % 40 == 0) or k >= 560)
 
 
+@pytest.mark.parametrize("D,H,A,batch", [(40, 64, 40, 7), (31, 192, 33, 130), (32, 64, 3, 513)])
+def test_mixed_precision_other_shapes(B, D, H, A, batch):
+    """Shapes off the tuned path of the MFMA step: states and action sets that need a second
+    32-wide tile (and no spare column for the bias trick), a batch below one tile and batches
+    that end inside a tile, a single 64-wide hidden tile."""
+    rows = synth.experiences(400, D, A, 0.05, seed=17, state_dtype="bf16")
+    pr = Pair(B, capacity=256, D=D, H=H, A=A, batch=batch, burn_in=100, seed=3, dtype="bf16",
+              appends=2)
+    assert pr.trainer.kernels_per_step() == 11
+    for k in range(0, 400, 2):
+        pr.step(synth.take(rows, k, k + 2), compare=(k % 60 == 0) or k >= 392)
+    assert pr.gpu_ring.state() == pr.ref_ring.state()
+
+
+def test_mixed_precision_layered_agrees(B):
+    """The one-kernel-per-layer bf16 step stays available behind RP_TRAIN_LAYERED."""
+    rows = synth.experiences(300, 27, 30, 0.05, seed=19, state_dtype="bf16")
+    pr = Pair(B, capacity=256, D=27, H=128, A=30, batch=96, burn_in=100, seed=3, dtype="bf16",
+              appends=2, layered=True)
+    assert pr.trainer.kernels_per_step() == 15
+    for k in range(0, 300, 2):
+        pr.step(synth.take(rows, k, k + 2), compare=(k % 60 == 0) or k >= 292)
+
+
 def test_wide_config_first_steps(B):
     """Capacity 4e6 (bf16 states), 27-1024-1024-30, batch 4096, 64 appends per step, Adam."""
     oracle.set_threads(16)
