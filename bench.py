@@ -9,7 +9,7 @@ Adam) with every input already in HBM.  The same JSON line carries the gather ke
 HBM roofline (measured live with events), the other workloads, and the CPU oracle
 timed on this machine's host cores.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--legs p,gather,large,wide,cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--legs p,pfull,phost,inram,gather,large,wide,cpu]
 """
 import argparse
 import json
@@ -191,6 +191,57 @@ def leg_wide(B, synth, steps, warmup):
             "TFLOPs": flops * steps / dt / 1e12, "kernels_per_step": tr.kernels_per_step()}
 
 
+def leg_device_vs_inram(B, synth, steps, warmup):
+    """Train-step rate of the device-resident replay and of the in-RAM comparison system (host
+    sampling and gather, one host-to-device copy of the batch per step) at the batch sizes of
+    the paper's speed-up table, on the full 1M-row paper-shaped ring."""
+    import torch
+    c = P_CFG
+    base = synth.experiences(100_000, c["D"], c["A"], c["p_term"], seed=0)
+    stream_rows = synth.experiences(steps + warmup, c["D"], c["A"], c["p_term"], seed=1)
+    fields = ("s", "s_next", "a", "r", "term")
+    w = {k: stream_rows[k][:warmup] for k in fields}
+    t = {k: stream_rows[k][warmup:] for k in fields}
+    d_all = dev_rows(stream_rows)
+    dw = {k: d_all[k][:warmup] for k in fields}
+    dt_ = {k: d_all[k][warmup:] for k in fields}
+    out = []
+    for batch in (16, 32, 64, 128, 256):
+        p0 = synth.init_params(c["D"], c["H"], c["A"], 0)
+        # device-resident replay
+        ring = B.Replay(c["capacity"], c["D"], burn_in=c["burn_in"], seed=0, max_append=4096)
+        prefill(ring, base, c["capacity"])
+        tr = B.Trainer(ring, c["H"], c["A"], batch, opt=B.RP_ADAM, loss=B.RP_HUBER, lr=c["lr"],
+                       appends_per_step=1, init_params=p0)
+        tr.steps(warmup, *[dw[k] for k in fields])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        assert tr.steps(steps, *[dt_[k] for k in fields]) == steps
+        torch.cuda.synchronize()
+        dev_rate = steps / (time.perf_counter() - t0)
+        loss_dev = tr.last()["loss"]
+        # in-RAM replay feeding the same step
+        idle = B.Replay(8, c["D"], seed=0)
+        tr2 = B.Trainer(idle, c["H"], c["A"], batch, opt=B.RP_ADAM, loss=B.RP_HUBER, lr=c["lr"],
+                        appends_per_step=0, init_params=p0)
+        ram = B.InRamReplay(c["capacity"], c["D"], batch, burn_in=c["burn_in"], seed=0)
+        for lo in range(0, c["capacity"], 100_000):
+            ram.append(*[base[k] for k in fields])
+        ram.train_steps(tr2, warmup, 1, *[w[k] for k in fields])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        assert ram.train_steps(tr2, steps, 1, *[t[k] for k in fields]) == steps
+        torch.cuda.synchronize()
+        ram_rate = steps / (time.perf_counter() - t0)
+        loss_ram = tr2.last()["loss"]
+        out.append({"batch": batch, "device_steps_per_s": dev_rate, "inram_steps_per_s": ram_rate,
+                    "speedup_pct": 100.0 * (dev_rate / ram_rate - 1.0),
+                    "same_final_loss": bool(loss_dev == loss_ram)})
+        for h in (tr, tr2, ram, ring, idle):
+            h.close()
+    return out
+
+
 def leg_cpu_oracle(synth, seconds_budget):
     """The oracle's own append + sample + gather + train step on the paper-shaped workload."""
     import oracle
@@ -229,7 +280,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10_000)
     ap.add_argument("--warmup", type=int, default=500)
-    ap.add_argument("--legs", default="p,pfull,phost,gather,large,wide,cpu")
+    ap.add_argument("--legs", default="p,pfull,phost,inram,gather,large,wide,cpu")
     ap.add_argument("--gather-reps", type=int, default=1000)
     ap.add_argument("--wide-steps", type=int, default=200)
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
@@ -259,6 +310,12 @@ def main():
         out["paper_shaped_host_payload"] = leg_paper_shaped(B, synth, args.steps, args.warmup,
                                                             False, host_payload=True)
         log("[bench]   %.0f steps/s" % out["paper_shaped_host_payload"]["steps_per_s"])
+    if "inram" in legs:
+        log("[bench] device-resident replay vs in-RAM replay with a per-step batch copy ...")
+        out["device_vs_inram"] = leg_device_vs_inram(B, synth, min(args.steps, 4000), 200)
+        for g in out["device_vs_inram"]:
+            log("[bench]   B=%-4d device %8.0f steps/s   in-RAM %8.0f steps/s   %+6.1f %%" %
+                (g["batch"], g["device_steps_per_s"], g["inram_steps_per_s"], g["speedup_pct"]))
     roofline = None
     if "gather" in legs:
         log("[bench] gather sweep on the full 1M-row ring ...")

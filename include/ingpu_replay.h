@@ -193,6 +193,17 @@ rp_status train_steps(trainer_t* tr, uint64_t count, const void* s, const void* 
                       const int32_t* a, const float* r, const uint8_t* term, int src_is_device,
                       void* hip_stream, uint64_t* executed);
 
+/*
+ * One train step on a batch the caller provides instead of a sampled one: device arrays of
+ * `batch` experiences, structure of arrays as replay_sample_gather writes them (states in the
+ * replay's state type).  Nothing is appended or drawn; the rest of the step is the one of
+ * train_step (Deep Q-Network Model, the update equation), the trainer's step counter advances,
+ * and train_get_last reports 0..batch-1 as the slot numbers.  This is the step the in-RAM
+ * comparison system below feeds.
+ */
+rp_status train_step_batch(trainer_t* tr, const void* s, const void* s_next, const int32_t* a,
+                           const float* r, const uint8_t* term, void* hip_stream);
+
 /* Test / inspection calls; host destinations, any may be NULL; all synchronise. */
 rp_status train_get_params(trainer_t* tr, float* params);             /* fp32 master weights */
 rp_status train_get_grads(trainer_t* tr, float* grads);               /* of the last step    */
@@ -206,6 +217,34 @@ rp_status train_get_last(trainer_t* tr, float* q, float* q_next, float* y, float
                          float* loss, uint32_t* idx);
 /* Number of GPU kernels one executed train step launches (graph nodes). */
 rp_status train_kernels_per_step(trainer_t* tr, uint32_t* n);
+
+/*
+ * The paper's comparison system, re-created for measurement: an experience replay kept in host
+ * RAM (Methods and Results: the "in-RAM" replay).  float32 states, both states stored.  Each
+ * train step draws its batch on the host with the same generator, key and counter layout as
+ * replay_sample_gather (so it trains on the same batches as the device-resident replay),
+ * gathers the rows into pinned memory, copies the batch to the GPU and calls train_step_batch.
+ * dev_batch: device memory of inram_device_bytes(state_dim, batch) bytes, 256-byte aligned,
+ * owned by the caller.  The trainer passed to the step calls must have been created with the
+ * same state_dim and batch.
+ */
+typedef struct inram_replay inram_replay_t;
+size_t    inram_device_bytes(uint32_t state_dim, uint32_t batch);
+rp_status inram_create(uint64_t capacity, uint32_t state_dim, uint64_t burn_in, uint64_t seed,
+                       uint32_t batch, void* dev_batch, size_t bytes, inram_replay_t** out);
+rp_status inram_destroy(inram_replay_t* h);
+/* host arrays, structure of arrays; FIFO with wraparound as replay_append */
+rp_status inram_append(inram_replay_t* h, uint64_t n, const float* s, const float* s_next,
+                       const int32_t* a, const float* r, const uint8_t* term);
+/* RP_SKIPPED_BURN_IN (nothing done) before burn-in completes; sampling step counter starts at 0 */
+rp_status inram_train_step(inram_replay_t* h, trainer_t* tr, void* hip_stream);
+/* count x (append appends_per_step experiences from the host arrays, then one train step) */
+rp_status inram_train_steps(inram_replay_t* h, trainer_t* tr, uint64_t count,
+                            uint32_t appends_per_step, const float* s, const float* s_next,
+                            const int32_t* a, const float* r, const uint8_t* term, void* hip_stream,
+                            uint64_t* executed);
+rp_status inram_get_state(inram_replay_t* h, uint64_t* head, uint64_t* size, uint64_t* total,
+                          uint64_t* step);
 
 /* Message for the last failure on this thread ("" if none). */
 const char* rp_last_error(void);

@@ -63,6 +63,14 @@ SYMBOLS = {
     "train_destroy": (_int, [_vp]),
     "train_step": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _int, _vp]),
     "train_steps": (_int, [_vp, _u64, _vp, _vp, _vp, _vp, _vp, _int, _vp, _vp]),
+    "train_step_batch": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "inram_device_bytes": (C.c_size_t, [_u32, _u32]),
+    "inram_create": (_int, [_u64, _u32, _u64, _u64, _u32, _vp, C.c_size_t, _vp]),
+    "inram_destroy": (_int, [_vp]),
+    "inram_append": (_int, [_vp, _u64, _vp, _vp, _vp, _vp, _vp]),
+    "inram_train_step": (_int, [_vp, _vp, _vp]),
+    "inram_train_steps": (_int, [_vp, _vp, _u64, _u32, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "inram_get_state": (_int, [_vp, _vp, _vp, _vp, _vp]),
     "train_get_params": (_int, [_vp, _vp]),
     "train_get_grads": (_int, [_vp, _vp]),
     "train_get_opt_state": (_int, [_vp, _vp, _vp, _vp, _vp]),
@@ -269,6 +277,11 @@ class Trainer:
                                  C.byref(done)))
         return done.value
 
+    def step_batch(self, s, s_next, a, r, term, stream=None):
+        """One train step on the given batch (torch CUDA tensors, as sample_gather returns them)."""
+        return _check(lib().train_step_batch(self._h, _dev(s), _dev(s_next), _dev(a), _dev(r),
+                                             _dev(term), _stream_ptr(stream)))
+
     def params(self):
         p = np.empty(self.n_params, np.float32)
         _check(lib().train_get_params(self._h, _host(p)))
@@ -304,3 +317,54 @@ class Trainer:
         n = C.c_uint32()
         _check(lib().train_kernels_per_step(self._h, C.byref(n)))
         return n.value
+
+
+class InRamReplay:
+    """The paper's comparison system: replay in host RAM, per-step host sampling and H2D copy."""
+
+    def __init__(self, capacity, state_dim, batch, burn_in=0, seed=0, device="cuda:0"):
+        self.D, self.batch = state_dim, batch
+        nbytes = int(lib().inram_device_bytes(state_dim, batch))
+        if nbytes == 0:
+            raise ReplayError(RP_EINVAL, "invalid in-RAM replay configuration")
+        self.dev_batch = _alloc_bytes(nbytes, torch.device(device))
+        h = C.c_void_p()
+        with torch.cuda.device(torch.device(device)):
+            _check(lib().inram_create(capacity, state_dim, burn_in, seed, batch, _dev(self.dev_batch),
+                                      nbytes, C.byref(h)))
+        self._h = h
+        self._destroy = lib().inram_destroy
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    @staticmethod
+    def _fields(s, s_next, a, r, term):
+        return [np.ascontiguousarray(s, np.float32), np.ascontiguousarray(s_next, np.float32),
+                np.ascontiguousarray(a, np.int32), np.ascontiguousarray(r, np.float32),
+                np.ascontiguousarray(term, np.uint8)]
+
+    def append(self, s, s_next, a, r, term):
+        keep = self._fields(s, s_next, a, r, term)
+        return _check(lib().inram_append(self._h, len(keep[2]), *[_host(x) for x in keep]))
+
+    def train_step(self, trainer, stream=None):
+        return _check(lib().inram_train_step(self._h, trainer._h, _stream_ptr(stream)))
+
+    def train_steps(self, trainer, count, appends_per_step, s, s_next, a, r, term, stream=None):
+        keep = self._fields(s, s_next, a, r, term)
+        if len(keep[2]) < count * appends_per_step:
+            raise ValueError("not enough experiences for that many steps")
+        done = C.c_uint64()
+        _check(lib().inram_train_steps(self._h, trainer._h, count, appends_per_step,
+                                       *[_host(x) for x in keep], _stream_ptr(stream), C.byref(done)))
+        return done.value
+
+    def state(self):
+        v = [C.c_uint64() for _ in range(4)]
+        _check(lib().inram_get_state(self._h, *[C.byref(x) for x in v]))
+        return tuple(x.value for x in v)

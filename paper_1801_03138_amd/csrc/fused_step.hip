@@ -34,16 +34,20 @@ __device__ __forceinline__ void lds_barrier() {
 }
 
 
-// One 32-bit word of the packed row of a new experience, taken from the staging arrays.
+// One 32-bit word of the packed row of experience k of a structure-of-arrays payload.
+__device__ __forceinline__ unsigned int payload_word(const Payload& src, unsigned int D,
+                                                     unsigned long long k, unsigned int w) {
+    if (w < D) return reinterpret_cast<const unsigned int*>(src.s)[k * D + w];
+    if (w < 2 * D) return reinterpret_cast<const unsigned int*>(src.s_next)[k * D + w - D];
+    if (w == 2 * D) return (unsigned int)src.a[k];
+    if (w == 2 * D + 1) return __float_as_uint(src.r[k]);
+    if (w == 2 * D + 2) return src.term[k] ? 1u : 0u;
+    return 0u;
+}
+// ... of a new experience of this step
 __device__ __forceinline__ unsigned int staged_word(const RowArgs& p, unsigned long long k,
                                                     unsigned int w) {
-    const unsigned int D = p.D;
-    if (w < D) return reinterpret_cast<const unsigned int*>(p.src.s)[k * D + w];
-    if (w < 2 * D) return reinterpret_cast<const unsigned int*>(p.src.s_next)[k * D + w - D];
-    if (w == 2 * D) return (unsigned int)p.src.a[k];
-    if (w == 2 * D + 1) return __float_as_uint(p.src.r[k]);
-    if (w == 2 * D + 2) return p.src.term[k] ? 1u : 0u;
-    return 0u;
+    return payload_word(p.src, p.D, k, w);
 }
 
 // ----------------------------------------------------------------------------------------
@@ -187,13 +191,19 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
         const unsigned int e = tid + pass * kRowThreads;
         if (e < nrows * words) {
             const unsigned int r = e / words, w = e - r * words;
-            const unsigned int slot = uniform_draw(p.seed, step, i0 + r, size);
-            unsigned long long off = (unsigned long long)slot + cap - head;
-            if (off >= cap) off -= cap;
-            gslot[pass] = slot;
-            gval[pass] = off < n ? staged_word(p, off, w)
-                                 : reinterpret_cast<const unsigned int*>(
-                                       p.g.rows + (unsigned long long)slot * p.g.row_bytes)[w];
+            if (p.from_batch) {
+                // the caller's batch: row i0 + r of its arrays; reported slot = position in the batch
+                gslot[pass] = i0 + r;
+                gval[pass] = payload_word(p.batch, D, i0 + r, w);
+            } else {
+                const unsigned int slot = uniform_draw(p.seed, step, i0 + r, size);
+                unsigned long long off = (unsigned long long)slot + cap - head;
+                if (off >= cap) off -= cap;
+                gslot[pass] = slot;
+                gval[pass] = off < n ? staged_word(p, off, w)
+                                     : reinterpret_cast<const unsigned int*>(
+                                           p.g.rows + (unsigned long long)slot * p.g.row_bytes)[w];
+            }
         }
     }
     float w1r[16], w2r[64];
@@ -559,13 +569,16 @@ bool fused_step_supported(const train_config& cfg, const replay* rp_) {
 
 void* fused_rows_func() { return reinterpret_cast<void*>(fused_rows_kernel); }
 
-hipError_t enqueue_fused_step(trainer* t, const Payload& src, hipStream_t st, unsigned int* count) {
+hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* batch, hipStream_t st,
+                              unsigned int* count) {
     replay* r = t->rp_;
     RowArgs& a = t->row_args;
     a.g = r->geom;
     a.seed = r->cfg.seed;
-    a.n_append = t->cfg.appends_per_step;
+    a.n_append = batch ? 0u : t->cfg.appends_per_step;
     a.src = src;
+    a.batch = batch ? *batch : Payload{nullptr, nullptr, nullptr, nullptr, nullptr};
+    a.from_batch = batch ? 1u : 0u;
     {
         // state before this step, from the host mirrors (train_step has not advanced them yet)
         const unsigned long long cap = r->cfg.capacity, after = r->size + a.n_append;

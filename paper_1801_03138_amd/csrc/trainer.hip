@@ -208,6 +208,32 @@ __global__ __launch_bounds__(kThreads) void optimizer_kernel(
     }
 }
 
+// A caller-provided batch (structure of arrays, B rows) into the step's input buffers:
+// X = [S ; S'] with row pitch Dp, the per-row fields, the batch position as "slot", and, for the
+// MFMA step, the transposed copy of S.  E = element type of a state (4 or 2 bytes).
+template <typename E>
+__global__ __launch_bounds__(kThreads) void load_batch_kernel(
+    unsigned int B, unsigned int D, unsigned int Dp, const E* __restrict__ s,
+    const E* __restrict__ s_next, const int* __restrict__ a, const float* __restrict__ r,
+    const unsigned char* __restrict__ term, E* __restrict__ X, E* __restrict__ XT,
+    unsigned int ldt, int* __restrict__ act, float* __restrict__ rew,
+    unsigned char* __restrict__ trm, unsigned int* __restrict__ idx) {
+    const size_t e = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    if (e < (size_t)B * D) {
+        const unsigned int i = (unsigned int)(e / D), c = (unsigned int)(e - (size_t)i * D);
+        const E v = s[e];
+        X[(size_t)i * Dp + c] = v;
+        X[(size_t)(B + i) * Dp + c] = s_next[e];
+        if (XT) XT[(size_t)c * ldt + i] = v;
+    }
+    if (e < B) {
+        act[e] = a[e];
+        rew[e] = r[e];
+        trm[e] = term[e] ? 1 : 0;
+        idx[e] = (unsigned int)e;
+    }
+}
+
 __global__ __launch_bounds__(kThreads) void to_bf16_kernel(unsigned int n,
                                                            const float* __restrict__ w,
                                                            bf16_t* __restrict__ wb) {
@@ -338,7 +364,7 @@ void gemm(hipStream_t st, int M, int N, int K, const void* A, int lda, const voi
 // Enqueue every kernel of one executed train step (after the append).  E is the element
 // type of activations and of the matrices the products read.
 template <typename E>
-hipError_t enqueue_step(trainer* t, hipStream_t st, unsigned int* count) {
+hipError_t enqueue_step(trainer* t, hipStream_t st, unsigned int* count, bool sample) {
     const int B = (int)t->B, H = (int)t->H, Dp = (int)t->Dp, Ap = (int)t->Ap;
     const unsigned int A = t->cfg.num_actions;
     const bool mixed = t->cfg.param_dtype == RP_BF16;
@@ -351,12 +377,14 @@ hipError_t enqueue_step(trainer* t, hipStream_t st, unsigned int* count) {
     unsigned int n = 0;
 
     // sample B slots with the device-resident step counter and unpack into X = [S ; S']
-    hipError_t e = launch_sample_gather(
-        t->rp_->geom, t->rp_->cfg.seed, 0, &t->ctr->step, t->B, t->X,
-        static_cast<unsigned char*>(t->X) + (size_t)B * Dp * eb, t->Dp, t->act, t->rew, t->term,
-        t->idx, st);
-    if (e != hipSuccess) return e;
-    ++n;
+    hipError_t e = hipSuccess;
+    if (sample) {
+        e = launch_sample_gather(t->rp_->geom, t->rp_->cfg.seed, 0, &t->ctr->step, t->B, t->X,
+                                 static_cast<unsigned char*>(t->X) + (size_t)B * Dp * eb, t->Dp,
+                                 t->act, t->rew, t->term, t->idx, st);
+        if (e != hipSuccess) return e;
+        ++n;
+    }
     // forward on the 2B rows of X
     gemm<E, E, E, false, false, EPI_BIAS_RELU>(st, 2 * B, H, Dp, t->X, Dp, W1, H, t->H1, H,
                                                t->w + t->ob1, nullptr, 0); ++n;
@@ -401,7 +429,7 @@ hipError_t enqueue_step(trainer* t, hipStream_t st, unsigned int* count) {
 // Enqueue one executed step: the kernel that consumes the new experiences first.
 hipError_t enqueue_append_and_step(trainer* t, const Payload& src, hipStream_t st,
                                    unsigned int* count) {
-    if (t->fused) return enqueue_fused_step(t, src, st, count);
+    if (t->fused) return enqueue_fused_step(t, src, nullptr, st, count);
     unsigned int n = 0, k = 0;
     replay* r = t->rp_;
     if (t->cfg.appends_per_step) {
@@ -413,11 +441,37 @@ hipError_t enqueue_append_and_step(trainer* t, const Payload& src, hipStream_t s
         if (e != hipSuccess) return e;
         ++n;
     }
-    hipError_t e = t->wide ? enqueue_wide_step(t, st, &k)
-                   : t->cfg.param_dtype == RP_BF16 ? enqueue_step<bf16_t>(t, st, &k)
-                                                   : enqueue_step<float>(t, st, &k);
+    hipError_t e = t->wide ? enqueue_wide_step(t, st, &k, true)
+                   : t->cfg.param_dtype == RP_BF16 ? enqueue_step<bf16_t>(t, st, &k, true)
+                                                   : enqueue_step<float>(t, st, &k, true);
     if (count) *count = n + k;
     return e;
+}
+
+// Enqueue one step on a caller-provided batch (device arrays): no append, no sampling.
+hipError_t enqueue_batch_step(trainer* t, const Payload& batch, hipStream_t st) {
+    if (t->fused) return enqueue_fused_step(t, Payload{nullptr, nullptr, nullptr, nullptr, nullptr},
+                                            &batch, st, nullptr);
+    const unsigned int B = t->B, D = t->cfg.state_dim;
+    const unsigned int blocks = (unsigned int)(((size_t)B * D + kThreads - 1) / kThreads);
+    if (t->cfg.param_dtype == RP_BF16) {
+        typedef unsigned short E;
+        hipLaunchKernelGGL(load_batch_kernel<E>, dim3(blocks), dim3(kThreads), 0, st, B, D, t->Dp,
+                           reinterpret_cast<const E*>(batch.s), reinterpret_cast<const E*>(batch.s_next),
+                           batch.a, batch.r, batch.term, static_cast<E*>(t->X),
+                           t->wide ? t->wd.XT : nullptr, t->Bp, t->act, t->rew, t->term, t->idx);
+    } else {
+        hipLaunchKernelGGL(load_batch_kernel<float>, dim3(blocks), dim3(kThreads), 0, st, B, D, t->Dp,
+                           reinterpret_cast<const float*>(batch.s),
+                           reinterpret_cast<const float*>(batch.s_next), batch.a, batch.r, batch.term,
+                           static_cast<float*>(t->X), static_cast<float*>(nullptr), 0u, t->act,
+                           t->rew, t->term, t->idx);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return t->wide ? enqueue_wide_step(t, st, nullptr, false)
+           : t->cfg.param_dtype == RP_BF16 ? enqueue_step<bf16_t>(t, st, nullptr, false)
+                                           : enqueue_step<float>(t, st, nullptr, false);
 }
 
 // Find the payload-consuming kernel's node in the recorded graph.
@@ -669,6 +723,8 @@ rp_status train_step(trainer_t* t, const void* s, const void* s_next, const int3
         if (t->payload_node) {
             if (t->fused) {
                 t->row_args.src = src;
+                t->row_args.n_append = (unsigned int)n;
+                t->row_args.from_batch = 0;
                 t->row_args.head = rpl->head;
                 t->row_args.step = t->host_step;
                 t->row_args.size_after = (unsigned int)size_after;
@@ -694,6 +750,32 @@ rp_status train_step(trainer_t* t, const void* s, const void* s_next, const int3
     rpl->size = size_after;
     rpl->head = (rpl->head + n) % rpl->cfg.capacity;
     if (!train) return RP_SKIPPED_BURN_IN;
+    t->host_step += 1;
+    return RP_OK;
+}
+
+rp_status train_step_batch(trainer_t* t, const void* s, const void* s_next, const int32_t* a,
+                           const float* r, const uint8_t* term, void* hip_stream) {
+    RP_REQUIRE(t, "train_step_batch: null handle");
+    RP_REQUIRE(s && s_next && a && r && term, "train_step_batch: null field array");
+    replay* rpl = t->rp_;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const rp::Payload batch{static_cast<const unsigned char*>(s),
+                            static_cast<const unsigned char*>(s_next), a, r, term};
+    if (t->fused && t->graph_exec && t->payload_node) {
+        // the recorded step with its row kernel pointed at the batch: nothing appended or drawn
+        t->row_args.src = rp::Payload{nullptr, nullptr, nullptr, nullptr, nullptr};
+        t->row_args.n_append = 0;
+        t->row_args.batch = batch;
+        t->row_args.from_batch = 1;
+        t->row_args.head = rpl->head;
+        t->row_args.step = t->host_step;
+        t->row_args.size_after = (unsigned int)rpl->size;
+        RP_CHECK_HIP(hipGraphExecKernelNodeSetParams(t->graph_exec, t->payload_node, &t->payload_np));
+        RP_CHECK_HIP(hipGraphLaunch(t->graph_exec, st));
+    } else {
+        RP_CHECK_HIP(rp::enqueue_batch_step(t, batch, st));
+    }
     t->host_step += 1;
     return RP_OK;
 }

@@ -58,6 +58,8 @@ struct RowArgs {
     unsigned long long seed;
     unsigned int n_append;
     Payload src;          // this step's new experiences
+    Payload batch;        // from_batch: the batch itself, given by the caller instead of sampled
+    unsigned int from_batch;
     // ring and trainer state before this step, from the host mirror (set before every launch,
     // so the kernel can start drawing without a dependent load)
     unsigned long long head, step;
@@ -147,11 +149,15 @@ bool fused_step_supported(const train_config& cfg, const replay* rp_);
 // Dynamic LDS bytes its row kernel needs.
 // Enqueue the fused step (append + sample + gather + forward + TD + backward; weight
 // gradients + optimizer).  *count receives the number of kernels launched.
-hipError_t enqueue_fused_step(trainer* t, const Payload& src, hipStream_t st, unsigned int* count);
+// With `batch` the step trains on the caller's batch: nothing is appended or sampled.
+hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* batch, hipStream_t st,
+                              unsigned int* count);
 void* fused_rows_func();
 // Mixed-precision step on MFMA (bf16 replay states and matrix operands).
 bool wide_step_supported(const train_config& cfg, const replay* rp_);
 hipError_t wide_init_buffers(trainer* t);                       // once, after the workspace is cleared
 hipError_t wide_set_weights(trainer* t, const float* padded);   // bf16 operand copies from fp32 (host)
-hipError_t enqueue_wide_step(trainer* t, hipStream_t st, unsigned int* count);  // after the append
+// Enqueue the step's kernels after the append; `sample` = draw and gather the batch first
+// (otherwise X, XT and the per-row fields have been filled by the caller).
+hipError_t enqueue_wide_step(trainer* t, hipStream_t st, unsigned int* count, bool sample);
 }  // namespace rp

@@ -746,7 +746,7 @@ hipError_t wide_set_weights(trainer* t, const float* padded) {
 }
 
 // Enqueue every kernel of one executed step after the append.
-hipError_t enqueue_wide_step(trainer* t, hipStream_t st, unsigned int* count) {
+hipError_t enqueue_wide_step(trainer* t, hipStream_t st, unsigned int* count, bool sample) {
     const unsigned int B = t->B, Bp = t->Bp, H = t->H, Dp = t->Dp, Ap = t->Ap;
     const unsigned int D = t->cfg.state_dim, A = t->cfg.num_actions;
     WideBuffers& w = t->wd;
@@ -758,11 +758,13 @@ hipError_t enqueue_wide_step(trainer* t, hipStream_t st, unsigned int* count) {
     OptState o{t->w, t->g, t->m, t->v, t->cfg.opt, t->cfg.lr, t->cfg.beta1, t->cfg.beta2, t->cfg.eps, t->ctr};
 
     // sample B slots and unpack into X = [S ; S'] and the transposed copy of S
-    hipError_t e = launch_sample_gather(t->rp_->geom, t->rp_->cfg.seed, 0, &t->ctr->step, B, X,
-                                        X + (size_t)B * Dp, Dp, t->act, t->rew, t->term, t->idx, st,
-                                        w.XT, Bp);
-    if (e != hipSuccess) return e;
-    ++n;
+    hipError_t e = hipSuccess;
+    if (sample) {
+        e = launch_sample_gather(t->rp_->geom, t->rp_->cfg.seed, 0, &t->ctr->step, B, X,
+                                 X + (size_t)B * Dp, Dp, t->act, t->rew, t->term, t->idx, st, w.XT, Bp);
+        if (e != hipSuccess) return e;
+        ++n;
+    }
     // forward on the 2B rows
     e = launch_gemm<128, 128, 32, 2, 2, 1>(st, X, Dp, w.W1T, Dp, 2 * B, H, Dp,
                                            EpiForward{t->w + t->ob1, H1, H, 2 * B, H});

@@ -314,3 +314,66 @@ def test_trainer_rejects_bad_configurations(B):
     chain = B.Replay(64, 5, B.RP_F32, B.RP_CHAIN)
     with pytest.raises(B.ReplayError):
         B.Trainer(chain, 64, 3, 4, init_params=p)
+
+
+@pytest.mark.parametrize("dtype,H,layered", [("f32", 64, False), ("f32", 320, False),
+                                             ("bf16", 128, False), ("bf16", 128, True)])
+def test_step_on_a_given_batch_matches_the_oracle(B, dtype, H, layered):
+    """train_step_batch: the caller's batch instead of a sampled one, on each kind of step."""
+    D, A, batch = 27, 30, 70
+    rows = synth.experiences(batch, D, A, 0.1, seed=31, state_dtype=dtype)
+    pr = Pair(B, capacity=64, D=D, H=H, A=A, batch=batch, burn_in=0, seed=1, dtype=dtype,
+              appends=0, layered=layered)
+    tr = pr.trainer
+    d = {k: torch.from_numpy(v.view(np.int16) if v.dtype == np.uint16 else v).cuda()
+         for k, v in rows.items()}
+    for k in range(3):
+        p, (m, v, t, step) = tr.params(), tr.opt_state()
+        assert tr.step_batch(d["s"], d["s_next"], d["a"], d["r"], d["term"]) == 0
+        ref = oracle.train_step(pr.cfg, p, m, v, t, pr.states_f64(rows["s"]),
+                                pr.states_f64(rows["s_next"]), rows["a"], rows["r"], rows["term"])
+        last = tr.last()
+        assert np.array_equal(last["idx"], np.arange(batch))
+        assert_close(last["Q"], ref.Q, pr.rtol, "Q(s,.)")
+        assert_close(last["Qn"], ref.Qn, pr.rtol, "Q(s',.)")
+        assert_close([last["loss"]], [ref.loss], pr.rtol, "loss")
+        assert_close(tr.params(), ref.params, pr.rtol, "updated weights")
+        assert tr.opt_state()[2:] == (t + 1, step + 1)
+    assert pr.gpu_ring.state() == (0, 0, 0)
+
+
+def test_in_ram_replay_trains_on_the_same_batches_as_the_device_replay(B):
+    """The in-RAM comparison system (host sampling, host gather, per-step copy) and the
+    device-resident replay draw the same slots and run the same step: identical weights."""
+    D, H, A, batch, cap, burn = 27, 64, 30, 48, 300, 100
+    rows = synth.experiences(700, D, A, 0.05, seed=41)
+    p0 = synth.init_params(D, H, A, 5)
+    ring = B.Replay(cap, D, burn_in=burn, seed=9)
+    tr_dev = B.Trainer(ring, H, A, batch, appends_per_step=2, init_params=p0)
+    done_dev = tr_dev.steps(350, rows["s"], rows["s_next"], rows["a"], rows["r"], rows["term"])
+    # the in-RAM side needs a trainer only for the step itself: its replay stays empty
+    idle = B.Replay(8, D, seed=9)
+    tr_ram = B.Trainer(idle, H, A, batch, appends_per_step=0, init_params=p0)
+    ram = B.InRamReplay(cap, D, batch, burn_in=burn, seed=9)
+    done_ram = ram.train_steps(tr_ram, 350, 2, rows["s"], rows["s_next"], rows["a"], rows["r"],
+                               rows["term"])
+    torch.cuda.synchronize()
+    assert done_dev == done_ram == 350 - 49
+    assert ram.state() == (700 % cap, cap, 700, done_ram)
+    assert np.array_equal(tr_dev.params(), tr_ram.params())
+    assert tr_dev.last()["loss"] == tr_ram.last()["loss"]
+    # and one more step of it against the oracle
+    ref_ring = oracle.Ring(cap, D, burn_in=burn)
+    for lo in range(0, 700, 100):
+        part = synth.take(rows, lo, lo + 100)
+        ref_ring.append(part["s"], part["s_next"], part["a"], part["r"], part["term"])
+    p, (m, v, t, _) = tr_ram.params(), tr_ram.opt_state()
+    assert ram.train_step(tr_ram) == 0
+    s, sn, a, r, term = ref_ring.gather(ref_ring.sample(9, done_ram, batch))
+    cfg = oracle.make_cfg(D, H, A, batch, loss=oracle.HUBER, opt=oracle.ADAM,
+                          lr=float(np.float32(1e-4)), gamma=float(np.float32(0.99)),
+                          beta1=float(np.float32(0.9)), beta2=float(np.float32(0.999)),
+                          eps=float(np.float32(1e-8)))
+    ref = oracle.train_step(cfg, p, m, v, t, s, sn, a, r, term)
+    assert_close(tr_ram.last()["Q"], ref.Q, F32_RTOL, "Q(s,.)")
+    assert_close(tr_ram.params(), ref.params, F32_RTOL, "updated weights")

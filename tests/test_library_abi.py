@@ -17,7 +17,7 @@ def _declared_functions():
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = re.findall(r"\b([a-z_]+)\s*\([^;{]*\)\s*;", text)
-    return sorted(set(n for n in names if n.startswith(("replay_", "train_", "rp_"))))
+    return sorted(set(n for n in names if n.startswith(("replay_", "train_", "rp_", "inram_"))))
 
 
 def test_header_and_binding_agree():
@@ -78,3 +78,8 @@ def test_null_arguments_are_rejected_before_any_gpu_call():
     assert lib.train_step(None, None, None, None, None, None, 0, None) == binding.RP_EINVAL
     assert lib.train_create(None, None, None, 0, None, None) == binding.RP_EINVAL
     assert lib.replay_destroy(None) == 0 and lib.train_destroy(None) == 0
+    assert lib.train_step_batch(None, None, None, None, None, None, None) == binding.RP_EINVAL
+    assert lib.inram_create(10, 4, 0, 0, 2, None, 0, None) == binding.RP_EINVAL
+    assert lib.inram_train_step(None, None, None) == binding.RP_EINVAL
+    assert lib.inram_destroy(None) == 0
+    assert lib.inram_device_bytes(27, 128) >= 128 * (2 * 27 * 4 + 9) and lib.inram_device_bytes(0, 1) == 0
