@@ -42,8 +42,7 @@ struct RingState {
     unsigned long long head;   // slot the next experience goes to
     unsigned long long size;   // experiences held
     unsigned long long total;  // experiences ever added
-    unsigned int blocks_done;  // fused train step: workgroups that have finished
-    unsigned int pad_[9];
+    unsigned int pad_[10];
 };
 static_assert(sizeof(RingState) == 64, "RingState is one 64-byte line");
 

@@ -182,6 +182,20 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     const unsigned int nrows = min(kRows, p.B - i0);
     const unsigned int words = 2 * D + 3;
 
+    // The state that follows this step is known up front (the host mirrors it exactly): one
+    // thread stores it for the kernels and calls that read it later, off everyone's critical path.
+    if (blockIdx.x == 0 && tid == kRowThreads - 1) {
+        unsigned long long h = head + n;
+        if (h >= cap) h -= cap;
+        p.g.state->head = h;
+        p.g.state->size = size;
+        p.g.state->total = p.total_after;
+        const unsigned long long t = p.adam_t_after;
+        p.ctr->adam_t = t;
+        p.ctr->c1 = (float)(1.0 - pow((double)p.beta1, (double)t));
+        p.ctr->c2 = (float)(1.0 - pow((double)p.beta2, (double)t));
+    }
+
     // sample and gather: one 32-bit word per thread (two passes at most, D <= 64).  A drawn
     // slot that this step's append is about to overwrite is read from the payload arrays,
     // which hold its new content.
@@ -204,6 +218,19 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
                                      : reinterpret_cast<const unsigned int*>(
                                            p.g.rows + (unsigned long long)slot * p.g.row_bytes)[w];
             }
+        }
+    }
+    // The last workgroup also writes the new experiences into the ring.  No workgroup reads
+    // those slots from the ring in this launch (see above), so this can go out right away and
+    // its latency is hidden behind the rest of the kernel.
+    if (blockIdx.x == gridDim.x - 1 && n) {
+        const unsigned int rw = p.g.row_bytes >> 2;
+        for (unsigned long long e = tid; e < n * rw; e += kRowThreads) {
+            const unsigned long long k = e / rw;
+            const unsigned int w = (unsigned int)(e - k * rw);
+            unsigned long long slot = head + k;
+            if (slot >= cap) slot -= cap;
+            reinterpret_cast<unsigned int*>(p.g.rows + slot * p.g.row_bytes)[w] = staged_word(p, k, w);
         }
     }
     float w1r[16], w2r[64];
@@ -355,36 +382,6 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
         p.dZ1[(size_t)(i0 + r) * H + c] = v;
     }
 
-    // ---- the last workgroup writes the new experiences into the ring
-    if (blockIdx.x == gridDim.x - 1 && n) {
-        const unsigned int rw = p.g.row_bytes >> 2;
-        for (unsigned long long e = tid; e < n * rw; e += kRowThreads) {
-            const unsigned long long k = e / rw;
-            const unsigned int w = (unsigned int)(e - k * rw);
-            unsigned long long slot = head + k;
-            if (slot >= cap) slot -= cap;
-            reinterpret_cast<unsigned int*>(p.g.rows + slot * p.g.row_bytes)[w] = staged_word(p, k, w);
-        }
-    }
-    // Every workgroup read the ring state and the counters at its start; the last one to arrive
-    // advances them.  Nothing written here is read again inside this launch, so no fence is
-    // needed: the end of the kernel publishes it to the next one.
-    if (tid == 0) {
-        const unsigned int done = __hip_atomic_fetch_add(&p.g.state->blocks_done, 1u, __ATOMIC_RELAXED,
-                                                         __HIP_MEMORY_SCOPE_AGENT);
-        if (done == gridDim.x - 1) {
-            unsigned long long h = head + n;
-            if (h >= cap) h -= cap;
-            p.g.state->head = h;            // the device copy of the ring state follows
-            p.g.state->size = size;
-            p.g.state->total += n;
-            p.g.state->blocks_done = 0;
-            const unsigned long long t = p.ctr->adam_t + 1;
-            p.ctr->adam_t = t;
-            p.ctr->c1 = (float)(1.0 - pow((double)p.beta1, (double)t));
-            p.ctr->c2 = (float)(1.0 - pow((double)p.beta2, (double)t));
-        }
-    }
 }
 
 // ----------------------------------------------------------------------------------------
@@ -585,6 +582,8 @@ hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* bat
         a.head = r->head;
         a.step = t->host_step;
         a.size_after = (unsigned int)(after > cap ? cap : after);
+        a.total_after = r->total + a.n_append;
+        a.adam_t_after = t->host_adam_t + 1;
     }
     a.ctr = t->ctr;
     a.w = t->w;

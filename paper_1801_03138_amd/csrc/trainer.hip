@@ -474,31 +474,70 @@ hipError_t enqueue_batch_step(trainer* t, const Payload& batch, hipStream_t st) 
                                            : enqueue_step<float>(t, st, nullptr, false);
 }
 
-// Find the payload-consuming kernel's node in the recorded graph.
-hipError_t find_payload_node(trainer* t) {
-    t->payload_node = nullptr;
-    if (!t->cfg.appends_per_step && !t->fused) return hipSuccess;
-    size_t n = 0;
-    hipError_t e = hipGraphGetNodes(t->graph, nullptr, &n);
+// Find the nodes of the payload-consuming kernel in a recorded graph, in execution order (the
+// graph is a chain: one root, every node one dependent).  Finds `want` of them or fails.
+hipError_t find_payload_nodes(trainer* t, hipGraph_t graph, unsigned int want, hipGraphNode_t* nodes,
+                              hipKernelNodeParams* params) {
+    size_t n_roots = 0;
+    hipError_t e = hipGraphGetRootNodes(graph, nullptr, &n_roots);
     if (e != hipSuccess) return e;
-    std::vector<hipGraphNode_t> nodes(n);
-    e = hipGraphGetNodes(t->graph, nodes.data(), &n);
+    if (n_roots != 1) return hipErrorInvalidValue;
+    hipGraphNode_t cur = nullptr;
+    e = hipGraphGetRootNodes(graph, &cur, &n_roots);
     if (e != hipSuccess) return e;
-    for (size_t i = 0; i < n; ++i) {
+    unsigned int found = 0;
+    for (;;) {
         hipGraphNodeType type;
-        if (hipGraphNodeGetType(nodes[i], &type) != hipSuccess || type != hipGraphNodeTypeKernel)
-            continue;
-        hipKernelNodeParams np;
-        if (hipGraphKernelNodeGetParams(nodes[i], &np) != hipSuccess) continue;
-        if (np.func == t->payload_func) {
-            t->payload_node = nodes[i];
-            t->payload_np = np;
-            t->payload_np.kernelParams = t->payload_kargs;
-            t->payload_np.extra = nullptr;
-            return hipSuccess;
+        e = hipGraphNodeGetType(cur, &type);
+        if (e != hipSuccess) return e;
+        if (type == hipGraphNodeTypeKernel) {
+            hipKernelNodeParams np;
+            e = hipGraphKernelNodeGetParams(cur, &np);
+            if (e != hipSuccess) return e;
+            if (np.func == t->payload_func && found < want) {
+                nodes[found] = cur;
+                params[found] = np;
+                params[found].kernelParams = t->payload_kargs;
+                params[found].extra = nullptr;
+                ++found;
+            }
         }
+        size_t n_next = 0;
+        e = hipGraphNodeGetDependentNodes(cur, nullptr, &n_next);
+        if (e != hipSuccess) return e;
+        if (n_next == 0) break;
+        if (n_next != 1) return hipErrorInvalidValue;
+        hipGraphNode_t next = nullptr;
+        e = hipGraphNodeGetDependentNodes(cur, &next, &n_next);
+        if (e != hipSuccess) return e;
+        cur = next;
     }
-    return hipErrorNotFound;
+    return found == want ? hipSuccess : hipErrorNotFound;
+}
+
+// Whether a recorded step has a node whose argument changes from step to step.
+bool has_payload_node(const trainer* t) { return t->fused || t->cfg.appends_per_step != 0; }
+
+// Point the payload kernel's argument block at step `k` steps ahead of the host mirrors.
+void set_payload_args(trainer* t, const Payload& src, unsigned int k) {
+    const replay* r = t->rp_;
+    const uint64_t n = t->cfg.appends_per_step, cap = r->cfg.capacity;
+    const uint64_t head = (r->head + k * n) % cap;
+    const uint64_t size = r->size + k * n > cap ? cap : r->size + k * n;
+    const uint64_t total = r->total + k * n;
+    if (t->fused) {
+        t->row_args.src = src;
+        t->row_args.n_append = (unsigned int)n;
+        t->row_args.from_batch = 0;
+        t->row_args.head = head;
+        t->row_args.step = t->host_step + k;
+        t->row_args.size_after = (unsigned int)(size + n > cap ? cap : size + n);
+        t->row_args.total_after = total + n;
+        t->row_args.adam_t_after = t->host_adam_t + k + 1;
+    } else {
+        t->append_args.src = src;
+        t->append_args.pos = RingPos{head, size, total};
+    }
 }
 
 }  // namespace
@@ -585,6 +624,7 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
     t->graph_exec = nullptr;
     t->capture_stream = nullptr;
     t->host_step = 0;
+    t->host_adam_t = 0;
 
     auto fail = [&](rp_status s) {
         train_destroy(t);
@@ -639,6 +679,8 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
     t->payload_func = t->fused ? rp::fused_rows_func() : rp::append_pair_func(rp_->geom);
     t->payload_kargs[0] = t->fused ? static_cast<void*>(&t->row_args) : static_cast<void*>(&t->append_args);
     t->payload_node = nullptr;
+    t->multi_graph = nullptr;
+    t->multi_exec = nullptr;
 
     if (cfg->flags & RP_TRAIN_GRAPH) {
         // recorded once with the replay's staging area as a stand-in payload; the payload
@@ -653,8 +695,21 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
             e = hipStreamEndCapture(t->capture_stream, &t->graph);
             if (ek != hipSuccess) e = ek;
         }
-        if (e == hipSuccess) e = rp::find_payload_node(t);
+        if (e == hipSuccess && rp::has_payload_node(t))
+            e = rp::find_payload_nodes(t, t->graph, 1, &t->payload_node, &t->payload_np);
         if (e == hipSuccess) e = hipGraphInstantiate(&t->graph_exec, t->graph, nullptr, nullptr, 0);
+        // the same for kGraphSteps steps in a row
+        if (e == hipSuccess) e = hipStreamBeginCapture(t->capture_stream, hipStreamCaptureModeThreadLocal);
+        if (e == hipSuccess) {
+            hipError_t ek = hipSuccess;
+            for (unsigned int k = 0; k < rp::kGraphSteps && ek == hipSuccess; ++k)
+                ek = rp::enqueue_append_and_step(t, stand_in, t->capture_stream, nullptr);
+            e = hipStreamEndCapture(t->capture_stream, &t->multi_graph);
+            if (ek != hipSuccess) e = ek;
+        }
+        if (e == hipSuccess && rp::has_payload_node(t))
+            e = rp::find_payload_nodes(t, t->multi_graph, rp::kGraphSteps, t->multi_node, t->multi_np);
+        if (e == hipSuccess) e = hipGraphInstantiate(&t->multi_exec, t->multi_graph, nullptr, nullptr, 0);
         if (e != hipSuccess) {
             rp::set_error("train_create: recording the step graph failed: %s", hipGetErrorString(e));
             return fail(RP_EHIP);
@@ -672,6 +727,8 @@ rp_status train_destroy(trainer_t* t) {
     if (!t) return RP_OK;
     if (t->graph_exec) (void)hipGraphExecDestroy(t->graph_exec);
     if (t->graph) (void)hipGraphDestroy(t->graph);
+    if (t->multi_exec) (void)hipGraphExecDestroy(t->multi_exec);
+    if (t->multi_graph) (void)hipGraphDestroy(t->multi_graph);
     if (t->capture_stream) (void)hipStreamDestroy(t->capture_stream);
     for (auto& ev : t->pin_event)
         if (ev) (void)hipEventDestroy(ev);
@@ -721,17 +778,7 @@ rp_status train_step(trainer_t* t, const void* s, const void* s_next, const int3
                                            src.s, src.s_next, src.a, src.r, src.term, st));
     } else if (t->graph_exec) {
         if (t->payload_node) {
-            if (t->fused) {
-                t->row_args.src = src;
-                t->row_args.n_append = (unsigned int)n;
-                t->row_args.from_batch = 0;
-                t->row_args.head = rpl->head;
-                t->row_args.step = t->host_step;
-                t->row_args.size_after = (unsigned int)size_after;
-            } else {
-                t->append_args.src = src;
-                t->append_args.pos = rp::RingPos{rpl->head, rpl->size, rpl->total};
-            }
+            rp::set_payload_args(t, src, 0);
             RP_CHECK_HIP(hipGraphExecKernelNodeSetParams(t->graph_exec, t->payload_node, &t->payload_np));
         }
         RP_CHECK_HIP(hipGraphLaunch(t->graph_exec, st));
@@ -751,6 +798,7 @@ rp_status train_step(trainer_t* t, const void* s, const void* s_next, const int3
     rpl->head = (rpl->head + n) % rpl->cfg.capacity;
     if (!train) return RP_SKIPPED_BURN_IN;
     t->host_step += 1;
+    t->host_adam_t += 1;
     return RP_OK;
 }
 
@@ -771,12 +819,15 @@ rp_status train_step_batch(trainer_t* t, const void* s, const void* s_next, cons
         t->row_args.head = rpl->head;
         t->row_args.step = t->host_step;
         t->row_args.size_after = (unsigned int)rpl->size;
+        t->row_args.total_after = rpl->total;
+        t->row_args.adam_t_after = t->host_adam_t + 1;
         RP_CHECK_HIP(hipGraphExecKernelNodeSetParams(t->graph_exec, t->payload_node, &t->payload_np));
         RP_CHECK_HIP(hipGraphLaunch(t->graph_exec, st));
     } else {
         RP_CHECK_HIP(rp::enqueue_batch_step(t, batch, st));
     }
     t->host_step += 1;
+    t->host_adam_t += 1;
     return RP_OK;
 }
 
@@ -784,11 +835,38 @@ rp_status train_steps(trainer_t* t, uint64_t count, const void* s, const void* s
                       const int32_t* a, const float* r, const uint8_t* term, int src_is_device,
                       void* hip_stream, uint64_t* executed) {
     RP_REQUIRE(t, "train_steps: null handle");
-    const uint64_t n = t->cfg.appends_per_step;
-    const size_t sb = t->rp_->geom.state_bytes;
+    replay* rpl = t->rp_;
+    const uint64_t n = t->cfg.appends_per_step, K = rp::kGraphSteps;
+    const size_t sb = rpl->geom.state_bytes;
+    RP_REQUIRE(n == 0 || (s && s_next && a && r && term), "train_steps: null field array for the append");
     uint64_t done = 0;
-    for (uint64_t k = 0; k < count; ++k) {
+    for (uint64_t k = 0; k < count;) {
         const uint64_t o = k * n;
+        // kGraphSteps steps in one graph launch when all of them train and their new
+        // experiences are already in device memory
+        if (t->multi_exec && count - k >= K && (n == 0 || src_is_device) &&
+            rpl->total + n >= rpl->cfg.burn_in && rpl->size + n >= 1) {
+            for (unsigned int j = 0; j < K && rp::has_payload_node(t); ++j) {
+                const uint64_t oj = o + j * n;
+                const rp::Payload src =
+                    n ? rp::Payload{static_cast<const unsigned char*>(s) + oj * sb,
+                                    static_cast<const unsigned char*>(s_next) + oj * sb, a + oj, r + oj,
+                                    term + oj}
+                      : rp::Payload{nullptr, nullptr, nullptr, nullptr, nullptr};
+                rp::set_payload_args(t, src, j);
+                RP_CHECK_HIP(hipGraphExecKernelNodeSetParams(t->multi_exec, t->multi_node[j], &t->multi_np[j]));
+            }
+            RP_CHECK_HIP(hipGraphLaunch(t->multi_exec, static_cast<hipStream_t>(hip_stream)));
+            const uint64_t cap = rpl->cfg.capacity;
+            rpl->total += K * n;
+            rpl->size = rpl->size + K * n > cap ? cap : rpl->size + K * n;
+            rpl->head = (rpl->head + K * n) % cap;
+            t->host_step += K;
+            t->host_adam_t += K;
+            done += K;
+            k += K;
+            continue;
+        }
         const rp_status st =
             n ? train_step(t, static_cast<const unsigned char*>(s) + o * sb,
                            static_cast<const unsigned char*>(s_next) + o * sb, a + o, r + o,
@@ -799,6 +877,7 @@ rp_status train_steps(trainer_t* t, uint64_t count, const void* s, const void* s
             return st;
         }
         done += st == RP_OK;
+        ++k;
     }
     if (executed) *executed = done;
     return RP_OK;
@@ -870,6 +949,7 @@ rp_status train_set_state(trainer_t* t, const float* params, const float* m, con
     c.step = step;
     RP_CHECK_HIP(hipMemcpy(t->ctr, &c, sizeof(c), hipMemcpyHostToDevice));
     t->host_step = step;
+    t->host_adam_t = adam_t;
     if (t->wb) {
         hipLaunchKernelGGL(rp::to_bf16_kernel, dim3((t->n_padded + rp::kThreads - 1) / rp::kThreads),
                            dim3(rp::kThreads), 0, nullptr, (unsigned int)t->n_padded, t->w, t->wb);

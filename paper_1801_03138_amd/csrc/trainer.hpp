@@ -64,6 +64,7 @@ struct RowArgs {
     // so the kernel can start drawing without a dependent load)
     unsigned long long head, step;
     unsigned int size_after;     // experiences held once this step's append is in
+    unsigned long long total_after, adam_t_after;   // experiences ever added / Adam steps, after this step
     TrainCounters* ctr;
     const float* w;       // padded parameters
     const float* w2t;     // W2 transposed
@@ -90,6 +91,7 @@ struct WideBuffers {
     float* part1;                            // K-split partials [splits][H][Dx] of [dW1^T | db1]
 };
 
+constexpr unsigned int kGraphSteps = 8;       // train steps per launch of the multi-step graph
 constexpr unsigned int kPinSlots = 64;       // pinned host slots for host-sourced payloads
 constexpr unsigned int kPinGroup = 16;       // slots per completion event
 
@@ -124,6 +126,7 @@ struct trainer {
     hipStream_t capture_stream;
     unsigned int kernels_per_step;
     uint64_t host_step;              // mirror of ctr->step
+    uint64_t host_adam_t;            // mirror of ctr->adam_t
     // The kernel that consumes the step's new experiences (fused row kernel, or the append
     // kernel of the layered step): host copy of its argument block, and its node in the graph,
     // whose argument is replaced before every launch.
@@ -133,6 +136,12 @@ struct trainer {
     void* payload_kargs[1];
     hipGraphNode_t payload_node;
     hipKernelNodeParams payload_np;
+    // kGraphSteps consecutive steps recorded as one graph, for train_steps: one launch (and one
+    // launch gap on the GPU) per kGraphSteps steps; each step's payload kernel has its own node.
+    hipGraph_t multi_graph;
+    hipGraphExec_t multi_exec;
+    hipGraphNode_t multi_node[rp::kGraphSteps];
+    hipKernelNodeParams multi_np[rp::kGraphSteps];
     // Host-sourced payloads are copied into a ring of pinned, device-mapped host slots that the
     // kernel reads directly; an event per group of slots tells when a group may be reused.
     unsigned char* pin_host;
