@@ -32,6 +32,11 @@ P_CFG = dict(capacity=1_000_000, D=27, A=30, B=128, H=256, burn_in=50_000, p_ter
 W_CFG = dict(capacity=4_000_000, D=27, A=30, B=4096, H=1024, p_term=0.005, lr=1e-4, appends=64)
 L_CFG = dict(capacity=200_000, D=84 * 84 * 4, p_term=0.001)
 GATHER_BATCHES = [32, 128, 512, 2048, 8192, 65536]
+# HBM bytes per launch of sample_gather_pair_kernel<4, 1> at batch 65,536 from rocprofv3 PMC runs
+# (FETCH_SIZE 8,182.8 KiB x 2.000 + WRITE_SIZE 14,720.0 KiB x 1.000, the factors being what the
+# same counters read for the 256 MiB plain copy of the copy_calibration leg); the runs and the
+# table are in profiles/gather_kernels_hbm_traffic_pmc.txt.  Set to None when that kernel changes.
+GATHER_65536_HBM_BYTES = (8182.8 * 2.000 + 14720.0 * 1.000) * 1024
 
 
 def log(*a):
@@ -135,6 +140,21 @@ def leg_gather_sweep(B, synth, reps):
         out.append({"batch": batch, "us_per_call": 1e3 * ms, "us_per_call_host_launched": 1e3 * ms_host,
                     "alg_bytes": alg, "GBps": alg / (ms * 1e-3) / 1e9})
     return out
+
+
+def leg_copy_calibration(reps):
+    """A plain device-to-device copy of known size (256 MiB read + 256 MiB written per launch):
+    the "achievable" bandwidth next to the 8 TB/s peak, and the kernel whose FETCH_SIZE /
+    WRITE_SIZE readings scale the HBM-traffic counters of the other kernels."""
+    import torch
+    n = 64 * 1024 * 1024
+    a = torch.empty(n, dtype=torch.float32, device="cuda")
+    b = torch.ones(n, dtype=torch.float32, device="cuda")
+    for _ in range(3):
+        a.copy_(b)
+    ms = event_time_ms(lambda k: a.copy_(b), reps)
+    return {"bytes_read": 4 * n, "bytes_written": 4 * n, "us_per_call": 1e3 * ms,
+            "GBps": 8 * n / (ms * 1e-3) / 1e9}
 
 
 def leg_large_state(B, reps):
@@ -280,7 +300,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10_000)
     ap.add_argument("--warmup", type=int, default=500)
-    ap.add_argument("--legs", default="p,pfull,phost,inram,gather,large,wide,cpu")
+    ap.add_argument("--legs", default="p,pfull,phost,inram,gather,copy,large,wide,cpu")
     ap.add_argument("--gather-reps", type=int, default=1000)
     ap.add_argument("--wide-steps", type=int, default=200)
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
@@ -326,8 +346,14 @@ def main():
         roofline = {"kernel": "sample_gather_pair_kernel<4>", "workload": "gather sweep, batch %d, "
                     "capacity 1,000,000, 27 fp32 per state" % g["batch"], "bound": "hbm",
                     "achieved": g["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": g["GBps"] / HBM_PEAK_GBS, "traffic": None,
+                    "frac": g["GBps"] / HBM_PEAK_GBS, "traffic": GATHER_65536_HBM_BYTES,
                     "alg_bytes_per_launch": g["alg_bytes"], "us_per_launch": g["us_per_call"]}
+    if "copy" in legs:
+        log("[bench] plain device-to-device copy, 256 MiB ...")
+        out["copy_calibration"] = leg_copy_calibration(20)
+        log("[bench]   %.1f GB/s" % out["copy_calibration"]["GBps"])
+        if roofline is not None:
+            roofline["frac_of_copy_bandwidth"] = roofline["achieved"] / out["copy_calibration"]["GBps"]
     if "large" in legs:
         log("[bench] large-state gather (200,000 x 84x84x4 uint8, one state per slot) ...")
         out["large_state_gather"] = leg_large_state(B, max(50, args.gather_reps // 5))

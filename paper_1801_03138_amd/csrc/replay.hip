@@ -206,59 +206,56 @@ __device__ __forceinline__ float unit_from_u8(unsigned int b) {
 }
 
 // ---------------------------------------------------------------------------------------
-// Sample + gather + unpack, PAIR layout.  A block draws the slot numbers of R batch rows,
-// pulls those rows into LDS with 16-byte loads (a 256-byte row is one load by 16 lanes; every
-// thread keeps up to four loads in flight), then writes each output tensor as contiguous,
-// coalesced runs.  lane_shift = log2 of the lanes that cooperate on one row.
+// Sample + gather + unpack, PAIR layout.  A block handles R = U * (256 >> lane_shift) batch
+// rows.  The lanes that cooperate on a row (2^lane_shift of them, one 16-byte piece each for a
+// 256-byte row) all draw the row's slot number themselves -- ten Philox rounds cost less than
+// a trip through LDS and a barrier -- and fetch their pieces of U rows with all loads in
+// flight at once; the rows go to LDS and then leave as contiguous, coalesced runs per output
+// tensor.
 // ---------------------------------------------------------------------------------------
-template <int ELEM>
+template <int ELEM, int U>
 __global__ __launch_bounds__(kThreads) void sample_gather_pair_kernel(
     RingGeom g, unsigned long long seed, unsigned long long step_value,
-    const unsigned long long* __restrict__ step_ptr, unsigned int batch, unsigned int R,
+    const unsigned long long* __restrict__ step_ptr, unsigned int size_value, unsigned int batch,
     unsigned int lane_shift, void* __restrict__ out_s, void* __restrict__ out_s_next,
     unsigned int out_ld, int* __restrict__ out_a, float* __restrict__ out_r,
     unsigned char* __restrict__ out_term, unsigned int* __restrict__ out_idx,
     void* __restrict__ out_s_t, unsigned int out_t_ld) {
     extern __shared__ uint4 smem[];
-    unsigned int* idx_s = reinterpret_cast<unsigned int*>(smem);               // R <= 64 entries
-    unsigned char* rows_s = reinterpret_cast<unsigned char*>(smem) + 256;
+    unsigned char* rows_s = reinterpret_cast<unsigned char*>(smem);
 
+    // callers that mirror the ring state pass the size by value: no dependent load up front
     const unsigned long long step = step_ptr ? *step_ptr : step_value;
-    const unsigned int size = (unsigned int)g.state->size;
+    const unsigned int size = size_value ? size_value : (unsigned int)g.state->size;
+    const unsigned int rows_per_pass = kThreads >> lane_shift;
+    const unsigned int R = U * rows_per_pass;
     const unsigned int i0 = blockIdx.x * R;
     const unsigned int nrows = min(R, batch - i0);
-
-    if (threadIdx.x < nrows) {
-        const unsigned int i = i0 + threadIdx.x;
-        const unsigned int p = uniform_draw(seed, step, i, size);
-        idx_s[threadIdx.x] = p;
-        if (out_idx) out_idx[i] = p;
-    }
-    __syncthreads();
 
     {
         const unsigned int V = g.row_bytes >> 4;             // 16-byte vectors per row
         const unsigned int lanes = 1u << lane_shift;         // lanes per row (power of two)
-        const unsigned int rows_per_pass = kThreads >> lane_shift;
         const unsigned int part0 = threadIdx.x & (lanes - 1u);
         const unsigned int rsub = threadIdx.x >> lane_shift;
+        const unsigned char* src[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            unsigned int rr = rsub + u * rows_per_pass;
+            rr = rr < nrows ? rr : 0u;   // a row past the end re-reads row 0; not stored
+            const unsigned int p = uniform_draw(seed, step, i0 + rr, size);
+            src[u] = g.rows + (unsigned long long)p * g.row_bytes;
+            if (out_idx && part0 == 0 && rsub + u * rows_per_pass < nrows) out_idx[i0 + rr] = p;
+        }
         for (unsigned int part = part0; part < V; part += lanes) {
-            for (unsigned int row = rsub; row < nrows; row += 4 * rows_per_pass) {
-                // (a native vector type: an array of HIP's uint4 struct would live in scratch memory)
-                u32x4 val[4];
+            // (a native vector type: an array of HIP's uint4 struct would live in scratch memory)
+            u32x4 val[U];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    unsigned int rr = row + u * rows_per_pass;
-                    rr = rr < nrows ? rr : row;   // a row past the end re-reads `row`; not stored
-                    val[u] = reinterpret_cast<const u32x4*>(
-                        g.rows + (unsigned long long)idx_s[rr] * g.row_bytes)[part];
-                }
+            for (int u = 0; u < U; ++u) val[u] = reinterpret_cast<const u32x4*>(src[u])[part];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const unsigned int rr = row + u * rows_per_pass;
-                    if (rr < nrows)
-                        reinterpret_cast<u32x4*>(rows_s + (size_t)rr * g.row_bytes)[part] = val[u];
-                }
+            for (int u = 0; u < U; ++u) {
+                const unsigned int rr = rsub + u * rows_per_pass;
+                if (rr < nrows)
+                    reinterpret_cast<u32x4*>(rows_s + (size_t)rr * g.row_bytes)[part] = val[u];
             }
         }
     }
@@ -287,10 +284,10 @@ __global__ __launch_bounds__(kThreads) void sample_gather_pair_kernel(
             }
         }
     }
-    if (threadIdx.x < nrows) {
-        const unsigned int i = i0 + threadIdx.x;
+    for (unsigned int row = threadIdx.x; row < nrows; row += kThreads) {
+        const unsigned int i = i0 + row;
         const unsigned int* meta =
-            reinterpret_cast<const unsigned int*>(rows_s + threadIdx.x * g.row_bytes + g.meta_off);
+            reinterpret_cast<const unsigned int*>(rows_s + (size_t)row * g.row_bytes + g.meta_off);
         if (out_a) out_a[i] = (int)meta[0];
         if (out_r) out_r[i] = __uint_as_float(meta[1]);
         if (out_term) out_term[i] = (unsigned char)meta[2];
@@ -308,7 +305,8 @@ __global__ __launch_bounds__(kThreads) void sample_gather_pair_kernel(
 template <int ELEM, int MODE>
 __global__ __launch_bounds__(kThreads) void sample_gather_chain_kernel(
     RingGeom g, unsigned long long seed, unsigned long long step_value,
-    const unsigned long long* __restrict__ step_ptr, unsigned int batch, unsigned int chunks,
+    const unsigned long long* __restrict__ step_ptr, unsigned int size_value,
+    unsigned long long head_value, unsigned int batch, unsigned int chunks,
     void* __restrict__ out_s, void* __restrict__ out_s_next, unsigned int out_ld,
     int* __restrict__ out_a, float* __restrict__ out_r, unsigned char* __restrict__ out_term,
     unsigned int* __restrict__ out_idx) {
@@ -319,7 +317,8 @@ __global__ __launch_bounds__(kThreads) void sample_gather_chain_kernel(
     if (i >= batch) return;
 
     const unsigned long long step = step_ptr ? *step_ptr : step_value;
-    const unsigned long long size = g.state->size, head = g.state->head;
+    const unsigned long long size = size_value ? size_value : g.state->size;
+    const unsigned long long head = size_value ? head_value : g.state->head;
     unsigned long long oldest = head + g.capacity - size;
     if (oldest >= g.capacity) oldest -= g.capacity;
     unsigned long long p = oldest + uniform_draw(seed, step, i, (unsigned int)(size - 1));
@@ -456,28 +455,31 @@ hipError_t launch_sample_gather(const RingGeom& g, unsigned long long seed,
                                 const unsigned long long* step_ptr, unsigned int batch,
                                 void* out_s, void* out_s_next, unsigned int out_ld, int* out_a,
                                 float* out_r, unsigned char* out_term, unsigned int* out_idx,
-                                hipStream_t stream, void* out_s_t, unsigned int out_t_ld) {
+                                hipStream_t stream, void* out_s_t, unsigned int out_t_ld,
+                                unsigned int size_value, unsigned long long head_value) {
     if (out_s_t && (g.layout != RP_PAIR || g.elem_bytes == 1)) return hipErrorInvalidValue;
     if (g.layout == RP_PAIR) {
-        // rows per block: 16 keeps eight blocks resident per CU and measured fastest at batch
-        // 65,536 (4..64 tried); small batches take 4 so that more CUs take part
-        unsigned int R = batch >= 2048 ? 16 : 4;
-        while (R > 1 && (size_t)R * g.row_bytes > kMaxPairRowBytes) R >>= 1;
+        // lanes per row: enough for one 16-byte piece each, at most the whole block
         const unsigned int V = g.row_bytes >> 4;
         unsigned int lane_shift = 0;
         while ((1u << lane_shift) < V && lane_shift < 8) ++lane_shift;
+        const unsigned int rows_per_pass = kThreads >> lane_shift;
+        // rows per thread: 1, 2 and 4 were tried on 256-byte rows at batches 2,048 to 65,536;
+        // 1 (sixteen rows per block, eight blocks resident per CU) was fastest throughout
+        const unsigned int U = 1;
+        const unsigned int R = U * rows_per_pass;
         const unsigned int blocks = (batch + R - 1) / R;
-        const size_t lds = 256 + (size_t)R * g.row_bytes;
-#define RP_LAUNCH_PAIR(E)                                                                         \
-    hipLaunchKernelGGL(sample_gather_pair_kernel<E>, dim3(blocks), dim3(kThreads), lds, stream, g, \
-                       seed, step_value, step_ptr, batch, R, lane_shift, out_s, out_s_next,        \
-                       out_ld, out_a, out_r, out_term, out_idx, out_s_t, out_t_ld)
+        const size_t lds = (size_t)R * g.row_bytes;
+#define RP_LAUNCH_PAIR(E, UU)                                                                       \
+    hipLaunchKernelGGL((sample_gather_pair_kernel<E, UU>), dim3(blocks), dim3(kThreads), lds, stream, \
+                       g, seed, step_value, step_ptr, size_value, batch, lane_shift, out_s,          \
+                       out_s_next, out_ld, out_a, out_r, out_term, out_idx, out_s_t, out_t_ld)
         if (g.elem_bytes == 4)
-            RP_LAUNCH_PAIR(4);
+            RP_LAUNCH_PAIR(4, 1);
         else if (g.elem_bytes == 2)
-            RP_LAUNCH_PAIR(2);
+            RP_LAUNCH_PAIR(2, 1);
         else
-            RP_LAUNCH_PAIR(1);
+            RP_LAUNCH_PAIR(1, 1);
 #undef RP_LAUNCH_PAIR
     } else {
         const unsigned int vectors = (g.state_bytes + 15u) >> 4;
@@ -490,7 +492,8 @@ hipError_t launch_sample_gather(const RingGeom& g, unsigned long long seed,
                          aligned16(out_s_next);
 #define RP_LAUNCH_CHAIN(E, MODE)                                                                 \
     hipLaunchKernelGGL((sample_gather_chain_kernel<E, MODE>), dim3(blocks), dim3(kThreads), 0,    \
-                       stream, g, seed, step_value, step_ptr, batch, chunks, out_s, out_s_next,   \
+                       stream, g, seed, step_value, step_ptr, size_value, head_value, batch,      \
+                       chunks, out_s, out_s_next,                                                 \
                        out_ld, out_a, out_r, out_term, out_idx)
         if (g.elem_bytes == 4) {
             if (vec) RP_LAUNCH_CHAIN(4, 1); else RP_LAUNCH_CHAIN(4, 2);
@@ -631,7 +634,8 @@ rp_status replay_sample_gather(replay_t* rp_, uint64_t step, uint32_t batch, voi
     if (rp_->size < (rp_->cfg.layout == RP_CHAIN ? 2u : 1u)) return RP_SKIPPED_BURN_IN;
     RP_CHECK_HIP(rp::launch_sample_gather(rp_->geom, rp_->cfg.seed, step, nullptr, batch, out_s,
                                           out_s_next, rp_->cfg.state_dim, out_a, out_r, out_term,
-                                          out_idx, static_cast<hipStream_t>(hip_stream)));
+                                          out_idx, static_cast<hipStream_t>(hip_stream), nullptr, 0,
+                                          (unsigned int)rp_->size, rp_->head));
     return RP_OK;
 }
 

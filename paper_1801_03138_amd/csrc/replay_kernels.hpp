@@ -22,12 +22,15 @@ void* append_pair_func(const RingGeom& g);   // the __global__ function, as hipL
 // out_s / out_s_next in elements (>= D); columns D..out_ld-1 are not written.
 // out_s_t (PAIR rings with 2- or 4-byte elements; may be null) receives the old states
 // transposed: element (column, i) at out_s_t[column * out_t_ld + i].
+// size_value, head_value: the number of experiences held and the write position, when the
+// caller mirrors them; size_value = 0 = read both from the device-resident ring state.
 hipError_t launch_sample_gather(const RingGeom& g, unsigned long long seed,
                                 unsigned long long step_value,
                                 const unsigned long long* step_ptr, unsigned int batch,
                                 void* out_s, void* out_s_next, unsigned int out_ld, int* out_a,
                                 float* out_r, unsigned char* out_term, unsigned int* out_idx,
                                 hipStream_t stream, void* out_s_t = nullptr,
-                                unsigned int out_t_ld = 0);
+                                unsigned int out_t_ld = 0, unsigned int size_value = 0,
+                                unsigned long long head_value = 0);
 
 }  // namespace rp
