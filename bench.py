@@ -142,6 +142,44 @@ def leg_gather_sweep(B, synth, reps):
     return out
 
 
+def leg_append_sweep(B, synth):
+    """Time to add experiences as a function of the update size (the paper's update-size figure):
+    n experiences per replay_append call, from device arrays (kernel time, events) and from host
+    arrays (wall clock per call including the staging copies), on the paper-shaped ring."""
+    import torch
+    c = P_CFG
+    ring = B.Replay(c["capacity"], c["D"], seed=0, max_append=65536)
+    rows = synth.experiences(65536, c["D"], c["A"], c["p_term"], seed=3)
+    d = dev_rows(rows)
+    row_alg = 2 * (2 * c["D"] + 3) * 4          # 228 B read from the source arrays + 228 B written
+    # the HIP runtime grows its pools during the first ~thousand launches of a process
+    # (individual calls then take hundreds of microseconds): get past that before timing
+    one = [rows[k][:1] for k in ("s", "s_next", "a", "r", "term")]
+    for _ in range(2000):
+        ring.append(*one)
+    torch.cuda.synchronize()
+    out = []
+    for n in (1, 16, 256, 2000, 16384, 65536):
+        dv = [d[k][:n] for k in ("s", "s_next", "a", "r", "term")]
+        hv = [rows[k][:n] for k in ("s", "s_next", "a", "r", "term")]
+        for _ in range(3):
+            ring.append(*dv)
+        reps = 200 if n <= 2000 else 50
+        ms_dev = graph_time_ms(lambda k: ring.append(*dv), 20, max(1, reps // 20))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            ring.append(*hv)
+        torch.cuda.synchronize()
+        ms_host = 1e3 * (time.perf_counter() - t0) / reps
+        out.append({"update_size": n, "device_src_us_per_call": 1e3 * ms_dev,
+                    "device_src_us_per_experience": 1e3 * ms_dev / n,
+                    "device_src_GBps": n * row_alg / (ms_dev * 1e-3) / 1e9,
+                    "host_src_us_per_call": 1e3 * ms_host,
+                    "host_src_us_per_experience": 1e3 * ms_host / n})
+    return out
+
+
 def leg_copy_calibration(reps):
     """A plain device-to-device copy of known size (256 MiB read + 256 MiB written per launch):
     the "achievable" bandwidth next to the 8 TB/s peak, and the kernel whose FETCH_SIZE /
@@ -300,7 +338,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10_000)
     ap.add_argument("--warmup", type=int, default=500)
-    ap.add_argument("--legs", default="p,pfull,phost,inram,gather,copy,large,wide,cpu")
+    ap.add_argument("--legs", default="p,pfull,phost,inram,gather,append,copy,large,wide,cpu")
     ap.add_argument("--gather-reps", type=int, default=1000)
     ap.add_argument("--wide-steps", type=int, default=200)
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
@@ -348,6 +386,14 @@ def main():
                     "achieved": g["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": g["GBps"] / HBM_PEAK_GBS, "traffic": GATHER_65536_HBM_BYTES,
                     "alg_bytes_per_launch": g["alg_bytes"], "us_per_launch": g["us_per_call"]}
+    if "append" in legs:
+        log("[bench] append: time per experience against the update size ...")
+        out["append_sweep"] = leg_append_sweep(B, synth)
+        for g in out["append_sweep"]:
+            log("[bench]   n=%-6d device src %8.2f us/call %9.4f us/exp %7.1f GB/s | host src %9.2f us/call "
+                "%9.4f us/exp" % (g["update_size"], g["device_src_us_per_call"],
+                                  g["device_src_us_per_experience"], g["device_src_GBps"],
+                                  g["host_src_us_per_call"], g["host_src_us_per_experience"]))
     if "copy" in legs:
         log("[bench] plain device-to-device copy, 256 MiB ...")
         out["copy_calibration"] = leg_copy_calibration(20)

@@ -12,8 +12,9 @@
  * Conventions
  *  - Ownership: the caller allocates every device buffer (ring storage,
  *    trainer workspace, sample outputs) and keeps it alive until the matching
- *    *_destroy call.  The library owns only its host-side handles, one small
- *    pinned host buffer per trainer, and its HIP graph objects.
+ *    *_destroy call.  The library owns only its host-side handles, pinned host
+ *    buffers for host-sourced experiences (a few times max_append rows per replay,
+ *    a few dozen steps' worth per trainer), and its HIP graph objects.
  *  - Streams: `hip_stream` is a hipStream_t passed as void* (NULL = the null
  *    stream).  All calls are asynchronous on that stream except the ones marked
  *    "synchronises", which exist for tests and inspection.  One handle must be
@@ -98,8 +99,9 @@ rp_status replay_destroy(replay_t* rp);
  * of the storage wraps to slot 0.  Arrays are structure-of-arrays, row-major:
  * s[n*D], s_next[n*D] of the state type (s_next is ignored and may be NULL for
  * RP_CHAIN), a[n], r[n], term[n] (any non-zero byte = terminal).
- * src_is_device = 0: host pointers, moved through the staging area in pieces of
- * max_append rows; 1: device pointers, read directly by the append kernel and
+ * src_is_device = 0: host pointers, copied into pinned memory in pieces of
+ * max_append rows, from where the append kernel reads them (the arrays may be
+ * reused as soon as the call returns); 1: device pointers, read directly by the append kernel and
  * to be left untouched until the stream reaches it.  n = 0 is a no-op; n >
  * capacity is RP_EINVAL.
  */

@@ -103,4 +103,14 @@ struct replay {
     unsigned char* stage_term;
     // host mirror of the ring state
     uint64_t head, size, total;
+    // Host-sourced appends: the caller's arrays are copied into one of kHostSlots pinned,
+    // device-mapped slots (max_append rows each, structure of arrays) that the append kernel
+    // reads in place; an event per slot tells when it may be reused.
+    static constexpr unsigned int kHostSlots = 4;
+    unsigned char* pin_host;
+    unsigned char* pin_dev;
+    size_t pin_slot_bytes, pin_off_s_next, pin_off_a, pin_off_r, pin_off_term;
+    uint64_t pin_next;
+    hipEvent_t pin_event[kHostSlots];
+    bool pin_live[kHostSlots];
 };

@@ -165,6 +165,49 @@ __global__ __launch_bounds__(kThreads) void append_pair_kernel(AppendArgs p) {
     }
 }
 
+// The same for large appends of 2- or 4-byte state elements: a block composes 32 rows in LDS.
+// Each source array is read as one contiguous run (consecutive lanes, consecutive elements),
+// and the finished rows leave as 16-byte vectors, sixteen lanes per 256-byte row.
+template <typename E>
+__global__ __launch_bounds__(kThreads) void append_pair_bulk_kernel(AppendArgs p) {
+    constexpr unsigned int kRows = 32;
+    extern __shared__ uint4 bulk_smem[];
+    unsigned char* rows_s = reinterpret_cast<unsigned char*>(bulk_smem);
+    const RingGeom& g = p.g;
+    const unsigned long long n = p.n, head = p.pos.head;
+    store_state_after(g, p.pos, n);
+    const unsigned long long row0 = (unsigned long long)blockIdx.x * kRows;
+    const unsigned int nrows = (unsigned int)(n - row0 < kRows ? n - row0 : kRows);
+    const unsigned int D = g.state_dim, rb = g.row_bytes;
+    const E* __restrict__ s = reinterpret_cast<const E*>(p.src.s) + row0 * D;
+    const E* __restrict__ sn = reinterpret_cast<const E*>(p.src.s_next) + row0 * D;
+    // padding first (bytes between the states and the scalars, and after them)
+    for (unsigned int e = threadIdx.x; e < nrows * (rb >> 2); e += kThreads)
+        reinterpret_cast<unsigned int*>(rows_s)[e] = 0u;
+    __syncthreads();
+    for (unsigned int e = threadIdx.x; e < nrows * D; e += kThreads) {
+        const unsigned int k = e / D, c = e - k * D;
+        E* row = reinterpret_cast<E*>(rows_s + (size_t)k * rb);
+        row[c] = s[e];
+        row[D + c] = sn[e];
+    }
+    for (unsigned int k = threadIdx.x; k < nrows; k += kThreads) {
+        unsigned int* meta = reinterpret_cast<unsigned int*>(rows_s + (size_t)k * rb + g.meta_off);
+        meta[0] = (unsigned int)p.src.a[row0 + k];
+        meta[1] = __float_as_uint(p.src.r[row0 + k]);
+        meta[2] = p.src.term[row0 + k] ? 1u : 0u;
+    }
+    __syncthreads();
+    const unsigned int V = rb >> 4;
+    for (unsigned int e = threadIdx.x; e < nrows * V; e += kThreads) {
+        const unsigned int k = e / V, v = e - k * V;
+        unsigned long long slot = head + row0 + k;
+        if (slot >= g.capacity) slot -= g.capacity;
+        reinterpret_cast<u32x4*>(g.rows + slot * rb)[v] =
+            reinterpret_cast<const u32x4*>(rows_s + (size_t)k * rb)[v];
+    }
+}
+
 // CHAIN: one block per experience copies the state into its slot and the three scalars
 // into the side arrays.  VEC: state_bytes is a multiple of 16 and the source is 16-byte aligned.
 template <bool VEC>
@@ -433,6 +476,17 @@ hipError_t launch_append(const RingGeom& g, const RingPos& pos, unsigned long lo
     const unsigned char* snp = static_cast<const unsigned char*>(s_next);
     if (g.layout == RP_PAIR) {
         AppendArgs args = make_append_args(g, pos, n, Payload{sp, snp, a, r, term});
+        if (n >= 1024 && g.elem_bytes >= 2 && g.row_bytes <= 1024) {
+            const unsigned int blocks = (unsigned int)((n + 31) / 32);
+            const size_t lds = 32 * (size_t)g.row_bytes;
+            if (g.elem_bytes == 4)
+                hipLaunchKernelGGL(append_pair_bulk_kernel<unsigned int>, dim3(blocks), dim3(kThreads),
+                                   lds, stream, args);
+            else
+                hipLaunchKernelGGL(append_pair_bulk_kernel<unsigned short>, dim3(blocks),
+                                   dim3(kThreads), lds, stream, args);
+            return hipGetLastError();
+        }
         const unsigned int blocks = append_blocks(args);
         void* kargs[] = {&args};
         hipError_t e = hipLaunchKernel(append_pair_func(g), dim3(blocks), dim3(kThreads), kargs, 0,
@@ -572,11 +626,46 @@ rp_status replay_create(const replay_config* cfg, void* dev_storage, size_t byte
     g.term = base + L.off_term;
     g.state = reinterpret_cast<rp::RingState*>(base);
     rp_->head = rp_->size = rp_->total = 0;
+    // pinned slots for host-sourced appends
+    {
+        const size_t m = cfg->max_append, sb = L.state_bytes;
+        size_t o = 0;
+        auto take = [&](size_t nbytes) { size_t at = o; o = rp::align_up(o + nbytes, 16); return at; };
+        take(m * sb);
+        rp_->pin_off_s_next = take(cfg->layout == RP_PAIR ? m * sb : 0);
+        rp_->pin_off_a = take(m * 4);
+        rp_->pin_off_r = take(m * 4);
+        rp_->pin_off_term = take(m);
+        rp_->pin_slot_bytes = rp::align_up(o, 256);
+        rp_->pin_host = rp_->pin_dev = nullptr;
+        rp_->pin_next = 0;
+        for (auto& ev : rp_->pin_event) ev = nullptr;
+        for (auto& live : rp_->pin_live) live = false;
+        void* hp = nullptr;
+        void* dp = nullptr;
+        hipError_t e = hipHostMalloc(&hp, rp_->pin_slot_bytes * replay::kHostSlots, hipHostMallocMapped);
+        if (e == hipSuccess) {
+            rp_->pin_host = static_cast<unsigned char*>(hp);
+            e = hipHostGetDevicePointer(&dp, hp, 0);
+        }
+        for (auto& ev : rp_->pin_event)
+            if (e == hipSuccess) e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+        if (e != hipSuccess) {
+            rp::set_error("replay_create: pinned staging slots: %s", hipGetErrorString(e));
+            replay_destroy(rp_);
+            return RP_EHIP;
+        }
+        rp_->pin_dev = static_cast<unsigned char*>(dp);
+    }
     *out = rp_;
     return RP_OK;
 }
 
 rp_status replay_destroy(replay_t* rp_) {
+    if (!rp_) return RP_OK;
+    for (auto& ev : rp_->pin_event)
+        if (ev) (void)hipEventDestroy(ev);
+    if (rp_->pin_host) (void)hipHostFree(rp_->pin_host);
     delete rp_;
     return RP_OK;
 }
@@ -599,23 +688,29 @@ rp_status replay_append(replay_t* rp_, uint64_t n, const void* s, const void* s_
         const size_t sb = g.state_bytes;
         for (uint64_t done = 0; done < n;) {
             const uint64_t m = (n - done < rp_->cfg.max_append) ? n - done : rp_->cfg.max_append;
-            RP_CHECK_HIP(hipMemcpyAsync(rp_->stage_s, static_cast<const unsigned char*>(s) + done * sb,
-                                        m * sb, hipMemcpyHostToDevice, stream));
+            // into the next pinned slot; the kernel reads it in place over the host link
+            const unsigned int slot = (unsigned int)(rp_->pin_next % replay::kHostSlots);
+            if (rp_->pin_live[slot]) RP_CHECK_HIP(hipEventSynchronize(rp_->pin_event[slot]));
+            const size_t base = (size_t)slot * rp_->pin_slot_bytes;
+            unsigned char* h = rp_->pin_host + base;
+            memcpy(h, static_cast<const unsigned char*>(s) + done * sb, m * sb);
             if (pair)
-                RP_CHECK_HIP(hipMemcpyAsync(rp_->stage_s_next,
-                                            static_cast<const unsigned char*>(s_next) + done * sb,
-                                            m * sb, hipMemcpyHostToDevice, stream));
-            RP_CHECK_HIP(hipMemcpyAsync(rp_->stage_a, a + done, m * 4, hipMemcpyHostToDevice, stream));
-            RP_CHECK_HIP(hipMemcpyAsync(rp_->stage_r, r + done, m * 4, hipMemcpyHostToDevice, stream));
-            RP_CHECK_HIP(hipMemcpyAsync(rp_->stage_term, term + done, m, hipMemcpyHostToDevice, stream));
+                memcpy(h + rp_->pin_off_s_next, static_cast<const unsigned char*>(s_next) + done * sb, m * sb);
+            memcpy(h + rp_->pin_off_a, a + done, m * 4);
+            memcpy(h + rp_->pin_off_r, r + done, m * 4);
+            memcpy(h + rp_->pin_off_term, term + done, m);
+            const unsigned char* d = rp_->pin_dev + base;
             const uint64_t cap = rp_->cfg.capacity;
             const rp::RingPos pos{(rp_->head + done) % cap,
                                   rp_->size + done > cap ? cap : rp_->size + done, rp_->total + done};
-            RP_CHECK_HIP(rp::launch_append(g, pos, m, rp_->stage_s, rp_->stage_s_next, rp_->stage_a,
-                                           rp_->stage_r, rp_->stage_term, stream));
+            RP_CHECK_HIP(rp::launch_append(g, pos, m, d, d + rp_->pin_off_s_next,
+                                           reinterpret_cast<const int*>(d + rp_->pin_off_a),
+                                           reinterpret_cast<const float*>(d + rp_->pin_off_r),
+                                           d + rp_->pin_off_term, stream));
+            RP_CHECK_HIP(hipEventRecord(rp_->pin_event[slot], stream));
+            rp_->pin_live[slot] = true;
+            rp_->pin_next += 1;
             done += m;
-            // pageable host memory: the copies above have left the caller's arrays when they
-            // return, and stream order keeps the staging area safe for the next piece
         }
     }
     rp_->total += n;
