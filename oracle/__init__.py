@@ -73,6 +73,7 @@ def lib():
         L.oracle_loss_fixed_targets.argtypes = [vp, vp, vp, vp, vp]
         L.oracle_loss_fixed_targets.restype = C.c_double
         L.oracle_train_step.argtypes = [vp] * 16
+        L.oracle_train_step_target.argtypes = [vp] * 17
         _lib = L
     return _lib
 
@@ -219,12 +220,22 @@ def loss_fixed_targets(cfg, params, S, a, y):
         _p(_c(y, np.float64))))
 
 
+def target_after_step(target, new_params, updates_applied, sync_every):
+    """The frozen target network after a train step (Deep Q-Network Model: overwritten with the
+    trained weights every `sync_every` steps): the new weights when the number of updates applied
+    so far is a multiple of sync_every, else unchanged."""
+    if sync_every and updates_applied % sync_every == 0:
+        return np.array(new_params, np.float64)
+    return np.array(target, np.float64)
+
+
 class StepResult:
     __slots__ = ("params", "m", "v", "t", "Q", "Qn", "y", "delta", "loss", "grads")
 
 
-def train_step(cfg, params, m, v, t, S, S_next, a, r, term):
-    """One step on copies of (params, m, v, t); returns a StepResult in float64."""
+def train_step(cfg, params, m, v, t, S, S_next, a, r, term, target=None):
+    """One step on copies of (params, m, v, t); returns a StepResult in float64.
+    target: parameters of the frozen target network used for Q(s', .) (None = the trained one)."""
     out = StepResult()
     out.params = np.array(params, np.float64, order="C")
     n = out.params.shape[0]
@@ -246,9 +257,12 @@ def train_step(cfg, params, m, v, t, S, S_next, a, r, term):
     assert S.shape == (B, cfg.state_dim) and S_next.shape == S.shape
     assert a.shape == (B,) and r.shape == (B,) and term.shape == (B,)
     assert n == param_count(cfg.state_dim, cfg.hidden, cfg.num_actions)
-    lib().oracle_train_step(C.byref(cfg), _p(out.params), _p(out.m), _p(out.v), C.byref(tt),
-                            _p(S), _p(S_next), _p(a), _p(r), _p(term), _p(out.Q), _p(out.Qn),
-                            _p(out.y), _p(out.delta), C.byref(loss), _p(out.grads))
+    tgt = None if target is None else _c(target, np.float64)
+    assert tgt is None or tgt.shape == (n,)
+    lib().oracle_train_step_target(C.byref(cfg), _p(out.params), _p(tgt), _p(out.m), _p(out.v),
+                                   C.byref(tt), _p(S), _p(S_next), _p(a), _p(r), _p(term),
+                                   _p(out.Q), _p(out.Qn), _p(out.y), _p(out.delta), C.byref(loss),
+                                   _p(out.grads))
     out.t = tt.value
     out.loss = loss.value
     return out

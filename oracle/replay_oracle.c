@@ -355,10 +355,19 @@ double oracle_loss_fixed_targets(const oracle_train_cfg* cfg, const double* para
  * followed by plain backpropagation of L through Q_w(s_i, .) only and an SGD
  * or Adam update.
  */
-void oracle_train_step(const oracle_train_cfg* cfg, double* params, double* m, double* v,
-                       uint64_t* t, const double* S, const double* S_next, const int32_t* a,
-                       const double* r, const uint8_t* term, double* Q_out, double* Qn_out,
-                       double* y_out, double* delta_out, double* loss_out, double* grads_out) {
+/*
+ * target_params (may be NULL): parameters of the frozen target network (Deep
+ * Q-Network Model: a non-trainable copy of the weights gives the target, and is
+ * overwritten with the trained weights every fixed number of steps); Q(s', .)
+ * is then evaluated with it.  NULL = the trained network itself, which is the
+ * update equation as printed (one w on both sides).
+ */
+void oracle_train_step_target(const oracle_train_cfg* cfg, double* params,
+                              const double* target_params, double* m, double* v, uint64_t* t,
+                              const double* S, const double* S_next, const int32_t* a,
+                              const double* r, const uint8_t* term, double* Q_out, double* Qn_out,
+                              double* y_out, double* delta_out, double* loss_out,
+                              double* grads_out) {
     const uint32_t D = cfg->state_dim, H = cfg->hidden, A = cfg->num_actions, B = cfg->batch;
     const size_t P = oracle_param_count(D, H, A);
     double* eff = effective_params(cfg, params);
@@ -369,7 +378,13 @@ void oracle_train_step(const oracle_train_cfg* cfg, double* params, double* m, d
     double* Q  = (double*)malloc((size_t)B * A * sizeof(double));
     double* Qn = (double*)malloc((size_t)B * A * sizeof(double));
     forward_with(cfg, eff, S, B, h1, h2, Q);
-    forward_with(cfg, eff, S_next, B, NULL, NULL, Qn);
+    if (target_params) {
+        double* eff_t = effective_params(cfg, target_params);
+        forward_with(cfg, eff_t, S_next, B, NULL, NULL, Qn);
+        free(eff_t);
+    } else {
+        forward_with(cfg, eff, S_next, B, NULL, NULL, Qn);
+    }
 
     /* targets, TD errors, loss, and dL/dQ (one non-zero per row) */
     double* dQ = (double*)calloc((size_t)B * A, sizeof(double));
@@ -464,4 +479,12 @@ void oracle_train_step(const oracle_train_cfg* cfg, double* params, double* m, d
     if (loss_out) *loss_out = L;
     if (grads_out) memcpy(grads_out, g, P * sizeof(double));
     free(eff); free(h1); free(h2); free(Q); free(Qn); free(dQ); free(g); free(dz2); free(dz1);
+}
+
+void oracle_train_step(const oracle_train_cfg* cfg, double* params, double* m, double* v,
+                       uint64_t* t, const double* S, const double* S_next, const int32_t* a,
+                       const double* r, const uint8_t* term, double* Q_out, double* Qn_out,
+                       double* y_out, double* delta_out, double* loss_out, double* grads_out) {
+    oracle_train_step_target(cfg, params, NULL, m, v, t, S, S_next, a, r, term, Q_out, Qn_out, y_out,
+                             delta_out, loss_out, grads_out);
 }

@@ -100,6 +100,13 @@ void oracle_train_step(const oracle_train_cfg* cfg, double* params, double* m, d
                        const double* r, const uint8_t* term, double* Q, double* Qn, double* y,
                        double* delta, double* loss, double* grads);
 
+/* The same with a frozen target network for Q(s', .) (NULL = the trained network). */
+void oracle_train_step_target(const oracle_train_cfg* cfg, double* params,
+                              const double* target_params, double* m, double* v, uint64_t* t,
+                              const double* S, const double* S_next, const int32_t* a,
+                              const double* r, const uint8_t* term, double* Q, double* Qn,
+                              double* y, double* delta, double* loss, double* grads);
+
 #ifdef __cplusplus
 }
 #endif

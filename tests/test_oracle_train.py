@@ -300,3 +300,74 @@ def test_bf16_mode_rounds_hidden_activations():
     # mixed precision stays close to the exact network
     exact = oracle.mlp_forward(oracle.make_cfg(D, H, A, B), p, S)
     assert 0 < np.abs(Q - exact).max() < 2e-2 * np.abs(exact).max()
+
+
+# ---------------------------------------------------------------- frozen target network
+# A second 2-2-2-2 network as the target; s' = (2,0):
+#   z1 = (2*2, 2*(-2)) + (1, 0) = (5,-4) h1 = (5,0); z2 = (5*1 - 1, 5*0 + 0.5) = (4, 0.5) h2 = (4, 0.5)
+#   Q' = (4*0.25 + 0.5*2 + 0, 4*1 + 0.5*(-2) - 0.5) = (2, 2.5)  ->  max = 2.5
+TW1 = [[2, -2], [3, 3]];     TB1 = [1, 0]
+TW2 = [[1, 0], [9, 9]];      TB2 = [-1, 0.5]
+TW3 = [[0.25, 1], [2, -2]];  TB3 = [0, -0.5]
+TARGET = _flat(TW1, TB1, TW2, TB2, TW3, TB3)
+
+
+def test_target_network_hand_worked():
+    """Q(s', .) comes from the target network, everything else from the trained one."""
+    cfg = _hand_cfg(oracle.MSE)
+    Qt = oracle.mlp_forward(cfg, TARGET, SN_HAND)
+    assert Qt.tolist() == [[2.0, 2.5]]
+    out = oracle.train_step(cfg, HAND, None, None, 0, S_HAND, SN_HAND, [0], [1.0], [0], target=TARGET)
+    # y = 1 + 0.5 * 2.5 = 2.25, q = Q(s,0) = 1.25 from the trained network, delta = 1
+    assert out.Qn.tolist() == [[2.0, 2.5]] and out.Q.tolist() == [[1.25, -1.5]]
+    assert out.y.tolist() == [2.25] and out.delta.tolist() == [1.0] and out.loss == 0.5
+    # gradient = -delta * dQ(s,0)/dw of the trained network: 8x the small-error case (delta 0.125)
+    g = 8 * _flat([[-0.0625, 0], [-0.0625, 0]], [-0.0625, 0], [[-0.1875, 0], [0, 0]], [-0.0625, 0],
+                  [[-0.25, 0], [0, 0]], [-0.125, 0])
+    assert out.grads.tolist() == g.tolist()
+    assert out.params.tolist() == (HAND - g).tolist()
+
+
+def test_target_equal_to_trained_network_changes_nothing():
+    D, H, A, n = 9, 16, 5, 12
+    rows = synth.experiences(n, D, A, 0.2, seed=3)
+    p = synth.init_params(D, H, A, 2).astype(np.float64)
+    cfg = oracle.make_cfg(D, H, A, n, loss=oracle.HUBER, opt=oracle.ADAM, lr=1e-3)
+    args = (rows["s"], rows["s_next"], rows["a"], rows["r"], rows["term"])
+    a = oracle.train_step(cfg, p, None, None, 0, *args)
+    b = oracle.train_step(cfg, p, None, None, 0, *args, target=p)
+    for f in ("params", "Q", "Qn", "y", "delta", "grads", "m", "v"):
+        assert np.array_equal(getattr(a, f), getattr(b, f)), f
+
+
+def test_targets_depend_on_the_target_network_only():
+    """y = r + gamma (1 - terminal) max_a Q_target(s', a): moving the trained weights leaves y
+    alone, moving the target weights leaves Q(s, .) alone; no gradient reaches the target."""
+    D, H, A, n = 9, 16, 5, 12
+    rows = synth.experiences(n, D, A, 0.2, seed=4)
+    p = synth.init_params(D, H, A, 2).astype(np.float64)
+    q = synth.init_params(D, H, A, 7).astype(np.float64)
+    tgt = synth.init_params(D, H, A, 9).astype(np.float64)
+    cfg = oracle.make_cfg(D, H, A, n, loss=oracle.MSE, opt=oracle.SGD, lr=1e-2)
+    args = (rows["s"], rows["s_next"], rows["a"], rows["r"], rows["term"])
+    a = oracle.train_step(cfg, p, None, None, 0, *args, target=tgt)
+    b = oracle.train_step(cfg, q, None, None, 0, *args, target=tgt)
+    c = oracle.train_step(cfg, p, None, None, 0, *args, target=q)
+    assert np.array_equal(a.y, b.y) and np.array_equal(a.Qn, b.Qn)
+    assert np.array_equal(a.Q, c.Q) and not np.array_equal(a.y, c.y)
+    want_y = rows["r"] + cfg.gamma * (1 - rows["term"]) * oracle.mlp_forward(cfg, tgt, rows["s_next"]).max(1)
+    assert np.allclose(a.y, want_y, rtol=1e-14, atol=0)
+    # the step is plain SGD on L(w) with y held constant: finite differences of that loss
+    rng = np.random.default_rng(0)
+    for k in rng.choice(len(p), 40, replace=False):
+        e = np.zeros_like(p); e[k] = 1e-5
+        fd = (oracle.loss_fixed_targets(cfg, p + e, rows["s"], rows["a"], a.y) -
+              oracle.loss_fixed_targets(cfg, p - e, rows["s"], rows["a"], a.y)) / 2e-5
+        assert abs(fd - a.grads[k]) <= 1e-7 * max(1.0, abs(fd))
+
+
+def test_target_sync_schedule():
+    new, old = np.arange(4.0), np.zeros(4)
+    assert oracle.target_after_step(old, new, 10, 5).tolist() == new.tolist()
+    assert oracle.target_after_step(old, new, 11, 5).tolist() == old.tolist()
+    assert oracle.target_after_step(old, new, 7, 0).tolist() == old.tolist()
