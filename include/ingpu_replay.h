@@ -154,6 +154,10 @@ typedef struct {
     uint32_t appends_per_step; /* experiences added by every train_step (0 = none)             */
     float lr, gamma, beta1, beta2, eps;
     uint32_t flags;            /* RP_TRAIN_GRAPH | RP_TRAIN_LAYERED                            */
+    uint32_t target_sync;      /* 0: Q(s',.) comes from the trained network itself (the update
+                                  equation as printed).  N > 0: from a frozen copy of the weights
+                                  that is overwritten with the trained ones after every N-th
+                                  update (Deep Q-Network Model: target fixing, N = 10,000)      */
 } train_config;
 
 /* number of network parameters: D*H + H + H*H + H + H*A + A */
@@ -172,6 +176,9 @@ rp_status train_create(const train_config* cfg, replay_t* rp, void* dev_workspac
 rp_status train_destroy(trainer_t* tr);
 
 /*
+ * With target_sync = N > 0 the target network starts as a copy of host_init_params; it is synced
+ * when the number of updates applied so far (Adam's t, counted for SGD too) is a multiple of N.
+ *
  * One train step with no network inputs from the host (Integration): append
  * appends_per_step experiences (arrays as in replay_append; ignored when
  * appends_per_step = 0), then, once burn-in is complete, sample a batch with
@@ -210,7 +217,12 @@ rp_status train_step_batch(trainer_t* tr, const void* s, const void* s_next, con
 rp_status train_get_params(trainer_t* tr, float* params);             /* fp32 master weights */
 rp_status train_get_grads(trainer_t* tr, float* grads);               /* of the last step    */
 rp_status train_get_opt_state(trainer_t* tr, float* m, float* v, uint64_t* t, uint64_t* step);
-/* Overwrite weights, Adam moments (NULL = keep), Adam t and the sampling step counter. */
+/* The frozen target network's weights (same order as train_get_params); equal to the trained
+ * weights when target_sync = 0.  train_set_target is RP_EINVAL when target_sync = 0. */
+rp_status train_get_target(trainer_t* tr, float* params);
+rp_status train_set_target(trainer_t* tr, const float* params);
+/* Overwrite weights, Adam moments (NULL = keep), Adam t and the sampling step counter.  The
+ * target network is left as it is. */
 rp_status train_set_state(trainer_t* tr, const float* params, const float* m, const float* v,
                           uint64_t t, uint64_t step);
 /* From the last executed step: Q(s,.) [B*A], Q(s',.) [B*A], y[B], delta[B], loss[1],

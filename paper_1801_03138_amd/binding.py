@@ -43,7 +43,7 @@ class TrainConfig(C.Structure):
                 ("batch", C.c_uint32), ("param_dtype", C.c_uint32), ("loss", C.c_uint32),
                 ("opt", C.c_uint32), ("appends_per_step", C.c_uint32), ("lr", C.c_float),
                 ("gamma", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
-                ("eps", C.c_float), ("flags", C.c_uint32)]
+                ("eps", C.c_float), ("flags", C.c_uint32), ("target_sync", C.c_uint32)]
 
 
 # every symbol include/ingpu_replay.h declares: name -> (restype, argtypes)
@@ -76,6 +76,8 @@ SYMBOLS = {
     "train_get_opt_state": (_int, [_vp, _vp, _vp, _vp, _vp]),
     "train_set_state": (_int, [_vp, _vp, _vp, _vp, _u64, _u64]),
     "train_get_last": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "train_get_target": (_int, [_vp, _vp]),
+    "train_set_target": (_int, [_vp, _vp]),
     "train_kernels_per_step": (_int, [_vp, _vp]),
     "rp_last_error": (C.c_char_p, []),
     "rp_version": (C.c_char_p, []),
@@ -214,11 +216,12 @@ class Trainer:
 
     def __init__(self, replay, hidden, num_actions, batch, param_dtype=RP_F32, loss=RP_HUBER,
                  opt=RP_ADAM, appends_per_step=1, lr=1e-4, gamma=0.99, beta1=0.9, beta2=0.999,
-                 eps=1e-8, use_graph=True, layered=False, init_params=None):
+                 eps=1e-8, use_graph=True, layered=False, target_sync=0, init_params=None):
         self.replay = replay
         self.cfg = TrainConfig(replay.cfg.state_dim, hidden, num_actions, batch, param_dtype, loss,
                                opt, appends_per_step, lr, gamma, beta1, beta2, eps,
-                               (RP_TRAIN_GRAPH if use_graph else 0) | (RP_TRAIN_LAYERED if layered else 0))
+                               (RP_TRAIN_GRAPH if use_graph else 0) | (RP_TRAIN_LAYERED if layered else 0),
+                               target_sync)
         nbytes = int(lib().train_workspace_bytes(C.byref(self.cfg)))
         if nbytes == 0:
             raise ReplayError(RP_EINVAL, "invalid train configuration")
@@ -286,6 +289,15 @@ class Trainer:
         p = np.empty(self.n_params, np.float32)
         _check(lib().train_get_params(self._h, _host(p)))
         return p
+
+    def target(self):
+        p = np.empty(self.n_params, np.float32)
+        _check(lib().train_get_target(self._h, _host(p)))
+        return p
+
+    def set_target(self, params):
+        p = np.ascontiguousarray(params, np.float32)
+        _check(lib().train_set_target(self._h, _host(p)))
 
     def grads(self):
         g = np.empty(self.n_params, np.float32)

@@ -554,6 +554,9 @@ size_t row_kernel_lds(unsigned int Dp, unsigned int H, unsigned int Ap) {
 bool fused_step_supported(const train_config& cfg, const replay* rp_) {
     if (cfg.param_dtype != RP_F32 || rp_->cfg.state_dtype != RP_F32 || rp_->cfg.layout != RP_PAIR)
         return false;
+    // the row kernel keeps one network's weights in registers: a frozen target network takes the
+    // layered step
+    if (cfg.target_sync) return false;
     // one lane owns one column of a layer and holds its share of the weights in registers:
     // hidden width up to 256, states and action sets up to 64 wide
     if (cfg.hidden % 64 != 0 || cfg.hidden > 256 || cfg.state_dim > 64 || cfg.num_actions > 64)

@@ -180,7 +180,7 @@ __global__ __launch_bounds__(kThreads) void optimizer_kernel(
     unsigned int n, float* __restrict__ w, const float* __restrict__ g, float* __restrict__ m,
     float* __restrict__ v, bf16_t* __restrict__ wb, unsigned int opt, float lr, float beta1,
     float beta2, float eps, TrainCounters* __restrict__ ctr, const float* __restrict__ lossi,
-    unsigned int B) {
+    unsigned int B, float* __restrict__ wt, bf16_t* __restrict__ wbt, unsigned int sync_every) {
     const unsigned int k = blockIdx.x * kThreads + threadIdx.x;
     if (k < n) {
         float wk = w[k];
@@ -196,6 +196,11 @@ __global__ __launch_bounds__(kThreads) void optimizer_kernel(
         }
         w[k] = wk;
         if (wb) wb[k] = from_float<bf16_t>(wk);
+        // the frozen target network takes the new weights when the update count says so
+        if (wt && sync_every && ctr->adam_t % sync_every == 0) {
+            wt[k] = wk;
+            if (wbt) wbt[k] = from_float<bf16_t>(wk);
+        }
     }
     if (blockIdx.x == 0 && threadIdx.x < 64) {
         float acc = 0.f;
@@ -251,10 +256,10 @@ namespace rp {
 namespace {
 
 struct WsLayout {
-    size_t ctr, w, g, m, v, w2t, wb, X, act, rew, term, idx, H1, H2, Q, y, delta, lossi, dQ, dZ2, dZ1,
+    size_t ctr, w, g, m, v, wt, w2t, wb, wbt, X, act, rew, term, idx, H1, H2, Q, y, delta, lossi, dQ, dZ2, dZ1,
         total;
     // mixed-precision step on MFMA
-    size_t W1T, W2b, W2T, W3T, XT, H1T, H2T, dQTh, dQTl, dZ2T, dZ1T, part3, part1;
+    size_t W1T, W2b, W2T, W3T, W1Tt, W2Tt, W3Tt, XT, H1T, H2T, dQTh, dQTl, dZ2T, dZ1T, part3, part1;
     unsigned int Dp, Ap, Bp;
     size_t n_params, n_padded, elem;
     size_t oW1, ob1, oW2, ob2, oW3, ob3;
@@ -289,8 +294,10 @@ bool ws_layout(const train_config* c, WsLayout* L) {
     L->g = take(L->n_padded * 4);
     L->m = take(L->n_padded * 4);
     L->v = take(L->n_padded * 4);
+    L->wt = take(c->target_sync ? L->n_padded * 4 : 0);
     L->w2t = take(c->param_dtype == RP_F32 ? H * H * 4 : 0);
     L->wb = take(c->param_dtype == RP_BF16 ? L->n_padded * 2 : 0);
+    L->wbt = take(c->param_dtype == RP_BF16 && c->target_sync ? L->n_padded * 2 : 0);
     L->X = take(2 * B * L->Dp * L->elem);
     L->act = take(B * 4);
     L->rew = take(B * 4);
@@ -312,6 +319,10 @@ bool ws_layout(const train_config* c, WsLayout* L) {
     L->W2b = take(mixed ? H * H * 2 : 0);
     L->W2T = take(mixed ? H * H * 2 : 0);
     L->W3T = take(mixed ? L->Ap * H * 2 : 0);
+    const bool mixed_t = mixed && c->target_sync;
+    L->W1Tt = take(mixed_t ? H * L->Dp * 2 : 0);
+    L->W2Tt = take(mixed_t ? H * H * 2 : 0);
+    L->W3Tt = take(mixed_t ? L->Ap * H * 2 : 0);
     L->XT = take(mixed ? Dx * Bp * 2 : 0);
     L->H1T = take(mixed ? (H + 1) * Bp * 2 : 0);
     L->H2T = take(mixed ? (H + 1) * Bp * 2 : 0);
@@ -385,13 +396,36 @@ hipError_t enqueue_step(trainer* t, hipStream_t st, unsigned int* count, bool sa
         if (e != hipSuccess) return e;
         ++n;
     }
-    // forward on the 2B rows of X
-    gemm<E, E, E, false, false, EPI_BIAS_RELU>(st, 2 * B, H, Dp, t->X, Dp, W1, H, t->H1, H,
-                                               t->w + t->ob1, nullptr, 0); ++n;
-    gemm<E, E, E, false, false, EPI_BIAS_RELU>(st, 2 * B, H, H, t->H1, H, W2, H, t->H2, H,
-                                               t->w + t->ob2, nullptr, 0); ++n;
-    gemm<E, E, float, false, false, EPI_BIAS>(st, 2 * B, Ap, H, t->H2, H, W3, Ap, t->Q, Ap,
-                                              t->w + t->ob3, nullptr, 0); ++n;
+    // forward on the 2B rows of X; with a frozen target network the rows of S' (B .. 2B-1) go
+    // through its weights in launches of their own
+    if (!t->wt) {
+        gemm<E, E, E, false, false, EPI_BIAS_RELU>(st, 2 * B, H, Dp, t->X, Dp, W1, H, t->H1, H,
+                                                   t->w + t->ob1, nullptr, 0); ++n;
+        gemm<E, E, E, false, false, EPI_BIAS_RELU>(st, 2 * B, H, H, t->H1, H, W2, H, t->H2, H,
+                                                   t->w + t->ob2, nullptr, 0); ++n;
+        gemm<E, E, float, false, false, EPI_BIAS>(st, 2 * B, Ap, H, t->H2, H, W3, Ap, t->Q, Ap,
+                                                  t->w + t->ob3, nullptr, 0); ++n;
+    } else {
+        const unsigned char* tsrc = mixed ? reinterpret_cast<const unsigned char*>(t->wbt)
+                                          : reinterpret_cast<const unsigned char*>(t->wt);
+        const unsigned char* Xb = static_cast<const unsigned char*>(t->X);
+        unsigned char* H1b = static_cast<unsigned char*>(t->H1);
+        unsigned char* H2b = static_cast<unsigned char*>(t->H2);
+        for (int half = 0; half < 2; ++half) {
+            const unsigned char* ws_ = half ? tsrc : wsrc;
+            const float* bias = half ? t->wt : t->w;
+            const size_t r0 = half ? (size_t)B : 0;
+            gemm<E, E, E, false, false, EPI_BIAS_RELU>(st, B, H, Dp, Xb + r0 * Dp * eb, Dp,
+                                                       ws_ + t->oW1 * eb, H, H1b + r0 * H * eb, H,
+                                                       bias + t->ob1, nullptr, 0); ++n;
+            gemm<E, E, E, false, false, EPI_BIAS_RELU>(st, B, H, H, H1b + r0 * H * eb, H,
+                                                       ws_ + t->oW2 * eb, H, H2b + r0 * H * eb, H,
+                                                       bias + t->ob2, nullptr, 0); ++n;
+            gemm<E, E, float, false, false, EPI_BIAS>(st, B, Ap, H, H2b + r0 * H * eb, H,
+                                                      ws_ + t->oW3 * eb, Ap, t->Q + r0 * Ap, Ap,
+                                                      bias + t->ob3, nullptr, 0); ++n;
+        }
+    }
     // targets, TD errors, loss terms, dL/dQ
     hipLaunchKernelGGL(td_loss_kernel, dim3((B + 3) / 4), dim3(kThreads), 0, st, t->B, A, t->Ap,
                        t->Q, t->act, t->rew, t->term, t->cfg.gamma, t->cfg.loss, t->y, t->delta,
@@ -421,7 +455,7 @@ hipError_t enqueue_step(trainer* t, hipStream_t st, unsigned int* count, bool sa
     hipLaunchKernelGGL(optimizer_kernel, dim3((t->n_padded + kThreads - 1) / kThreads),
                        dim3(kThreads), 0, st, (unsigned int)t->n_padded, t->w, t->g, t->m, t->v,
                        t->wb, t->cfg.opt, t->cfg.lr, t->cfg.beta1, t->cfg.beta2, t->cfg.eps, t->ctr,
-                       t->lossi, t->B); ++n;
+                       t->lossi, t->B, t->wt, t->wbt, t->cfg.target_sync); ++n;
     if (count) *count = n;
     return hipGetLastError();
 }
@@ -595,12 +629,16 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
     t->g = reinterpret_cast<float*>(ws + L.g);
     t->m = reinterpret_cast<float*>(ws + L.m);
     t->v = reinterpret_cast<float*>(ws + L.v);
+    t->wt = cfg->target_sync ? reinterpret_cast<float*>(ws + L.wt) : nullptr;
+    t->wbt = cfg->target_sync && cfg->param_dtype == RP_BF16 ? reinterpret_cast<bf16_t*>(ws + L.wbt)
+                                                              : nullptr;
     t->w2t = cfg->param_dtype == RP_F32 ? reinterpret_cast<float*>(ws + L.w2t) : nullptr;
     t->fused = !(cfg->flags & RP_TRAIN_LAYERED) && rp::fused_step_supported(*cfg, rp_);
     t->wide = !(cfg->flags & RP_TRAIN_LAYERED) && rp::wide_step_supported(*cfg, rp_);
     {
         auto at = [&](size_t off) { return reinterpret_cast<unsigned short*>(ws + off); };
-        t->wd = rp::WideBuffers{at(L.W1T), at(L.W2b), at(L.W2T), at(L.W3T), at(L.XT), at(L.H1T),
+        t->wd = rp::WideBuffers{at(L.W1T), at(L.W2b), at(L.W2T), at(L.W3T), at(L.W1Tt), at(L.W2Tt),
+                                at(L.W3Tt), at(L.XT), at(L.H1T),
                                 at(L.H2T), at(L.dQTh), at(L.dQTl), at(L.dZ2T), at(L.dZ1T),
                                 reinterpret_cast<float*>(ws + L.part3),
                                 reinterpret_cast<float*>(ws + L.part1)};
@@ -644,6 +682,7 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
         }
     }
     rp_status s = train_set_state(t, host_init_params, nullptr, nullptr, 0, 0);
+    if (s == RP_OK && t->wt) s = train_set_target(t, host_init_params);
     if (s != RP_OK) return fail(s);
 
     // pinned host slots for host-sourced payloads
@@ -717,7 +756,9 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
     } else {
         // the launch count is static
         t->kernels_per_step =
-            t->fused ? 2u : (cfg->appends_per_step ? 1u : 0u) + (t->wide ? 10u : 14u);
+            t->fused ? 2u
+                     : (cfg->appends_per_step ? 1u : 0u) +
+                           (t->wide ? (t->wt && cfg->batch % 128 ? 13u : 10u) : (t->wt ? 17u : 14u));
     }
     *out = t;
     return RP_OK;
@@ -892,6 +933,32 @@ rp_status train_get_params(trainer_t* t, float* params) {
     return RP_OK;
 }
 
+rp_status train_get_target(trainer_t* t, float* params) {
+    RP_REQUIRE(t && params, "train_get_target: null argument");
+    std::vector<float> pad(t->n_padded);
+    RP_CHECK_HIP(hipDeviceSynchronize());
+    RP_CHECK_HIP(hipMemcpy(pad.data(), t->wt ? t->wt : t->w, t->n_padded * 4, hipMemcpyDeviceToHost));
+    rp::unpad_params(t, pad, params);
+    return RP_OK;
+}
+
+rp_status train_set_target(trainer_t* t, const float* params) {
+    RP_REQUIRE(t && params, "train_set_target: null argument");
+    RP_REQUIRE(t->wt, "train_set_target: this trainer has no target network (target_sync = 0)");
+    std::vector<float> pad;
+    RP_CHECK_HIP(hipDeviceSynchronize());
+    rp::pad_params(t, params, pad);
+    RP_CHECK_HIP(hipMemcpy(t->wt, pad.data(), t->n_padded * 4, hipMemcpyHostToDevice));
+    if (t->wide) RP_CHECK_HIP(rp::wide_set_weights(t, pad.data(), true));
+    if (t->wbt) {
+        hipLaunchKernelGGL(rp::to_bf16_kernel, dim3((t->n_padded + rp::kThreads - 1) / rp::kThreads),
+                           dim3(rp::kThreads), 0, nullptr, (unsigned int)t->n_padded, t->wt, t->wbt);
+        RP_CHECK_HIP(hipGetLastError());
+    }
+    RP_CHECK_HIP(hipDeviceSynchronize());
+    return RP_OK;
+}
+
 rp_status train_get_grads(trainer_t* t, float* grads) {
     RP_REQUIRE(t && grads, "train_get_grads: null argument");
     std::vector<float> pad(t->n_padded);
@@ -927,7 +994,7 @@ rp_status train_set_state(trainer_t* t, const float* params, const float* m, con
     RP_CHECK_HIP(hipDeviceSynchronize());
     rp::pad_params(t, params, pad);
     RP_CHECK_HIP(hipMemcpy(t->w, pad.data(), t->n_padded * 4, hipMemcpyHostToDevice));
-    if (t->wide) RP_CHECK_HIP(rp::wide_set_weights(t, pad.data()));
+    if (t->wide) RP_CHECK_HIP(rp::wide_set_weights(t, pad.data(), false));
     if (t->w2t) {
         const size_t H = t->H;
         std::vector<float> tr(H * H);

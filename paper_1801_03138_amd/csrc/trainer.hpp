@@ -83,6 +83,7 @@ struct RowArgs {
 // batch index is the contiguous one, rows are padded to Bp (a multiple of 128) with zeros.
 struct WideBuffers {
     unsigned short *W1T, *W2, *W2T, *W3T;   // [H x Dp], [H x H], [H x H] transposed, [Ap x H]
+    unsigned short *W1T_t, *W2T_t, *W3T_t;  // forward operands of the frozen target network
     unsigned short* XT;                      // [>= D+1 x Bp], row D all ones
     unsigned short *H1T, *H2T;               // [H+1 x Bp], row H all ones
     unsigned short *dQT_hi, *dQT_lo;         // [Ap x Bp] each, dQT_lo right after dQT_hi
@@ -107,8 +108,10 @@ struct trainer {
     unsigned char* ws;
     rp::TrainCounters* ctr;
     float *w, *g, *m, *v;
+    float* wt;                       // frozen target network (padded, as w); null without one
     float* w2t;                      // fused path: W2 transposed, [H x H]
     rp::bf16_t* wb;
+    rp::bf16_t* wbt;                 // layered mixed precision: bf16 copy of the target network
     void* X;                         // [2B x Dp]
     int* act;
     float* rew;
@@ -165,7 +168,8 @@ void* fused_rows_func();
 // Mixed-precision step on MFMA (bf16 replay states and matrix operands).
 bool wide_step_supported(const train_config& cfg, const replay* rp_);
 hipError_t wide_init_buffers(trainer* t);                       // once, after the workspace is cleared
-hipError_t wide_set_weights(trainer* t, const float* padded);   // bf16 operand copies from fp32 (host)
+// bf16 operand copies from padded fp32 parameters (host): of the trained network, or of the target
+hipError_t wide_set_weights(trainer* t, const float* padded, bool target);
 // Enqueue the step's kernels after the append; `sample` = draw and gather the batch first
 // (otherwise X, XT and the per-row fields have been filled by the caller).
 hipError_t enqueue_wide_step(trainer* t, hipStream_t st, unsigned int* count, bool sample);

@@ -50,11 +50,25 @@ struct OptState {
     unsigned int opt;
     float lr, beta1, beta2, eps;
     const TrainCounters* ctr;
+    float* wt;                  // frozen target network, or null
+    unsigned int sync_every;    // the target takes the new weights when Adam's t is a multiple of this
 };
 
-// c1, c2: Adam's bias corrections 1 - beta^t of this step
-__device__ __forceinline__ float opt_update(const OptState& o, size_t k, float gk, float c1,
-                                            float c2) {
+// What every update of one step shares: Adam's bias corrections 1 - beta^t and whether the
+// target network is due for a sync (t was advanced earlier in the step).
+struct OptStep {
+    float c1, c2;
+    bool sync;
+};
+__device__ __forceinline__ OptStep opt_step(const OptState& o) {
+    OptStep s;
+    s.c1 = o.ctr->c1;
+    s.c2 = o.ctr->c2;
+    s.sync = o.wt && o.sync_every && o.ctr->adam_t % o.sync_every == 0;
+    return s;
+}
+
+__device__ __forceinline__ float opt_update(const OptState& o, size_t k, float gk, const OptStep& st) {
     float wk = o.w[k];
     o.g[k] = gk;
     if (o.opt == RP_SGD) {
@@ -64,15 +78,17 @@ __device__ __forceinline__ float opt_update(const OptState& o, size_t k, float g
         const float vk = o.beta2 * o.v[k] + (1.f - o.beta2) * gk * gk;
         o.m[k] = mk;
         o.v[k] = vk;
-        wk -= o.lr * (mk / c1) / (sqrtf(vk / c2) + o.eps);
+        wk -= o.lr * (mk / st.c1) / (sqrtf(vk / st.c2) + o.eps);
     }
     o.w[k] = wk;
+    if (st.sync) o.wt[k] = wk;
     return wk;
 }
 
 // ----------------------------------------------------------------------------------------
 // Epilogues of the tiled product.
-// "Staged" epilogues (bf16 output in the product's own orientation): the product is formed with
+// "Staged" epilogues (bf16 output in the product's own orientation; pre() also gets the first
+// row of the workgroup's tile): the product is formed with
 // the MFMA operands exchanged, so a lane holds four consecutive columns of one output row; it
 // passes each value through pre(), rounds to bf16 and parks the wavefront's tile in LDS, from
 // where it leaves in 16-byte pieces -- eight lanes write one 128-byte run of a row -- through
@@ -82,11 +98,13 @@ __device__ __forceinline__ float opt_update(const OptState& o, size_t k, float g
 struct EpiForward {
     static constexpr bool kStaged = true;
     const float* bias;
+    const float* bias_hi;     // bias for rows from m_split on (the target network's)
+    unsigned int m_split;
     bf16_bits* out;
     unsigned int ldo;
     unsigned int M, N;
-    __device__ __forceinline__ float pre(unsigned int n, float x) const {
-        x += bias[n < N ? n : 0u];
+    __device__ __forceinline__ float pre(unsigned int m0, unsigned int n, float x) const {
+        x += (m0 >= m_split ? bias_hi : bias)[n < N ? n : 0u];
         return x > 0.f ? x : 0.f;
     }
     // eight consecutive columns n..n+7 of row m (N is a multiple of 8)
@@ -103,7 +121,7 @@ struct EpiMask {
     bf16_bits* out;
     unsigned int ld;
     unsigned int M, N;
-    __device__ __forceinline__ float pre(unsigned int, float x) const { return x; }
+    __device__ __forceinline__ float pre(unsigned int, unsigned int, float x) const { return x; }
     __device__ __forceinline__ void store(unsigned int m, unsigned int n, const u32x4& v) const {
         if (m >= M || n >= N) return;
         const size_t at = (size_t)m * ld + n;
@@ -130,21 +148,23 @@ struct EpiOptSquare {
     size_t w_off, b_off;
     bf16_bits* wb;              // [R x N]
     bf16_bits* wbT;             // [N x R]
+    bf16_bits* wbT_target;      // [N x R] of the target network, or null
     __device__ __forceinline__ void tile(unsigned int mb, unsigned int nb, const f32x16& c,
                                          unsigned int lane, unsigned int) const {
         const unsigned int n = nb + (lane & 31u);
         if (n >= N) return;
-        const float c1 = o.ctr->c1, c2 = o.ctr->c2;
+        const OptStep st = opt_step(o);
 #pragma unroll
         for (unsigned int v = 0; v < 16; ++v) {
             const unsigned int m = mb + acc_row(v, lane);
             if (m < R) {
-                const float wk = opt_update(o, w_off + (size_t)m * N + n, c[v], c1, c2);
+                const float wk = opt_update(o, w_off + (size_t)m * N + n, c[v], st);
                 const bf16_bits h = bf16_bits_rne(wk);
                 wb[(size_t)m * N + n] = h;
                 wbT[(size_t)n * R + m] = h;
+                if (st.sync) wbT_target[(size_t)n * R + m] = h;
             } else if (m == R) {
-                opt_update(o, b_off + n, c[v], c1, c2);
+                opt_update(o, b_off + n, c[v], st);
             }
         }
     }
@@ -183,6 +203,8 @@ struct GemmArgs {
     const bf16_bits* A;
     unsigned int lda;
     const bf16_bits* Bt;
+    const bf16_bits* Bt_hi;        // B operand of the tiles whose first row is m_split or beyond
+    unsigned int m_split;
     unsigned int ldb;
     unsigned int M, N, K;          // K: columns one workgroup contracts over
     unsigned int tiles_m, tiles_n, splits;
@@ -238,7 +260,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(GemmArgs p, Epi e
     for (int u = 0; u < PB; ++u) {
         unsigned int gn = n0 + lrow + u * RPP;
         gn = gn < p.N ? gn : p.N - 1;
-        b_ptr[u] = p.Bt + (size_t)gn * p.ldb + k_base + lpiece * 8u;
+        b_ptr[u] = (m0 >= p.m_split ? p.Bt_hi : p.Bt) + (size_t)gn * p.ldb + k_base + lpiece * 8u;
     }
     u32x4 ra[PA], rb[PB];
 
@@ -327,7 +349,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(GemmArgs p, Epi e
                     bf16_bits h[4];
 #pragma unroll
                     for (unsigned int e = 0; e < 4; ++e)
-                        h[e] = bf16_bits_rne(epi.pre(wn0 + nl + e, acc[i][j][4 * grp + e]));
+                        h[e] = bf16_bits_rne(epi.pre(m0, wn0 + nl + e, acc[i][j][4 * grp + e]));
                     uint2 pk;
                     pk.x = (unsigned int)h[0] | ((unsigned int)h[1] << 16);
                     pk.y = (unsigned int)h[2] | ((unsigned int)h[3] << 16);
@@ -383,11 +405,15 @@ hipError_t configure_gemm() {
 template <int BM, int BN, int BK, int WGM, int WGN, int WGK, class Epi>
 hipError_t launch_gemm(hipStream_t st, const bf16_bits* A, unsigned int lda, const bf16_bits* Bt,
                        unsigned int ldb, unsigned int M, unsigned int N, unsigned int K,
-                       const Epi& epi, unsigned int splits = 1) {
+                       const Epi& epi, unsigned int splits = 1, const bf16_bits* Bt_hi = nullptr,
+                       unsigned int m_split = 0xFFFFFFFFu) {
     if (K == 0 || splits == 0 || K % (splits * BK) != 0 || lda % 8 != 0 || ldb % 8 != 0)
         return hipErrorInvalidValue;
+    if (Bt_hi && m_split % BM != 0) return hipErrorInvalidValue;   // a tile takes one B operand
     GemmArgs a;
     a.A = A; a.lda = lda; a.Bt = Bt; a.ldb = ldb; a.M = M; a.N = N; a.K = K / splits;
+    a.Bt_hi = Bt_hi ? Bt_hi : Bt;
+    a.m_split = Bt_hi ? m_split : 0xFFFFFFFFu;
     a.tiles_m = (M + BM - 1) / BM;
     a.tiles_n = (N + BN - 1) / BN;
     a.splits = splits;
@@ -415,6 +441,10 @@ struct SkinnyArgs {
     const float* bias;   // [N]
     float* out;          // [M x ldo], fp32
     unsigned int ldo;
+    // tiles whose first row is m_split (a multiple of 32) or beyond use these (the target network's)
+    const bf16_bits* Bt_hi;
+    const float* bias_hi;
+    unsigned int m_split;
 };
 
 template <int NW>
@@ -424,7 +454,9 @@ __global__ __launch_bounds__(64 * NW) void skinny_nt_kernel(SkinnyArgs p) {
     const unsigned int m0 = blockIdx.x * 32u, n0 = blockIdx.y * 32u;
     const unsigned int am = m0 + (lane & 31u), bn = n0 + (lane & 31u);
     const bf16_bits* ap = p.A + (size_t)(am < p.M ? am : 0u) * p.lda + 8u * (lane >> 5);
-    const bf16_bits* bp = p.Bt + (size_t)(bn < p.N ? bn : 0u) * p.ldb + 8u * (lane >> 5);
+    const bool hi = m0 >= p.m_split;
+    const bf16_bits* bp = (hi ? p.Bt_hi : p.Bt) + (size_t)(bn < p.N ? bn : 0u) * p.ldb + 8u * (lane >> 5);
+    const float* bias = hi ? p.bias_hi : p.bias;
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
     f32x16 acc;
 #pragma unroll
@@ -451,7 +483,7 @@ __global__ __launch_bounds__(64 * NW) void skinny_nt_kernel(SkinnyArgs p) {
 #pragma unroll
         for (unsigned int w = 0; w < (unsigned int)NW; ++w) s += red[(w * 16u + v) * 64u + l];
         const unsigned int m = m0 + acc_row(v, l), n = n0 + (l & 31u);
-        if (m < p.M && n < p.N) p.out[(size_t)m * p.ldo + n] = s + p.bias[n];
+        if (m < p.M && n < p.N) p.out[(size_t)m * p.ldo + n] = s + bias[n];
     }
 }
 
@@ -620,6 +652,7 @@ struct SmallOptArgs {
     size_t oW1, ob1, oW3, ob3;
     bf16_bits* W1T;   // [H x Dp]
     bf16_bits* W3T;   // [Ap x H]
+    bf16_bits *W1T_target, *W3T_target;   // the target network's, or null
     TrainCounters* ctr;
     const float* lossi;
 };
@@ -627,7 +660,7 @@ struct SmallOptArgs {
 __global__ __launch_bounds__(256) void small_opt_kernel(SmallOptArgs p) {
     const unsigned int n3 = (p.H + 1u) * p.Ap, n1 = p.H * (p.D + 1u);
     const unsigned int e = blockIdx.x * 256u + threadIdx.x;
-    const float c1 = p.o.ctr->c1, c2 = p.o.ctr->c2;
+    const OptStep st = opt_step(p.o);
     if (e < n3) {
         const unsigned int m = e / p.Ap, a = e - m * p.Ap;
         const size_t stride = (size_t)(p.H + 1u) * 2u * p.Ap;
@@ -642,10 +675,11 @@ __global__ __launch_bounds__(256) void small_opt_kernel(SmallOptArgs p) {
 #pragma unroll
         for (unsigned int z = 0; z < 16; ++z) g += hi[z] + lo[z];
         if (m < p.H) {
-            const float wk = opt_update(p.o, p.oW3 + (size_t)m * p.Ap + a, g, c1, c2);
-            p.W3T[(size_t)a * p.H + m] = bf16_bits_rne(wk);
+            const bf16_bits h = bf16_bits_rne(opt_update(p.o, p.oW3 + (size_t)m * p.Ap + a, g, st));
+            p.W3T[(size_t)a * p.H + m] = h;
+            if (st.sync) p.W3T_target[(size_t)a * p.H + m] = h;
         } else {
-            opt_update(p.o, p.ob3 + a, g, c1, c2);
+            opt_update(p.o, p.ob3 + a, g, st);
         }
     } else if (e < n3 + n1) {
         const unsigned int f = e - n3, j = f / (p.D + 1u), d = f - j * (p.D + 1u);
@@ -658,10 +692,11 @@ __global__ __launch_bounds__(256) void small_opt_kernel(SmallOptArgs p) {
 #pragma unroll
         for (unsigned int z = 0; z < 16; ++z) g += part[z];
         if (d < p.D) {
-            const float wk = opt_update(p.o, p.oW1 + (size_t)d * p.H + j, g, c1, c2);
-            p.W1T[(size_t)j * p.Dp + d] = bf16_bits_rne(wk);
+            const bf16_bits h = bf16_bits_rne(opt_update(p.o, p.oW1 + (size_t)d * p.H + j, g, st));
+            p.W1T[(size_t)j * p.Dp + d] = h;
+            if (st.sync) p.W1T_target[(size_t)j * p.Dp + d] = h;
         } else {
-            opt_update(p.o, p.ob1 + j, g, c1, c2);
+            opt_update(p.o, p.ob1 + j, g, st);
         }
     }
     if (blockIdx.x == 0) {
@@ -724,8 +759,9 @@ hipError_t wide_init_buffers(trainer* t) {
     return e;
 }
 
-// Refresh the bf16 operand copies of the weights from padded fp32 parameters (host array).
-hipError_t wide_set_weights(trainer* t, const float* padded) {
+// Refresh the bf16 operand copies of the weights from padded fp32 parameters (host array): all
+// four of the trained network, or the three forward operands of the target network.
+hipError_t wide_set_weights(trainer* t, const float* padded, bool target) {
     const size_t H = t->H, Dp = t->Dp, Ap = t->Ap;
     std::vector<bf16_bits> w1t(H * Dp), w2(H * H), w2t(H * H), w3t(Ap * H);
     for (size_t d = 0; d < Dp; ++d)
@@ -738,10 +774,13 @@ hipError_t wide_set_weights(trainer* t, const float* padded) {
         }
     for (size_t k = 0; k < H; ++k)
         for (size_t a = 0; a < Ap; ++a) w3t[a * H + k] = host_bf16(padded[t->oW3 + k * Ap + a]);
-    hipError_t e = hipMemcpy(t->wd.W1T, w1t.data(), w1t.size() * 2, hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemcpy(t->wd.W2, w2.data(), w2.size() * 2, hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemcpy(t->wd.W2T, w2t.data(), w2t.size() * 2, hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemcpy(t->wd.W3T, w3t.data(), w3t.size() * 2, hipMemcpyHostToDevice);
+    const WideBuffers& w = t->wd;
+    hipError_t e = hipMemcpy(target ? w.W1T_t : w.W1T, w1t.data(), w1t.size() * 2, hipMemcpyHostToDevice);
+    if (e == hipSuccess && !target) e = hipMemcpy(w.W2, w2.data(), w2.size() * 2, hipMemcpyHostToDevice);
+    if (e == hipSuccess)
+        e = hipMemcpy(target ? w.W2T_t : w.W2T, w2t.data(), w2t.size() * 2, hipMemcpyHostToDevice);
+    if (e == hipSuccess)
+        e = hipMemcpy(target ? w.W3T_t : w.W3T, w3t.data(), w3t.size() * 2, hipMemcpyHostToDevice);
     return e;
 }
 
@@ -755,7 +794,15 @@ hipError_t enqueue_wide_step(trainer* t, hipStream_t st, unsigned int* count, bo
     bf16_bits* H2 = static_cast<bf16_bits*>(t->H2);
     bf16_bits* dZ2 = static_cast<bf16_bits*>(t->dZ2);
     unsigned int n = 0;
-    OptState o{t->w, t->g, t->m, t->v, t->cfg.opt, t->cfg.lr, t->cfg.beta1, t->cfg.beta2, t->cfg.eps, t->ctr};
+    OptState o{t->w, t->g, t->m, t->v, t->cfg.opt, t->cfg.lr, t->cfg.beta1, t->cfg.beta2, t->cfg.eps,
+               t->ctr, t->wt, t->cfg.target_sync};
+    // With a frozen target network the rows of S' (B .. 2B-1) are multiplied by its weights: in
+    // the same launch when tiles do not straddle row B, else in a launch of their own.
+    const bool tgt = t->wt != nullptr;
+    const float *b1t = tgt ? t->wt + t->ob1 : nullptr, *b2t = tgt ? t->wt + t->ob2 : nullptr;
+    const float* b3t = tgt ? t->wt + t->ob3 : nullptr;
+    const bool one_launch = !tgt || B % 128 == 0;
+    const unsigned int rows = one_launch ? 2 * B : B;   // rows of the first forward launch
 
     // sample B slots and unpack into X = [S ; S'] and the transposed copy of S
     hipError_t e = hipSuccess;
@@ -766,23 +813,46 @@ hipError_t enqueue_wide_step(trainer* t, hipStream_t st, unsigned int* count, bo
         ++n;
     }
     // forward on the 2B rows
-    e = launch_gemm<128, 128, 32, 2, 2, 1>(st, X, Dp, w.W1T, Dp, 2 * B, H, Dp,
-                                           EpiForward{t->w + t->ob1, H1, H, 2 * B, H});
+    e = launch_gemm<128, 128, 32, 2, 2, 1>(st, X, Dp, w.W1T, Dp, rows, H, Dp,
+                                           EpiForward{t->w + t->ob1, b1t, tgt ? B : ~0u, H1, H, rows, H},
+                                           1, tgt && one_launch ? w.W1T_t : nullptr, B);
     if (e != hipSuccess) return e;
     ++n;
-    e = launch_gemm<128, 128, 64, 2, 2, 1>(st, H1, H, w.W2T, H, 2 * B, H, H,
-                                           EpiForward{t->w + t->ob2, H2, H, 2 * B, H});
+    if (!one_launch) {
+        e = launch_gemm<128, 128, 32, 2, 2, 1>(st, X + (size_t)B * Dp, Dp, w.W1T_t, Dp, B, H, Dp,
+                                               EpiForward{b1t, b1t, ~0u, H1 + (size_t)B * H, H, B, H});
+        if (e != hipSuccess) return e;
+        ++n;
+    }
+    e = launch_gemm<128, 128, 64, 2, 2, 1>(st, H1, H, w.W2T, H, rows, H, H,
+                                           EpiForward{t->w + t->ob2, b2t, tgt ? B : ~0u, H2, H, rows, H},
+                                           1, tgt && one_launch ? w.W2T_t : nullptr, B);
     if (e != hipSuccess) return e;
     ++n;
+    if (!one_launch) {
+        e = launch_gemm<128, 128, 64, 2, 2, 1>(st, H1 + (size_t)B * H, H, w.W2T_t, H, B, H, H,
+                                               EpiForward{b2t, b2t, ~0u, H2 + (size_t)B * H, H, B, H});
+        if (e != hipSuccess) return e;
+        ++n;
+    }
     {
         SkinnyArgs a;
-        a.A = H2; a.lda = H; a.Bt = w.W3T; a.ldb = H; a.M = 2 * B; a.N = Ap; a.K = H;
+        a.A = H2; a.lda = H; a.Bt = w.W3T; a.ldb = H; a.M = rows; a.N = Ap; a.K = H;
         a.bias = t->w + t->ob3; a.out = t->Q; a.ldo = Ap;
-        hipLaunchKernelGGL(skinny_nt_kernel<4>, dim3((2 * B + 31) / 32, Ap / 32), dim3(256), 0, st, a);
+        a.Bt_hi = tgt ? w.W3T_t : w.W3T; a.bias_hi = tgt ? b3t : a.bias; a.m_split = tgt ? B : ~0u;
+        hipLaunchKernelGGL(skinny_nt_kernel<4>, dim3((rows + 31) / 32, Ap / 32), dim3(256), 0, st, a);
         e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        ++n;
+        if (!one_launch) {
+            a.A = H2 + (size_t)B * H; a.Bt = w.W3T_t; a.bias = b3t; a.out = t->Q + (size_t)B * Ap;
+            a.M = B; a.Bt_hi = a.Bt; a.bias_hi = a.bias; a.m_split = ~0u;
+            hipLaunchKernelGGL(skinny_nt_kernel<4>, dim3((B + 31) / 32, Ap / 32), dim3(256), 0, st, a);
+            e = hipGetLastError();
+        }
     }
     if (e != hipSuccess) return e;
-    ++n;
+    if (!one_launch) ++n;
     // targets, TD errors, loss terms, dL/dQ and dZ2
     {
         TdArgs a;
@@ -814,7 +884,7 @@ hipError_t enqueue_wide_step(trainer* t, hipStream_t st, unsigned int* count, bo
     ++n;
     // second hidden layer: W2 and b2
     e = launch_gemm<64, 64, 128, 1, 1, 4>(st, w.H1T, Bp, w.dZ2T, Bp, H + 1, H, Bp,
-                                          EpiOptSquare{o, H, H, t->oW2, t->ob2, w.W2, w.W2T});
+                                          EpiOptSquare{o, H, H, t->oW2, t->ob2, w.W2, w.W2T, w.W2T_t});
     if (e != hipSuccess) return e;
     ++n;
     // first hidden layer: partial products of [dW1^T | db1] (column D)
@@ -830,7 +900,8 @@ hipError_t enqueue_wide_step(trainer* t, hipStream_t st, unsigned int* count, bo
         a.o = o; a.splits = splits; a.H = H; a.D = D; a.Dp = Dp; a.Dx = Dx; a.Ap = Ap; a.B = B;
         a.part3 = w.part3; a.part1 = w.part1;
         a.oW1 = t->oW1; a.ob1 = t->ob1; a.oW3 = t->oW3; a.ob3 = t->ob3;
-        a.W1T = w.W1T; a.W3T = w.W3T; a.ctr = t->ctr; a.lossi = t->lossi;
+        a.W1T = w.W1T; a.W3T = w.W3T; a.W1T_target = w.W1T_t; a.W3T_target = w.W3T_t;
+        a.ctr = t->ctr; a.lossi = t->lossi;
         const unsigned int elems = (H + 1) * Ap + H * (D + 1);
         hipLaunchKernelGGL(small_opt_kernel, dim3((elems + 255) / 256), dim3(256), 0, st, a);
         ++n;

@@ -45,9 +45,11 @@ class Pair:
     """A GPU replay + trainer and the oracle ring it is compared with."""
 
     def __init__(self, B, *, capacity, D, H, A, batch, burn_in, seed, dtype="f32", loss="huber",
-                 opt="adam", lr=1e-4, appends=1, use_graph=True, max_append=4096, layered=False):
+                 opt="adam", lr=1e-4, appends=1, use_graph=True, max_append=4096, layered=False,
+                 target_sync=0):
         self.B, self.D, self.H, self.A, self.batch, self.seed = B, D, H, A, batch, seed
         self.bf16 = dtype == "bf16"
+        self.target_sync = target_sync
         sd = B.RP_BF16 if self.bf16 else B.RP_F32
         self.gpu_ring = B.Replay(capacity, D, sd, B.RP_PAIR, burn_in=burn_in, seed=seed,
                                  max_append=max_append)
@@ -60,7 +62,7 @@ class Pair:
                                  loss=B.RP_HUBER if loss == "huber" else B.RP_MSE,
                                  opt=B.RP_ADAM if opt == "adam" else B.RP_SGD,
                                  appends_per_step=appends, use_graph=use_graph, layered=layered,
-                                 init_params=self.p0, **{k: float(v) for k, v in self.hyper.items()})
+                                 target_sync=target_sync, init_params=self.p0, **{k: float(v) for k, v in self.hyper.items()})
         self.cfg = oracle.make_cfg(D, H, A, batch,
                                    loss=oracle.HUBER if loss == "huber" else oracle.MSE,
                                    opt=oracle.ADAM if opt == "adam" else oracle.SGD,
@@ -85,6 +87,7 @@ class Pair:
         tr = self.trainer
         if compare:
             p, (m, v, t, step) = tr.params(), tr.opt_state()
+            tgt = tr.target() if self.target_sync else None
         self.ref_ring.append(part["s"], part["s_next"], part["a"], part["r"], part["term"])
         status = tr.step(part["s"], part["s_next"], part["a"], part["r"], part["term"])
         if not compare:
@@ -97,7 +100,7 @@ class Pair:
         assert status == 0
         s, sn, a, r, term = self.ref_ring.gather(idx)
         ref = oracle.train_step(self.cfg, p, m, v, t, self.states_f64(s), self.states_f64(sn), a,
-                                r, term)
+                                r, term, target=tgt)
         last = tr.last()
         assert np.array_equal(last["idx"], idx)
         rt = self.rtol
@@ -113,6 +116,10 @@ class Pair:
         assert_close(new_p, ref.params, rt, "updated weights")
         m2, v2, t2, step2 = tr.opt_state()
         assert step2 == step + 1
+        if self.target_sync:
+            # the frozen copy is exactly the old one, or exactly the new weights when a sync is due
+            want = oracle.target_after_step(tgt, new_p, t + 1, self.target_sync)
+            assert np.array_equal(tr.target().astype(np.float64), want), "target network"
         if self.cfg.opt == oracle.ADAM:
             assert t2 == t + 1 == ref.t
             assert_close(m2, ref.m, 10 * rt if not self.bf16 else 2 * rt, "Adam m")
@@ -377,3 +384,28 @@ def test_in_ram_replay_trains_on_the_same_batches_as_the_device_replay(B):
     ref = oracle.train_step(cfg, p, m, v, t, s, sn, a, r, term)
     assert_close(tr_ram.last()["Q"], ref.Q, F32_RTOL, "Q(s,.)")
     assert_close(tr_ram.params(), ref.params, F32_RTOL, "updated weights")
+
+
+@pytest.mark.parametrize("dtype,H,batch,layered,kernels", [
+    ("f32", 64, 50, False, 18), ("bf16", 128, 200, False, 14), ("bf16", 64, 256, False, 11),
+    ("bf16", 128, 96, True, 18)])
+def test_frozen_target_network(B, dtype, H, batch, layered, kernels):
+    """Q(s', .) from a frozen copy of the weights, synced every 7th update (Deep Q-Network Model);
+    the fp32 case runs layer by layer, the bf16 cases on the MFMA step with the S' rows in the
+    same launches (batch 256) or in launches of their own (batch 200)."""
+    rows = synth.experiences(400, 27, 30, 0.05, seed=23, state_dtype=dtype)
+    pr = Pair(B, capacity=256, D=27, H=H, A=30, batch=batch, burn_in=100, seed=3, dtype=dtype,
+              appends=2, layered=layered, target_sync=7, lr=1e-3)
+    assert pr.trainer.kernels_per_step() == kernels
+    assert np.array_equal(pr.trainer.target(), pr.trainer.params())
+    synced = 0
+    for k in range(0, 400, 2):
+        before = pr.trainer.target()
+        pr.step(synth.take(rows, k, k + 2), compare=(k % 10 == 0) or k >= 380)
+        synced += not np.array_equal(before, pr.trainer.target())
+    assert synced == (200 - 49) // 7
+    # a target set by hand is used as it is
+    other = synth.init_params(27, H, 30, 99)
+    pr.trainer.set_target(other)
+    assert np.array_equal(pr.trainer.target(), other)
+    pr.step(synth.experiences(2, 27, 30, 0.05, seed=24, state_dtype=dtype), compare=True)
