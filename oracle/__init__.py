@@ -55,6 +55,9 @@ def lib():
         L.oracle_uniform_index.argtypes = [u64, u64, u32, u64]
         L.oracle_uniform_index.restype = u32
         L.oracle_uniform_indices.argtypes = [u64, u64, u64, u32, u64, vp]
+        L.oracle_distinct_index.argtypes = [u64, u64, u32, u64]
+        L.oracle_distinct_index.restype = u32
+        L.oracle_ring_sample_mode.argtypes = [vp, u64, u64, u32, C.c_int, vp]
         L.oracle_ring_create.argtypes = [u64, u32, u32, u32, u64]
         L.oracle_ring_create.restype = vp
         L.oracle_ring_destroy.argtypes = [vp]
@@ -104,6 +107,16 @@ def philox4x32_10(ctr, key):
 
 def uniform_index(seed, step, i, n_choices):
     return int(lib().oracle_uniform_index(seed, step, i, n_choices))
+
+
+def distinct_index(seed, step, i, n_choices):
+    return int(lib().oracle_distinct_index(seed, step, i, n_choices))
+
+
+def distinct_indices(seed, step, batch, n_choices):
+    """The first `batch` members of the step's sample without duplicates."""
+    f = lib().oracle_distinct_index
+    return np.array([f(seed, step, i, n_choices) for i in range(batch)], np.uint32)
 
 
 def uniform_indices(seed, step0, nsteps, batch, n_choices):
@@ -171,10 +184,10 @@ class Ring:
             raise ValueError("oracle_ring_read rejected the arguments")
         return s, sn, a, r, term
 
-    def sample(self, seed, step, batch):
+    def sample(self, seed, step, batch, distinct=False):
         """Slot numbers of one sample, or None while sampling is refused."""
         idx = np.empty(batch, np.uint32)
-        rc = lib().oracle_ring_sample(self._h, seed, step, batch, _p(idx))
+        rc = lib().oracle_ring_sample_mode(self._h, seed, step, batch, int(distinct), _p(idx))
         if rc < 0:
             raise ValueError("oracle_ring_sample rejected the arguments")
         return None if rc == 1 else idx

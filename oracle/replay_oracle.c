@@ -72,6 +72,37 @@ uint32_t oracle_uniform_index(uint64_t seed, uint64_t step, uint32_t i, uint64_t
     return (uint32_t)(((uint64_t)x[i % 4u] * n_choices) >> 32);
 }
 
+/*
+ * Member i (i < n) of a sample of distinct integers from [0, n)  (Methods: the in-RAM replay
+ * samples without duplicates; the author wants the device replay to do so too).
+ * The sample is the image of 0, 1, 2, ... under a keyed permutation of [0, n), so its members
+ * are distinct by construction and each is a pure function of (seed, step, i).  The permutation
+ * is a swap-or-not shuffle (Hoang, Morris, Rogaway, CRYPTO 2012), which works on a domain of any
+ * size: in round r every x is paired with its partner K_r - x (mod n) and the pair is swapped
+ * or not according to one pseudorandom bit that both members agree on (it is a function of the
+ * larger of the two).  Rounds: 2 * bitlen(n - 1) + 8.  Randomness comes from Philox4x32-10 with
+ * key = seed: K_r = floor(w * n / 2^32) with w = word r mod 4 of counter (r div 4, 1, step);
+ * the bit of round r for pair maximum m = bit 0 of word 0 of counter (m, 2 + r, step).
+ */
+uint32_t oracle_distinct_index(uint64_t seed, uint64_t step, uint32_t i, uint64_t n) {
+    uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    unsigned bitlen = 0;
+    for (uint64_t v = n - 1; v; v >>= 1) ++bitlen;
+    const uint32_t rounds = 2 * bitlen + 8;
+    uint64_t x = i;
+    for (uint32_t r = 0; r < rounds; ++r) {
+        uint32_t kc[4] = {r / 4u, 1u, (uint32_t)step, (uint32_t)(step >> 32)}, kw[4];
+        oracle_philox4x32_10(kc, key, kw);
+        uint64_t K = ((uint64_t)kw[r % 4u] * n) >> 32;
+        uint64_t partner = (K + n - x) % n;
+        uint64_t m = partner > x ? partner : x;
+        uint32_t bc[4] = {(uint32_t)m, 2u + r, (uint32_t)step, (uint32_t)(step >> 32)}, bw[4];
+        oracle_philox4x32_10(bc, key, bw);
+        if (bw[0] & 1u) x = partner;
+    }
+    return (uint32_t)x;
+}
+
 void oracle_uniform_indices(uint64_t seed, uint64_t step0, uint64_t nsteps, uint32_t batch,
                             uint64_t n_choices, uint32_t* out) {
     for (uint64_t k = 0; k < nsteps; ++k)
@@ -181,23 +212,25 @@ int oracle_ring_read(const oracle_ring* g, uint64_t first_slot, uint64_t n, void
  * no successor yet, so the draw is over the size-1 older experiences, counted
  * from the oldest one.
  */
-int oracle_ring_sample(const oracle_ring* g, uint64_t seed, uint64_t step, uint32_t batch,
-                       uint32_t* idx) {
+int oracle_ring_sample_mode(const oracle_ring* g, uint64_t seed, uint64_t step, uint32_t batch,
+                            int distinct, uint32_t* idx) {
     if (!g || !idx || batch == 0) return -1;
     if (g->total < g->burn_in) return 1;
-    if (g->layout == ORACLE_PAIR) {
-        if (g->size == 0) return 1;
-        for (uint32_t i = 0; i < batch; ++i)
-            idx[i] = oracle_uniform_index(seed, step, i, g->size);
-    } else {
-        if (g->size < 2) return 1;
-        uint64_t oldest = (g->head + g->capacity - g->size) % g->capacity;
-        for (uint32_t i = 0; i < batch; ++i) {
-            uint64_t u = oracle_uniform_index(seed, step, i, g->size - 1);
-            idx[i] = (uint32_t)((oldest + u) % g->capacity);
-        }
+    /* experiences that can be drawn; a sample of distinct ones needs at least `batch` of them */
+    uint64_t choices = g->layout == ORACLE_PAIR ? g->size : (g->size < 2 ? 0 : g->size - 1);
+    if (choices == 0 || (distinct && choices < batch)) return 1;
+    uint64_t oldest = (g->head + g->capacity - g->size) % g->capacity;
+    for (uint32_t i = 0; i < batch; ++i) {
+        uint64_t u = distinct ? oracle_distinct_index(seed, step, i, choices)
+                              : oracle_uniform_index(seed, step, i, choices);
+        idx[i] = g->layout == ORACLE_PAIR ? (uint32_t)u : (uint32_t)((oldest + u) % g->capacity);
     }
     return 0;
+}
+
+int oracle_ring_sample(const oracle_ring* g, uint64_t seed, uint64_t step, uint32_t batch,
+                       uint32_t* idx) {
+    return oracle_ring_sample_mode(g, seed, step, batch, 0, idx);
 }
 
 /* one state out of the ring into a batch row: raw bits, or u8 / 255 as float */

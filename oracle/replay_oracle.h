@@ -43,6 +43,8 @@ void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t
 
 /* The i-th uniform draw from [0, n_choices) of sampling step `step`. */
 uint32_t oracle_uniform_index(uint64_t seed, uint64_t step, uint32_t i, uint64_t n_choices);
+/* The i-th member (i < n_choices) of a sample of distinct integers from [0, n_choices). */
+uint32_t oracle_distinct_index(uint64_t seed, uint64_t step, uint32_t i, uint64_t n_choices);
 /* `nsteps` consecutive steps, `batch` draws each: out[k*batch + i]. */
 void oracle_uniform_indices(uint64_t seed, uint64_t step0, uint64_t nsteps, uint32_t batch,
                             uint64_t n_choices, uint32_t* out);
@@ -62,6 +64,10 @@ int  oracle_ring_read(const oracle_ring* ring, uint64_t first_slot, uint64_t n, 
  * (burn-in not complete, or nothing to sample), -1 for bad arguments. */
 int  oracle_ring_sample(const oracle_ring* ring, uint64_t seed, uint64_t step, uint32_t batch,
                         uint32_t* idx);
+/* The same with distinct != 0: a sample without duplicates (refused, 1, while fewer than
+ * `batch` experiences can be drawn). */
+int  oracle_ring_sample_mode(const oracle_ring* ring, uint64_t seed, uint64_t step, uint32_t batch,
+                             int distinct, uint32_t* idx);
 /* Unpack the experiences at idx[] into contiguous batch arrays.  F32 and BF16
  * states are copied bit for bit; U8 states come out as float = u8 / 255. */
 int  oracle_ring_gather(const oracle_ring* ring, const uint32_t* idx, uint32_t batch, void* out_s,

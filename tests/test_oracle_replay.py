@@ -369,3 +369,70 @@ def test_chain_sampling_is_uniform_over_complete_experiences():
     expected = 500 * 126 / (C - 1)
     chi2 = float(((others - expected) ** 2 / expected).sum())
     assert abs(chi2 - (C - 2)) < 5 * math.sqrt(2 * (C - 2)), chi2
+
+
+# ---------------------------------------------------------------- sampling without duplicates
+def test_distinct_sample_is_a_permutation_of_the_choices():
+    """Fed with 0..n-1 the generator must return every choice exactly once, for every n."""
+    for n in list(range(1, 70)) + [255, 256, 257, 1000, 4096, 4097]:
+        for seed, step in ((0, 0), (7, 3), (2**40 + 5, 2**33 + 1)):
+            out = oracle.distinct_indices(seed, step, n, n)
+            assert sorted(out.tolist()) == list(range(n)), (n, seed, step)
+
+
+def test_distinct_sample_at_paper_size_has_no_duplicates():
+    """With replacement a batch of 32 out of 1,000,000 repeats an experience 0.05 % of the time
+    (Methods); without, never."""
+    for step in range(300):
+        idx = oracle.distinct_indices(0, step, 32, 1_000_000)
+        assert idx.max() < 1_000_000 and len(set(idx.tolist())) == 32
+    big = oracle.distinct_indices(1, 0, 20_000, 1_000_000)
+    assert len(set(big.tolist())) == 20_000
+
+
+def test_distinct_sample_is_uniform_and_changes_with_the_step():
+    # chi-square of the first member over 1000 choices, 100,000 steps: df = 999
+    n, steps = 1000, 100_000
+    first = np.array([oracle.distinct_index(5, k, 0, n) for k in range(steps)])
+    counts = np.bincount(first, minlength=n)
+    chi2 = ((counts - steps / n) ** 2 / (steps / n)).sum()
+    assert abs(chi2 - 999) < 5 * np.sqrt(2 * 999)
+    # ordered pairs (member 0, member 1) over 6 choices: 30 equally likely outcomes, df = 29
+    pairs = np.zeros((6, 6))
+    for k in range(30_000):
+        a, b = oracle.distinct_index(9, k, 0, 6), oracle.distinct_index(9, k, 1, 6)
+        assert a != b
+        pairs[a, b] += 1
+    exp = 30_000 / 30
+    chi2 = ((pairs[~np.eye(6, dtype=bool)] - exp) ** 2 / exp).sum()
+    assert abs(chi2 - 29) < 5 * np.sqrt(2 * 29)
+    # whole samples of 5 out of 5: all 120 orders equally likely, df = 119 (a keyed permutation
+    # built from too few or too regular rounds reaches only part of them)
+    orders = {}
+    for k in range(60_000):
+        o = tuple(oracle.distinct_indices(3, k, 5, 5).tolist())
+        orders[o] = orders.get(o, 0) + 1
+    assert len(orders) == 120
+    chi2 = sum((c - 500.0) ** 2 / 500.0 for c in orders.values())
+    assert abs(chi2 - 119) < 5 * np.sqrt(2 * 119)
+    # the key is (seed, step): other steps and seeds give other samples, the same ones the same
+    a = oracle.distinct_indices(3, 10, 64, 10_000)
+    assert np.array_equal(a, oracle.distinct_indices(3, 10, 64, 10_000))
+    assert not np.array_equal(a, oracle.distinct_indices(3, 11, 64, 10_000))
+    assert not np.array_equal(a, oracle.distinct_indices(4, 10, 64, 10_000))
+
+
+def test_ring_sampling_without_duplicates():
+    ring = oracle.Ring(50, 3, burn_in=0)
+    rows = synth.experiences(40, 3, 4, 0.1, seed=1)
+    ring.append(rows["s"][:10], rows["s_next"][:10], rows["a"][:10], rows["r"][:10], rows["term"][:10])
+    assert ring.sample(0, 0, 11, distinct=True) is None          # only 10 to choose from
+    idx = ring.sample(0, 0, 10, distinct=True)
+    assert sorted(idx.tolist()) == list(range(10))
+    chain = oracle.Ring(8, 3, oracle.F32, oracle.CHAIN, burn_in=0)
+    for lo in range(0, 12, 4):
+        chain.append(rows["s"][lo:lo + 4], None, rows["a"][lo:lo + 4], rows["r"][lo:lo + 4],
+                     rows["term"][lo:lo + 4])
+    # full ring of 8 with head 4: the newest slot (3) has no successor and is never drawn
+    assert chain.sample(0, 0, 8, distinct=True) is None
+    assert sorted(chain.sample(0, 1, 7, distinct=True).tolist()) == [0, 1, 2, 4, 5, 6, 7]
