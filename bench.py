@@ -124,13 +124,14 @@ def leg_paper_shaped(B, synth, steps, warmup, full_ring, host_payload=False):
             "ring_rows": ring.state()[1]}
 
 
-def leg_gather_sweep(B, synth, reps):
+def leg_gather_sweep(B, synth, reps, distinct=False):
+    """replay_sample_gather alone on the full 1M-row ring; distinct = batches without duplicates."""
     import torch
     c = P_CFG
-    ring = B.Replay(c["capacity"], c["D"], seed=0, max_append=4096)
+    ring = B.Replay(c["capacity"], c["D"], seed=0, max_append=4096, distinct=distinct)
     prefill(ring, synth.experiences(100_000, c["D"], c["A"], c["p_term"], seed=0), c["capacity"])
     out = []
-    for batch in GATHER_BATCHES:
+    for batch in ([128, 65536] if distinct else GATHER_BATCHES):
         bufs = ring.alloc_batch(batch)
         for k in range(10):
             ring.sample_gather(k, batch, out=bufs)
@@ -386,6 +387,12 @@ def main():
                     "achieved": g["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": g["GBps"] / HBM_PEAK_GBS, "traffic": GATHER_65536_HBM_BYTES,
                     "alg_bytes_per_launch": g["alg_bytes"], "us_per_launch": g["us_per_call"]}
+    if "gather" in legs:
+        out["gather_sweep_without_duplicates"] = leg_gather_sweep(B, synth, max(100, args.gather_reps // 4),
+                                                                  distinct=True)
+        for g in out["gather_sweep_without_duplicates"]:
+            log("[bench]   without duplicates B=%-6d %8.2f us  %8.1f GB/s" %
+                (g["batch"], g["us_per_call"], g["GBps"]))
     if "append" in legs:
         log("[bench] append: time per experience against the update size ...")
         out["append_sweep"] = leg_append_sweep(B, synth)

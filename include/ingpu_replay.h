@@ -61,6 +61,10 @@ enum { RP_SGD = 0, RP_ADAM = 1 };
  * LAYERED = always use the one-kernel-per-layer step, also where the two-kernel step for
  * small fp32 networks would apply (both give the same results to rounding). */
 enum { RP_TRAIN_GRAPH = 1, RP_TRAIN_LAYERED = 2 };
+/* replay_config.sampling.  RP_WITH_REPLACEMENT: every draw independent (Methods: what the
+ * in-GPU replay does; a batch may repeat an experience).  RP_DISTINCT: a batch never repeats an
+ * experience (Methods: what the in-RAM replay does and the author wants back). */
+enum { RP_WITH_REPLACEMENT = 0, RP_DISTINCT = 1 };
 
 typedef struct {
     uint64_t capacity;    /* number of experiences the replay holds (1,000,000 in the paper) */
@@ -72,6 +76,8 @@ typedef struct {
     uint64_t burn_in;     /* sampling and training are refused until this many experiences
                              have been added in total                                         */
     uint64_t seed;        /* key of the index generator                                       */
+    uint32_t sampling;    /* RP_WITH_REPLACEMENT | RP_DISTINCT                                */
+    uint32_t reserved;    /* 0                                                                */
 } replay_config;
 
 /* Bytes of device memory replay_create needs for this configuration (0 if the
@@ -123,8 +129,13 @@ rp_status replay_append(replay_t* rp, uint64_t n, const void* s, const void* s_n
  * experiences that already have a successor.  For RP_CHAIN, out_s_next of a
  * terminal experience holds the next slot's state and is to be masked by the
  * caller with out_term.
- * Returns RP_SKIPPED_BURN_IN, writing nothing, before burn-in completes or
- * while there is nothing to sample.  batch = 0 or batch > 2^24 is RP_EINVAL.
+ * With RP_DISTINCT, draw i is instead the image of i under a keyed permutation of the
+ * choices: a swap-or-not shuffle of 2*bitlen(choices-1)+8 rounds driven by the same
+ * generator (round r: partner K_r - x mod choices with K_r from word r mod 4 of counter
+ * (r div 4, 1, step); swap bit = bit 0 of word 0 of counter (max(x, partner), 2 + r, step)).
+ * Returns RP_SKIPPED_BURN_IN, writing nothing, before burn-in completes, while there is
+ * nothing to sample, or (RP_DISTINCT) while fewer than `batch` experiences can be drawn.
+ * batch = 0 or batch > 2^24 is RP_EINVAL.
  */
 rp_status replay_sample_gather(replay_t* rp, uint64_t step, uint32_t batch, void* out_s,
                                void* out_s_next, int32_t* out_a, float* out_r, uint8_t* out_term,

@@ -21,6 +21,7 @@ RP_PAIR, RP_CHAIN = 0, 1
 RP_HUBER, RP_MSE = 0, 1
 RP_SGD, RP_ADAM = 0, 1
 RP_TRAIN_GRAPH, RP_TRAIN_LAYERED = 1, 2
+RP_WITH_REPLACEMENT, RP_DISTINCT = 0, 1
 
 _NP_STATE = {RP_F32: np.float32, RP_BF16: np.uint16, RP_U8: np.uint8}
 _TORCH_OUT = {RP_F32: torch.float32, RP_BF16: torch.bfloat16, RP_U8: torch.float32}
@@ -35,7 +36,7 @@ class ReplayError(RuntimeError):
 class ReplayConfig(C.Structure):
     _fields_ = [("capacity", C.c_uint64), ("state_dim", C.c_uint32), ("state_dtype", C.c_uint32),
                 ("layout", C.c_uint32), ("max_append", C.c_uint32), ("burn_in", C.c_uint64),
-                ("seed", C.c_uint64)]
+                ("seed", C.c_uint64), ("sampling", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 class TrainConfig(C.Structure):
@@ -139,8 +140,9 @@ class Replay:
     """The experience replay of the paper's Methods section, resident in HBM."""
 
     def __init__(self, capacity, state_dim, state_dtype=RP_F32, layout=RP_PAIR, burn_in=0, seed=0,
-                 max_append=4096, device="cuda:0"):
-        self.cfg = ReplayConfig(capacity, state_dim, state_dtype, layout, max_append, burn_in, seed)
+                 max_append=4096, device="cuda:0", distinct=False):
+        self.cfg = ReplayConfig(capacity, state_dim, state_dtype, layout, max_append, burn_in, seed,
+                                RP_DISTINCT if distinct else RP_WITH_REPLACEMENT, 0)
         nbytes = storage_bytes(self.cfg)
         if nbytes == 0:
             raise ReplayError(RP_EINVAL, "invalid replay configuration")

@@ -56,6 +56,7 @@ struct RingGeom {
     unsigned int meta_off;      // PAIR: byte offset of (action, reward, terminal) in a row
     unsigned int layout;
     unsigned int dtype;
+    unsigned int sampling;      // 0: with replacement, 1: without duplicates
     unsigned char* rows;        // PAIR: [capacity][row_bytes]; CHAIN: [capacity][row_bytes] states
     int* a;                     // CHAIN side arrays [capacity]
     float* r;

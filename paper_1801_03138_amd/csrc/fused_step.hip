@@ -210,7 +210,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
                 gslot[pass] = i0 + r;
                 gval[pass] = payload_word(p.batch, D, i0 + r, w);
             } else {
-                const unsigned int slot = uniform_draw(p.seed, step, i0 + r, size);
+                const unsigned int slot = batch_draw(p.g.sampling, p.seed, step, i0 + r, size);
                 unsigned long long off = (unsigned long long)slot + cap - head;
                 if (off >= cap) off -= cap;
                 gslot[pass] = slot;

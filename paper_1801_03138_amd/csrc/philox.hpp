@@ -45,4 +45,38 @@ __device__ __forceinline__ unsigned int uniform_draw(unsigned long long seed,
     return __umulhi(word, choices);
 }
 
+// Member i (i < choices) of a sample without duplicates: the image of i under a keyed
+// permutation of [0, choices), a swap-or-not shuffle (Hoang, Morris, Rogaway, CRYPTO 2012) of
+// 2 * bitlen(choices - 1) + 8 rounds.  Round r pairs x with K_r - x (mod choices), K_r = the
+// scaled word r mod 4 of the block with counter (r div 4, stream 1, step), and swaps the pair
+// when bit 0 of word 0 of the block with counter (larger of the pair, stream 2 + r, step) is set.
+__device__ __forceinline__ unsigned int distinct_draw(unsigned long long seed,
+                                                      unsigned long long step, unsigned int i,
+                                                      unsigned int choices) {
+    const unsigned int k0 = (unsigned int)seed, k1 = (unsigned int)(seed >> 32);
+    const unsigned int s0 = (unsigned int)step, s1 = (unsigned int)(step >> 32);
+    const unsigned int bitlen = choices > 1u ? 32u - (unsigned int)__clz((int)(choices - 1u)) : 0u;
+    const unsigned int rounds = 2u * bitlen + 8u;
+    unsigned int x = i;
+    Philox4 kw = {0u, 0u, 0u, 0u};
+    for (unsigned int r = 0; r < rounds; ++r) {
+        if ((r & 3u) == 0u) kw = philox4x32_10(r >> 2, 1u, s0, s1, k0, k1);
+        const unsigned int lane = r & 3u;
+        const unsigned int word = lane == 0 ? kw.x : lane == 1 ? kw.y : lane == 2 ? kw.z : kw.w;
+        const unsigned int K = __umulhi(word, choices);
+        const unsigned int partner = K >= x ? K - x : K + (choices - x);
+        const unsigned int larger = partner > x ? partner : x;
+        const Philox4 b = philox4x32_10(larger, 2u + r, s0, s1, k0, k1);
+        if (b.x & 1u) x = partner;
+    }
+    return x;
+}
+
+// Draw i of a batch in the replay's sampling mode (0 = with replacement).
+__device__ __forceinline__ unsigned int batch_draw(unsigned int sampling, unsigned long long seed,
+                                                   unsigned long long step, unsigned int i,
+                                                   unsigned int choices) {
+    return sampling ? distinct_draw(seed, step, i, choices) : uniform_draw(seed, step, i, choices);
+}
+
 }  // namespace rp

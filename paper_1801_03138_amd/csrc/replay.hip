@@ -48,7 +48,8 @@ struct Layout {
 bool compute_layout(const replay_config* c, Layout* L) {
     if (!c || c->capacity == 0 || c->capacity >= (1ull << 32) || c->state_dim == 0 ||
         c->state_dim > (1u << 24) || c->state_dtype > RP_U8 || c->layout > RP_CHAIN ||
-        c->max_append == 0 || c->max_append > (1u << 24))
+        c->max_append == 0 || c->max_append > (1u << 24) || c->sampling > RP_DISTINCT ||
+        c->reserved != 0)
         return false;
     const size_t eb = elem_bytes_of(c->state_dtype);
     L->state_bytes = (size_t)c->state_dim * eb;
@@ -265,7 +266,8 @@ __global__ __launch_bounds__(kThreads) void sample_gather_pair_kernel(
     unsigned char* __restrict__ out_term, unsigned int* __restrict__ out_idx,
     void* __restrict__ out_s_t, unsigned int out_t_ld) {
     extern __shared__ uint4 smem[];
-    unsigned char* rows_s = reinterpret_cast<unsigned char*>(smem);
+    unsigned int* idx_s = reinterpret_cast<unsigned int*>(smem);   // distinct mode: R slot numbers
+    unsigned char* rows_s = reinterpret_cast<unsigned char*>(smem) + 4 * U * kThreads;
 
     // callers that mirror the ring state pass the size by value: no dependent load up front
     const unsigned long long step = step_ptr ? *step_ptr : step_value;
@@ -280,12 +282,19 @@ __global__ __launch_bounds__(kThreads) void sample_gather_pair_kernel(
         const unsigned int lanes = 1u << lane_shift;         // lanes per row (power of two)
         const unsigned int part0 = threadIdx.x & (lanes - 1u);
         const unsigned int rsub = threadIdx.x >> lane_shift;
+        // A draw without duplicates takes some sixty Philox blocks: one lane per row makes
+        // it and the others pick it up from LDS.
+        if (g.sampling) {
+            for (unsigned int rr = threadIdx.x; rr < nrows; rr += kThreads)
+                idx_s[rr] = distinct_draw(seed, step, i0 + rr, size);
+            __syncthreads();
+        }
         const unsigned char* src[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             unsigned int rr = rsub + u * rows_per_pass;
             rr = rr < nrows ? rr : 0u;   // a row past the end re-reads row 0; not stored
-            const unsigned int p = uniform_draw(seed, step, i0 + rr, size);
+            const unsigned int p = g.sampling ? idx_s[rr] : uniform_draw(seed, step, i0 + rr, size);
             src[u] = g.rows + (unsigned long long)p * g.row_bytes;
             if (out_idx && part0 == 0 && rsub + u * rows_per_pass < nrows) out_idx[i0 + rr] = p;
         }
@@ -364,7 +373,7 @@ __global__ __launch_bounds__(kThreads) void sample_gather_chain_kernel(
     const unsigned long long head = size_value ? head_value : g.state->head;
     unsigned long long oldest = head + g.capacity - size;
     if (oldest >= g.capacity) oldest -= g.capacity;
-    unsigned long long p = oldest + uniform_draw(seed, step, i, (unsigned int)(size - 1));
+    unsigned long long p = oldest + batch_draw(g.sampling, seed, step, i, (unsigned int)(size - 1));
     if (p >= g.capacity) p -= g.capacity;
     unsigned long long q = p;
     if (which) q = (p + 1 == g.capacity) ? 0 : p + 1;
@@ -523,7 +532,7 @@ hipError_t launch_sample_gather(const RingGeom& g, unsigned long long seed,
         const unsigned int U = 1;
         const unsigned int R = U * rows_per_pass;
         const unsigned int blocks = (batch + R - 1) / R;
-        const size_t lds = (size_t)R * g.row_bytes;
+        const size_t lds = 4 * (size_t)U * kThreads + (size_t)R * g.row_bytes;
 #define RP_LAUNCH_PAIR(E, UU)                                                                       \
     hipLaunchKernelGGL((sample_gather_pair_kernel<E, UU>), dim3(blocks), dim3(kThreads), lds, stream, \
                        g, seed, step_value, step_ptr, size_value, batch, lane_shift, out_s,          \
@@ -620,6 +629,7 @@ rp_status replay_create(const replay_config* cfg, void* dev_storage, size_t byte
     g.meta_off = (unsigned int)L.meta_off;
     g.layout = cfg->layout;
     g.dtype = cfg->state_dtype;
+    g.sampling = cfg->sampling;
     g.rows = base + L.off_rows;
     g.a = reinterpret_cast<int*>(base + L.off_a);
     g.r = reinterpret_cast<float*>(base + L.off_r);
@@ -726,7 +736,9 @@ rp_status replay_sample_gather(replay_t* rp_, uint64_t step, uint32_t batch, voi
     RP_REQUIRE(batch >= 1 && batch <= (1u << 24), "replay_sample_gather: batch %u not in 1..2^24",
                batch);
     if (rp_->total < rp_->cfg.burn_in) return RP_SKIPPED_BURN_IN;
-    if (rp_->size < (rp_->cfg.layout == RP_CHAIN ? 2u : 1u)) return RP_SKIPPED_BURN_IN;
+    // experiences that can be drawn; a batch without duplicates needs at least `batch` of them
+    const uint64_t choices = rp_->cfg.layout == RP_CHAIN ? (rp_->size ? rp_->size - 1 : 0) : rp_->size;
+    if (choices == 0 || (rp_->cfg.sampling == RP_DISTINCT && choices < batch)) return RP_SKIPPED_BURN_IN;
     RP_CHECK_HIP(rp::launch_sample_gather(rp_->geom, rp_->cfg.seed, step, nullptr, batch, out_s,
                                           out_s_next, rp_->cfg.state_dim, out_a, out_r, out_term,
                                           out_idx, static_cast<hipStream_t>(hip_stream), nullptr, 0,

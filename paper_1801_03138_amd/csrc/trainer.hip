@@ -812,7 +812,8 @@ rp_status train_step(trainer_t* t, const void* s, const void* s_next, const int3
     }
     const uint64_t total_after = rpl->total + n;
     const uint64_t size_after = rpl->size + n > rpl->cfg.capacity ? rpl->cfg.capacity : rpl->size + n;
-    const bool train = total_after >= rpl->cfg.burn_in && size_after >= 1;
+    const bool train = total_after >= rpl->cfg.burn_in &&
+                       size_after >= (rpl->cfg.sampling == RP_DISTINCT ? t->cfg.batch : 1u);
     if (!train) {
         if (n)
             RP_CHECK_HIP(rp::launch_append(rpl->geom, rp::RingPos{rpl->head, rpl->size, rpl->total}, n,
@@ -886,7 +887,8 @@ rp_status train_steps(trainer_t* t, uint64_t count, const void* s, const void* s
         // kGraphSteps steps in one graph launch when all of them train and their new
         // experiences are already in device memory
         if (t->multi_exec && count - k >= K && (n == 0 || src_is_device) &&
-            rpl->total + n >= rpl->cfg.burn_in && rpl->size + n >= 1) {
+            rpl->total + n >= rpl->cfg.burn_in &&
+            rpl->size + n >= (rpl->cfg.sampling == RP_DISTINCT ? t->cfg.batch : 1u)) {
             for (unsigned int j = 0; j < K && rp::has_payload_node(t); ++j) {
                 const uint64_t oj = o + j * n;
                 const rp::Payload src =

@@ -257,3 +257,51 @@ def test_large_state_ring_full_size(B):
         st, out = gpu.sample_gather(step, batch)
         assert st == 0
         _assert_batch_equal(out, ref, ref.sample(3, step, batch))
+
+
+@pytest.mark.parametrize("dtype,D,chain", [("f32", 27, False), ("bf16", 27, False), ("u8", 37, True)])
+def test_sampling_without_duplicates_matches_oracle(B, dtype, D, chain):
+    """RP_DISTINCT: bit-exact slot numbers and batches, no slot twice, refused while fewer
+    experiences can be drawn than the batch asks for; whole-ring batches are permutations."""
+    C = 300
+    gpu = B.Replay(C, D, DT[dtype][1], B.RP_CHAIN if chain else B.RP_PAIR, seed=11, max_append=256,
+                   distinct=True)
+    ref = oracle.Ring(C, D, DT[dtype][0], oracle.CHAIN if chain else oracle.PAIR)
+    rows = _rows(900, D, 30, 0.05, 2, dtype)
+    k, step = 0, 0
+    for n in [1, 2, 40, 100, 157, 250, 250]:
+        _append_both(gpu, ref, synth.take(rows, k, k + n), True, chain=chain)
+        k += n
+        choices = ref.state()[1] - (1 if chain else 0)
+        for batch in [1, 2, 16, 17, 64, 129, 299, 300]:
+            idx = ref.sample(11, step, batch, distinct=True)
+            st, out = gpu.sample_gather(step, batch)
+            if batch > choices:
+                assert idx is None and st == B.RP_SKIPPED_BURN_IN
+                continue
+            assert st == 0 and len(set(idx.tolist())) == batch
+            _assert_batch_equal(out, ref, idx)
+            if batch == choices:
+                assert len(set(idx.tolist())) == choices
+            step += 1
+
+
+def test_sampling_without_duplicates_at_paper_size(B):
+    """1,000,000 experiences, batch 65,536: the launch shape the bench times; every slot number
+    against the oracle on a sample of positions, all of them distinct."""
+    C, D = 1_000_000, 27
+    gpu = B.Replay(C, D, seed=3, max_append=4096, distinct=True)
+    rows = synth.experiences(100_000, D, 30, 0.005, seed=0)
+    d = _to_dev(rows)
+    for _ in range(10):
+        gpu.append(d["s"], d["s_next"], d["a"], d["r"], d["term"])
+    st, out = gpu.sample_gather(7, 65536)
+    assert st == 0
+    torch.cuda.synchronize()
+    idx = out[5].cpu().numpy().view(np.uint32)
+    assert idx.max() < C and len(np.unique(idx)) == 65536
+    for i in list(range(0, 65536, 997)) + [65535]:
+        assert idx[i] == oracle.distinct_index(3, 7, i, C)
+    # the gathered rows are those slots' rows (the ring holds the 100,000 source rows ten times)
+    s = out[0].cpu().numpy()
+    assert np.array_equal(s.view(np.uint32), rows["s"][idx % 100_000].view(np.uint32))

@@ -46,13 +46,14 @@ class Pair:
 
     def __init__(self, B, *, capacity, D, H, A, batch, burn_in, seed, dtype="f32", loss="huber",
                  opt="adam", lr=1e-4, appends=1, use_graph=True, max_append=4096, layered=False,
-                 target_sync=0):
+                 target_sync=0, distinct=False):
         self.B, self.D, self.H, self.A, self.batch, self.seed = B, D, H, A, batch, seed
         self.bf16 = dtype == "bf16"
         self.target_sync = target_sync
+        self.distinct = distinct
         sd = B.RP_BF16 if self.bf16 else B.RP_F32
         self.gpu_ring = B.Replay(capacity, D, sd, B.RP_PAIR, burn_in=burn_in, seed=seed,
-                                 max_append=max_append)
+                                 max_append=max_append, distinct=distinct)
         self.ref_ring = oracle.Ring(capacity, D, oracle.BF16 if self.bf16 else oracle.F32,
                                     oracle.PAIR, burn_in=burn_in)
         self.p0 = synth.init_params(D, H, A, seed)
@@ -92,7 +93,7 @@ class Pair:
         status = tr.step(part["s"], part["s_next"], part["a"], part["r"], part["term"])
         if not compare:
             return status
-        idx = self.ref_ring.sample(self.seed, step, self.batch)
+        idx = self.ref_ring.sample(self.seed, step, self.batch, distinct=self.distinct)
         if idx is None:
             assert status == self.B.RP_SKIPPED_BURN_IN
             assert np.array_equal(tr.params(), p)
@@ -409,3 +410,21 @@ def test_frozen_target_network(B, dtype, H, batch, layered, kernels):
     pr.trainer.set_target(other)
     assert np.array_equal(pr.trainer.target(), other)
     pr.step(synth.experiences(2, 27, 30, 0.05, seed=24, state_dtype=dtype), compare=True)
+
+
+@pytest.mark.parametrize("dtype,H,layered", [("f32", 64, False), ("f32", 64, True), ("bf16", 128, False)])
+def test_train_step_with_batches_without_duplicates(B, dtype, H, layered):
+    """RP_DISTINCT replay under each kind of train step; with burn-in 10 and batch 40 the first
+    steps are refused until 40 experiences are held."""
+    rows = synth.experiences(300, 27, 30, 0.05, seed=29, state_dtype=dtype)
+    pr = Pair(B, capacity=128, D=27, H=H, A=30, batch=40, burn_in=10, seed=8, dtype=dtype,
+              appends=2, layered=layered, distinct=True)
+    executed = 0
+    for k in range(0, 300, 2):
+        st = pr.step(synth.take(rows, k, k + 2), compare=(k % 20 == 0) or k >= 290)
+        assert st == (B.RP_SKIPPED_BURN_IN if k + 2 < 40 else 0)
+        executed += st == 0
+        if st == 0:
+            assert len(set(pr.trainer.last()["idx"].tolist())) == 40 or k % 20
+    assert executed == 150 - 19
+    assert pr.gpu_ring.state() == pr.ref_ring.state()
