@@ -34,7 +34,7 @@ def build(force=True):
 class TrainCfg(C.Structure):
     _fields_ = [("state_dim", C.c_uint32), ("hidden", C.c_uint32), ("num_actions", C.c_uint32),
                 ("batch", C.c_uint32), ("loss", C.c_uint32), ("opt", C.c_uint32),
-                ("bf16", C.c_uint32), ("reserved", C.c_uint32), ("lr", C.c_double),
+                ("bf16", C.c_uint32), ("dueling", C.c_uint32), ("lr", C.c_double),
                 ("gamma", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double),
                 ("eps", C.c_double)]
 
@@ -207,9 +207,14 @@ class Ring:
 
 
 def make_cfg(state_dim, hidden, num_actions, batch, loss=HUBER, opt=SGD, bf16=0, lr=1e-3,
-             gamma=0.99, beta1=0.9, beta2=0.999, eps=1e-8):
-    return TrainCfg(state_dim, hidden, num_actions, batch, loss, opt, bf16, 0, lr, gamma, beta1,
+             gamma=0.99, beta1=0.9, beta2=0.999, eps=1e-8, dueling=0):
+    return TrainCfg(state_dim, hidden, num_actions, batch, loss, opt, bf16, dueling, lr, gamma, beta1,
                     beta2, eps)
+
+
+def cfg_param_count(cfg):
+    """Parameters of the network a configuration describes (the dueling head has one more output)."""
+    return param_count(cfg.state_dim, cfg.hidden, cfg.num_actions + (1 if cfg.dueling else 0))
 
 
 def param_count(D, H, A):
@@ -269,7 +274,7 @@ def train_step(cfg, params, m, v, t, S, S_next, a, r, term, target=None):
     term = _c(term, np.uint8)
     assert S.shape == (B, cfg.state_dim) and S_next.shape == S.shape
     assert a.shape == (B,) and r.shape == (B,) and term.shape == (B,)
-    assert n == param_count(cfg.state_dim, cfg.hidden, cfg.num_actions)
+    assert n == cfg_param_count(cfg)
     tgt = None if target is None else _c(target, np.float64)
     assert tgt is None or tgt.shape == (n,)
     lib().oracle_train_step_target(C.byref(cfg), _p(out.params), _p(tgt), _p(out.m), _p(out.v),

@@ -285,7 +285,20 @@ double oracle_round_bf16(double x) {
 
 /* ------------------------------------------------------------------------
  * Q-network: D -> H -> H -> A, ReLU after the two hidden layers, linear out.
+ *
+ * With cfg->dueling the last layer is the dueling head of the paper (Deep
+ * Q-Network Model): the second hidden layer is two streams side by side, units
+ * 0 .. H/2-1 feed a scalar state value V and units H/2 .. H-1 feed one
+ * advantage per action, and
+ *     Q(s, a) = V(s) + A(s, a) - mean_a' A(s, a').
+ * The last layer then has 1 + A outputs (column 0 = V, column 1 + a = A(., a));
+ * its weights from the other stream's units are structurally zero and get no
+ * gradient.
  * --------------------------------------------------------------------- */
+static uint32_t out_width(const oracle_train_cfg* cfg) {
+    return cfg->num_actions + (cfg->dueling ? 1u : 0u);
+}
+
 size_t oracle_param_count(uint32_t D, uint32_t H, uint32_t A) {
     return (size_t)D * H + H + (size_t)H * H + H + (size_t)H * A + A;
 }
@@ -306,18 +319,29 @@ static net_view view_params(const double* p, uint32_t D, uint32_t H, uint32_t A)
     return n;
 }
 
-/* the weights the matrix products see: bf16-rounded copies in mixed precision */
+/* 1 where the dueling head has a weight from hidden unit k to output o */
+static int head_connected(const oracle_train_cfg* cfg, uint32_t k, uint32_t o) {
+    if (!cfg->dueling) return 1;
+    const int value_stream = k < cfg->hidden / 2;
+    return o == 0 ? value_stream : !value_stream;
+}
+
+/* the weights the matrix products see: bf16-rounded copies in mixed precision, and the
+ * structural zeros of the dueling head */
 static double* effective_params(const oracle_train_cfg* cfg, const double* params) {
-    const uint32_t D = cfg->state_dim, H = cfg->hidden, A = cfg->num_actions;
-    size_t n = oracle_param_count(D, H, A);
+    const uint32_t D = cfg->state_dim, H = cfg->hidden, O = out_width(cfg);
+    size_t n = oracle_param_count(D, H, O);
     double* e = (double*)malloc(n * sizeof(double));
     memcpy(e, params, n * sizeof(double));
+    size_t oW1 = 0, oW2 = (size_t)D * H + H, oW3 = oW2 + (size_t)H * H + H;
     if (cfg->bf16) {
-        size_t oW1 = 0, oW2 = (size_t)D * H + H, oW3 = oW2 + (size_t)H * H + H;
         for (size_t k = 0; k < (size_t)D * H; ++k) e[oW1 + k] = oracle_round_bf16(e[oW1 + k]);
         for (size_t k = 0; k < (size_t)H * H; ++k) e[oW2 + k] = oracle_round_bf16(e[oW2 + k]);
-        for (size_t k = 0; k < (size_t)H * A; ++k) e[oW3 + k] = oracle_round_bf16(e[oW3 + k]);
+        for (size_t k = 0; k < (size_t)H * O; ++k) e[oW3 + k] = oracle_round_bf16(e[oW3 + k]);
     }
+    for (uint32_t k = 0; k < H; ++k)
+        for (uint32_t o = 0; o < O; ++o)
+            if (!head_connected(cfg, k, o)) e[oW3 + (size_t)k * O + o] = 0.0;
     return e;
 }
 
@@ -337,15 +361,34 @@ static void dense(const double* in, uint32_t n, uint32_t K, const double* W, con
     }
 }
 
+/* Q[i][a] from the last layer's outputs z[i][.]: the outputs themselves, or the dueling combine */
+static void head_combine(const oracle_train_cfg* cfg, const double* z, uint32_t n, double* Q) {
+    const uint32_t A = cfg->num_actions, O = out_width(cfg);
+    for (uint32_t i = 0; i < n; ++i) {
+        if (!cfg->dueling) {
+            for (uint32_t a = 0; a < A; ++a) Q[(size_t)i * A + a] = z[(size_t)i * O + a];
+            continue;
+        }
+        double mean = 0.0;
+        for (uint32_t a = 0; a < A; ++a) mean += z[(size_t)i * O + 1 + a];
+        mean /= A;
+        for (uint32_t a = 0; a < A; ++a)
+            Q[(size_t)i * A + a] = z[(size_t)i * O] + z[(size_t)i * O + 1 + a] - mean;
+    }
+}
+
 static void forward_with(const oracle_train_cfg* cfg, const double* eff, const double* X,
                          uint32_t n, double* h1, double* h2, double* Q) {
-    const uint32_t D = cfg->state_dim, H = cfg->hidden, A = cfg->num_actions;
-    net_view w = view_params(eff, D, H, A);
+    const uint32_t D = cfg->state_dim, H = cfg->hidden, O = out_width(cfg);
+    net_view w = view_params(eff, D, H, O);
     double* t1 = h1 ? h1 : (double*)malloc((size_t)n * H * sizeof(double));
     double* t2 = h2 ? h2 : (double*)malloc((size_t)n * H * sizeof(double));
+    double* z = (double*)malloc((size_t)n * O * sizeof(double));
     dense(X, n, D, w.W1, w.b1, H, 1, (int)cfg->bf16, t1);
     dense(t1, n, H, w.W2, w.b2, H, 1, (int)cfg->bf16, t2);
-    dense(t2, n, H, w.W3, w.b3, A, 0, 0, Q);
+    dense(t2, n, H, w.W3, w.b3, O, 0, 0, z);
+    head_combine(cfg, z, n, Q);
+    free(z);
     if (!h1) free(t1);
     if (!h2) free(t2);
 }
@@ -402,9 +445,10 @@ void oracle_train_step_target(const oracle_train_cfg* cfg, double* params,
                               double* y_out, double* delta_out, double* loss_out,
                               double* grads_out) {
     const uint32_t D = cfg->state_dim, H = cfg->hidden, A = cfg->num_actions, B = cfg->batch;
-    const size_t P = oracle_param_count(D, H, A);
+    const uint32_t O = out_width(cfg);
+    const size_t P = oracle_param_count(D, H, O);
     double* eff = effective_params(cfg, params);
-    net_view w = view_params(eff, D, H, A);
+    net_view w = view_params(eff, D, H, O);
 
     double* h1 = (double*)malloc((size_t)B * H * sizeof(double));
     double* h2 = (double*)malloc((size_t)B * H * sizeof(double));
@@ -436,30 +480,45 @@ void oracle_train_step_target(const oracle_train_cfg* cfg, double* params,
     }
     L /= B;
 
+    /* gradient at the last layer's outputs: dQ itself, or dQ pulled back through the dueling
+     * combine: dV = sum_a dQ[a], dA[a] = dQ[a] - mean_a' dQ[a'] */
+    double* dz3 = (double*)calloc((size_t)B * O, sizeof(double));
+    for (uint32_t i = 0; i < B; ++i) {
+        if (!cfg->dueling) {
+            for (uint32_t a = 0; a < A; ++a) dz3[(size_t)i * O + a] = dQ[(size_t)i * A + a];
+            continue;
+        }
+        double sum = 0.0;
+        for (uint32_t a = 0; a < A; ++a) sum += dQ[(size_t)i * A + a];
+        dz3[(size_t)i * O] = sum;
+        for (uint32_t a = 0; a < A; ++a) dz3[(size_t)i * O + 1 + a] = dQ[(size_t)i * A + a] - sum / A;
+    }
+
     double* g = (double*)calloc(P, sizeof(double));
     double* gW1 = g;
     double* gb1 = gW1 + (size_t)D * H;
     double* gW2 = gb1 + H;
     double* gb2 = gW2 + (size_t)H * H;
     double* gW3 = gb2 + H;
-    double* gb3 = gW3 + (size_t)H * A;
+    double* gb3 = gW3 + (size_t)H * O;
 
-    /* output layer: dW3 = h2^T dQ, db3 = column sums of dQ */
+    /* output layer: dW3 = h2^T dz3 where the head has a weight, db3 = column sums of dz3 */
 #pragma omp parallel for schedule(static)
     for (int64_t k = 0; k < (int64_t)H; ++k)
         for (uint32_t i = 0; i < B; ++i)
-            for (uint32_t o = 0; o < A; ++o)
-                gW3[(size_t)k * A + o] += h2[(size_t)i * H + k] * dQ[(size_t)i * A + o];
+            for (uint32_t o = 0; o < O; ++o)
+                if (head_connected(cfg, (uint32_t)k, o))
+                    gW3[(size_t)k * O + o] += h2[(size_t)i * H + k] * dz3[(size_t)i * O + o];
     for (uint32_t i = 0; i < B; ++i)
-        for (uint32_t o = 0; o < A; ++o) gb3[o] += dQ[(size_t)i * A + o];
+        for (uint32_t o = 0; o < O; ++o) gb3[o] += dz3[(size_t)i * O + o];
 
-    /* dz2 = (dQ W3^T) masked by the second ReLU */
+    /* dz2 = (dz3 W3^T) masked by the second ReLU */
     double* dz2 = (double*)malloc((size_t)B * H * sizeof(double));
 #pragma omp parallel for schedule(static)
     for (int64_t i = 0; i < (int64_t)B; ++i)
         for (uint32_t k = 0; k < H; ++k) {
             double acc = 0.0;
-            for (uint32_t o = 0; o < A; ++o) acc += dQ[(size_t)i * A + o] * w.W3[(size_t)k * A + o];
+            for (uint32_t o = 0; o < O; ++o) acc += dz3[(size_t)i * O + o] * w.W3[(size_t)k * O + o];
             if (!(h2[(size_t)i * H + k] > 0.0)) acc = 0.0;
             dz2[(size_t)i * H + k] = cfg->bf16 ? oracle_round_bf16(acc) : acc;
         }
@@ -511,7 +570,7 @@ void oracle_train_step_target(const oracle_train_cfg* cfg, double* params,
     if (Qn_out) memcpy(Qn_out, Qn, (size_t)B * A * sizeof(double));
     if (loss_out) *loss_out = L;
     if (grads_out) memcpy(grads_out, g, P * sizeof(double));
-    free(eff); free(h1); free(h2); free(Q); free(Qn); free(dQ); free(g); free(dz2); free(dz1);
+    free(eff); free(h1); free(h2); free(Q); free(Qn); free(dQ); free(dz3); free(g); free(dz2); free(dz1);
 }
 
 void oracle_train_step(const oracle_train_cfg* cfg, double* params, double* m, double* v,

@@ -82,12 +82,15 @@ typedef struct {
     uint32_t loss;     /* ORACLE_HUBER | ORACLE_MSE */
     uint32_t opt;      /* ORACLE_SGD | ORACLE_ADAM  */
     uint32_t bf16;     /* 1: apply the bf16 rounding points of the mixed-precision path */
-    uint32_t reserved;
+    uint32_t dueling;  /* 1: dueling head (Deep Q-Network Model): Q = V + A - mean A; the last layer
+                          has 1 + num_actions outputs (V first), fed by the two halves of the second
+                          hidden layer */
     double lr, gamma, beta1, beta2, eps;
 } oracle_train_cfg;
 
 /* Parameters are one flat array: W1[D*H] b1[H] W2[H*H] b2[H] W3[H*A] b3[A],
- * every matrix row-major [in x out]. */
+ * every matrix row-major [in x out]; with the dueling head W3 and b3 have 1 + num_actions
+ * columns, i.e. the count is oracle_param_count(D, H, num_actions + 1). */
 size_t oracle_param_count(uint32_t D, uint32_t H, uint32_t A);
 
 /* Q = MLP(X) for n rows of X[n x D]; h1, h2 (post-ReLU, [n x H]) may be NULL. */

@@ -371,3 +371,91 @@ def test_target_sync_schedule():
     assert oracle.target_after_step(old, new, 10, 5).tolist() == new.tolist()
     assert oracle.target_after_step(old, new, 11, 5).tolist() == old.tolist()
     assert oracle.target_after_step(old, new, 7, 0).tolist() == old.tolist()
+
+
+# ---------------------------------------------------------------- dueling head
+def _dueling_numpy(p, X, D, H, A):
+    """The dueling network written with library matmuls: shared layer, then a value stream and
+    an advantage stream of H/2 units each, Q = V + A - mean A (Deep Q-Network Model)."""
+    p = np.asarray(p, np.float64)
+    o = 0
+    W1 = p[o:o + D * H].reshape(D, H); o += D * H
+    b1 = p[o:o + H]; o += H
+    W2 = p[o:o + H * H].reshape(H, H); o += H * H
+    b2 = p[o:o + H]; o += H
+    W3 = p[o:o + H * (A + 1)].reshape(H, A + 1); o += H * (A + 1)
+    b3 = p[o:o + A + 1]
+    h1 = np.maximum(np.asarray(X, np.float64) @ W1 + b1, 0)
+    hv = np.maximum(h1 @ W2[:, :H // 2] + b2[:H // 2], 0)       # value stream
+    ha = np.maximum(h1 @ W2[:, H // 2:] + b2[H // 2:], 0)       # advantage stream
+    V = hv @ W3[:H // 2, 0] + b3[0]
+    Adv = ha @ W3[H // 2:, 1:] + b3[1:]
+    return V[:, None] + Adv - Adv.mean(1, keepdims=True), V
+
+
+def test_dueling_forward_hand_worked():
+    # first two layers of the second hand-worked network: s = (1,1) gives h2 = (14, 9.5),
+    # s' = (2,0) gives h2 = (4, 0.5); unit 0 is the value stream, unit 1 the advantage stream.
+    # V = 0.5 h2[0] + 0.25; A = (h2[1] + 0.5, -0.5 h2[1] - 1).  The 99s are the structural zeros.
+    p = _flat(TW1, TB1, TW2, TB2, [[0.5, 99, 99], [99, 1, -0.5]], [0.25, 0.5, -1])
+    cfg = oracle.make_cfg(2, 2, 2, 1, loss=oracle.MSE, opt=oracle.SGD, lr=1.0, gamma=0.5, dueling=1)
+    Q, h1, h2 = oracle.mlp_forward(cfg, p, S_HAND + SN_HAND, want_hidden=True)
+    assert h2.tolist() == [[14, 9.5], [4, 0.5]]
+    # s: V = 7.25, A = (10, -5.75), mean 2.125; s': V = 2.25, A = (1, -1.25), mean -0.125
+    assert Q.tolist() == [[15.125, -0.625], [3.375, 1.125]]
+
+
+def test_dueling_head_identities():
+    D, H, A, n = 9, 16, 5, 40
+    rows = synth.experiences(n, D, A, 0.2, seed=11)
+    p = synth.init_params(D, H, A + 1, 3).astype(np.float64)
+    cfg = oracle.make_cfg(D, H, A, n, loss=oracle.HUBER, opt=oracle.SGD, lr=1e-2, dueling=1)
+    Q = oracle.mlp_forward(cfg, p, rows["s"])
+    want, V = _dueling_numpy(p, rows["s"], D, H, A)
+    assert np.allclose(Q, want, rtol=1e-13, atol=1e-13)
+    assert np.allclose(Q.mean(1), V, rtol=1e-13, atol=1e-13)          # mean_a Q(s, a) = V(s)
+    # weights between the streams do not exist: changing them changes nothing
+    q = p.copy()
+    oW3 = D * H + H + H * H + H
+    W3 = q[oW3:oW3 + H * (A + 1)].reshape(H, A + 1)
+    W3[H // 2:, 0] += 5.0
+    W3[:H // 2, 1:] -= 3.0
+    assert np.array_equal(oracle.mlp_forward(cfg, q, rows["s"]), Q)
+    a = oracle.train_step(cfg, p, None, None, 0, rows["s"], rows["s_next"], rows["a"], rows["r"], rows["term"])
+    g3 = a.grads[oW3:oW3 + H * (A + 1)].reshape(H, A + 1)
+    assert not g3[H // 2:, 0].any() and not g3[:H // 2, 1:].any()
+    assert g3[:H // 2, 0].any() and g3[H // 2:, 1:].any()
+    # the advantage gradients of a sample sum to zero over the actions, the value gradient is dQ
+    gb3 = a.grads[oW3 + H * (A + 1):]
+    assert abs(gb3[1:].sum()) < 1e-15 and abs(gb3[0] - (-np.clip(a.delta, -1, 1) / n).sum()) < 1e-15
+
+
+def test_dueling_gradients_match_finite_differences():
+    D, H, A, n = 7, 8, 4, 30
+    rows = synth.experiences(n, D, A, 0.2, seed=12)
+    p = synth.init_params(D, H, A + 1, 4).astype(np.float64)
+    cfg = oracle.make_cfg(D, H, A, n, loss=oracle.HUBER, opt=oracle.SGD, lr=1e-2, dueling=1)
+    out = oracle.train_step(cfg, p, None, None, 0, rows["s"], rows["s_next"], rows["a"], rows["r"], rows["term"])
+    assert np.allclose(out.params, p - 1e-2 * out.grads, rtol=0, atol=1e-18)
+    h = 1e-5
+    for k in range(len(p)):
+        e = np.zeros_like(p); e[k] = h
+        fd = (oracle.loss_fixed_targets(cfg, p + e, rows["s"], rows["a"], out.y) -
+              oracle.loss_fixed_targets(cfg, p - e, rows["s"], rows["a"], out.y)) / (2 * h)
+        assert abs(fd - out.grads[k]) <= 2e-7 * max(1.0, abs(fd)), k
+
+
+def test_dueling_with_one_action_is_the_value_stream_alone():
+    """A = 1: the advantage cancels, Q = V, and the step is that of a plain D-H-H-1 network whose
+    last layer sees the value stream only."""
+    D, H, n = 6, 8, 20
+    rows = synth.experiences(n, D, 1, 0.2, seed=13)
+    p = synth.init_params(D, H, 2, 5).astype(np.float64)
+    cfg = oracle.make_cfg(D, H, 1, n, loss=oracle.MSE, opt=oracle.SGD, lr=1e-2, dueling=1)
+    plain = oracle.make_cfg(D, H, 1, n, loss=oracle.MSE, opt=oracle.SGD, lr=1e-2)
+    oW3 = D * H + H + H * H + H
+    W3 = p[oW3:oW3 + 2 * H].reshape(H, 2)
+    w_plain = W3[:, 0].copy(); w_plain[H // 2:] = 0
+    q = np.concatenate([p[:oW3], w_plain, p[oW3 + 2 * H:oW3 + 2 * H + 1]])
+    assert np.allclose(oracle.mlp_forward(cfg, p, rows["s"]), oracle.mlp_forward(plain, q, rows["s"]),
+                       rtol=1e-13, atol=1e-15)
