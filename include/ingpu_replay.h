@@ -65,6 +65,13 @@ enum { RP_TRAIN_GRAPH = 1, RP_TRAIN_LAYERED = 2 };
  * in-GPU replay does; a batch may repeat an experience).  RP_DISTINCT: a batch never repeats an
  * experience (Methods: what the in-RAM replay does and the author wants back). */
 enum { RP_WITH_REPLACEMENT = 0, RP_DISTINCT = 1 };
+/* train_config.head.  RP_HEAD_PLAIN: the last layer gives Q(s, .) directly.  RP_HEAD_DUELING: the
+ * dueling head of the paper's network (Deep Q-Network Model): the second hidden layer is two
+ * streams side by side, units 0 .. H/2-1 feed a state value V, units H/2 .. H-1 feed one
+ * advantage per action, and Q(s,a) = V(s) + A(s,a) - mean_a' A(s,a').  The last layer then has
+ * 1 + num_actions outputs (V first) in every parameter array: W3[H*(1+A)] b3[1+A]; its weights
+ * from the other stream's units take no part and never change. */
+enum { RP_HEAD_PLAIN = 0, RP_HEAD_DUELING = 1 };
 
 typedef struct {
     uint64_t capacity;    /* number of experiences the replay holds (1,000,000 in the paper) */
@@ -169,9 +176,10 @@ typedef struct {
                                   equation as printed).  N > 0: from a frozen copy of the weights
                                   that is overwritten with the trained ones after every N-th
                                   update (Deep Q-Network Model: target fixing, N = 10,000)      */
+    uint32_t head;             /* RP_HEAD_PLAIN | RP_HEAD_DUELING                              */
 } train_config;
 
-/* number of network parameters: D*H + H + H*H + H + H*A + A */
+/* number of network parameters: D*H + H + H*H + H + H*O + O, O = A (plain head) or 1 + A (dueling) */
 size_t train_param_count(const train_config* cfg);
 /* Bytes of device workspace train_create needs (0 if the configuration is invalid). */
 size_t train_workspace_bytes(const train_config* cfg);

@@ -22,6 +22,7 @@ RP_HUBER, RP_MSE = 0, 1
 RP_SGD, RP_ADAM = 0, 1
 RP_TRAIN_GRAPH, RP_TRAIN_LAYERED = 1, 2
 RP_WITH_REPLACEMENT, RP_DISTINCT = 0, 1
+RP_HEAD_PLAIN, RP_HEAD_DUELING = 0, 1
 
 _NP_STATE = {RP_F32: np.float32, RP_BF16: np.uint16, RP_U8: np.uint8}
 _TORCH_OUT = {RP_F32: torch.float32, RP_BF16: torch.bfloat16, RP_U8: torch.float32}
@@ -44,7 +45,8 @@ class TrainConfig(C.Structure):
                 ("batch", C.c_uint32), ("param_dtype", C.c_uint32), ("loss", C.c_uint32),
                 ("opt", C.c_uint32), ("appends_per_step", C.c_uint32), ("lr", C.c_float),
                 ("gamma", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
-                ("eps", C.c_float), ("flags", C.c_uint32), ("target_sync", C.c_uint32)]
+                ("eps", C.c_float), ("flags", C.c_uint32), ("target_sync", C.c_uint32),
+                ("head", C.c_uint32)]
 
 
 # every symbol include/ingpu_replay.h declares: name -> (restype, argtypes)
@@ -218,12 +220,12 @@ class Trainer:
 
     def __init__(self, replay, hidden, num_actions, batch, param_dtype=RP_F32, loss=RP_HUBER,
                  opt=RP_ADAM, appends_per_step=1, lr=1e-4, gamma=0.99, beta1=0.9, beta2=0.999,
-                 eps=1e-8, use_graph=True, layered=False, target_sync=0, init_params=None):
+                 eps=1e-8, use_graph=True, layered=False, target_sync=0, dueling=False, init_params=None):
         self.replay = replay
         self.cfg = TrainConfig(replay.cfg.state_dim, hidden, num_actions, batch, param_dtype, loss,
                                opt, appends_per_step, lr, gamma, beta1, beta2, eps,
                                (RP_TRAIN_GRAPH if use_graph else 0) | (RP_TRAIN_LAYERED if layered else 0),
-                               target_sync)
+                               target_sync, RP_HEAD_DUELING if dueling else RP_HEAD_PLAIN)
         nbytes = int(lib().train_workspace_bytes(C.byref(self.cfg)))
         if nbytes == 0:
             raise ReplayError(RP_EINVAL, "invalid train configuration")

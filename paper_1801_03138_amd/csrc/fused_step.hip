@@ -407,6 +407,7 @@ struct WArgs {
     float lr, beta1, beta2, eps;
     TrainCounters* ctr;
     const float* lossi;
+    unsigned int grad_only_job;   // a job whose update another kernel makes (dueling head), or ~0
 };
 
 constexpr unsigned int kTM = 32, kTN = 64, kTK = 128;
@@ -414,8 +415,9 @@ constexpr unsigned int kTM = 32, kTN = 64, kTK = 128;
 // One optimizer update of parameter k with gradient gk, from values loaded earlier.
 // r1 = 1 / (1 - beta1^t), r2 = 1 / (1 - beta2^t).
 __device__ __forceinline__ float opt_apply(const WArgs& p, unsigned int k, float gk, float wk,
-                                           float mk, float vk, float r1, float r2) {
+                                           float mk, float vk, float r1, float r2, bool grad_only) {
     p.g[k] = gk;
+    if (grad_only) return wk;
     if (p.opt == RP_SGD) {
         wk -= p.lr * gk;
     } else {
@@ -523,6 +525,7 @@ __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
     }
 
     const float r1 = 1.f / c1, r2 = 1.f / c2;
+    const bool grad_only = j == p.grad_only_job;
 #pragma unroll
     for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
@@ -530,10 +533,10 @@ __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
             const unsigned int m = m0 + 16u * rt + 4u * lq + v;
             if (!col_ok || m >= jb.M) continue;
             const float wk = opt_apply(p, jb.w_off + m * jb.ldw + nn, acc[rt][v], w_old[rt][v],
-                                       m_old[rt][v], v_old[rt][v], r1, r2);
+                                       m_old[rt][v], v_old[rt][v], r1, r2, grad_only);
             if (jb.wT) jb.wT[(size_t)nn * jb.M + m] = wk;
         }
-    if (do_bias) opt_apply(p, jb.b_off + nn, accb[0], wb_old, mb_old, vb_old, r1, r2);
+    if (do_bias) opt_apply(p, jb.b_off + nn, accb[0], wb_old, mb_old, vb_old, r1, r2, grad_only);
     if (blockIdx.x == 0 && tid < 64) {
         const float s = wave_sum(loss_part);
         if (tid == 0) {
@@ -627,9 +630,14 @@ hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* bat
     w.w = t->w; w.g = t->g; w.m = t->m; w.v = t->v;
     w.opt = t->cfg.opt; w.lr = t->cfg.lr; w.beta1 = t->cfg.beta1; w.beta2 = t->cfg.beta2;
     w.eps = t->cfg.eps; w.ctr = t->ctr; w.lossi = t->lossi;
+    w.grad_only_job = t->dueling ? 2u : ~0u;
     hipLaunchKernelGGL(fused_weights_kernel, dim3(nt), dim3(kThreads), 0, st, w);
-    if (count) *count = 2;
-    return hipGetLastError();
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    unsigned int nh = 0;
+    e = enqueue_head_update(t, st, &nh);
+    if (count) *count = 2 + nh;
+    return e;
 }
 
 }  // namespace rp

@@ -261,7 +261,7 @@ struct WsLayout {
     // mixed-precision step on MFMA
     size_t W1T, W2b, W2T, W3T, W1Tt, W2Tt, W3Tt, XT, H1T, H2T, dQTh, dQTl, dZ2T, dZ1T, part3, part1;
     unsigned int Dp, Ap, Bp;
-    size_t n_params, n_padded, elem;
+    size_t n_params, n_padded, n_head, elem;
     size_t oW1, ob1, oW2, ob2, oW3, ob3;
 };
 
@@ -269,13 +269,15 @@ bool ws_layout(const train_config* c, WsLayout* L) {
     if (!c || c->state_dim == 0 || c->state_dim > 4096 || c->hidden == 0 || c->hidden % 64 != 0 ||
         c->hidden > 8192 || c->num_actions == 0 || c->num_actions > 4096 || c->batch == 0 ||
         c->batch > (1u << 20) || (c->param_dtype != RP_F32 && c->param_dtype != RP_BF16) ||
-        c->loss > RP_MSE || c->opt > RP_ADAM)
+        c->loss > RP_MSE || c->opt > RP_ADAM || c->head > RP_HEAD_DUELING)
         return false;
     const size_t D = c->state_dim, H = c->hidden, A = c->num_actions, B = c->batch;
     L->Dp = (unsigned int)align_up(D, 32);
     L->Ap = (unsigned int)align_up(A, 32);
     L->elem = c->param_dtype == RP_BF16 ? 2 : 4;
-    L->n_params = D * H + H + H * H + H + H * A + A;
+    const size_t O = c->head == RP_HEAD_DUELING ? A + 1 : A;   // outputs of the last layer
+    L->n_params = D * H + H + H * H + H + H * O + O;
+    L->n_head = c->head == RP_HEAD_DUELING ? (H + 1) * O : 0;
     L->oW1 = 0;
     L->ob1 = L->oW1 + (size_t)L->Dp * H;
     L->oW2 = L->ob1 + H;
@@ -290,11 +292,12 @@ bool ws_layout(const train_config* c, WsLayout* L) {
         return at;
     };
     L->ctr = take(sizeof(TrainCounters));
-    L->w = take(L->n_padded * 4);
-    L->g = take(L->n_padded * 4);
-    L->m = take(L->n_padded * 4);
-    L->v = take(L->n_padded * 4);
-    L->wt = take(c->target_sync ? L->n_padded * 4 : 0);
+    const size_t n_dev = L->n_padded + L->n_head;
+    L->w = take(n_dev * 4);
+    L->g = take(n_dev * 4);
+    L->m = take(n_dev * 4);
+    L->v = take(n_dev * 4);
+    L->wt = take(c->target_sync ? n_dev * 4 : 0);
     L->w2t = take(c->param_dtype == RP_F32 ? H * H * 4 : 0);
     L->wb = take(c->param_dtype == RP_BF16 ? L->n_padded * 2 : 0);
     L->wbt = take(c->param_dtype == RP_BF16 && c->target_sync ? L->n_padded * 2 : 0);
@@ -337,18 +340,44 @@ bool ws_layout(const train_config* c, WsLayout* L) {
     return true;
 }
 
-// external [W1 b1 W2 b2 W3 b3] <-> padded device order (zero rows / columns as padding)
-void pad_params(const trainer* t, const float* ext, std::vector<float>& pad) {
+// Whether the dueling head has a weight from hidden unit k (k = H: the bias) to output o
+// (0 = state value, fed by units 0 .. H/2-1; 1 + a = advantage of action a, fed by the rest).
+__host__ __device__ inline bool head_connected(unsigned int H, unsigned int k, unsigned int o) {
+    if (k >= H) return true;
+    return o == 0 ? k < H / 2 : k >= H / 2;
+}
+
+// external [W1 b1 W2 b2 W3 b3] <-> device order: padded arrays (zero rows / columns as padding)
+// and, for the dueling head, its own parameters behind them.  `weights`: also fill positions
+// W3 / b3 of the padded part with the plain output layer the dueling head amounts to.
+void pad_params(const trainer* t, const float* ext, std::vector<float>& pad, bool weights = true) {
     const size_t D = t->cfg.state_dim, H = t->H, A = t->cfg.num_actions, Ap = t->Ap;
-    pad.assign(t->n_padded, 0.f);
+    pad.assign(t->n_dev, 0.f);
     const float* p = ext;
     memcpy(&pad[t->oW1], p, D * H * 4); p += D * H;
     memcpy(&pad[t->ob1], p, H * 4);     p += H;
     memcpy(&pad[t->oW2], p, H * H * 4); p += H * H;
     memcpy(&pad[t->ob2], p, H * 4);     p += H;
-    for (size_t k = 0; k < H; ++k) memcpy(&pad[t->oW3 + k * Ap], p + k * A, A * 4);
-    p += H * A;
-    memcpy(&pad[t->ob3], p, A * 4);
+    if (!t->dueling) {
+        for (size_t k = 0; k < H; ++k) memcpy(&pad[t->oW3 + k * Ap], p + k * A, A * 4);
+        p += H * A;
+        memcpy(&pad[t->ob3], p, A * 4);
+        return;
+    }
+    const size_t O = A + 1;
+    float* head = &pad[t->n_padded];
+    memcpy(head, p, (H + 1) * O * 4);          // W3[H x O] followed by b3[O] = [(H+1) x O]
+    if (!weights) return;
+    for (size_t k = 0; k <= H; ++k) {
+        const float* row = head + k * O;
+        const float v = head_connected((unsigned int)H, (unsigned int)k, 0) ? row[0] : 0.f;
+        const bool adv_on = head_connected((unsigned int)H, (unsigned int)k, 1);
+        float sum = 0.f;
+        for (size_t a = 0; a < A; ++a) sum += adv_on ? row[1 + a] : 0.f;
+        const float mean = sum / (float)A;
+        float* dst = k < H ? &pad[t->oW3 + k * Ap] : &pad[t->ob3];
+        for (size_t a = 0; a < A; ++a) dst[a] = v + (adv_on ? row[1 + a] : 0.f) - mean;
+    }
 }
 
 void unpad_params(const trainer* t, const std::vector<float>& pad, float* ext) {
@@ -358,9 +387,78 @@ void unpad_params(const trainer* t, const std::vector<float>& pad, float* ext) {
     memcpy(p, &pad[t->ob1], H * 4);     p += H;
     memcpy(p, &pad[t->oW2], H * H * 4); p += H * H;
     memcpy(p, &pad[t->ob2], H * 4);     p += H;
+    if (t->dueling) {
+        memcpy(p, &pad[t->n_padded], (H + 1) * (A + 1) * 4);
+        return;
+    }
     for (size_t k = 0; k < H; ++k) memcpy(p + k * A, &pad[t->oW3 + k * Ap], A * 4);
     p += H * A;
     memcpy(p, &pad[t->ob3], A * 4);
+}
+
+// ----------------------------------------------------------------------------- dueling head
+// One thread per hidden unit k (k = H: the biases).  g holds the gradient of the equivalent
+// plain output layer, dW[k][a]; the head's own gradients follow from the combine
+// Q = V + A - mean A:  dV[k] = sum_a dW[k][a],  dA[k][a] = dW[k][a] - mean_a' dW[k][a'],
+// restricted to the weights the head has.  After the optimizer step the equivalent layer is
+// rebuilt, with its bf16 copies, and the target network takes it all when a sync is due.
+struct HeadArgs {
+    unsigned int H, A, Ap;
+    size_t oW3, ob3, n_padded;
+    float *w, *g, *m, *v, *wt;
+    unsigned int opt, sync_every;
+    float lr, beta1, beta2, eps;
+    const TrainCounters* ctr;
+    unsigned short *W3T, *W3T_t;   // MFMA step: [Ap x H] operand copies (trained / target)
+    bf16_t *wb, *wbt;              // layered mixed precision: padded bf16 copies
+};
+
+__global__ __launch_bounds__(kThreads) void dueling_head_kernel(HeadArgs p) {
+    const unsigned int k = blockIdx.x * kThreads + threadIdx.x;
+    if (k > p.H) return;
+    const unsigned int A = p.A, O = A + 1;
+    const size_t eff = k < p.H ? p.oW3 + (size_t)k * p.Ap : p.ob3;   // row k of the plain layer
+    const size_t head = p.n_padded + (size_t)k * O;
+    const bool v_on = head_connected(p.H, k, 0), a_on = head_connected(p.H, k, 1);
+    const float c1 = p.ctr->c1, c2 = p.ctr->c2;
+    const bool sync = p.wt && p.sync_every && p.ctr->adam_t % p.sync_every == 0;
+
+    float gsum = 0.f;
+    for (unsigned int a = 0; a < A; ++a) gsum += p.g[eff + a];
+    const float gmean = gsum / (float)A;
+    float vnew = 0.f, asum = 0.f;
+    for (unsigned int o = 0; o < O; ++o) {
+        const bool on = o == 0 ? v_on : a_on;
+        const float gk = !on ? 0.f : o == 0 ? gsum : p.g[eff + o - 1] - gmean;
+        float wk = p.w[head + o];
+        p.g[head + o] = gk;
+        if (on) {
+            if (p.opt == RP_SGD) {
+                wk -= p.lr * gk;
+            } else {
+                const float mk = p.beta1 * p.m[head + o] + (1.f - p.beta1) * gk;
+                const float vk = p.beta2 * p.v[head + o] + (1.f - p.beta2) * gk * gk;
+                p.m[head + o] = mk;
+                p.v[head + o] = vk;
+                wk -= p.lr * (mk / c1) / (sqrtf(vk / c2) + p.eps);
+            }
+            p.w[head + o] = wk;
+            if (o == 0) vnew = wk; else asum += wk;
+        }
+        if (sync) p.wt[head + o] = wk;
+    }
+    const float amean = asum / (float)A;
+    for (unsigned int a = 0; a < A; ++a) {
+        const float e = vnew + (a_on ? p.w[head + 1 + a] : 0.f) - amean;
+        p.w[eff + a] = e;
+        if (p.wb) p.wb[eff + a] = from_float<bf16_t>(e);
+        if (p.W3T && k < p.H) p.W3T[(size_t)a * p.H + k] = bf16_bits_rne(e);
+        if (sync) {
+            p.wt[eff + a] = e;
+            if (p.wbt) p.wbt[eff + a] = from_float<bf16_t>(e);
+            if (p.W3T_t && k < p.H) p.W3T_t[(size_t)a * p.H + k] = bf16_bits_rne(e);
+        }
+    }
 }
 
 template <typename TA, typename TB, typename TC, bool TRA, bool TRB, int EPI>
@@ -452,11 +550,16 @@ hipError_t enqueue_step(trainer* t, hipStream_t st, unsigned int* count, bool sa
     hipLaunchKernelGGL(colsum_kernel<E>, dim3((H + kThreads - 1) / kThreads), dim3(kThreads), 0, st,
                        B, H, static_cast<const E*>(t->dZ1), H, t->g + t->ob1); ++n;
     // update
-    hipLaunchKernelGGL(optimizer_kernel, dim3((t->n_padded + kThreads - 1) / kThreads),
-                       dim3(kThreads), 0, st, (unsigned int)t->n_padded, t->w, t->g, t->m, t->v,
+    // (with the dueling head the output layer's update belongs to the head kernel)
+    const unsigned int n_opt = (unsigned int)(t->dueling ? t->oW3 : t->n_padded);
+    hipLaunchKernelGGL(optimizer_kernel, dim3((n_opt + kThreads - 1) / kThreads),
+                       dim3(kThreads), 0, st, n_opt, t->w, t->g, t->m, t->v,
                        t->wb, t->cfg.opt, t->cfg.lr, t->cfg.beta1, t->cfg.beta2, t->cfg.eps, t->ctr,
                        t->lossi, t->B, t->wt, t->wbt, t->cfg.target_sync); ++n;
-    if (count) *count = n;
+    unsigned int nh = 0;
+    e = enqueue_head_update(t, st, &nh);
+    if (e != hipSuccess) return e;
+    if (count) *count = n + nh;
     return hipGetLastError();
 }
 
@@ -575,6 +678,27 @@ void set_payload_args(trainer* t, const Payload& src, unsigned int k) {
 }
 
 }  // namespace
+
+hipError_t enqueue_head_update(trainer* t, hipStream_t st, unsigned int* count) {
+    if (count) *count = 0;
+    if (!t->dueling) return hipSuccess;
+    HeadArgs a;
+    a.H = t->H; a.A = t->cfg.num_actions; a.Ap = t->Ap;
+    a.oW3 = t->oW3; a.ob3 = t->ob3; a.n_padded = t->n_padded;
+    a.w = t->w; a.g = t->g; a.m = t->m; a.v = t->v; a.wt = t->wt;
+    a.opt = t->cfg.opt; a.sync_every = t->cfg.target_sync;
+    a.lr = t->cfg.lr; a.beta1 = t->cfg.beta1; a.beta2 = t->cfg.beta2; a.eps = t->cfg.eps;
+    a.ctr = t->ctr;
+    a.W3T = t->wide ? t->wd.W3T : nullptr;
+    a.W3T_t = t->wide && t->wt ? t->wd.W3T_t : nullptr;
+    a.wb = t->wide ? nullptr : t->wb;
+    a.wbt = t->wide ? nullptr : t->wbt;
+    hipLaunchKernelGGL(dueling_head_kernel, dim3((t->H + 1 + kThreads - 1) / kThreads), dim3(kThreads),
+                       0, st, a);
+    if (count) *count = 1;
+    return hipGetLastError();
+}
+
 }  // namespace rp
 
 extern "C" {
@@ -621,6 +745,9 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
     t->rp_ = rp_;
     t->Dp = L.Dp; t->Ap = L.Ap; t->H = cfg->hidden; t->B = cfg->batch; t->Bp = L.Bp;
     t->n_params = L.n_params; t->n_padded = L.n_padded; t->elem = L.elem;
+    t->dueling = cfg->head == RP_HEAD_DUELING;
+    t->n_head = L.n_head;
+    t->n_dev = L.n_padded + L.n_head;
     t->oW1 = L.oW1; t->ob1 = L.ob1; t->oW2 = L.oW2; t->ob2 = L.ob2; t->oW3 = L.oW3; t->ob3 = L.ob3;
     unsigned char* ws = static_cast<unsigned char*>(dev_workspace);
     t->ws = ws;
@@ -756,9 +883,10 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
     } else {
         // the launch count is static
         t->kernels_per_step =
-            t->fused ? 2u
-                     : (cfg->appends_per_step ? 1u : 0u) +
-                           (t->wide ? (t->wt && cfg->batch % 128 ? 13u : 10u) : (t->wt ? 17u : 14u));
+            (t->dueling ? 1u : 0u) +
+            (t->fused ? 2u
+                      : (cfg->appends_per_step ? 1u : 0u) +
+                            (t->wide ? (t->wt && cfg->batch % 128 ? 13u : 10u) : (t->wt ? 17u : 14u)));
     }
     *out = t;
     return RP_OK;
@@ -928,18 +1056,18 @@ rp_status train_steps(trainer_t* t, uint64_t count, const void* s, const void* s
 
 rp_status train_get_params(trainer_t* t, float* params) {
     RP_REQUIRE(t && params, "train_get_params: null argument");
-    std::vector<float> pad(t->n_padded);
+    std::vector<float> pad(t->n_dev);
     RP_CHECK_HIP(hipDeviceSynchronize());
-    RP_CHECK_HIP(hipMemcpy(pad.data(), t->w, t->n_padded * 4, hipMemcpyDeviceToHost));
+    RP_CHECK_HIP(hipMemcpy(pad.data(), t->w, t->n_dev * 4, hipMemcpyDeviceToHost));
     rp::unpad_params(t, pad, params);
     return RP_OK;
 }
 
 rp_status train_get_target(trainer_t* t, float* params) {
     RP_REQUIRE(t && params, "train_get_target: null argument");
-    std::vector<float> pad(t->n_padded);
+    std::vector<float> pad(t->n_dev);
     RP_CHECK_HIP(hipDeviceSynchronize());
-    RP_CHECK_HIP(hipMemcpy(pad.data(), t->wt ? t->wt : t->w, t->n_padded * 4, hipMemcpyDeviceToHost));
+    RP_CHECK_HIP(hipMemcpy(pad.data(), t->wt ? t->wt : t->w, t->n_dev * 4, hipMemcpyDeviceToHost));
     rp::unpad_params(t, pad, params);
     return RP_OK;
 }
@@ -950,7 +1078,7 @@ rp_status train_set_target(trainer_t* t, const float* params) {
     std::vector<float> pad;
     RP_CHECK_HIP(hipDeviceSynchronize());
     rp::pad_params(t, params, pad);
-    RP_CHECK_HIP(hipMemcpy(t->wt, pad.data(), t->n_padded * 4, hipMemcpyHostToDevice));
+    RP_CHECK_HIP(hipMemcpy(t->wt, pad.data(), t->n_dev * 4, hipMemcpyHostToDevice));
     if (t->wide) RP_CHECK_HIP(rp::wide_set_weights(t, pad.data(), true));
     if (t->wbt) {
         hipLaunchKernelGGL(rp::to_bf16_kernel, dim3((t->n_padded + rp::kThreads - 1) / rp::kThreads),
@@ -963,23 +1091,23 @@ rp_status train_set_target(trainer_t* t, const float* params) {
 
 rp_status train_get_grads(trainer_t* t, float* grads) {
     RP_REQUIRE(t && grads, "train_get_grads: null argument");
-    std::vector<float> pad(t->n_padded);
+    std::vector<float> pad(t->n_dev);
     RP_CHECK_HIP(hipDeviceSynchronize());
-    RP_CHECK_HIP(hipMemcpy(pad.data(), t->g, t->n_padded * 4, hipMemcpyDeviceToHost));
+    RP_CHECK_HIP(hipMemcpy(pad.data(), t->g, t->n_dev * 4, hipMemcpyDeviceToHost));
     rp::unpad_params(t, pad, grads);
     return RP_OK;
 }
 
 rp_status train_get_opt_state(trainer_t* t, float* m, float* v, uint64_t* adam_t, uint64_t* step) {
     RP_REQUIRE(t, "train_get_opt_state: null handle");
-    std::vector<float> pad(t->n_padded);
+    std::vector<float> pad(t->n_dev);
     RP_CHECK_HIP(hipDeviceSynchronize());
     if (m) {
-        RP_CHECK_HIP(hipMemcpy(pad.data(), t->m, t->n_padded * 4, hipMemcpyDeviceToHost));
+        RP_CHECK_HIP(hipMemcpy(pad.data(), t->m, t->n_dev * 4, hipMemcpyDeviceToHost));
         rp::unpad_params(t, pad, m);
     }
     if (v) {
-        RP_CHECK_HIP(hipMemcpy(pad.data(), t->v, t->n_padded * 4, hipMemcpyDeviceToHost));
+        RP_CHECK_HIP(hipMemcpy(pad.data(), t->v, t->n_dev * 4, hipMemcpyDeviceToHost));
         rp::unpad_params(t, pad, v);
     }
     TrainCounters c;
@@ -995,7 +1123,7 @@ rp_status train_set_state(trainer_t* t, const float* params, const float* m, con
     std::vector<float> pad;
     RP_CHECK_HIP(hipDeviceSynchronize());
     rp::pad_params(t, params, pad);
-    RP_CHECK_HIP(hipMemcpy(t->w, pad.data(), t->n_padded * 4, hipMemcpyHostToDevice));
+    RP_CHECK_HIP(hipMemcpy(t->w, pad.data(), t->n_dev * 4, hipMemcpyHostToDevice));
     if (t->wide) RP_CHECK_HIP(rp::wide_set_weights(t, pad.data(), false));
     if (t->w2t) {
         const size_t H = t->H;
@@ -1005,12 +1133,12 @@ rp_status train_set_state(trainer_t* t, const float* params, const float* m, con
         RP_CHECK_HIP(hipMemcpy(t->w2t, tr.data(), H * H * 4, hipMemcpyHostToDevice));
     }
     if (m) {
-        rp::pad_params(t, m, pad);
-        RP_CHECK_HIP(hipMemcpy(t->m, pad.data(), t->n_padded * 4, hipMemcpyHostToDevice));
+        rp::pad_params(t, m, pad, false);
+        RP_CHECK_HIP(hipMemcpy(t->m, pad.data(), t->n_dev * 4, hipMemcpyHostToDevice));
     }
     if (v) {
-        rp::pad_params(t, v, pad);
-        RP_CHECK_HIP(hipMemcpy(t->v, pad.data(), t->n_padded * 4, hipMemcpyHostToDevice));
+        rp::pad_params(t, v, pad, false);
+        RP_CHECK_HIP(hipMemcpy(t->v, pad.data(), t->n_dev * 4, hipMemcpyHostToDevice));
     }
     TrainCounters c;
     RP_CHECK_HIP(hipMemcpy(&c, t->ctr, sizeof(c), hipMemcpyDeviceToHost));

@@ -103,6 +103,12 @@ struct trainer {
     replay* rp_;
     unsigned int Dp, Ap, H, B, Bp;
     size_t n_params, n_padded;       // external / padded parameter counts
+    // Dueling head: the arrays w, g, m, v, wt each continue past their n_padded entries with the
+    // head's own parameters [(H+1) x (1+A)] (row H = biases); positions oW3.. / ob3.. of w then
+    // hold the equivalent plain output layer W[k][a] = V[k] + A[k][a] - mean_a' A[k][a'], which
+    // is all the forward and backward kernels see.
+    bool dueling;
+    size_t n_head, n_dev;            // head parameters; entries per device array (n_padded + n_head)
     size_t oW1, ob1, oW2, ob2, oW3, ob3;
     size_t elem;                     // bytes of an activation element
     unsigned char* ws;
@@ -165,6 +171,9 @@ bool fused_step_supported(const train_config& cfg, const replay* rp_);
 hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* batch, hipStream_t st,
                               unsigned int* count);
 void* fused_rows_func();
+// Dueling head: turn the gradient of the equivalent plain output layer (in g) into the head's
+// update and refresh that layer (and its bf16 / target copies).  No-op for a plain head.
+hipError_t enqueue_head_update(trainer* t, hipStream_t st, unsigned int* count);
 // Mixed-precision step on MFMA (bf16 replay states and matrix operands).
 bool wide_step_supported(const train_config& cfg, const replay* rp_);
 hipError_t wide_init_buffers(trainer* t);                       // once, after the workspace is cleared

@@ -655,6 +655,7 @@ struct SmallOptArgs {
     bf16_bits *W1T_target, *W3T_target;   // the target network's, or null
     TrainCounters* ctr;
     const float* lossi;
+    unsigned int out_grad_only;   // dueling head: only store the output layer's gradient
 };
 
 __global__ __launch_bounds__(256) void small_opt_kernel(SmallOptArgs p) {
@@ -674,7 +675,9 @@ __global__ __launch_bounds__(256) void small_opt_kernel(SmallOptArgs p) {
         float g = 0.f;
 #pragma unroll
         for (unsigned int z = 0; z < 16; ++z) g += hi[z] + lo[z];
-        if (m < p.H) {
+        if (p.out_grad_only) {
+            p.o.g[m < p.H ? p.oW3 + (size_t)m * p.Ap + a : p.ob3 + a] = g;
+        } else if (m < p.H) {
             const bf16_bits h = bf16_bits_rne(opt_update(p.o, p.oW3 + (size_t)m * p.Ap + a, g, st));
             p.W3T[(size_t)a * p.H + m] = h;
             if (st.sync) p.W3T_target[(size_t)a * p.H + m] = h;
@@ -902,9 +905,14 @@ hipError_t enqueue_wide_step(trainer* t, hipStream_t st, unsigned int* count, bo
         a.oW1 = t->oW1; a.ob1 = t->ob1; a.oW3 = t->oW3; a.ob3 = t->ob3;
         a.W1T = w.W1T; a.W3T = w.W3T; a.W1T_target = w.W1T_t; a.W3T_target = w.W3T_t;
         a.ctr = t->ctr; a.lossi = t->lossi;
+        a.out_grad_only = t->dueling ? 1u : 0u;
         const unsigned int elems = (H + 1) * Ap + H * (D + 1);
         hipLaunchKernelGGL(small_opt_kernel, dim3((elems + 255) / 256), dim3(256), 0, st, a);
         ++n;
+        unsigned int nh = 0;
+        e = enqueue_head_update(t, st, &nh);
+        if (e != hipSuccess) return e;
+        n += nh;
     }
     if (count) *count = n;
     return hipGetLastError();

@@ -46,7 +46,7 @@ class Pair:
 
     def __init__(self, B, *, capacity, D, H, A, batch, burn_in, seed, dtype="f32", loss="huber",
                  opt="adam", lr=1e-4, appends=1, use_graph=True, max_append=4096, layered=False,
-                 target_sync=0, distinct=False):
+                 target_sync=0, distinct=False, dueling=False):
         self.B, self.D, self.H, self.A, self.batch, self.seed = B, D, H, A, batch, seed
         self.bf16 = dtype == "bf16"
         self.target_sync = target_sync
@@ -56,18 +56,19 @@ class Pair:
                                  max_append=max_append, distinct=distinct)
         self.ref_ring = oracle.Ring(capacity, D, oracle.BF16 if self.bf16 else oracle.F32,
                                     oracle.PAIR, burn_in=burn_in)
-        self.p0 = synth.init_params(D, H, A, seed)
+        self.p0 = synth.init_params(D, H, A + (1 if dueling else 0), seed)
         f = np.float32
         self.hyper = dict(lr=f(lr), gamma=f(0.99), beta1=f(0.9), beta2=f(0.999), eps=f(1e-8))
         self.trainer = B.Trainer(self.gpu_ring, H, A, batch, param_dtype=sd,
                                  loss=B.RP_HUBER if loss == "huber" else B.RP_MSE,
                                  opt=B.RP_ADAM if opt == "adam" else B.RP_SGD,
                                  appends_per_step=appends, use_graph=use_graph, layered=layered,
-                                 target_sync=target_sync, init_params=self.p0, **{k: float(v) for k, v in self.hyper.items()})
+                                 target_sync=target_sync, dueling=dueling, init_params=self.p0, **{k: float(v) for k, v in self.hyper.items()})
         self.cfg = oracle.make_cfg(D, H, A, batch,
                                    loss=oracle.HUBER if loss == "huber" else oracle.MSE,
                                    opt=oracle.ADAM if opt == "adam" else oracle.SGD,
-                                   bf16=int(self.bf16), **{k: float(v) for k, v in self.hyper.items()})
+                                   bf16=int(self.bf16), dueling=int(dueling),
+                                   **{k: float(v) for k, v in self.hyper.items()})
         self.rtol = BF16_RTOL if self.bf16 else F32_RTOL
 
     def append_only(self, part, device_src=True):
@@ -428,3 +429,25 @@ def test_train_step_with_batches_without_duplicates(B, dtype, H, layered):
             assert len(set(pr.trainer.last()["idx"].tolist())) == 40 or k % 20
     assert executed == 150 - 19
     assert pr.gpu_ring.state() == pr.ref_ring.state()
+
+
+@pytest.mark.parametrize("dtype,H,batch,layered,target_sync,kernels", [
+    ("f32", 64, 50, False, 0, 3), ("f32", 64, 50, True, 0, 16), ("f32", 128, 33, False, 5, 19),
+    ("bf16", 128, 200, False, 0, 12), ("bf16", 64, 256, False, 5, 12), ("bf16", 128, 96, True, 0, 16)])
+def test_dueling_head(B, dtype, H, batch, layered, target_sync, kernels):
+    """Q = V + A - mean A with a value stream and an advantage stream (Deep Q-Network Model), on
+    every kind of step, alone and together with the frozen target network."""
+    A = 30
+    rows = synth.experiences(300, 27, A, 0.05, seed=37, state_dtype=dtype)
+    pr = Pair(B, capacity=256, D=27, H=H, A=A, batch=batch, burn_in=60, seed=6, dtype=dtype,
+              appends=2, layered=layered, target_sync=target_sync, dueling=True, lr=1e-3)
+    assert pr.trainer.kernels_per_step() == kernels
+    assert len(pr.trainer.params()) == 27 * H + H + H * H + H + H * (A + 1) + A + 1
+    for k in range(0, 300, 2):
+        pr.step(synth.take(rows, k, k + 2), compare=(k % 20 == 0) or k >= 290)
+    # weights between the two streams never move, and the mean over actions of Q is the value V
+    p0, p1 = pr.p0, pr.trainer.params()
+    oW3 = 27 * H + H + H * H + H
+    W3a, W3b = (x[oW3:oW3 + H * (A + 1)].reshape(H, A + 1) for x in (p0, p1))
+    assert np.array_equal(W3a[H // 2:, 0], W3b[H // 2:, 0]) and np.array_equal(W3a[:H // 2, 1:], W3b[:H // 2, 1:])
+    assert not np.array_equal(W3a[:H // 2, 0], W3b[:H // 2, 0])
