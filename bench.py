@@ -98,14 +98,16 @@ def prefill(ring, rows, n_total):
 
 
 # ----------------------------------------------------------------------------- legs
-def leg_paper_shaped(B, synth, steps, warmup, full_ring, host_payload=False):
+def leg_paper_shaped(B, synth, steps, warmup, full_ring, host_payload=False, target_sync=0,
+                     dueling=False):
     import torch
     c = P_CFG
     ring = B.Replay(c["capacity"], c["D"], burn_in=c["burn_in"], seed=0, max_append=4096)
     base = synth.experiences(100_000, c["D"], c["A"], c["p_term"], seed=0)
     prefill(ring, base, c["capacity"] if full_ring else c["burn_in"])
     tr = B.Trainer(ring, c["H"], c["A"], c["B"], opt=B.RP_ADAM, loss=B.RP_HUBER, lr=c["lr"],
-                   appends_per_step=c["appends"], init_params=synth.init_params(c["D"], c["H"], c["A"], 0))
+                   appends_per_step=c["appends"], target_sync=target_sync, dueling=dueling,
+                   init_params=synth.init_params(c["D"], c["H"], c["A"] + (1 if dueling else 0), 0))
     stream_rows = synth.experiences(steps + warmup, c["D"], c["A"], c["p_term"], seed=1)
     src = stream_rows if host_payload else dev_rows(stream_rows)
     w = {k: v[:warmup] for k, v in src.items()}
@@ -339,7 +341,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10_000)
     ap.add_argument("--warmup", type=int, default=500)
-    ap.add_argument("--legs", default="p,pfull,phost,inram,gather,append,copy,large,wide,cpu")
+    ap.add_argument("--legs", default="p,pfull,phost,pmodel,inram,gather,append,copy,large,wide,cpu")
     ap.add_argument("--gather-reps", type=int, default=1000)
     ap.add_argument("--wide-steps", type=int, default=200)
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
@@ -369,6 +371,17 @@ def main():
         out["paper_shaped_host_payload"] = leg_paper_shaped(B, synth, args.steps, args.warmup,
                                                             False, host_payload=True)
         log("[bench]   %.0f steps/s" % out["paper_shaped_host_payload"]["steps_per_s"])
+    if "pmodel" in legs:
+        log("[bench] paper-shaped train steps with the paper's model options (frozen target network "
+            "synced every 10,000 updates; dueling head) ...")
+        out["paper_shaped_target_network"] = leg_paper_shaped(B, synth, args.steps, args.warmup, False,
+                                                              target_sync=10_000)
+        out["paper_shaped_dueling"] = leg_paper_shaped(B, synth, args.steps, args.warmup, False, dueling=True)
+        out["paper_shaped_dueling_target_network"] = leg_paper_shaped(
+            B, synth, args.steps, args.warmup, False, target_sync=10_000, dueling=True)
+        for k in ("paper_shaped_target_network", "paper_shaped_dueling", "paper_shaped_dueling_target_network"):
+            log("[bench]   %-38s %8.0f steps/s, %d kernels/step" %
+                (k, out[k]["steps_per_s"], out[k]["kernels_per_step"]))
     if "inram" in legs:
         log("[bench] device-resident replay vs in-RAM replay with a per-step batch copy ...")
         out["device_vs_inram"] = leg_device_vs_inram(B, synth, min(args.steps, 4000), 200)

@@ -184,7 +184,8 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
 
     // The state that follows this step is known up front (the host mirrors it exactly): one
     // thread stores it for the kernels and calls that read it later, off everyone's critical path.
-    if (blockIdx.x == 0 && tid == kRowThreads - 1) {
+    const bool target_pass = p.mode == kRowsTargetPass;
+    if (blockIdx.x == 0 && tid == kRowThreads - 1 && !target_pass) {
         unsigned long long h = head + n;
         if (h >= cap) h -= cap;
         p.g.state->head = h;
@@ -223,7 +224,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     // The last workgroup also writes the new experiences into the ring.  No workgroup reads
     // those slots from the ring in this launch (see above), so this can go out right away and
     // its latency is hidden behind the rest of the kernel.
-    if (blockIdx.x == gridDim.x - 1 && n) {
+    if (blockIdx.x == gridDim.x - 1 && n && !target_pass) {
         const unsigned int rw = p.g.row_bytes >> 2;
         for (unsigned long long e = tid; e < n * rw; e += kRowThreads) {
             const unsigned long long k = e / rw;
@@ -253,10 +254,10 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
             const unsigned int val = gval[pass];
             if (w < D) {
                 Xs[r * ldx + w] = __uint_as_float(val);
-                p.X[(size_t)i * Dp + w] = __uint_as_float(val);
+                if (!target_pass) p.X[(size_t)i * Dp + w] = __uint_as_float(val);
             } else if (w < 2 * D) {
                 Xs[(4 + r) * ldx + w - D] = __uint_as_float(val);
-            } else {
+            } else if (!target_pass) {
                 meta[r * 4 + (w - 2 * D)] = val;
                 if (w == 2 * D) {
                     p.act[i] = (int)val;
@@ -299,7 +300,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
         float v = sum_part(part, 4, 8, kChunk, row, c) + b1s[c];
         v = v > 0.f ? v : 0.f;
         H1s[row * ldh + c] = v;
-        if (row < nrows) p.H1[(size_t)(i0 + row) * H + c] = v;
+        if (row < nrows && !target_pass) p.H1[(size_t)(i0 + row) * H + c] = v;
     }
     lds_barrier();
 
@@ -312,7 +313,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
         float v = sum_part(part, 4, 8, kChunk, row, c) + b2s[c];
         v = v > 0.f ? v : 0.f;
         H2s[row * ldh + c] = v;
-        if (row < nrows) p.H2[(size_t)(i0 + row) * H + c] = v;
+        if (row < nrows && !target_pass) p.H2[(size_t)(i0 + row) * H + c] = v;
     }
     lds_barrier();
 
@@ -324,7 +325,19 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
         const unsigned int row = e / Ap, c = e - row * Ap, r = row & 3u;
         const float v = sum_part(part, 16, 8, 64, row, c) + b3s[c];
         Qs[row * ldq + c] = v;
-        if (r < nrows) p.Q[((size_t)(row < 4 ? 0 : p.B) + i0 + r) * Ap + c] = v;
+        // Q(s, .) belongs to the trained network's pass, Q(s', .) to the target network's when
+        // there is one
+        const bool mine = row < 4 ? !target_pass : p.mode != kRowsAfterTargetPass;
+        if (r < nrows && mine) p.Q[((size_t)(row < 4 ? 0 : p.B) + i0 + r) * Ap + c] = v;
+    }
+    if (target_pass) return;
+    if (p.mode == kRowsAfterTargetPass) {
+        // Q(s', .) of this workgroup's rows, left in global memory by the target pass
+        lds_barrier();
+        for (unsigned int e = tid; e < nrows * Ap; e += kRowThreads) {
+            const unsigned int r = e / Ap, c = e - r * Ap;
+            Qs[(4 + r) * ldq + c] = p.Q[((size_t)p.B + i0 + r) * Ap + c];
+        }
     }
     lds_barrier();
 
@@ -408,6 +421,8 @@ struct WArgs {
     TrainCounters* ctr;
     const float* lossi;
     unsigned int grad_only_job;   // a job whose update another kernel makes (dueling head), or ~0
+    float* wt;                    // frozen target network, synced when Adam's t is a multiple of
+    unsigned int sync_every;      // sync_every (0: never)
 };
 
 constexpr unsigned int kTM = 32, kTN = 64, kTK = 128;
@@ -428,6 +443,7 @@ __device__ __forceinline__ float opt_apply(const WArgs& p, unsigned int k, float
         wk -= p.lr * (mk * r1) / (sqrtf(vk * r2) + p.eps);
     }
     p.w[k] = wk;
+    if (p.wt && p.sync_every && p.ctr->adam_t % p.sync_every == 0) p.wt[k] = wk;
     return wk;
 }
 
@@ -557,9 +573,6 @@ size_t row_kernel_lds(unsigned int Dp, unsigned int H, unsigned int Ap) {
 bool fused_step_supported(const train_config& cfg, const replay* rp_) {
     if (cfg.param_dtype != RP_F32 || rp_->cfg.state_dtype != RP_F32 || rp_->cfg.layout != RP_PAIR)
         return false;
-    // the row kernel keeps one network's weights in registers: a frozen target network takes the
-    // layered step
-    if (cfg.target_sync) return false;
     // one lane owns one column of a layer and holds its share of the weights in registers:
     // hidden width up to 256, states and action sets up to 64 wide
     if (cfg.hidden % 64 != 0 || cfg.hidden > 256 || cfg.state_dim > 64 || cfg.num_actions > 64)
@@ -582,6 +595,7 @@ hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* bat
     a.src = src;
     a.batch = batch ? *batch : Payload{nullptr, nullptr, nullptr, nullptr, nullptr};
     a.from_batch = batch ? 1u : 0u;
+    a.mode = t->wt ? kRowsAfterTargetPass : kRowsWholeStep;
     {
         // state before this step, from the host mirrors (train_step has not advanced them yet)
         const unsigned long long cap = r->cfg.capacity, after = r->size + a.n_append;
@@ -605,9 +619,23 @@ hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* bat
     a.dZ1 = static_cast<float*>(t->dZ1);
     a.act = t->act; a.rew = t->rew; a.term = t->term; a.idx = t->idx;
     const unsigned int blocks = (t->B + kRows - 1) / kRows;
+    hipError_t e = hipSuccess;
+    unsigned int n_rows_launches = 1;
+    if (t->wt) {
+        // first pass: Q(s', .) with the frozen target network's weights
+        RowArgs& b = t->row_args_target;
+        b = a;
+        b.w = t->wt;
+        b.mode = kRowsTargetPass;
+        void* targs[] = {&b};
+        e = hipLaunchKernel(fused_rows_func(), dim3(blocks), dim3(kRowThreads), targs,
+                            row_kernel_lds(t->Dp, t->H, t->Ap), st);
+        if (e != hipSuccess) return e;
+        n_rows_launches = 2;
+    }
     void* kargs[] = {&a};
-    hipError_t e = hipLaunchKernel(fused_rows_func(), dim3(blocks), dim3(kRowThreads), kargs,
-                                   row_kernel_lds(t->Dp, t->H, t->Ap), st);
+    e = hipLaunchKernel(fused_rows_func(), dim3(blocks), dim3(kRowThreads), kargs,
+                        row_kernel_lds(t->Dp, t->H, t->Ap), st);
     if (e != hipSuccess) return e;
 
     WArgs w;
@@ -631,12 +659,14 @@ hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* bat
     w.opt = t->cfg.opt; w.lr = t->cfg.lr; w.beta1 = t->cfg.beta1; w.beta2 = t->cfg.beta2;
     w.eps = t->cfg.eps; w.ctr = t->ctr; w.lossi = t->lossi;
     w.grad_only_job = t->dueling ? 2u : ~0u;
+    w.wt = t->wt;
+    w.sync_every = t->cfg.target_sync;
     hipLaunchKernelGGL(fused_weights_kernel, dim3(nt), dim3(kThreads), 0, st, w);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     unsigned int nh = 0;
     e = enqueue_head_update(t, st, &nh);
-    if (count) *count = 2 + nh;
+    if (count) *count = 1 + n_rows_launches + nh;
     return e;
 }
 

@@ -52,6 +52,8 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
+enum { kRowsWholeStep = 0, kRowsTargetPass = 1, kRowsAfterTargetPass = 2 };
+
 // Argument block of the fused row kernel.
 struct RowArgs {
     RingGeom g;
@@ -60,6 +62,10 @@ struct RowArgs {
     Payload src;          // this step's new experiences
     Payload batch;        // from_batch: the batch itself, given by the caller instead of sampled
     unsigned int from_batch;
+    // Frozen target network: the row kernel runs twice per step.  kRowsTargetPass: `w` is the
+    // target network; forward only, leaves Q(s', .) in Q and touches nothing else.
+    // kRowsAfterTargetPass: the normal pass, taking Q(s', .) from Q instead of its own forward.
+    unsigned int mode;
     // ring and trainer state before this step, from the host mirror (set before every launch,
     // so the kernel can start drawing without a dependent load)
     unsigned long long head, step;
@@ -140,17 +146,20 @@ struct trainer {
     // kernel of the layered step): host copy of its argument block, and its node in the graph,
     // whose argument is replaced before every launch.
     rp::RowArgs row_args;
+    rp::RowArgs row_args_target;     // fused step with a frozen target network: its first pass
     rp::AppendArgs append_args;
     void* payload_func;
-    void* payload_kargs[1];
-    hipGraphNode_t payload_node;
-    hipKernelNodeParams payload_np;
+    void* payload_kargs[1];          // -> row_args / append_args
+    void* payload_kargs_target[1];   // -> row_args_target
+    unsigned int payload_per_step;   // payload nodes per recorded step: 1, or 2 with the target pass first
+    hipGraphNode_t payload_node[2];
+    hipKernelNodeParams payload_np[2];
     // kGraphSteps consecutive steps recorded as one graph, for train_steps: one launch (and one
     // launch gap on the GPU) per kGraphSteps steps; each step's payload kernel has its own node.
     hipGraph_t multi_graph;
     hipGraphExec_t multi_exec;
-    hipGraphNode_t multi_node[rp::kGraphSteps];
-    hipKernelNodeParams multi_np[rp::kGraphSteps];
+    hipGraphNode_t multi_node[2 * rp::kGraphSteps];
+    hipKernelNodeParams multi_np[2 * rp::kGraphSteps];
     // Host-sourced payloads are copied into a ring of pinned, device-mapped host slots that the
     // kernel reads directly; an event per group of slots tells when a group may be reused.
     unsigned char* pin_host;

@@ -389,12 +389,13 @@ def test_in_ram_replay_trains_on_the_same_batches_as_the_device_replay(B):
 
 
 @pytest.mark.parametrize("dtype,H,batch,layered,kernels", [
-    ("f32", 64, 50, False, 18), ("bf16", 128, 200, False, 14), ("bf16", 64, 256, False, 11),
-    ("bf16", 128, 96, True, 18)])
+    ("f32", 64, 50, False, 3), ("f32", 64, 50, True, 18), ("f32", 256, 128, False, 3),
+    ("bf16", 128, 200, False, 14), ("bf16", 64, 256, False, 11), ("bf16", 128, 96, True, 18)])
 def test_frozen_target_network(B, dtype, H, batch, layered, kernels):
-    """Q(s', .) from a frozen copy of the weights, synced every 7th update (Deep Q-Network Model);
-    the fp32 case runs layer by layer, the bf16 cases on the MFMA step with the S' rows in the
-    same launches (batch 256) or in launches of their own (batch 200)."""
+    """Q(s', .) from a frozen copy of the weights, synced every 7th update (Deep Q-Network Model):
+    the small fp32 step with a target pass of its row kernel first, the layered step, and the
+    MFMA step with the S' rows in the same launches (batch 256) or in launches of their own
+    (batch 200)."""
     rows = synth.experiences(400, 27, 30, 0.05, seed=23, state_dtype=dtype)
     pr = Pair(B, capacity=256, D=27, H=H, A=30, batch=batch, burn_in=100, seed=3, dtype=dtype,
               appends=2, layered=layered, target_sync=7, lr=1e-3)
@@ -432,7 +433,8 @@ def test_train_step_with_batches_without_duplicates(B, dtype, H, layered):
 
 
 @pytest.mark.parametrize("dtype,H,batch,layered,target_sync,kernels", [
-    ("f32", 64, 50, False, 0, 3), ("f32", 64, 50, True, 0, 16), ("f32", 128, 33, False, 5, 19),
+    ("f32", 64, 50, False, 0, 3), ("f32", 64, 50, True, 0, 16), ("f32", 128, 33, False, 5, 4),
+    ("f32", 128, 33, True, 5, 19),
     ("bf16", 128, 200, False, 0, 12), ("bf16", 64, 256, False, 5, 12), ("bf16", 128, 96, True, 0, 16)])
 def test_dueling_head(B, dtype, H, batch, layered, target_sync, kernels):
     """Q = V + A - mean A with a value stream and an advantage stream (Deep Q-Network Model), on
