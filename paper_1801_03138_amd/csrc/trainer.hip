@@ -397,7 +397,7 @@ void unpad_params(const trainer* t, const std::vector<float>& pad, float* ext) {
 }
 
 // ----------------------------------------------------------------------------- dueling head
-// One thread per hidden unit k (k = H: the biases).  g holds the gradient of the equivalent
+// One wavefront per hidden unit k (k = H: the biases).  g holds the gradient of the equivalent
 // plain output layer, dW[k][a]; the head's own gradients follow from the combine
 // Q = V + A - mean A:  dV[k] = sum_a dW[k][a],  dA[k][a] = dW[k][a] - mean_a' dW[k][a'],
 // restricted to the weights the head has.  After the optimizer step the equivalent layer is
@@ -413,9 +413,12 @@ struct HeadArgs {
     bf16_t *wb, *wbt;              // layered mixed precision: padded bf16 copies
 };
 
-__global__ __launch_bounds__(kThreads) void dueling_head_kernel(HeadArgs p) {
-    const unsigned int k = blockIdx.x * kThreads + threadIdx.x;
-    if (k > p.H) return;
+__global__ __launch_bounds__(64) void dueling_head_kernel(HeadArgs p) {
+    // one single-wavefront workgroup per hidden unit k, one lane per output (striding when there
+    // are more than 64); the new head weights of the row pass through LDS
+    extern __shared__ float head_row[];   // [1 + A]
+    const unsigned int lane = threadIdx.x;
+    const unsigned int k = blockIdx.x;
     const unsigned int A = p.A, O = A + 1;
     const size_t eff = k < p.H ? p.oW3 + (size_t)k * p.Ap : p.ob3;   // row k of the plain layer
     const size_t head = p.n_padded + (size_t)k * O;
@@ -423,11 +426,12 @@ __global__ __launch_bounds__(kThreads) void dueling_head_kernel(HeadArgs p) {
     const float c1 = p.ctr->c1, c2 = p.ctr->c2;
     const bool sync = p.wt && p.sync_every && p.ctr->adam_t % p.sync_every == 0;
 
-    float gsum = 0.f;
-    for (unsigned int a = 0; a < A; ++a) gsum += p.g[eff + a];
+    float part = 0.f;
+    for (unsigned int a = lane; a < A; a += 64) part += p.g[eff + a];
+    const float gsum = wave_sum(part);
     const float gmean = gsum / (float)A;
-    float vnew = 0.f, asum = 0.f;
-    for (unsigned int o = 0; o < O; ++o) {
+    float vpart = 0.f, apart = 0.f;
+    for (unsigned int o = lane; o < O; o += 64) {
         const bool on = o == 0 ? v_on : a_on;
         const float gk = !on ? 0.f : o == 0 ? gsum : p.g[eff + o - 1] - gmean;
         float wk = p.w[head + o];
@@ -443,13 +447,17 @@ __global__ __launch_bounds__(kThreads) void dueling_head_kernel(HeadArgs p) {
                 wk -= p.lr * (mk / c1) / (sqrtf(vk / c2) + p.eps);
             }
             p.w[head + o] = wk;
-            if (o == 0) vnew = wk; else asum += wk;
+            if (o == 0) vpart = wk; else apart += wk;
         }
+        head_row[o] = on ? wk : 0.f;
         if (sync) p.wt[head + o] = wk;
     }
-    const float amean = asum / (float)A;
-    for (unsigned int a = 0; a < A; ++a) {
-        const float e = vnew + (a_on ? p.w[head + 1 + a] : 0.f) - amean;
+    // the new value weight sits in lane 0, the advantage weights are spread over the lanes
+    const float vnew = wave_sum(vpart);
+    const float amean = wave_sum(apart) / (float)A;
+    // (LDS operations of a wavefront complete in order: the row is there)
+    for (unsigned int a = lane; a < A; a += 64) {
+        const float e = vnew + head_row[1 + a] - amean;
         p.w[eff + a] = e;
         if (p.wb) p.wb[eff + a] = from_float<bf16_t>(e);
         if (p.W3T && k < p.H) p.W3T[(size_t)a * p.H + k] = bf16_bits_rne(e);
@@ -700,8 +708,8 @@ hipError_t enqueue_head_update(trainer* t, hipStream_t st, unsigned int* count) 
     a.W3T_t = t->wide && t->wt ? t->wd.W3T_t : nullptr;
     a.wb = t->wide ? nullptr : t->wb;
     a.wbt = t->wide ? nullptr : t->wbt;
-    hipLaunchKernelGGL(dueling_head_kernel, dim3((t->H + 1 + kThreads - 1) / kThreads), dim3(kThreads),
-                       0, st, a);
+    hipLaunchKernelGGL(dueling_head_kernel, dim3(t->H + 1), dim3(64),
+                       (t->cfg.num_actions + 1) * sizeof(float), st, a);
     if (count) *count = 1;
     return hipGetLastError();
 }
