@@ -32,7 +32,7 @@ P_CFG = dict(capacity=1_000_000, D=27, A=30, B=128, H=256, burn_in=50_000, p_ter
 W_CFG = dict(capacity=4_000_000, D=27, A=30, B=4096, H=1024, p_term=0.005, lr=1e-4, appends=64)
 L_CFG = dict(capacity=200_000, D=84 * 84 * 4, p_term=0.001)
 GATHER_BATCHES = [32, 128, 512, 2048, 8192, 65536]
-# HBM bytes per launch of sample_gather_pair_kernel<4, 1> at batch 65,536 from rocprofv3 PMC runs
+# HBM bytes per launch of sample_gather_pair_kernel<4, 1, false> at batch 65,536 from rocprofv3 PMC runs
 # (FETCH_SIZE 8,182.8 KiB x 2.000 + WRITE_SIZE 14,720.0 KiB x 1.000, the factors being what the
 # same counters read for the 256 MiB plain copy of the copy_calibration leg); the runs and the
 # table are in profiles/gather_kernels_hbm_traffic_pmc.txt.  Set to None when that kernel changes.
@@ -395,7 +395,7 @@ def main():
         for g in out["gather_sweep"]:
             log("[bench]   B=%-6d %8.2f us  %8.1f GB/s" % (g["batch"], g["us_per_call"], g["GBps"]))
         g = out["gather_sweep"][-1]
-        roofline = {"kernel": "sample_gather_pair_kernel<4>", "workload": "gather sweep, batch %d, "
+        roofline = {"kernel": "sample_gather_pair_kernel<4, 1, false>", "workload": "gather sweep, batch %d, "
                     "capacity 1,000,000, 27 fp32 per state" % g["batch"], "bound": "hbm",
                     "achieved": g["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": g["GBps"] / HBM_PEAK_GBS, "traffic": GATHER_65536_HBM_BYTES,

@@ -257,7 +257,7 @@ __device__ __forceinline__ float unit_from_u8(unsigned int b) {
 // flight at once; the rows go to LDS and then leave as contiguous, coalesced runs per output
 // tensor.
 // ---------------------------------------------------------------------------------------
-template <int ELEM, int U>
+template <int ELEM, int U, bool DISTINCT>
 __global__ __launch_bounds__(kThreads) void sample_gather_pair_kernel(
     RingGeom g, unsigned long long seed, unsigned long long step_value,
     const unsigned long long* __restrict__ step_ptr, unsigned int size_value, unsigned int batch,
@@ -267,7 +267,7 @@ __global__ __launch_bounds__(kThreads) void sample_gather_pair_kernel(
     void* __restrict__ out_s_t, unsigned int out_t_ld) {
     extern __shared__ uint4 smem[];
     unsigned int* idx_s = reinterpret_cast<unsigned int*>(smem);   // distinct mode: R slot numbers
-    unsigned char* rows_s = reinterpret_cast<unsigned char*>(smem) + 4 * U * kThreads;
+    unsigned char* rows_s = reinterpret_cast<unsigned char*>(smem) + (DISTINCT ? 4 * U * kThreads : 0);
 
     // callers that mirror the ring state pass the size by value: no dependent load up front
     const unsigned long long step = step_ptr ? *step_ptr : step_value;
@@ -284,7 +284,7 @@ __global__ __launch_bounds__(kThreads) void sample_gather_pair_kernel(
         const unsigned int rsub = threadIdx.x >> lane_shift;
         // A draw without duplicates takes some sixty Philox blocks: one lane per row makes
         // it and the others pick it up from LDS.
-        if (g.sampling) {
+        if (DISTINCT) {
             for (unsigned int rr = threadIdx.x; rr < nrows; rr += kThreads)
                 idx_s[rr] = distinct_draw(seed, step, i0 + rr, size);
             __syncthreads();
@@ -294,7 +294,7 @@ __global__ __launch_bounds__(kThreads) void sample_gather_pair_kernel(
         for (int u = 0; u < U; ++u) {
             unsigned int rr = rsub + u * rows_per_pass;
             rr = rr < nrows ? rr : 0u;   // a row past the end re-reads row 0; not stored
-            const unsigned int p = g.sampling ? idx_s[rr] : uniform_draw(seed, step, i0 + rr, size);
+            const unsigned int p = DISTINCT ? idx_s[rr] : uniform_draw(seed, step, i0 + rr, size);
             src[u] = g.rows + (unsigned long long)p * g.row_bytes;
             if (out_idx && part0 == 0 && rsub + u * rows_per_pass < nrows) out_idx[i0 + rr] = p;
         }
@@ -532,17 +532,21 @@ hipError_t launch_sample_gather(const RingGeom& g, unsigned long long seed,
         const unsigned int U = 1;
         const unsigned int R = U * rows_per_pass;
         const unsigned int blocks = (batch + R - 1) / R;
-        const size_t lds = 4 * (size_t)U * kThreads + (size_t)R * g.row_bytes;
-#define RP_LAUNCH_PAIR(E, UU)                                                                       \
-    hipLaunchKernelGGL((sample_gather_pair_kernel<E, UU>), dim3(blocks), dim3(kThreads), lds, stream, \
-                       g, seed, step_value, step_ptr, size_value, batch, lane_shift, out_s,          \
+        const bool distinct = g.sampling == RP_DISTINCT;
+        const size_t lds = (distinct ? 4 * (size_t)U * kThreads : 0) + (size_t)R * g.row_bytes;
+#define RP_LAUNCH_PAIR(E, UU, DD)                                                                  \
+    hipLaunchKernelGGL((sample_gather_pair_kernel<E, UU, DD>), dim3(blocks), dim3(kThreads), lds,   \
+                       stream, g, seed, step_value, step_ptr, size_value, batch, lane_shift, out_s, \
                        out_s_next, out_ld, out_a, out_r, out_term, out_idx, out_s_t, out_t_ld)
+#define RP_LAUNCH_PAIR_E(E) \
+    do { if (distinct) RP_LAUNCH_PAIR(E, 1, true); else RP_LAUNCH_PAIR(E, 1, false); } while (0)
         if (g.elem_bytes == 4)
-            RP_LAUNCH_PAIR(4, 1);
+            RP_LAUNCH_PAIR_E(4);
         else if (g.elem_bytes == 2)
-            RP_LAUNCH_PAIR(2, 1);
+            RP_LAUNCH_PAIR_E(2);
         else
-            RP_LAUNCH_PAIR(1, 1);
+            RP_LAUNCH_PAIR_E(1);
+#undef RP_LAUNCH_PAIR_E
 #undef RP_LAUNCH_PAIR
     } else {
         const unsigned int vectors = (g.state_bytes + 15u) >> 4;
