@@ -259,7 +259,7 @@ struct WsLayout {
     size_t ctr, w, g, m, v, wt, w2t, wb, wbt, X, act, rew, term, idx, H1, H2, Q, y, delta, lossi, dQ, dZ2, dZ1,
         total;
     // mixed-precision step on MFMA
-    size_t W1T, W2b, W2T, W3T, W1Tt, W2Tt, W3Tt, XT, H1T, H2T, dQTh, dQTl, dZ2T, dZ1T, part3, part1;
+    size_t W1T, W2b, W2T, W3T, W1Tt, W2Tt, W3Tt, XT, H1T, H2T, dQTh, dQTl, dZ2T, dZ1T, part3, part1, part2;
     unsigned int Dp, Ap, Bp;
     size_t n_params, n_padded, n_head, elem;
     size_t oW1, ob1, oW2, ob2, oW3, ob3;
@@ -336,6 +336,7 @@ bool ws_layout(const train_config* c, WsLayout* L) {
     // K-split partial products of the narrow layers' gradients (at most 16 splits)
     L->part3 = take(mixed ? 16 * (H + 1) * 2 * L->Ap * 4 : 0);
     L->part1 = take(mixed ? 16 * H * Dx * 4 : 0);
+    L->part2 = take(mixed ? (size_t)square_splits((unsigned int)Bp, (unsigned int)H) * (H + 1) * H * 4 : 0);
     L->total = o;
     return true;
 }
@@ -783,7 +784,8 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
                                 at(L.W3Tt), at(L.XT), at(L.H1T),
                                 at(L.H2T), at(L.dQTh), at(L.dQTl), at(L.dZ2T), at(L.dZ1T),
                                 reinterpret_cast<float*>(ws + L.part3),
-                                reinterpret_cast<float*>(ws + L.part1)};
+                                reinterpret_cast<float*>(ws + L.part1),
+                                reinterpret_cast<float*>(ws + L.part2)};
     }
     t->wb = cfg->param_dtype == RP_BF16 ? reinterpret_cast<bf16_t*>(ws + L.wb) : nullptr;
     t->X = ws + L.X;

@@ -96,6 +96,7 @@ struct WideBuffers {
     unsigned short *dZ2T, *dZ1T;             // [H x Bp]
     float* part3;                            // K-split partials [splits][H+1][2 Ap] of [dW3 ; db3]
     float* part1;                            // K-split partials [splits][H][Dx] of [dW1^T | db1]
+    float* part2;                            // K-split partials [splits][H+1][H] of [dW2 ; db2]
 };
 
 constexpr unsigned int kGraphSteps = 8;       // train steps per launch of the multi-step graph
@@ -185,6 +186,7 @@ void* fused_rows_func();
 hipError_t enqueue_head_update(trainer* t, hipStream_t st, unsigned int* count);
 // Mixed-precision step on MFMA (bf16 replay states and matrix operands).
 bool wide_step_supported(const train_config& cfg, const replay* rp_);
+unsigned int square_splits(unsigned int Bp, unsigned int H);   // K splits of the dW2 product
 hipError_t wide_init_buffers(trainer* t);                       // once, after the workspace is cleared
 // bf16 operand copies from padded fp32 parameters (host): of the trained network, or of the target
 hipError_t wide_set_weights(trainer* t, const float* padded, bool target);

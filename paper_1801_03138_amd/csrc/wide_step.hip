@@ -8,7 +8,9 @@
 // the pre-activation gradients; the kernels that produce those tensors write both orientations.
 // A bias gradient is the product of the error with a vector of ones: the transposed activation
 // buffers carry one extra row of ones, so the bias gradient falls out of the weight-gradient
-// product as one more output row, and the optimizer runs in the epilogue of that product.
+// product as one more output row.  The weight-gradient products contract over the batch, which
+// is long while their outputs are small: they are split along the batch over several workgroups
+// per tile, and the optimizer kernels add the fp32 partial products up.
 //
 // Paper: Integration with Reinforcement Learning Algorithm (train step with no host inputs),
 // Deep Q-Network Model (update equation).
@@ -22,6 +24,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned short bf16_bits;
 // 16 bytes in flight between a load and its use.  A native vector type: arrays of HIP's uint4
 // struct are not promoted to registers by the compiler and end up in scratch memory.
@@ -136,37 +139,6 @@ struct EpiMask {
             o[e] = (lo_on ? v[e] & 0xFFFFu : 0u) | (hi_on ? v[e] & 0xFFFF0000u : 0u);
         }
         *reinterpret_cast<u32x4*>(out + at) = o;
-    }
-};
-
-// acc is the gradient of W[m][n] (rows below R) or of bias[n] (row R): optimizer step, then the
-// bf16 copies of the new weight in both orientations.
-struct EpiOptSquare {
-    static constexpr bool kStaged = false;
-    OptState o;
-    unsigned int R, N;          // weight matrix [R x N], row-major at w_off; bias [N] at b_off
-    size_t w_off, b_off;
-    bf16_bits* wb;              // [R x N]
-    bf16_bits* wbT;             // [N x R]
-    bf16_bits* wbT_target;      // [N x R] of the target network, or null
-    __device__ __forceinline__ void tile(unsigned int mb, unsigned int nb, const f32x16& c,
-                                         unsigned int lane, unsigned int) const {
-        const unsigned int n = nb + (lane & 31u);
-        if (n >= N) return;
-        const OptStep st = opt_step(o);
-#pragma unroll
-        for (unsigned int v = 0; v < 16; ++v) {
-            const unsigned int m = mb + acc_row(v, lane);
-            if (m < R) {
-                const float wk = opt_update(o, w_off + (size_t)m * N + n, c[v], st);
-                const bf16_bits h = bf16_bits_rne(wk);
-                wb[(size_t)m * N + n] = h;
-                wbT[(size_t)n * R + m] = h;
-                if (st.sync) wbT_target[(size_t)n * R + m] = h;
-            } else if (m == R) {
-                opt_update(o, b_off + n, c[v], st);
-            }
-        }
     }
 };
 
@@ -716,6 +688,93 @@ __global__ __launch_bounds__(256) void small_opt_kernel(SmallOptArgs p) {
     }
 }
 
+// The square layer's update from the K-split partial products of [dW ; db] (row R = bias):
+//   part[z][m][n], m <= R, n < N; the gradient is the sum over z, splits added in order.
+// A workgroup owns a 64 x 64 tile of W: a thread takes four consecutive columns of a row
+// (16-byte accesses to the partials and to the fp32 weight, gradient and moments), writes the
+// new weights' bf16 copy in the same orientation and parks it in LDS, from where the
+// transposed copy (and the target network's, when a sync is due) leaves as 128-byte runs.
+// R and N are multiples of 64.
+struct SquareOptArgs {
+    OptState o;
+    unsigned int R, N, splits;
+    const float* part;
+    size_t w_off, b_off;
+    bf16_bits* wb;              // [R x N]
+    bf16_bits* wbT;             // [N x R]
+    bf16_bits* wbT_target;      // [N x R] of the target network, or null
+};
+
+__device__ __forceinline__ f32x4 opt_update4(const OptState& o, size_t k, const f32x4& g, const OptStep& st) {
+    f32x4 w = *reinterpret_cast<const f32x4*>(o.w + k);
+    *reinterpret_cast<f32x4*>(o.g + k) = g;
+    if (o.opt == RP_SGD) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] -= o.lr * g[e];
+    } else {
+        f32x4 m = *reinterpret_cast<const f32x4*>(o.m + k);
+        f32x4 v = *reinterpret_cast<const f32x4*>(o.v + k);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            m[e] = o.beta1 * m[e] + (1.f - o.beta1) * g[e];
+            v[e] = o.beta2 * v[e] + (1.f - o.beta2) * g[e] * g[e];
+            w[e] -= o.lr * (m[e] / st.c1) / (sqrtf(v[e] / st.c2) + o.eps);
+        }
+        *reinterpret_cast<f32x4*>(o.m + k) = m;
+        *reinterpret_cast<f32x4*>(o.v + k) = v;
+    }
+    *reinterpret_cast<f32x4*>(o.w + k) = w;
+    if (st.sync) *reinterpret_cast<f32x4*>(o.wt + k) = w;
+    return w;
+}
+
+__global__ __launch_bounds__(256) void square_opt_kernel(SquareOptArgs p) {
+    constexpr unsigned int TS = 68;                       // bf16 per parked row (64 + padding)
+    __shared__ bf16_bits tile[64 * TS];
+    const unsigned int tid = threadIdx.x, c4 = (tid & 15u) * 4u, r0 = tid >> 4;
+    const unsigned int m0 = blockIdx.y * 64u, n0 = blockIdx.x * 64u;
+    const OptStep st = opt_step(p.o);
+    const size_t zs = (size_t)(p.R + 1u) * p.N;           // one split's partials
+    f32x4 g[4];
+#pragma unroll
+    for (unsigned int q = 0; q < 4; ++q) {
+        const float* src = p.part + (size_t)(m0 + q * 16u + r0) * p.N + n0 + c4;
+        g[q] = *reinterpret_cast<const f32x4*>(src);
+        for (unsigned int z = 1; z < p.splits; ++z) g[q] += *reinterpret_cast<const f32x4*>(src + z * zs);
+    }
+#pragma unroll
+    for (unsigned int q = 0; q < 4; ++q) {
+        const unsigned int r = q * 16u + r0;
+        const size_t at = (size_t)(m0 + r) * p.N + n0 + c4;
+        const f32x4 w = opt_update4(p.o, p.w_off + at, g[q], st);
+        bf16_bits h[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) h[e] = bf16_bits_rne(w[e]);
+        uint2 pk;
+        pk.x = (unsigned int)h[0] | ((unsigned int)h[1] << 16);
+        pk.y = (unsigned int)h[2] | ((unsigned int)h[3] << 16);
+        *reinterpret_cast<uint2*>(p.wb + at) = pk;
+        *reinterpret_cast<uint2*>(tile + r * TS + c4) = pk;
+    }
+    if (blockIdx.y == 0 && tid < 16) {                     // the bias: row R of the partials
+        const float* src = p.part + (size_t)p.R * p.N + n0 + c4;
+        f32x4 gb = *reinterpret_cast<const f32x4*>(src);
+        for (unsigned int z = 1; z < p.splits; ++z) gb += *reinterpret_cast<const f32x4*>(src + z * zs);
+        opt_update4(p.o, p.b_off + n0 + c4, gb, st);
+    }
+    __syncthreads();
+    // transposed copy: a wavefront writes two rows of 64 (one column of the tile each) per pass
+    const unsigned int mp = (tid & 31u) * 2u;
+#pragma unroll
+    for (unsigned int pass = 0; pass < 8; ++pass) {
+        const unsigned int n = pass * 8u + (tid >> 5);
+        const unsigned int pair = (unsigned int)tile[mp * TS + n] | ((unsigned int)tile[(mp + 1u) * TS + n] << 16);
+        const size_t at = (size_t)(n0 + n) * p.R + m0 + mp;
+        *reinterpret_cast<unsigned int*>(p.wbT + at) = pair;
+        if (st.sync) *reinterpret_cast<unsigned int*>(p.wbT_target + at) = pair;
+    }
+}
+
 // K splits of the narrow layers' gradient products (contraction over the padded batch): as
 // many as leave every workgroup at least 256 columns, in whole 64-wide slices, at most 16.
 unsigned int batch_splits(unsigned int Bp) {
@@ -723,6 +782,15 @@ unsigned int batch_splits(unsigned int Bp) {
     for (unsigned int s = 2; s <= 16; ++s)
         if (Bp % (s * 64u) == 0 && Bp / s >= 256u) best = s;
     return best;
+}
+
+// K splits of the square layer's gradient product: doubled while its 128 x 128 tiles number
+// fewer than the compute units, every split keeps at least 256 columns in whole 64-wide slices.
+unsigned int square_splits_for(unsigned int Bp, unsigned int H) {
+    const unsigned int tiles = ((H + 1u + 127u) / 128u) * ((H + 127u) / 128u);
+    unsigned int s = 1;
+    while (tiles * s < 256u && s < 8u && Bp % (2u * s * 64u) == 0 && Bp / (2u * s) >= 256u) s *= 2u;
+    return s;
 }
 
 bf16_bits host_bf16(float f) {
@@ -735,6 +803,8 @@ bf16_bits host_bf16(float f) {
 
 }  // namespace
 
+unsigned int square_splits(unsigned int Bp, unsigned int H) { return square_splits_for(Bp, H); }
+
 bool wide_step_supported(const train_config& cfg, const replay* rp_) {
     return cfg.param_dtype == RP_BF16 && rp_->cfg.state_dtype == RP_BF16 &&
            rp_->cfg.layout == RP_PAIR && cfg.hidden % 64 == 0;
@@ -746,7 +816,6 @@ hipError_t wide_init_buffers(trainer* t) {
     hipError_t ec = configure_gemm<128, 128, 32, 2, 2, 1, EpiForward>();
     if (ec == hipSuccess) ec = configure_gemm<128, 128, 64, 2, 2, 1, EpiForward>();
     if (ec == hipSuccess) ec = configure_gemm<128, 64, 64, 2, 2, 1, EpiMask>();
-    if (ec == hipSuccess) ec = configure_gemm<64, 64, 128, 1, 1, 4, EpiOptSquare>();
     if (ec == hipSuccess) ec = configure_gemm<128, 64, 64, 4, 1, 1, EpiPartial>();
     if (ec == hipSuccess) ec = configure_gemm<128, 32, 64, 4, 1, 1, EpiPartial>();
     if (ec == hipSuccess) ec = configure_gemm<128, 128, 64, 2, 2, 1, EpiPartial>();
@@ -885,11 +954,21 @@ hipError_t enqueue_wide_step(trainer* t, hipStream_t st, unsigned int* count, bo
                                           EpiMask{w.H1T, w.dZ1T, Bp, H, B});
     if (e != hipSuccess) return e;
     ++n;
-    // second hidden layer: W2 and b2
-    e = launch_gemm<64, 64, 128, 1, 1, 4>(st, w.H1T, Bp, w.dZ2T, Bp, H + 1, H, Bp,
-                                          EpiOptSquare{o, H, H, t->oW2, t->ob2, w.W2, w.W2T, w.W2T_t});
+    // second hidden layer: partial products of [dW2 ; db2] (row H), then the update of W2 and b2
+    const unsigned int splits2 = square_splits_for(Bp, H);
+    e = launch_gemm<128, 128, 64, 2, 2, 1>(st, w.H1T, Bp, w.dZ2T, Bp, H + 1, H, Bp,
+                                           EpiPartial{w.part2, H + 1, H}, splits2);
     if (e != hipSuccess) return e;
     ++n;
+    {
+        SquareOptArgs a;
+        a.o = o; a.R = H; a.N = H; a.splits = splits2; a.part = w.part2;
+        a.w_off = t->oW2; a.b_off = t->ob2; a.wb = w.W2; a.wbT = w.W2T; a.wbT_target = w.W2T_t;
+        hipLaunchKernelGGL(square_opt_kernel, dim3(H / 64, H / 64), dim3(256), 0, st, a);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        ++n;
+    }
     // first hidden layer: partial products of [dW1^T | db1] (column D)
     e = Dx == 32 ? launch_gemm<128, 32, 64, 4, 1, 1>(st, w.dZ1T, Bp, w.XT, Bp, H, Dx, Bp,
                                                      EpiPartial{w.part1, H, Dx}, splits)
