@@ -160,12 +160,14 @@ struct EpiPartial {
 };
 
 // ----------------------------------------------------------------------------------------
-// Tiled product C = A Bt^T: a workgroup of four wavefronts owns a BM x BN tile, streams BK-wide
-// slices of both operands through LDS (two stages; the next slice is fetched into registers
-// while the current one is multiplied) and keeps the accumulators in registers.  The
-// wavefronts split the tile WGM x WGN ways and the slice WGK ways; with WGK > 1 the partial
-// accumulators are added through LDS before the epilogue.  LDS rows are padded by 16 bytes,
-// which spreads the 16-byte operand reads of 8 consecutive rows over all banks.
+// Tiled product C = A Bt^T: a workgroup of four wavefronts owns a BM x BN tile and keeps the
+// accumulators in registers; the wavefronts split the tile WGM x WGN ways.  BK-wide slices of
+// both operands go from global memory straight into LDS (global_load_lds, 16 bytes per lane, no
+// trip through registers), two slices deep: the next slice is in flight while the current one
+// is multiplied.  Such a load writes the wavefront's 64 pieces to consecutive LDS addresses,
+// so LDS rows cannot be padded; instead the 16-byte piece at position c of row r holds piece
+// c ^ swz(r) of that row's slice (the lanes fetch their global pieces in that order), which
+// spreads the MFMA operand reads of 8 consecutive rows over all banks.
 // The contraction may also be split over `splits` workgroups per tile, each taking K / splits
 // consecutive columns and handing its split number to the epilogue.
 // K / splits must be a multiple of BK.  Loads of rows beyond M / N are redirected to the last valid row:
@@ -182,26 +184,29 @@ struct GemmArgs {
     unsigned int tiles_m, tiles_n, splits;
 };
 
-template <int BM, int BN, int BK, int WGK>
+template <int BM, int BN, int BK, int WGM, int WGN>
 constexpr size_t gemm_lds_bytes() {
-    const size_t stage = (size_t)(BM + BN) * (BK * 2 + 16);
-    const size_t red = WGK > 1 ? 4 * 4 * 16 * 64 * sizeof(float) : 0;  // 4 waves x 4 tiles
-    return 2 * stage > red ? 2 * stage : red;
+    const size_t slices = 2 * (size_t)(BM + BN) * BK * 2;
+    // staged epilogues park every wavefront's bf16 tile, rows padded by 16 bytes
+    const size_t parked = 4 * (size_t)(BM / WGM) * ((BN / WGN) * 2 + 16);
+    return slices > parked ? slices : parked;
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, int WGK, class Epi>
+#define RP_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+#define RP_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+
+template <int BM, int BN, int BK, int WGM, int WGN, class Epi>
 __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(GemmArgs p, Epi epi) {
-    static_assert(WGM * WGN * WGK == 4, "four wavefronts");
-    constexpr int STRIDE = BK * 2 + 16;                    // bytes per LDS row
-    constexpr int A_BYTES = BM * STRIDE, STAGE = (BM + BN) * STRIDE;
-    constexpr int CPR = BK / 8;                            // 16-byte pieces per row of a slice
-    constexpr int RPP = kGemmThreads / CPR;                // rows one pass of the workgroup covers
-    constexpr int PA = BM / RPP, PB = BN / RPP;
-    static_assert(PA >= 1 && PB >= 1 && BM % RPP == 0 && BN % RPP == 0, "loader shape");
+    static_assert(WGM * WGN == 4, "four wavefronts");
+    static_assert(BK == 32 || BK == 64, "slice width");
+    constexpr int RB = BK * 2;                             // bytes per LDS row
+    constexpr int CPR = RB / 16;                           // 16-byte pieces per row
+    constexpr int RPI = 64 / CPR;                          // rows one wavefront-wide load covers
+    constexpr int A_BYTES = BM * RB, STAGE = (BM + BN) * RB;
+    constexpr int GA = BM / RPI / 4, GB = BN / RPI / 4;    // loads per wavefront, slice and operand
+    static_assert(GA >= 1 && GB >= 1 && BM % (4 * RPI) == 0 && BN % (4 * RPI) == 0, "loader shape");
     constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;  // 32x32 tiles per wavefront
-    constexpr int KSW = BK / 16 / WGK;                     // 16-deep MFMA steps per wavefront and slice
-    static_assert(TM >= 1 && TN >= 1 && KSW >= 1, "wavefront shape");
-    static_assert(WGK == 1 || (WGM == 1 && WGN == 1 && TM * TN == 4), "K split reduces 4 tiles");
+    static_assert(TM >= 1 && TN >= 1, "wavefront shape");
 
     extern __shared__ uint4 gemm_smem[];
     unsigned char* smem = reinterpret_cast<unsigned char*>(gemm_smem);
@@ -217,24 +222,39 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(GemmArgs p, Epi e
     const unsigned int k_base = split * p.K;
 
     const unsigned int tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
-    const unsigned int wk = wave % WGK, wn = (wave / WGK) % WGN, wm = wave / (WGK * WGN);
-    const unsigned int lrow = tid / CPR, lpiece = tid % CPR;
+    const unsigned int wn = wave % WGN, wm = wave / WGN;
+    // position of the piece of row r that shares a bank group with piece 0 of row 0
+    auto swz = [](unsigned int r) { return CPR == 8 ? (r & 7u) : ((r >> 1) & 3u); };
 
-    const bf16_bits* a_ptr[PA];
-    const bf16_bits* b_ptr[PB];
+    // loader: wavefront w moves row groups w*GA.. of A and w*GB.. of B; a lane's piece lands at
+    // LDS position `lane` of the group, so the lane fetches the piece that belongs there
+    const unsigned int lr = lane / CPR, lc = lane % CPR;
+    const bf16_bits* a_ptr[GA];
+    const bf16_bits* b_ptr[GB];
 #pragma unroll
-    for (int u = 0; u < PA; ++u) {
-        unsigned int gm = m0 + lrow + u * RPP;
+    for (int u = 0; u < GA; ++u) {
+        const unsigned int r = (wave * GA + u) * RPI + lr;
+        unsigned int gm = m0 + r;
         gm = gm < p.M ? gm : p.M - 1;
-        a_ptr[u] = p.A + (size_t)gm * p.lda + k_base + lpiece * 8u;
+        a_ptr[u] = p.A + (size_t)gm * p.lda + k_base + (lc ^ swz(r)) * 8u;
     }
 #pragma unroll
-    for (int u = 0; u < PB; ++u) {
-        unsigned int gn = n0 + lrow + u * RPP;
+    for (int u = 0; u < GB; ++u) {
+        const unsigned int r = (wave * GB + u) * RPI + lr;
+        unsigned int gn = n0 + r;
         gn = gn < p.N ? gn : p.N - 1;
-        b_ptr[u] = (m0 >= p.m_split ? p.Bt_hi : p.Bt) + (size_t)gn * p.ldb + k_base + lpiece * 8u;
+        b_ptr[u] = (m0 >= p.m_split ? p.Bt_hi : p.Bt) + (size_t)gn * p.ldb + k_base + (lc ^ swz(r)) * 8u;
     }
-    u32x4 ra[PA], rb[PB];
+    auto fetch = [&](unsigned int buf, unsigned int k0) {
+        unsigned char* sa = smem + buf * STAGE + (wave * GA) * 1024u;
+        unsigned char* sb = smem + buf * STAGE + A_BYTES + (wave * GB) * 1024u;
+#pragma unroll
+        for (int u = 0; u < GA; ++u)
+            __builtin_amdgcn_global_load_lds(RP_GLOBAL_PTR(a_ptr[u] + k0), RP_LDS_PTR(sa + u * 1024), 16, 0, 0);
+#pragma unroll
+        for (int u = 0; u < GB; ++u)
+            __builtin_amdgcn_global_load_lds(RP_GLOBAL_PTR(b_ptr[u] + k0), RP_LDS_PTR(sb + u * 1024), 16, 0, 0);
+    };
 
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -244,21 +264,22 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(GemmArgs p, Epi e
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    const unsigned int a_row = (wm * TM * 32u + (lane & 31u)) * STRIDE + (lane >> 5) * 16u;
-    const unsigned int b_row = (wn * TN * 32u + (lane & 31u)) * STRIDE + (lane >> 5) * 16u;
+    const unsigned int a_row = (wm * TM * 32u + (lane & 31u)) * RB;
+    const unsigned int b_row = (wn * TN * 32u + (lane & 31u)) * RB;
+    const unsigned int sw = swz(lane & 31u), half = lane >> 5;
     auto multiply = [&](unsigned int buf) {
         const unsigned char* as = smem + buf * STAGE + a_row;
         const unsigned char* bs = smem + buf * STAGE + A_BYTES + b_row;
 #pragma unroll
-        for (int s = 0; s < KSW; ++s) {
-            const unsigned int ko = (wk * KSW + s) * 32u;   // byte offset of this 16-deep step
+        for (int s = 0; s < BK / 16; ++s) {
+            const unsigned int ko = ((2u * s + half) ^ sw) * 16u;   // where this 16-deep step's piece sits
             bf16x8 a[TM], b[TN];
 #pragma unroll
             for (int i = 0; i < TM; ++i)
-                a[i] = as_bf16x8(*reinterpret_cast<const u32x4*>(as + i * 32 * STRIDE + ko));
+                a[i] = as_bf16x8(*reinterpret_cast<const u32x4*>(as + i * 32 * RB + ko));
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                b[j] = as_bf16x8(*reinterpret_cast<const u32x4*>(bs + j * 32 * STRIDE + ko));
+                b[j] = as_bf16x8(*reinterpret_cast<const u32x4*>(bs + j * 32 * RB + ko));
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -269,45 +290,26 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(GemmArgs p, Epi e
         }
     };
 
-    // The loop is written without branches between a slice's loads and its LDS stores, so
-    // that the loads stay in flight across the multiply.
+    // Slice kt is awaited (every wavefront waits for its own loads, the barrier covers the
+    // others'); after the barrier nobody reads the other buffer any more, so slice kt+1 is
+    // requested into it and travels while slice kt is multiplied.
     const unsigned int nk = p.K / BK;
-    unsigned char* const st_a = smem + lrow * STRIDE + lpiece * 16u;
-    unsigned char* const st_b = st_a + A_BYTES;
-#pragma unroll
-    for (int u = 0; u < PA; ++u) ra[u] = *reinterpret_cast<const u32x4*>(a_ptr[u]);
-#pragma unroll
-    for (int u = 0; u < PB; ++u) rb[u] = *reinterpret_cast<const u32x4*>(b_ptr[u]);
-#pragma unroll
-    for (int u = 0; u < PA; ++u) *reinterpret_cast<u32x4*>(st_a + u * RPP * STRIDE) = ra[u];
-#pragma unroll
-    for (int u = 0; u < PB; ++u) *reinterpret_cast<u32x4*>(st_b + u * RPP * STRIDE) = rb[u];
-    __syncthreads();
-    for (unsigned int kt = 0; kt + 1 < nk; ++kt) {
-        const unsigned int k1 = (kt + 1) * BK;
-#pragma unroll
-        for (int u = 0; u < PA; ++u) ra[u] = *reinterpret_cast<const u32x4*>(a_ptr[u] + k1);
-#pragma unroll
-        for (int u = 0; u < PB; ++u) rb[u] = *reinterpret_cast<const u32x4*>(b_ptr[u] + k1);
-        multiply(kt & 1u);
-        const unsigned int nb = ((kt + 1) & 1u) * STAGE;
-#pragma unroll
-        for (int u = 0; u < PA; ++u) *reinterpret_cast<u32x4*>(st_a + nb + u * RPP * STRIDE) = ra[u];
-#pragma unroll
-        for (int u = 0; u < PB; ++u) *reinterpret_cast<u32x4*>(st_b + nb + u * RPP * STRIDE) = rb[u];
+    fetch(0, 0);
+    for (unsigned int kt = 0; kt < nk; ++kt) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's loads have landed in LDS
         __syncthreads();
+        if (kt + 1 < nk) fetch((kt + 1) & 1u, (kt + 1) * BK);
+        multiply(kt & 1u);
     }
-    multiply((nk - 1) & 1u);
 
     if constexpr (Epi::kStaged) {
-        static_assert(WGK == 1, "staged epilogues take whole accumulators");
         // The accumulator of tile (i, j) is transposed: element v of a lane is output row
         // lane % 32, column acc_row(v, lane).  Park the wavefront's (TM*32) x (TN*32) tile as
         // bf16 in its own LDS region (the operand slices are no longer needed).
         constexpr int TSTRIDE = TN * 64 + 16;                // bytes per parked row
         constexpr int CR = TN * 4;                           // 16-byte pieces per row
         constexpr int RP = 64 / CR;                          // rows per pass of the wavefront
-        static_assert(4 * TM * 32 * TSTRIDE <= 2 * STAGE, "parked tiles fit in the slice buffers");
+        static_assert(4 * TM * 32 * TSTRIDE <= (int)gemm_lds_bytes<BM, BN, BK, WGM, WGN>(), "parked tiles fit");
         __syncthreads();
         unsigned char* park = smem + wave * (TM * 32 * TSTRIDE);
         const unsigned int wm0 = m0 + wm * TM * 32u, wn0 = n0 + wn * TN * 32u;
@@ -334,47 +336,26 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(GemmArgs p, Epi e
             const u32x4 v = *reinterpret_cast<const u32x4*>(park + row * TSTRIDE + piece * 16u);
             epi.store(wm0 + row, wn0 + piece * 8u, v);
         }
-    } else if constexpr (WGK == 1) {
+    } else {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
                 epi.tile(m0 + (wm * TM + i) * 32u, n0 + (wn * TN + j) * 32u, acc[i][j], lane, split);
-    } else {
-        // every wavefront holds a partial sum of all four tiles; wavefront w finishes tile w
-        __syncthreads();                                   // the slices in LDS are no longer needed
-        float* red = reinterpret_cast<float*>(smem);       // [wave][tile][v][lane]
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    red[((wave * 4u + (i * TN + j)) * 16u + v) * 64u + lane] = acc[i][j][v];
-        __syncthreads();
-        f32x16 sum;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            float s = 0.f;
-#pragma unroll
-            for (unsigned int src = 0; src < 4; ++src) s += red[((src * 4u + wave) * 16u + v) * 64u + lane];
-            sum[v] = s;
-        }
-        epi.tile(m0 + (wave / TN) * 32u, n0 + (wave % TN) * 32u, sum, lane, split);
     }
 }
 
-// Workgroups of these kernels use more than 64 KB of dynamic LDS, which has to be allowed per
-// kernel before the first launch (done at trainer creation, outside any stream capture).
-template <int BM, int BN, int BK, int WGM, int WGN, int WGK, class Epi>
+// The dynamic LDS size of each kernel (up to 64 KB) is announced per kernel before the first
+// launch (done at trainer creation, outside any stream capture).
+template <int BM, int BN, int BK, int WGM, int WGN, class Epi>
 hipError_t configure_gemm() {
-    auto kernel = gemm_nt_kernel<BM, BN, BK, WGM, WGN, WGK, Epi>;
+    auto kernel = gemm_nt_kernel<BM, BN, BK, WGM, WGN, Epi>;
     return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                hipFuncAttributeMaxDynamicSharedMemorySize,
-                               (int)gemm_lds_bytes<BM, BN, BK, WGK>());
+                               (int)gemm_lds_bytes<BM, BN, BK, WGM, WGN>());
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, int WGK, class Epi>
+template <int BM, int BN, int BK, int WGM, int WGN, class Epi>
 hipError_t launch_gemm(hipStream_t st, const bf16_bits* A, unsigned int lda, const bf16_bits* Bt,
                        unsigned int ldb, unsigned int M, unsigned int N, unsigned int K,
                        const Epi& epi, unsigned int splits = 1, const bf16_bits* Bt_hi = nullptr,
@@ -391,8 +372,8 @@ hipError_t launch_gemm(hipStream_t st, const bf16_bits* A, unsigned int lda, con
     a.splits = splits;
     const unsigned int n_tiles = a.tiles_m * a.tiles_n * splits;
     const unsigned int blocks = 8u * ((n_tiles + 7u) / 8u);
-    constexpr size_t lds = gemm_lds_bytes<BM, BN, BK, WGK>();
-    hipLaunchKernelGGL((gemm_nt_kernel<BM, BN, BK, WGM, WGN, WGK, Epi>), dim3(blocks),
+    constexpr size_t lds = gemm_lds_bytes<BM, BN, BK, WGM, WGN>();
+    hipLaunchKernelGGL((gemm_nt_kernel<BM, BN, BK, WGM, WGN, Epi>), dim3(blocks),
                        dim3(kGemmThreads), lds, st, a, epi);
     return hipGetLastError();
 }
@@ -813,12 +794,12 @@ bool wide_step_supported(const train_config& cfg, const replay* rp_) {
 // Allow the products' LDS sizes and fill the ones rows of the transposed activation buffers
 // (once, at creation).
 hipError_t wide_init_buffers(trainer* t) {
-    hipError_t ec = configure_gemm<128, 128, 32, 2, 2, 1, EpiForward>();
-    if (ec == hipSuccess) ec = configure_gemm<128, 128, 64, 2, 2, 1, EpiForward>();
-    if (ec == hipSuccess) ec = configure_gemm<128, 64, 64, 2, 2, 1, EpiMask>();
-    if (ec == hipSuccess) ec = configure_gemm<128, 64, 64, 4, 1, 1, EpiPartial>();
-    if (ec == hipSuccess) ec = configure_gemm<128, 32, 64, 4, 1, 1, EpiPartial>();
-    if (ec == hipSuccess) ec = configure_gemm<128, 128, 64, 2, 2, 1, EpiPartial>();
+    hipError_t ec = configure_gemm<128, 128, 32, 2, 2, EpiForward>();
+    if (ec == hipSuccess) ec = configure_gemm<128, 128, 64, 2, 2, EpiForward>();
+    if (ec == hipSuccess) ec = configure_gemm<128, 64, 64, 2, 2, EpiMask>();
+    if (ec == hipSuccess) ec = configure_gemm<128, 64, 64, 4, 1, EpiPartial>();
+    if (ec == hipSuccess) ec = configure_gemm<128, 32, 64, 4, 1, EpiPartial>();
+    if (ec == hipSuccess) ec = configure_gemm<128, 128, 64, 2, 2, EpiPartial>();
     if (ec != hipSuccess) return ec;
     std::vector<bf16_bits> ones(t->Bp, (bf16_bits)0x3F80u);
     const size_t bytes = (size_t)t->Bp * sizeof(bf16_bits);
@@ -885,24 +866,24 @@ hipError_t enqueue_wide_step(trainer* t, hipStream_t st, unsigned int* count, bo
         ++n;
     }
     // forward on the 2B rows
-    e = launch_gemm<128, 128, 32, 2, 2, 1>(st, X, Dp, w.W1T, Dp, rows, H, Dp,
+    e = launch_gemm<128, 128, 32, 2, 2>(st, X, Dp, w.W1T, Dp, rows, H, Dp,
                                            EpiForward{t->w + t->ob1, b1t, tgt ? B : ~0u, H1, H, rows, H},
                                            1, tgt && one_launch ? w.W1T_t : nullptr, B);
     if (e != hipSuccess) return e;
     ++n;
     if (!one_launch) {
-        e = launch_gemm<128, 128, 32, 2, 2, 1>(st, X + (size_t)B * Dp, Dp, w.W1T_t, Dp, B, H, Dp,
+        e = launch_gemm<128, 128, 32, 2, 2>(st, X + (size_t)B * Dp, Dp, w.W1T_t, Dp, B, H, Dp,
                                                EpiForward{b1t, b1t, ~0u, H1 + (size_t)B * H, H, B, H});
         if (e != hipSuccess) return e;
         ++n;
     }
-    e = launch_gemm<128, 128, 64, 2, 2, 1>(st, H1, H, w.W2T, H, rows, H, H,
+    e = launch_gemm<128, 128, 64, 2, 2>(st, H1, H, w.W2T, H, rows, H, H,
                                            EpiForward{t->w + t->ob2, b2t, tgt ? B : ~0u, H2, H, rows, H},
                                            1, tgt && one_launch ? w.W2T_t : nullptr, B);
     if (e != hipSuccess) return e;
     ++n;
     if (!one_launch) {
-        e = launch_gemm<128, 128, 64, 2, 2, 1>(st, H1 + (size_t)B * H, H, w.W2T_t, H, B, H, H,
+        e = launch_gemm<128, 128, 64, 2, 2>(st, H1 + (size_t)B * H, H, w.W2T_t, H, B, H, H,
                                                EpiForward{b2t, b2t, ~0u, H2 + (size_t)B * H, H, B, H});
         if (e != hipSuccess) return e;
         ++n;
@@ -943,20 +924,20 @@ hipError_t enqueue_wide_step(trainer* t, hipStream_t st, unsigned int* count, bo
     // output layer: partial products of [dW3 ; db3] (row H), high and low part of dL/dQ side by side
     const unsigned int splits = batch_splits(Bp);
     const unsigned int Dx = (D + 1 + 31) / 32 * 32;
-    e = Ap == 32 ? launch_gemm<128, 64, 64, 4, 1, 1>(st, w.H2T, Bp, w.dQT_hi, Bp, H + 1, 2 * Ap, Bp,
+    e = Ap == 32 ? launch_gemm<128, 64, 64, 4, 1>(st, w.H2T, Bp, w.dQT_hi, Bp, H + 1, 2 * Ap, Bp,
                                                      EpiPartial{w.part3, H + 1, 2 * Ap}, splits)
-                 : launch_gemm<128, 128, 64, 2, 2, 1>(st, w.H2T, Bp, w.dQT_hi, Bp, H + 1, 2 * Ap, Bp,
+                 : launch_gemm<128, 128, 64, 2, 2>(st, w.H2T, Bp, w.dQT_hi, Bp, H + 1, 2 * Ap, Bp,
                                                       EpiPartial{w.part3, H + 1, 2 * Ap}, splits);
     if (e != hipSuccess) return e;
     ++n;
     // dZ1^T = (W2 dZ2^T) masked by the first ReLU; uses W2 before its update
-    e = launch_gemm<128, 64, 64, 2, 2, 1>(st, w.W2, H, dZ2, H, H, B, H,
+    e = launch_gemm<128, 64, 64, 2, 2>(st, w.W2, H, dZ2, H, H, B, H,
                                           EpiMask{w.H1T, w.dZ1T, Bp, H, B});
     if (e != hipSuccess) return e;
     ++n;
     // second hidden layer: partial products of [dW2 ; db2] (row H), then the update of W2 and b2
     const unsigned int splits2 = square_splits_for(Bp, H);
-    e = launch_gemm<128, 128, 64, 2, 2, 1>(st, w.H1T, Bp, w.dZ2T, Bp, H + 1, H, Bp,
+    e = launch_gemm<128, 128, 64, 2, 2>(st, w.H1T, Bp, w.dZ2T, Bp, H + 1, H, Bp,
                                            EpiPartial{w.part2, H + 1, H}, splits2);
     if (e != hipSuccess) return e;
     ++n;
@@ -970,9 +951,9 @@ hipError_t enqueue_wide_step(trainer* t, hipStream_t st, unsigned int* count, bo
         ++n;
     }
     // first hidden layer: partial products of [dW1^T | db1] (column D)
-    e = Dx == 32 ? launch_gemm<128, 32, 64, 4, 1, 1>(st, w.dZ1T, Bp, w.XT, Bp, H, Dx, Bp,
+    e = Dx == 32 ? launch_gemm<128, 32, 64, 4, 1>(st, w.dZ1T, Bp, w.XT, Bp, H, Dx, Bp,
                                                      EpiPartial{w.part1, H, Dx}, splits)
-                 : launch_gemm<128, 128, 64, 2, 2, 1>(st, w.dZ1T, Bp, w.XT, Bp, H, Dx, Bp,
+                 : launch_gemm<128, 128, 64, 2, 2>(st, w.dZ1T, Bp, w.XT, Bp, H, Dx, Bp,
                                                       EpiPartial{w.part1, H, Dx}, splits);
     if (e != hipSuccess) return e;
     ++n;
