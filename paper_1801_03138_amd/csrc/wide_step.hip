@@ -196,7 +196,7 @@ constexpr size_t gemm_lds_bytes() {
 #define RP_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 
 template <int BM, int BN, int BK, int WGM, int WGN, class Epi>
-__global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(GemmArgs p, Epi epi) {
+__device__ __forceinline__ void gemm_nt_block(const GemmArgs& p, const Epi& epi, unsigned int block) {
     static_assert(WGM * WGN == 4, "four wavefronts");
     static_assert(BK == 32 || BK == 64, "slice width");
     constexpr int RB = BK * 2;                             // bytes per LDS row
@@ -215,7 +215,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(GemmArgs p, Epi e
     // tiles (N fastest), so the workgroups that share an L2 also share operand panels.
     const unsigned int per_split = p.tiles_m * p.tiles_n, n_tiles = per_split * p.splits;
     const unsigned int per_xcd = (n_tiles + 7u) / 8u;
-    const unsigned int tile_s = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+    const unsigned int tile_s = (block & 7u) * per_xcd + (block >> 3);
     if (tile_s >= n_tiles) return;
     const unsigned int split = tile_s / per_split, tile = tile_s % per_split;
     const unsigned int m0 = (tile / p.tiles_n) * BM, n0 = (tile % p.tiles_n) * BN;
@@ -345,6 +345,32 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(GemmArgs p, Epi e
     }
 }
 
+template <int BM, int BN, int BK, int WGM, int WGN, class Epi>
+__global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(GemmArgs p, Epi epi) {
+    gemm_nt_block<BM, BN, BK, WGM, WGN>(p, epi, blockIdx.x);
+}
+
+// The three weight-gradient products of a step in one launch (each writes K-split partials):
+// workgroups [0, n2) take the square layer's, [n2, n2 + n3) the output layer's, the rest the
+// first layer's.  n2 and n3 are multiples of 8, which keeps a workgroup's index within its
+// product congruent to its XCD.  NARROW3 / NARROW1: the layer's gradient is at most 64 / 32
+// columns wide and uses the matching narrow tile.
+template <bool NARROW3, bool NARROW1>
+__global__ __launch_bounds__(kGemmThreads) void grad_products_kernel(GemmArgs p2, EpiPartial e2, unsigned int n2,
+                                                                     GemmArgs p3, EpiPartial e3, unsigned int n3,
+                                                                     GemmArgs p1, EpiPartial e1) {
+    const unsigned int b = blockIdx.x;
+    if (b < n2) {
+        gemm_nt_block<128, 128, 64, 2, 2>(p2, e2, b);
+    } else if (b < n2 + n3) {
+        if constexpr (NARROW3) gemm_nt_block<128, 64, 64, 4, 1>(p3, e3, b - n2);
+        else gemm_nt_block<128, 128, 64, 2, 2>(p3, e3, b - n2);
+    } else {
+        if constexpr (NARROW1) gemm_nt_block<128, 32, 64, 4, 1>(p1, e1, b - n2 - n3);
+        else gemm_nt_block<128, 128, 64, 2, 2>(p1, e1, b - n2 - n3);
+    }
+}
+
 // The dynamic LDS size of each kernel (up to 64 KB) is announced per kernel before the first
 // launch (done at trainer creation, outside any stream capture).
 template <int BM, int BN, int BK, int WGM, int WGN, class Epi>
@@ -355,23 +381,43 @@ hipError_t configure_gemm() {
                                (int)gemm_lds_bytes<BM, BN, BK, WGM, WGN>());
 }
 
+template <bool NARROW3, bool NARROW1>
+hipError_t configure_grad_products() {
+    auto kernel = grad_products_kernel<NARROW3, NARROW1>;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize,
+                               (int)gemm_lds_bytes<128, 128, 64, 2, 2>());
+}
+
+// Arguments and workgroup count (a multiple of 8) of one product with BM x BN tiles and BK-wide
+// slices; false when the shape does not fit the kernel's assumptions.
+template <int BM, int BN, int BK>
+bool gemm_args(const bf16_bits* A, unsigned int lda, const bf16_bits* Bt, unsigned int ldb,
+               unsigned int M, unsigned int N, unsigned int K, unsigned int splits,
+               const bf16_bits* Bt_hi, unsigned int m_split, GemmArgs* a, unsigned int* blocks) {
+    if (K == 0 || splits == 0 || K % (splits * BK) != 0 || lda % 8 != 0 || ldb % 8 != 0 || M == 0 || N == 0)
+        return false;
+    if (Bt_hi && m_split % BM != 0) return false;   // a tile takes one B operand
+    a->A = A; a->lda = lda; a->Bt = Bt; a->ldb = ldb; a->M = M; a->N = N; a->K = K / splits;
+    a->Bt_hi = Bt_hi ? Bt_hi : Bt;
+    a->m_split = Bt_hi ? m_split : 0xFFFFFFFFu;
+    a->tiles_m = (M + BM - 1) / BM;
+    a->tiles_n = (N + BN - 1) / BN;
+    a->splits = splits;
+    const unsigned int n_tiles = a->tiles_m * a->tiles_n * splits;
+    *blocks = 8u * ((n_tiles + 7u) / 8u);
+    return true;
+}
+
 template <int BM, int BN, int BK, int WGM, int WGN, class Epi>
 hipError_t launch_gemm(hipStream_t st, const bf16_bits* A, unsigned int lda, const bf16_bits* Bt,
                        unsigned int ldb, unsigned int M, unsigned int N, unsigned int K,
                        const Epi& epi, unsigned int splits = 1, const bf16_bits* Bt_hi = nullptr,
                        unsigned int m_split = 0xFFFFFFFFu) {
-    if (K == 0 || splits == 0 || K % (splits * BK) != 0 || lda % 8 != 0 || ldb % 8 != 0)
-        return hipErrorInvalidValue;
-    if (Bt_hi && m_split % BM != 0) return hipErrorInvalidValue;   // a tile takes one B operand
     GemmArgs a;
-    a.A = A; a.lda = lda; a.Bt = Bt; a.ldb = ldb; a.M = M; a.N = N; a.K = K / splits;
-    a.Bt_hi = Bt_hi ? Bt_hi : Bt;
-    a.m_split = Bt_hi ? m_split : 0xFFFFFFFFu;
-    a.tiles_m = (M + BM - 1) / BM;
-    a.tiles_n = (N + BN - 1) / BN;
-    a.splits = splits;
-    const unsigned int n_tiles = a.tiles_m * a.tiles_n * splits;
-    const unsigned int blocks = 8u * ((n_tiles + 7u) / 8u);
+    unsigned int blocks;
+    if (!gemm_args<BM, BN, BK>(A, lda, Bt, ldb, M, N, K, splits, Bt_hi, m_split, &a, &blocks))
+        return hipErrorInvalidValue;
     constexpr size_t lds = gemm_lds_bytes<BM, BN, BK, WGM, WGN>();
     hipLaunchKernelGGL((gemm_nt_kernel<BM, BN, BK, WGM, WGN, Epi>), dim3(blocks),
                        dim3(kGemmThreads), lds, st, a, epi);
@@ -611,9 +657,9 @@ struct SmallOptArgs {
     unsigned int out_grad_only;   // dueling head: only store the output layer's gradient
 };
 
-__global__ __launch_bounds__(256) void small_opt_kernel(SmallOptArgs p) {
+__device__ __forceinline__ void small_opt_block(const SmallOptArgs& p, unsigned int block) {
     const unsigned int n3 = (p.H + 1u) * p.Ap, n1 = p.H * (p.D + 1u);
-    const unsigned int e = blockIdx.x * 256u + threadIdx.x;
+    const unsigned int e = block * 256u + threadIdx.x;
     const OptStep st = opt_step(p.o);
     if (e < n3) {
         const unsigned int m = e / p.Ap, a = e - m * p.Ap;
@@ -655,7 +701,7 @@ __global__ __launch_bounds__(256) void small_opt_kernel(SmallOptArgs p) {
             opt_update(p.o, p.ob1 + j, g, st);
         }
     }
-    if (blockIdx.x == 0) {
+    if (block == 0) {
         __shared__ float wsum[4];
         float acc = 0.f;
         for (unsigned int i = threadIdx.x; i < p.B; i += 256) acc += p.lossi[i];
@@ -709,11 +755,11 @@ __device__ __forceinline__ f32x4 opt_update4(const OptState& o, size_t k, const 
     return w;
 }
 
-__global__ __launch_bounds__(256) void square_opt_kernel(SquareOptArgs p) {
+__device__ __forceinline__ void square_opt_block(const SquareOptArgs& p, unsigned int block_x, unsigned int block_y) {
     constexpr unsigned int TS = 68;                       // bf16 per parked row (64 + padding)
     __shared__ bf16_bits tile[64 * TS];
     const unsigned int tid = threadIdx.x, c4 = (tid & 15u) * 4u, r0 = tid >> 4;
-    const unsigned int m0 = blockIdx.y * 64u, n0 = blockIdx.x * 64u;
+    const unsigned int m0 = block_y * 64u, n0 = block_x * 64u;
     const OptStep st = opt_step(p.o);
     const size_t zs = (size_t)(p.R + 1u) * p.N;           // one split's partials
     f32x4 g[4];
@@ -737,7 +783,7 @@ __global__ __launch_bounds__(256) void square_opt_kernel(SquareOptArgs p) {
         *reinterpret_cast<uint2*>(p.wb + at) = pk;
         *reinterpret_cast<uint2*>(tile + r * TS + c4) = pk;
     }
-    if (blockIdx.y == 0 && tid < 16) {                     // the bias: row R of the partials
+    if (block_y == 0 && tid < 16) {                        // the bias: row R of the partials
         const float* src = p.part + (size_t)p.R * p.N + n0 + c4;
         f32x4 gb = *reinterpret_cast<const f32x4*>(src);
         for (unsigned int z = 1; z < p.splits; ++z) gb += *reinterpret_cast<const f32x4*>(src + z * zs);
@@ -754,6 +800,16 @@ __global__ __launch_bounds__(256) void square_opt_kernel(SquareOptArgs p) {
         *reinterpret_cast<unsigned int*>(p.wbT + at) = pair;
         if (st.sync) *reinterpret_cast<unsigned int*>(p.wbT_target + at) = pair;
     }
+}
+
+// One launch updates all three layers: the first (N / 64)^2 workgroups take the tiles of the square
+// layer, the rest the two narrow layers.
+__global__ __launch_bounds__(256) void opt_kernel(SquareOptArgs sq, SmallOptArgs sm) {
+    const unsigned int tiles_n = sq.N / 64u, n_square = tiles_n * (sq.R / 64u);
+    if (blockIdx.x < n_square)
+        square_opt_block(sq, blockIdx.x % tiles_n, blockIdx.x / tiles_n);
+    else
+        small_opt_block(sm, blockIdx.x - n_square);
 }
 
 // K splits of the narrow layers' gradient products (contraction over the padded batch): as
@@ -797,9 +853,10 @@ hipError_t wide_init_buffers(trainer* t) {
     hipError_t ec = configure_gemm<128, 128, 32, 2, 2, EpiForward>();
     if (ec == hipSuccess) ec = configure_gemm<128, 128, 64, 2, 2, EpiForward>();
     if (ec == hipSuccess) ec = configure_gemm<128, 64, 64, 2, 2, EpiMask>();
-    if (ec == hipSuccess) ec = configure_gemm<128, 64, 64, 4, 1, EpiPartial>();
-    if (ec == hipSuccess) ec = configure_gemm<128, 32, 64, 4, 1, EpiPartial>();
-    if (ec == hipSuccess) ec = configure_gemm<128, 128, 64, 2, 2, EpiPartial>();
+    if (ec == hipSuccess) ec = configure_grad_products<true, true>();
+    if (ec == hipSuccess) ec = configure_grad_products<true, false>();
+    if (ec == hipSuccess) ec = configure_grad_products<false, true>();
+    if (ec == hipSuccess) ec = configure_grad_products<false, false>();
     if (ec != hipSuccess) return ec;
     std::vector<bf16_bits> ones(t->Bp, (bf16_bits)0x3F80u);
     const size_t bytes = (size_t)t->Bp * sizeof(bf16_bits);
@@ -921,44 +978,51 @@ hipError_t enqueue_wide_step(trainer* t, hipStream_t st, unsigned int* count, bo
         if (e != hipSuccess) return e;
         ++n;
     }
-    // output layer: partial products of [dW3 ; db3] (row H), high and low part of dL/dQ side by side
-    const unsigned int splits = batch_splits(Bp);
-    const unsigned int Dx = (D + 1 + 31) / 32 * 32;
-    e = Ap == 32 ? launch_gemm<128, 64, 64, 4, 1>(st, w.H2T, Bp, w.dQT_hi, Bp, H + 1, 2 * Ap, Bp,
-                                                     EpiPartial{w.part3, H + 1, 2 * Ap}, splits)
-                 : launch_gemm<128, 128, 64, 2, 2>(st, w.H2T, Bp, w.dQT_hi, Bp, H + 1, 2 * Ap, Bp,
-                                                      EpiPartial{w.part3, H + 1, 2 * Ap}, splits);
-    if (e != hipSuccess) return e;
-    ++n;
     // dZ1^T = (W2 dZ2^T) masked by the first ReLU; uses W2 before its update
     e = launch_gemm<128, 64, 64, 2, 2>(st, w.W2, H, dZ2, H, H, B, H,
                                           EpiMask{w.H1T, w.dZ1T, Bp, H, B});
     if (e != hipSuccess) return e;
     ++n;
-    // second hidden layer: partial products of [dW2 ; db2] (row H), then the update of W2 and b2
+    // the three weight-gradient products, K-split partials each, in one launch:
+    //   [dW2 ; db2] (row H);  [dW3 ; db3] (row H) with the high and low part of dL/dQ side by
+    //   side;  [dW1^T | db1] (column D)
+    const unsigned int splits = batch_splits(Bp);
     const unsigned int splits2 = square_splits_for(Bp, H);
-    e = launch_gemm<128, 128, 64, 2, 2>(st, w.H1T, Bp, w.dZ2T, Bp, H + 1, H, Bp,
-                                           EpiPartial{w.part2, H + 1, H}, splits2);
-    if (e != hipSuccess) return e;
-    ++n;
+    const unsigned int Dx = (D + 1 + 31) / 32 * 32;
     {
-        SquareOptArgs a;
-        a.o = o; a.R = H; a.N = H; a.splits = splits2; a.part = w.part2;
-        a.w_off = t->oW2; a.b_off = t->ob2; a.wb = w.W2; a.wbT = w.W2T; a.wbT_target = w.W2T_t;
-        hipLaunchKernelGGL(square_opt_kernel, dim3(H / 64, H / 64), dim3(256), 0, st, a);
+        GemmArgs g2, g3, g1;
+        unsigned int n2 = 0, n3 = 0, n1 = 0;
+        const bool narrow3 = Ap == 32, narrow1 = Dx == 32;
+        bool ok = gemm_args<128, 128, 64>(w.H1T, Bp, w.dZ2T, Bp, H + 1, H, Bp, splits2, nullptr, 0, &g2, &n2);
+        ok = ok && (narrow3 ? gemm_args<128, 64, 64>(w.H2T, Bp, w.dQT_hi, Bp, H + 1, 2 * Ap, Bp, splits,
+                                                     nullptr, 0, &g3, &n3)
+                            : gemm_args<128, 128, 64>(w.H2T, Bp, w.dQT_hi, Bp, H + 1, 2 * Ap, Bp, splits,
+                                                      nullptr, 0, &g3, &n3));
+        ok = ok && (narrow1 ? gemm_args<128, 32, 64>(w.dZ1T, Bp, w.XT, Bp, H, Dx, Bp, splits, nullptr, 0,
+                                                     &g1, &n1)
+                            : gemm_args<128, 128, 64>(w.dZ1T, Bp, w.XT, Bp, H, Dx, Bp, splits, nullptr, 0,
+                                                      &g1, &n1));
+        if (!ok) return hipErrorInvalidValue;
+        const EpiPartial e2{w.part2, H + 1, H}, e3{w.part3, H + 1, 2 * Ap}, e1{w.part1, H, Dx};
+        constexpr size_t lds = gemm_lds_bytes<128, 128, 64, 2, 2>();
+        const dim3 grid(n2 + n3 + n1), block(kGemmThreads);
+        if (narrow3 && narrow1)
+            hipLaunchKernelGGL((grad_products_kernel<true, true>), grid, block, lds, st, g2, e2, n2, g3, e3, n3, g1, e1);
+        else if (narrow3)
+            hipLaunchKernelGGL((grad_products_kernel<true, false>), grid, block, lds, st, g2, e2, n2, g3, e3, n3, g1, e1);
+        else if (narrow1)
+            hipLaunchKernelGGL((grad_products_kernel<false, true>), grid, block, lds, st, g2, e2, n2, g3, e3, n3, g1, e1);
+        else
+            hipLaunchKernelGGL((grad_products_kernel<false, false>), grid, block, lds, st, g2, e2, n2, g3, e3, n3, g1, e1);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         ++n;
     }
-    // first hidden layer: partial products of [dW1^T | db1] (column D)
-    e = Dx == 32 ? launch_gemm<128, 32, 64, 4, 1>(st, w.dZ1T, Bp, w.XT, Bp, H, Dx, Bp,
-                                                     EpiPartial{w.part1, H, Dx}, splits)
-                 : launch_gemm<128, 128, 64, 2, 2>(st, w.dZ1T, Bp, w.XT, Bp, H, Dx, Bp,
-                                                      EpiPartial{w.part1, H, Dx}, splits);
-    if (e != hipSuccess) return e;
-    ++n;
-    // both narrow layers' update, mean loss, step counter
+    // all three layers' update, mean loss, step counter
     {
+        SquareOptArgs q;
+        q.o = o; q.R = H; q.N = H; q.splits = splits2; q.part = w.part2;
+        q.w_off = t->oW2; q.b_off = t->ob2; q.wb = w.W2; q.wbT = w.W2T; q.wbT_target = w.W2T_t;
         SmallOptArgs a;
         a.o = o; a.splits = splits; a.H = H; a.D = D; a.Dp = Dp; a.Dx = Dx; a.Ap = Ap; a.B = B;
         a.part3 = w.part3; a.part1 = w.part1;
@@ -967,7 +1031,9 @@ hipError_t enqueue_wide_step(trainer* t, hipStream_t st, unsigned int* count, bo
         a.ctr = t->ctr; a.lossi = t->lossi;
         a.out_grad_only = t->dueling ? 1u : 0u;
         const unsigned int elems = (H + 1) * Ap + H * (D + 1);
-        hipLaunchKernelGGL(small_opt_kernel, dim3((elems + 255) / 256), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(opt_kernel, dim3((H / 64) * (H / 64) + (elems + 255) / 256), dim3(256), 0, st, q, a);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
         ++n;
         unsigned int nh = 0;
         e = enqueue_head_update(t, st, &nh);
