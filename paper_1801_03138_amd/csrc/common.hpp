@@ -89,6 +89,28 @@ struct AppendArgs {
     RingPos pos;               // ring state before this append
 };
 
+// Where a sample-and-gather launch writes the unpacked batch (see launch_sample_gather).
+struct GatherOut {
+    void* out_s;
+    void* out_s_next;
+    unsigned int out_ld;
+    int* out_a;
+    float* out_r;
+    unsigned char* out_term;
+    unsigned int* out_idx;
+    void* out_s_t;
+    unsigned int out_t_ld;
+};
+
+// Argument block of the kernel that appends and then samples and gathers in one launch.  It
+// starts with the append kernel's block, so one object can feed either kernel.
+struct AppendGatherArgs : AppendArgs {
+    unsigned long long seed;
+    const unsigned long long* step_ptr;   // sampling step (device)
+    unsigned int batch, lane_shift;
+    GatherOut out;
+};
+
 }  // namespace rp
 
 struct replay {

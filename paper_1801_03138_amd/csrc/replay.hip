@@ -99,69 +99,71 @@ __device__ __forceinline__ void store_state_after(const RingGeom& g, const RingP
     }
 }
 
-// PAIR rows: [s | s' | pad to 4 | action | reward bits | terminal 0/1 | zero pad], built one
-// 32-bit word per thread.
+// Word w of the packed PAIR row of payload experience `row`:
+// [s | s' | pad to 4 | action | reward bits | terminal 0/1 | zero pad].
+template <int ELEM>
+__device__ __forceinline__ unsigned int payload_row_word(const RingGeom& g, const Payload& src,
+                                                         unsigned long long row, unsigned int w) {
+    const unsigned int o = w * 4u, sb = g.state_bytes;
+    unsigned int val = 0;
+    if (o < g.meta_off) {
+        if (ELEM == 4) {
+            const unsigned int col = w;
+            val = col < g.state_dim
+                      ? reinterpret_cast<const unsigned int*>(src.s)[row * g.state_dim + col]
+                      : reinterpret_cast<const unsigned int*>(src.s_next)[row * g.state_dim + col -
+                                                                          g.state_dim];
+        } else if (ELEM == 2) {
+#pragma unroll
+            for (unsigned int h = 0; h < 2; ++h) {
+                const unsigned int col = 2u * w + h;
+                unsigned int half = 0;
+                if (col < g.state_dim)
+                    half = reinterpret_cast<const unsigned short*>(src.s)[row * g.state_dim + col];
+                else if (col < 2u * g.state_dim)
+                    half = reinterpret_cast<const unsigned short*>(src.s_next)[row * g.state_dim + col -
+                                                                               g.state_dim];
+                val |= half << (16 * h);
+            }
+        } else {
+#pragma unroll
+            for (unsigned int b = 0; b < 4; ++b) {
+                const unsigned int ob = o + b;
+                unsigned int byte = 0;
+                if (ob < sb)
+                    byte = src.s[row * sb + ob];
+                else if (ob < 2 * sb)
+                    byte = src.s_next[row * sb + ob - sb];
+                val |= byte << (8 * b);
+            }
+        }
+    } else if (o == g.meta_off) {
+        val = (unsigned int)src.a[row];
+    } else if (o == g.meta_off + 4) {
+        val = __float_as_uint(src.r[row]);
+    } else if (o == g.meta_off + 8) {
+        val = src.term[row] ? 1u : 0u;
+    }
+    return val;
+}
+
+// PAIR rows, built one 32-bit word per thread.
 template <int ELEM>
 __global__ __launch_bounds__(kThreads) void append_pair_kernel(AppendArgs p) {
     const RingGeom& g = p.g;
     const unsigned long long n = p.n;
-    const unsigned char* __restrict__ s = p.src.s;
-    const unsigned char* __restrict__ s_next = p.src.s_next;
-    const int* __restrict__ a = p.src.a;
-    const float* __restrict__ r = p.src.r;
-    const unsigned char* __restrict__ term = p.src.term;
     const unsigned int rows_per_block = p.rows_per_block;
     const unsigned long long head = p.pos.head;
     store_state_after(g, p.pos, n);
     const unsigned int words = g.row_bytes >> 2;
     const unsigned long long row0 = (unsigned long long)blockIdx.x * rows_per_block;
-    const unsigned int sb = g.state_bytes;
     for (unsigned int e = threadIdx.x; e < rows_per_block * words; e += kThreads) {
         const unsigned int k = e / words, w = e - k * words;
         const unsigned long long row = row0 + k;
         if (row >= n) break;
         unsigned long long slot = head + row;
         if (slot >= g.capacity) slot -= g.capacity;
-        const unsigned int o = w * 4u;
-        unsigned int val = 0;
-        if (o < g.meta_off) {
-            if (ELEM == 4) {
-                const unsigned int col = w;
-                val = col < g.state_dim
-                          ? reinterpret_cast<const unsigned int*>(s)[row * g.state_dim + col]
-                          : reinterpret_cast<const unsigned int*>(s_next)[row * g.state_dim + col -
-                                                                          g.state_dim];
-            } else if (ELEM == 2) {
-#pragma unroll
-                for (unsigned int h = 0; h < 2; ++h) {
-                    const unsigned int col = 2u * w + h;
-                    unsigned int half = 0;
-                    if (col < g.state_dim)
-                        half = reinterpret_cast<const unsigned short*>(s)[row * g.state_dim + col];
-                    else if (col < 2u * g.state_dim)
-                        half = reinterpret_cast<const unsigned short*>(s_next)[row * g.state_dim + col -
-                                                                               g.state_dim];
-                    val |= half << (16 * h);
-                }
-            } else {
-#pragma unroll
-                for (unsigned int b = 0; b < 4; ++b) {
-                    const unsigned int ob = o + b;
-                    unsigned int byte = 0;
-                    if (ob < sb)
-                        byte = s[row * sb + ob];
-                    else if (ob < 2 * sb)
-                        byte = s_next[row * sb + ob - sb];
-                    val |= byte << (8 * b);
-                }
-            }
-        } else if (o == g.meta_off) {
-            val = (unsigned int)a[row];
-        } else if (o == g.meta_off + 4) {
-            val = __float_as_uint(r[row]);
-        } else if (o == g.meta_off + 8) {
-            val = term[row] ? 1u : 0u;
-        }
+        const unsigned int val = payload_row_word<ELEM>(g, p.src, row, w);
         reinterpret_cast<unsigned int*>(g.rows + slot * g.row_bytes)[w] = val;
     }
 }
@@ -257,21 +259,18 @@ __device__ __forceinline__ float unit_from_u8(unsigned int b) {
 // flight at once; the rows go to LDS and then leave as contiguous, coalesced runs per output
 // tensor.
 // ---------------------------------------------------------------------------------------
-template <int ELEM, int U, bool DISTINCT>
-__global__ __launch_bounds__(kThreads) void sample_gather_pair_kernel(
-    RingGeom g, unsigned long long seed, unsigned long long step_value,
-    const unsigned long long* __restrict__ step_ptr, unsigned int size_value, unsigned int batch,
-    unsigned int lane_shift, void* __restrict__ out_s, void* __restrict__ out_s_next,
-    unsigned int out_ld, int* __restrict__ out_a, float* __restrict__ out_r,
-    unsigned char* __restrict__ out_term, unsigned int* __restrict__ out_idx,
-    void* __restrict__ out_s_t, unsigned int out_t_ld) {
+// FRESH: `n_fresh` experiences from `fresh` are being appended at `head` by this same launch; a
+// drawn slot among them is composed from those arrays instead of read from the ring.
+template <int ELEM, int U, bool DISTINCT, bool FRESH>
+__device__ __forceinline__ void gather_pair_block(const RingGeom& g, unsigned long long seed,
+                                                  unsigned long long step, unsigned int size,
+                                                  unsigned int batch, unsigned int lane_shift,
+                                                  const GatherOut& o, const Payload& fresh,
+                                                  unsigned long long head, unsigned long long n_fresh) {
     extern __shared__ uint4 smem[];
     unsigned int* idx_s = reinterpret_cast<unsigned int*>(smem);   // distinct mode: R slot numbers
     unsigned char* rows_s = reinterpret_cast<unsigned char*>(smem) + (DISTINCT ? 4 * U * kThreads : 0);
 
-    // callers that mirror the ring state pass the size by value: no dependent load up front
-    const unsigned long long step = step_ptr ? *step_ptr : step_value;
-    const unsigned int size = size_value ? size_value : (unsigned int)g.state->size;
     const unsigned int rows_per_pass = kThreads >> lane_shift;
     const unsigned int R = U * rows_per_pass;
     const unsigned int i0 = blockIdx.x * R;
@@ -290,19 +289,33 @@ __global__ __launch_bounds__(kThreads) void sample_gather_pair_kernel(
             __syncthreads();
         }
         const unsigned char* src[U];
+        unsigned long long fresh_row[U];
+        bool is_fresh[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             unsigned int rr = rsub + u * rows_per_pass;
             rr = rr < nrows ? rr : 0u;   // a row past the end re-reads row 0; not stored
             const unsigned int p = DISTINCT ? idx_s[rr] : uniform_draw(seed, step, i0 + rr, size);
             src[u] = g.rows + (unsigned long long)p * g.row_bytes;
-            if (out_idx && part0 == 0 && rsub + u * rows_per_pass < nrows) out_idx[i0 + rr] = p;
+            unsigned long long off = (unsigned long long)p + g.capacity - head;
+            if (off >= g.capacity) off -= g.capacity;
+            fresh_row[u] = off;
+            is_fresh[u] = FRESH && off < n_fresh;
+            if (o.out_idx && part0 == 0 && rsub + u * rows_per_pass < nrows) o.out_idx[i0 + rr] = p;
         }
         for (unsigned int part = part0; part < V; part += lanes) {
             // (a native vector type: an array of HIP's uint4 struct would live in scratch memory)
             u32x4 val[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) val[u] = reinterpret_cast<const u32x4*>(src[u])[part];
+            for (int u = 0; u < U; ++u) {
+                if (FRESH && is_fresh[u]) {
+#pragma unroll
+                    for (unsigned int j = 0; j < 4; ++j)
+                        val[u][j] = payload_row_word<ELEM>(g, fresh, fresh_row[u], 4u * part + j);
+                } else {
+                    val[u] = reinterpret_cast<const u32x4*>(src[u])[part];
+                }
+            }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const unsigned int rr = rsub + u * rows_per_pass;
@@ -318,21 +331,21 @@ __global__ __launch_bounds__(kThreads) void sample_gather_pair_kernel(
     const unsigned int D = g.state_dim;
     for (unsigned int row = threadIdx.x >> 5; row < nrows; row += kThreads >> 5) {
         const unsigned char* base = rows_s + (size_t)row * g.row_bytes;
-        const size_t o = (size_t)(i0 + row) * out_ld;
+        const size_t at = (size_t)(i0 + row) * o.out_ld;
         for (unsigned int col = threadIdx.x & 31u; col < D; col += 32) {
             if (ELEM == 4) {
                 const unsigned int* w = reinterpret_cast<const unsigned int*>(base);
-                if (out_s) static_cast<unsigned int*>(out_s)[o + col] = w[col];
-                if (out_s_next) static_cast<unsigned int*>(out_s_next)[o + col] = w[D + col];
-                if (out_s_t) static_cast<unsigned int*>(out_s_t)[(size_t)col * out_t_ld + i0 + row] = w[col];
+                if (o.out_s) static_cast<unsigned int*>(o.out_s)[at + col] = w[col];
+                if (o.out_s_next) static_cast<unsigned int*>(o.out_s_next)[at + col] = w[D + col];
+                if (o.out_s_t) static_cast<unsigned int*>(o.out_s_t)[(size_t)col * o.out_t_ld + i0 + row] = w[col];
             } else if (ELEM == 2) {
                 const unsigned short* h = reinterpret_cast<const unsigned short*>(base);
-                if (out_s) static_cast<unsigned short*>(out_s)[o + col] = h[col];
-                if (out_s_next) static_cast<unsigned short*>(out_s_next)[o + col] = h[D + col];
-                if (out_s_t) static_cast<unsigned short*>(out_s_t)[(size_t)col * out_t_ld + i0 + row] = h[col];
+                if (o.out_s) static_cast<unsigned short*>(o.out_s)[at + col] = h[col];
+                if (o.out_s_next) static_cast<unsigned short*>(o.out_s_next)[at + col] = h[D + col];
+                if (o.out_s_t) static_cast<unsigned short*>(o.out_s_t)[(size_t)col * o.out_t_ld + i0 + row] = h[col];
             } else {
-                if (out_s) static_cast<float*>(out_s)[o + col] = unit_from_u8(base[col]);
-                if (out_s_next) static_cast<float*>(out_s_next)[o + col] = unit_from_u8(base[D + col]);
+                if (o.out_s) static_cast<float*>(o.out_s)[at + col] = unit_from_u8(base[col]);
+                if (o.out_s_next) static_cast<float*>(o.out_s_next)[at + col] = unit_from_u8(base[D + col]);
             }
         }
     }
@@ -340,10 +353,44 @@ __global__ __launch_bounds__(kThreads) void sample_gather_pair_kernel(
         const unsigned int i = i0 + row;
         const unsigned int* meta =
             reinterpret_cast<const unsigned int*>(rows_s + (size_t)row * g.row_bytes + g.meta_off);
-        if (out_a) out_a[i] = (int)meta[0];
-        if (out_r) out_r[i] = __uint_as_float(meta[1]);
-        if (out_term) out_term[i] = (unsigned char)meta[2];
+        if (o.out_a) o.out_a[i] = (int)meta[0];
+        if (o.out_r) o.out_r[i] = __uint_as_float(meta[1]);
+        if (o.out_term) o.out_term[i] = (unsigned char)meta[2];
     }
+}
+
+template <int ELEM, int U, bool DISTINCT>
+__global__ __launch_bounds__(kThreads) void sample_gather_pair_kernel(
+    RingGeom g, unsigned long long seed, unsigned long long step_value,
+    const unsigned long long* __restrict__ step_ptr, unsigned int size_value, unsigned int batch,
+    unsigned int lane_shift, GatherOut out) {
+    // callers that mirror the ring state pass the size by value: no dependent load up front
+    const unsigned long long step = step_ptr ? *step_ptr : step_value;
+    const unsigned int size = size_value ? size_value : (unsigned int)g.state->size;
+    gather_pair_block<ELEM, U, DISTINCT, false>(g, seed, step, size, batch, lane_shift, out,
+                                                Payload{nullptr, nullptr, nullptr, nullptr, nullptr}, 0, 0);
+}
+
+// Append, then sample and gather, in one launch (the train step of wide networks).  The ring
+// state before the append comes by value.  The workgroups share the new rows out among
+// themselves and send them to the ring first; nobody reads those slots from the ring in this
+// launch (see FRESH above), so the order of the two halves within the launch does not matter.
+template <int ELEM, bool DISTINCT>
+__global__ __launch_bounds__(kThreads) void append_sample_gather_pair_kernel(AppendGatherArgs p) {
+    const RingGeom& g = p.g;
+    store_state_after(g, p.pos, p.n);
+    const unsigned int words = g.row_bytes >> 2;
+    for (unsigned long long row = blockIdx.x; row < p.n; row += gridDim.x) {
+        unsigned long long slot = p.pos.head + row;
+        if (slot >= g.capacity) slot -= g.capacity;
+        for (unsigned int w = threadIdx.x; w < words; w += kThreads)
+            reinterpret_cast<unsigned int*>(g.rows + slot * g.row_bytes)[w] =
+                payload_row_word<ELEM>(g, p.src, row, w);
+    }
+    const unsigned long long sz = p.pos.size + p.n;
+    const unsigned int size = (unsigned int)(sz > g.capacity ? g.capacity : sz);
+    gather_pair_block<ELEM, 1, DISTINCT, true>(g, p.seed, *p.step_ptr, size, p.batch, p.lane_shift,
+                                               p.out, p.src, p.pos.head, p.n);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -471,6 +518,44 @@ unsigned int append_blocks(const AppendArgs& a) {
     return (unsigned int)((a.n + a.rows_per_block - 1) / a.rows_per_block);
 }
 
+// lanes per PAIR row in the gather kernels: enough for one 16-byte piece each, at most the whole block
+static unsigned int pair_lane_shift(const RingGeom& g) {
+    const unsigned int V = g.row_bytes >> 4;
+    unsigned int lane_shift = 0;
+    while ((1u << lane_shift) < V && lane_shift < 8) ++lane_shift;
+    return lane_shift;
+}
+
+AppendGatherArgs make_append_gather_args(const RingGeom& g, const RingPos& pos, unsigned long long n,
+                                         const Payload& src, unsigned long long seed,
+                                         const unsigned long long* step_ptr, unsigned int batch,
+                                         const GatherOut& out) {
+    AppendGatherArgs a;
+    static_cast<AppendArgs&>(a) = make_append_args(g, pos, n, src);
+    a.seed = seed;
+    a.step_ptr = step_ptr;
+    a.batch = batch;
+    a.lane_shift = pair_lane_shift(g);
+    a.out = out;
+    return a;
+}
+
+void* append_gather_func(const RingGeom& g) {
+    if (g.layout != RP_PAIR || g.elem_bytes == 1) return nullptr;
+    const bool distinct = g.sampling == RP_DISTINCT;
+    if (g.elem_bytes == 4)
+        return distinct ? reinterpret_cast<void*>(append_sample_gather_pair_kernel<4, true>)
+                        : reinterpret_cast<void*>(append_sample_gather_pair_kernel<4, false>);
+    return distinct ? reinterpret_cast<void*>(append_sample_gather_pair_kernel<2, true>)
+                    : reinterpret_cast<void*>(append_sample_gather_pair_kernel<2, false>);
+}
+
+void append_gather_shape(const AppendGatherArgs& a, unsigned int* blocks, size_t* lds) {
+    const unsigned int R = kThreads >> a.lane_shift;   // one row per thread group
+    *blocks = (a.batch + R - 1) / R;
+    *lds = (a.g.sampling == RP_DISTINCT ? 4 * (size_t)kThreads : 0) + (size_t)R * a.g.row_bytes;
+}
+
 void* append_pair_func(const RingGeom& g) {
     if (g.elem_bytes == 4) return reinterpret_cast<void*>(append_pair_kernel<4>);
     if (g.elem_bytes == 2) return reinterpret_cast<void*>(append_pair_kernel<2>);
@@ -522,10 +607,7 @@ hipError_t launch_sample_gather(const RingGeom& g, unsigned long long seed,
                                 unsigned int size_value, unsigned long long head_value) {
     if (out_s_t && (g.layout != RP_PAIR || g.elem_bytes == 1)) return hipErrorInvalidValue;
     if (g.layout == RP_PAIR) {
-        // lanes per row: enough for one 16-byte piece each, at most the whole block
-        const unsigned int V = g.row_bytes >> 4;
-        unsigned int lane_shift = 0;
-        while ((1u << lane_shift) < V && lane_shift < 8) ++lane_shift;
+        const unsigned int lane_shift = pair_lane_shift(g);
         const unsigned int rows_per_pass = kThreads >> lane_shift;
         // rows per thread: 1, 2 and 4 were tried on 256-byte rows at batches 2,048 to 65,536;
         // 1 (sixteen rows per block, eight blocks resident per CU) was fastest throughout
@@ -534,10 +616,10 @@ hipError_t launch_sample_gather(const RingGeom& g, unsigned long long seed,
         const unsigned int blocks = (batch + R - 1) / R;
         const bool distinct = g.sampling == RP_DISTINCT;
         const size_t lds = (distinct ? 4 * (size_t)U * kThreads : 0) + (size_t)R * g.row_bytes;
+        const GatherOut out{out_s, out_s_next, out_ld, out_a, out_r, out_term, out_idx, out_s_t, out_t_ld};
 #define RP_LAUNCH_PAIR(E, UU, DD)                                                                  \
     hipLaunchKernelGGL((sample_gather_pair_kernel<E, UU, DD>), dim3(blocks), dim3(kThreads), lds,   \
-                       stream, g, seed, step_value, step_ptr, size_value, batch, lane_shift, out_s, \
-                       out_s_next, out_ld, out_a, out_r, out_term, out_idx, out_s_t, out_t_ld)
+                       stream, g, seed, step_value, step_ptr, size_value, batch, lane_shift, out)
 #define RP_LAUNCH_PAIR_E(E) \
     do { if (distinct) RP_LAUNCH_PAIR(E, 1, true); else RP_LAUNCH_PAIR(E, 1, false); } while (0)
         if (g.elem_bytes == 4)

@@ -17,6 +17,16 @@ AppendArgs make_append_args(const RingGeom& g, const RingPos& pos, unsigned long
 unsigned int append_blocks(const AppendArgs& a);
 void* append_pair_func(const RingGeom& g);   // the __global__ function, as hipLaunchKernel takes it
 
+// Pieces of the launch that appends n experiences and then samples and gathers a batch (PAIR
+// rings with 2- or 4-byte elements; the function is null otherwise): argument block, the
+// __global__ function, grid size and dynamic LDS bytes.
+AppendGatherArgs make_append_gather_args(const RingGeom& g, const RingPos& pos, unsigned long long n,
+                                         const Payload& src, unsigned long long seed,
+                                         const unsigned long long* step_ptr, unsigned int batch,
+                                         const GatherOut& out);
+void* append_gather_func(const RingGeom& g);
+void append_gather_shape(const AppendGatherArgs& a, unsigned int* blocks, size_t* lds);
+
 // Sample `batch` slots and unpack them.  The sampling step is *step_ptr when
 // step_ptr is non-null (device), else step_value.  out_ld is the row pitch of
 // out_s / out_s_next in elements (>= D); columns D..out_ld-1 are not written.

@@ -578,9 +578,28 @@ hipError_t enqueue_append_and_step(trainer* t, const Payload& src, hipStream_t s
     if (t->fused) return enqueue_fused_step(t, src, nullptr, st, count);
     unsigned int n = 0, k = 0;
     replay* r = t->rp_;
+    if (t->cfg.appends_per_step && t->wide) {
+        // append, sample and gather in one launch; the step then starts from the gathered batch
+        const unsigned int Dp = t->Dp;
+        unsigned short* X = static_cast<unsigned short*>(t->X);
+        t->append_args = make_append_gather_args(
+            r->geom, RingPos{r->head, r->size, r->total}, t->cfg.appends_per_step, src, r->cfg.seed,
+            &t->ctr->step, t->B,
+            GatherOut{X, X + (size_t)t->B * Dp, Dp, t->act, t->rew, t->term, t->idx, t->wd.XT, t->Bp});
+        unsigned int blocks;
+        size_t lds;
+        append_gather_shape(t->append_args, &blocks, &lds);
+        void* kargs[] = {&t->append_args};
+        hipError_t e = hipLaunchKernel(append_gather_func(r->geom), dim3(blocks), dim3(kThreads), kargs,
+                                       lds, st);
+        if (e != hipSuccess) return e;
+        e = enqueue_wide_step(t, st, &k, false);
+        if (count) *count = 1 + k;
+        return e;
+    }
     if (t->cfg.appends_per_step) {
-        t->append_args = make_append_args(r->geom, RingPos{r->head, r->size, r->total},
-                                          t->cfg.appends_per_step, src);
+        static_cast<AppendArgs&>(t->append_args) =
+            make_append_args(r->geom, RingPos{r->head, r->size, r->total}, t->cfg.appends_per_step, src);
         void* kargs[] = {&t->append_args};
         hipError_t e = hipLaunchKernel(append_pair_func(r->geom), dim3(append_blocks(t->append_args)),
                                        dim3(kThreads), kargs, 0, st);
@@ -859,7 +878,9 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
         }
         t->pin_dev = static_cast<unsigned char*>(dp);
     }
-    t->payload_func = t->fused ? rp::fused_rows_func() : rp::append_pair_func(rp_->geom);
+    t->payload_func = t->fused  ? rp::fused_rows_func()
+                      : t->wide ? rp::append_gather_func(rp_->geom)
+                                : rp::append_pair_func(rp_->geom);
     t->payload_kargs[0] = t->fused ? static_cast<void*>(&t->row_args) : static_cast<void*>(&t->append_args);
     t->payload_kargs_target[0] = &t->row_args_target;
     t->payload_per_step = t->fused && t->wt ? 2u : 1u;

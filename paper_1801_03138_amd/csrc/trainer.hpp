@@ -148,7 +148,7 @@ struct trainer {
     // whose argument is replaced before every launch.
     rp::RowArgs row_args;
     rp::RowArgs row_args_target;     // fused step with a frozen target network: its first pass
-    rp::AppendArgs append_args;
+    rp::AppendGatherArgs append_args;   // the append kernel reads its leading AppendArgs part
     void* payload_func;
     void* payload_kargs[1];          // -> row_args / append_args
     void* payload_kargs_target[1];   // -> row_args_target
