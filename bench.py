@@ -99,10 +99,11 @@ def prefill(ring, rows, n_total):
 
 # ----------------------------------------------------------------------------- legs
 def leg_paper_shaped(B, synth, steps, warmup, full_ring, host_payload=False, target_sync=0,
-                     dueling=False):
+                     dueling=False, distinct=False):
     import torch
     c = P_CFG
-    ring = B.Replay(c["capacity"], c["D"], burn_in=c["burn_in"], seed=0, max_append=4096)
+    ring = B.Replay(c["capacity"], c["D"], burn_in=c["burn_in"], seed=0, max_append=4096,
+                    distinct=distinct)
     base = synth.experiences(100_000, c["D"], c["A"], c["p_term"], seed=0)
     prefill(ring, base, c["capacity"] if full_ring else c["burn_in"])
     tr = B.Trainer(ring, c["H"], c["A"], c["B"], opt=B.RP_ADAM, loss=B.RP_HUBER, lr=c["lr"],
@@ -183,12 +184,11 @@ def leg_append_sweep(B, synth):
     return out
 
 
-def leg_copy_calibration(reps):
+def leg_copy_calibration(reps, n=64 * 1024 * 1024):
     """A plain device-to-device copy of known size (256 MiB read + 256 MiB written per launch):
     the "achievable" bandwidth next to the 8 TB/s peak, and the kernel whose FETCH_SIZE /
     WRITE_SIZE readings scale the HBM-traffic counters of the other kernels."""
     import torch
-    n = 64 * 1024 * 1024
     a = torch.empty(n, dtype=torch.float32, device="cuda")
     b = torch.ones(n, dtype=torch.float32, device="cuda")
     for _ in range(3):
@@ -196,6 +196,24 @@ def leg_copy_calibration(reps):
     ms = event_time_ms(lambda k: a.copy_(b), reps)
     return {"bytes_read": 4 * n, "bytes_written": 4 * n, "us_per_call": 1e3 * ms,
             "GBps": 8 * n / (ms * 1e-3) / 1e9}
+
+
+def leg_copy_small(n, reps):
+    """Plain copies of n floats each (4n bytes read + 4n written per launch), recorded in a graph
+    like the gather sweep.  Every launch of a replay takes another slice of two 1 GiB buffers,
+    so the data comes from HBM rather than from the 256 MB last-level cache."""
+    import torch
+    slices = max(2, (256 * 1024 * 1024) // n)
+    a = torch.empty(slices * n, dtype=torch.float32, device="cuda")
+    b = torch.ones(slices * n, dtype=torch.float32, device="cuda")
+
+    def one(k):
+        lo = (k % slices) * n
+        a[lo:lo + n].copy_(b[lo:lo + n])
+    launches = min(slices, 64)
+    ms = graph_time_ms(one, launches, max(1, reps // launches))
+    return {"bytes_read": 4 * n, "bytes_written": 4 * n, "us_per_call": 1e3 * ms,
+            "GBps": 8 * n / (ms * 1e-3) / 1e9, "distinct_slices": slices}
 
 
 def leg_large_state(B, reps):
@@ -379,7 +397,10 @@ def main():
         out["paper_shaped_dueling"] = leg_paper_shaped(B, synth, args.steps, args.warmup, False, dueling=True)
         out["paper_shaped_dueling_target_network"] = leg_paper_shaped(
             B, synth, args.steps, args.warmup, False, target_sync=10_000, dueling=True)
-        for k in ("paper_shaped_target_network", "paper_shaped_dueling", "paper_shaped_dueling_target_network"):
+        out["paper_shaped_without_duplicates"] = leg_paper_shaped(B, synth, args.steps, args.warmup, False,
+                                                                  distinct=True)
+        for k in ("paper_shaped_target_network", "paper_shaped_dueling", "paper_shaped_dueling_target_network",
+                  "paper_shaped_without_duplicates"):
             log("[bench]   %-38s %8.0f steps/s, %d kernels/step" %
                 (k, out[k]["steps_per_s"], out[k]["kernels_per_step"]))
     if "inram" in legs:
@@ -420,6 +441,12 @@ def main():
         log("[bench]   %.1f GB/s" % out["copy_calibration"]["GBps"])
         if roofline is not None:
             roofline["frac_of_copy_bandwidth"] = roofline["achieved"] / out["copy_calibration"]["GBps"]
+            # a plain copy that moves as many bytes as the roofline launch (half read, half written)
+            small = leg_copy_small(roofline["alg_bytes_per_launch"] // 8, 640)
+            out["copy_same_bytes_as_gather"] = small
+            roofline["frac_of_same_size_copy"] = roofline["achieved"] / small["GBps"]
+            log("[bench]   same-size copy (%.1f MB): %.2f us, %.1f GB/s" %
+                (8 * (roofline["alg_bytes_per_launch"] // 8) / 1e6, small["us_per_call"], small["GBps"]))
     if "large" in legs:
         log("[bench] large-state gather (200,000 x 84x84x4 uint8, one state per slot) ...")
         out["large_state_gather"] = leg_large_state(B, max(50, args.gather_reps // 5))
