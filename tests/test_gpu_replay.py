@@ -305,3 +305,49 @@ def test_sampling_without_duplicates_at_paper_size(B):
     # the gathered rows are those slots' rows (the ring holds the 100,000 source rows ten times)
     s = out[0].cpu().numpy()
     assert np.array_equal(s.view(np.uint32), rows["s"][idx % 100_000].view(np.uint32))
+
+
+def _random_rings(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        dtype = str(rng.choice(["f32", "bf16", "u8"]))
+        chain = bool(rng.random() < 0.4)
+        D = int(rng.choice([1, 2, 3, 7, 27, 31, 32, 33, 63, 64, 65, 100, 255, 1000, 4099]))
+        if not chain:
+            D = min(D, 255)
+        out.append(dict(dtype=dtype, chain=chain, D=D, capacity=int(rng.choice([1, 2, 7, 64, 129, 1000, 4097])),
+                        burn_in=int(rng.choice([0, 0, 5, 50])), distinct=bool(rng.random() < 0.3),
+                        seed=int(rng.integers(0, 10_000))))
+    return out
+
+
+@pytest.mark.parametrize("c", _random_rings(40, 271127), ids=lambda c: "%s-%s-D%d-C%d-%s" % (
+    c["dtype"], "chain" if c["chain"] else "pair", c["D"], c["capacity"], "distinct" if c["distinct"] else "repl"))
+def test_random_rings(B, c):
+    """Seeded random rings: a run of appends of random sizes (host and device sources, wrapping
+    several times) with sampling at random batch sizes in between; ring contents, state, slot
+    numbers and batches bit-exact, refusals in the same places."""
+    rng = np.random.default_rng(c["seed"])
+    C, D, chain = c["capacity"], c["D"], c["chain"]
+    gpu = B.Replay(C, D, DT[c["dtype"]][1], B.RP_CHAIN if chain else B.RP_PAIR, burn_in=c["burn_in"],
+                   seed=c["seed"], max_append=min(C, 600), distinct=c["distinct"])
+    ref = oracle.Ring(C, D, DT[c["dtype"]][0], oracle.CHAIN if chain else oracle.PAIR, burn_in=c["burn_in"])
+    total = min(3 * C + 40, 2500 if D > 300 else 9000)
+    rows = _rows(total, D, 11, 0.1, c["seed"], c["dtype"])
+    k, step = 0, 0
+    while k < total:
+        n = int(min(total - k, min(C, 600), rng.choice([1, 1, 2, 3, 17, 64, 200, 600])))
+        _append_both(gpu, ref, synth.take(rows, k, k + n), bool(rng.random() < 0.5), chain=chain)
+        k += n
+        for batch in rng.choice([1, 2, 15, 16, 17, 100, 256, 1000], size=2):
+            batch = int(batch)
+            idx = ref.sample(c["seed"], step, batch, distinct=c["distinct"])
+            st, out = gpu.sample_gather(step, batch)
+            if idx is None:
+                assert st == B.RP_SKIPPED_BURN_IN
+                continue
+            assert st == 0
+            _assert_batch_equal(out, ref, idx)
+            step += 1
+    _assert_ring_equal(gpu, ref)
