@@ -511,3 +511,39 @@ def test_random_configurations(B, c):
         part = synth.take(rows, at, at + c["appends"])
         at += c["appends"]
         assert pr.step(part, compare=True) == 0
+
+
+def test_paper_shaped_free_running_drift(B, capsys):
+    """100 consecutive steps with no teacher forcing: the GPU (fp32) and the oracle (fp64) each
+    carry their own weights and Adam moments from the same start.  The drift of the weights is
+    reported; it is only loosely bounded, because a ReLU or an argmax that switches on one side
+    first makes the two trajectories part for good (beyond a few hundred steps nothing is pinned)."""
+    oracle.set_threads(16)
+    try:
+        rows = synth.experiences(50_200, 27, 30, 0.005, seed=0)
+        pr = Pair(B, capacity=1_000_000, D=27, H=256, A=30, batch=128, burn_in=50_000, seed=0)
+        pr.append_only(synth.take(rows, 0, 49_999))
+        tr = pr.trainer
+        p = tr.params().astype(np.float64)
+        m, v, t, step = tr.opt_state()
+        m, v = np.asarray(m, np.float64), np.asarray(v, np.float64)
+        curve = {}
+        for k in range(100):
+            part = synth.take(rows, 49_999 + k, 50_000 + k)
+            pr.ref_ring.append(part["s"], part["s_next"], part["a"], part["r"], part["term"])
+            assert tr.step(part["s"], part["s_next"], part["a"], part["r"], part["term"]) == 0
+            idx = pr.ref_ring.sample(pr.seed, step + k, pr.batch)
+            s, sn, a, r, term = pr.ref_ring.gather(idx)
+            ref = oracle.train_step(pr.cfg, p, m, v, t + k, s.astype(np.float64), sn.astype(np.float64),
+                                    a, r, term)
+            p, m, v = ref.params, ref.m, ref.v
+            if k + 1 in (1, 2, 5, 10, 20, 50, 100):
+                got = tr.params().astype(np.float64)
+                curve[k + 1] = float(np.abs(got - p).max() / np.abs(p).max())
+        with capsys.disabled():
+            print("\nfree-running drift, max |w_gpu - w_oracle| / max |w|: " +
+                  ", ".join("step %d: %.2e" % kv for kv in curve.items()))
+        assert curve[1] <= 2e-5
+        assert curve[100] <= 1e-2
+    finally:
+        oracle.set_threads(1)
