@@ -167,7 +167,7 @@ struct EpiPartial {
 // is multiplied.  Such a load writes the wavefront's 64 pieces to consecutive LDS addresses,
 // so LDS rows cannot be padded; instead the 16-byte piece at position c of row r holds piece
 // c ^ swz(r) of that row's slice (the lanes fetch their global pieces in that order), which
-// spreads the MFMA operand reads of 8 consecutive rows over all banks.
+// spreads the MFMA operand reads of 16 consecutive rows over all banks.
 // The contraction may also be split over `splits` workgroups per tile, each taking K / splits
 // consecutive columns and handing its split number to the epilogue.
 // K / splits must be a multiple of BK.  Loads of rows beyond M / N are redirected to the last valid row:
@@ -223,8 +223,10 @@ __device__ __forceinline__ void gemm_nt_block(const GemmArgs& p, const Epi& epi,
 
     const unsigned int tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const unsigned int wn = wave % WGN, wm = wave / WGN;
-    // position of the piece of row r that shares a bank group with piece 0 of row 0
-    auto swz = [](unsigned int r) { return CPR == 8 ? (r & 7u) : ((r >> 1) & 3u); };
+    // LDS has 64 four-byte banks: 16 lanes' 16-byte reads are conflict-free when they fall into 16
+    // different slots of a 256-byte span.  256 / RB rows share such a span; successive groups of
+    // that many rows get their pieces rotated by XOR with the group number.
+    auto swz = [](unsigned int r) { return (r / (256u / RB)) & (CPR - 1u); };
 
     // loader: wavefront w moves row groups w*GA.. of A and w*GB.. of B; a lane's piece lands at
     // LDS position `lane` of the group, so the lane fetches the piece that belongs there
