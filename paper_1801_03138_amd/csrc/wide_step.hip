@@ -617,10 +617,12 @@ __global__ __launch_bounds__(256) void td_dz_kernel(TdArgs p) {
             for (int e = 0; e < 16; ++e) out[e] = h2[e] = h1[e] = 0;
         }
 #pragma unroll
+        // (the four lanes of a row hold k-ranges 16 apart, whose tile rows start in the same bank:
+        // each range gets its columns rotated by a different multiple of 16, undone when read)
         for (int e = 0; e < 16; ++e) {
-            tileT[0][ks + e][r] = out[e];
-            tileT[1][ks + e][r] = h2[e];
-            tileT[2][ks + e][r] = h1[e];
+            tileT[0][ks + e][r ^ ks] = out[e];
+            tileT[1][ks + e][r ^ ks] = h2[e];
+            tileT[2][ks + e][r ^ ks] = h1[e];
         }
     }
     __syncthreads();
@@ -631,7 +633,7 @@ __global__ __launch_bounds__(256) void td_dz_kernel(TdArgs p) {
         bf16_bits* const dst[3] = {p.dZ2T, p.H2T, p.H1T};
 #pragma unroll
         for (int w = 0; w < 3; ++w) {
-            const u32x4* sp = reinterpret_cast<const u32x4*>(&tileT[w][k][rs]);
+            const u32x4* sp = reinterpret_cast<const u32x4*>(&tileT[w][k][rs ^ (k & 48u)]);
             u32x4* dp = reinterpret_cast<u32x4*>(dst[w] + at);
             dp[0] = sp[0];
             dp[1] = sp[1];
