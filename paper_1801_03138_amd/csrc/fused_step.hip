@@ -144,6 +144,7 @@ __device__ __forceinline__ float sum_part(const float* part, unsigned int slices
     return v;
 }
 
+template <bool BOTH>
 __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     extern __shared__ float lds[];
     const unsigned int tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
@@ -158,12 +159,19 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     float* b1s = part + 4 * 8 * kChunk;   // [H]
     float* b2s = b1s + H;                 // [H]
     float* b3s = b2s + H;                 // [Ap]
-    unsigned int* meta = reinterpret_cast<unsigned int*>(b3s + Ap);  // [4][4]
+    float* b1ts = b3s + Ap;               // [H]   the frozen target network's biases
+    float* b2ts = b1ts + H;               // [H]
+    float* b3ts = b2ts + H;               // [Ap]
+    unsigned int* meta = reinterpret_cast<unsigned int*>(b3ts + Ap);  // [4][4]
     float* gs = reinterpret_cast<float*>(meta + 16);                 // [4]
 
     const float* W1 = p.w + p.oW1;
     const float* W2 = p.w + p.oW2;
     const float* W3 = p.w + p.oW3;
+    // Frozen target network: rows 4..7 (the new states) go through its weights instead.  The lane's
+    // registers take the trained network's share of a layer first (rows 0..3) and are refilled
+    // with the target's during those MFMAs.
+    constexpr bool both = BOTH;
     // wide split
     const unsigned int cc = 64u * (wave & 3u) + lane, ks = wave >> 2;
     const unsigned int q1 = Dp >> 2, q2 = H >> 2;   // K quarter of layer 1 / layers 2 and backward
@@ -184,8 +192,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
 
     // The state that follows this step is known up front (the host mirrors it exactly): one
     // thread stores it for the kernels and calls that read it later, off everyone's critical path.
-    const bool target_pass = p.mode == kRowsTargetPass;
-    if (blockIdx.x == 0 && tid == kRowThreads - 1 && !target_pass) {
+    if (blockIdx.x == 0 && tid == kRowThreads - 1) {
         unsigned long long h = head + n;
         if (h >= cap) h -= cap;
         p.g.state->head = h;
@@ -224,7 +231,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     // The last workgroup also writes the new experiences into the ring.  No workgroup reads
     // those slots from the ring in this launch (see above), so this can go out right away and
     // its latency is hidden behind the rest of the kernel.
-    if (blockIdx.x == gridDim.x - 1 && n && !target_pass) {
+    if (blockIdx.x == gridDim.x - 1 && n) {
         const unsigned int rw = p.g.row_bytes >> 2;
         for (unsigned long long e = tid; e < n * rw; e += kRowThreads) {
             const unsigned long long k = e / rw;
@@ -254,10 +261,10 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
             const unsigned int val = gval[pass];
             if (w < D) {
                 Xs[r * ldx + w] = __uint_as_float(val);
-                if (!target_pass) p.X[(size_t)i * Dp + w] = __uint_as_float(val);
+                p.X[(size_t)i * Dp + w] = __uint_as_float(val);
             } else if (w < 2 * D) {
                 Xs[(4 + r) * ldx + w - D] = __uint_as_float(val);
-            } else if (!target_pass) {
+            } else {
                 meta[r * 4 + (w - 2 * D)] = val;
                 if (w == 2 * D) {
                     p.act[i] = (int)val;
@@ -290,54 +297,76 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
 
     // ---- layer 1
     f32x4 acc2[2];
-    mma_cols<2, 16>(acc2, Xs, ldx, ks * q1, q1, w1r);
+    if (!both) {
+        mma_cols<2, 16>(acc2, Xs, ldx, ks * q1, q1, w1r);
+    } else {
+        // the target network's biases travel during the first MFMAs (kept out of the registers
+        // that are scarce while W2 is arriving)
+        const float b1tv = tid < H ? p.wt[p.ob1 + tid] : 0.f;
+        const float b2tv = tid < H ? p.wt[p.ob2 + tid] : 0.f;
+        const float b3tv = tid < Ap ? p.wt[p.ob3 + tid] : 0.f;
+        f32x4 lo[1], hi[1];
+        mma_cols_reload<1, 16>(lo, Xs, ldx, ks * q1, q1, w1r, p.wt + p.oW1, H, cc, ks * q1, q1);
+        mma_cols<1, 16>(hi, Xs + 4 * ldx, ldx, ks * q1, q1, w1r);
+        acc2[0] = lo[0];
+        acc2[1] = hi[0];
+        if (tid < H) {
+            b1ts[tid] = b1tv;
+            b2ts[tid] = b2tv;
+        }
+        if (tid < Ap) b3ts[tid] = b3tv;
+    }
     float w3r[16];   // layer 1's registers are free: request layer 3's weights
     load_cols<16>(w3r, W3, Ap, lane, wave * s3, s3);
     store_part<2>(part, ks, kChunk, cc, acc2);
     lds_barrier();
     for (unsigned int e = tid; e < 8 * H; e += kRowThreads) {
         const unsigned int row = e / H, c = e - row * H;
-        float v = sum_part(part, 4, 8, kChunk, row, c) + b1s[c];
+        float v = sum_part(part, 4, 8, kChunk, row, c) + (both && row >= 4 ? b1ts : b1s)[c];
         v = v > 0.f ? v : 0.f;
         H1s[row * ldh + c] = v;
-        if (row < nrows && !target_pass) p.H1[(size_t)(i0 + row) * H + c] = v;
+        if (row < nrows) p.H1[(size_t)(i0 + row) * H + c] = v;
     }
     lds_barrier();
 
     // ---- layer 2; its registers are then refilled with W2^T (backward) and W3 is requested
-    mma_cols_reload<2, 64>(acc2, H1s, ldh, ks * q2, q2, w2r, p.w2t, H, cc, ks * q2, q2);
+    if (!both) {
+        mma_cols_reload<2, 64>(acc2, H1s, ldh, ks * q2, q2, w2r, p.w2t, H, cc, ks * q2, q2);
+    } else {
+        f32x4 lo[1], hi[1];
+        mma_cols_reload<1, 64>(lo, H1s, ldh, ks * q2, q2, w2r, p.wt + p.oW2, H, cc, ks * q2, q2);
+        mma_cols_reload<1, 64>(hi, H1s + 4 * ldh, ldh, ks * q2, q2, w2r, p.w2t, H, cc, ks * q2, q2);
+        acc2[0] = lo[0];
+        acc2[1] = hi[0];
+    }
     store_part<2>(part, ks, kChunk, cc, acc2);
     lds_barrier();
     for (unsigned int e = tid; e < 8 * H; e += kRowThreads) {
         const unsigned int row = e / H, c = e - row * H;
-        float v = sum_part(part, 4, 8, kChunk, row, c) + b2s[c];
+        float v = sum_part(part, 4, 8, kChunk, row, c) + (both && row >= 4 ? b2ts : b2s)[c];
         v = v > 0.f ? v : 0.f;
         H2s[row * ldh + c] = v;
-        if (row < nrows && !target_pass) p.H2[(size_t)(i0 + row) * H + c] = v;
+        if (row < nrows) p.H2[(size_t)(i0 + row) * H + c] = v;
     }
     lds_barrier();
 
     // ---- layer 3 (narrow split: 16 K slices, columns 0..63)
-    mma_cols<2, 16>(acc2, H2s, ldh, wave * s3, s3, w3r);
+    if (!both) {
+        mma_cols<2, 16>(acc2, H2s, ldh, wave * s3, s3, w3r);
+    } else {
+        f32x4 lo[1], hi[1];
+        mma_cols_reload<1, 16>(lo, H2s, ldh, wave * s3, s3, w3r, p.wt + p.oW3, Ap, lane, wave * s3, s3);
+        mma_cols<1, 16>(hi, H2s + 4 * ldh, ldh, wave * s3, s3, w3r);
+        acc2[0] = lo[0];
+        acc2[1] = hi[0];
+    }
     store_part<2>(part, wave, 64, lane, acc2);
     lds_barrier();
     for (unsigned int e = tid; e < 8 * Ap; e += kRowThreads) {
         const unsigned int row = e / Ap, c = e - row * Ap, r = row & 3u;
-        const float v = sum_part(part, 16, 8, 64, row, c) + b3s[c];
+        const float v = sum_part(part, 16, 8, 64, row, c) + (both && row >= 4 ? b3ts : b3s)[c];
         Qs[row * ldq + c] = v;
-        // Q(s, .) belongs to the trained network's pass, Q(s', .) to the target network's when
-        // there is one
-        const bool mine = row < 4 ? !target_pass : p.mode != kRowsAfterTargetPass;
-        if (r < nrows && mine) p.Q[((size_t)(row < 4 ? 0 : p.B) + i0 + r) * Ap + c] = v;
-    }
-    if (target_pass) return;
-    if (p.mode == kRowsAfterTargetPass) {
-        // Q(s', .) of this workgroup's rows, left in global memory by the target pass
-        lds_barrier();
-        for (unsigned int e = tid; e < nrows * Ap; e += kRowThreads) {
-            const unsigned int r = e / Ap, c = e - r * Ap;
-            Qs[(4 + r) * ldq + c] = p.Q[((size_t)p.B + i0 + r) * Ap + c];
-        }
+        if (r < nrows) p.Q[((size_t)(row < 4 ? 0 : p.B) + i0 + r) * Ap + c] = v;
     }
     lds_barrier();
 
@@ -564,7 +593,7 @@ __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
 
 size_t row_kernel_lds(unsigned int Dp, unsigned int H, unsigned int Ap) {
     const size_t ldx = Dp + kPadK, ldh = H + kPadK, ldq = Ap + kPadK;
-    return (8 * ldx + 8 * ldh * 2 + 8 * ldq + 4 * ldh + 4 * 8 * kChunk + 2 * H + Ap + 16 + 4) *
+    return (8 * ldx + 8 * ldh * 2 + 8 * ldq + 4 * ldh + 4 * 8 * kChunk + 2 * (2 * H + Ap) + 16 + 4) *
            sizeof(float);
 }
 
@@ -583,7 +612,10 @@ bool fused_step_supported(const train_config& cfg, const replay* rp_) {
     return row_kernel_lds(Dp, cfg.hidden, Ap) <= 64 * 1024;
 }
 
-void* fused_rows_func() { return reinterpret_cast<void*>(fused_rows_kernel); }
+void* fused_rows_func(bool target_network) {
+    return target_network ? reinterpret_cast<void*>(fused_rows_kernel<true>)
+                          : reinterpret_cast<void*>(fused_rows_kernel<false>);
+}
 
 hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* batch, hipStream_t st,
                               unsigned int* count) {
@@ -595,7 +627,6 @@ hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* bat
     a.src = src;
     a.batch = batch ? *batch : Payload{nullptr, nullptr, nullptr, nullptr, nullptr};
     a.from_batch = batch ? 1u : 0u;
-    a.mode = t->wt ? kRowsAfterTargetPass : kRowsWholeStep;
     {
         // state before this step, from the host mirrors (train_step has not advanced them yet)
         const unsigned long long cap = r->cfg.capacity, after = r->size + a.n_append;
@@ -607,6 +638,7 @@ hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* bat
     }
     a.ctr = t->ctr;
     a.w = t->w;
+    a.wt = t->wt;
     a.w2t = t->w2t;
     a.B = t->B; a.D = t->cfg.state_dim; a.Dp = t->Dp; a.H = t->H; a.A = t->cfg.num_actions; a.Ap = t->Ap;
     a.oW1 = (unsigned int)t->oW1; a.ob1 = (unsigned int)t->ob1; a.oW2 = (unsigned int)t->oW2;
@@ -620,21 +652,8 @@ hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* bat
     a.act = t->act; a.rew = t->rew; a.term = t->term; a.idx = t->idx;
     const unsigned int blocks = (t->B + kRows - 1) / kRows;
     hipError_t e = hipSuccess;
-    unsigned int n_rows_launches = 1;
-    if (t->wt) {
-        // first pass: Q(s', .) with the frozen target network's weights
-        RowArgs& b = t->row_args_target;
-        b = a;
-        b.w = t->wt;
-        b.mode = kRowsTargetPass;
-        void* targs[] = {&b};
-        e = hipLaunchKernel(fused_rows_func(), dim3(blocks), dim3(kRowThreads), targs,
-                            row_kernel_lds(t->Dp, t->H, t->Ap), st);
-        if (e != hipSuccess) return e;
-        n_rows_launches = 2;
-    }
     void* kargs[] = {&a};
-    e = hipLaunchKernel(fused_rows_func(), dim3(blocks), dim3(kRowThreads), kargs,
+    e = hipLaunchKernel(fused_rows_func(t->wt != nullptr), dim3(blocks), dim3(kRowThreads), kargs,
                         row_kernel_lds(t->Dp, t->H, t->Ap), st);
     if (e != hipSuccess) return e;
 
@@ -666,7 +685,7 @@ hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* bat
     if (e != hipSuccess) return e;
     unsigned int nh = 0;
     e = enqueue_head_update(t, st, &nh);
-    if (count) *count = 1 + n_rows_launches + nh;
+    if (count) *count = 2 + nh;
     return e;
 }
 

@@ -660,11 +660,9 @@ hipError_t find_payload_nodes(trainer* t, hipGraph_t graph, unsigned int want, h
             e = hipGraphKernelNodeGetParams(cur, &np);
             if (e != hipSuccess) return e;
             if (np.func == t->payload_func && found < want) {
-                // with two payload kernels per step the target pass comes first
-                const bool target_pass = t->payload_per_step == 2 && found % 2 == 0;
                 nodes[found] = cur;
                 params[found] = np;
-                params[found].kernelParams = target_pass ? t->payload_kargs_target : t->payload_kargs;
+                params[found].kernelParams = t->payload_kargs;
                 params[found].extra = nullptr;
                 ++found;
             }
@@ -701,11 +699,6 @@ void set_payload_args(trainer* t, const Payload& src, unsigned int k) {
         t->row_args.size_after = (unsigned int)(size + n > cap ? cap : size + n);
         t->row_args.total_after = total + n;
         t->row_args.adam_t_after = t->host_adam_t + k + 1;
-        if (t->wt) {
-            t->row_args_target = t->row_args;
-            t->row_args_target.w = t->wt;
-            t->row_args_target.mode = kRowsTargetPass;
-        }
     } else {
         t->append_args.src = src;
         t->append_args.pos = RingPos{head, size, total};
@@ -878,13 +871,11 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
         }
         t->pin_dev = static_cast<unsigned char*>(dp);
     }
-    t->payload_func = t->fused  ? rp::fused_rows_func()
+    t->payload_func = t->fused  ? rp::fused_rows_func(t->wt != nullptr)
                       : t->wide ? rp::append_gather_func(rp_->geom)
                                 : rp::append_pair_func(rp_->geom);
     t->payload_kargs[0] = t->fused ? static_cast<void*>(&t->row_args) : static_cast<void*>(&t->append_args);
-    t->payload_kargs_target[0] = &t->row_args_target;
-    t->payload_per_step = t->fused && t->wt ? 2u : 1u;
-    t->payload_node[0] = t->payload_node[1] = nullptr;
+    t->payload_node[0] = nullptr;
     t->multi_graph = nullptr;
     t->multi_exec = nullptr;
 
@@ -902,7 +893,7 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
             if (ek != hipSuccess) e = ek;
         }
         if (e == hipSuccess && rp::has_payload_node(t))
-            e = rp::find_payload_nodes(t, t->graph, t->payload_per_step, t->payload_node, t->payload_np);
+            e = rp::find_payload_nodes(t, t->graph, 1, t->payload_node, t->payload_np);
         if (e == hipSuccess) e = hipGraphInstantiate(&t->graph_exec, t->graph, nullptr, nullptr, 0);
         // the same for kGraphSteps steps in a row
         if (e == hipSuccess) e = hipStreamBeginCapture(t->capture_stream, hipStreamCaptureModeThreadLocal);
@@ -914,7 +905,7 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
             if (ek != hipSuccess) e = ek;
         }
         if (e == hipSuccess && rp::has_payload_node(t))
-            e = rp::find_payload_nodes(t, t->multi_graph, rp::kGraphSteps * t->payload_per_step,
+            e = rp::find_payload_nodes(t, t->multi_graph, rp::kGraphSteps,
                                        t->multi_node, t->multi_np);
         if (e == hipSuccess) e = hipGraphInstantiate(&t->multi_exec, t->multi_graph, nullptr, nullptr, 0);
         if (e != hipSuccess) {
@@ -990,9 +981,8 @@ rp_status train_step(trainer_t* t, const void* s, const void* s_next, const int3
     } else if (t->graph_exec) {
         if (t->payload_node[0]) {
             rp::set_payload_args(t, src, 0);
-            for (unsigned int j = 0; j < t->payload_per_step; ++j)
-                RP_CHECK_HIP(hipGraphExecKernelNodeSetParams(t->graph_exec, t->payload_node[j],
-                                                             &t->payload_np[j]));
+            RP_CHECK_HIP(hipGraphExecKernelNodeSetParams(t->graph_exec, t->payload_node[0],
+                                                         &t->payload_np[0]));
         }
         RP_CHECK_HIP(hipGraphLaunch(t->graph_exec, st));
     } else {
@@ -1034,14 +1024,8 @@ rp_status train_step_batch(trainer_t* t, const void* s, const void* s_next, cons
         t->row_args.size_after = (unsigned int)rpl->size;
         t->row_args.total_after = rpl->total;
         t->row_args.adam_t_after = t->host_adam_t + 1;
-        if (t->wt) {
-            t->row_args_target = t->row_args;
-            t->row_args_target.w = t->wt;
-            t->row_args_target.mode = rp::kRowsTargetPass;
-        }
-        for (unsigned int j = 0; j < t->payload_per_step; ++j)
-            RP_CHECK_HIP(hipGraphExecKernelNodeSetParams(t->graph_exec, t->payload_node[j],
-                                                         &t->payload_np[j]));
+        RP_CHECK_HIP(hipGraphExecKernelNodeSetParams(t->graph_exec, t->payload_node[0],
+                                                     &t->payload_np[0]));
         RP_CHECK_HIP(hipGraphLaunch(t->graph_exec, st));
     } else {
         RP_CHECK_HIP(rp::enqueue_batch_step(t, batch, st));
@@ -1075,11 +1059,8 @@ rp_status train_steps(trainer_t* t, uint64_t count, const void* s, const void* s
                                     term + oj}
                       : rp::Payload{nullptr, nullptr, nullptr, nullptr, nullptr};
                 rp::set_payload_args(t, src, j);
-                for (unsigned int q = 0; q < t->payload_per_step; ++q) {
-                    const unsigned int node = j * t->payload_per_step + q;
-                    RP_CHECK_HIP(hipGraphExecKernelNodeSetParams(t->multi_exec, t->multi_node[node],
-                                                                 &t->multi_np[node]));
-                }
+                RP_CHECK_HIP(hipGraphExecKernelNodeSetParams(t->multi_exec, t->multi_node[j],
+                                                             &t->multi_np[j]));
             }
             RP_CHECK_HIP(hipGraphLaunch(t->multi_exec, static_cast<hipStream_t>(hip_stream)));
             const uint64_t cap = rpl->cfg.capacity;

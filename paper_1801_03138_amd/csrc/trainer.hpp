@@ -52,7 +52,6 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
-enum { kRowsWholeStep = 0, kRowsTargetPass = 1, kRowsAfterTargetPass = 2 };
 
 // Argument block of the fused row kernel.
 struct RowArgs {
@@ -62,10 +61,6 @@ struct RowArgs {
     Payload src;          // this step's new experiences
     Payload batch;        // from_batch: the batch itself, given by the caller instead of sampled
     unsigned int from_batch;
-    // Frozen target network: the row kernel runs twice per step.  kRowsTargetPass: `w` is the
-    // target network; forward only, leaves Q(s', .) in Q and touches nothing else.
-    // kRowsAfterTargetPass: the normal pass, taking Q(s', .) from Q instead of its own forward.
-    unsigned int mode;
     // ring and trainer state before this step, from the host mirror (set before every launch,
     // so the kernel can start drawing without a dependent load)
     unsigned long long head, step;
@@ -73,6 +68,7 @@ struct RowArgs {
     unsigned long long total_after, adam_t_after;   // experiences ever added / Adam steps, after this step
     TrainCounters* ctr;
     const float* w;       // padded parameters
+    const float* wt;      // the frozen target network's (Q(s', .) is computed with them), or null
     const float* w2t;     // W2 transposed
     unsigned int B, D, Dp, H, A, Ap;
     unsigned int oW1, ob1, oW2, ob2, oW3, ob3;
@@ -147,20 +143,17 @@ struct trainer {
     // kernel of the layered step): host copy of its argument block, and its node in the graph,
     // whose argument is replaced before every launch.
     rp::RowArgs row_args;
-    rp::RowArgs row_args_target;     // fused step with a frozen target network: its first pass
     rp::AppendGatherArgs append_args;   // the append kernel reads its leading AppendArgs part
     void* payload_func;
     void* payload_kargs[1];          // -> row_args / append_args
-    void* payload_kargs_target[1];   // -> row_args_target
-    unsigned int payload_per_step;   // payload nodes per recorded step: 1, or 2 with the target pass first
-    hipGraphNode_t payload_node[2];
-    hipKernelNodeParams payload_np[2];
+    hipGraphNode_t payload_node[1];
+    hipKernelNodeParams payload_np[1];
     // kGraphSteps consecutive steps recorded as one graph, for train_steps: one launch (and one
     // launch gap on the GPU) per kGraphSteps steps; each step's payload kernel has its own node.
     hipGraph_t multi_graph;
     hipGraphExec_t multi_exec;
-    hipGraphNode_t multi_node[2 * rp::kGraphSteps];
-    hipKernelNodeParams multi_np[2 * rp::kGraphSteps];
+    hipGraphNode_t multi_node[rp::kGraphSteps];
+    hipKernelNodeParams multi_np[rp::kGraphSteps];
     // Host-sourced payloads are copied into a ring of pinned, device-mapped host slots that the
     // kernel reads directly; an event per group of slots tells when a group may be reused.
     unsigned char* pin_host;
@@ -180,7 +173,7 @@ bool fused_step_supported(const train_config& cfg, const replay* rp_);
 // With `batch` the step trains on the caller's batch: nothing is appended or sampled.
 hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* batch, hipStream_t st,
                               unsigned int* count);
-void* fused_rows_func();
+void* fused_rows_func(bool target_network);   // the row kernel, without / with a frozen target network
 // Dueling head: turn the gradient of the equivalent plain output layer (in g) into the head's
 // update and refresh that layer (and its bf16 / target copies).  No-op for a plain head.
 hipError_t enqueue_head_update(trainer* t, hipStream_t st, unsigned int* count);

@@ -401,7 +401,7 @@ def test_in_ram_replay_trains_on_the_same_batches_as_the_device_replay(B):
 
 
 @pytest.mark.parametrize("dtype,H,batch,layered,kernels", [
-    ("f32", 64, 50, False, 3), ("f32", 64, 50, True, 18), ("f32", 256, 128, False, 3),
+    ("f32", 64, 50, False, 2), ("f32", 64, 50, True, 18), ("f32", 256, 128, False, 2),
     ("bf16", 128, 200, False, 11), ("bf16", 64, 256, False, 8), ("bf16", 128, 96, True, 18)])
 def test_frozen_target_network(B, dtype, H, batch, layered, kernels):
     """Q(s', .) from a frozen copy of the weights, synced every 7th update (Deep Q-Network Model):
@@ -445,7 +445,7 @@ def test_train_step_with_batches_without_duplicates(B, dtype, H, layered):
 
 
 @pytest.mark.parametrize("dtype,H,batch,layered,target_sync,kernels", [
-    ("f32", 64, 50, False, 0, 3), ("f32", 64, 50, True, 0, 16), ("f32", 128, 33, False, 5, 4),
+    ("f32", 64, 50, False, 0, 3), ("f32", 64, 50, True, 0, 16), ("f32", 128, 33, False, 5, 3),
     ("f32", 128, 33, True, 5, 19),
     ("bf16", 128, 200, False, 0, 9), ("bf16", 64, 256, False, 5, 9), ("bf16", 128, 96, True, 0, 16)])
 def test_dueling_head(B, dtype, H, batch, layered, target_sync, kernels):
