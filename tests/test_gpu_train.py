@@ -211,15 +211,16 @@ def test_paper_shaped_config_sampled_steps(B):
     assert all(np.array_equal(x.view(np.uint8), y.view(np.uint8)) for x, y in zip(g, o))
 
 
-@pytest.mark.parametrize("layered", [False, True])
-def test_many_steps_in_flight_with_device_payload(B, layered):
+@pytest.mark.parametrize("dtype,layered", [("f32", False), ("f32", True), ("bf16", False)])
+def test_many_steps_in_flight_with_device_payload(B, dtype, layered):
     """train_steps with device arrays: 3000 steps queued without a sync, 2 appends each, into a
-    ring that wraps; the ring must end up exactly as the oracle's and the counters must add up."""
+    ring that wraps; the ring must end up exactly as the oracle's and the counters must add up.
+    (Two-kernel fp32 step, layered step, and the MFMA step whose first kernel appends and gathers.)"""
     n_steps, per = 3000, 2
-    rows = synth.experiences(n_steps * per, 27, 30, 0.05, seed=21)
+    rows = synth.experiences(n_steps * per, 27, 30, 0.05, seed=21, state_dtype=dtype)
     pr = Pair(B, capacity=4096, D=27, H=64, A=30, batch=64, burn_in=100, seed=5, appends=per,
-              layered=layered)
-    d = {k: torch.from_numpy(v).cuda() for k, v in rows.items()}
+              layered=layered, dtype=dtype)
+    d = {k: torch.from_numpy(v.view(np.int16) if v.dtype == np.uint16 else v).cuda() for k, v in rows.items()}
     done = pr.trainer.steps(n_steps, d["s"], d["s_next"], d["a"], d["r"], d["term"])
     for lo in range(0, n_steps * per, 4096):
         part = synth.take(rows, lo, min(lo + 4096, n_steps * per))
@@ -230,7 +231,7 @@ def test_many_steps_in_flight_with_device_payload(B, layered):
     g, o = pr.gpu_ring.read_rows(0, 4096), pr.ref_ring.read(0, 4096)
     assert all(np.array_equal(x.view(np.uint8), y.view(np.uint8)) for x, y in zip(g, o))
     # and the next step still matches the oracle
-    extra = synth.experiences(per, 27, 30, 0.05, seed=22)
+    extra = synth.experiences(per, 27, 30, 0.05, seed=22, state_dtype=dtype)
     assert pr.step(extra, compare=True) == 0
 
 
