@@ -361,7 +361,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=500)
     ap.add_argument("--legs", default="p,pfull,phost,pmodel,inram,gather,append,copy,large,wide,cpu")
     ap.add_argument("--gather-reps", type=int, default=1000)
-    ap.add_argument("--wide-steps", type=int, default=200)
+    ap.add_argument("--wide-steps", type=int, default=2000)
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
     args = ap.parse_args()
     if args.gpus != 1:
