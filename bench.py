@@ -365,7 +365,7 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only; --gpus %d is not supported "
+        sys.exit("bench.py: this library runs on one GPU only; --gpus %d is not supported "
                  "(no collectives or multi-GPU sharding are part of it)" % args.gpus)
     legs = set(args.legs.split(","))
 
