@@ -721,7 +721,7 @@ __device__ __forceinline__ void small_opt_block(const SmallOptArgs& p, unsigned 
 
 // The square layer's update from the K-split partial products of [dW ; db] (row R = bias):
 //   part[z][m][n], m <= R, n < N; the gradient is the sum over z, splits added in order.
-// A workgroup owns a 64 x 64 tile of W: a thread takes four consecutive columns of a row
+// A workgroup owns a kSqRows x 64 tile of W: a thread takes four consecutive columns of a row
 // (16-byte accesses to the partials and to the fp32 weight, gradient and moments), writes the
 // new weights' bf16 copy in the same orientation and parks it in LDS, from where the
 // transposed copy (and the target network's, when a sync is due) leaves as 128-byte runs.
@@ -759,22 +759,25 @@ __device__ __forceinline__ f32x4 opt_update4(const OptState& o, size_t k, const 
     return w;
 }
 
+constexpr unsigned int kSqRows = 32;   // rows of W per workgroup of the square layer's update (columns: 64)
+
 __device__ __forceinline__ void square_opt_block(const SquareOptArgs& p, unsigned int block_x, unsigned int block_y) {
     constexpr unsigned int TS = 68;                       // bf16 per parked row (64 + padding)
-    __shared__ bf16_bits tile[64 * TS];
+    __shared__ bf16_bits tile[kSqRows * TS];
     const unsigned int tid = threadIdx.x, c4 = (tid & 15u) * 4u, r0 = tid >> 4;
-    const unsigned int m0 = block_y * 64u, n0 = block_x * 64u;
+    const unsigned int m0 = block_y * kSqRows, n0 = block_x * 64u;
     const OptStep st = opt_step(p.o);
     const size_t zs = (size_t)(p.R + 1u) * p.N;           // one split's partials
-    f32x4 g[4];
+    constexpr unsigned int Q = kSqRows / 16u;
+    f32x4 g[Q];
 #pragma unroll
-    for (unsigned int q = 0; q < 4; ++q) {
+    for (unsigned int q = 0; q < Q; ++q) {
         const float* src = p.part + (size_t)(m0 + q * 16u + r0) * p.N + n0 + c4;
         g[q] = *reinterpret_cast<const f32x4*>(src);
         for (unsigned int z = 1; z < p.splits; ++z) g[q] += *reinterpret_cast<const f32x4*>(src + z * zs);
     }
 #pragma unroll
-    for (unsigned int q = 0; q < 4; ++q) {
+    for (unsigned int q = 0; q < Q; ++q) {
         const unsigned int r = q * 16u + r0;
         const size_t at = (size_t)(m0 + r) * p.N + n0 + c4;
         const f32x4 w = opt_update4(p.o, p.w_off + at, g[q], st);
@@ -794,11 +797,12 @@ __device__ __forceinline__ void square_opt_block(const SquareOptArgs& p, unsigne
         opt_update4(p.o, p.b_off + n0 + c4, gb, st);
     }
     __syncthreads();
-    // transposed copy: a wavefront writes two rows of 64 (one column of the tile each) per pass
-    const unsigned int mp = (tid & 31u) * 2u;
+    // transposed copy: kSqRows / 2 lanes write one column of the tile as pairs of rows
+    constexpr unsigned int LPC = kSqRows / 2u, CPP = 256u / LPC;   // lanes per column, columns per pass
+    const unsigned int mp = (tid % LPC) * 2u;
 #pragma unroll
-    for (unsigned int pass = 0; pass < 8; ++pass) {
-        const unsigned int n = pass * 8u + (tid >> 5);
+    for (unsigned int pass = 0; pass < 64u / CPP; ++pass) {
+        const unsigned int n = pass * CPP + tid / LPC;
         const unsigned int pair = (unsigned int)tile[mp * TS + n] | ((unsigned int)tile[(mp + 1u) * TS + n] << 16);
         const size_t at = (size_t)(n0 + n) * p.R + m0 + mp;
         *reinterpret_cast<unsigned int*>(p.wbT + at) = pair;
@@ -806,10 +810,10 @@ __device__ __forceinline__ void square_opt_block(const SquareOptArgs& p, unsigne
     }
 }
 
-// One launch updates all three layers: the first (N / 64)^2 workgroups take the tiles of the square
-// layer, the rest the two narrow layers.
+// One launch updates all three layers: the first (N / 64) (R / kSqRows) workgroups take the tiles
+// of the square layer, the rest the two narrow layers.
 __global__ __launch_bounds__(256) void opt_kernel(SquareOptArgs sq, SmallOptArgs sm) {
-    const unsigned int tiles_n = sq.N / 64u, n_square = tiles_n * (sq.R / 64u);
+    const unsigned int tiles_n = sq.N / 64u, n_square = tiles_n * (sq.R / kSqRows);
     if (blockIdx.x < n_square)
         square_opt_block(sq, blockIdx.x % tiles_n, blockIdx.x / tiles_n);
     else
@@ -1035,7 +1039,7 @@ hipError_t enqueue_wide_step(trainer* t, hipStream_t st, unsigned int* count, bo
         a.ctr = t->ctr; a.lossi = t->lossi;
         a.out_grad_only = t->dueling ? 1u : 0u;
         const unsigned int elems = (H + 1) * Ap + H * (D + 1);
-        hipLaunchKernelGGL(opt_kernel, dim3((H / 64) * (H / 64) + (elems + 255) / 256), dim3(256), 0, st, q, a);
+        hipLaunchKernelGGL(opt_kernel, dim3((H / 64) * (H / kSqRows) + (elems + 255) / 256), dim3(256), 0, st, q, a);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         ++n;
