@@ -958,14 +958,14 @@ hipError_t enqueue_wide_step(trainer* t, hipStream_t st, unsigned int* count, bo
         a.A = H2; a.lda = H; a.Bt = w.W3T; a.ldb = H; a.M = rows; a.N = Ap; a.K = H;
         a.bias = t->w + t->ob3; a.out = t->Q; a.ldo = Ap;
         a.Bt_hi = tgt ? w.W3T_t : w.W3T; a.bias_hi = tgt ? b3t : a.bias; a.m_split = tgt ? B : ~0u;
-        hipLaunchKernelGGL(skinny_nt_kernel<4>, dim3((rows + 31) / 32, Ap / 32), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(skinny_nt_kernel<8>, dim3((rows + 31) / 32, Ap / 32), dim3(512), 0, st, a);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         ++n;
         if (!one_launch) {
             a.A = H2 + (size_t)B * H; a.Bt = w.W3T_t; a.bias = b3t; a.out = t->Q + (size_t)B * Ap;
             a.M = B; a.Bt_hi = a.Bt; a.bias_hi = a.bias; a.m_split = ~0u;
-            hipLaunchKernelGGL(skinny_nt_kernel<4>, dim3((B + 31) / 32, Ap / 32), dim3(256), 0, st, a);
+            hipLaunchKernelGGL(skinny_nt_kernel<8>, dim3((B + 31) / 32, Ap / 32), dim3(512), 0, st, a);
             e = hipGetLastError();
         }
     }
