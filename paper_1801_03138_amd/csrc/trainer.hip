@@ -727,6 +727,47 @@ hipError_t enqueue_head_update(trainer* t, hipStream_t st, unsigned int* count) 
     return hipGetLastError();
 }
 
+// Host-sourced payloads: the experiences of one step are copied into the next pinned,
+// device-mapped slot, which the payload kernel then reads in place over the host link.  Slots
+// are reused in a ring; one event per group of kPinGroup slots tells when the kernels that read
+// the group have finished.  stage_host_payload fills slot pin_next + ahead and returns the
+// device view of it; commit_host_slots is called after the launch(es) that read `count` slots.
+hipError_t stage_host_payload(trainer* t, unsigned int ahead, uint64_t n, const void* s,
+                              const void* s_next, const int32_t* a, const float* r,
+                              const uint8_t* term, Payload* out) {
+    const unsigned int slot = (unsigned int)((t->pin_next + ahead) % kPinSlots);
+    const unsigned int grp = slot / kPinGroup;
+    if (slot % kPinGroup == 0 && t->pin_event_live[grp]) {
+        hipError_t e = hipEventSynchronize(t->pin_event[grp]);
+        if (e != hipSuccess) return e;
+    }
+    const size_t sb = t->rp_->geom.state_bytes, base = (size_t)slot * t->pin_slot_bytes;
+    unsigned char* h = t->pin_host + base;
+    memcpy(h, s, n * sb);
+    memcpy(h + t->pin_off_s_next, s_next, n * sb);
+    memcpy(h + t->pin_off_a, a, n * 4);
+    memcpy(h + t->pin_off_r, r, n * 4);
+    memcpy(h + t->pin_off_term, term, n);
+    const unsigned char* d = t->pin_dev + base;
+    *out = Payload{d, d + t->pin_off_s_next, reinterpret_cast<const int*>(d + t->pin_off_a),
+                   reinterpret_cast<const float*>(d + t->pin_off_r), d + t->pin_off_term};
+    return hipSuccess;
+}
+
+hipError_t commit_host_slots(trainer* t, unsigned int count, hipStream_t st) {
+    for (unsigned int c = 0; c < count; ++c) {
+        const unsigned int slot = (unsigned int)(t->pin_next % kPinSlots);
+        if (slot % kPinGroup == kPinGroup - 1) {
+            const unsigned int grp = slot / kPinGroup;
+            hipError_t e = hipEventRecord(t->pin_event[grp], st);
+            if (e != hipSuccess) return e;
+            t->pin_event_live[grp] = true;
+        }
+        t->pin_next += 1;
+    }
+    return hipSuccess;
+}
+
 }  // namespace rp
 
 extern "C" {
@@ -945,30 +986,14 @@ rp_status train_step(trainer_t* t, const void* s, const void* s_next, const int3
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const uint64_t n = t->cfg.appends_per_step;
     rp::Payload src{nullptr, nullptr, nullptr, nullptr, nullptr};
-    unsigned int slot = 0;
     const bool host_src = n && !src_is_device;
     if (n) {
         RP_REQUIRE(s && s_next && a && r && term, "train_step: null field array for the append");
-        if (src_is_device) {
+        if (src_is_device)
             src = rp::Payload{static_cast<const unsigned char*>(s), static_cast<const unsigned char*>(s_next),
                               a, r, term};
-        } else {
-            // copy into the next pinned slot; the kernel reads it in place over the host link
-            slot = (unsigned int)(t->pin_next % rp::kPinSlots);
-            const unsigned int grp = slot / rp::kPinGroup;
-            if (slot % rp::kPinGroup == 0 && t->pin_event_live[grp])
-                RP_CHECK_HIP(hipEventSynchronize(t->pin_event[grp]));
-            const size_t sb = rpl->geom.state_bytes, base = (size_t)slot * t->pin_slot_bytes;
-            unsigned char* h = t->pin_host + base;
-            memcpy(h, s, n * sb);
-            memcpy(h + t->pin_off_s_next, s_next, n * sb);
-            memcpy(h + t->pin_off_a, a, n * 4);
-            memcpy(h + t->pin_off_r, r, n * 4);
-            memcpy(h + t->pin_off_term, term, n);
-            const unsigned char* d = t->pin_dev + base;
-            src = rp::Payload{d, d + t->pin_off_s_next, reinterpret_cast<const int*>(d + t->pin_off_a),
-                              reinterpret_cast<const float*>(d + t->pin_off_r), d + t->pin_off_term};
-        }
+        else
+            RP_CHECK_HIP(rp::stage_host_payload(t, 0, n, s, s_next, a, r, term, &src));
     }
     const uint64_t total_after = rpl->total + n;
     const uint64_t size_after = rpl->size + n > rpl->cfg.capacity ? rpl->cfg.capacity : rpl->size + n;
@@ -988,14 +1013,7 @@ rp_status train_step(trainer_t* t, const void* s, const void* s_next, const int3
     } else {
         RP_CHECK_HIP(rp::enqueue_append_and_step(t, src, st, nullptr));
     }
-    if (host_src) {
-        if (slot % rp::kPinGroup == rp::kPinGroup - 1) {
-            const unsigned int grp = slot / rp::kPinGroup;
-            RP_CHECK_HIP(hipEventRecord(t->pin_event[grp], st));
-            t->pin_event_live[grp] = true;
-        }
-        t->pin_next += 1;
-    }
+    if (host_src) RP_CHECK_HIP(rp::commit_host_slots(t, 1, st));
     rpl->total = total_after;
     rpl->size = size_after;
     rpl->head = (rpl->head + n) % rpl->cfg.capacity;
@@ -1046,23 +1064,28 @@ rp_status train_steps(trainer_t* t, uint64_t count, const void* s, const void* s
     uint64_t done = 0;
     for (uint64_t k = 0; k < count;) {
         const uint64_t o = k * n;
-        // kGraphSteps steps in one graph launch when all of them train and their new
-        // experiences are already in device memory
-        if (t->multi_exec && count - k >= K && (n == 0 || src_is_device) &&
+        // kGraphSteps steps in one graph launch when all of them train (new experiences in host
+        // memory go through one pinned slot per step)
+        const bool host_src = n && !src_is_device;
+        if (t->multi_exec && count - k >= K && (!host_src || rp::has_payload_node(t)) &&
             rpl->total + n >= rpl->cfg.burn_in &&
             rpl->size + n >= (rpl->cfg.sampling == RP_DISTINCT ? t->cfg.batch : 1u)) {
             for (unsigned int j = 0; j < K && rp::has_payload_node(t); ++j) {
                 const uint64_t oj = o + j * n;
-                const rp::Payload src =
+                rp::Payload src =
                     n ? rp::Payload{static_cast<const unsigned char*>(s) + oj * sb,
                                     static_cast<const unsigned char*>(s_next) + oj * sb, a + oj, r + oj,
                                     term + oj}
                       : rp::Payload{nullptr, nullptr, nullptr, nullptr, nullptr};
+                if (host_src)
+                    RP_CHECK_HIP(rp::stage_host_payload(t, j, n, src.s, src.s_next, src.a, src.r, src.term, &src));
                 rp::set_payload_args(t, src, j);
                 RP_CHECK_HIP(hipGraphExecKernelNodeSetParams(t->multi_exec, t->multi_node[j],
                                                              &t->multi_np[j]));
             }
             RP_CHECK_HIP(hipGraphLaunch(t->multi_exec, static_cast<hipStream_t>(hip_stream)));
+            if (host_src)
+                RP_CHECK_HIP(rp::commit_host_slots(t, (unsigned int)K, static_cast<hipStream_t>(hip_stream)));
             const uint64_t cap = rpl->cfg.capacity;
             rpl->total += K * n;
             rpl->size = rpl->size + K * n > cap ? cap : rpl->size + K * n;

@@ -211,16 +211,21 @@ def test_paper_shaped_config_sampled_steps(B):
     assert all(np.array_equal(x.view(np.uint8), y.view(np.uint8)) for x, y in zip(g, o))
 
 
-@pytest.mark.parametrize("dtype,layered", [("f32", False), ("f32", True), ("bf16", False)])
-def test_many_steps_in_flight_with_device_payload(B, dtype, layered):
-    """train_steps with device arrays: 3000 steps queued without a sync, 2 appends each, into a
-    ring that wraps; the ring must end up exactly as the oracle's and the counters must add up.
-    (Two-kernel fp32 step, layered step, and the MFMA step whose first kernel appends and gathers.)"""
+@pytest.mark.parametrize("dtype,layered,device_src", [("f32", False, True), ("f32", True, True),
+                                                      ("bf16", False, True), ("f32", False, False),
+                                                      ("bf16", False, False), ("f32", True, False)])
+def test_many_steps_in_flight(B, dtype, layered, device_src):
+    """train_steps with device or host arrays: 3000 steps queued without a sync, 2 appends each,
+    into a ring that wraps; the ring must end up exactly as the oracle's and the counters must add
+    up.  (Two-kernel fp32 step, layered step, and the MFMA step whose first kernel appends and
+    gathers; host arrays travel through the ring of pinned slots, eight steps per graph launch.)"""
     n_steps, per = 3000, 2
     rows = synth.experiences(n_steps * per, 27, 30, 0.05, seed=21, state_dtype=dtype)
     pr = Pair(B, capacity=4096, D=27, H=64, A=30, batch=64, burn_in=100, seed=5, appends=per,
               layered=layered, dtype=dtype)
-    d = {k: torch.from_numpy(v.view(np.int16) if v.dtype == np.uint16 else v).cuda() for k, v in rows.items()}
+    d = rows
+    if device_src:
+        d = {k: torch.from_numpy(v.view(np.int16) if v.dtype == np.uint16 else v).cuda() for k, v in rows.items()}
     done = pr.trainer.steps(n_steps, d["s"], d["s_next"], d["a"], d["r"], d["term"])
     for lo in range(0, n_steps * per, 4096):
         part = synth.take(rows, lo, min(lo + 4096, n_steps * per))
