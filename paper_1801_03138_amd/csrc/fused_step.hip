@@ -65,10 +65,19 @@ template <int NR>
 __device__ __forceinline__ void load_cols(float (&wr)[NR], const float* __restrict__ W,
                                           unsigned int N, unsigned int col, unsigned int kbeg,
                                           unsigned int kcount) {
-    const bool active = col < N;
-    const float* wp = W + (size_t)kbeg * N + col;
+    // kbeg and kcount are the same for the whole wavefront: the row base stays in scalar
+    // registers and every load is unconditional.  A lane past the matrix re-reads its last
+    // column and rows past kcount re-read the last row: valid memory, finite values, and the
+    // products never use them (mma_cols skips k >= kcount; columns >= N are never summed).
+    const unsigned int kb = __builtin_amdgcn_readfirstlane(kbeg);
+    const unsigned int kc = __builtin_amdgcn_readfirstlane(kcount);
+    const unsigned int c = col < N ? col : N - 1u;
+    const float* row = W + (size_t)kb * N;
 #pragma unroll
-    for (int u = 0; u < NR; ++u) wr[u] = (active && (unsigned int)u < kcount) ? wp[(size_t)u * N] : 0.f;
+    for (int u = 0; u < NR; ++u) {
+        const unsigned int uu = (unsigned int)u < kc ? (unsigned int)u : kc - 1u;
+        wr[u] = row[(size_t)uu * N + c];
+    }
 }
 
 // acc[mg][v] += sum_{u < kcount} act[mg*4 + v][kbeg + u] * wr[u]   (kcount a multiple of 4)
@@ -104,8 +113,11 @@ __device__ __forceinline__ void mma_cols_reload(f32x4 (&acc)[MG], const float* a
                                                 unsigned int col_n, unsigned int kbeg_n,
                                                 unsigned int kcount_n) {
     const float* ap = act + (threadIdx.x & 3u) * ldk + kbeg;
-    const bool active_n = col_n < Nn;
-    const float* wp = Wn + (size_t)kbeg_n * Nn + col_n;
+    // (unconditional loads from a scalar row base, as in load_cols)
+    const unsigned int kbn = __builtin_amdgcn_readfirstlane(kbeg_n);
+    const unsigned int kcn = __builtin_amdgcn_readfirstlane(kcount_n);
+    const unsigned int cn = col_n < Nn ? col_n : Nn - 1u;
+    const float* row_n = Wn + (size_t)kbn * Nn;
 #pragma unroll
     for (int mg = 0; mg < MG; ++mg) acc[mg] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -120,8 +132,10 @@ __device__ __forceinline__ void mma_cols_reload(f32x4 (&acc)[MG], const float* a
             }
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
-            wr[u4 + u] = (active_n && (unsigned int)(u4 + u) < kcount_n) ? wp[(size_t)(u4 + u) * Nn] : 0.f;
+        for (int u = 0; u < 4; ++u) {
+            const unsigned int uu = (unsigned int)(u4 + u) < kcn ? (unsigned int)(u4 + u) : kcn - 1u;
+            wr[u4 + u] = row_n[(size_t)uu * Nn + cn];
+        }
     }
 }
 
