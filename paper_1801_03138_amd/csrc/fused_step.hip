@@ -22,6 +22,7 @@ constexpr unsigned int kThreads = kTrainThreads;   // weight kernel
 constexpr unsigned int kRowThreads = 1024;         // row kernel: 16 wavefronts
 constexpr unsigned int kRows = 4;          // experiences per workgroup of the row kernel
 constexpr unsigned int kChunk = 256;       // output columns the workgroup covers per pass
+constexpr size_t kRowLdsMax = 160 * 1024;  // dynamic LDS the row kernel may ask for (all of a CU's)
 constexpr unsigned int kPadK = 4;          // LDS row padding (floats) against bank conflicts
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -33,6 +34,20 @@ __device__ __forceinline__ void lds_barrier() {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+
+// A kernel's arguments arrive through the scalar cache, one 64-byte line per miss, and a miss
+// costs a few hundred nanoseconds.  Touching every line of the argument block at once, first
+// thing, turns a chain of such misses (one per group of fields, as the code reaches them)
+// into a single wait.
+template <class Args>
+__device__ __forceinline__ void touch_kernel_args() {
+    const __attribute__((address_space(4))) unsigned int* ka =
+        (const __attribute__((address_space(4))) unsigned int*)__builtin_amdgcn_kernarg_segment_ptr();
+    unsigned int seen = 0;
+#pragma unroll
+    for (unsigned int i = 0; i < sizeof(Args) / 4; i += 16) seen |= ka[i];
+    asm volatile("" ::"s"(seen));
+}
 
 // One 32-bit word of the packed row of experience k of a structure-of-arrays payload.
 __device__ __forceinline__ unsigned int payload_word(const Payload& src, unsigned int D,
@@ -58,25 +73,51 @@ __device__ __forceinline__ unsigned int staged_word(const RowArgs& p, unsigned l
 // the matching mma_* consumes it.  A lane owns one output column and the MFMA takes the
 // activations of four rows as its broadcast A operand.
 //
-// "wide" split (N up to 256): wavefront w covers columns 64*(w&3).. and the K quarter w>>2.
-// "narrow" split (N up to 64): every wavefront covers columns 0..63 and K sixteenth w.
+// "wide" split (N up to 256): a lane owns four adjacent columns, every wavefront covers columns
+// 0..255 and K sixteenth w; one load fetches a lane's four columns of one row (16 bytes), the
+// widest and, measured, the fastest way to bring a matrix into a compute unit's registers.
+// "narrow" split (N up to 64): a lane owns one column, every wavefront covers columns 0..63
+// and K sixteenth w.
 // ----------------------------------------------------------------------------------------
+typedef const __attribute__((address_space(1))) char* gbytes;   // global memory, byte-addressed
+
 template <int NR>
 __device__ __forceinline__ void load_cols(float (&wr)[NR], const float* __restrict__ W,
                                           unsigned int N, unsigned int col, unsigned int kbeg,
                                           unsigned int kcount) {
-    // kbeg and kcount are the same for the whole wavefront: the row base stays in scalar
-    // registers and every load is unconditional.  A lane past the matrix re-reads its last
-    // column and rows past kcount re-read the last row: valid memory, finite values, and the
-    // products never use them (mma_cols skips k >= kcount; columns >= N are never summed).
+    // kbeg and kcount are the same for the whole wavefront: the address of a row is kept in
+    // scalar registers (the empty asm pins it there), the lane adds its 32-bit column offset,
+    // and every load is unconditional.  A lane past the matrix re-reads its last column and
+    // rows past kcount re-read the last row: valid memory, finite values, and the products
+    // never use them (mma_cols skips k >= kcount; columns >= N are never summed).
     const unsigned int kb = __builtin_amdgcn_readfirstlane(kbeg);
     const unsigned int kc = __builtin_amdgcn_readfirstlane(kcount);
-    const unsigned int c = col < N ? col : N - 1u;
-    const float* row = W + (size_t)kb * N;
+    const unsigned int cb = (col < N ? col : N - 1u) * 4u;
+    const gbytes base = (gbytes)reinterpret_cast<const char*>(W) + (size_t)kb * N * 4u;
 #pragma unroll
     for (int u = 0; u < NR; ++u) {
         const unsigned int uu = (unsigned int)u < kc ? (unsigned int)u : kc - 1u;
-        wr[u] = row[(size_t)uu * N + c];
+        gbytes rb = base + (size_t)uu * N * 4u;
+        asm volatile("" : "+s"(rb));
+        wr[u] = *(const __attribute__((address_space(1))) float*)(rb + cb);
+    }
+}
+
+// The same for the wide split: wr[u] = W[kbeg + u][col .. col+3], col a multiple of 4.
+template <int NR>
+__device__ __forceinline__ void load_cols4(f32x4 (&wr)[NR], const float* __restrict__ W,
+                                           unsigned int N, unsigned int col, unsigned int kbeg,
+                                           unsigned int kcount) {
+    const unsigned int kb = __builtin_amdgcn_readfirstlane(kbeg);
+    const unsigned int kc = __builtin_amdgcn_readfirstlane(kcount);
+    const unsigned int cb = (col + 3u < N ? col : N - 4u) * 4u;
+    const gbytes base = (gbytes)reinterpret_cast<const char*>(W) + (size_t)kb * N * 4u;
+#pragma unroll
+    for (int u = 0; u < NR; ++u) {
+        const unsigned int uu = (unsigned int)u < kc ? (unsigned int)u : kc - 1u;
+        gbytes rb = base + (size_t)uu * N * 4u;
+        asm volatile("" : "+s"(rb));
+        wr[u] = *(const __attribute__((address_space(1))) f32x4*)(rb + cb);
     }
 }
 
@@ -113,11 +154,11 @@ __device__ __forceinline__ void mma_cols_reload(f32x4 (&acc)[MG], const float* a
                                                 unsigned int col_n, unsigned int kbeg_n,
                                                 unsigned int kcount_n) {
     const float* ap = act + (threadIdx.x & 3u) * ldk + kbeg;
-    // (unconditional loads from a scalar row base, as in load_cols)
+    // (unconditional loads from a scalar row address, as in load_cols)
     const unsigned int kbn = __builtin_amdgcn_readfirstlane(kbeg_n);
     const unsigned int kcn = __builtin_amdgcn_readfirstlane(kcount_n);
-    const unsigned int cn = col_n < Nn ? col_n : Nn - 1u;
-    const float* row_n = Wn + (size_t)kbn * Nn;
+    const unsigned int cbn = (col_n < Nn ? col_n : Nn - 1u) * 4u;
+    const gbytes base_n = (gbytes)reinterpret_cast<const char*>(Wn) + (size_t)kbn * Nn * 4u;
 #pragma unroll
     for (int mg = 0; mg < MG; ++mg) acc[mg] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -134,9 +175,93 @@ __device__ __forceinline__ void mma_cols_reload(f32x4 (&acc)[MG], const float* a
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const unsigned int uu = (unsigned int)(u4 + u) < kcn ? (unsigned int)(u4 + u) : kcn - 1u;
-            wr[u4 + u] = row_n[(size_t)uu * Nn + cn];
+            gbytes rb = base_n + (size_t)uu * Nn * 4u;
+            asm volatile("" : "+s"(rb));
+            wr[u4 + u] = *(const __attribute__((address_space(1))) float*)(rb + cbn);
         }
     }
+}
+
+// Wide split, four rows of activations: acc[j][v] += sum_{u < kcount} act[v][kbeg + u] * wr[u][j],
+// j = 0..3.  The activations are read VEC (2 or 4) consecutive k at a time; kcount is a
+// multiple of VEC.
+template <int VEC> struct ActVec;
+template <> struct ActVec<2> { typedef float type __attribute__((ext_vector_type(2))); };
+template <> struct ActVec<4> { typedef f32x4 type; };
+
+template <int NR, int VEC>
+__device__ __forceinline__ void mma_cols4(f32x4 (&acc)[4], const float* act, unsigned int ldk,
+                                          unsigned int kbeg, unsigned int kcount,
+                                          const f32x4 (&wr)[NR]) {
+    typedef typename ActVec<VEC>::type avec;
+    const float* ap = act + (threadIdx.x & 3u) * ldk + kbeg;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u0 = 0; u0 < NR; u0 += VEC) {
+        if ((unsigned int)u0 < kcount) {
+            const avec a = *reinterpret_cast<const avec*>(ap + u0);
+#pragma unroll
+            for (int u = 0; u < VEC; ++u)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[j] = __builtin_amdgcn_mfma_f32_4x4x1f32(a[u], wr[u0 + u][j], acc[j], 0, 0, 0);
+        }
+    }
+}
+
+// ... refilling each group of VEC weight registers from the next matrix (Wn, [.. x Nn], rows
+// kbeg_n..) as soon as it has been consumed: the loads of the next layer's weights overlap this
+// layer's MFMAs instead of queueing up behind them.
+template <int MG, int NR, int VEC>
+__device__ __forceinline__ void mma_cols4_reload(f32x4 (&acc)[MG][4], const float* act,
+                                                 unsigned int ldk, unsigned int kbeg,
+                                                 unsigned int kcount, f32x4 (&wr)[NR],
+                                                 const float* __restrict__ Wn, unsigned int Nn,
+                                                 unsigned int col_n, unsigned int kbeg_n,
+                                                 unsigned int kcount_n) {
+    // MG groups of four activation rows (rows mg*4 .. mg*4+3 of act) share the weights
+    typedef typename ActVec<VEC>::type avec;
+    const float* ap = act + (threadIdx.x & 3u) * ldk + kbeg;
+    const unsigned int kbn = __builtin_amdgcn_readfirstlane(kbeg_n);
+    const unsigned int kcn = __builtin_amdgcn_readfirstlane(kcount_n);
+    const unsigned int cbn = (col_n + 3u < Nn ? col_n : Nn - 4u) * 4u;
+    const gbytes base_n = (gbytes)reinterpret_cast<const char*>(Wn) + (size_t)kbn * Nn * 4u;
+#pragma unroll
+    for (int mg = 0; mg < MG; ++mg)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[mg][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u0 = 0; u0 < NR; u0 += VEC) {
+        if ((unsigned int)u0 < kcount) {
+#pragma unroll
+            for (int mg = 0; mg < MG; ++mg) {
+                const avec a = *reinterpret_cast<const avec*>(ap + (size_t)mg * 4 * ldk + u0);
+#pragma unroll
+                for (int u = 0; u < VEC; ++u)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        acc[mg][j] = __builtin_amdgcn_mfma_f32_4x4x1f32(a[u], wr[u0 + u][j], acc[mg][j], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < VEC; ++u) {
+            const unsigned int uu = (unsigned int)(u0 + u) < kcn ? (unsigned int)(u0 + u) : kcn - 1u;
+            gbytes rb = base_n + (size_t)uu * Nn * 4u;
+            asm volatile("" : "+s"(rb));
+            wr[u0 + u] = *(const __attribute__((address_space(1))) f32x4*)(rb + cbn);
+        }
+    }
+}
+
+// part[slice][row0 + v][cc .. cc+3] = acc[.][v] (wide split; `rows` rows per slice, cc a multiple of 4)
+__device__ __forceinline__ void store_part4(float* part, unsigned int slice, unsigned int rows,
+                                            unsigned int row0, unsigned int pitch, unsigned int cc,
+                                            const f32x4 (&acc)[4]) {
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+        *reinterpret_cast<f32x4*>(part + ((size_t)(slice * rows + row0 + v)) * pitch + cc) =
+            f32x4{acc[0][v], acc[1][v], acc[2][v], acc[3][v]};
 }
 
 // part[slice][row][cc] = acc; the lane holds rows v = 0..3 of its column cc
@@ -158,9 +283,11 @@ __device__ __forceinline__ float sum_part(const float* part, unsigned int slices
     return v;
 }
 
-template <bool BOTH>
+// BOTH: a frozen target network evaluates s'.  NR1: rows of W1 a lane holds (Dp / 16, 2 or 4).
+template <bool BOTH, int NR1>
 __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     extern __shared__ float lds[];
+    touch_kernel_args<RowArgs>();
     const unsigned int tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const unsigned int D = p.D, Dp = p.Dp, H = p.H, A = p.A, Ap = p.Ap;
     const unsigned int ldx = Dp + kPadK, ldh = H + kPadK, ldq = Ap + kPadK;
@@ -169,8 +296,8 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     float* H2s = H1s + 8 * ldh;           // [8][ldh]
     float* Qs = H2s + 8 * ldh;            // [8][ldq]
     float* dZs = Qs + 8 * ldq;            // [4][ldh]
-    float* part = dZs + 4 * ldh;          // [4][8][256] or [16][8][64]
-    float* b1s = part + 4 * 8 * kChunk;   // [H]
+    float* part = dZs + 4 * ldh;          // [16][8][256] or [16][8][64]
+    float* b1s = part + 16 * 8 * kChunk;  // [H]
     float* b2s = b1s + H;                 // [H]
     float* b3s = b2s + H;                 // [Ap]
     float* b1ts = b3s + Ap;               // [H]   the frozen target network's biases
@@ -186,9 +313,9 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     // registers take the trained network's share of a layer first (rows 0..3) and are refilled
     // with the target's during those MFMAs.
     constexpr bool both = BOTH;
-    // wide split
-    const unsigned int cc = 64u * (wave & 3u) + lane, ks = wave >> 2;
-    const unsigned int q1 = Dp >> 2, q2 = H >> 2;   // K quarter of layer 1 / layers 2 and backward
+    // wide split: K sixteenths of layer 1 / of layers 2 and backward
+    const unsigned int cc = 4u * lane, ks = wave;
+    const unsigned int q1 = Dp >> 4, q2 = H >> 4;
     // narrow split
     const unsigned int s3 = H >> 4;                 // K sixteenth of layer 3
 
@@ -255,9 +382,9 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
             reinterpret_cast<unsigned int*>(p.g.rows + slot * p.g.row_bytes)[w] = staged_word(p, k, w);
         }
     }
-    float w1r[16], w2r[64];
-    load_cols<16>(w1r, W1, H, cc, ks * q1, q1);
-    load_cols<64>(w2r, W2, H, cc, ks * q2, q2);
+    f32x4 w1r[NR1], w2r[16];
+    load_cols4<NR1>(w1r, W1, H, cc, ks * q1, q1);
+    load_cols4<16>(w2r, W2, H, cc, ks * q2, q2);
     const float b1v = tid < H ? p.w[p.ob1 + tid] : 0.f;
     const float b2v = tid < H ? p.w[p.ob2 + tid] : 0.f;
     const float b3v = tid < Ap ? p.w[p.ob3 + tid] : 0.f;
@@ -298,7 +425,58 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     if (tid < Ap) b3s[tid] = b3v;
     lds_barrier();
 
-    // the column of W3 that the backward pass of each row needs: W3[k][a_r], one per thread
+    // ---- layer 1
+    // The wide layers take rows 0..3 (s) and then rows 4..7 (s') with the same accumulators.
+    f32x4 accw[4];
+    if (!both) {
+        mma_cols4<NR1, 2>(accw, Xs, ldx, ks * q1, q1, w1r);
+    } else {
+        // the target network's biases travel during the first MFMAs (kept out of the registers
+        // that are scarce while W2 is arriving)
+        const float b1tv = tid < H ? p.wt[p.ob1 + tid] : 0.f;
+        const float b2tv = tid < H ? p.wt[p.ob2 + tid] : 0.f;
+        const float b3tv = tid < Ap ? p.wt[p.ob3 + tid] : 0.f;
+        f32x4 lo[1][4];
+        mma_cols4_reload<1, NR1, 2>(lo, Xs, ldx, ks * q1, q1, w1r, p.wt + p.oW1, H, cc, ks * q1, q1);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) accw[j] = lo[0][j];
+        if (tid < H) {
+            b1ts[tid] = b1tv;
+            b2ts[tid] = b2tv;
+        }
+        if (tid < Ap) b3ts[tid] = b3tv;
+    }
+    store_part4(part, ks, 8, 0, kChunk, cc, accw);
+    mma_cols4<NR1, 2>(accw, Xs + 4 * ldx, ldx, ks * q1, q1, w1r);
+    store_part4(part, ks, 8, 4, kChunk, cc, accw);
+    lds_barrier();
+    for (unsigned int e = tid; e < 8 * H; e += kRowThreads) {
+        const unsigned int row = e / H, c = e - row * H;
+        float v = sum_part(part, 16, 8, kChunk, row, c) + (both && row >= 4 ? b1ts : b1s)[c];
+        v = v > 0.f ? v : 0.f;
+        H1s[row * ldh + c] = v;
+        if (row < nrows) p.H1[(size_t)(i0 + row) * H + c] = v;
+    }
+    lds_barrier();
+
+    // ---- layer 2; its registers are then refilled with W2^T (backward)
+    if (!both) {
+        // one pass over the weights for all eight rows, so that the refill starts at once
+        f32x4 acc8[2][4];
+        mma_cols4_reload<2, 16, 4>(acc8, H1s, ldh, ks * q2, q2, w2r, p.w2t, H, cc, ks * q2, q2);
+        store_part4(part, ks, 8, 0, kChunk, cc, acc8[0]);
+        store_part4(part, ks, 8, 4, kChunk, cc, acc8[1]);
+    } else {
+        f32x4 acc4[1][4];
+        mma_cols4_reload<1, 16, 4>(acc4, H1s, ldh, ks * q2, q2, w2r, p.wt + p.oW2, H, cc, ks * q2, q2);
+        store_part4(part, ks, 8, 0, kChunk, cc, acc4[0]);
+        mma_cols4_reload<1, 16, 4>(acc4, H1s + 4 * ldh, ldh, ks * q2, q2, w2r, p.w2t, H, cc, ks * q2, q2);
+        store_part4(part, ks, 8, 4, kChunk, cc, acc4[0]);
+    }
+    // The accumulators are free: layer 3's weights are requested, and ...
+    float w3r[16];
+    load_cols<16>(w3r, W3, Ap, lane, wave * s3, s3);
+    // ... the column of W3 that the backward pass of each row needs: W3[k][a_r], one per thread
     float w3sel = 0.f;
     {
         const unsigned int r = tid / H, k = tid - r * H;
@@ -308,56 +486,10 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
             w3sel = W3[(size_t)k * Ap + ai];
         }
     }
-
-    // ---- layer 1
-    f32x4 acc2[2];
-    if (!both) {
-        mma_cols<2, 16>(acc2, Xs, ldx, ks * q1, q1, w1r);
-    } else {
-        // the target network's biases travel during the first MFMAs (kept out of the registers
-        // that are scarce while W2 is arriving)
-        const float b1tv = tid < H ? p.wt[p.ob1 + tid] : 0.f;
-        const float b2tv = tid < H ? p.wt[p.ob2 + tid] : 0.f;
-        const float b3tv = tid < Ap ? p.wt[p.ob3 + tid] : 0.f;
-        f32x4 lo[1], hi[1];
-        mma_cols_reload<1, 16>(lo, Xs, ldx, ks * q1, q1, w1r, p.wt + p.oW1, H, cc, ks * q1, q1);
-        mma_cols<1, 16>(hi, Xs + 4 * ldx, ldx, ks * q1, q1, w1r);
-        acc2[0] = lo[0];
-        acc2[1] = hi[0];
-        if (tid < H) {
-            b1ts[tid] = b1tv;
-            b2ts[tid] = b2tv;
-        }
-        if (tid < Ap) b3ts[tid] = b3tv;
-    }
-    float w3r[16];   // layer 1's registers are free: request layer 3's weights
-    load_cols<16>(w3r, W3, Ap, lane, wave * s3, s3);
-    store_part<2>(part, ks, kChunk, cc, acc2);
     lds_barrier();
     for (unsigned int e = tid; e < 8 * H; e += kRowThreads) {
         const unsigned int row = e / H, c = e - row * H;
-        float v = sum_part(part, 4, 8, kChunk, row, c) + (both && row >= 4 ? b1ts : b1s)[c];
-        v = v > 0.f ? v : 0.f;
-        H1s[row * ldh + c] = v;
-        if (row < nrows) p.H1[(size_t)(i0 + row) * H + c] = v;
-    }
-    lds_barrier();
-
-    // ---- layer 2; its registers are then refilled with W2^T (backward) and W3 is requested
-    if (!both) {
-        mma_cols_reload<2, 64>(acc2, H1s, ldh, ks * q2, q2, w2r, p.w2t, H, cc, ks * q2, q2);
-    } else {
-        f32x4 lo[1], hi[1];
-        mma_cols_reload<1, 64>(lo, H1s, ldh, ks * q2, q2, w2r, p.wt + p.oW2, H, cc, ks * q2, q2);
-        mma_cols_reload<1, 64>(hi, H1s + 4 * ldh, ldh, ks * q2, q2, w2r, p.w2t, H, cc, ks * q2, q2);
-        acc2[0] = lo[0];
-        acc2[1] = hi[0];
-    }
-    store_part<2>(part, ks, kChunk, cc, acc2);
-    lds_barrier();
-    for (unsigned int e = tid; e < 8 * H; e += kRowThreads) {
-        const unsigned int row = e / H, c = e - row * H;
-        float v = sum_part(part, 4, 8, kChunk, row, c) + (both && row >= 4 ? b2ts : b2s)[c];
+        float v = sum_part(part, 16, 8, kChunk, row, c) + (both && row >= 4 ? b2ts : b2s)[c];
         v = v > 0.f ? v : 0.f;
         H2s[row * ldh + c] = v;
         if (row < nrows) p.H2[(size_t)(i0 + row) * H + c] = v;
@@ -365,6 +497,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     lds_barrier();
 
     // ---- layer 3 (narrow split: 16 K slices, columns 0..63)
+    f32x4 acc2[2];
     if (!both) {
         mma_cols<2, 16>(acc2, H2s, ldh, wave * s3, s3, w3r);
     } else {
@@ -427,13 +560,12 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     lds_barrier();
 
     // ---- dZ1 = (dZ2 W2^T) masked by the first ReLU
-    f32x4 acc1[1];
-    mma_cols<1, 64>(acc1, dZs, ldh, ks * q2, q2, w2r);
-    store_part<1>(part, ks, kChunk, cc, acc1);
+    mma_cols4<16, 4>(accw, dZs, ldh, ks * q2, q2, w2r);
+    store_part4(part, ks, 4, 0, kChunk, cc, accw);
     lds_barrier();
     for (unsigned int e = tid; e < nrows * H; e += kRowThreads) {
         const unsigned int r = e / H, c = e - r * H;
-        float v = sum_part(part, 4, 4, kChunk, r, c);
+        float v = sum_part(part, 16, 4, kChunk, r, c);
         if (!(H1s[r * ldh + c] > 0.f)) v = 0.f;
         p.dZ1[(size_t)(i0 + r) * H + c] = v;
     }
@@ -500,6 +632,7 @@ __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
     __shared__ float Bs[kTK][kTN + 4];
     const unsigned int tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const unsigned int l16 = lane & 15u, lq = lane >> 4;
+    touch_kernel_args<WArgs>();
     unsigned int j = 0;
     if (blockIdx.x >= p.job[1].tile_begin) j = 1;
     if (blockIdx.x >= p.job[2].tile_begin) j = 2;
@@ -607,7 +740,7 @@ __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
 
 size_t row_kernel_lds(unsigned int Dp, unsigned int H, unsigned int Ap) {
     const size_t ldx = Dp + kPadK, ldh = H + kPadK, ldq = Ap + kPadK;
-    return (8 * ldx + 8 * ldh * 2 + 8 * ldq + 4 * ldh + 4 * 8 * kChunk + 2 * (2 * H + Ap) + 16 + 4) *
+    return (8 * ldx + 8 * ldh * 2 + 8 * ldq + 4 * ldh + 16 * 8 * kChunk + 2 * (2 * H + Ap) + 16 + 4) *
            sizeof(float);
 }
 
@@ -616,19 +749,36 @@ size_t row_kernel_lds(unsigned int Dp, unsigned int H, unsigned int Ap) {
 bool fused_step_supported(const train_config& cfg, const replay* rp_) {
     if (cfg.param_dtype != RP_F32 || rp_->cfg.state_dtype != RP_F32 || rp_->cfg.layout != RP_PAIR)
         return false;
-    // one lane owns one column of a layer and holds its share of the weights in registers:
-    // hidden width up to 256, states and action sets up to 64 wide
+    // a lane owns one or four columns of a layer and holds its share of the weights in
+    // registers: hidden width up to 256, states and action sets up to 64 wide
     if (cfg.hidden % 64 != 0 || cfg.hidden > 256 || cfg.state_dim > 64 || cfg.num_actions > 64)
         return false;
     if (cfg.batch > 8192 || cfg.appends_per_step > 8192) return false;
     const unsigned int Dp = (unsigned int)align_up(cfg.state_dim, 32);
     const unsigned int Ap = (unsigned int)align_up(cfg.num_actions, 32);
-    return row_kernel_lds(Dp, cfg.hidden, Ap) <= 64 * 1024;
+    return row_kernel_lds(Dp, cfg.hidden, Ap) <= kRowLdsMax;
 }
 
-void* fused_rows_func(bool target_network) {
-    return target_network ? reinterpret_cast<void*>(fused_rows_kernel<true>)
-                          : reinterpret_cast<void*>(fused_rows_kernel<false>);
+// The row kernel's dynamic LDS exceeds the default limit: announced once per process, at trainer
+// creation (outside any stream capture).
+hipError_t fused_init() {
+    const void* kernels[] = {reinterpret_cast<const void*>(fused_rows_kernel<false, 2>),
+                             reinterpret_cast<const void*>(fused_rows_kernel<false, 4>),
+                             reinterpret_cast<const void*>(fused_rows_kernel<true, 2>),
+                             reinterpret_cast<const void*>(fused_rows_kernel<true, 4>)};
+    for (const void* k : kernels) {
+        hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kRowLdsMax);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+void* fused_rows_func(bool target_network, unsigned int Dp) {
+    if (Dp <= 32)
+        return target_network ? reinterpret_cast<void*>(fused_rows_kernel<true, 2>)
+                              : reinterpret_cast<void*>(fused_rows_kernel<false, 2>);
+    return target_network ? reinterpret_cast<void*>(fused_rows_kernel<true, 4>)
+                          : reinterpret_cast<void*>(fused_rows_kernel<false, 4>);
 }
 
 hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* batch, hipStream_t st,
@@ -667,7 +817,7 @@ hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* bat
     const unsigned int blocks = (t->B + kRows - 1) / kRows;
     hipError_t e = hipSuccess;
     void* kargs[] = {&a};
-    e = hipLaunchKernel(fused_rows_func(t->wt != nullptr), dim3(blocks), dim3(kRowThreads), kargs,
+    e = hipLaunchKernel(fused_rows_func(t->wt != nullptr, t->Dp), dim3(blocks), dim3(kRowThreads), kargs,
                         row_kernel_lds(t->Dp, t->H, t->Ap), st);
     if (e != hipSuccess) return e;
 

@@ -871,6 +871,13 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
         rp::set_error("train_create: clearing the workspace failed: %s", hipGetErrorString(e));
         return fail(RP_EHIP);
     }
+    if (t->fused) {
+        e = rp::fused_init();
+        if (e != hipSuccess) {
+            rp::set_error("train_create: allowing the row kernel's LDS size failed: %s", hipGetErrorString(e));
+            return fail(RP_EHIP);
+        }
+    }
     if (t->wide) {
         e = rp::wide_init_buffers(t);
         if (e != hipSuccess) {
@@ -912,7 +919,7 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
         }
         t->pin_dev = static_cast<unsigned char*>(dp);
     }
-    t->payload_func = t->fused  ? rp::fused_rows_func(t->wt != nullptr)
+    t->payload_func = t->fused  ? rp::fused_rows_func(t->wt != nullptr, t->Dp)
                       : t->wide ? rp::append_gather_func(rp_->geom)
                                 : rp::append_pair_func(rp_->geom);
     t->payload_kargs[0] = t->fused ? static_cast<void*>(&t->row_args) : static_cast<void*>(&t->append_args);
