@@ -600,12 +600,14 @@ struct WArgs {
     unsigned int sync_every;      // sync_every (0: never)
 };
 
-constexpr unsigned int kTM = 32, kTN = 64, kTK = 128;
+constexpr unsigned int kTM = 32, kTN = 32, kTK = 128;
+constexpr unsigned int kTPitch = 48;   // LDS row pitch (floats): the MFMA operand reads hit 64 distinct banks
 
 // One optimizer update of parameter k with gradient gk, from values loaded earlier.
-// r1 = 1 / (1 - beta1^t), r2 = 1 / (1 - beta2^t).
+// r1 = 1 / (1 - beta1^t), r2 = 1 / (1 - beta2^t); sync: this step also refreshes the target network.
 __device__ __forceinline__ float opt_apply(const WArgs& p, unsigned int k, float gk, float wk,
-                                           float mk, float vk, float r1, float r2, bool grad_only) {
+                                           float mk, float vk, float r1, float r2, bool grad_only,
+                                           bool sync) {
     p.g[k] = gk;
     if (grad_only) return wk;
     if (p.opt == RP_SGD) {
@@ -618,20 +620,22 @@ __device__ __forceinline__ float opt_apply(const WArgs& p, unsigned int k, float
         wk -= p.lr * (mk * r1) / (sqrtf(vk * r2) + p.eps);
     }
     p.w[k] = wk;
-    if (p.wt && p.sync_every && p.ctr->adam_t % p.sync_every == 0) p.wt[k] = wk;
+    if (sync) p.wt[k] = wk;
     return wk;
 }
 
-// A workgroup owns a 32 x 64 tile of one layer's weight matrix: it reduces the outer products
-// over the batch (128 rows per LDS pass, every global load of a pass issued before the first
-// use) with 16x16x4 fp32 MFMA -- wavefront w takes columns 16w..16w+15 and both 16-row halves --
-// adds the bias gradient when it sits on tile row 0 (a third MFMA with an all-ones A operand
-// gives the column sums), and applies the optimizer to what it holds.
+// A workgroup owns a 32 x 32 tile of one layer's weight matrix (every matrix here is a whole
+// number of tiles): it reduces the outer products over the batch, 128 rows per LDS pass, with
+// 16x16x4 fp32 MFMA -- wavefront w takes the 16 x 16 quarter (w >> 1, w & 1) -- adds the bias
+// gradient when it sits on tile row 0 (a second MFMA with an all-ones A operand gives the
+// column sums), and applies the optimizer to what it holds.  The batch tiles are requested
+// before anything else; the optimizer state follows and arrives during the product.
 __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
-    __shared__ float As[kTK][kTM + 4];
-    __shared__ float Bs[kTK][kTN + 4];
+    __shared__ float As[kTK][kTPitch];
+    __shared__ float Bs[kTK][kTPitch];
     const unsigned int tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const unsigned int l16 = lane & 15u, lq = lane >> 4;
+    const unsigned int wr = wave >> 1, wc = wave & 1u;
     touch_kernel_args<WArgs>();
     unsigned int j = 0;
     if (blockIdx.x >= p.job[1].tile_begin) j = 1;
@@ -639,28 +643,41 @@ __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
     const WJob jb = j == 0 ? p.job[0] : j == 1 ? p.job[1] : p.job[2];
     const unsigned int tile = blockIdx.x - jb.tile_begin;
     const unsigned int m0 = (tile / jb.tiles_n) * kTM, n0 = (tile % jb.tiles_n) * kTN;
-    const bool bias_tile = m0 == 0;
-    // this lane's outputs: rows m0 + 16 rt + 4 lq + v (rt = 0,1; v = 0..3), column nn
-    const unsigned int nn = n0 + 16u * wave + l16;
-    const bool col_ok = nn < jb.N;
-    const bool do_bias = bias_tile && lq == 0 && col_ok;
+    // this lane's outputs: rows mm .. mm+3 of column nn
+    const unsigned int nn = n0 + 16u * wc + l16;
+    const unsigned int mm = m0 + 16u * wr + 4u * lq;
+    const bool bias_wave = m0 == 0 && wr == 0;
+    const bool do_bias = bias_wave && lq == 0;
 
-    // bias corrections and the optimizer state of this lane's outputs, fetched early so that
-    // their latency overlaps the product
+    // one pass of the batch: rows b0 .. b0+127 of the activation tile (32 columns from m0) and
+    // of the error tile (32 columns from n0); 4 + 4 float4 per thread, rows past the batch read
+    // the last row and count as zero
+    float4 av[4], bv[4];
+    auto load_tiles = [&](unsigned int b0) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const unsigned int e = tid + u * kThreads;          // 128 rows x 8 float4
+            const unsigned int i = e >> 3, c4 = (e & 7u) * 4u;
+            const unsigned int bi = b0 + i, bc = bi < p.B ? bi : p.B - 1u;
+            av[u] = *reinterpret_cast<const float4*>(jb.act + (size_t)bc * jb.lda + m0 + c4);
+            bv[u] = *reinterpret_cast<const float4*>(jb.err + (size_t)bc * jb.ldb + n0 + c4);
+            if (bi >= p.B) av[u] = bv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
+    load_tiles(0);
+
+    // bias corrections and the optimizer state of this lane's outputs
     const float c1 = p.ctr->c1, c2 = p.ctr->c2;
     const bool adam = p.opt != RP_SGD;
-    float w_old[2][4], m_old[2][4], v_old[2][4];
+    const bool sync = p.wt && p.sync_every && p.ctr->adam_t % p.sync_every == 0;
+    float w_old[4], m_old[4], v_old[4];
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const unsigned int m = m0 + 16u * rt + 4u * lq + v;
-            const bool ok = col_ok && m < jb.M;
-            const unsigned int k = jb.w_off + m * jb.ldw + nn;
-            w_old[rt][v] = ok ? p.w[k] : 0.f;
-            m_old[rt][v] = ok && adam ? p.m[k] : 0.f;
-            v_old[rt][v] = ok && adam ? p.v[k] : 0.f;
-        }
+    for (int v = 0; v < 4; ++v) {
+        const unsigned int k = jb.w_off + (mm + v) * jb.ldw + nn;
+        w_old[v] = p.w[k];
+        m_old[v] = adam ? p.m[k] : 0.f;
+        v_old[v] = adam ? p.v[k] : 0.f;
+    }
     const float wb_old = do_bias ? p.w[jb.b_off + nn] : 0.f;
     const float mb_old = do_bias && adam ? p.m[jb.b_off + nn] : 0.f;
     const float vb_old = do_bias && adam ? p.v[jb.b_off + nn] : 0.f;
@@ -670,65 +687,39 @@ __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
     if (blockIdx.x == 0 && tid < 64)
         for (unsigned int i = tid; i < p.B; i += 64) loss_part += p.lossi[i];
 
-    f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
     f32x4 accb = f32x4{0.f, 0.f, 0.f, 0.f};
     for (unsigned int b0 = 0; b0 < p.B; b0 += kTK) {
-        // M and N are multiples of 32, so float4 pieces are all in or all out
-        float4 av[4], bv[8];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const unsigned int e = tid + u * kThreads;          // 128 rows x 8 float4
-            const unsigned int i = e >> 3, c4 = (e & 7u) * 4u;
-            const unsigned int bi = b0 + i, m = m0 + c4;
-            av[u] = (bi < p.B && m < jb.M)
-                        ? *reinterpret_cast<const float4*>(jb.act + (size_t)bi * jb.lda + m)
-                        : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const unsigned int e = tid + u * kThreads;          // 128 rows x 16 float4
-            const unsigned int i = e >> 4, c4 = (e & 15u) * 4u;
-            const unsigned int bi = b0 + i, nc = n0 + c4;
-            bv[u] = (bi < p.B && nc < jb.N)
-                        ? *reinterpret_cast<const float4*>(jb.err + (size_t)bi * jb.ldb + nc)
-                        : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
         if (b0) __syncthreads();
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const unsigned int e = tid + u * kThreads;
             *reinterpret_cast<float4*>(&As[e >> 3][(e & 7u) * 4u]) = av[u];
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const unsigned int e = tid + u * kThreads;
-            *reinterpret_cast<float4*>(&Bs[e >> 4][(e & 15u) * 4u]) = bv[u];
+            *reinterpret_cast<float4*>(&Bs[e >> 3][(e & 7u) * 4u]) = bv[u];
         }
         __syncthreads();
+        if (b0 + kTK < p.B) load_tiles(b0 + kTK);   // the next pass travels during this product
         // A fragment: lane holds Act[k4 + lq][row l16]; B fragment: Err[k4 + lq][column l16]
 #pragma unroll 8
         for (unsigned int k4 = 0; k4 < kTK; k4 += 4) {
-            const float b = Bs[k4 + lq][16u * wave + l16];
-            const float a0 = As[k4 + lq][l16], a1 = As[k4 + lq][16u + l16];
-            acc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b, acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b, acc[1], 0, 0, 0);
-            if (bias_tile) accb = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, b, accb, 0, 0, 0);
+            const float a = As[k4 + lq][16u * wr + l16];
+            const float b = Bs[k4 + lq][16u * wc + l16];
+            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc, 0, 0, 0);
+            if (bias_wave) accb = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, b, accb, 0, 0, 0);
         }
     }
 
     const float r1 = 1.f / c1, r2 = 1.f / c2;
     const bool grad_only = j == p.grad_only_job;
+    float w_new[4];
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const unsigned int m = m0 + 16u * rt + 4u * lq + v;
-            if (!col_ok || m >= jb.M) continue;
-            const float wk = opt_apply(p, jb.w_off + m * jb.ldw + nn, acc[rt][v], w_old[rt][v],
-                                       m_old[rt][v], v_old[rt][v], r1, r2, grad_only);
-            if (jb.wT) jb.wT[(size_t)nn * jb.M + m] = wk;
-        }
-    if (do_bias) opt_apply(p, jb.b_off + nn, accb[0], wb_old, mb_old, vb_old, r1, r2, grad_only);
+    for (int v = 0; v < 4; ++v)
+        w_new[v] = opt_apply(p, jb.w_off + (mm + v) * jb.ldw + nn, acc[v], w_old[v], m_old[v],
+                             v_old[v], r1, r2, grad_only, sync);
+    if (jb.wT)
+        *reinterpret_cast<float4*>(jb.wT + (size_t)nn * jb.M + mm) =
+            make_float4(w_new[0], w_new[1], w_new[2], w_new[3]);
+    if (do_bias) opt_apply(p, jb.b_off + nn, accb[0], wb_old, mb_old, vb_old, r1, r2, grad_only, sync);
     if (blockIdx.x == 0 && tid < 64) {
         const float s = wave_sum(loss_part);
         if (tid == 0) {
