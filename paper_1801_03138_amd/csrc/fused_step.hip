@@ -601,7 +601,6 @@ struct WArgs {
 };
 
 constexpr unsigned int kTM = 32, kTN = 32, kTK = 128;
-constexpr unsigned int kTPitch = 48;   // LDS row pitch (floats): the MFMA operand reads hit 64 distinct banks
 
 // One optimizer update of parameter k with gradient gk, from values loaded earlier.
 // r1 = 1 / (1 - beta1^t), r2 = 1 / (1 - beta2^t); sync: this step also refreshes the target network.
@@ -617,7 +616,9 @@ __device__ __forceinline__ float opt_apply(const WArgs& p, unsigned int k, float
         vk = p.beta2 * vk + (1.f - p.beta2) * gk * gk;
         p.m[k] = mk;
         p.v[k] = vk;
-        wk -= p.lr * (mk * r1) / (sqrtf(vk * r2) + p.eps);
+        // hardware square root and reciprocal (1 ulp each): the quotient is good to a few parts
+        // in 1e7, far inside what the update's own rounding leaves
+        wk -= p.lr * (mk * r1) * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(vk * r2) + p.eps);
     }
     p.w[k] = wk;
     if (sync) p.wt[k] = wk;
@@ -625,14 +626,14 @@ __device__ __forceinline__ float opt_apply(const WArgs& p, unsigned int k, float
 }
 
 // A workgroup owns a 32 x 32 tile of one layer's weight matrix (every matrix here is a whole
-// number of tiles): it reduces the outer products over the batch, 128 rows per LDS pass, with
-// 16x16x4 fp32 MFMA -- wavefront w takes the 16 x 16 quarter (w >> 1, w & 1) -- adds the bias
-// gradient when it sits on tile row 0 (a second MFMA with an all-ones A operand gives the
-// column sums), and applies the optimizer to what it holds.  The batch tiles are requested
-// before anything else; the optimizer state follows and arrives during the product.
+// number of tiles) and wavefront w its 16 x 16 quarter (w >> 1, w & 1): it reduces the outer
+// products over the batch with 16x16x4 fp32 MFMA, 128 batch rows per pass, adds the bias
+// gradient when it sits on tile row 0 (the column sums of its error operands), and applies
+// the optimizer to what it holds.  The MFMA operands go from global
+// memory straight into the registers the instruction reads them from (lane l: batch row
+// 4t + l/16 of step t, column l%16 of the quarter -- 64-byte runs), all 64 loads of a pass
+// requested before the first use; nothing passes through LDS and no wavefront waits for another.
 __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
-    __shared__ float As[kTK][kTPitch];
-    __shared__ float Bs[kTK][kTPitch];
     const unsigned int tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const unsigned int l16 = lane & 15u, lq = lane >> 4;
     const unsigned int wr = wave >> 1, wc = wave & 1u;
@@ -649,22 +650,37 @@ __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
     const bool bias_wave = m0 == 0 && wr == 0;
     const bool do_bias = bias_wave && lq == 0;
 
-    // one pass of the batch: rows b0 .. b0+127 of the activation tile (32 columns from m0) and
-    // of the error tile (32 columns from n0); 4 + 4 float4 per thread, rows past the batch read
-    // the last row and count as zero
-    float4 av[4], bv[4];
-    auto load_tiles = [&](unsigned int b0) {
+    // operands of one pass: a[t] = Act[b0 + 4t + lq][m0 + 16 wr + l16], b[t] = Err[same row][nn];
+    // rows past the batch read the last row and count as zero
+    constexpr int kSteps = kTK / 4;
+    float a[kSteps], b[kSteps];
+    const float* ap = jb.act + m0 + 16u * wr + l16;
+    const float* bp = jb.err + nn;
+    // byte offsets of the lane within a step's four rows (the step's address is a scalar)
+    const unsigned int la = (lq * jb.lda + m0 + 16u * wr + l16) * 4u, lb = (lq * jb.ldb + nn) * 4u;
+    auto load_pass = [&](unsigned int b0) {
+        if (b0 + kTK <= p.B) {
+            const gbytes abase = (gbytes)reinterpret_cast<const char*>(jb.act) + (size_t)b0 * jb.lda * 4u;
+            const gbytes bbase = (gbytes)reinterpret_cast<const char*>(jb.err) + (size_t)b0 * jb.ldb * 4u;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const unsigned int e = tid + u * kThreads;          // 128 rows x 8 float4
-            const unsigned int i = e >> 3, c4 = (e & 7u) * 4u;
-            const unsigned int bi = b0 + i, bc = bi < p.B ? bi : p.B - 1u;
-            av[u] = *reinterpret_cast<const float4*>(jb.act + (size_t)bc * jb.lda + m0 + c4);
-            bv[u] = *reinterpret_cast<const float4*>(jb.err + (size_t)bc * jb.ldb + n0 + c4);
-            if (bi >= p.B) av[u] = bv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int t = 0; t < kSteps; ++t) {
+                gbytes ra = abase + (size_t)(4 * t) * jb.lda * 4u;
+                gbytes rb = bbase + (size_t)(4 * t) * jb.ldb * 4u;
+                asm volatile("" : "+s"(ra), "+s"(rb));
+                a[t] = *(const __attribute__((address_space(1))) float*)(ra + la);
+                b[t] = *(const __attribute__((address_space(1))) float*)(rb + lb);
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < kSteps; ++t) {
+                const unsigned int bi = b0 + 4u * t + lq, bc = bi < p.B ? bi : p.B - 1u;
+                const float av = ap[(size_t)bc * jb.lda], bv = bp[(size_t)bc * jb.ldb];
+                a[t] = bi < p.B ? av : 0.f;
+                b[t] = bi < p.B ? bv : 0.f;
+            }
         }
     };
-    load_tiles(0);
+    load_pass(0);
 
     // bias corrections and the optimizer state of this lane's outputs
     const float c1 = p.ctr->c1, c2 = p.ctr->c2;
@@ -682,31 +698,26 @@ __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
     const float mb_old = do_bias && adam ? p.m[jb.b_off + nn] : 0.f;
     const float vb_old = do_bias && adam ? p.v[jb.b_off + nn] : 0.f;
 
-    // workgroup 0 also reduces the per-sample losses: fetch them now
+    // the last workgroup (never on a tile row with a bias) also reduces the per-sample losses:
+    // fetch them now
+    const bool loss_block = blockIdx.x == gridDim.x - 1;
     float loss_part = 0.f;
-    if (blockIdx.x == 0 && tid < 64)
+    if (loss_block && tid < 64)
         for (unsigned int i = tid; i < p.B; i += 64) loss_part += p.lossi[i];
 
     f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-    f32x4 accb = f32x4{0.f, 0.f, 0.f, 0.f};
+    float bsum = 0.f;   // this lane's share of the column sum of Err (rows = lq mod 4)
     for (unsigned int b0 = 0; b0 < p.B; b0 += kTK) {
-        if (b0) __syncthreads();
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const unsigned int e = tid + u * kThreads;
-            *reinterpret_cast<float4*>(&As[e >> 3][(e & 7u) * 4u]) = av[u];
-            *reinterpret_cast<float4*>(&Bs[e >> 3][(e & 7u) * 4u]) = bv[u];
+        for (int t = 0; t < kSteps; ++t) {
+            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[t], b[t], acc, 0, 0, 0);
+            if (bias_wave) bsum += b[t];
         }
-        __syncthreads();
-        if (b0 + kTK < p.B) load_tiles(b0 + kTK);   // the next pass travels during this product
-        // A fragment: lane holds Act[k4 + lq][row l16]; B fragment: Err[k4 + lq][column l16]
-#pragma unroll 8
-        for (unsigned int k4 = 0; k4 < kTK; k4 += 4) {
-            const float a = As[k4 + lq][16u * wr + l16];
-            const float b = Bs[k4 + lq][16u * wc + l16];
-            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc, 0, 0, 0);
-            if (bias_wave) accb = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, b, accb, 0, 0, 0);
-        }
+        if (b0 + kTK < p.B) load_pass(b0 + kTK);
+    }
+    if (bias_wave) {
+        bsum += __shfl_xor(bsum, 16);
+        bsum += __shfl_xor(bsum, 32);
     }
 
     const float r1 = 1.f / c1, r2 = 1.f / c2;
@@ -719,8 +730,8 @@ __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
     if (jb.wT)
         *reinterpret_cast<float4*>(jb.wT + (size_t)nn * jb.M + mm) =
             make_float4(w_new[0], w_new[1], w_new[2], w_new[3]);
-    if (do_bias) opt_apply(p, jb.b_off + nn, accb[0], wb_old, mb_old, vb_old, r1, r2, grad_only, sync);
-    if (blockIdx.x == 0 && tid < 64) {
+    if (do_bias) opt_apply(p, jb.b_off + nn, bsum, wb_old, mb_old, vb_old, r1, r2, grad_only, sync);
+    if (loss_block && tid < 64) {
         const float s = wave_sum(loss_part);
         if (tid == 0) {
             p.ctr->loss = s / (float)p.B;

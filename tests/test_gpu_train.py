@@ -9,6 +9,14 @@ larger than its own tolerance).  Gradients and Adam moments are linear (quadrati
 clip(delta) with delta = y - Q(s,a), a difference of two quantities that each carry the Q
 tolerance, so in fp32 their bound is 10x (m: 10x, v: 20x) the Q bound; a wrong index, sign or
 operand in the backward pass is off by O(1), far outside either.
+
+The ReLU derivative is a step function: where a hidden pre-activation lies within the rounding
+error of its own fp32 sum of zero (|z| <= 64 * 2^-24 * (sum_k |h_k w_k| + |b|)), the two sides may
+land on different sides of the kink, and one hidden unit of one sample then enters the backward
+pass on one side only.  A step whose backward quantities disagree AND that has such a unit in
+the oracle's forward pass is counted in Pair.kink_steps and its backward comparison is dropped
+(forward quantities are still compared); any other disagreement fails as before.  With some
+1e4..1e5 hidden activations per step this happens about once in a few hundred steps.
 """
 import numpy as np
 import pytest
@@ -71,6 +79,23 @@ class Pair:
                                    bf16=int(self.bf16), dueling=int(dueling),
                                    **{k: float(v) for k, v in self.hyper.items()})
         self.rtol = BF16_RTOL if self.bf16 else F32_RTOL
+        self.kink_steps = 0
+
+    def on_relu_kink(self, p, S):
+        """Whether, from parameters p on states S, some hidden unit of some sample lies within its
+        fp32 rounding error of the ReLU kink (both hidden layers; float64)."""
+        D, H = self.D, self.H
+        p = np.asarray(p, np.float64)
+        W1, b1 = p[:D * H].reshape(D, H), p[D * H:D * H + H]
+        o = D * H + H
+        W2, b2 = p[o:o + H * H].reshape(H, H), p[o + H * H:o + H * H + H]
+        u = 64.0 * 2.0 ** -24
+        z1 = S @ W1 + b1
+        if (np.abs(z1) <= u * (np.abs(S) @ np.abs(W1) + np.abs(b1))).any():
+            return True
+        h1 = np.maximum(z1, 0.0)
+        z2 = h1 @ W2 + b2
+        return bool((np.abs(z2) <= u * (h1 @ np.abs(W2) + np.abs(b2))).any())
 
     def append_only(self, part, device_src=True):
         self.ref_ring.append(part["s"], part["s_next"], part["a"], part["r"], part["term"])
@@ -116,7 +141,17 @@ class Pair:
         assert_close([last["loss"]], [ref.loss], rt, "loss")
         g_rt = 10 * rt if not self.bf16 else 2 * rt
         g_got = tr.grads()
-        assert_close(g_got, ref.grads, g_rt, "gradients")
+        try:
+            assert_close(g_got, ref.grads, g_rt, "gradients")
+        except AssertionError:
+            if self.bf16 or not self.on_relu_kink(p, self.states_f64(s)):
+                raise
+            # a hidden unit on the ReLU kink (see the module docstring): forward quantities
+            # were compared, the backward ones are not comparable for this step
+            self.kink_steps += 1
+            m2, v2, t2, step2 = tr.opt_state()
+            assert step2 == step + 1
+            return status
         new_p = tr.params()
         slack = 0.0
         if self.cfg.opt == oracle.ADAM:
@@ -517,6 +552,7 @@ def test_random_configurations(B, c):
         part = synth.take(rows, at, at + c["appends"])
         at += c["appends"]
         assert pr.step(part, compare=True) == 0
+    assert pr.kink_steps <= 1, "ReLU kinks are rare: more than one in twelve steps is a backward bug"
 
 
 def test_paper_shaped_free_running_drift(B, capsys):
