@@ -87,19 +87,23 @@ __device__ __forceinline__ void load_cols(float (&wr)[NR], const float* __restri
                                           unsigned int kcount) {
     // kbeg and kcount are the same for the whole wavefront: the address of a row is kept in
     // scalar registers (the empty asm pins it there), the lane adds its 32-bit column offset,
-    // and every load is unconditional.  A lane past the matrix re-reads its last column and
-    // rows past kcount re-read the last row: valid memory, finite values, and the products
-    // never use them (mma_cols skips k >= kcount; columns >= N are never summed).
+    // and the loads of a lane are unconditional.  Rows past kcount re-read the last row: valid
+    // memory, finite values, and the products never use them (mma_cols skips k >= kcount).
+    // Lanes past the matrix request nothing and hold zeros (their columns are never summed).
     const unsigned int kb = __builtin_amdgcn_readfirstlane(kbeg);
     const unsigned int kc = __builtin_amdgcn_readfirstlane(kcount);
-    const unsigned int cb = (col < N ? col : N - 1u) * 4u;
+    const unsigned int cb = col * 4u;
     const gbytes base = (gbytes)reinterpret_cast<const char*>(W) + (size_t)kb * N * 4u;
 #pragma unroll
-    for (int u = 0; u < NR; ++u) {
-        const unsigned int uu = (unsigned int)u < kc ? (unsigned int)u : kc - 1u;
-        gbytes rb = base + (size_t)uu * N * 4u;
-        asm volatile("" : "+s"(rb));
-        wr[u] = *(const __attribute__((address_space(1))) float*)(rb + cb);
+    for (int u = 0; u < NR; ++u) wr[u] = 0.f;
+    if (col < N) {
+#pragma unroll
+        for (int u = 0; u < NR; ++u) {
+            const unsigned int uu = (unsigned int)u < kc ? (unsigned int)u : kc - 1u;
+            gbytes rb = base + (size_t)uu * N * 4u;
+            asm volatile("" : "+s"(rb));
+            wr[u] = *(const __attribute__((address_space(1))) float*)(rb + cb);
+        }
     }
 }
 
@@ -319,9 +323,13 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     // narrow split
     const unsigned int s3 = H >> 4;                 // K sixteenth of layer 3
 
-    // ---- phase 0.  The ring and trainer state before this step come as arguments (the host
-    // mirrors them exactly), so the slot draw and the row fetch go out first; then everything
-    // that does not depend on the sample is requested, long before its first use.
+    // ---- phase 0.  Fetching the weights is what the kernel waits for longest (the rate at which
+    // a compute unit takes in data bounds it), so those requests go out before anything else.
+    // The ring and trainer state before this step come as arguments (the host mirrors them
+    // exactly), so the slot draw and the row fetch need no memory access and follow at once.
+    f32x4 w1r[NR1], w2r[16];
+    load_cols4<NR1>(w1r, W1, H, cc, ks * q1, q1);
+    load_cols4<16>(w2r, W2, H, cc, ks * q2, q2);
     const unsigned long long cap = p.g.capacity;
     const unsigned long long head = p.head;
     const unsigned long long step = p.step;
@@ -339,10 +347,9 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
         p.g.state->head = h;
         p.g.state->size = size;
         p.g.state->total = p.total_after;
-        const unsigned long long t = p.adam_t_after;
-        p.ctr->adam_t = t;
-        p.ctr->c1 = (float)(1.0 - pow((double)p.beta1, (double)t));
-        p.ctr->c2 = (float)(1.0 - pow((double)p.beta2, (double)t));
+        p.ctr->adam_t = p.adam_t_after;
+        p.ctr->c1 = p.c1_after;
+        p.ctr->c2 = p.c2_after;
     }
 
     // sample and gather: one 32-bit word per thread (two passes at most, D <= 64).  A drawn
@@ -382,9 +389,6 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
             reinterpret_cast<unsigned int*>(p.g.rows + slot * p.g.row_bytes)[w] = staged_word(p, k, w);
         }
     }
-    f32x4 w1r[NR1], w2r[16];
-    load_cols4<NR1>(w1r, W1, H, cc, ks * q1, q1);
-    load_cols4<16>(w2r, W2, H, cc, ks * q2, q2);
     const float b1v = tid < H ? p.w[p.ob1 + tid] : 0.f;
     const float b2v = tid < H ? p.w[p.ob2 + tid] : 0.f;
     const float b3v = tid < Ap ? p.w[p.ob3 + tid] : 0.f;
@@ -518,29 +522,31 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     lds_barrier();
 
     // ---- TD target, loss term, dL/dQ
-    if (tid < nrows) {
-        const unsigned int r = tid, i = i0 + r;
-        float best = -INFINITY;
-        for (unsigned int k = 0; k < A; ++k) best = fmaxf(best, Qs[(4 + r) * ldq + k]);
-        unsigned int ai = meta[r * 4 + 0];
-        if (ai >= A) ai = A - 1;
-        meta[r * 4 + 3] = ai;
-        const float q = Qs[r * ldq + ai];
-        const float y = __uint_as_float(meta[r * 4 + 1]) + (meta[r * 4 + 2] ? 0.f : p.gamma * best);
-        const float d = y - q;
-        float li, slope;
-        if (p.loss_kind == RP_MSE || fabsf(d) <= 1.f) {
-            li = 0.5f * d * d;
-            slope = d;
-        } else {
-            li = fabsf(d) - 0.5f;
-            slope = d > 0.f ? 1.f : -1.f;
+    if (wave < nrows) {
+        // wavefront r takes row r: the maximum over actions (A <= 64) across its lanes
+        const unsigned int r = wave, i = i0 + r;
+        const float best = wave_max(lane < A ? Qs[(4 + r) * ldq + lane] : -INFINITY);
+        if (lane == 0) {
+            unsigned int ai = meta[r * 4 + 0];
+            if (ai >= A) ai = A - 1;
+            meta[r * 4 + 3] = ai;
+            const float q = Qs[r * ldq + ai];
+            const float y = __uint_as_float(meta[r * 4 + 1]) + (meta[r * 4 + 2] ? 0.f : p.gamma * best);
+            const float d = y - q;
+            float li, slope;
+            if (p.loss_kind == RP_MSE || fabsf(d) <= 1.f) {
+                li = 0.5f * d * d;
+                slope = d;
+            } else {
+                li = fabsf(d) - 0.5f;
+                slope = d > 0.f ? 1.f : -1.f;
+            }
+            const float gr = -slope / (float)p.B;
+            gs[r] = gr;
+            p.y[i] = y;
+            p.delta[i] = d;
+    p.lossi[i] = li;
         }
-        const float gr = -slope / (float)p.B;
-        gs[r] = gr;
-        p.y[i] = y;
-        p.delta[i] = d;
-        p.lossi[i] = li;
     }
     lds_barrier();
     for (unsigned int e = tid; e < nrows * Ap; e += kRowThreads) {
@@ -800,7 +806,7 @@ hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* bat
         a.step = t->host_step;
         a.size_after = (unsigned int)(after > cap ? cap : after);
         a.total_after = r->total + a.n_append;
-        a.adam_t_after = t->host_adam_t + 1;
+        set_adam_step(a, t->host_adam_t + 1, t->cfg.beta1, t->cfg.beta2);
     }
     a.ctr = t->ctr;
     a.w = t->w;

@@ -698,7 +698,7 @@ void set_payload_args(trainer* t, const Payload& src, unsigned int k) {
         t->row_args.step = t->host_step + k;
         t->row_args.size_after = (unsigned int)(size + n > cap ? cap : size + n);
         t->row_args.total_after = total + n;
-        t->row_args.adam_t_after = t->host_adam_t + k + 1;
+        rp::set_adam_step(t->row_args, t->host_adam_t + k + 1, t->cfg.beta1, t->cfg.beta2);
     } else {
         t->append_args.src = src;
         t->append_args.pos = RingPos{head, size, total};
@@ -1048,7 +1048,7 @@ rp_status train_step_batch(trainer_t* t, const void* s, const void* s_next, cons
         t->row_args.step = t->host_step;
         t->row_args.size_after = (unsigned int)rpl->size;
         t->row_args.total_after = rpl->total;
-        t->row_args.adam_t_after = t->host_adam_t + 1;
+        rp::set_adam_step(t->row_args, t->host_adam_t + 1, t->cfg.beta1, t->cfg.beta2);
         RP_CHECK_HIP(hipGraphExecKernelNodeSetParams(t->graph_exec, t->payload_node[0],
                                                      &t->payload_np[0]));
         RP_CHECK_HIP(hipGraphLaunch(t->graph_exec, st));

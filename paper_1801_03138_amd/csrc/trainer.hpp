@@ -1,6 +1,8 @@
 // Shared definitions of the trainer: element types, device-resident counters, the host handle.
 #pragma once
 
+#include <cmath>
+
 #include "common.hpp"
 
 namespace rp {
@@ -66,6 +68,7 @@ struct RowArgs {
     unsigned long long head, step;
     unsigned int size_after;     // experiences held once this step's append is in
     unsigned long long total_after, adam_t_after;   // experiences ever added / Adam steps, after this step
+    float c1_after, c2_after;    // Adam's bias corrections 1 - beta^t for that step count
     TrainCounters* ctr;
     const float* w;       // padded parameters
     const float* wt;      // the frozen target network's (Q(s', .) is computed with them), or null
@@ -80,6 +83,15 @@ struct RowArgs {
     unsigned char* term;
     unsigned int* idx;
 };
+
+// The Adam step count after a step and its bias corrections (the host mirrors the count, so
+// the device never evaluates a power).
+inline void set_adam_step(RowArgs& a, unsigned long long t_after, float beta1, float beta2) {
+    a.adam_t_after = t_after;
+    a.c1_after = (float)(1.0 - std::pow((double)beta1, (double)t_after));
+    a.c2_after = (float)(1.0 - std::pow((double)beta2, (double)t_after));
+}
+
 
 // Buffers of the mixed-precision step on MFMA (bf16 bit patterns).  "T" = transposed: the
 // batch index is the contiguous one, rows are padded to Bp (a multiple of 128) with zeros.
