@@ -107,8 +107,9 @@ __device__ __forceinline__ void load_cols(float (&wr)[NR], const float* __restri
     }
 }
 
-// The same for the wide split: wr[u] = W[kbeg + u][col .. col+3], col a multiple of 4.
-template <int NR>
+// The same for the wide split: wr[u] = W[kbeg + u][col .. col+3], col a multiple of 4, for
+// u = U0 .. U1-1 (a lane's share can be requested in parts).
+template <int NR, int U0 = 0, int U1 = NR>
 __device__ __forceinline__ void load_cols4(f32x4 (&wr)[NR], const float* __restrict__ W,
                                            unsigned int N, unsigned int col, unsigned int kbeg,
                                            unsigned int kcount) {
@@ -117,7 +118,7 @@ __device__ __forceinline__ void load_cols4(f32x4 (&wr)[NR], const float* __restr
     const unsigned int cb = (col + 3u < N ? col : N - 4u) * 4u;
     const gbytes base = (gbytes)reinterpret_cast<const char*>(W) + (size_t)kb * N * 4u;
 #pragma unroll
-    for (int u = 0; u < NR; ++u) {
+    for (int u = U0; u < U1; ++u) {
         const unsigned int uu = (unsigned int)u < kc ? (unsigned int)u : kc - 1u;
         gbytes rb = base + (size_t)uu * N * 4u;
         asm volatile("" : "+s"(rb));
@@ -287,7 +288,7 @@ __device__ __forceinline__ float sum_part(const float* part, unsigned int slices
     return v;
 }
 
-// BOTH: a frozen target network evaluates s'.  NR1: rows of W1 a lane holds (Dp / 16, 2 or 4).
+// BOTH: a frozen target network evaluates s'.  NR1: rows of W1 a lane holds (Dp / 4, 8 or 16).
 template <bool BOTH, int NR1>
 __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     extern __shared__ float lds[];
@@ -317,19 +318,25 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     // registers take the trained network's share of a layer first (rows 0..3) and are refilled
     // with the target's during those MFMAs.
     constexpr bool both = BOTH;
-    // wide split: K sixteenths of layer 1 / of layers 2 and backward
+    // wide split (layer 2 and backward): K sixteenths
     const unsigned int cc = 4u * lane, ks = wave;
-    const unsigned int q1 = Dp >> 4, q2 = H >> 4;
+    const unsigned int q2 = H >> 4;
+    // layer 1 (a small matrix: sixteen slices of partial sums would cost more than its fetch):
+    // a lane owns one column, wavefront w covers columns 64*(w&3).. and the K quarter w>>2
+    const unsigned int c1 = 64u * (wave & 3u) + lane, k1 = wave >> 2;
+    const unsigned int q1 = Dp >> 2;
     // narrow split
     const unsigned int s3 = H >> 4;                 // K sixteenth of layer 3
 
     // ---- phase 0.  Fetching the weights is what the kernel waits for longest (the rate at which
-    // a compute unit takes in data bounds it), so those requests go out before anything else.
-    // The ring and trainer state before this step come as arguments (the host mirrors them
-    // exactly), so the slot draw and the row fetch need no memory access and follow at once.
-    f32x4 w1r[NR1], w2r[16];
-    load_cols4<NR1>(w1r, W1, H, cc, ks * q1, q1);
-    load_cols4<16>(w2r, W2, H, cc, ks * q2, q2);
+    // a compute unit takes in data bounds it), so the request stream never pauses: layer 1's
+    // weights first, the sampled rows (the ring and trainer state before this step come as
+    // arguments, the host mirrors them exactly, so the draw needs no memory access), the first
+    // half of layer 2's weights, and its second half once the sample is in LDS, behind which
+    // layer 1 runs.
+    float w1r[NR1];
+    f32x4 w2r[16];
+    load_cols<NR1>(w1r, W1, H, c1, k1 * q1, q1);
     const unsigned long long cap = p.g.capacity;
     const unsigned long long head = p.head;
     const unsigned long long step = p.step;
@@ -392,10 +399,14 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     const float b1v = tid < H ? p.w[p.ob1 + tid] : 0.f;
     const float b2v = tid < H ? p.w[p.ob2 + tid] : 0.f;
     const float b3v = tid < Ap ? p.w[p.ob3 + tid] : 0.f;
+    load_cols4<16, 0, 8>(w2r, W2, H, cc, ks * q2, q2);
 
-    for (unsigned int e = tid; e < 8 * ldx; e += kRowThreads) Xs[e] = 0.f;
-    if (tid < 16) meta[tid] = 0;
-    lds_barrier();
+    // zeros wherever no sampled word goes: padding columns, rows past the batch, unused meta
+    for (unsigned int e = tid; e < 8 * ldx; e += kRowThreads) {
+        const unsigned int row = e / ldx, col = e - row * ldx;
+        if (col >= D || (row & 3u) >= nrows) Xs[e] = 0.f;
+    }
+    if (tid < 16 && ((tid >> 2) >= nrows || (tid & 3u) == 3u)) meta[tid] = 0;
 
 #pragma unroll
     for (int pass = 0; pass < 2; ++pass) {
@@ -428,35 +439,34 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     }
     if (tid < Ap) b3s[tid] = b3v;
     lds_barrier();
+    load_cols4<16, 8, 16>(w2r, W2, H, cc, ks * q2, q2);
 
     // ---- layer 1
-    // The wide layers take rows 0..3 (s) and then rows 4..7 (s') with the same accumulators.
-    f32x4 accw[4];
+    f32x4 acc2[2];
     if (!both) {
-        mma_cols4<NR1, 2>(accw, Xs, ldx, ks * q1, q1, w1r);
+        mma_cols<2, NR1>(acc2, Xs, ldx, k1 * q1, q1, w1r);
     } else {
         // the target network's biases travel during the first MFMAs (kept out of the registers
         // that are scarce while W2 is arriving)
         const float b1tv = tid < H ? p.wt[p.ob1 + tid] : 0.f;
         const float b2tv = tid < H ? p.wt[p.ob2 + tid] : 0.f;
         const float b3tv = tid < Ap ? p.wt[p.ob3 + tid] : 0.f;
-        f32x4 lo[1][4];
-        mma_cols4_reload<1, NR1, 2>(lo, Xs, ldx, ks * q1, q1, w1r, p.wt + p.oW1, H, cc, ks * q1, q1);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) accw[j] = lo[0][j];
+        f32x4 lo[1], hi[1];
+        mma_cols_reload<1, NR1>(lo, Xs, ldx, k1 * q1, q1, w1r, p.wt + p.oW1, H, c1, k1 * q1, q1);
+        mma_cols<1, NR1>(hi, Xs + 4 * ldx, ldx, k1 * q1, q1, w1r);
+        acc2[0] = lo[0];
+        acc2[1] = hi[0];
         if (tid < H) {
             b1ts[tid] = b1tv;
             b2ts[tid] = b2tv;
         }
         if (tid < Ap) b3ts[tid] = b3tv;
     }
-    store_part4(part, ks, 8, 0, kChunk, cc, accw);
-    mma_cols4<NR1, 2>(accw, Xs + 4 * ldx, ldx, ks * q1, q1, w1r);
-    store_part4(part, ks, 8, 4, kChunk, cc, accw);
+    store_part<2>(part, k1, kChunk, c1, acc2);
     lds_barrier();
     for (unsigned int e = tid; e < 8 * H; e += kRowThreads) {
         const unsigned int row = e / H, c = e - row * H;
-        float v = sum_part(part, 16, 8, kChunk, row, c) + (both && row >= 4 ? b1ts : b1s)[c];
+        float v = sum_part(part, 4, 8, kChunk, row, c) + (both && row >= 4 ? b1ts : b1s)[c];
         v = v > 0.f ? v : 0.f;
         H1s[row * ldh + c] = v;
         if (row < nrows) p.H1[(size_t)(i0 + row) * H + c] = v;
@@ -501,7 +511,6 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     lds_barrier();
 
     // ---- layer 3 (narrow split: 16 K slices, columns 0..63)
-    f32x4 acc2[2];
     if (!both) {
         mma_cols<2, 16>(acc2, H2s, ldh, wave * s3, s3, w3r);
     } else {
@@ -566,6 +575,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     lds_barrier();
 
     // ---- dZ1 = (dZ2 W2^T) masked by the first ReLU
+    f32x4 accw[4];
     mma_cols4<16, 4>(accw, dZs, ldh, ks * q2, q2, w2r);
     store_part4(part, ks, 4, 0, kChunk, cc, accw);
     lds_barrier();
@@ -770,10 +780,10 @@ bool fused_step_supported(const train_config& cfg, const replay* rp_) {
 // The row kernel's dynamic LDS exceeds the default limit: announced once per process, at trainer
 // creation (outside any stream capture).
 hipError_t fused_init() {
-    const void* kernels[] = {reinterpret_cast<const void*>(fused_rows_kernel<false, 2>),
-                             reinterpret_cast<const void*>(fused_rows_kernel<false, 4>),
-                             reinterpret_cast<const void*>(fused_rows_kernel<true, 2>),
-                             reinterpret_cast<const void*>(fused_rows_kernel<true, 4>)};
+    const void* kernels[] = {reinterpret_cast<const void*>(fused_rows_kernel<false, 8>),
+                             reinterpret_cast<const void*>(fused_rows_kernel<false, 16>),
+                             reinterpret_cast<const void*>(fused_rows_kernel<true, 8>),
+                             reinterpret_cast<const void*>(fused_rows_kernel<true, 16>)};
     for (const void* k : kernels) {
         hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kRowLdsMax);
         if (e != hipSuccess) return e;
@@ -783,10 +793,10 @@ hipError_t fused_init() {
 
 void* fused_rows_func(bool target_network, unsigned int Dp) {
     if (Dp <= 32)
-        return target_network ? reinterpret_cast<void*>(fused_rows_kernel<true, 2>)
-                              : reinterpret_cast<void*>(fused_rows_kernel<false, 2>);
-    return target_network ? reinterpret_cast<void*>(fused_rows_kernel<true, 4>)
-                          : reinterpret_cast<void*>(fused_rows_kernel<false, 4>);
+        return target_network ? reinterpret_cast<void*>(fused_rows_kernel<true, 8>)
+                              : reinterpret_cast<void*>(fused_rows_kernel<false, 8>);
+    return target_network ? reinterpret_cast<void*>(fused_rows_kernel<true, 16>)
+                          : reinterpret_cast<void*>(fused_rows_kernel<false, 16>);
 }
 
 hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* batch, hipStream_t st,
