@@ -666,18 +666,22 @@ __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
     const bool bias_wave = m0 == 0 && wr == 0;
     const bool do_bias = bias_wave && lq == 0;
 
-    // operands of one pass: a[t] = Act[b0 + 4t + lq][m0 + 16 wr + l16], b[t] = Err[same row][nn];
-    // rows past the batch read the last row and count as zero
+    // operands of one pass: a[t] = Act[b0 + 4t + lq][m0 + 16 wr + l16], b[t] = Err[same row][nn].
+    // The address of a step's four rows is a scalar and the lane adds its byte offset within
+    // them.  A step past the batch contributes zeros without touching memory; the one step
+    // that straddles its end (batch not a multiple of 4) reads the last row in the lanes past
+    // it and zeroes them.
     constexpr int kSteps = kTK / 4;
     float a[kSteps], b[kSteps];
-    const float* ap = jb.act + m0 + 16u * wr + l16;
-    const float* bp = jb.err + nn;
-    // byte offsets of the lane within a step's four rows (the step's address is a scalar)
-    const unsigned int la = (lq * jb.lda + m0 + 16u * wr + l16) * 4u, lb = (lq * jb.ldb + nn) * 4u;
+    const unsigned int ca = (m0 + 16u * wr + l16) * 4u, cb = nn * 4u;
+    const unsigned int la = lq * jb.lda * 4u + ca, lb = lq * jb.ldb * 4u + cb;
+    const unsigned int lqc = min(lq, (p.B - 1u) & 3u);
+    const unsigned int la_c = lqc * jb.lda * 4u + ca, lb_c = lqc * jb.ldb * 4u + cb;
     auto load_pass = [&](unsigned int b0) {
+        const gbytes abase = (gbytes)reinterpret_cast<const char*>(jb.act) + (size_t)b0 * jb.lda * 4u;
+        const gbytes bbase = (gbytes)reinterpret_cast<const char*>(jb.err) + (size_t)b0 * jb.ldb * 4u;
         if (b0 + kTK <= p.B) {
-            const gbytes abase = (gbytes)reinterpret_cast<const char*>(jb.act) + (size_t)b0 * jb.lda * 4u;
-            const gbytes bbase = (gbytes)reinterpret_cast<const char*>(jb.err) + (size_t)b0 * jb.ldb * 4u;
+            // a full pass: straight-line code, every request out before the first use
 #pragma unroll
             for (int t = 0; t < kSteps; ++t) {
                 gbytes ra = abase + (size_t)(4 * t) * jb.lda * 4u;
@@ -686,13 +690,28 @@ __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
                 a[t] = *(const __attribute__((address_space(1))) float*)(ra + la);
                 b[t] = *(const __attribute__((address_space(1))) float*)(rb + lb);
             }
-        } else {
+            return;
+        }
 #pragma unroll
-            for (int t = 0; t < kSteps; ++t) {
-                const unsigned int bi = b0 + 4u * t + lq, bc = bi < p.B ? bi : p.B - 1u;
-                const float av = ap[(size_t)bc * jb.lda], bv = bp[(size_t)bc * jb.ldb];
-                a[t] = bi < p.B ? av : 0.f;
-                b[t] = bi < p.B ? bv : 0.f;
+        for (int t = 0; t < kSteps; ++t) {
+            const unsigned int row = b0 + 4u * t;
+            if (row + 4u <= p.B) {
+                gbytes ra = abase + (size_t)(4 * t) * jb.lda * 4u;
+                gbytes rb = bbase + (size_t)(4 * t) * jb.ldb * 4u;
+                asm volatile("" : "+s"(ra), "+s"(rb));
+                a[t] = *(const __attribute__((address_space(1))) float*)(ra + la);
+                b[t] = *(const __attribute__((address_space(1))) float*)(rb + lb);
+            } else if (row < p.B) {
+                gbytes ra = abase + (size_t)(4 * t) * jb.lda * 4u;
+                gbytes rb = bbase + (size_t)(4 * t) * jb.ldb * 4u;
+                asm volatile("" : "+s"(ra), "+s"(rb));
+                const float av = *(const __attribute__((address_space(1))) float*)(ra + la_c);
+                const float bv = *(const __attribute__((address_space(1))) float*)(rb + lb_c);
+                a[t] = row + lq < p.B ? av : 0.f;
+                b[t] = row + lq < p.B ? bv : 0.f;
+            } else {
+                a[t] = 0.f;
+                b[t] = 0.f;
             }
         }
     };
@@ -724,10 +743,19 @@ __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
     f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
     float bsum = 0.f;   // this lane's share of the column sum of Err (rows = lq mod 4)
     for (unsigned int b0 = 0; b0 < p.B; b0 += kTK) {
+        if (b0 + kTK <= p.B) {
 #pragma unroll
-        for (int t = 0; t < kSteps; ++t) {
-            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[t], b[t], acc, 0, 0, 0);
-            if (bias_wave) bsum += b[t];
+            for (int t = 0; t < kSteps; ++t) {
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[t], b[t], acc, 0, 0, 0);
+                if (bias_wave) bsum += b[t];
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < kSteps; ++t) {
+                if (b0 + 4u * t >= p.B) break;   // steps past the batch hold zeros
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[t], b[t], acc, 0, 0, 0);
+                if (bias_wave) bsum += b[t];
+            }
         }
         if (b0 + kTK < p.B) load_pass(b0 + kTK);
     }
