@@ -293,6 +293,19 @@ template <bool BOTH, int NR1>
 __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     extern __shared__ float lds[];
     touch_kernel_args<RowArgs>();
+    if (blockIdx.x * kRows >= p.B) {
+        // the extra workgroup of a replay that samples without duplicates: the next step's slots
+        const unsigned long long ns = p.step + 1;
+        unsigned int* dst = p.pre + ((ns & 1u) ? p.pre_stride : 0u);
+        for (unsigned int i = threadIdx.x; i < p.B; i += kRowThreads)
+            dst[4 + i] = distinct_draw(p.seed, ns, i, p.next_size);
+        if (threadIdx.x == 0) {
+            dst[0] = (unsigned int)ns;
+            dst[1] = (unsigned int)(ns >> 32);
+            dst[2] = p.next_size;
+        }
+        return;
+    }
     const unsigned int tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const unsigned int D = p.D, Dp = p.Dp, H = p.H, A = p.A, Ap = p.Ap;
     const unsigned int ldx = Dp + kPadK, ldh = H + kPadK, ldq = Ap + kPadK;
@@ -373,7 +386,13 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
                 gslot[pass] = i0 + r;
                 gval[pass] = payload_word(p.batch, D, i0 + r, w);
             } else {
-                const unsigned int slot = batch_draw(p.g.sampling, p.seed, step, i0 + r, size);
+                unsigned int slot;
+                const unsigned int* ahead = p.pre ? p.pre + ((step & 1u) ? p.pre_stride : 0u) : nullptr;
+                if (ahead && ahead[0] == (unsigned int)step && ahead[1] == (unsigned int)(step >> 32) &&
+                    ahead[2] == size)
+                    slot = ahead[4 + i0 + r];   // drawn during the previous step
+                else
+                    slot = batch_draw(p.g.sampling, p.seed, step, i0 + r, size);
                 unsigned long long off = (unsigned long long)slot + cap - head;
                 if (off >= cap) off -= cap;
                 gslot[pass] = slot;
@@ -386,7 +405,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     // The last workgroup also writes the new experiences into the ring.  No workgroup reads
     // those slots from the ring in this launch (see above), so this can go out right away and
     // its latency is hidden behind the rest of the kernel.
-    if (blockIdx.x == gridDim.x - 1 && n) {
+    if (i0 + kRows >= p.B && n) {
         const unsigned int rw = p.g.row_bytes >> 2;
         for (unsigned long long e = tid; e < n * rw; e += kRowThreads) {
             const unsigned long long k = e / rw;
@@ -554,7 +573,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
             gs[r] = gr;
             p.y[i] = y;
             p.delta[i] = d;
-    p.lossi[i] = li;
+            p.lossi[i] = li;
         }
     }
     lds_barrier();
@@ -843,6 +862,7 @@ hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* bat
         a.head = r->head;
         a.step = t->host_step;
         a.size_after = (unsigned int)(after > cap ? cap : after);
+        a.next_size = (unsigned int)(after + a.n_append > cap ? cap : after + a.n_append);
         a.total_after = r->total + a.n_append;
         set_adam_step(a, t->host_adam_t + 1, t->cfg.beta1, t->cfg.beta2);
     }
@@ -860,7 +880,12 @@ hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* bat
     a.lossi = t->lossi; a.dQ = t->dQ; a.dZ2 = static_cast<float*>(t->dZ2);
     a.dZ1 = static_cast<float*>(t->dZ1);
     a.act = t->act; a.rew = t->rew; a.term = t->term; a.idx = t->idx;
-    const unsigned int blocks = (t->B + kRows - 1) / kRows;
+    // slots drawn a step ahead: when sampling without duplicates, for batches one workgroup covers
+    // (the launch shape must not depend on the kind of step: graph launches reuse it)
+    const bool ahead = r->cfg.sampling == RP_DISTINCT && t->B <= kRowThreads;
+    a.pre = ahead ? t->pre : nullptr;
+    a.pre_stride = 4u + t->B;
+    const unsigned int blocks = (t->B + kRows - 1) / kRows + (ahead ? 1u : 0u);
     hipError_t e = hipSuccess;
     void* kargs[] = {&a};
     e = hipLaunchKernel(fused_rows_func(t->wt != nullptr, t->Dp), dim3(blocks), dim3(kRowThreads), kargs,

@@ -257,7 +257,7 @@ namespace {
 
 struct WsLayout {
     size_t ctr, w, g, m, v, wt, w2t, wb, wbt, X, act, rew, term, idx, H1, H2, Q, y, delta, lossi, dQ, dZ2, dZ1,
-        total;
+        pre, total;
     // mixed-precision step on MFMA
     size_t W1T, W2b, W2T, W3T, W1Tt, W2Tt, W3Tt, XT, H1T, H2T, dQTh, dQTl, dZ2T, dZ1T, part3, part1, part2;
     unsigned int Dp, Ap, Bp;
@@ -315,6 +315,7 @@ bool ws_layout(const train_config* c, WsLayout* L) {
     L->dQ = take(B * L->Ap * 4);
     L->dZ2 = take(B * H * L->elem);
     L->dZ1 = take(B * H * L->elem);
+    L->pre = take(2 * (4 + B) * 4);
     const bool mixed = c->param_dtype == RP_BF16;
     const size_t Bp = align_up(B, 128), Dx = align_up(D + 1, 32);
     L->Bp = (unsigned int)Bp;
@@ -697,6 +698,7 @@ void set_payload_args(trainer* t, const Payload& src, unsigned int k) {
         t->row_args.head = head;
         t->row_args.step = t->host_step + k;
         t->row_args.size_after = (unsigned int)(size + n > cap ? cap : size + n);
+        t->row_args.next_size = (unsigned int)(size + 2 * n > cap ? cap : size + 2 * n);
         t->row_args.total_after = total + n;
         rp::set_adam_step(t->row_args, t->host_adam_t + k + 1, t->cfg.beta1, t->cfg.beta2);
     } else {
@@ -855,6 +857,7 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
     t->dQ = reinterpret_cast<float*>(ws + L.dQ);
     t->dZ2 = ws + L.dZ2;
     t->dZ1 = ws + L.dZ1;
+    t->pre = reinterpret_cast<unsigned int*>(ws + L.pre);
     t->graph = nullptr;
     t->graph_exec = nullptr;
     t->capture_stream = nullptr;

@@ -69,6 +69,13 @@ struct RowArgs {
     unsigned int size_after;     // experiences held once this step's append is in
     unsigned long long total_after, adam_t_after;   // experiences ever added / Adam steps, after this step
     float c1_after, c2_after;    // Adam's bias corrections 1 - beta^t for that step count
+    // Sampling without duplicates: an extra workgroup draws the NEXT step's slots while this step
+    // runs (a draw is a long chain of dependent Philox blocks).  pre holds two buffers of
+    // pre_stride words, [step lo, step hi, size, -, slots...], used alternately by step parity; a
+    // step takes its slots from there when step and size match and draws them itself otherwise.
+    unsigned int* pre;           // null: no extra workgroup, no look-up
+    unsigned int pre_stride;
+    unsigned int next_size;      // experiences held after the next step's append
     TrainCounters* ctr;
     const float* w;       // padded parameters
     const float* wt;      // the frozen target network's (Q(s', .) is computed with them), or null
@@ -142,6 +149,7 @@ struct trainer {
     float* Q;                        // [2B x Ap]
     float *y, *delta, *lossi, *dQ;   // [B], [B], [B], [B x Ap]
     void *dZ2, *dZ1;                 // [B x H]
+    unsigned int* pre;               // slots drawn ahead, 2 x (4 + B) words
     bool fused;                      // two-kernel step for small fp32 networks
     bool wide;                       // mixed-precision step on MFMA
     rp::WideBuffers wd;

@@ -485,6 +485,35 @@ def test_train_step_with_batches_without_duplicates(B, dtype, H, layered):
     assert pr.gpu_ring.state() == pr.ref_ring.state()
 
 
+def test_without_duplicates_slots_drawn_ahead(B):
+    """The two-kernel step draws the next step's slots while a step runs, for the ring size the
+    next step is expected to see.  Whatever happens between two steps, the slots are those of
+    the step's own (seed, step, size): consecutive steps (drawn ahead), appends from outside
+    between steps while the ring fills (size differs from the expected one: drawn again), steps
+    in a full ring, and a step after one that was refused."""
+    rows = synth.experiences(700, 27, 30, 0.05, seed=31)
+    pr = Pair(B, capacity=256, D=27, H=64, A=30, batch=48, burn_in=10, seed=12, appends=1,
+              distinct=True)
+    at = 0
+    for k in range(40):                      # refused until 48 experiences are held
+        assert pr.step(synth.take(rows, at, at + 1), compare=True) == B.RP_SKIPPED_BURN_IN
+        at += 1
+    pr.append_only(synth.take(rows, at, at + 20)); at += 20
+    for k in range(60):
+        assert pr.step(synth.take(rows, at, at + 1), compare=True) == 0
+        at += 1
+        if k % 7 == 3 and k < 40:            # the ring grows behind the trainer's back
+            n = 1 + k % 5
+            pr.append_only(synth.take(rows, at, at + n), device_src=bool(k % 2)); at += n
+    for n in (200, 100):                                          # full, wrapped
+        pr.append_only(synth.take(rows, at, at + n)); at += n
+    for k in range(20):
+        assert pr.step(synth.take(rows, at, at + 1), compare=True) == 0
+        at += 1
+        assert len(set(pr.trainer.last()["idx"].tolist())) == 48
+    assert pr.gpu_ring.state() == pr.ref_ring.state()
+
+
 @pytest.mark.parametrize("dtype,H,batch,layered,target_sync,kernels", [
     ("f32", 64, 50, False, 0, 3), ("f32", 64, 50, True, 0, 16), ("f32", 128, 33, False, 5, 3),
     ("f32", 128, 33, True, 5, 19),
