@@ -187,30 +187,35 @@ __device__ __forceinline__ void mma_cols_reload(f32x4 (&acc)[MG], const float* a
     }
 }
 
-// Wide split, four rows of activations: acc[j][v] += sum_{u < kcount} act[v][kbeg + u] * wr[u][j],
-// j = 0..3.  The activations are read VEC (2 or 4) consecutive k at a time; kcount is a
+// Wide split: acc[mg][j][v] += sum_{u < kcount} act[mg*4 + v][kbeg + u] * wr[u][j], j = 0..3.  The activations are read VEC (2 or 4) consecutive k at a time; kcount is a
 // multiple of VEC.
 template <int VEC> struct ActVec;
 template <> struct ActVec<2> { typedef float type __attribute__((ext_vector_type(2))); };
 template <> struct ActVec<4> { typedef f32x4 type; };
 
-template <int NR, int VEC>
-__device__ __forceinline__ void mma_cols4(f32x4 (&acc)[4], const float* act, unsigned int ldk,
+template <int MG, int NR, int VEC>
+__device__ __forceinline__ void mma_cols4(f32x4 (&acc)[MG][4], const float* act, unsigned int ldk,
                                           unsigned int kbeg, unsigned int kcount,
                                           const f32x4 (&wr)[NR]) {
+    // MG groups of four activation rows (rows mg*4 .. mg*4+3 of act) share the weights
     typedef typename ActVec<VEC>::type avec;
     const float* ap = act + (threadIdx.x & 3u) * ldk + kbeg;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int mg = 0; mg < MG; ++mg)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[mg][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int u0 = 0; u0 < NR; u0 += VEC) {
         if ((unsigned int)u0 < kcount) {
-            const avec a = *reinterpret_cast<const avec*>(ap + u0);
 #pragma unroll
-            for (int u = 0; u < VEC; ++u)
+            for (int mg = 0; mg < MG; ++mg) {
+                const avec a = *reinterpret_cast<const avec*>(ap + (size_t)mg * 4 * ldk + u0);
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[j] = __builtin_amdgcn_mfma_f32_4x4x1f32(a[u], wr[u0 + u][j], acc[j], 0, 0, 0);
+                for (int u = 0; u < VEC; ++u)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        acc[mg][j] = __builtin_amdgcn_mfma_f32_4x4x1f32(a[u], wr[u0 + u][j], acc[mg][j], 0, 0, 0);
+            }
         }
     }
 }
@@ -492,18 +497,21 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     }
     lds_barrier();
 
-    // ---- layer 2; its registers are then refilled with W2^T (backward)
+    // ---- layer 2.  From here on the fetch of W2^T (for the backward pass, into the registers
+    // that layer 2 frees) is the long pole: a wavefront that requests its share stalls for about
+    // half a microsecond while its SIMD's load path is busy, so each wavefront does it in a
+    // phase in which the others have all the work: wavefronts 8..15 during layer 2's sums
+    // (wavefronts 0..7), wavefronts 0..7 during layer 3's sums and the TD phase (12..15).
     if (!both) {
-        // one pass over the weights for all eight rows, so that the refill starts at once
         f32x4 acc8[2][4];
-        mma_cols4_reload<2, 16, 4>(acc8, H1s, ldh, ks * q2, q2, w2r, p.w2t, H, cc, ks * q2, q2);
+        mma_cols4<2, 16, 4>(acc8, H1s, ldh, ks * q2, q2, w2r);
         store_part4(part, ks, 8, 0, kChunk, cc, acc8[0]);
         store_part4(part, ks, 8, 4, kChunk, cc, acc8[1]);
     } else {
         f32x4 acc4[1][4];
         mma_cols4_reload<1, 16, 4>(acc4, H1s, ldh, ks * q2, q2, w2r, p.wt + p.oW2, H, cc, ks * q2, q2);
         store_part4(part, ks, 8, 0, kChunk, cc, acc4[0]);
-        mma_cols4_reload<1, 16, 4>(acc4, H1s + 4 * ldh, ldh, ks * q2, q2, w2r, p.w2t, H, cc, ks * q2, q2);
+        mma_cols4<1, 16, 4>(acc4, H1s + 4 * ldh, ldh, ks * q2, q2, w2r);
         store_part4(part, ks, 8, 4, kChunk, cc, acc4[0]);
     }
     // The accumulators are free: layer 3's weights are requested, and ...
@@ -520,12 +528,20 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
         }
     }
     lds_barrier();
-    for (unsigned int e = tid; e < 8 * H; e += kRowThreads) {
-        const unsigned int row = e / H, c = e - row * H;
-        float v = sum_part(part, 16, 8, kChunk, row, c) + (both && row >= 4 ? b2ts : b2s)[c];
-        v = v > 0.f ? v : 0.f;
-        H2s[row * ldh + c] = v;
-        if (row < nrows) p.H2[(size_t)(i0 + row) * H + c] = v;
+    if (wave < 8) {
+        // four adjacent columns of one row per thread, 16-byte LDS accesses
+        for (unsigned int e = tid; e < 2 * H; e += 512u) {
+            const unsigned int row = e / (H >> 2), c = (e - row * (H >> 2)) * 4u;
+            f32x4 v = *reinterpret_cast<const f32x4*>((both && row >= 4 ? b2ts : b2s) + c);
+            for (unsigned int sl = 0; sl < 16; ++sl)
+                v += *reinterpret_cast<const f32x4*>(part + ((size_t)(sl * 8 + row)) * kChunk + c);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = v[j] > 0.f ? v[j] : 0.f;
+            *reinterpret_cast<f32x4*>(H2s + row * ldh + c) = v;
+            if (row < nrows) *reinterpret_cast<f32x4*>(p.H2 + (size_t)(i0 + row) * H + c) = v;
+        }
+    } else {
+        load_cols4<16>(w2r, p.w2t, H, cc, ks * q2, q2);
     }
     lds_barrier();
 
@@ -541,45 +557,53 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     }
     store_part<2>(part, wave, 64, lane, acc2);
     lds_barrier();
-    for (unsigned int e = tid; e < 8 * Ap; e += kRowThreads) {
-        const unsigned int row = e / Ap, c = e - row * Ap, r = row & 3u;
-        const float v = sum_part(part, 16, 8, 64, row, c) + (both && row >= 4 ? b3ts : b3s)[c];
-        Qs[row * ldq + c] = v;
-        if (r < nrows) p.Q[((size_t)(row < 4 ? 0 : p.B) + i0 + r) * Ap + c] = v;
-    }
-    lds_barrier();
 
-    // ---- TD target, loss term, dL/dQ
-    if (wave < nrows) {
-        // wavefront r takes row r: the maximum over actions (A <= 64) across its lanes
-        const unsigned int r = wave, i = i0 + r;
-        const float best = wave_max(lane < A ? Qs[(4 + r) * ldq + lane] : -INFINITY);
-        if (lane == 0) {
-            unsigned int ai = meta[r * 4 + 0];
-            if (ai >= A) ai = A - 1;
-            meta[r * 4 + 3] = ai;
-            const float q = Qs[r * ldq + ai];
-            const float y = __uint_as_float(meta[r * 4 + 1]) + (meta[r * 4 + 2] ? 0.f : p.gamma * best);
-            const float d = y - q;
-            float li, slope;
-            if (p.loss_kind == RP_MSE || fabsf(d) <= 1.f) {
-                li = 0.5f * d * d;
-                slope = d;
-            } else {
-                li = fabsf(d) - 0.5f;
-                slope = d > 0.f ? 1.f : -1.f;
-            }
-            const float gr = -slope / (float)p.B;
-            gs[r] = gr;
-            p.y[i] = y;
-            p.delta[i] = d;
-            p.lossi[i] = li;
+    // ---- Q values (sums of the partial products), TD target, loss term, dL/dQ: wavefront
+    // 12 + r takes rows r (s) and 4 + r (s'), one action per lane (A <= 64).  What it has to
+    // store to global memory waits until the next phase: right now the load path is busy with
+    // the other wavefronts' requests and a store would queue up behind them.
+    float td_qs = 0.f, td_qn = 0.f, td_y = 0.f, td_d = 0.f, td_li = 0.f, td_gr = 0.f;
+    unsigned int td_ai = 0;
+    if (wave >= 12) {
+        const unsigned int r = wave - 12u;
+        if (lane < Ap) {
+            td_qs = sum_part(part, 16, 8, 64, r, lane) + b3s[lane];
+            td_qn = sum_part(part, 16, 8, 64, 4 + r, lane) + (both ? b3ts : b3s)[lane];
         }
+        if (r < nrows) {
+            const float best = wave_max(lane < A ? td_qn : -INFINITY);
+            td_ai = meta[r * 4 + 0];
+            if (td_ai >= A) td_ai = A - 1;
+            const float q = __shfl(td_qs, (int)td_ai, 64);
+            td_y = __uint_as_float(meta[r * 4 + 1]) + (meta[r * 4 + 2] ? 0.f : p.gamma * best);
+            td_d = td_y - q;
+            float slope;
+            if (p.loss_kind == RP_MSE || fabsf(td_d) <= 1.f) {
+                td_li = 0.5f * td_d * td_d;
+                slope = td_d;
+            } else {
+                td_li = fabsf(td_d) - 0.5f;
+                slope = td_d > 0.f ? 1.f : -1.f;
+            }
+            td_gr = -slope / (float)p.B;
+            if (lane == 0) gs[r] = td_gr;
+        }
+    } else if (wave < 8) {
+        load_cols4<16>(w2r, p.w2t, H, cc, ks * q2, q2);
     }
     lds_barrier();
-    for (unsigned int e = tid; e < nrows * Ap; e += kRowThreads) {
-        const unsigned int r = e / Ap, c = e - r * Ap;
-        p.dQ[(size_t)(i0 + r) * Ap + c] = (c == meta[r * 4 + 3]) ? gs[r] : 0.f;
+    if (wave >= 12 && wave - 12u < nrows) {
+        const unsigned int i = i0 + wave - 12u;
+        if (lane < Ap) {
+            p.Q[(size_t)i * Ap + lane] = td_qs;
+            p.Q[((size_t)p.B + i) * Ap + lane] = td_qn;
+            p.dQ[(size_t)i * Ap + lane] = lane == td_ai ? td_gr : 0.f;
+        }
+        if (lane == 0) {
+            p.y[i] = td_y;
+            p.delta[i] = td_d;
+            p.lossi[i] = td_li;
+        }
     }
     // dZ2[r][k] = dQ[r][a_r] * W3[k][a_r] * 1[H2[r][k] > 0]
     {
@@ -594,9 +618,9 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     lds_barrier();
 
     // ---- dZ1 = (dZ2 W2^T) masked by the first ReLU
-    f32x4 accw[4];
-    mma_cols4<16, 4>(accw, dZs, ldh, ks * q2, q2, w2r);
-    store_part4(part, ks, 4, 0, kChunk, cc, accw);
+    f32x4 accw[1][4];
+    mma_cols4<1, 16, 4>(accw, dZs, ldh, ks * q2, q2, w2r);
+    store_part4(part, ks, 4, 0, kChunk, cc, accw[0]);
     lds_barrier();
     for (unsigned int e = tid; e < nrows * H; e += kRowThreads) {
         const unsigned int r = e / H, c = e - r * H;
