@@ -11,7 +11,7 @@ tolerance, so in fp32 their bound is 10x (m: 10x, v: 20x) the Q bound; a wrong i
 operand in the backward pass is off by O(1), far outside either.
 
 The ReLU derivative is a step function: where a hidden pre-activation lies within the rounding
-error of its own fp32 sum of zero (|z| <= 64 * 2^-24 * (sum_k |h_k w_k| + |b|)), the two sides may
+error of its own fp32 sum of zero (|z| <= 16 * 2^-24 * (sum_k |h_k w_k| + |b|)), the two sides may
 land on different sides of the kink, and one hidden unit of one sample then enters the backward
 pass on one side only.  A step whose backward quantities disagree AND that has such a unit in
 the oracle's forward pass is counted in Pair.kink_steps and its backward comparison is dropped
@@ -89,7 +89,7 @@ class Pair:
         W1, b1 = p[:D * H].reshape(D, H), p[D * H:D * H + H]
         o = D * H + H
         W2, b2 = p[o:o + H * H].reshape(H, H), p[o + H * H:o + H * H + H]
-        u = 64.0 * 2.0 ** -24
+        u = 16.0 * 2.0 ** -24
         z1 = S @ W1 + b1
         if (np.abs(z1) <= u * (np.abs(S) @ np.abs(W1) + np.abs(b1))).any():
             return True
