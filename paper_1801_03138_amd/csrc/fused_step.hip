@@ -655,32 +655,58 @@ struct WArgs {
     TrainCounters* ctr;
     const float* lossi;
     unsigned int grad_only_job;   // a job whose update another kernel makes (dueling head), or ~0
+    // A dueling head of up to 32 actions is updated here: the tiles of job fold_job (else ~0)
+    // hold the gradient of the plain output layer the head amounts to, one whole row of it per
+    // 32 lanes, which is all the head's own update needs.  The head's parameters are rows of
+    // 1 + head_A entries (state value first) starting at entry head_off of w, g, m, v, wt.
+    unsigned int fold_job, head_A, head_off;
     float* wt;                    // frozen target network, synced when Adam's t is a multiple of
     unsigned int sync_every;      // sync_every (0: never)
 };
 
 constexpr unsigned int kTM = 32, kTN = 32, kTK = 128;
 
+// Sum over the 16 lanes of a DPP row (lanes 16 q .. 16 q + 15), returned in each of them.
+__device__ __forceinline__ float row16_sum(float v) {
+    // row_ror:8, 4, 2, 1 -- rotations within a row of 16 lanes
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x128, 0xf, 0xf, false));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x124, 0xf, 0xf, false));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x122, 0xf, 0xf, false));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x121, 0xf, 0xf, false));
+    return v;
+}
+
+// Element k of a parameter array, addressed as the array's (uniform) base plus a 32-bit byte
+// offset: one address register per access instead of 64-bit arithmetic per lane.  (The arrays
+// are far smaller than 4 GiB.)
+__device__ __forceinline__ float ldw(const float* base, unsigned int k) {
+    return *(const __attribute__((address_space(1))) float*)((gbytes)reinterpret_cast<const char*>(base) + k * 4u);
+}
+__device__ __forceinline__ void stw(float* base, unsigned int k, float v) {
+    typedef __attribute__((address_space(1))) char* gwbytes;
+    *(__attribute__((address_space(1))) float*)((gwbytes)reinterpret_cast<char*>(base) + k * 4u) = v;
+}
+
 // One optimizer update of parameter k with gradient gk, from values loaded earlier.
 // r1 = 1 / (1 - beta1^t), r2 = 1 / (1 - beta2^t); sync: this step also refreshes the target network.
 __device__ __forceinline__ float opt_apply(const WArgs& p, unsigned int k, float gk, float wk,
                                            float mk, float vk, float r1, float r2, bool grad_only,
                                            bool sync) {
-    p.g[k] = gk;
+    stw(p.g, k, gk);
     if (grad_only) return wk;
     if (p.opt == RP_SGD) {
         wk -= p.lr * gk;
     } else {
         mk = p.beta1 * mk + (1.f - p.beta1) * gk;
         vk = p.beta2 * vk + (1.f - p.beta2) * gk * gk;
-        p.m[k] = mk;
-        p.v[k] = vk;
+        stw(p.m, k, mk);
+        stw(p.v, k, vk);
         // hardware square root and reciprocal (1 ulp each): the quotient is good to a few parts
         // in 1e7, far inside what the update's own rounding leaves
         wk -= p.lr * (mk * r1) * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(vk * r2) + p.eps);
     }
-    p.w[k] = wk;
-    if (sync) p.wt[k] = wk;
+    stw(p.w, k, wk);
+    if (sync) stw(p.wt, k, wk);
     return wk;
 }
 
@@ -762,19 +788,30 @@ __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
 
     // bias corrections and the optimizer state of this lane's outputs
     const float c1 = p.ctr->c1, c2 = p.ctr->c2;
-    const bool adam = p.opt != RP_SGD;
     const bool sync = p.wt && p.sync_every && p.ctr->adam_t % p.sync_every == 0;
+    // (dueling head updated here: the lane of action nn holds the state of that action's
+    // advantage weights instead; the state-value weight of row 4 lq + l16 of the quarter, and
+    // of the bias row in lane 4, belongs to lanes l16 = 0 .. 4 of the left wavefronts)
+    const bool fold = j == p.fold_job;
+    const unsigned int O = p.head_A + 1u;
+    const bool colv = nn < p.head_A;
+    const bool val_lane = fold && wc == 0 && (l16 < 4 || (l16 == 4 && do_bias));
+    // (every load below is unconditional, from an index that is valid in every lane: a branch
+    // here would make the wavefront wait for the operand loads in flight)
     float w_old[4], m_old[4], v_old[4];
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
-        const unsigned int k = jb.w_off + (mm + v) * jb.ldw + nn;
-        w_old[v] = p.w[k];
-        m_old[v] = adam ? p.m[k] : 0.f;
-        v_old[v] = adam ? p.v[k] : 0.f;
+        const unsigned int k = fold ? p.head_off + (mm + v) * O + (colv ? 1u + nn : 0u)
+                                    : jb.w_off + (mm + v) * jb.ldw + nn;
+        w_old[v] = ldw(p.w, k);
+        m_old[v] = ldw(p.m, k);
+        v_old[v] = ldw(p.v, k);
     }
-    const float wb_old = do_bias ? p.w[jb.b_off + nn] : 0.f;
-    const float mb_old = do_bias && adam ? p.m[jb.b_off + nn] : 0.f;
-    const float vb_old = do_bias && adam ? p.v[jb.b_off + nn] : 0.f;
+    const unsigned int hbias = p.head_off + jb.M * O;
+    const unsigned int kb = fold ? hbias + (colv ? 1u + nn : 0u) : jb.b_off + nn;
+    const float wb_old = ldw(p.w, kb), mb_old = ldw(p.m, kb), vb_old = ldw(p.v, kb);
+    const unsigned int kval = !val_lane ? kb : l16 < 4 ? p.head_off + (mm + l16) * O : hbias;
+    const float vw_old = ldw(p.w, kval), vm_old = ldw(p.m, kval), vv_old = ldw(p.v, kval);
 
     // the last workgroup (never on a tile row with a bias) also reduces the per-sample losses:
     // fetch them now
@@ -807,17 +844,99 @@ __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
         bsum += __shfl_xor(bsum, 32);
     }
 
-    const float r1 = 1.f / c1, r2 = 1.f / c2;
-    const bool grad_only = j == p.grad_only_job;
-    float w_new[4];
+    // The optimizer state requested before the products has long arrived.  Naming every value
+    // as an operand here makes the compiler wait for them now, before the first store: vmcnt
+    // counts stores as well and retires in order, so a wait for one of these loads placed among
+    // the stores below would also wait for the stores ahead of it to complete.
 #pragma unroll
-    for (int v = 0; v < 4; ++v)
-        w_new[v] = opt_apply(p, jb.w_off + (mm + v) * jb.ldw + nn, acc[v], w_old[v], m_old[v],
-                             v_old[v], r1, r2, grad_only, sync);
-    if (jb.wT)
-        *reinterpret_cast<float4*>(jb.wT + (size_t)nn * jb.M + mm) =
-            make_float4(w_new[0], w_new[1], w_new[2], w_new[3]);
-    if (do_bias) opt_apply(p, jb.b_off + nn, bsum, wb_old, mb_old, vb_old, r1, r2, grad_only, sync);
+    for (int v = 0; v < 4; ++v) asm volatile("" ::"v"(w_old[v]), "v"(m_old[v]), "v"(v_old[v]));
+    asm volatile("" ::"v"(wb_old), "v"(mb_old), "v"(vb_old), "v"(vw_old), "v"(vm_old), "v"(vv_old));
+    const float r1 = 1.f / c1, r2 = 1.f / c2;
+    if (fold) {
+        // Dueling head (Q = V + A - mean A).  This lane holds dW[k][nn] of the plain layer for
+        // hidden units k = mm .. mm+3 (entries 0..3) and, on the bias row, for k = H (entry 4).
+        // The head's gradients are dV[k] = sum_a dW[k][a] and dA[k][a] = dW[k][a] - mean_a' dW[k][a'],
+        // kept to the weights the head has (a gradient of zero where it has none: moments and
+        // weight stay as they are); after their optimizer step the plain layer's row is rebuilt
+        // as V[k] + A[k][a] - mean_a' A[k][a'].  A row's 32 columns sit in 16 lanes of each of the
+        // two wavefronts of a tile row, so both sums take a lane reduction and a few words of LDS.
+        __shared__ float hsum[2][2][17][2];   // [gradient / new weights][wr][row][wc]
+        __shared__ float hval[2][17];         // new state-value weights [wr][row]
+        const float inv_A = 1.f / (float)p.head_A;
+        const unsigned int H = jb.M;
+        const float x[5] = {acc[0], acc[1], acc[2], acc[3], bias_wave ? bsum : 0.f};
+        float red[5];
+#pragma unroll
+        for (int i = 0; i < 5; ++i) red[i] = row16_sum(colv ? x[i] : 0.f);
+        if (l16 == 0) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) hsum[0][wr][4u * lq + i][wc] = red[i];
+            if (lq == 0) hsum[0][wr][16][wc] = red[4];
+        }
+        lds_barrier();   // (not __syncthreads: that would also wait for global stores in flight)
+        float gsum[5];
+#pragma unroll
+        for (int i = 0; i < 5; ++i) {
+            const unsigned int slot = i < 4 ? 4u * lq + i : 16u;
+            gsum[i] = hsum[0][wr][slot][0] + hsum[0][wr][slot][1];
+        }
+        float a_new[5];   // this lane's new advantage weight (0 where the head has none)
+#pragma unroll
+        for (int i = 0; i < 5; ++i) a_new[i] = 0.f;
+        if (colv) {
+#pragma unroll
+            for (int i = 0; i < 5; ++i) {
+                if (i == 4 && !do_bias) continue;
+                const unsigned int k = i < 4 ? mm + i : H;
+                const bool a_on = head_connected(H, k, 1);
+                const float wn = opt_apply(p, p.head_off + k * O + 1u + nn,
+                                           a_on ? x[i] - gsum[i] * inv_A : 0.f,
+                                           i < 4 ? w_old[i & 3] : wb_old, i < 4 ? m_old[i & 3] : mb_old,
+                                           i < 4 ? v_old[i & 3] : vb_old, r1, r2, false, sync);
+                a_new[i] = a_on ? wn : 0.f;
+            }
+        }
+        if (val_lane) {
+            const unsigned int k = l16 < 4 ? mm + l16 : H;
+            const bool v_on = head_connected(H, k, 0);
+            const unsigned int slot = l16 < 4 ? 4u * lq + l16 : 16u;
+            const float gv = hsum[0][wr][slot][0] + hsum[0][wr][slot][1];
+            const float wn = opt_apply(p, kval, v_on ? gv : 0.f, vw_old, vm_old, vv_old, r1, r2, false, sync);
+            hval[wr][slot] = v_on ? wn : 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < 5; ++i) red[i] = row16_sum(a_new[i]);
+        if (l16 == 0) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) hsum[1][wr][4u * lq + i][wc] = red[i];
+            if (lq == 0) hsum[1][wr][16][wc] = red[4];
+        }
+        lds_barrier();
+        if (colv) {
+#pragma unroll
+            for (int i = 0; i < 5; ++i) {
+                if (i == 4 && !do_bias) continue;
+                const unsigned int slot = i < 4 ? 4u * lq + i : 16u;
+                const unsigned int k = i < 4 ? mm + i : H;
+                const float amean = (hsum[1][wr][slot][0] + hsum[1][wr][slot][1]) * inv_A;
+                const float e = hval[wr][slot] + a_new[i] - amean;
+                const unsigned int eff = (i < 4 ? jb.w_off + k * jb.ldw : jb.b_off) + nn;
+                stw(p.w, eff, e);
+                if (sync) stw(p.wt, eff, e);
+            }
+        }
+    } else {
+        const bool grad_only = j == p.grad_only_job;
+        float w_new[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            w_new[v] = opt_apply(p, jb.w_off + (mm + v) * jb.ldw + nn, acc[v], w_old[v], m_old[v],
+                                 v_old[v], r1, r2, grad_only, sync);
+        if (jb.wT)
+            *reinterpret_cast<float4*>(jb.wT + (size_t)nn * jb.M + mm) =
+                make_float4(w_new[0], w_new[1], w_new[2], w_new[3]);
+        if (do_bias) opt_apply(p, jb.b_off + nn, bsum, wb_old, mb_old, vb_old, r1, r2, grad_only, sync);
+    }
     if (loss_block && tid < 64) {
         const float s = wave_sum(loss_part);
         if (tid == 0) {
@@ -936,14 +1055,19 @@ hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* bat
     w.w = t->w; w.g = t->g; w.m = t->m; w.v = t->v;
     w.opt = t->cfg.opt; w.lr = t->cfg.lr; w.beta1 = t->cfg.beta1; w.beta2 = t->cfg.beta2;
     w.eps = t->cfg.eps; w.ctr = t->ctr; w.lossi = t->lossi;
-    w.grad_only_job = t->dueling ? 2u : ~0u;
+    // the head of up to 32 actions (one tile column) is updated by job 2's own tiles
+    const bool fold = t->dueling && t->Ap == kTN;
+    w.grad_only_job = t->dueling && !fold ? 2u : ~0u;
+    w.fold_job = fold ? 2u : ~0u;
+    w.head_A = t->cfg.num_actions;
+    w.head_off = (unsigned int)t->n_padded;
     w.wt = t->wt;
     w.sync_every = t->cfg.target_sync;
     hipLaunchKernelGGL(fused_weights_kernel, dim3(nt), dim3(kThreads), 0, st, w);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     unsigned int nh = 0;
-    e = enqueue_head_update(t, st, &nh);
+    if (!fold) e = enqueue_head_update(t, st, &nh);
     if (count) *count = 2 + nh;
     return e;
 }

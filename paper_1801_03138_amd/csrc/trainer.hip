@@ -342,13 +342,6 @@ bool ws_layout(const train_config* c, WsLayout* L) {
     return true;
 }
 
-// Whether the dueling head has a weight from hidden unit k (k = H: the bias) to output o
-// (0 = state value, fed by units 0 .. H/2-1; 1 + a = advantage of action a, fed by the rest).
-__host__ __device__ inline bool head_connected(unsigned int H, unsigned int k, unsigned int o) {
-    if (k >= H) return true;
-    return o == 0 ? k < H / 2 : k >= H / 2;
-}
-
 // external [W1 b1 W2 b2 W3 b3] <-> device order: padded arrays (zero rows / columns as padding)
 // and, for the dueling head, its own parameters behind them.  `weights`: also fill positions
 // W3 / b3 of the padded part with the plain output layer the dueling head amounts to.

@@ -43,6 +43,13 @@ struct TrainCounters {
 static_assert(sizeof(TrainCounters) == 64, "one line");
 
 
+// Whether the dueling head has a weight from hidden unit k (k = H: the bias) to output o
+// (0 = state value, fed by units 0 .. H/2-1; 1 + a = advantage of action a, fed by the rest).
+__host__ __device__ inline bool head_connected(unsigned int H, unsigned int k, unsigned int o) {
+    if (k >= H) return true;
+    return o == 0 ? k < H / 2 : k >= H / 2;
+}
+
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));

@@ -514,14 +514,18 @@ def test_without_duplicates_slots_drawn_ahead(B):
     assert pr.gpu_ring.state() == pr.ref_ring.state()
 
 
-@pytest.mark.parametrize("dtype,H,batch,layered,target_sync,kernels", [
-    ("f32", 64, 50, False, 0, 3), ("f32", 64, 50, True, 0, 16), ("f32", 128, 33, False, 5, 3),
-    ("f32", 128, 33, True, 5, 19),
-    ("bf16", 128, 200, False, 0, 9), ("bf16", 64, 256, False, 5, 9), ("bf16", 128, 96, True, 0, 16)])
-def test_dueling_head(B, dtype, H, batch, layered, target_sync, kernels):
+@pytest.mark.parametrize("dtype,H,batch,layered,target_sync,kernels,A", [
+    ("f32", 64, 50, False, 0, 2, 30), ("f32", 64, 50, True, 0, 16, 30), ("f32", 128, 33, False, 5, 2, 30),
+    ("f32", 128, 33, True, 5, 19, 30),
+    ("f32", 256, 130, False, 3, 2, 32), ("f32", 64, 7, False, 0, 2, 2), ("f32", 128, 64, False, 4, 2, 5),
+    ("f32", 64, 50, False, 0, 3, 40), ("f32", 128, 33, False, 5, 3, 64),
+    ("bf16", 128, 200, False, 0, 9, 30), ("bf16", 64, 256, False, 5, 9, 30),
+    ("bf16", 128, 96, True, 0, 16, 30)])
+def test_dueling_head(B, dtype, H, batch, layered, target_sync, kernels, A):
     """Q = V + A - mean A with a value stream and an advantage stream (Deep Q-Network Model), on
-    every kind of step, alone and together with the frozen target network."""
-    A = 30
+    every kind of step, alone and together with the frozen target network.  In the two-kernel
+    step the weights kernel itself updates a head of up to 32 actions; wider heads get a kernel
+    of their own."""
     rows = synth.experiences(300, 27, A, 0.05, seed=37, state_dtype=dtype)
     pr = Pair(B, capacity=256, D=27, H=H, A=A, batch=batch, burn_in=60, seed=6, dtype=dtype,
               appends=2, layered=layered, target_sync=target_sync, dueling=True, lr=1e-3)
