@@ -718,6 +718,8 @@ __device__ __forceinline__ float opt_apply(const WArgs& p, unsigned int k, float
 // memory straight into the registers the instruction reads them from (lane l: batch row
 // 4t + l/16 of step t, column l%16 of the quarter -- 64-byte runs), all 64 loads of a pass
 // requested before the first use; nothing passes through LDS and no wavefront waits for another.
+// FOLD: the variant that also updates a dueling head (the tiles of job fold_job).
+template <bool FOLD>
 __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
     const unsigned int tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const unsigned int l16 = lane & 15u, lq = lane >> 4;
@@ -792,7 +794,7 @@ __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
     // (dueling head updated here: the lane of action nn holds the state of that action's
     // advantage weights instead; the state-value weight of row 4 lq + l16 of the quarter, and
     // of the bias row in lane 4, belongs to lanes l16 = 0 .. 4 of the left wavefronts)
-    const bool fold = j == p.fold_job;
+    const bool fold = FOLD && j == p.fold_job;
     const unsigned int O = p.head_A + 1u;
     const bool colv = nn < p.head_A;
     const bool val_lane = fold && wc == 0 && (l16 < 4 || (l16 == 4 && do_bias));
@@ -1063,7 +1065,10 @@ hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* bat
     w.head_off = (unsigned int)t->n_padded;
     w.wt = t->wt;
     w.sync_every = t->cfg.target_sync;
-    hipLaunchKernelGGL(fused_weights_kernel, dim3(nt), dim3(kThreads), 0, st, w);
+    if (fold)
+        hipLaunchKernelGGL(fused_weights_kernel<true>, dim3(nt), dim3(kThreads), 0, st, w);
+    else
+        hipLaunchKernelGGL(fused_weights_kernel<false>, dim3(nt), dim3(kThreads), 0, st, w);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     unsigned int nh = 0;
