@@ -20,7 +20,8 @@ namespace {
 
 constexpr unsigned int kThreads = kTrainThreads;   // weight kernel
 constexpr unsigned int kRowThreads = 1024;         // row kernel: 16 wavefronts
-constexpr unsigned int kRows = 4;          // experiences per workgroup of the row kernel
+constexpr unsigned int kRows = 4;          // experiences per workgroup of the row kernel ...
+constexpr unsigned int kSmallBatch = 256;  // ... and 2 for batches up to this size (no target network)
 constexpr unsigned int kChunk = 256;       // output columns the workgroup covers per pass
 constexpr size_t kRowLdsMax = 160 * 1024;  // dynamic LDS the row kernel may ask for (all of a CU's)
 constexpr unsigned int kPadK = 4;          // LDS row padding (floats) against bank conflicts
@@ -294,11 +295,18 @@ __device__ __forceinline__ float sum_part(const float* part, unsigned int slices
 }
 
 // BOTH: a frozen target network evaluates s'.  NR1: rows of W1 a lane holds (Dp / 4, 8 or 16).
-template <bool BOTH, int NR1>
+// R: experiences per workgroup, 4 or 2.  A workgroup's 2 R rows (R states s, then R states s')
+// form R / 2 groups of four MFMA rows.  Every workgroup fetches all the weights whatever R is,
+// so R = 2 halves a workgroup's products at twice the workgroups: the choice for batches that
+// leave most compute units idle anyway.  (With a target network s and s' cannot share a group.)
+template <bool BOTH, int NR1, int R>
 __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
+    static_assert(R == 4 || (R == 2 && !BOTH), "rows per workgroup");
+    constexpr int MG = R / 2;            // groups of four rows
+    constexpr unsigned int NRW = 2 * R;  // rows of a workgroup
     extern __shared__ float lds[];
     touch_kernel_args<RowArgs>();
-    if (blockIdx.x * kRows >= p.B) {
+    if (blockIdx.x * R >= p.B) {
         // the extra workgroup of a replay that samples without duplicates: the next step's slots
         const unsigned long long ns = p.step + 1;
         unsigned int* dst = p.pre + ((ns & 1u) ? p.pre_stride : 0u);
@@ -314,7 +322,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     const unsigned int tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const unsigned int D = p.D, Dp = p.Dp, H = p.H, A = p.A, Ap = p.Ap;
     const unsigned int ldx = Dp + kPadK, ldh = H + kPadK, ldq = Ap + kPadK;
-    float* Xs = lds;                      // [8][ldx]  rows 0..3 = s, 4..7 = s'
+    float* Xs = lds;                      // [8][ldx]  rows 0..R-1 = s, R..2R-1 = s' (laid out for R = 4)
     float* H1s = Xs + 8 * ldx;            // [8][ldh]
     float* H2s = H1s + 8 * ldh;           // [8][ldh]
     float* Qs = H2s + 8 * ldh;            // [8][ldq]
@@ -360,8 +368,8 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     const unsigned long long step = p.step;
     const unsigned long long n = p.n_append;
     const unsigned int size = p.size_after;
-    const unsigned int i0 = blockIdx.x * kRows;
-    const unsigned int nrows = min(kRows, p.B - i0);
+    const unsigned int i0 = blockIdx.x * R;
+    const unsigned int nrows = min((unsigned int)R, p.B - i0);
     const unsigned int words = 2 * D + 3;
 
     // The state that follows this step is known up front (the host mirrors it exactly): one
@@ -410,7 +418,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     // The last workgroup also writes the new experiences into the ring.  No workgroup reads
     // those slots from the ring in this launch (see above), so this can go out right away and
     // its latency is hidden behind the rest of the kernel.
-    if (i0 + kRows >= p.B && n) {
+    if (i0 + R >= p.B && n) {
         const unsigned int rw = p.g.row_bytes >> 2;
         for (unsigned long long e = tid; e < n * rw; e += kRowThreads) {
             const unsigned long long k = e / rw;
@@ -426,9 +434,9 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     load_cols4<16, 0, 8>(w2r, W2, H, cc, ks * q2, q2);
 
     // zeros wherever no sampled word goes: padding columns, rows past the batch, unused meta
-    for (unsigned int e = tid; e < 8 * ldx; e += kRowThreads) {
+    for (unsigned int e = tid; e < NRW * ldx; e += kRowThreads) {
         const unsigned int row = e / ldx, col = e - row * ldx;
-        if (col >= D || (row & 3u) >= nrows) Xs[e] = 0.f;
+        if (col >= D || (row & (R - 1u)) >= nrows) Xs[e] = 0.f;
     }
     if (tid < 16 && ((tid >> 2) >= nrows || (tid & 3u) == 3u)) meta[tid] = 0;
 
@@ -443,7 +451,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
                 Xs[r * ldx + w] = __uint_as_float(val);
                 p.X[(size_t)i * Dp + w] = __uint_as_float(val);
             } else if (w < 2 * D) {
-                Xs[(4 + r) * ldx + w - D] = __uint_as_float(val);
+                Xs[(R + r) * ldx + w - D] = __uint_as_float(val);
             } else {
                 meta[r * 4 + (w - 2 * D)] = val;
                 if (w == 2 * D) {
@@ -466,9 +474,9 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     load_cols4<16, 8, 16>(w2r, W2, H, cc, ks * q2, q2);
 
     // ---- layer 1
-    f32x4 acc2[2];
-    if (!both) {
-        mma_cols<2, NR1>(acc2, Xs, ldx, k1 * q1, q1, w1r);
+    f32x4 acc2[MG];
+    if constexpr (!BOTH) {
+        mma_cols<MG, NR1>(acc2, Xs, ldx, k1 * q1, q1, w1r);
     } else {
         // the target network's biases travel during the first MFMAs (kept out of the registers
         // that are scarce while W2 is arriving)
@@ -486,11 +494,11 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
         }
         if (tid < Ap) b3ts[tid] = b3tv;
     }
-    store_part<2>(part, k1, kChunk, c1, acc2);
+    store_part<MG>(part, k1, kChunk, c1, acc2);
     lds_barrier();
-    for (unsigned int e = tid; e < 8 * H; e += kRowThreads) {
+    for (unsigned int e = tid; e < NRW * H; e += kRowThreads) {
         const unsigned int row = e / H, c = e - row * H;
-        float v = sum_part(part, 4, 8, kChunk, row, c) + (both && row >= 4 ? b1ts : b1s)[c];
+        float v = sum_part(part, 4, NRW, kChunk, row, c) + (both && row >= R ? b1ts : b1s)[c];
         v = v > 0.f ? v : 0.f;
         H1s[row * ldh + c] = v;
         if (row < nrows) p.H1[(size_t)(i0 + row) * H + c] = v;
@@ -502,11 +510,11 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     // half a microsecond while its SIMD's load path is busy, so each wavefront does it in a
     // phase in which the others have all the work: wavefronts 8..15 during layer 2's sums
     // (wavefronts 0..7), wavefronts 0..7 during layer 3's sums and the TD phase (12..15).
-    if (!both) {
-        f32x4 acc8[2][4];
-        mma_cols4<2, 16, 4>(acc8, H1s, ldh, ks * q2, q2, w2r);
-        store_part4(part, ks, 8, 0, kChunk, cc, acc8[0]);
-        store_part4(part, ks, 8, 4, kChunk, cc, acc8[1]);
+    if constexpr (!BOTH) {
+        f32x4 acc8[MG][4];
+        mma_cols4<MG, 16, 4>(acc8, H1s, ldh, ks * q2, q2, w2r);
+#pragma unroll
+        for (int mg = 0; mg < MG; ++mg) store_part4(part, ks, NRW, 4 * mg, kChunk, cc, acc8[mg]);
     } else {
         f32x4 acc4[1][4];
         mma_cols4_reload<1, 16, 4>(acc4, H1s, ldh, ks * q2, q2, w2r, p.wt + p.oW2, H, cc, ks * q2, q2);
@@ -530,11 +538,11 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     lds_barrier();
     if (wave < 8) {
         // four adjacent columns of one row per thread, 16-byte LDS accesses
-        for (unsigned int e = tid; e < 2 * H; e += 512u) {
+        for (unsigned int e = tid; e < NRW * (H >> 2); e += 512u) {
             const unsigned int row = e / (H >> 2), c = (e - row * (H >> 2)) * 4u;
-            f32x4 v = *reinterpret_cast<const f32x4*>((both && row >= 4 ? b2ts : b2s) + c);
+            f32x4 v = *reinterpret_cast<const f32x4*>((both && row >= R ? b2ts : b2s) + c);
             for (unsigned int sl = 0; sl < 16; ++sl)
-                v += *reinterpret_cast<const f32x4*>(part + ((size_t)(sl * 8 + row)) * kChunk + c);
+                v += *reinterpret_cast<const f32x4*>(part + ((size_t)(sl * NRW + row)) * kChunk + c);
 #pragma unroll
             for (int j = 0; j < 4; ++j) v[j] = v[j] > 0.f ? v[j] : 0.f;
             *reinterpret_cast<f32x4*>(H2s + row * ldh + c) = v;
@@ -546,8 +554,8 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     lds_barrier();
 
     // ---- layer 3 (narrow split: 16 K slices, columns 0..63)
-    if (!both) {
-        mma_cols<2, 16>(acc2, H2s, ldh, wave * s3, s3, w3r);
+    if constexpr (!BOTH) {
+        mma_cols<MG, 16>(acc2, H2s, ldh, wave * s3, s3, w3r);
     } else {
         f32x4 lo[1], hi[1];
         mma_cols_reload<1, 16>(lo, H2s, ldh, wave * s3, s3, w3r, p.wt + p.oW3, Ap, lane, wave * s3, s3);
@@ -555,7 +563,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
         acc2[0] = lo[0];
         acc2[1] = hi[0];
     }
-    store_part<2>(part, wave, 64, lane, acc2);
+    store_part<MG>(part, wave, 64, lane, acc2);
     lds_barrier();
 
     // ---- Q values (sums of the partial products), TD target, loss term, dL/dQ: wavefront
@@ -566,9 +574,9 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     unsigned int td_ai = 0;
     if (wave >= 12) {
         const unsigned int r = wave - 12u;
-        if (lane < Ap) {
-            td_qs = sum_part(part, 16, 8, 64, r, lane) + b3s[lane];
-            td_qn = sum_part(part, 16, 8, 64, 4 + r, lane) + (both ? b3ts : b3s)[lane];
+        if (r < (unsigned int)R && lane < Ap) {
+            td_qs = sum_part(part, 16, NRW, 64, r, lane) + b3s[lane];
+            td_qn = sum_part(part, 16, NRW, 64, R + r, lane) + (both ? b3ts : b3s)[lane];
         }
         if (r < nrows) {
             const float best = wave_max(lane < A ? td_qn : -INFINITY);
@@ -972,10 +980,12 @@ bool fused_step_supported(const train_config& cfg, const replay* rp_) {
 // The row kernel's dynamic LDS exceeds the default limit: announced once per process, at trainer
 // creation (outside any stream capture).
 hipError_t fused_init() {
-    const void* kernels[] = {reinterpret_cast<const void*>(fused_rows_kernel<false, 8>),
-                             reinterpret_cast<const void*>(fused_rows_kernel<false, 16>),
-                             reinterpret_cast<const void*>(fused_rows_kernel<true, 8>),
-                             reinterpret_cast<const void*>(fused_rows_kernel<true, 16>)};
+    const void* kernels[] = {reinterpret_cast<const void*>(fused_rows_kernel<false, 8, 4>),
+                             reinterpret_cast<const void*>(fused_rows_kernel<false, 16, 4>),
+                             reinterpret_cast<const void*>(fused_rows_kernel<false, 8, 2>),
+                             reinterpret_cast<const void*>(fused_rows_kernel<false, 16, 2>),
+                             reinterpret_cast<const void*>(fused_rows_kernel<true, 8, 4>),
+                             reinterpret_cast<const void*>(fused_rows_kernel<true, 16, 4>)};
     for (const void* k : kernels) {
         hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kRowLdsMax);
         if (e != hipSuccess) return e;
@@ -983,12 +993,22 @@ hipError_t fused_init() {
     return hipSuccess;
 }
 
-void* fused_rows_func(bool target_network, unsigned int Dp) {
-    if (Dp <= 32)
-        return target_network ? reinterpret_cast<void*>(fused_rows_kernel<true, 8>)
-                              : reinterpret_cast<void*>(fused_rows_kernel<false, 8>);
-    return target_network ? reinterpret_cast<void*>(fused_rows_kernel<true, 16>)
-                          : reinterpret_cast<void*>(fused_rows_kernel<false, 16>);
+// Experiences per workgroup of the row kernel: two while that still leaves compute units idle
+// (every workgroup fetches all the weights, so more workgroups than that only add traffic).
+unsigned int fused_rows_per_group(bool target_network, unsigned int B) {
+    return !target_network && B <= kSmallBatch ? 2u : kRows;
+}
+
+void* fused_rows_func(bool target_network, unsigned int Dp, unsigned int B) {
+    const bool narrow = Dp <= 32;
+    if (target_network)
+        return narrow ? reinterpret_cast<void*>(fused_rows_kernel<true, 8, 4>)
+                      : reinterpret_cast<void*>(fused_rows_kernel<true, 16, 4>);
+    if (fused_rows_per_group(false, B) == 2)
+        return narrow ? reinterpret_cast<void*>(fused_rows_kernel<false, 8, 2>)
+                      : reinterpret_cast<void*>(fused_rows_kernel<false, 16, 2>);
+    return narrow ? reinterpret_cast<void*>(fused_rows_kernel<false, 8, 4>)
+                  : reinterpret_cast<void*>(fused_rows_kernel<false, 16, 4>);
 }
 
 hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* batch, hipStream_t st,
@@ -1030,10 +1050,11 @@ hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* bat
     const bool ahead = r->cfg.sampling == RP_DISTINCT && t->B <= kRowThreads;
     a.pre = ahead ? t->pre : nullptr;
     a.pre_stride = 4u + t->B;
-    const unsigned int blocks = (t->B + kRows - 1) / kRows + (ahead ? 1u : 0u);
+    const unsigned int per = fused_rows_per_group(t->wt != nullptr, t->B);
+    const unsigned int blocks = (t->B + per - 1) / per + (ahead ? 1u : 0u);
     hipError_t e = hipSuccess;
     void* kargs[] = {&a};
-    e = hipLaunchKernel(fused_rows_func(t->wt != nullptr, t->Dp), dim3(blocks), dim3(kRowThreads), kargs,
+    e = hipLaunchKernel(fused_rows_func(t->wt != nullptr, t->Dp, t->B), dim3(blocks), dim3(kRowThreads), kargs,
                         row_kernel_lds(t->Dp, t->H, t->Ap), st);
     if (e != hipSuccess) return e;
 

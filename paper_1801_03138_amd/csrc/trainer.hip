@@ -915,7 +915,7 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
         }
         t->pin_dev = static_cast<unsigned char*>(dp);
     }
-    t->payload_func = t->fused  ? rp::fused_rows_func(t->wt != nullptr, t->Dp)
+    t->payload_func = t->fused  ? rp::fused_rows_func(t->wt != nullptr, t->Dp, t->B)
                       : t->wide ? rp::append_gather_func(rp_->geom)
                                 : rp::append_pair_func(rp_->geom);
     t->payload_kargs[0] = t->fused ? static_cast<void*>(&t->row_args) : static_cast<void*>(&t->append_args);

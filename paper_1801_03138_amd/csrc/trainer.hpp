@@ -201,7 +201,7 @@ bool fused_step_supported(const train_config& cfg, const replay* rp_);
 hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* batch, hipStream_t st,
                               unsigned int* count);
 hipError_t fused_init();                      // once, at trainer creation
-void* fused_rows_func(bool target_network, unsigned int Dp);   // the row kernel variant for a configuration
+void* fused_rows_func(bool target_network, unsigned int Dp, unsigned int B);   // the row kernel variant for a configuration
 // Dueling head: turn the gradient of the equivalent plain output layer (in g) into the head's
 // update and refresh that layer (and its bf16 / target copies).  No-op for a plain head.
 hipError_t enqueue_head_update(trainer* t, hipStream_t st, unsigned int* count);
