@@ -21,7 +21,8 @@ namespace {
 constexpr unsigned int kThreads = kTrainThreads;   // weight kernel
 constexpr unsigned int kRowThreads = 1024;         // row kernel: 16 wavefronts
 constexpr unsigned int kRows = 4;          // experiences per workgroup of the row kernel ...
-constexpr unsigned int kSmallBatch = 256;  // ... and 2 for batches up to this size (no target network)
+constexpr unsigned int kSmallBatch = 512;  // ... and 2 for batches up to this size (no target network):
+                                           // measured faster while the workgroups fit the 256 compute units
 constexpr unsigned int kChunk = 256;       // output columns the workgroup covers per pass
 constexpr size_t kRowLdsMax = 160 * 1024;  // dynamic LDS the row kernel may ask for (all of a CU's)
 constexpr unsigned int kPadK = 4;          // LDS row padding (floats) against bank conflicts

@@ -288,6 +288,23 @@ def test_other_widths_agree_with_oracle(B, H, layered, kernels):
     assert pr.gpu_ring.state() == pr.ref_ring.state()
 
 
+@pytest.mark.parametrize("D,H,A,batch,target_sync,dueling", [
+    (27, 256, 30, 513, 0, False), (60, 128, 9, 771, 0, False), (27, 64, 30, 600, 0, True),
+    (27, 128, 30, 514, 4, False), (40, 256, 5, 512, 0, False)])
+def test_batches_beyond_one_workgroup_per_compute_unit(B, D, H, A, batch, target_sync, dueling):
+    """The row kernel takes two experiences per workgroup up to batch 512 and four beyond (and
+    always four with a target network): batches on both sides of that limit, ragged against 2
+    and against 4, on both widths of the first layer."""
+    rows = synth.experiences(1400, D, A, 0.05, seed=41)
+    pr = Pair(B, capacity=1200, D=D, H=H, A=A, batch=batch, burn_in=800, seed=9, appends=3,
+              target_sync=target_sync, dueling=dueling)
+    assert pr.trainer.kernels_per_step() == 2
+    pr.append_only(synth.take(rows, 0, 1000))
+    for k in range(8):
+        assert pr.step(synth.take(rows, 1000 + 3 * k, 1003 + 3 * k), compare=True) == 0
+    assert pr.gpu_ring.state() == pr.ref_ring.state()
+
+
 def test_wide_state_and_action_sets(B):
     """D = 60 and A = 64 fill the row kernel's 64-wide limits; D = 70 goes layer by layer."""
     for D, A, kernels in ((60, 64, 2), (70, 40, 15)):
