@@ -433,6 +433,12 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     const float b2v = tid < H ? p.w[p.ob2 + tid] : 0.f;
     const float b3v = tid < Ap ? p.w[p.ob3 + tid] : 0.f;
     load_cols4<16, 0, 8>(w2r, W2, H, cc, ks * q2, q2);
+    // A wavefront that holds none of the sampled words has nothing to deliver before the
+    // barrier that publishes the sample: it requests the rest of W2 right away.  The others do
+    // so behind the barrier, so that their wait for the load path does not hold the sample up
+    // (requesting nothing of W2 before the barrier was slower for them).
+    const bool has_sample = wave * 64u < nrows * words;
+    if (!has_sample) load_cols4<16, 8, 16>(w2r, W2, H, cc, ks * q2, q2);
 
     // zeros wherever no sampled word goes: padding columns, rows past the batch, unused meta
     for (unsigned int e = tid; e < NRW * ldx; e += kRowThreads) {
@@ -472,7 +478,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     }
     if (tid < Ap) b3s[tid] = b3v;
     lds_barrier();
-    load_cols4<16, 8, 16>(w2r, W2, H, cc, ks * q2, q2);
+    if (has_sample) load_cols4<16, 8, 16>(w2r, W2, H, cc, ks * q2, q2);
 
     // ---- layer 1
     f32x4 acc2[MG];
