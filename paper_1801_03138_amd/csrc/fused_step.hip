@@ -305,6 +305,8 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     static_assert(R == 4 || (R == 2 && !BOTH), "rows per workgroup");
     constexpr int MG = R / 2;            // groups of four rows
     constexpr unsigned int NRW = 2 * R;  // rows of a workgroup
+    constexpr unsigned int PR = NRW;     // rows of its MFMA groups
+    constexpr bool FAST = !BOTH && NR1 == 8;   // layer 1 by four wavefronts on their own
     extern __shared__ float lds[];
     touch_kernel_args<RowArgs>();
     if (blockIdx.x * R >= p.B) {
@@ -361,9 +363,8 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     // arguments, the host mirrors them exactly, so the draw needs no memory access), the first
     // half of layer 2's weights, and its second half once the sample is in LDS, behind which
     // layer 1 runs.
-    float w1r[NR1];
     f32x4 w2r[16];
-    load_cols<NR1>(w1r, W1, H, c1, k1 * q1, q1);
+    f32x4 acc2[MG];
     const unsigned long long cap = p.g.capacity;
     const unsigned long long head = p.head;
     const unsigned long long step = p.step;
@@ -386,131 +387,291 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
         p.ctr->c2 = p.c2_after;
     }
 
-    // sample and gather: one 32-bit word per thread (two passes at most, D <= 64).  A drawn
-    // slot that this step's append is about to overwrite is read from the payload arrays,
-    // which hold its new content.
-    unsigned int gval[2] = {0u, 0u}, gslot[2] = {0u, 0u};
+    if constexpr (FAST) {
+        // ---- narrow first layer (Dp = 32): wavefronts 0..3 take layer 1 on their own, each for
+        // 64 output columns over the whole K, from a private copy of the sample: no partial sums
+        // and no barrier before layer 2's, so nothing here waits for the wavefronts that are still
+        // queueing their requests for W2.  Each of the four draws and gathers the (few) sampled
+        // words itself; wavefront 0 also publishes them.
+        if (wave < 4) {
+            // one draw per row, in the lane of that row: first of all, the sampled words take
+            // longest to arrive
+            unsigned int myslot = 0;
+            if (lane < nrows) {
+                if (p.from_batch) {
+                    myslot = i0 + lane;
+                } else {
+                    const unsigned int* ahead = p.pre ? p.pre + ((step & 1u) ? p.pre_stride : 0u) : nullptr;
+                    if (ahead && ahead[0] == (unsigned int)step && ahead[1] == (unsigned int)(step >> 32) &&
+                        ahead[2] == size)
+                        myslot = ahead[4 + i0 + lane];   // drawn during the previous step
+                    else
+                        myslot = batch_draw(p.g.sampling, p.seed, step, i0 + lane, size);
+                }
+            }
+            constexpr int NPASS = (R * 67 + 63) / 64;   // 2 D + 3 <= 67 words per row
+            unsigned int gv[NPASS], gsl[NPASS];
 #pragma unroll
-    for (int pass = 0; pass < 2; ++pass) {
-        const unsigned int e = tid + pass * kRowThreads;
-        if (e < nrows * words) {
-            const unsigned int r = e / words, w = e - r * words;
-            if (p.from_batch) {
-                // the caller's batch: row i0 + r of its arrays; reported slot = position in the batch
-                gslot[pass] = i0 + r;
-                gval[pass] = payload_word(p.batch, D, i0 + r, w);
-            } else {
-                unsigned int slot;
-                const unsigned int* ahead = p.pre ? p.pre + ((step & 1u) ? p.pre_stride : 0u) : nullptr;
-                if (ahead && ahead[0] == (unsigned int)step && ahead[1] == (unsigned int)(step >> 32) &&
-                    ahead[2] == size)
-                    slot = ahead[4 + i0 + r];   // drawn during the previous step
-                else
-                    slot = batch_draw(p.g.sampling, p.seed, step, i0 + r, size);
-                unsigned long long off = (unsigned long long)slot + cap - head;
-                if (off >= cap) off -= cap;
-                gslot[pass] = slot;
-                gval[pass] = off < n ? staged_word(p, off, w)
-                                     : reinterpret_cast<const unsigned int*>(
-                                           p.g.rows + (unsigned long long)slot * p.g.row_bytes)[w];
+            for (int pass = 0; pass < NPASS; ++pass) {
+                const unsigned int e = lane + 64u * pass;
+                const unsigned int r = min(e / words, (unsigned int)R - 1u), w = e - r * words;
+                const unsigned int slot = __shfl(myslot, (int)r, 64);
+                gv[pass] = 0u;
+                gsl[pass] = slot;
+                if (e < nrows * words) {
+                    if (p.from_batch) {
+                        gv[pass] = payload_word(p.batch, D, i0 + r, w);
+                    } else {
+                        unsigned long long off = (unsigned long long)slot + cap - head;
+                        if (off >= cap) off -= cap;
+                        gv[pass] = off < n ? staged_word(p, off, w)
+                                           : reinterpret_cast<const unsigned int*>(
+                                                 p.g.rows + (unsigned long long)slot * p.g.row_bytes)[w];
+                    }
+                }
+            }
+            // W1: the wavefront covers columns 64 w .. 64 w + 63 as 16 groups of four adjacent
+            // columns times 4 quarters of K (8 rows each).  Lane l = 16 q + 4 kq + i: column
+            // group 4 q + i, K quarter kq -- the four lanes of an MFMA block share their kq (they
+            // exchange operands), the four quarters of a column sit in one DPP row.
+            const unsigned int kq = (lane >> 2) & 3u;
+            const unsigned int ccf = 64u * wave + 4u * (4u * (lane >> 4) + (lane & 3u));
+            const bool colf = ccf < H;   // (H is a multiple of 64: all four columns or none)
+            f32x4 w1x[8];
+            {
+                const unsigned int loff = ((8u * kq) * H + (colf ? ccf : H - 4u)) * 4u;
+                const gbytes base = (gbytes)reinterpret_cast<const char*>(W1);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    gbytes rb = base + (size_t)u * H * 4u;
+                    asm volatile("" : "+s"(rb));
+                    w1x[u] = *(const __attribute__((address_space(1))) f32x4*)(rb + loff);
+                }
+            }
+            const f32x4 b1f = *reinterpret_cast<const f32x4*>(p.w + p.ob1 + (colf ? ccf : H - 4u));
+            // the private copy (in the partial-sum buffer, which nothing uses before layer 2)
+            float* Xp = part + wave * (PR * ldx);
+            for (unsigned int e = lane; e < PR * ldx; e += 64u) Xp[e] = 0.f;
+            if (wave == 0 && lane < 16 && ((lane >> 2) >= nrows || (lane & 3u) == 3u)) meta[lane] = 0;
+#pragma unroll
+            for (int pass = 0; pass < NPASS; ++pass) {
+                const unsigned int e = lane + 64u * pass;
+                if (e < nrows * words) {
+                    const unsigned int r = e / words, w = e - r * words;
+                    const unsigned int i = i0 + r;
+                    const unsigned int val = gv[pass];
+                    if (w < D) {
+                        Xp[r * ldx + w] = __uint_as_float(val);
+                        if (wave == 0) p.X[(size_t)i * Dp + w] = __uint_as_float(val);
+                    } else if (w < 2 * D) {
+                        Xp[(R + r) * ldx + w - D] = __uint_as_float(val);
+                    } else if (wave == 0) {
+                        meta[r * 4 + (w - 2 * D)] = val;
+                        if (w == 2 * D) {
+                            p.act[i] = (int)val;
+                            p.idx[i] = gsl[pass];
+                        } else if (w == 2 * D + 1) {
+                            p.rew[i] = __uint_as_float(val);
+                        } else {
+                            p.term[i] = (unsigned char)val;
+                        }
+                    }
+                }
+            }
+            // (a wavefront's LDS operations complete in order: its copy is there)
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            f32x4 accf[MG][4];
+            {
+                const float* ap = Xp + (lane & 3u) * ldx + 8u * kq;
+#pragma unroll
+                for (int mg = 0; mg < MG; ++mg)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) accf[mg][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int u0 = 0; u0 < 8; u0 += 4)
+#pragma unroll
+                    for (int mg = 0; mg < MG; ++mg) {
+                        const f32x4 av = *reinterpret_cast<const f32x4*>(ap + (size_t)mg * 4 * ldx + u0);
+#pragma unroll
+                        for (int u = 0; u < 4; ++u)
+#pragma unroll
+                            for (int j = 0; j < 4; ++j)
+                                accf[mg][j] = __builtin_amdgcn_mfma_f32_4x4x1f32(av[u], w1x[u0 + u][j],
+                                                                                 accf[mg][j], 0, 0, 0);
+                    }
+            }
+            // sum the four K quarters (lanes 4 apart within a DPP row), then lane kq takes row kq
+#pragma unroll
+            for (int mg = 0; mg < MG; ++mg) {
+                f32x4 hv = b1f;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        float x = accf[mg][j][v];
+                        x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x128, 0xf, 0xf, false));
+                        x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x124, 0xf, 0xf, false));
+                        if ((unsigned int)v == kq) hv[j] += x;
+                    }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) hv[j] = hv[j] > 0.f ? hv[j] : 0.f;
+                const unsigned int row = mg * 4 + kq;
+                if (colf) {
+                    *reinterpret_cast<f32x4*>(H1s + row * ldh + ccf) = hv;
+                    if (row < nrows) *reinterpret_cast<f32x4*>(p.H1 + (size_t)(i0 + row) * H + ccf) = hv;
+                }
+            }
+            load_cols4<16>(w2r, W2, H, cc, ks * q2, q2);
+        } else {
+            load_cols4<16>(w2r, W2, H, cc, ks * q2, q2);
+            // the other biases: wavefronts 4..7
+            const unsigned int t4 = tid - 256u;
+            if (t4 < H) b2s[t4] = p.w[p.ob2 + t4];
+            if (t4 < Ap) b3s[t4] = p.w[p.ob3 + t4];
+        }
+        // The last workgroup also writes the new experiences into the ring.  No workgroup reads
+        // those slots from the ring in this launch (see above), so this can go out right away and
+        // its latency is hidden behind the rest of the kernel.
+        if (i0 + R >= p.B && n) {
+            const unsigned int rw = p.g.row_bytes >> 2;
+            for (unsigned long long e = tid; e < n * rw; e += kRowThreads) {
+                const unsigned long long k = e / rw;
+                const unsigned int w = (unsigned int)(e - k * rw);
+                unsigned long long slot = head + k;
+                if (slot >= cap) slot -= cap;
+                reinterpret_cast<unsigned int*>(p.g.rows + slot * p.g.row_bytes)[w] = staged_word(p, k, w);
             }
         }
-    }
-    // The last workgroup also writes the new experiences into the ring.  No workgroup reads
-    // those slots from the ring in this launch (see above), so this can go out right away and
-    // its latency is hidden behind the rest of the kernel.
-    if (i0 + R >= p.B && n) {
-        const unsigned int rw = p.g.row_bytes >> 2;
-        for (unsigned long long e = tid; e < n * rw; e += kRowThreads) {
-            const unsigned long long k = e / rw;
-            const unsigned int w = (unsigned int)(e - k * rw);
-            unsigned long long slot = head + k;
-            if (slot >= cap) slot -= cap;
-            reinterpret_cast<unsigned int*>(p.g.rows + slot * p.g.row_bytes)[w] = staged_word(p, k, w);
-        }
-    }
-    const float b1v = tid < H ? p.w[p.ob1 + tid] : 0.f;
-    const float b2v = tid < H ? p.w[p.ob2 + tid] : 0.f;
-    const float b3v = tid < Ap ? p.w[p.ob3 + tid] : 0.f;
-    load_cols4<16, 0, 8>(w2r, W2, H, cc, ks * q2, q2);
-    // A wavefront that holds none of the sampled words has nothing to deliver before the
-    // barrier that publishes the sample: it requests the rest of W2 right away.  The others do
-    // so behind the barrier, so that their wait for the load path does not hold the sample up
-    // (requesting nothing of W2 before the barrier was slower for them).
-    const bool has_sample = wave * 64u < nrows * words;
-    if (!has_sample) load_cols4<16, 8, 16>(w2r, W2, H, cc, ks * q2, q2);
-
-    // zeros wherever no sampled word goes: padding columns, rows past the batch, unused meta
-    for (unsigned int e = tid; e < NRW * ldx; e += kRowThreads) {
-        const unsigned int row = e / ldx, col = e - row * ldx;
-        if (col >= D || (row & (R - 1u)) >= nrows) Xs[e] = 0.f;
-    }
-    if (tid < 16 && ((tid >> 2) >= nrows || (tid & 3u) == 3u)) meta[tid] = 0;
-
-#pragma unroll
-    for (int pass = 0; pass < 2; ++pass) {
-        const unsigned int e = tid + pass * kRowThreads;
-        if (e < nrows * words) {
-            const unsigned int r = e / words, w = e - r * words;
-            const unsigned int i = i0 + r;
-            const unsigned int val = gval[pass];
-            if (w < D) {
-                Xs[r * ldx + w] = __uint_as_float(val);
-                p.X[(size_t)i * Dp + w] = __uint_as_float(val);
-            } else if (w < 2 * D) {
-                Xs[(R + r) * ldx + w - D] = __uint_as_float(val);
-            } else {
-                meta[r * 4 + (w - 2 * D)] = val;
-                if (w == 2 * D) {
-                    p.act[i] = (int)val;
-                    p.idx[i] = gslot[pass];
-                } else if (w == 2 * D + 1) {
-                    p.rew[i] = __uint_as_float(val);
+        lds_barrier();
+    } else {
+        float w1r[NR1];
+        load_cols<NR1>(w1r, W1, H, c1, k1 * q1, q1);
+        // sample and gather: one 32-bit word per thread (two passes at most, D <= 64).  A drawn
+        // slot that this step's append is about to overwrite is read from the payload arrays,
+        // which hold its new content.
+        unsigned int gval[2] = {0u, 0u}, gslot[2] = {0u, 0u};
+    #pragma unroll
+        for (int pass = 0; pass < 2; ++pass) {
+            const unsigned int e = tid + pass * kRowThreads;
+            if (e < nrows * words) {
+                const unsigned int r = e / words, w = e - r * words;
+                if (p.from_batch) {
+                    // the caller's batch: row i0 + r of its arrays; reported slot = position in the batch
+                    gslot[pass] = i0 + r;
+                    gval[pass] = payload_word(p.batch, D, i0 + r, w);
                 } else {
-                    p.term[i] = (unsigned char)val;
+                    unsigned int slot;
+                    const unsigned int* ahead = p.pre ? p.pre + ((step & 1u) ? p.pre_stride : 0u) : nullptr;
+                    if (ahead && ahead[0] == (unsigned int)step && ahead[1] == (unsigned int)(step >> 32) &&
+                        ahead[2] == size)
+                        slot = ahead[4 + i0 + r];   // drawn during the previous step
+                    else
+                        slot = batch_draw(p.g.sampling, p.seed, step, i0 + r, size);
+                    unsigned long long off = (unsigned long long)slot + cap - head;
+                    if (off >= cap) off -= cap;
+                    gslot[pass] = slot;
+                    gval[pass] = off < n ? staged_word(p, off, w)
+                                         : reinterpret_cast<const unsigned int*>(
+                                               p.g.rows + (unsigned long long)slot * p.g.row_bytes)[w];
                 }
             }
         }
-    }
-    if (tid < H) {
-        b1s[tid] = b1v;
-        b2s[tid] = b2v;
-    }
-    if (tid < Ap) b3s[tid] = b3v;
-    lds_barrier();
-    if (has_sample) load_cols4<16, 8, 16>(w2r, W2, H, cc, ks * q2, q2);
-
-    // ---- layer 1
-    f32x4 acc2[MG];
-    if constexpr (!BOTH) {
-        mma_cols<MG, NR1>(acc2, Xs, ldx, k1 * q1, q1, w1r);
-    } else {
-        // the target network's biases travel during the first MFMAs (kept out of the registers
-        // that are scarce while W2 is arriving)
-        const float b1tv = tid < H ? p.wt[p.ob1 + tid] : 0.f;
-        const float b2tv = tid < H ? p.wt[p.ob2 + tid] : 0.f;
-        const float b3tv = tid < Ap ? p.wt[p.ob3 + tid] : 0.f;
-        f32x4 lo[1], hi[1];
-        mma_cols_reload<1, NR1>(lo, Xs, ldx, k1 * q1, q1, w1r, p.wt + p.oW1, H, c1, k1 * q1, q1);
-        mma_cols<1, NR1>(hi, Xs + 4 * ldx, ldx, k1 * q1, q1, w1r);
-        acc2[0] = lo[0];
-        acc2[1] = hi[0];
-        if (tid < H) {
-            b1ts[tid] = b1tv;
-            b2ts[tid] = b2tv;
+        // The last workgroup also writes the new experiences into the ring.  No workgroup reads
+        // those slots from the ring in this launch (see above), so this can go out right away and
+        // its latency is hidden behind the rest of the kernel.
+        if (i0 + R >= p.B && n) {
+            const unsigned int rw = p.g.row_bytes >> 2;
+            for (unsigned long long e = tid; e < n * rw; e += kRowThreads) {
+                const unsigned long long k = e / rw;
+                const unsigned int w = (unsigned int)(e - k * rw);
+                unsigned long long slot = head + k;
+                if (slot >= cap) slot -= cap;
+                reinterpret_cast<unsigned int*>(p.g.rows + slot * p.g.row_bytes)[w] = staged_word(p, k, w);
+            }
         }
-        if (tid < Ap) b3ts[tid] = b3tv;
+        const float b1v = tid < H ? p.w[p.ob1 + tid] : 0.f;
+        const float b2v = tid < H ? p.w[p.ob2 + tid] : 0.f;
+        const float b3v = tid < Ap ? p.w[p.ob3 + tid] : 0.f;
+        load_cols4<16, 0, 8>(w2r, W2, H, cc, ks * q2, q2);
+        // A wavefront that holds none of the sampled words has nothing to deliver before the
+        // barrier that publishes the sample: it requests the rest of W2 right away.  The others do
+        // so behind the barrier, so that their wait for the load path does not hold the sample up
+        // (requesting nothing of W2 before the barrier was slower for them).
+        const bool has_sample = wave * 64u < nrows * words;
+        if (!has_sample) load_cols4<16, 8, 16>(w2r, W2, H, cc, ks * q2, q2);
+
+        // zeros wherever no sampled word goes: padding columns, rows past the batch, unused meta
+        for (unsigned int e = tid; e < NRW * ldx; e += kRowThreads) {
+            const unsigned int row = e / ldx, col = e - row * ldx;
+            if (col >= D || (row & (R - 1u)) >= nrows) Xs[e] = 0.f;
+        }
+        if (tid < 16 && ((tid >> 2) >= nrows || (tid & 3u) == 3u)) meta[tid] = 0;
+
+    #pragma unroll
+        for (int pass = 0; pass < 2; ++pass) {
+            const unsigned int e = tid + pass * kRowThreads;
+            if (e < nrows * words) {
+                const unsigned int r = e / words, w = e - r * words;
+                const unsigned int i = i0 + r;
+                const unsigned int val = gval[pass];
+                if (w < D) {
+                    Xs[r * ldx + w] = __uint_as_float(val);
+                    p.X[(size_t)i * Dp + w] = __uint_as_float(val);
+                } else if (w < 2 * D) {
+                    Xs[(R + r) * ldx + w - D] = __uint_as_float(val);
+                } else {
+                    meta[r * 4 + (w - 2 * D)] = val;
+                    if (w == 2 * D) {
+                        p.act[i] = (int)val;
+                        p.idx[i] = gslot[pass];
+                    } else if (w == 2 * D + 1) {
+                        p.rew[i] = __uint_as_float(val);
+                    } else {
+                        p.term[i] = (unsigned char)val;
+                    }
+                }
+            }
+        }
+        if (tid < H) {
+            b1s[tid] = b1v;
+            b2s[tid] = b2v;
+        }
+        if (tid < Ap) b3s[tid] = b3v;
+        lds_barrier();
+        if (has_sample) load_cols4<16, 8, 16>(w2r, W2, H, cc, ks * q2, q2);
+
+        // ---- layer 1
+        if constexpr (!BOTH) {
+            mma_cols<MG, NR1>(acc2, Xs, ldx, k1 * q1, q1, w1r);
+        } else {
+            // the target network's biases travel during the first MFMAs (kept out of the registers
+            // that are scarce while W2 is arriving)
+            const float b1tv = tid < H ? p.wt[p.ob1 + tid] : 0.f;
+            const float b2tv = tid < H ? p.wt[p.ob2 + tid] : 0.f;
+            const float b3tv = tid < Ap ? p.wt[p.ob3 + tid] : 0.f;
+            f32x4 lo[1], hi[1];
+            mma_cols_reload<1, NR1>(lo, Xs, ldx, k1 * q1, q1, w1r, p.wt + p.oW1, H, c1, k1 * q1, q1);
+            mma_cols<1, NR1>(hi, Xs + 4 * ldx, ldx, k1 * q1, q1, w1r);
+            acc2[0] = lo[0];
+            acc2[1] = hi[0];
+            if (tid < H) {
+                b1ts[tid] = b1tv;
+                b2ts[tid] = b2tv;
+            }
+            if (tid < Ap) b3ts[tid] = b3tv;
+        }
+        store_part<MG>(part, k1, kChunk, c1, acc2);
+        lds_barrier();
+        for (unsigned int e = tid; e < NRW * H; e += kRowThreads) {
+            const unsigned int row = e / H, c = e - row * H;
+            float v = sum_part(part, 4, NRW, kChunk, row, c) + (both && row >= R ? b1ts : b1s)[c];
+            v = v > 0.f ? v : 0.f;
+            H1s[row * ldh + c] = v;
+            if (row < nrows) p.H1[(size_t)(i0 + row) * H + c] = v;
+        }
+        lds_barrier();
+
     }
-    store_part<MG>(part, k1, kChunk, c1, acc2);
-    lds_barrier();
-    for (unsigned int e = tid; e < NRW * H; e += kRowThreads) {
-        const unsigned int row = e / H, c = e - row * H;
-        float v = sum_part(part, 4, NRW, kChunk, row, c) + (both && row >= R ? b1ts : b1s)[c];
-        v = v > 0.f ? v : 0.f;
-        H1s[row * ldh + c] = v;
-        if (row < nrows) p.H1[(size_t)(i0 + row) * H + c] = v;
-    }
-    lds_barrier();
 
     // ---- layer 2.  From here on the fetch of W2^T (for the backward pass, into the registers
     // that layer 2 frees) is the long pole: a wavefront that requests its share stalls for about
