@@ -364,7 +364,11 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     // half of layer 2's weights, and its second half once the sample is in LDS, behind which
     // layer 1 runs.
     f32x4 w2r[16];
+    float w3r[16];
     f32x4 acc2[MG];
+    // layer 3's weights can be requested with W2 by the wavefronts that have no part in the fast
+    // layer 1 (two experiences per workgroup: the registers hold them next to layer 2's sums)
+    constexpr bool W3_EARLY = FAST && R == 2;
     const unsigned long long cap = p.g.capacity;
     const unsigned long long head = p.head;
     const unsigned long long step = p.step;
@@ -524,6 +528,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
             load_cols4<16>(w2r, W2, H, cc, ks * q2, q2);
         } else {
             load_cols4<16>(w2r, W2, H, cc, ks * q2, q2);
+            if constexpr (W3_EARLY) load_cols<16>(w3r, W3, Ap, lane, wave * s3, s3);
             // the other biases: wavefronts 4..7
             const unsigned int t4 = tid - 256u;
             if (t4 < H) b2s[t4] = p.w[p.ob2 + t4];
@@ -691,8 +696,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
         store_part4(part, ks, 8, 4, kChunk, cc, acc4[0]);
     }
     // The accumulators are free: layer 3's weights are requested, and ...
-    float w3r[16];
-    load_cols<16>(w3r, W3, Ap, lane, wave * s3, s3);
+    if (!W3_EARLY || wave < 4) load_cols<16>(w3r, W3, Ap, lane, wave * s3, s3);
     // ... the column of W3 that the backward pass of each row needs: W3[k][a_r], one per thread
     float w3sel = 0.f;
     {
