@@ -721,7 +721,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
             if (row < nrows) *reinterpret_cast<f32x4*>(p.H2 + (size_t)(i0 + row) * H + c) = v;
         }
     } else {
-        load_cols4<16>(w2r, p.w2t, H, cc, ks * q2, q2);
+        load_cols4<16, 0, BOTH ? 12 : 16>(w2r, p.w2t, H, cc, ks * q2, q2);
     }
     lds_barrier();
 
@@ -736,6 +736,13 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
         acc2[1] = hi[0];
     }
     store_part<MG>(part, wave, 64, lane, acc2);
+    // (with a target network: a few rows of W2^T per wavefront here, so that the two phases around
+    // this one, whose length is that of their requests, get shorter; measured a gain there, a small
+    // loss without the target network)
+    if constexpr (BOTH) {
+        if (wave < 8) load_cols4<16, 0, 4>(w2r, p.w2t, H, cc, ks * q2, q2);
+        else load_cols4<16, 12, 16>(w2r, p.w2t, H, cc, ks * q2, q2);
+    }
     lds_barrier();
 
     // ---- Q values (sums of the partial products), TD target, loss term, dL/dQ: wavefront
@@ -769,7 +776,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
             if (lane == 0) gs[r] = td_gr;
         }
     } else if (wave < 8) {
-        load_cols4<16>(w2r, p.w2t, H, cc, ks * q2, q2);
+        load_cols4<16, BOTH ? 4 : 0, 16>(w2r, p.w2t, H, cc, ks * q2, q2);
     }
     lds_barrier();
     if (wave >= 12 && wave - 12u < nrows) {
