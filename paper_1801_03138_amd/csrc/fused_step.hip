@@ -396,7 +396,8 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
         // 64 output columns over the whole K, from a private copy of the sample: no partial sums
         // and no barrier before layer 2's, so nothing here waits for the wavefronts that are still
         // queueing their requests for W2.  Each of the four draws and gathers the (few) sampled
-        // words itself; wavefront 0 also publishes them.
+        // words itself, and they share publishing them: wavefront 1 the action / reward / terminal
+        // words, the others the states, a pass each.
         if (wave < 4) {
             // one draw per row, in the lane of that row: first of all, the sampled words take
             // longest to arrive
@@ -456,7 +457,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
             // the private copy (in the partial-sum buffer, which nothing uses before layer 2)
             float* Xp = part + wave * (PR * ldx);
             for (unsigned int e = lane; e < PR * ldx; e += 64u) Xp[e] = 0.f;
-            if (wave == 0 && lane < 16 && ((lane >> 2) >= nrows || (lane & 3u) == 3u)) meta[lane] = 0;
+            if (wave == 1 && lane < 16 && ((lane >> 2) >= nrows || (lane & 3u) == 3u)) meta[lane] = 0;
 #pragma unroll
             for (int pass = 0; pass < NPASS; ++pass) {
                 const unsigned int e = lane + 64u * pass;
@@ -466,10 +467,11 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
                     const unsigned int val = gv[pass];
                     if (w < D) {
                         Xp[r * ldx + w] = __uint_as_float(val);
-                        if (wave == 0) p.X[(size_t)i * Dp + w] = __uint_as_float(val);
+                        if (wave == (pass % 3 == 0 ? 0u : pass % 3 == 1 ? 2u : 3u))
+                            p.X[(size_t)i * Dp + w] = __uint_as_float(val);
                     } else if (w < 2 * D) {
                         Xp[(R + r) * ldx + w - D] = __uint_as_float(val);
-                    } else if (wave == 0) {
+                    } else if (wave == 1) {
                         meta[r * 4 + (w - 2 * D)] = val;
                         if (w == 2 * D) {
                             p.act[i] = (int)val;
