@@ -306,7 +306,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     constexpr int MG = R / 2;            // groups of four rows
     constexpr unsigned int NRW = 2 * R;  // rows of a workgroup
     constexpr unsigned int PR = NRW;     // rows of its MFMA groups
-    constexpr bool FAST = !BOTH && NR1 == 8;   // layer 1 by four wavefronts on their own
+    constexpr bool FAST = NR1 == 8;   // layer 1 by four (with a target network: eight) wavefronts on their own
     extern __shared__ float lds[];
     touch_kernel_args<RowArgs>();
     if (blockIdx.x * R >= p.B) {
@@ -398,7 +398,11 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
         // queueing their requests for W2.  Each of the four draws and gathers the (few) sampled
         // words itself, and they share publishing them: wavefront 1 the action / reward / terminal
         // words, the others the states, a pass each.
-        if (wave < 4) {
+        // With a target network wavefronts 4..7 do the same for the rows s' with its W1 and b1.
+        constexpr unsigned int NL1 = BOTH ? 8u : 4u;   // wavefronts in layer 1
+        constexpr int MGF = BOTH ? 1 : MG;              // groups of four rows each of them takes
+        const unsigned int grp = BOTH ? __builtin_amdgcn_readfirstlane(wave >> 2) : 0u, wq = wave & 3u;
+        if (wave < NL1) {
             // one draw per row, in the lane of that row: first of all, the sampled words take
             // longest to arrive
             unsigned int myslot = 0;
@@ -440,12 +444,12 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
             // group 4 q + i, K quarter kq -- the four lanes of an MFMA block share their kq (they
             // exchange operands), the four quarters of a column sit in one DPP row.
             const unsigned int kq = (lane >> 2) & 3u;
-            const unsigned int ccf = 64u * wave + 4u * (4u * (lane >> 4) + (lane & 3u));
+            const unsigned int ccf = 64u * wq + 4u * (4u * (lane >> 4) + (lane & 3u));
             const bool colf = ccf < H;   // (H is a multiple of 64: all four columns or none)
             f32x4 w1x[8];
             {
                 const unsigned int loff = ((8u * kq) * H + (colf ? ccf : H - 4u)) * 4u;
-                const gbytes base = (gbytes)reinterpret_cast<const char*>(W1);
+                const gbytes base = (gbytes)reinterpret_cast<const char*>(BOTH && grp ? p.wt + p.oW1 : W1);
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
                     gbytes rb = base + (size_t)u * H * 4u;
@@ -453,7 +457,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
                     w1x[u] = *(const __attribute__((address_space(1))) f32x4*)(rb + loff);
                 }
             }
-            const f32x4 b1f = *reinterpret_cast<const f32x4*>(p.w + p.ob1 + (colf ? ccf : H - 4u));
+            const f32x4 b1f = *reinterpret_cast<const f32x4*>((BOTH && grp ? p.wt : p.w) + p.ob1 + (colf ? ccf : H - 4u));
             // the private copy (in the partial-sum buffer, which nothing uses before layer 2)
             float* Xp = part + wave * (PR * ldx);
             for (unsigned int e = lane; e < PR * ldx; e += 64u) Xp[e] = 0.f;
@@ -486,17 +490,17 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
             }
             // (a wavefront's LDS operations complete in order: its copy is there)
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            f32x4 accf[MG][4];
+            f32x4 accf[MGF][4];
             {
-                const float* ap = Xp + (lane & 3u) * ldx + 8u * kq;
+                const float* ap = Xp + (4u * grp + (lane & 3u)) * ldx + 8u * kq;
 #pragma unroll
-                for (int mg = 0; mg < MG; ++mg)
+                for (int mg = 0; mg < MGF; ++mg)
 #pragma unroll
                     for (int j = 0; j < 4; ++j) accf[mg][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int u0 = 0; u0 < 8; u0 += 4)
 #pragma unroll
-                    for (int mg = 0; mg < MG; ++mg) {
+                    for (int mg = 0; mg < MGF; ++mg) {
                         const f32x4 av = *reinterpret_cast<const f32x4*>(ap + (size_t)mg * 4 * ldx + u0);
 #pragma unroll
                         for (int u = 0; u < 4; ++u)
@@ -508,7 +512,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
             }
             // sum the four K quarters (lanes 4 apart within a DPP row), then lane kq takes row kq
 #pragma unroll
-            for (int mg = 0; mg < MG; ++mg) {
+            for (int mg = 0; mg < MGF; ++mg) {
                 f32x4 hv = b1f;
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
@@ -521,7 +525,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
                     }
 #pragma unroll
                 for (int j = 0; j < 4; ++j) hv[j] = hv[j] > 0.f ? hv[j] : 0.f;
-                const unsigned int row = mg * 4 + kq;
+                const unsigned int row = (mg + grp) * 4 + kq;
                 if (colf) {
                     *reinterpret_cast<f32x4*>(H1s + row * ldh + ccf) = hv;
                     if (row < nrows) *reinterpret_cast<f32x4*>(p.H1 + (size_t)(i0 + row) * H + ccf) = hv;
@@ -531,10 +535,14 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
         } else {
             load_cols4<16>(w2r, W2, H, cc, ks * q2, q2);
             if constexpr (W3_EARLY) load_cols<16>(w3r, W3, Ap, lane, wave * s3, s3);
-            // the other biases: wavefronts 4..7
-            const unsigned int t4 = tid - 256u;
+            // the other biases: the four wavefronts after layer 1's
+            const unsigned int t4 = tid - 64u * NL1;
             if (t4 < H) b2s[t4] = p.w[p.ob2 + t4];
             if (t4 < Ap) b3s[t4] = p.w[p.ob3 + t4];
+            if constexpr (BOTH) {
+                if (t4 < H) b2ts[t4] = p.wt[p.ob2 + t4];
+                if (t4 < Ap) b3ts[t4] = p.wt[p.ob3 + t4];
+            }
         }
         // The last workgroup also writes the new experiences into the ring.  No workgroup reads
         // those slots from the ring in this launch (see above), so this can go out right away and
