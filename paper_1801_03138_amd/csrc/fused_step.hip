@@ -368,7 +368,8 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     f32x4 acc2[MG];
     // layer 3's weights can be requested with W2 by the wavefronts that have no part in the fast
     // layer 1 (two experiences per workgroup: the registers hold them next to layer 2's sums)
-    constexpr bool W3_EARLY = FAST && R == 2;
+    constexpr bool W3_EARLY = FAST && (R == 2 || BOTH);   // (four experiences without a target network: no room)
+    constexpr unsigned int NL1 = BOTH ? 8u : 4u;   // wavefronts in the fast layer 1
     const unsigned long long cap = p.g.capacity;
     const unsigned long long head = p.head;
     const unsigned long long step = p.step;
@@ -399,7 +400,6 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
         // words itself, and they share publishing them: wavefront 1 the action / reward / terminal
         // words, the others the states, a pass each.
         // With a target network wavefronts 4..7 do the same for the rows s' with its W1 and b1.
-        constexpr unsigned int NL1 = BOTH ? 8u : 4u;   // wavefronts in layer 1
         constexpr int MGF = BOTH ? 1 : MG;              // groups of four rows each of them takes
         const unsigned int grp = BOTH ? __builtin_amdgcn_readfirstlane(wave >> 2) : 0u, wq = wave & 3u;
         if (wave < NL1) {
@@ -706,7 +706,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
         store_part4(part, ks, 8, 4, kChunk, cc, acc4[0]);
     }
     // The accumulators are free: layer 3's weights are requested, and ...
-    if (!W3_EARLY || wave < 4) load_cols<16>(w3r, W3, Ap, lane, wave * s3, s3);
+    if (!W3_EARLY || wave < NL1) load_cols<16>(w3r, W3, Ap, lane, wave * s3, s3);
     // ... the column of W3 that the backward pass of each row needs: W3[k][a_r], one per thread
     float w3sel = 0.f;
     {
