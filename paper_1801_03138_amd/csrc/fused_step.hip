@@ -3,7 +3,7 @@
 //
 // Everything that concerns one sampled experience is independent of the other rows of the
 // batch: its slot draw, its gather, the forward pass on s and s', the TD target, and the
-// backward pass down to the pre-activation gradients.  Kernel 1 does all of that for four
+// backward pass down to the pre-activation gradients.  Kernel 1 does all of that for two or four
 // experiences per workgroup, keeping activations in LDS and streaming the weights through
 // 4x4x1 fp32 MFMA (four rows per instruction, so a four-row tile is not padded).  It also
 // appends the step's new experiences.  Only the weight gradients reduce over the batch:
@@ -344,7 +344,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     const float* W2 = p.w + p.oW2;
     const float* W3 = p.w + p.oW3;
     // Frozen target network: rows 4..7 (the new states) go through its weights instead.  The lane's
-    // registers take the trained network's share of a layer first (rows 0..3) and are refilled
+    // registers take the trained network's share of a layer first (rows 0..3: R = 4 then) and are refilled
     // with the target's during those MFMAs.
     constexpr bool both = BOTH;
     // wide split (layer 2 and backward): K sixteenths
@@ -756,7 +756,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     lds_barrier();
 
     // ---- Q values (sums of the partial products), TD target, loss term, dL/dQ: wavefront
-    // 12 + r takes rows r (s) and 4 + r (s'), one action per lane (A <= 64).  What it has to
+    // 12 + r takes rows r (s) and R + r (s'), one action per lane (A <= 64).  What it has to
     // store to global memory waits until the next phase: right now the load path is busy with
     // the other wavefronts' requests and a store would queue up behind them.
     float td_qs = 0.f, td_qn = 0.f, td_y = 0.f, td_d = 0.f, td_li = 0.f, td_gr = 0.f;
