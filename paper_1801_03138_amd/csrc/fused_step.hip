@@ -306,7 +306,6 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     constexpr int MG = R / 2;            // groups of four rows
     constexpr unsigned int NRW = 2 * R;  // rows of a workgroup
     constexpr unsigned int PR = NRW;     // rows of its MFMA groups
-    constexpr bool FAST = NR1 == 8;   // layer 1 by four (with a target network: eight) wavefronts on their own
     extern __shared__ float lds[];
     touch_kernel_args<RowArgs>();
     if (blockIdx.x * R >= p.B) {
@@ -331,7 +330,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     float* Qs = H2s + 8 * ldh;            // [8][ldq]
     float* dZs = Qs + 8 * ldq;            // [4][ldh]
     float* part = dZs + 4 * ldh;          // [16][8][256] or [16][8][64]
-    float* b1s = part + 16 * 8 * kChunk;  // [H]
+    float* b1s = part + 16 * 8 * kChunk;  // [H]   (layer 1's biases stay in registers: unused)
     float* b2s = b1s + H;                 // [H]
     float* b3s = b2s + H;                 // [Ap]
     float* b1ts = b3s + Ap;               // [H]   the frozen target network's biases
@@ -350,26 +349,21 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     // wide split (layer 2 and backward): K sixteenths
     const unsigned int cc = 4u * lane, ks = wave;
     const unsigned int q2 = H >> 4;
-    // layer 1 (a small matrix: sixteen slices of partial sums would cost more than its fetch):
-    // a lane owns one column, wavefront w covers columns 64*(w&3).. and the K quarter w>>2
-    const unsigned int c1 = 64u * (wave & 3u) + lane, k1 = wave >> 2;
-    const unsigned int q1 = Dp >> 2;
     // narrow split
     const unsigned int s3 = H >> 4;                 // K sixteenth of layer 3
 
     // ---- phase 0.  Fetching the weights is what the kernel waits for longest (the rate at which
-    // a compute unit takes in data bounds it), so the request stream never pauses: layer 1's
-    // weights first, the sampled rows (the ring and trainer state before this step come as
-    // arguments, the host mirrors them exactly, so the draw needs no memory access), the first
-    // half of layer 2's weights, and its second half once the sample is in LDS, behind which
-    // layer 1 runs.
+    // a compute unit takes in data bounds it), so the request stream never pauses: most
+    // wavefronts queue their share of W2 (and W3) from the first instruction on, while a few
+    // draw and gather the sample and run layer 1 (the ring and trainer state before this step
+    // come as arguments, the host mirrors them exactly, so the draw needs no memory access).
     f32x4 w2r[16];
     float w3r[16];
     f32x4 acc2[MG];
-    // layer 3's weights can be requested with W2 by the wavefronts that have no part in the fast
+    // layer 3's weights can be requested with W2 by the wavefronts that have no part in
     // layer 1 (two experiences per workgroup: the registers hold them next to layer 2's sums)
-    constexpr bool W3_EARLY = FAST && (R == 2 || BOTH);   // (four experiences without a target network: no room)
-    constexpr unsigned int NL1 = BOTH ? 8u : 4u;   // wavefronts in the fast layer 1
+    constexpr bool W3_EARLY = R == 2 || BOTH;   // (four experiences without a target network: no room)
+    constexpr unsigned int NL1 = BOTH ? 8u : 4u;   // wavefronts in layer 1
     const unsigned long long cap = p.g.capacity;
     const unsigned long long head = p.head;
     const unsigned long long step = p.step;
@@ -392,8 +386,8 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
         p.ctr->c2 = p.c2_after;
     }
 
-    if constexpr (FAST) {
-        // ---- narrow first layer (Dp = 32): wavefronts 0..3 take layer 1 on their own, each for
+    {
+        // ---- layer 1: wavefronts 0..3 take it on their own, each for
         // 64 output columns over the whole K, from a private copy of the sample: no partial sums
         // and no barrier before layer 2's, so nothing here waits for the wavefronts that are still
         // queueing their requests for W2.  Each of the four draws and gathers the (few) sampled
@@ -418,7 +412,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
                         myslot = batch_draw(p.g.sampling, p.seed, step, i0 + lane, size);
                 }
             }
-            constexpr int NPASS = (R * 67 + 63) / 64;   // 2 D + 3 <= 67 words per row
+            constexpr int NPASS = (R * (8 * NR1 + 3) + 63) / 64;   // 2 D + 3 <= 8 NR1 + 3 words per row
             unsigned int gv[NPASS], gsl[NPASS];
 #pragma unroll
             for (int pass = 0; pass < NPASS; ++pass) {
@@ -440,18 +434,18 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
                 }
             }
             // W1: the wavefront covers columns 64 w .. 64 w + 63 as 16 groups of four adjacent
-            // columns times 4 quarters of K (8 rows each).  Lane l = 16 q + 4 kq + i: column
+            // columns times 4 quarters of K (NR1 rows each).  Lane l = 16 q + 4 kq + i: column
             // group 4 q + i, K quarter kq -- the four lanes of an MFMA block share their kq (they
             // exchange operands), the four quarters of a column sit in one DPP row.
             const unsigned int kq = (lane >> 2) & 3u;
             const unsigned int ccf = 64u * wq + 4u * (4u * (lane >> 4) + (lane & 3u));
             const bool colf = ccf < H;   // (H is a multiple of 64: all four columns or none)
-            f32x4 w1x[8];
+            f32x4 w1x[NR1];
             {
-                const unsigned int loff = ((8u * kq) * H + (colf ? ccf : H - 4u)) * 4u;
+                const unsigned int loff = (((unsigned int)NR1 * kq) * H + (colf ? ccf : H - 4u)) * 4u;
                 const gbytes base = (gbytes)reinterpret_cast<const char*>(BOTH && grp ? p.wt + p.oW1 : W1);
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
+                for (int u = 0; u < NR1; ++u) {
                     gbytes rb = base + (size_t)u * H * 4u;
                     asm volatile("" : "+s"(rb));
                     w1x[u] = *(const __attribute__((address_space(1))) f32x4*)(rb + loff);
@@ -492,13 +486,13 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             f32x4 accf[MGF][4];
             {
-                const float* ap = Xp + (4u * grp + (lane & 3u)) * ldx + 8u * kq;
+                const float* ap = Xp + (4u * grp + (lane & 3u)) * ldx + (unsigned int)NR1 * kq;
 #pragma unroll
                 for (int mg = 0; mg < MGF; ++mg)
 #pragma unroll
                     for (int j = 0; j < 4; ++j) accf[mg][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int u0 = 0; u0 < 8; u0 += 4)
+                for (int u0 = 0; u0 < NR1; u0 += 4)
 #pragma unroll
                     for (int mg = 0; mg < MGF; ++mg) {
                         const f32x4 av = *reinterpret_cast<const f32x4*>(ap + (size_t)mg * 4 * ldx + u0);
@@ -558,134 +552,6 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
             }
         }
         lds_barrier();
-    } else {
-        float w1r[NR1];
-        load_cols<NR1>(w1r, W1, H, c1, k1 * q1, q1);
-        // sample and gather: one 32-bit word per thread (two passes at most, D <= 64).  A drawn
-        // slot that this step's append is about to overwrite is read from the payload arrays,
-        // which hold its new content.
-        unsigned int gval[2] = {0u, 0u}, gslot[2] = {0u, 0u};
-    #pragma unroll
-        for (int pass = 0; pass < 2; ++pass) {
-            const unsigned int e = tid + pass * kRowThreads;
-            if (e < nrows * words) {
-                const unsigned int r = e / words, w = e - r * words;
-                if (p.from_batch) {
-                    // the caller's batch: row i0 + r of its arrays; reported slot = position in the batch
-                    gslot[pass] = i0 + r;
-                    gval[pass] = payload_word(p.batch, D, i0 + r, w);
-                } else {
-                    unsigned int slot;
-                    const unsigned int* ahead = p.pre ? p.pre + ((step & 1u) ? p.pre_stride : 0u) : nullptr;
-                    if (ahead && ahead[0] == (unsigned int)step && ahead[1] == (unsigned int)(step >> 32) &&
-                        ahead[2] == size)
-                        slot = ahead[4 + i0 + r];   // drawn during the previous step
-                    else
-                        slot = batch_draw(p.g.sampling, p.seed, step, i0 + r, size);
-                    unsigned long long off = (unsigned long long)slot + cap - head;
-                    if (off >= cap) off -= cap;
-                    gslot[pass] = slot;
-                    gval[pass] = off < n ? staged_word(p, off, w)
-                                         : reinterpret_cast<const unsigned int*>(
-                                               p.g.rows + (unsigned long long)slot * p.g.row_bytes)[w];
-                }
-            }
-        }
-        // The last workgroup also writes the new experiences into the ring.  No workgroup reads
-        // those slots from the ring in this launch (see above), so this can go out right away and
-        // its latency is hidden behind the rest of the kernel.
-        if (i0 + R >= p.B && n) {
-            const unsigned int rw = p.g.row_bytes >> 2;
-            for (unsigned long long e = tid; e < n * rw; e += kRowThreads) {
-                const unsigned long long k = e / rw;
-                const unsigned int w = (unsigned int)(e - k * rw);
-                unsigned long long slot = head + k;
-                if (slot >= cap) slot -= cap;
-                reinterpret_cast<unsigned int*>(p.g.rows + slot * p.g.row_bytes)[w] = staged_word(p, k, w);
-            }
-        }
-        const float b1v = tid < H ? p.w[p.ob1 + tid] : 0.f;
-        const float b2v = tid < H ? p.w[p.ob2 + tid] : 0.f;
-        const float b3v = tid < Ap ? p.w[p.ob3 + tid] : 0.f;
-        load_cols4<16, 0, 8>(w2r, W2, H, cc, ks * q2, q2);
-        // A wavefront that holds none of the sampled words has nothing to deliver before the
-        // barrier that publishes the sample: it requests the rest of W2 right away.  The others do
-        // so behind the barrier, so that their wait for the load path does not hold the sample up
-        // (requesting nothing of W2 before the barrier was slower for them).
-        const bool has_sample = wave * 64u < nrows * words;
-        if (!has_sample) load_cols4<16, 8, 16>(w2r, W2, H, cc, ks * q2, q2);
-
-        // zeros wherever no sampled word goes: padding columns, rows past the batch, unused meta
-        for (unsigned int e = tid; e < NRW * ldx; e += kRowThreads) {
-            const unsigned int row = e / ldx, col = e - row * ldx;
-            if (col >= D || (row & (R - 1u)) >= nrows) Xs[e] = 0.f;
-        }
-        if (tid < 16 && ((tid >> 2) >= nrows || (tid & 3u) == 3u)) meta[tid] = 0;
-
-    #pragma unroll
-        for (int pass = 0; pass < 2; ++pass) {
-            const unsigned int e = tid + pass * kRowThreads;
-            if (e < nrows * words) {
-                const unsigned int r = e / words, w = e - r * words;
-                const unsigned int i = i0 + r;
-                const unsigned int val = gval[pass];
-                if (w < D) {
-                    Xs[r * ldx + w] = __uint_as_float(val);
-                    p.X[(size_t)i * Dp + w] = __uint_as_float(val);
-                } else if (w < 2 * D) {
-                    Xs[(R + r) * ldx + w - D] = __uint_as_float(val);
-                } else {
-                    meta[r * 4 + (w - 2 * D)] = val;
-                    if (w == 2 * D) {
-                        p.act[i] = (int)val;
-                        p.idx[i] = gslot[pass];
-                    } else if (w == 2 * D + 1) {
-                        p.rew[i] = __uint_as_float(val);
-                    } else {
-                        p.term[i] = (unsigned char)val;
-                    }
-                }
-            }
-        }
-        if (tid < H) {
-            b1s[tid] = b1v;
-            b2s[tid] = b2v;
-        }
-        if (tid < Ap) b3s[tid] = b3v;
-        lds_barrier();
-        if (has_sample) load_cols4<16, 8, 16>(w2r, W2, H, cc, ks * q2, q2);
-
-        // ---- layer 1
-        if constexpr (!BOTH) {
-            mma_cols<MG, NR1>(acc2, Xs, ldx, k1 * q1, q1, w1r);
-        } else {
-            // the target network's biases travel during the first MFMAs (kept out of the registers
-            // that are scarce while W2 is arriving)
-            const float b1tv = tid < H ? p.wt[p.ob1 + tid] : 0.f;
-            const float b2tv = tid < H ? p.wt[p.ob2 + tid] : 0.f;
-            const float b3tv = tid < Ap ? p.wt[p.ob3 + tid] : 0.f;
-            f32x4 lo[1], hi[1];
-            mma_cols_reload<1, NR1>(lo, Xs, ldx, k1 * q1, q1, w1r, p.wt + p.oW1, H, c1, k1 * q1, q1);
-            mma_cols<1, NR1>(hi, Xs + 4 * ldx, ldx, k1 * q1, q1, w1r);
-            acc2[0] = lo[0];
-            acc2[1] = hi[0];
-            if (tid < H) {
-                b1ts[tid] = b1tv;
-                b2ts[tid] = b2tv;
-            }
-            if (tid < Ap) b3ts[tid] = b3tv;
-        }
-        store_part<MG>(part, k1, kChunk, c1, acc2);
-        lds_barrier();
-        for (unsigned int e = tid; e < NRW * H; e += kRowThreads) {
-            const unsigned int row = e / H, c = e - row * H;
-            float v = sum_part(part, 4, NRW, kChunk, row, c) + (both && row >= R ? b1ts : b1s)[c];
-            v = v > 0.f ? v : 0.f;
-            H1s[row * ldh + c] = v;
-            if (row < nrows) p.H1[(size_t)(i0 + row) * H + c] = v;
-        }
-        lds_barrier();
-
     }
 
     // ---- layer 2.  From here on the fetch of W2^T (for the backward pass, into the registers
