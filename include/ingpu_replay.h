@@ -88,11 +88,16 @@ typedef struct {
 } replay_config;
 
 /* Bytes of device memory replay_create needs for this configuration (0 if the
- * configuration is invalid).  Pure host arithmetic. */
+ * configuration is invalid).  Pure host arithmetic.  (Methods: the replay is one device-resident
+ * array of capacity x (2D+3) values, 1,000,000 x 57 floats in the paper; here each row is padded,
+ * see replay_row_bytes, and a small state block and staging area precede the rows.) */
 size_t replay_storage_bytes(const replay_config* cfg);
 
-/* Bytes of one stored experience (PAIR: the padded packed row; CHAIN: the padded
- * state slot plus 9 bytes of side data).  Pure host arithmetic; 0 if invalid. */
+/* Bytes of one stored experience.  PAIR (Methods: a row packs both states, action, reward and
+ * is_terminal, 2D+3 values): the packed row padded to 16, 32 or 64 bytes or to a multiple of
+ * 128 bytes, 256 for the paper's 57 floats.  CHAIN (Discussion: one state per experience): the
+ * state padded the same way plus 9 bytes of side data (action, reward, is_terminal).
+ * Pure host arithmetic; 0 if invalid. */
 size_t replay_row_bytes(const replay_config* cfg);
 
 /*

@@ -76,6 +76,7 @@ def lib():
         L.oracle_loss_fixed_targets.argtypes = [vp, vp, vp, vp, vp]
         L.oracle_loss_fixed_targets.restype = C.c_double
         L.oracle_train_step.argtypes = [vp] * 16
+        L.oracle_opt_apply.argtypes = [vp, C.c_size_t, vp, vp, vp, vp, vp]
         L.oracle_train_step_target.argtypes = [vp] * 17
         _lib = L
     return _lib
@@ -245,6 +246,23 @@ def target_after_step(target, new_params, updates_applied, sync_every):
     if sync_every and updates_applied % sync_every == 0:
         return np.array(new_params, np.float64)
     return np.array(target, np.float64)
+
+
+def opt_apply(cfg, params, m, v, t, grads):
+    """The parameter update alone from a given gradient, on copies; returns (params, m, v, t) in
+    float64 (m, v None and t unchanged for SGD)."""
+    p = np.array(params, np.float64, order="C")
+    g = _c(grads, np.float64)
+    assert g.shape == p.shape
+    tt = C.c_uint64(int(t))
+    if cfg.opt == SGD:
+        lib().oracle_opt_apply(C.byref(cfg), p.shape[0], _p(p), None, None, C.byref(tt), _p(g))
+        return p, None, None, tt.value
+    mm = np.array(m, np.float64, order="C")
+    vv = np.array(v, np.float64, order="C")
+    assert mm.shape == p.shape and vv.shape == p.shape
+    lib().oracle_opt_apply(C.byref(cfg), p.shape[0], _p(p), _p(mm), _p(vv), C.byref(tt), _p(g))
+    return p, mm, vv, tt.value
 
 
 class StepResult:

@@ -423,6 +423,29 @@ double oracle_loss_fixed_targets(const oracle_train_cfg* cfg, const double* para
 }
 
 /*
+ * The parameter update of one step from a given gradient g of the mean loss (Deep Q-Network
+ * Model: the update equation moves w against the gradient, scaled by the step size alpha).
+ * SGD: w <- w - lr g.  Adam (Kingma & Ba): t <- t + 1, m <- beta1 m + (1 - beta1) g,
+ * v <- beta2 v + (1 - beta2) g^2, w <- w - lr (m / (1 - beta1^t)) / (sqrt(v / (1 - beta2^t)) + eps).
+ * m, v, t are untouched by SGD (and may be NULL then).
+ */
+void oracle_opt_apply(const oracle_train_cfg* cfg, size_t n, double* params, double* m, double* v,
+                      uint64_t* t, const double* g) {
+    if (cfg->opt == ORACLE_SGD) {
+        for (size_t k = 0; k < n; ++k) params[k] -= cfg->lr * g[k];
+        return;
+    }
+    *t += 1;
+    double c1 = 1.0 - pow(cfg->beta1, (double)*t);
+    double c2 = 1.0 - pow(cfg->beta2, (double)*t);
+    for (size_t k = 0; k < n; ++k) {
+        m[k] = cfg->beta1 * m[k] + (1.0 - cfg->beta1) * g[k];
+        v[k] = cfg->beta2 * v[k] + (1.0 - cfg->beta2) * g[k] * g[k];
+        params[k] -= cfg->lr * (m[k] / c1) / (sqrt(v[k] / c2) + cfg->eps);
+    }
+}
+
+/*
  * One Q-learning step (Deep Q-Network Model, the update equation; Integration:
  * Q(s,a) is entry i*A + a_i of the flattened network output).
  *   y_i     = r_i + gamma * (1 - terminal_i) * max_a' Q_w(s'_i, a')   (a constant)
@@ -553,18 +576,7 @@ void oracle_train_step_target(const oracle_train_cfg* cfg, double* params,
         for (uint32_t j = 0; j < H; ++j) gb1[j] += dz1[(size_t)i * H + j];
 
     /* parameter update on the (unrounded) master parameters */
-    if (cfg->opt == ORACLE_SGD) {
-        for (size_t k = 0; k < P; ++k) params[k] -= cfg->lr * g[k];
-    } else {
-        *t += 1;
-        double c1 = 1.0 - pow(cfg->beta1, (double)*t);
-        double c2 = 1.0 - pow(cfg->beta2, (double)*t);
-        for (size_t k = 0; k < P; ++k) {
-            m[k] = cfg->beta1 * m[k] + (1.0 - cfg->beta1) * g[k];
-            v[k] = cfg->beta2 * v[k] + (1.0 - cfg->beta2) * g[k] * g[k];
-            params[k] -= cfg->lr * (m[k] / c1) / (sqrt(v[k] / c2) + cfg->eps);
-        }
-    }
+    oracle_opt_apply(cfg, P, params, m, v, t, g);
 
     if (Q_out) memcpy(Q_out, Q, (size_t)B * A * sizeof(double));
     if (Qn_out) memcpy(Qn_out, Qn, (size_t)B * A * sizeof(double));

@@ -101,6 +101,11 @@ void oracle_mlp_forward(const oracle_train_cfg* cfg, const double* params, const
 double oracle_loss_fixed_targets(const oracle_train_cfg* cfg, const double* params,
                                  const double* S, const int32_t* a, const double* y);
 
+/* The parameter update alone, from a given gradient of the mean loss: SGD, or Adam with bias
+ * correction (t is advanced first).  params, m, v [n] are updated in place. */
+void oracle_opt_apply(const oracle_train_cfg* cfg, size_t n, double* params, double* m, double* v,
+                      uint64_t* t, const double* g);
+
 /* One Q-learning step on a batch.  params (and m, v, t for Adam) are updated in
  * place.  Optional outputs (NULL to skip): Q[B*A], Qn[B*A], y[B], delta[B],
  * loss[1], grads[param_count]. */

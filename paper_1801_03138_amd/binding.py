@@ -123,6 +123,68 @@ def _host(arr):
     return None if arr is None else arr.ctypes.data_as(C.c_void_p)
 
 
+# torch dtypes a device array of each state type may have (bf16 bits also travel as 16-bit ints)
+_TORCH_STATE = {RP_F32: (torch.float32,), RP_BF16: (torch.bfloat16, torch.int16, torch.uint16),
+                RP_U8: (torch.uint8,)}
+_TORCH_I32 = (torch.int32, torch.uint32)
+
+
+def check_device_array(t, dtypes, numel, device, what):
+    """The C interface carries no lengths: a device array handed to the library must be a
+    contiguous tensor on the replay's device with the expected element type and count, or the
+    kernels would read or write out of bounds.  Raises ValueError otherwise; returns t."""
+    if not isinstance(t, torch.Tensor):
+        raise ValueError(f"{what}: expected a torch tensor on {device}, got {type(t).__name__}")
+    dev = torch.device(device)
+    if t.device.type != dev.type or (dev.index is not None and t.device.index != dev.index):
+        raise ValueError(f"{what}: tensor is on {t.device}, the replay is on {dev}")
+    if t.dtype not in dtypes:
+        raise ValueError(f"{what}: dtype {t.dtype}, expected one of {tuple(str(d) for d in dtypes)}")
+    if not t.is_contiguous():
+        raise ValueError(f"{what}: tensor is not contiguous")
+    if t.numel() != numel:
+        raise ValueError(f"{what}: {t.numel()} elements, expected {numel}")
+    return t
+
+
+def check_device_experiences(cfg, device, n, s, s_next, a, r, term, what):
+    """n experiences as device arrays, structure of arrays (s_next is ignored for RP_CHAIN)."""
+    D, st = cfg.state_dim, _TORCH_STATE[cfg.state_dtype]
+    check_device_array(s, st, n * D, device, what + ": s")
+    if cfg.layout == RP_PAIR:
+        check_device_array(s_next, st, n * D, device, what + ": s_next")
+    check_device_array(a, _TORCH_I32, n, device, what + ": a")
+    check_device_array(r, (torch.float32,), n, device, what + ": r")
+    check_device_array(term, (torch.uint8, torch.bool), n, device, what + ": term")
+
+
+def check_host_experiences(cfg, n, s, s_next, a, r, term, what):
+    """n experiences as host arrays (already converted to the field types): element counts."""
+    D = cfg.state_dim
+    fields = [("s", s, n * D), ("a", a, n), ("r", r, n), ("term", term, n)]
+    if cfg.layout == RP_PAIR:
+        fields.append(("s_next", s_next, n * D))
+    for name, arr, want in fields:
+        if arr is None or arr.size != want:
+            raise ValueError(f"{what}: {name} has {None if arr is None else arr.size} elements, expected {want}")
+
+
+def check_batch_out(cfg, device, batch, out, what):
+    """The six output tensors of sample_gather for `batch` experiences."""
+    if len(out) != 6:
+        raise ValueError(f"{what}: expected (s, s_next, a, r, term, idx)")
+    s, s_next, a, r, term, idx = out
+    D, dt = cfg.state_dim, _TORCH_OUT[cfg.state_dtype]
+    st = (dt,) if dt != torch.bfloat16 else _TORCH_STATE[RP_BF16]
+    check_device_array(s, st, batch * D, device, what + ": s")
+    check_device_array(s_next, st, batch * D, device, what + ": s_next")
+    check_device_array(a, _TORCH_I32, batch, device, what + ": a")
+    check_device_array(r, (torch.float32,), batch, device, what + ": r")
+    check_device_array(term, (torch.uint8,), batch, device, what + ": term")
+    if idx is not None:
+        check_device_array(idx, _TORCH_I32, batch, device, what + ": idx")
+
+
 def _alloc_bytes(nbytes, device):
     # torch's caching allocator hands out blocks aligned to at least 256 bytes
     buf = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
@@ -172,6 +234,9 @@ class Replay:
         on_dev = isinstance(a, torch.Tensor)
         n = len(a)
         if on_dev:
+            check_device_experiences(self.cfg, self.device, n, s, s_next, a, r, term, "append")
+            if self.cfg.layout != RP_PAIR:
+                s_next = None
             args = [_dev(s), _dev(s_next), _dev(a), _dev(r), _dev(term)]
             keep = None
         else:
@@ -179,6 +244,7 @@ class Replay:
                     None if s_next is None else np.ascontiguousarray(s_next, self.np_state),
                     np.ascontiguousarray(a, np.int32), np.ascontiguousarray(r, np.float32),
                     np.ascontiguousarray(term, np.uint8)]
+            check_host_experiences(self.cfg, n, *keep, "append")
             args = [_host(x) for x in keep]
         return _check(lib().replay_append(self._h, n, *args, 1 if on_dev else 0,
                                           _stream_ptr(stream)))
@@ -196,6 +262,7 @@ class Replay:
     def sample_gather(self, step, batch, out=None, stream=None):
         """Returns (status, (s, s_next, a, r, term, idx)); status 1 = refused during burn-in."""
         out = self.alloc_batch(batch) if out is None else out
+        check_batch_out(self.cfg, self.device, batch, out, "sample_gather")
         st = _check(lib().replay_sample_gather(self._h, step, batch, *[_dev(t) for t in out],
                                                _stream_ptr(stream)))
         return st, out
@@ -248,44 +315,48 @@ class Trainer:
 
     __del__ = close
 
+    def _payload(self, n, s, s_next, a, r, term, what):
+        """Marshal n new experiences (numpy arrays or CUDA tensors; none when n = 0): returns
+        (pointer arguments, src_is_device, arrays to keep alive)."""
+        if n == 0:
+            return [None] * 5, 0, None
+        if a is None:
+            raise ValueError(f"{what}: this trainer appends {self.cfg.appends_per_step} experiences per "
+                             "step; the arrays are missing")
+        rc = self.replay.cfg
+        if isinstance(a, torch.Tensor):
+            check_device_experiences(rc, self.replay.device, n, s, s_next, a, r, term, what)
+            return [_dev(s), _dev(s_next), _dev(a), _dev(r), _dev(term)], 1, None
+        st = self.replay.np_state
+        keep = [np.ascontiguousarray(s, st), np.ascontiguousarray(s_next, st),
+                np.ascontiguousarray(a, np.int32), np.ascontiguousarray(r, np.float32),
+                np.ascontiguousarray(term, np.uint8)]
+        # the library reads exactly n experiences; longer arrays are allowed (steps() slices them)
+        for name, arr, want in (("s", keep[0], n * rc.state_dim), ("s_next", keep[1], n * rc.state_dim),
+                                ("a", keep[2], n), ("r", keep[3], n), ("term", keep[4], n)):
+            if arr.size < want:
+                raise ValueError(f"{what}: {name} has {arr.size} elements, needs {want}")
+        return [_host(x) for x in keep], 0, keep
+
     def step(self, s=None, s_next=None, a=None, r=None, term=None, stream=None):
         """One train step; the arrays are the appends_per_step new experiences (numpy or CUDA tensors)."""
-        on_dev = isinstance(a, torch.Tensor)
-        if a is None:
-            args, keep = [None] * 5, None
-        elif on_dev:
-            args, keep = [_dev(s), _dev(s_next), _dev(a), _dev(r), _dev(term)], None
-        else:
-            st = self.replay.np_state
-            keep = [np.ascontiguousarray(s, st), np.ascontiguousarray(s_next, st),
-                    np.ascontiguousarray(a, np.int32), np.ascontiguousarray(r, np.float32),
-                    np.ascontiguousarray(term, np.uint8)]
-            args = [_host(x) for x in keep]
-        return _check(lib().train_step(self._h, *args, 1 if on_dev else 0, _stream_ptr(stream)))
+        args, on_dev, keep = self._payload(self.cfg.appends_per_step, s, s_next, a, r, term, "step")
+        return _check(lib().train_step(self._h, *args, on_dev, _stream_ptr(stream)))
 
     def steps(self, count, s=None, s_next=None, a=None, r=None, term=None, stream=None):
         """`count` train steps in one call; the arrays hold count*appends_per_step experiences.
         Returns the number of steps that trained (the others only appended, during burn-in)."""
-        on_dev = isinstance(a, torch.Tensor)
-        if a is None:
-            args, keep = [None] * 5, None
-        elif on_dev:
-            args, keep = [_dev(s), _dev(s_next), _dev(a), _dev(r), _dev(term)], None
-        else:
-            st = self.replay.np_state
-            keep = [np.ascontiguousarray(s, st), np.ascontiguousarray(s_next, st),
-                    np.ascontiguousarray(a, np.int32), np.ascontiguousarray(r, np.float32),
-                    np.ascontiguousarray(term, np.uint8)]
-            args = [_host(x) for x in keep]
-        if a is not None and len(a) < count * self.cfg.appends_per_step:
-            raise ValueError("not enough experiences for that many steps")
+        args, on_dev, keep = self._payload(int(count) * self.cfg.appends_per_step, s, s_next, a, r,
+                                           term, "steps")
         done = C.c_uint64()
-        _check(lib().train_steps(self._h, count, *args, 1 if on_dev else 0, _stream_ptr(stream),
+        _check(lib().train_steps(self._h, count, *args, on_dev, _stream_ptr(stream),
                                  C.byref(done)))
         return done.value
 
     def step_batch(self, s, s_next, a, r, term, stream=None):
         """One train step on the given batch (torch CUDA tensors, as sample_gather returns them)."""
+        check_device_experiences(self.replay.cfg, self.replay.device, self.cfg.batch, s, s_next, a,
+                                 r, term, "step_batch")
         return _check(lib().train_step_batch(self._h, _dev(s), _dev(s_next), _dev(a), _dev(r),
                                              _dev(term), _stream_ptr(stream)))
 

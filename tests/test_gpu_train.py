@@ -2,21 +2,33 @@
 step the oracle is given the GPU's own state (weights, Adam moments, t), both take one step
 on the same sampled batch, and Q-values, targets, loss, gradients and new weights are compared.
 
-Tolerance (written here as the test of record): |x - y| <= rtol * max(|x|, |y|) + rtol * max|ref|
-with rtol = 1e-5 for fp32 and 2e-2 for the bf16 mixed-precision path, for Q-values, targets,
-loss and updated weights (for Adam plus the slack derived in Pair.step where a gradient is no
-larger than its own tolerance).  Gradients and Adam moments are linear (quadratic for v) in
-clip(delta) with delta = y - Q(s,a), a difference of two quantities that each carry the Q
-tolerance, so in fp32 their bound is 10x (m: 10x, v: 20x) the Q bound; a wrong index, sign or
-operand in the backward pass is off by O(1), far outside either.
-
-The ReLU derivative is a step function: where a hidden pre-activation lies within the rounding
-error of its own fp32 sum of zero (|z| <= 16 * 2^-24 * (sum_k |h_k w_k| + |b|)), the two sides may
-land on different sides of the kink, and one hidden unit of one sample then enters the backward
-pass on one side only.  A step whose backward quantities disagree AND that has such a unit in
-the oracle's forward pass is counted in Pair.kink_steps and its backward comparison is dropped
-(forward quantities are still compared); any other disagreement fails as before.  With some
-1e4..1e5 hidden activations per step this happens about once in a few hundred steps.
+Tolerances (written here as the test of record; rtol = 1e-5 for fp32, 2e-2 for the bf16
+mixed-precision path; "close" means |x - y| <= rtol * max(|x|, |y|) + rtol * max|ref|):
+ 1. Q(s,.), Q(s',.), targets, loss: close at rtol.
+ 2. The update rule, with no slack: the oracle's update rule (oracle.opt_apply) is fed the GPU's
+    OWN gradient, moments and t; the GPU's new weights and moments must be close at 1e-5 (both
+    precisions: the update runs on fp32 master weights), and the weight change itself must
+    agree to 1e-3 of the largest change.
+ 3. Gradients, end to end: gradients are linear in clip(delta), delta = y - Q(s,a) being a
+    difference of two quantities that each carry the Q tolerance, so in fp32 their bound is
+    10 x rtol (Adam m: 10 x, v: 20 x); bf16: 2 x (m 2 x, v 4 x).  A wrong index, sign or operand
+    in the backward pass is off by O(1), far outside either.
+ 4. Updated weights, end to end (GPU weights against the oracle's weights from the oracle's own
+    gradient): close at rtol, for Adam plus a slack for the one ill-conditioned spot of the
+    rule: where a gradient is no larger than its own tolerance d (item 3), Adam's quotient
+    m^ / (sqrt(v^) + eps) can move by 2 d / (sqrt(v^) + eps), each factor contributing once, and by
+    no more than 2 in any case, so the slack is 2 lr min(1, 2 d / (sqrt(v^) + eps)).  Item 2 is
+    the check of the rule itself; this one only ties the two ends together.
+ 5. The ReLU derivative is a step function: where a hidden pre-activation lies within the
+    rounding error of its own fp32 sum of zero (|z| <= 16 * 2^-24 * (sum_k |h_k w_k| + |b|)), the
+    two sides may land on different sides of the kink, and that unit of that sample then enters
+    the backward pass on one side only.  A unit of layer 1 can only change column j of dW1 and
+    db1[j]; a unit k of layer 2 column k of dW2, db2[k] and (through dZ1) all of dW1, db1.  On an
+    fp32 step whose gradients disagree AND whose forward pass (oracle side) has such a unit, the
+    entries a kink can reach are left out and everything else (always dW3, db3; dW2, db2 except
+    the kink's columns; dW1, db1 when only layer 1 has kinks) is compared as usual, as are the
+    moments and weights of those entries.  Such steps are counted in Pair.kink_steps, and every
+    test ends with the check that they stayed rare (at most 1 + compared steps / 100).
 """
 import numpy as np
 import pytest
@@ -36,6 +48,20 @@ def B():
     assert torch.cuda.is_available(), "these tests need the MI355X"
     binding.lib()
     return binding
+
+
+_PAIRS = []
+
+
+@pytest.fixture(autouse=True)
+def _kink_budget():
+    """Every test ends with the check that steps excused for a ReLU kink stayed rare."""
+    _PAIRS.clear()
+    yield
+    for pr in _PAIRS:
+        assert pr.kink_steps <= 1 + pr.compared // 100, (
+            "ReLU kinks are rare: %d in %d compared steps is a backward bug" % (pr.kink_steps, pr.compared))
+    _PAIRS.clear()
 
 
 def assert_close(got, ref, rtol, what, slack=0.0):
@@ -80,22 +106,37 @@ class Pair:
                                    **{k: float(v) for k, v in self.hyper.items()})
         self.rtol = BF16_RTOL if self.bf16 else F32_RTOL
         self.kink_steps = 0
+        self.compared = 0
+        self.dueling = dueling
+        _PAIRS.append(self)
 
-    def on_relu_kink(self, p, S):
-        """Whether, from parameters p on states S, some hidden unit of some sample lies within its
-        fp32 rounding error of the ReLU kink (both hidden layers; float64)."""
+    def kink_reach(self, p, S):
+        """Boolean mask over the parameter vector: the gradient entries that a hidden unit lying
+        within its fp32 rounding error of the ReLU kink (from parameters p on states S, float64)
+        can change; None when there is no such unit."""
         D, H = self.D, self.H
+        O = self.A + (1 if self.dueling else 0)
         p = np.asarray(p, np.float64)
         W1, b1 = p[:D * H].reshape(D, H), p[D * H:D * H + H]
         o = D * H + H
         W2, b2 = p[o:o + H * H].reshape(H, H), p[o + H * H:o + H * H + H]
         u = 16.0 * 2.0 ** -24
         z1 = S @ W1 + b1
-        if (np.abs(z1) <= u * (np.abs(S) @ np.abs(W1) + np.abs(b1))).any():
-            return True
+        k1 = (np.abs(z1) <= u * (np.abs(S) @ np.abs(W1) + np.abs(b1))).any(axis=0)
         h1 = np.maximum(z1, 0.0)
         z2 = h1 @ W2 + b2
-        return bool((np.abs(z2) <= u * (h1 @ np.abs(W2) + np.abs(b2))).any())
+        k2 = (np.abs(z2) <= u * (h1 @ np.abs(W2) + np.abs(b2))).any(axis=0)
+        if not k1.any() and not k2.any():
+            return None
+        mW1, mb1 = np.zeros((D, H), bool), np.zeros(H, bool)
+        mW2, mb2 = np.zeros((H, H), bool), np.zeros(H, bool)
+        mW1[:, k1] = True
+        mb1[k1] = True
+        if k2.any():
+            mW2[:, k2] = True
+            mb2[k2] = True
+            mW1[:], mb1[:] = True, True
+        return np.concatenate([mW1.ravel(), mb1, mW2.ravel(), mb2, np.zeros(H * O + O, bool)])
 
     def append_only(self, part, device_src=True):
         self.ref_ring.append(part["s"], part["s_next"], part["a"], part["r"], part["term"])
@@ -139,43 +180,51 @@ class Pair:
         assert np.abs(last["delta"] - ref.delta).max() <= 2 * rt * max(1.0, np.abs(ref.y).max(),
                                                                       np.abs(ref.Q).max())
         assert_close([last["loss"]], [ref.loss], rt, "loss")
-        g_rt = 10 * rt if not self.bf16 else 2 * rt
+        self.compared += 1
         g_got = tr.grads()
+        new_p = tr.params()
+        m2, v2, t2, step2 = tr.opt_state()
+        assert step2 == step + 1
+        # the update rule on the GPU's own gradient: no slack (item 2 of the module docstring)
+        own_p, own_m, own_v, own_t = oracle.opt_apply(self.cfg, p, m, v, t, g_got)
+        assert_close(new_p, own_p, F32_RTOL, "update rule applied to the GPU's own gradient")
+        du = np.abs((new_p.astype(np.float64) - p) - (own_p - p.astype(np.float64)))
+        assert (du <= 1e-3 * np.abs(own_p - p).max() + 2.0 ** -22 * np.abs(p)).all(), "weight change"
+        if self.cfg.opt == oracle.ADAM:
+            assert t2 == t + 1 == own_t
+            assert_close(m2, own_m, F32_RTOL, "Adam m from the GPU's own gradient")
+            assert_close(v2, own_v, F32_RTOL, "Adam v from the GPU's own gradient")
+        # end to end against the oracle's own backward pass
+        g_rt = 10 * rt if not self.bf16 else 2 * rt
+        keep = slice(None)
         try:
             assert_close(g_got, ref.grads, g_rt, "gradients")
         except AssertionError:
-            if self.bf16 or not self.on_relu_kink(p, self.states_f64(s)):
+            reach = None if self.bf16 else self.kink_reach(p, self.states_f64(s))
+            if reach is None:
                 raise
-            # a hidden unit on the ReLU kink (see the module docstring): forward quantities
-            # were compared, the backward ones are not comparable for this step
+            # a hidden unit on the ReLU kink (item 5): what it can reach is left out
             self.kink_steps += 1
-            m2, v2, t2, step2 = tr.opt_state()
-            assert step2 == step + 1
-            return status
-        new_p = tr.params()
+            keep = ~reach
+            assert_close(g_got[keep], ref.grads[keep], g_rt, "gradients a ReLU kink cannot reach")
         slack = 0.0
         if self.cfg.opt == oracle.ADAM:
-            # Adam's step lr * m^ / (sqrt(v^) + eps) is ill-conditioned where a gradient is as
-            # small as its own tolerance d: there the step may move by lr * 2d / (sqrt(v^) + eps),
-            # each factor of the quotient contributing once, and by no more than 2 lr in any case
             d = g_rt * np.maximum(np.abs(g_got), np.abs(ref.grads)) + g_rt * np.abs(ref.grads).max()
             v_hat = np.asarray(ref.v, np.float64) / (1.0 - float(self.hyper["beta2"]) ** ref.t)
             lr, eps = float(self.hyper["lr"]), float(self.hyper["eps"])
-            slack = 2.0 * lr * np.minimum(1.0, 2.0 * d / (np.sqrt(v_hat) + eps))
-        assert_close(new_p, ref.params, rt, "updated weights", slack)
-        m2, v2, t2, step2 = tr.opt_state()
-        assert step2 == step + 1
+            slack = (2.0 * lr * np.minimum(1.0, 2.0 * d / (np.sqrt(v_hat) + eps)))[keep]
+        assert_close(new_p[keep], ref.params[keep], rt, "updated weights", slack)
         if self.target_sync:
             # the frozen copy is exactly the old one, or exactly the new weights when a sync is due
             want = oracle.target_after_step(tgt, new_p, t + 1, self.target_sync)
             assert np.array_equal(tr.target().astype(np.float64), want), "target network"
         if self.cfg.opt == oracle.ADAM:
-            assert t2 == t + 1 == ref.t
-            assert_close(m2, ref.m, 10 * rt if not self.bf16 else 2 * rt, "Adam m")
-            assert_close(v2, ref.v, 20 * rt if not self.bf16 else 4 * rt, "Adam v")
+            assert t2 == ref.t
+            assert_close(m2[keep], ref.m[keep], 10 * rt if not self.bf16 else 2 * rt, "Adam m")
+            assert_close(v2[keep], ref.v[keep], 20 * rt if not self.bf16 else 4 * rt, "Adam v")
         else:
             # the update itself, on its own scale
-            assert_close(new_p.astype(np.float64) - p, ref.params - p.astype(np.float64),
+            assert_close((new_p.astype(np.float64) - p)[keep], (ref.params - p.astype(np.float64))[keep],
                          1e-3 if not self.bf16 else 4 * rt, "weight update")
         return status
 
@@ -273,6 +322,49 @@ def test_many_steps_in_flight(B, dtype, layered, device_src):
     # and the next step still matches the oracle
     extra = synth.experiences(per, 27, 30, 0.05, seed=22, state_dtype=dtype)
     assert pr.step(extra, compare=True) == 0
+
+
+@pytest.mark.parametrize("dtype,H,layered,device_src", [("f32", 64, False, True), ("f32", 64, False, False),
+                                                        ("bf16", 128, False, True), ("f32", 64, True, True)])
+def test_steps_in_flight_equal_steps_synchronised_one_by_one(B, dtype, H, layered, device_src):
+    """The argument block of the kernel that consumes a step's new experiences is rewritten in
+    the recorded graph before every launch, while earlier launches of the same graph may still be
+    running.  2,000 steps queued without any synchronisation (eight steps per graph launch) must
+    leave exactly the state that the same 2,000 steps leave when the device is synchronised after
+    every single step (one step per graph launch): ring, weights, moments, counters and the last
+    step's sampled slots, bit for bit.  Two-kernel step (device and host arrays), MFMA step,
+    layered step."""
+    n_steps, per = 2000, 2
+    rows = synth.experiences(n_steps * per, 27, 30, 0.05, seed=51, state_dtype=dtype)
+    outs = []
+    for one_by_one in (False, True):
+        pr = Pair(B, capacity=1500, D=27, H=H, A=30, batch=64, burn_in=100, seed=5, appends=per,
+                  layered=layered, dtype=dtype, target_sync=9)
+        d = rows
+        if device_src:
+            d = {k: torch.from_numpy(v.view(np.int16) if v.dtype == np.uint16 else v).cuda()
+                 for k, v in rows.items()}
+        tr = pr.trainer
+        if one_by_one:
+            done = 0
+            for k in range(n_steps):
+                lo, hi = k * per, (k + 1) * per
+                done += tr.step(d["s"][lo:hi], d["s_next"][lo:hi], d["a"][lo:hi], d["r"][lo:hi],
+                                d["term"][lo:hi]) == 0
+                torch.cuda.synchronize()
+        else:
+            done = tr.steps(n_steps, d["s"], d["s_next"], d["a"], d["r"], d["term"])
+        assert done == n_steps - 49
+        last = tr.last()
+        outs.append((tr.params(), tr.target(), tr.opt_state(), last["idx"], last["loss"], last["Q"],
+                     pr.gpu_ring.state(), pr.gpu_ring.read_rows(0, 1500)))
+    a, b = outs
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]), "weights / target network"
+    assert np.array_equal(a[2][0], b[2][0]) and np.array_equal(a[2][1], b[2][1]), "Adam moments"
+    assert a[2][2:] == b[2][2:] == (n_steps - 49, n_steps - 49)
+    assert np.array_equal(a[3], b[3]) and a[4] == b[4] and np.array_equal(a[5], b[5])
+    assert a[6] == b[6]
+    assert all(np.array_equal(x.view(np.uint8), y.view(np.uint8)) for x, y in zip(a[7], b[7]))
 
 
 @pytest.mark.parametrize("H,layered,kernels", [(192, False, 2), (320, False, 15), (320, True, 15)])
@@ -602,7 +694,6 @@ def test_random_configurations(B, c):
         part = synth.take(rows, at, at + c["appends"])
         at += c["appends"]
         assert pr.step(part, compare=True) == 0
-    assert pr.kink_steps <= 1, "ReLU kinks are rare: more than one in twelve steps is a backward bug"
 
 
 def test_paper_shaped_free_running_drift(B, capsys):

@@ -258,6 +258,41 @@ def test_adam_bias_correction_with_constant_gradient_history():
     np.testing.assert_allclose(out.params - p, -lr * g / (np.abs(g) + eps), rtol=1e-8, atol=1e-20)
 
 
+def test_update_rule_alone_hand_worked():
+    """oracle.opt_apply on given gradients, every number worked by hand in dyadic arithmetic.
+    SGD: w - lr g.  Adam with beta1 = 1/2, beta2 = 3/4, eps = 0, lr = 1, second step (t: 1 -> 2)
+    from m = 2, v = 4 with g = 4:  m' = 1 + 2 = 3,  v' = 3 + 4 = 7,  1 - beta1^2 = 3/4,
+    1 - beta2^2 = 7/16,  m^ = 4,  v^ = 16,  step = 4 / sqrt(16) = 1."""
+    sgd = oracle.make_cfg(2, 2, 2, 1, opt=oracle.SGD, lr=0.25)
+    p, m, v, t = oracle.opt_apply(sgd, [1.0, -2.0, 0.5], None, None, 7, [4.0, -8.0, 0.0])
+    assert p.tolist() == [0.0, 0.0, 0.5] and m is None and v is None and t == 7
+    adam = oracle.make_cfg(2, 2, 2, 1, opt=oracle.ADAM, lr=1.0, beta1=0.5, beta2=0.75, eps=0.0)
+    p, m, v, t = oracle.opt_apply(adam, [10.0, 10.0], [2.0, -2.0], [4.0, 4.0], 1, [4.0, -4.0])
+    assert t == 2 and m.tolist() == [3.0, -3.0] and v.tolist() == [7.0, 7.0]
+    assert p.tolist() == [9.0, 11.0]
+    # eps sits outside the root: with eps = 4 the same step is 4 / (4 + 4) = 1/2
+    adam_eps = oracle.make_cfg(2, 2, 2, 1, opt=oracle.ADAM, lr=1.0, beta1=0.5, beta2=0.75, eps=4.0)
+    p, _, _, _ = oracle.opt_apply(adam_eps, [10.0, 10.0], [2.0, -2.0], [4.0, 4.0], 1, [4.0, -4.0])
+    assert p.tolist() == [9.5, 10.5]
+    # a zero gradient from zero moments does not move the weight (0 / (0 + eps))
+    p, m, v, t = oracle.opt_apply(oracle.make_cfg(2, 2, 2, 1, opt=oracle.ADAM), [3.0], [0.0], [0.0], 0, [0.0])
+    assert p.tolist() == [3.0] and m.tolist() == [0.0] and v.tolist() == [0.0] and t == 1
+
+
+def test_train_step_applies_the_update_rule_to_its_gradient():
+    D, H, A, B = 27, 64, 8, 32
+    p, S, Sn, a, r, term = _random_problem(D, H, A, B, 13)
+    g0 = np.random.default_rng(3)
+    m0, v0 = g0.standard_normal(p.size) * 1e-3, g0.random(p.size) * 1e-5
+    for opt in (oracle.SGD, oracle.ADAM):
+        cfg = oracle.make_cfg(D, H, A, B, opt=opt, lr=1e-3)
+        out = oracle.train_step(cfg, p, m0, v0, 4, S, Sn, a, r, term)
+        q, m, v, t = oracle.opt_apply(cfg, p, m0, v0, 4, out.grads)
+        assert np.array_equal(q, out.params)
+        if opt == oracle.ADAM:
+            assert t == out.t == 5 and np.array_equal(m, out.m) and np.array_equal(v, out.v)
+
+
 # ----------------------------------------------------------------------------- bf16
 def test_bf16_rounding_against_library_and_ties():
     x = np.random.default_rng(0).standard_normal(20000).astype(np.float32)
@@ -285,6 +320,36 @@ def test_bf16_mode_rounds_weights_but_not_master_copy():
     exact = oracle.train_step(_hand_cfg(oracle.MSE, bf16=0), p, None, None, 0, S_HAND, SN_HAND,
                               [0], [1.0], [0])
     assert not np.array_equal(exact.Q, ref.Q)
+
+
+def test_bf16_mode_rounds_the_pre_activation_gradients():
+    """Hand-worked backward pass whose pre-activation gradients are not bf16 numbers (bf16 keeps
+    8 significant bits, round to nearest even).  Network HAND, s = (1,3), s' = (2,0), action 0:
+      z1 = (7,1) h1 = (7,1); z2 = (11,-8) h2 = (11,0); Q = (5.75,-10.5); max Q' = 0.75
+      r = 5.5 + 3*2^-12: y = r + 0.5*0.75, delta = y - 5.75 = 2^-3 + 3*2^-12 =: e (|e| < 1)
+      dQ = (-e, 0);  gW3 = h2^T dQ = [[-11 e, 0], [0, 0]], gb3 = (-e, 0)      (not rounded)
+      dZ2 = (-e * 0.5, 0) = (-(2^-4)(1 + 3*2^-9), 0) -> bf16 -(2^-4)(1 + 2^-7) =: -p  (rounds up)
+      gW2 = h1^T dZ2 = [[-7 p, 0], [-p, 0]], gb2 = (-p, 0)
+      dZ1 = (-p * 1, -p * 5); 5 p = 2^-2 (1 + 2^-2 + 2^-7 + 2^-9) -> bf16 2^-2 (1 + 2^-2 + 2^-7) =: q
+      gW1 = s^T dZ1 = [[-p, -q], [-3 p, -3 q]], gb1 = (-p, -q)."""
+    e = 2.0 ** -3 + 3 * 2.0 ** -12
+    pp = 2.0 ** -4 * (1 + 2.0 ** -7)
+    qq = 2.0 ** -2 * (1 + 2.0 ** -2 + 2.0 ** -7)
+    r = 5.5 + 3 * 2.0 ** -12
+    for loss in (oracle.MSE, oracle.HUBER):
+        out = oracle.train_step(_hand_cfg(loss, bf16=1), HAND, None, None, 0, [[1.0, 3.0]], SN_HAND,
+                                [0], [r], [0])
+        assert out.Q.tolist() == [[5.75, -10.5]] and out.delta.tolist() == [e]
+        g = _flat([[-pp, -qq], [-3 * pp, -3 * qq]], [-pp, -qq], [[-7 * pp, 0], [-pp, 0]], [-pp, 0],
+                  [[-11 * e, 0], [0, 0]], [-e, 0])
+        assert out.grads.tolist() == g.tolist()
+        assert out.params.tolist() == (HAND - g).tolist()
+    # without mixed precision nothing is rounded: dZ2 = -e/2, dZ1 = (-e/2, -5e/2)
+    exact = oracle.train_step(_hand_cfg(oracle.MSE, bf16=0), HAND, None, None, 0, [[1.0, 3.0]],
+                              SN_HAND, [0], [r], [0])
+    g = _flat([[-e / 2, -5 * e / 2], [-3 * e / 2, -15 * e / 2]], [-e / 2, -5 * e / 2],
+              [[-7 * e / 2, 0], [-e / 2, 0]], [-e / 2, 0], [[-11 * e, 0], [0, 0]], [-e, 0])
+    assert exact.grads.tolist() == g.tolist()
 
 
 def test_bf16_mode_rounds_hidden_activations():
