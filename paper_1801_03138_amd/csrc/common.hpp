@@ -124,6 +124,9 @@ struct replay {
     int* stage_a;
     float* stage_r;
     unsigned char* stage_term;
+    // scratch for the slot numbers of a batch without duplicates (`capacity` words inside the
+    // storage; null for a replay that samples with replacement)
+    unsigned int* draw_scratch;
     // host mirror of the ring state
     uint64_t head, size, total;
     // Host-sourced appends: the caller's arrays are copied into one of kHostSlots pinned,

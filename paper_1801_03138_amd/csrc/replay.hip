@@ -42,7 +42,7 @@ size_t padded_row(size_t raw) {
 struct Layout {
     size_t state_bytes, meta_off, row_bytes;
     size_t off_stage_s, off_stage_s_next, off_stage_a, off_stage_r, off_stage_term;
-    size_t off_a, off_r, off_term, off_rows, total;
+    size_t off_a, off_r, off_term, off_draw, off_rows, total;
 };
 
 bool compute_layout(const replay_config* c, Layout* L) {
@@ -77,6 +77,9 @@ bool compute_layout(const replay_config* c, Layout* L) {
     L->off_a = take(side * 4);
     L->off_r = take(side * 4);
     L->off_term = take(side);
+    // slot numbers of a batch without duplicates, drawn by a kernel of its own ahead of the gather
+    // (a batch never holds more members than the replay has experiences)
+    L->off_draw = take(c->sampling == RP_DISTINCT ? (size_t)c->capacity * 4 : 0);
     L->off_rows = take((size_t)c->capacity * L->row_bytes);
     L->total = o;
     return true;
@@ -261,12 +264,19 @@ __device__ __forceinline__ float unit_from_u8(unsigned int b) {
 // ---------------------------------------------------------------------------------------
 // FRESH: `n_fresh` experiences from `fresh` are being appended at `head` by this same launch; a
 // drawn slot among them is composed from those arrays instead of read from the ring.
-template <int ELEM, int U, bool DISTINCT, bool FRESH>
+// MODE: where a row's slot number comes from.  kDrawUniform: every lane of the row draws it
+// (with replacement).  kDrawDistinct: without duplicates, drawn here by one lane per row.
+// kDrawGiven: read from `drawn`, which an earlier kernel filled (see distinct_draw_kernel).
+enum { kDrawUniform = 0, kDrawDistinct = 1, kDrawGiven = 2 };
+
+template <int ELEM, int U, int MODE, bool FRESH>
 __device__ __forceinline__ void gather_pair_block(const RingGeom& g, unsigned long long seed,
                                                   unsigned long long step, unsigned int size,
                                                   unsigned int batch, unsigned int lane_shift,
                                                   const GatherOut& o, const Payload& fresh,
-                                                  unsigned long long head, unsigned long long n_fresh) {
+                                                  unsigned long long head, unsigned long long n_fresh,
+                                                  const unsigned int* __restrict__ drawn = nullptr) {
+    constexpr bool DISTINCT = MODE == kDrawDistinct;
     extern __shared__ uint4 smem[];
     unsigned int* idx_s = reinterpret_cast<unsigned int*>(smem);   // distinct mode: R slot numbers
     unsigned char* rows_s = reinterpret_cast<unsigned char*>(smem) + (DISTINCT ? 4 * U * kThreads : 0);
@@ -295,7 +305,9 @@ __device__ __forceinline__ void gather_pair_block(const RingGeom& g, unsigned lo
         for (int u = 0; u < U; ++u) {
             unsigned int rr = rsub + u * rows_per_pass;
             rr = rr < nrows ? rr : 0u;   // a row past the end re-reads row 0; not stored
-            const unsigned int p = DISTINCT ? idx_s[rr] : uniform_draw(seed, step, i0 + rr, size);
+            const unsigned int p = MODE == kDrawGiven ? drawn[i0 + rr]
+                                   : DISTINCT         ? idx_s[rr]
+                                                      : uniform_draw(seed, step, i0 + rr, size);
             src[u] = g.rows + (unsigned long long)p * g.row_bytes;
             unsigned long long off = (unsigned long long)p + g.capacity - head;
             if (off >= g.capacity) off -= g.capacity;
@@ -359,23 +371,69 @@ __device__ __forceinline__ void gather_pair_block(const RingGeom& g, unsigned lo
     }
 }
 
-template <int ELEM, int U, bool DISTINCT>
+template <int ELEM, int U, int MODE>
 __global__ __launch_bounds__(kThreads) void sample_gather_pair_kernel(
     RingGeom g, unsigned long long seed, unsigned long long step_value,
     const unsigned long long* __restrict__ step_ptr, unsigned int size_value, unsigned int batch,
-    unsigned int lane_shift, GatherOut out) {
+    unsigned int lane_shift, GatherOut out, const unsigned int* __restrict__ drawn) {
     // callers that mirror the ring state pass the size by value: no dependent load up front
+    unsigned long long step = 0;
+    unsigned int size = 0;
+    if (MODE != kDrawGiven) {
+        step = step_ptr ? *step_ptr : step_value;
+        size = size_value ? size_value : (unsigned int)g.state->size;
+    }
+    gather_pair_block<ELEM, U, MODE, false>(g, seed, step, size, batch, lane_shift, out,
+                                            Payload{nullptr, nullptr, nullptr, nullptr, nullptr}, 0, 0, drawn);
+}
+
+// ---------------------------------------------------------------------------------------
+// Slot numbers of a batch without duplicates, drawn ahead of the gather into `out` (device
+// scratch).  A draw is some sixty dependent Philox blocks, all arithmetic: it wants every lane of
+// the chip busy with a draw of its own (G = 0: one draw per lane, 64 per single-wavefront
+// workgroup, so that 65,536 draws put one wavefront on each of the chip's 1,024 SIMDs), or, for
+// batches too small to fill the chip that way, 2^G lanes per draw that take G rounds at a time
+// (distinct_draw_team).  CHAIN rings: the draw counts from the oldest experience and skips the
+// newest (it has no successor yet); `out` receives physical slot numbers either way.
+// ---------------------------------------------------------------------------------------
+template <int G>
+__global__ __launch_bounds__(64) void distinct_draw_kernel(
+    RingGeom g, unsigned long long seed, unsigned long long step_value,
+    const unsigned long long* __restrict__ step_ptr, unsigned int size_value,
+    unsigned long long head_value, unsigned int batch, unsigned int* __restrict__ out) {
+    __shared__ unsigned int keys[kMaxDistinctRounds];
+    const unsigned int lane = threadIdx.x;
     const unsigned long long step = step_ptr ? *step_ptr : step_value;
-    const unsigned int size = size_value ? size_value : (unsigned int)g.state->size;
-    gather_pair_block<ELEM, U, DISTINCT, false>(g, seed, step, size, batch, lane_shift, out,
-                                                Payload{nullptr, nullptr, nullptr, nullptr, nullptr}, 0, 0);
+    const unsigned long long size = size_value ? size_value : g.state->size;
+    const unsigned long long head = size_value ? head_value : g.state->head;
+    const bool chain = g.layout == RP_CHAIN;
+    const unsigned int choices = (unsigned int)(chain ? size - 1 : size);
+    const unsigned int rounds = distinct_rounds(choices);
+    distinct_round_keys(seed, step, choices, rounds, lane, keys);
+    __syncthreads();
+    constexpr unsigned int per_block = 64u >> G;
+    const unsigned int i = blockIdx.x * per_block + (lane >> G);
+    const unsigned int ic = i < batch ? i : batch - 1u;
+    unsigned int u;
+    if constexpr (G == 0) u = distinct_draw_serial(seed, step, ic, choices, rounds, keys);
+    else u = distinct_draw_team<G>(seed, step, ic, choices, rounds, keys, lane);
+    if (i < batch && (lane & ((1u << G) - 1u)) == 0) {
+        unsigned long long p = u;
+        if (chain) {
+            unsigned long long oldest = head + g.capacity - size;
+            if (oldest >= g.capacity) oldest -= g.capacity;
+            p += oldest;
+            if (p >= g.capacity) p -= g.capacity;
+        }
+        out[i] = (unsigned int)p;
+    }
 }
 
 // Append, then sample and gather, in one launch (the train step of wide networks).  The ring
 // state before the append comes by value.  The workgroups share the new rows out among
 // themselves and send them to the ring first; nobody reads those slots from the ring in this
 // launch (see FRESH above), so the order of the two halves within the launch does not matter.
-template <int ELEM, bool DISTINCT>
+template <int ELEM, int MODE>
 __global__ __launch_bounds__(kThreads) void append_sample_gather_pair_kernel(AppendGatherArgs p) {
     const RingGeom& g = p.g;
     store_state_after(g, p.pos, p.n);
@@ -389,8 +447,8 @@ __global__ __launch_bounds__(kThreads) void append_sample_gather_pair_kernel(App
     }
     const unsigned long long sz = p.pos.size + p.n;
     const unsigned int size = (unsigned int)(sz > g.capacity ? g.capacity : sz);
-    gather_pair_block<ELEM, 1, DISTINCT, true>(g, p.seed, *p.step_ptr, size, p.batch, p.lane_shift,
-                                               p.out, p.src, p.pos.head, p.n);
+    gather_pair_block<ELEM, 1, MODE, true>(g, p.seed, *p.step_ptr, size, p.batch, p.lane_shift,
+                                           p.out, p.src, p.pos.head, p.n);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -408,20 +466,25 @@ __global__ __launch_bounds__(kThreads) void sample_gather_chain_kernel(
     unsigned long long head_value, unsigned int batch, unsigned int chunks,
     void* __restrict__ out_s, void* __restrict__ out_s_next, unsigned int out_ld,
     int* __restrict__ out_a, float* __restrict__ out_r, unsigned char* __restrict__ out_term,
-    unsigned int* __restrict__ out_idx) {
+    unsigned int* __restrict__ out_idx, const unsigned int* __restrict__ drawn) {
     const unsigned int chunk = blockIdx.x % chunks;
     const unsigned int t = blockIdx.x / chunks;
     const unsigned int which = t & 1u;
     const unsigned int i = t >> 1;
     if (i >= batch) return;
 
-    const unsigned long long step = step_ptr ? *step_ptr : step_value;
-    const unsigned long long size = size_value ? size_value : g.state->size;
-    const unsigned long long head = size_value ? head_value : g.state->head;
-    unsigned long long oldest = head + g.capacity - size;
-    if (oldest >= g.capacity) oldest -= g.capacity;
-    unsigned long long p = oldest + batch_draw(g.sampling, seed, step, i, (unsigned int)(size - 1));
-    if (p >= g.capacity) p -= g.capacity;
+    unsigned long long p;
+    if (drawn) {
+        p = drawn[i];   // physical slot numbers, drawn by an earlier kernel
+    } else {
+        const unsigned long long step = step_ptr ? *step_ptr : step_value;
+        const unsigned long long size = size_value ? size_value : g.state->size;
+        const unsigned long long head = size_value ? head_value : g.state->head;
+        unsigned long long oldest = head + g.capacity - size;
+        if (oldest >= g.capacity) oldest -= g.capacity;
+        p = oldest + batch_draw(g.sampling, seed, step, i, (unsigned int)(size - 1));
+        if (p >= g.capacity) p -= g.capacity;
+    }
     unsigned long long q = p;
     if (which) q = (p + 1 == g.capacity) ? 0 : p + 1;
 
@@ -544,10 +607,10 @@ void* append_gather_func(const RingGeom& g) {
     if (g.layout != RP_PAIR || g.elem_bytes == 1) return nullptr;
     const bool distinct = g.sampling == RP_DISTINCT;
     if (g.elem_bytes == 4)
-        return distinct ? reinterpret_cast<void*>(append_sample_gather_pair_kernel<4, true>)
-                        : reinterpret_cast<void*>(append_sample_gather_pair_kernel<4, false>);
-    return distinct ? reinterpret_cast<void*>(append_sample_gather_pair_kernel<2, true>)
-                    : reinterpret_cast<void*>(append_sample_gather_pair_kernel<2, false>);
+        return distinct ? reinterpret_cast<void*>(append_sample_gather_pair_kernel<4, kDrawDistinct>)
+                        : reinterpret_cast<void*>(append_sample_gather_pair_kernel<4, kDrawUniform>);
+    return distinct ? reinterpret_cast<void*>(append_sample_gather_pair_kernel<2, kDrawDistinct>)
+                    : reinterpret_cast<void*>(append_sample_gather_pair_kernel<2, kDrawUniform>);
 }
 
 void append_gather_shape(const AppendGatherArgs& a, unsigned int* blocks, size_t* lds) {
@@ -598,14 +661,49 @@ hipError_t launch_append(const RingGeom& g, const RingPos& pos, unsigned long lo
     return hipGetLastError();
 }
 
+// Lanes per draw of the kernel that draws a batch without duplicates: a whole wavefront per
+// draw while that leaves SIMDs idle (1,024 on the chip), sixteen lanes up to four times that, one
+// lane beyond (measured cross-over points are of that order; the arithmetic of a draw is the same
+// in every shape, only its latency differs).
+static int draw_team_log2(unsigned int batch) { return batch <= 1024u ? 6 : batch <= 8192u ? 4 : 0; }
+
+hipError_t launch_distinct_draw(const RingGeom& g, unsigned long long seed, unsigned long long step_value,
+                                const unsigned long long* step_ptr, unsigned int batch,
+                                unsigned int size_value, unsigned long long head_value,
+                                unsigned int* out, hipStream_t stream) {
+    const int G = draw_team_log2(batch);
+    const unsigned int per_block = 64u >> G;
+    const unsigned int blocks = (batch + per_block - 1) / per_block;
+#define RP_LAUNCH_DRAW(GG)                                                                        \
+    hipLaunchKernelGGL((distinct_draw_kernel<GG>), dim3(blocks), dim3(64), 0, stream, g, seed,   \
+                       step_value, step_ptr, size_value, head_value, batch, out)
+    if (G == 6) RP_LAUNCH_DRAW(6);
+    else if (G == 4) RP_LAUNCH_DRAW(4);
+    else RP_LAUNCH_DRAW(0);
+#undef RP_LAUNCH_DRAW
+    return hipGetLastError();
+}
+
 hipError_t launch_sample_gather(const RingGeom& g, unsigned long long seed,
                                 unsigned long long step_value,
                                 const unsigned long long* step_ptr, unsigned int batch,
                                 void* out_s, void* out_s_next, unsigned int out_ld, int* out_a,
                                 float* out_r, unsigned char* out_term, unsigned int* out_idx,
                                 hipStream_t stream, void* out_s_t, unsigned int out_t_ld,
-                                unsigned int size_value, unsigned long long head_value) {
+                                unsigned int size_value, unsigned long long head_value,
+                                unsigned int* draw_scratch, unsigned int* launched) {
+    if (launched) *launched = 0;
     if (out_s_t && (g.layout != RP_PAIR || g.elem_bytes == 1)) return hipErrorInvalidValue;
+    // a batch without duplicates is drawn by a kernel of its own when the caller has scratch for it
+    const bool distinct = g.sampling == RP_DISTINCT;
+    const unsigned int* drawn = nullptr;
+    if (distinct && draw_scratch) {
+        hipError_t e = launch_distinct_draw(g, seed, step_value, step_ptr, batch, size_value, head_value,
+                                            draw_scratch, stream);
+        if (e != hipSuccess) return e;
+        drawn = draw_scratch;
+        if (launched) *launched += 1;
+    }
     if (g.layout == RP_PAIR) {
         const unsigned int lane_shift = pair_lane_shift(g);
         const unsigned int rows_per_pass = kThreads >> lane_shift;
@@ -614,14 +712,18 @@ hipError_t launch_sample_gather(const RingGeom& g, unsigned long long seed,
         const unsigned int U = 1;
         const unsigned int R = U * rows_per_pass;
         const unsigned int blocks = (batch + R - 1) / R;
-        const bool distinct = g.sampling == RP_DISTINCT;
-        const size_t lds = (distinct ? 4 * (size_t)U * kThreads : 0) + (size_t)R * g.row_bytes;
+        const int mode = drawn ? kDrawGiven : distinct ? kDrawDistinct : kDrawUniform;
+        const size_t lds = (mode == kDrawDistinct ? 4 * (size_t)U * kThreads : 0) + (size_t)R * g.row_bytes;
         const GatherOut out{out_s, out_s_next, out_ld, out_a, out_r, out_term, out_idx, out_s_t, out_t_ld};
-#define RP_LAUNCH_PAIR(E, UU, DD)                                                                  \
-    hipLaunchKernelGGL((sample_gather_pair_kernel<E, UU, DD>), dim3(blocks), dim3(kThreads), lds,   \
-                       stream, g, seed, step_value, step_ptr, size_value, batch, lane_shift, out)
-#define RP_LAUNCH_PAIR_E(E) \
-    do { if (distinct) RP_LAUNCH_PAIR(E, 1, true); else RP_LAUNCH_PAIR(E, 1, false); } while (0)
+#define RP_LAUNCH_PAIR(E, UU, MM)                                                                  \
+    hipLaunchKernelGGL((sample_gather_pair_kernel<E, UU, MM>), dim3(blocks), dim3(kThreads), lds,   \
+                       stream, g, seed, step_value, step_ptr, size_value, batch, lane_shift, out, drawn)
+#define RP_LAUNCH_PAIR_E(E)                                                \
+    do {                                                                   \
+        if (mode == kDrawGiven) RP_LAUNCH_PAIR(E, 1, kDrawGiven);          \
+        else if (mode == kDrawDistinct) RP_LAUNCH_PAIR(E, 1, kDrawDistinct); \
+        else RP_LAUNCH_PAIR(E, 1, kDrawUniform);                           \
+    } while (0)
         if (g.elem_bytes == 4)
             RP_LAUNCH_PAIR_E(4);
         else if (g.elem_bytes == 2)
@@ -643,7 +745,7 @@ hipError_t launch_sample_gather(const RingGeom& g, unsigned long long seed,
     hipLaunchKernelGGL((sample_gather_chain_kernel<E, MODE>), dim3(blocks), dim3(kThreads), 0,    \
                        stream, g, seed, step_value, step_ptr, size_value, head_value, batch,      \
                        chunks, out_s, out_s_next,                                                 \
-                       out_ld, out_a, out_r, out_term, out_idx)
+                       out_ld, out_a, out_r, out_term, out_idx, drawn)
         if (g.elem_bytes == 4) {
             if (vec) RP_LAUNCH_CHAIN(4, 1); else RP_LAUNCH_CHAIN(4, 2);
         } else if (g.elem_bytes == 2) {
@@ -653,6 +755,7 @@ hipError_t launch_sample_gather(const RingGeom& g, unsigned long long seed,
         }
 #undef RP_LAUNCH_CHAIN
     }
+    if (launched) *launched += 1;
     return hipGetLastError();
 }
 
@@ -706,6 +809,8 @@ rp_status replay_create(const replay_config* cfg, void* dev_storage, size_t byte
     rp_->stage_a = reinterpret_cast<int*>(base + L.off_stage_a);
     rp_->stage_r = reinterpret_cast<float*>(base + L.off_stage_r);
     rp_->stage_term = base + L.off_stage_term;
+    rp_->draw_scratch = cfg->sampling == RP_DISTINCT ? reinterpret_cast<unsigned int*>(base + L.off_draw)
+                                                     : nullptr;
     rp::RingGeom& g = rp_->geom;
     g.capacity = cfg->capacity;
     g.state_dim = cfg->state_dim;
@@ -815,12 +920,13 @@ rp_status replay_append(replay_t* rp_, uint64_t n, const void* s, const void* s_
     return RP_OK;
 }
 
-rp_status replay_sample_gather(replay_t* rp_, uint64_t step, uint32_t batch, void* out_s,
-                               void* out_s_next, int32_t* out_a, float* out_r, uint8_t* out_term,
-                               uint32_t* out_idx, void* hip_stream) {
-    RP_REQUIRE(rp_, "replay_sample_gather: null handle");
-    RP_REQUIRE(batch >= 1 && batch <= (1u << 24), "replay_sample_gather: batch %u not in 1..2^24",
-               batch);
+// replay_sample_gather with the given scratch for the slot numbers of a batch without duplicates
+static rp_status sample_gather_with(replay_t* rp_, uint64_t step, uint32_t batch, void* out_s,
+                                    void* out_s_next, int32_t* out_a, float* out_r, uint8_t* out_term,
+                                    uint32_t* out_idx, void* hip_stream, unsigned int* draw_scratch,
+                                    const char* who) {
+    RP_REQUIRE(rp_, "%s: null handle", who);
+    RP_REQUIRE(batch >= 1 && batch <= (1u << 24), "%s: batch %u not in 1..2^24", who, batch);
     if (rp_->total < rp_->cfg.burn_in) return RP_SKIPPED_BURN_IN;
     // experiences that can be drawn; a batch without duplicates needs at least `batch` of them
     const uint64_t choices = rp_->cfg.layout == RP_CHAIN ? (rp_->size ? rp_->size - 1 : 0) : rp_->size;
@@ -828,8 +934,15 @@ rp_status replay_sample_gather(replay_t* rp_, uint64_t step, uint32_t batch, voi
     RP_CHECK_HIP(rp::launch_sample_gather(rp_->geom, rp_->cfg.seed, step, nullptr, batch, out_s,
                                           out_s_next, rp_->cfg.state_dim, out_a, out_r, out_term,
                                           out_idx, static_cast<hipStream_t>(hip_stream), nullptr, 0,
-                                          (unsigned int)rp_->size, rp_->head));
+                                          (unsigned int)rp_->size, rp_->head, draw_scratch));
     return RP_OK;
+}
+
+rp_status replay_sample_gather(replay_t* rp_, uint64_t step, uint32_t batch, void* out_s,
+                               void* out_s_next, int32_t* out_a, float* out_r, uint8_t* out_term,
+                               uint32_t* out_idx, void* hip_stream) {
+    return sample_gather_with(rp_, step, batch, out_s, out_s_next, out_a, out_r, out_term, out_idx,
+                              hip_stream, rp_ ? rp_->draw_scratch : nullptr, "replay_sample_gather");
 }
 
 rp_status replay_get_state(replay_t* rp_, uint64_t* head, uint64_t* size, uint64_t* total) {

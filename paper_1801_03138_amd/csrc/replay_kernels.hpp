@@ -34,6 +34,10 @@ void append_gather_shape(const AppendGatherArgs& a, unsigned int* blocks, size_t
 // transposed: element (column, i) at out_s_t[column * out_t_ld + i].
 // size_value, head_value: the number of experiences held and the write position, when the
 // caller mirrors them; size_value = 0 = read both from the device-resident ring state.
+// draw_scratch (device, `batch` words; may be null): with it, a batch without duplicates is drawn
+// by a kernel of its own into that buffer and the gather reads the slot numbers from there;
+// without it the gather kernel draws them itself.  *launched (may be null) receives the number
+// of kernels enqueued.
 hipError_t launch_sample_gather(const RingGeom& g, unsigned long long seed,
                                 unsigned long long step_value,
                                 const unsigned long long* step_ptr, unsigned int batch,
@@ -41,6 +45,7 @@ hipError_t launch_sample_gather(const RingGeom& g, unsigned long long seed,
                                 float* out_r, unsigned char* out_term, unsigned int* out_idx,
                                 hipStream_t stream, void* out_s_t = nullptr,
                                 unsigned int out_t_ld = 0, unsigned int size_value = 0,
-                                unsigned long long head_value = 0);
+                                unsigned long long head_value = 0, unsigned int* draw_scratch = nullptr,
+                                unsigned int* launched = nullptr);
 
 }  // namespace rp

@@ -490,12 +490,14 @@ hipError_t enqueue_step(trainer* t, hipStream_t st, unsigned int* count, bool sa
 
     // sample B slots with the device-resident step counter and unpack into X = [S ; S']
     hipError_t e = hipSuccess;
+    unsigned int launched = 0;
     if (sample) {
         e = launch_sample_gather(t->rp_->geom, t->rp_->cfg.seed, 0, &t->ctr->step, t->B, t->X,
                                  static_cast<unsigned char*>(t->X) + (size_t)B * Dp * eb, t->Dp,
-                                 t->act, t->rew, t->term, t->idx, st);
+                                 t->act, t->rew, t->term, t->idx, st, nullptr, 0, 0, 0,
+                                 t->rp_->draw_scratch, &launched);
         if (e != hipSuccess) return e;
-        ++n;
+        n += launched;
     }
     // forward on the 2B rows of X; with a frozen target network the rows of S' (B .. 2B-1) go
     // through its weights in launches of their own
@@ -958,8 +960,12 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
         }
     } else {
         // the launch count is static
+        // (a batch without duplicates is drawn by a kernel of its own wherever the step samples
+        // through the replay's stand-alone gather)
+        const bool own_draw = rp_->cfg.sampling == RP_DISTINCT && !t->fused &&
+                              !(t->wide && cfg->appends_per_step);
         t->kernels_per_step =
-            (t->dueling ? 1u : 0u) +
+            (t->dueling ? 1u : 0u) + (own_draw ? 1u : 0u) +
             (t->fused ? (t->wt ? 3u : 2u)
                       : (cfg->appends_per_step ? 1u : 0u) +
                             (t->wide ? (t->wt && cfg->batch % 128 ? 13u : 10u) : (t->wt ? 17u : 14u)));

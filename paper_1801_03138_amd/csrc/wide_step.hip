@@ -924,11 +924,13 @@ hipError_t enqueue_wide_step(trainer* t, hipStream_t st, unsigned int* count, bo
 
     // sample B slots and unpack into X = [S ; S'] and the transposed copy of S
     hipError_t e = hipSuccess;
+    unsigned int launched = 0;
     if (sample) {
         e = launch_sample_gather(t->rp_->geom, t->rp_->cfg.seed, 0, &t->ctr->step, B, X,
-                                 X + (size_t)B * Dp, Dp, t->act, t->rew, t->term, t->idx, st, w.XT, Bp);
+                                 X + (size_t)B * Dp, Dp, t->act, t->rew, t->term, t->idx, st, w.XT, Bp,
+                                 0, 0, t->rp_->draw_scratch, &launched);
         if (e != hipSuccess) return e;
-        ++n;
+        n += launched;
     }
     // forward on the 2B rows
     e = launch_gemm<128, 128, 32, 2, 2>(st, X, Dp, w.W1T, Dp, rows, H, Dp,

@@ -286,6 +286,25 @@ def test_sampling_without_duplicates_matches_oracle(B, dtype, D, chain):
             step += 1
 
 
+@pytest.mark.parametrize("chain", [False, True])
+def test_sampling_without_duplicates_every_draw_shape(B, chain):
+    """The kernel that draws a batch without duplicates gives a draw to a whole wavefront, to
+    sixteen lanes or to one lane depending on the batch: batches on both sides of each limit
+    (1,024 and 8,192), every slot number against the oracle, on a ring that has wrapped."""
+    C, D = 20_000, 9
+    gpu = B.Replay(C, D, DT["f32"][1], B.RP_CHAIN if chain else B.RP_PAIR, seed=21, max_append=4096,
+                   distinct=True)
+    ref = oracle.Ring(C, D, DT["f32"][0], oracle.CHAIN if chain else oracle.PAIR)
+    rows = _rows(4000, D, 30, 0.05, 5, "f32")
+    for k in range(7):                       # 28,000 experiences into 20,000 slots
+        _append_both(gpu, ref, rows, True, chain=chain)
+    for step, batch in enumerate([1024, 1025, 4096, 8192, 8193, 19_999]):
+        idx = ref.sample(21, step, batch, distinct=True)
+        st, out = gpu.sample_gather(step, batch)
+        assert st == 0 and len(set(idx.tolist())) == batch
+        _assert_batch_equal(out, ref, idx)
+
+
 def test_sampling_without_duplicates_at_paper_size(B):
     """1,000,000 experiences, batch 65,536: the launch shape the bench times; every slot number
     against the oracle on a sample of positions, all of them distinct."""
