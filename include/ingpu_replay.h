@@ -153,6 +153,24 @@ rp_status replay_sample_gather(replay_t* rp, uint64_t step, uint32_t batch, void
                                void* out_s_next, int32_t* out_a, float* out_r, uint8_t* out_term,
                                uint32_t* out_idx, void* hip_stream);
 
+/*
+ * replay_sample_gather for callers that cannot allocate device memory or accept a library that
+ * does: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, same results.  The one scratch buffer the call needs (the slot numbers of a
+ * batch without duplicates, handed from the kernel that draws them to the kernel that gathers)
+ * is a fixed 256 KB array inside the library's own image instead of part of dev_storage, so the
+ * call allocates nothing and calls no allocating routine.  Limits and rules:
+ *  - RP_DISTINCT replays: batch <= 65,536 (the array's size), else RP_EINVAL; RP_WITH_REPLACEMENT
+ *    replays need no scratch and have no extra limit.
+ *  - every GPU the library runs on holds its own copy of the array until the process ends;
+ *    all calls on one GPU share it.  Nothing in it has to be cleared between calls (a call
+ *    writes every word it later reads), but two calls that overlap in time on the same GPU, from
+ *    different streams or handles, race on it: serialise them (one stream, or events).
+ */
+rp_status replay_sample_gather_static(replay_t* rp, uint64_t step, uint32_t batch, void* out_s,
+                                      void* out_s_next, int32_t* out_a, float* out_r,
+                                      uint8_t* out_term, uint32_t* out_idx, void* hip_stream);
+
 /* Write position, number of experiences held, and experiences ever added, as
  * read back from the device.  RP_ESTATE if they differ from the host mirror.
  * Synchronises the device. */

@@ -58,6 +58,7 @@ SYMBOLS = {
     "replay_destroy": (_int, [_vp]),
     "replay_append": (_int, [_vp, _u64, _vp, _vp, _vp, _vp, _vp, _int, _vp]),
     "replay_sample_gather": (_int, [_vp, _u64, _u32, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "replay_sample_gather_static": (_int, [_vp, _u64, _u32, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "replay_get_state": (_int, [_vp, _vp, _vp, _vp]),
     "replay_read_rows": (_int, [_vp, _u64, _u64, _vp, _vp, _vp, _vp, _vp]),
     "train_param_count": (C.c_size_t, [_vp]),
@@ -265,6 +266,14 @@ class Replay:
         check_batch_out(self.cfg, self.device, batch, out, "sample_gather")
         st = _check(lib().replay_sample_gather(self._h, step, batch, *[_dev(t) for t in out],
                                                _stream_ptr(stream)))
+        return st, out
+
+    def sample_gather_static(self, step, batch, out, stream=None):
+        """sample_gather through the entry point that allocates nothing (its scratch is a fixed
+        array inside the library); `out` must be given, e.g. from alloc_batch."""
+        check_batch_out(self.cfg, self.device, batch, out, "sample_gather_static")
+        st = _check(lib().replay_sample_gather_static(self._h, step, batch, *[_dev(t) for t in out],
+                                                      _stream_ptr(stream)))
         return st, out
 
     def state(self):

@@ -115,6 +115,7 @@ struct AppendGatherArgs : AppendArgs {
 
 struct replay {
     replay_config cfg;
+    int device;                 // the GPU the replay was created on
     rp::RingGeom geom;
     unsigned char* storage;
     size_t storage_bytes;

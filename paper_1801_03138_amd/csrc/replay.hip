@@ -3,11 +3,20 @@
 //
 // Paper: Methods (packed rows of 2D+3 values, add / sample API, FIFO, uniform
 // integer sampling with replacement) and Discussion (one state per experience).
+#include <mutex>
 #include <vector>
 
 #include "common.hpp"
 #include "philox.hpp"
 #include "replay_kernels.hpp"
+
+// Scratch of replay_sample_gather_static, the entry point for callers that cannot allocate:
+// the slot numbers of one batch without duplicates, between the kernel that draws them and the
+// kernel that gathers.  It is part of the library's image, so every GPU the library runs on holds
+// its own copy (256 KB) at its own address until the process ends.  In host code the name below
+// is only a handle for hipGetSymbolAddress; kernels get the looked-up device address.
+constexpr unsigned int kStaticDrawWords = 65536;
+static __device__ __align__(256) unsigned int scratch[kStaticDrawWords];
 
 namespace rp {
 
@@ -562,6 +571,28 @@ __global__ __launch_bounds__(kThreads) void sample_gather_chain_kernel(
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Device address of `scratch` on GPU `device`, looked up once per GPU with that GPU current.
+constexpr int kMaxDevices = 64;
+unsigned int* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+hipError_t static_scratch_address(int device, unsigned int** out) {
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        int current = -1;
+        hipError_t e = hipGetDevice(&current);
+        if (e != hipSuccess) return e;
+        if (current != device) return hipErrorInvalidDevice;   // looked up with its own GPU current only
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        g_scratch_ptr[device] = static_cast<unsigned int*>(p);
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
+
 }  // namespace
 
 AppendArgs make_append_args(const RingGeom& g, const RingPos& pos, unsigned long long n,
@@ -795,6 +826,13 @@ rp_status replay_create(const replay_config* cfg, void* dev_storage, size_t byte
     }
     RP_CHECK_HIP(hipMemset(dev_storage, 0, L.total));
     RP_CHECK_HIP(hipDeviceSynchronize());
+    int device = -1;
+    RP_CHECK_HIP(hipGetDevice(&device));
+    {
+        // set-up for replay_sample_gather_static: this GPU's address of the static scratch
+        unsigned int* unused = nullptr;
+        RP_CHECK_HIP(rp::static_scratch_address(device, &unused));
+    }
     replay* rp_ = new (std::nothrow) replay();
     if (!rp_) {
         rp::set_error("replay_create: out of host memory");
@@ -802,6 +840,7 @@ rp_status replay_create(const replay_config* cfg, void* dev_storage, size_t byte
     }
     unsigned char* base = static_cast<unsigned char*>(dev_storage);
     rp_->cfg = *cfg;
+    rp_->device = device;
     rp_->storage = base;
     rp_->storage_bytes = L.total;
     rp_->stage_s = base + L.off_stage_s;
@@ -943,6 +982,21 @@ rp_status replay_sample_gather(replay_t* rp_, uint64_t step, uint32_t batch, voi
                                uint32_t* out_idx, void* hip_stream) {
     return sample_gather_with(rp_, step, batch, out_s, out_s_next, out_a, out_r, out_term, out_idx,
                               hip_stream, rp_ ? rp_->draw_scratch : nullptr, "replay_sample_gather");
+}
+
+rp_status replay_sample_gather_static(replay_t* rp_, uint64_t step, uint32_t batch, void* out_s,
+                                      void* out_s_next, int32_t* out_a, float* out_r,
+                                      uint8_t* out_term, uint32_t* out_idx, void* hip_stream) {
+    RP_REQUIRE(rp_, "replay_sample_gather_static: null handle");
+    unsigned int* ptr = nullptr;
+    if (rp_->cfg.sampling == RP_DISTINCT) {
+        RP_REQUIRE(batch <= kStaticDrawWords,
+                   "replay_sample_gather_static: batch %u exceeds the %u slot numbers the static "
+                   "scratch holds (use replay_sample_gather)", batch, kStaticDrawWords);
+        RP_CHECK_HIP(rp::static_scratch_address(rp_->device, &ptr));
+    }
+    return sample_gather_with(rp_, step, batch, out_s, out_s_next, out_a, out_r, out_term, out_idx,
+                              hip_stream, ptr, "replay_sample_gather_static");
 }
 
 rp_status replay_get_state(replay_t* rp_, uint64_t* head, uint64_t* size, uint64_t* total) {
