@@ -37,6 +37,9 @@ GATHER_BATCHES = [32, 128, 512, 2048, 8192, 65536]
 # same counters read for the 256 MiB plain copy of the copy_calibration leg); the runs and the
 # table are in profiles/gather_kernels_hbm_traffic_pmc.txt.  Set to None when that kernel changes.
 GATHER_65536_HBM_BYTES = (8182.8 * 2.000 + 14720.0 * 1.000) * 1024
+GATHER_KERNEL = "sample_gather_pair_kernel<4, 1, 0>"
+# the same for sample_gather_chain_kernel<1, 0> at batch 256 (None: not taken for this kernel build)
+LARGE_256_HBM_BYTES = None
 
 
 def log(*a):
@@ -99,16 +102,21 @@ def prefill(ring, rows, n_total):
 
 # ----------------------------------------------------------------------------- legs
 def leg_paper_shaped(B, synth, steps, warmup, full_ring, host_payload=False, target_sync=0,
-                     dueling=False, distinct=False):
+                     dueling=False, distinct=False, widths=None):
+    """widths = (H, G): the two hidden widths instead of the workload's 256, 256."""
     import torch
-    c = P_CFG
+    c = dict(P_CFG)
+    H2 = 0
+    if widths:
+        c["H"], H2 = widths
     ring = B.Replay(c["capacity"], c["D"], burn_in=c["burn_in"], seed=0, max_append=4096,
                     distinct=distinct)
     base = synth.experiences(100_000, c["D"], c["A"], c["p_term"], seed=0)
     prefill(ring, base, c["capacity"] if full_ring else c["burn_in"])
     tr = B.Trainer(ring, c["H"], c["A"], c["B"], opt=B.RP_ADAM, loss=B.RP_HUBER, lr=c["lr"],
-                   appends_per_step=c["appends"], target_sync=target_sync, dueling=dueling,
-                   init_params=synth.init_params(c["D"], c["H"], c["A"] + (1 if dueling else 0), 0))
+                   appends_per_step=c["appends"], target_sync=target_sync, dueling=dueling, hidden2=H2,
+                   init_params=synth.init_params(c["D"], c["H"], c["A"] + (1 if dueling else 0), 0,
+                                                 hidden2=H2 or None))
     stream_rows = synth.experiences(steps + warmup, c["D"], c["A"], c["p_term"], seed=1)
     src = stream_rows if host_payload else dev_rows(stream_rows)
     w = {k: v[:warmup] for k, v in src.items()}
@@ -127,14 +135,18 @@ def leg_paper_shaped(B, synth, steps, warmup, full_ring, host_payload=False, tar
             "ring_rows": ring.state()[1]}
 
 
-def leg_gather_sweep(B, synth, reps, distinct=False):
-    """replay_sample_gather alone on the full 1M-row ring; distinct = batches without duplicates."""
+def leg_gather_sweep(B, synth, reps, distinct=False, capacity=None, batches=None):
+    """replay_sample_gather alone on a full ring (1M rows unless given); distinct = batches
+    without duplicates.  Timed as a recorded graph of 100 calls with steps 0..99 (each launch
+    draws other rows; one replay of the graph touches 100 x batch rows, 1.7 GB at batch 65,536,
+    far more than the last-level cache holds, so rows do not survive from one use to the next)."""
     import torch
     c = P_CFG
-    ring = B.Replay(c["capacity"], c["D"], seed=0, max_append=4096, distinct=distinct)
-    prefill(ring, synth.experiences(100_000, c["D"], c["A"], c["p_term"], seed=0), c["capacity"])
+    capacity = capacity or c["capacity"]
+    ring = B.Replay(capacity, c["D"], seed=0, max_append=4096, distinct=distinct)
+    prefill(ring, synth.experiences(100_000, c["D"], c["A"], c["p_term"], seed=0), capacity)
     out = []
-    for batch in ([128, 65536] if distinct else GATHER_BATCHES):
+    for batch in (batches or ([128, 2048, 8192, 65536] if distinct else GATHER_BATCHES)):
         bufs = ring.alloc_batch(batch)
         for k in range(10):
             ring.sample_gather(k, batch, out=bufs)
@@ -143,6 +155,7 @@ def leg_gather_sweep(B, synth, reps, distinct=False):
         alg = batch * 2 * (2 * c["D"] + 3) * 4      # 228 B read + 228 B written per sampled row
         out.append({"batch": batch, "us_per_call": 1e3 * ms, "us_per_call_host_launched": 1e3 * ms_host,
                     "alg_bytes": alg, "GBps": alg / (ms * 1e-3) / 1e9})
+    ring.close()
     return out
 
 
@@ -354,12 +367,73 @@ def leg_cpu_oracle(synth, seconds_budget):
     return res
 
 
+def leg_cpu_oracle_extras(synth, threads):
+    """The oracle on the other workloads: the gather sweep's six batch sizes on a full 1M-row
+    ring, the Tiny workload's 100 train steps, and two steps of the wide workload."""
+    import oracle
+    oracle.set_threads(threads)
+    res = {"threads": oracle.get_threads()}
+    # gather sweep
+    c = P_CFG
+    rows = synth.experiences(100_000, c["D"], c["A"], c["p_term"], seed=0)
+    ring = oracle.Ring(c["capacity"], c["D"])
+    for _ in range(c["capacity"] // 100_000):
+        ring.append(rows["s"], rows["s_next"], rows["a"], rows["r"], rows["term"])
+    g = []
+    for batch in GATHER_BATCHES:
+        reps, t0 = 0, time.perf_counter()
+        while reps < 1000 and (reps < 3 or time.perf_counter() - t0 < 0.7):
+            ring.gather(ring.sample(0, reps, batch))
+            reps += 1
+        dt = (time.perf_counter() - t0) / reps
+        alg = batch * 2 * (2 * c["D"] + 3) * 4
+        g.append({"batch": batch, "reps": reps, "us_per_call": 1e6 * dt, "GBps": alg / dt / 1e9})
+    res["gather_sweep"] = g
+    del ring
+    # Tiny: capacity 1024, 27-64-64-8, batch 32, SGD 1e-3, burn-in 256, one append per step, 100 steps
+    rows = synth.experiences(400, 27, 8, 0.01, seed=0)
+    ring = oracle.Ring(1024, 27, burn_in=256)
+    ring.append(rows["s"][:255], rows["s_next"][:255], rows["a"][:255], rows["r"][:255], rows["term"][:255])
+    cfg = oracle.make_cfg(27, 64, 8, 32, loss=oracle.HUBER, opt=oracle.SGD, lr=1e-3)
+    p = synth.init_params(27, 64, 8, 0).astype(np.float64)
+    t0 = time.perf_counter()
+    for k in range(100):
+        j = 255 + k
+        ring.append(rows["s"][j:j + 1], rows["s_next"][j:j + 1], rows["a"][j:j + 1], rows["r"][j:j + 1],
+                    rows["term"][j:j + 1])
+        s_, sn, a, r, term = ring.gather(ring.sample(0, k, 32))
+        p = oracle.train_step(cfg, p, None, None, 0, s_, sn, a, r, term).params
+    res["tiny"] = {"steps": 100, "steps_per_s": 100 / (time.perf_counter() - t0)}
+    # Wide: 27-1024-1024-30 with the bf16 rounding points, batch 4096, Adam, 64 appends per step
+    w = W_CFG
+    rows = synth.experiences(20_000, w["D"], w["A"], w["p_term"], seed=0, state_dtype="bf16")
+    ring = oracle.Ring(20_000, w["D"], oracle.BF16)
+    ring.append(rows["s"][:19_872], rows["s_next"][:19_872], rows["a"][:19_872], rows["r"][:19_872],
+                rows["term"][:19_872])
+    cfg = oracle.make_cfg(w["D"], w["H"], w["A"], w["B"], loss=oracle.HUBER, opt=oracle.ADAM, lr=w["lr"],
+                          bf16=1)
+    p = synth.init_params(w["D"], w["H"], w["A"], 0).astype(np.float64)
+    m, v, t = np.zeros_like(p), np.zeros_like(p), 0
+    t0 = time.perf_counter()
+    for k in range(2):
+        j = 19_872 + 64 * k
+        ring.append(rows["s"][j:j + 64], rows["s_next"][j:j + 64], rows["a"][j:j + 64], rows["r"][j:j + 64],
+                    rows["term"][j:j + 64])
+        s_, sn, a, r, term = ring.gather(ring.sample(0, k, w["B"]))
+        o = oracle.train_step(cfg, p, m, v, t, synth.bf16_bits_to_f32(s_), synth.bf16_bits_to_f32(sn), a, r, term)
+        p, m, v, t = o.params, o.m, o.v, o.t
+    res["wide"] = {"steps": 2, "steps_per_s": 2 / (time.perf_counter() - t0),
+                   "note": "ring of 20,000 rows instead of 4,000,000 (the oracle's step does not depend on it)"}
+    oracle.set_threads(1)
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10_000)
     ap.add_argument("--warmup", type=int, default=500)
-    ap.add_argument("--legs", default="p,pfull,phost,pmodel,inram,gather,append,copy,large,wide,cpu")
+    ap.add_argument("--legs", default="p,psteady,pfull,phost,pmodel,inram,gather,append,copy,large,wide,cpu")
     ap.add_argument("--gather-reps", type=int, default=1000)
     ap.add_argument("--wide-steps", type=int, default=2000)
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
@@ -380,6 +454,13 @@ def main():
     log("[bench] paper-shaped train steps (burn-in ring) ...")
     p = leg_paper_shaped(B, synth, args.steps, args.warmup, full_ring=False)
     log("[bench]   %.0f steps/s, %d kernels/step" % (p["steps_per_s"], p["kernels_per_step"]))
+    if "psteady" in legs:
+        # a fixed-length run whatever --steps says, so that the steady-state rate is on record
+        log("[bench] paper-shaped train steps, fixed 10,000-step run ...")
+        out["paper_shaped_steady_state"] = leg_paper_shaped(B, synth, 10_000, 500, full_ring=False)
+        out["paper_shaped_steady_state"]["steps"] = 10_000
+        out["paper_shaped_steady_state"]["warmup"] = 500
+        log("[bench]   %.0f steps/s" % out["paper_shaped_steady_state"]["steps_per_s"])
     if "pfull" in legs:
         log("[bench] paper-shaped train steps (full 1M-row ring) ...")
         out["paper_shaped_full_ring"] = leg_paper_shaped(B, synth, args.steps, args.warmup, True)
@@ -399,9 +480,14 @@ def main():
             B, synth, args.steps, args.warmup, False, target_sync=10_000, dueling=True)
         out["paper_shaped_without_duplicates"] = leg_paper_shaped(B, synth, args.steps, args.warmup, False,
                                                                   distinct=True)
+        # the paper's own network: shared layer 128, value and advantage stream 512 each, dueling
+        # head, frozen target network synced every 10,000 updates (Deep Q-Network Model), fp32
+        out["paper_network_27_128_1024_dueling_target"] = leg_paper_shaped(
+            B, synth, args.steps, args.warmup, False, target_sync=10_000, dueling=True, widths=(128, 1024))
+        out["paper_network_27_128_1024_dueling_target"]["network"] = "27-128-(512+512)-(1+30), fp32"
         for k in ("paper_shaped_target_network", "paper_shaped_dueling", "paper_shaped_dueling_target_network",
-                  "paper_shaped_without_duplicates"):
-            log("[bench]   %-38s %8.0f steps/s, %d kernels/step" %
+                  "paper_shaped_without_duplicates", "paper_network_27_128_1024_dueling_target"):
+            log("[bench]   %-42s %8.0f steps/s, %d kernels/step" %
                 (k, out[k]["steps_per_s"], out[k]["kernels_per_step"]))
     if "inram" in legs:
         log("[bench] device-resident replay vs in-RAM replay with a per-step batch copy ...")
@@ -410,17 +496,31 @@ def main():
             log("[bench]   B=%-4d device %8.0f steps/s   in-RAM %8.0f steps/s   %+6.1f %%" %
                 (g["batch"], g["device_steps_per_s"], g["inram_steps_per_s"], g["speedup_pct"]))
     roofline = None
+    rooflines = []
     if "gather" in legs:
         log("[bench] gather sweep on the full 1M-row ring ...")
         out["gather_sweep"] = leg_gather_sweep(B, synth, args.gather_reps)
         for g in out["gather_sweep"]:
             log("[bench]   B=%-6d %8.2f us  %8.1f GB/s" % (g["batch"], g["us_per_call"], g["GBps"]))
         g = out["gather_sweep"][-1]
-        roofline = {"kernel": "sample_gather_pair_kernel<4, 1, false>", "workload": "gather sweep, batch %d, "
+        roofline = {"kernel": GATHER_KERNEL, "workload": "gather sweep, batch %d, "
                     "capacity 1,000,000, 27 fp32 per state" % g["batch"], "bound": "hbm",
                     "achieved": g["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": g["GBps"] / HBM_PEAK_GBS, "traffic": GATHER_65536_HBM_BYTES,
-                    "alg_bytes_per_launch": g["alg_bytes"], "us_per_launch": g["us_per_call"]}
+                    "alg_bytes_per_launch": g["alg_bytes"], "us_per_launch": g["us_per_call"],
+                    "note": "the 256 MB ring is about the size of the last-level cache: a cache / HBM mix; "
+                            "see rooflines for a 2 GB ring and the 5.6 GB large-state ring"}
+        rooflines.append(dict(roofline))
+        # the same kernel on a ring eight times the size of the last-level cache
+        big = leg_gather_sweep(B, synth, max(100, args.gather_reps // 4), capacity=8_000_000,
+                               batches=[65536])[0]
+        out["gather_8M_row_ring"] = big
+        log("[bench]   8M-row ring (2 GB) B=65536 %8.2f us  %8.1f GB/s" % (big["us_per_call"], big["GBps"]))
+        rooflines.append({"kernel": GATHER_KERNEL, "workload": "gather, batch 65536, capacity 8,000,000 "
+                          "(2 GB ring, eight times the last-level cache), 27 fp32 per state",
+                          "bound": "hbm", "achieved": big["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                          "frac": big["GBps"] / HBM_PEAK_GBS, "traffic": None,
+                          "alg_bytes_per_launch": big["alg_bytes"], "us_per_launch": big["us_per_call"]})
     if "gather" in legs:
         out["gather_sweep_without_duplicates"] = leg_gather_sweep(B, synth, max(100, args.gather_reps // 4),
                                                                   distinct=True)
@@ -453,12 +553,25 @@ def main():
         for g in out["large_state_gather"]:
             g["frac_hbm"] = g["GBps"] / HBM_PEAK_GBS
             log("[bench]   B=%-6d %8.2f us  %8.1f GB/s" % (g["batch"], g["us_per_call"], g["GBps"]))
+        g = out["large_state_gather"][-1]
+        rooflines.append({"kernel": "sample_gather_chain_kernel<1, 0>", "workload": "large-state gather, batch "
+                          "%d, 200,000 x 84x84x4 uint8 (5.6 GB ring), uint8 -> fp32 / 255" % g["batch"],
+                          "bound": "hbm", "achieved": g["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                          "frac": g["GBps"] / HBM_PEAK_GBS, "traffic": LARGE_256_HBM_BYTES,
+                          "alg_bytes_per_launch": g["alg_bytes"], "us_per_launch": g["us_per_call"]})
     if "wide" in legs:
         log("[bench] wide fused step (bf16, batch 4096, 27-1024-1024-30) ...")
         w = leg_wide(B, synth, args.wide_steps, 10)
         w["frac_mfma"] = w["TFLOPs"] / BF16_MFMA_PEAK_TFLOPS
         out["wide_step"] = w
         log("[bench]   %.1f steps/s, %.1f TFLOP/s" % (w["steps_per_s"], w["TFLOPs"]))
+        rooflines.append({"kernel": "whole wide step (%d kernels; the dense products are gemm_nt_kernel)"
+                          % w["kernels_per_step"],
+                          "workload": "wide fused step: batch 4096, 27-1024-1024-30, bf16 operands, fp32 "
+                                      "accumulation, Adam, 64 appends per step", "bound": "mfma",
+                          "achieved": w["TFLOPs"], "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                          "frac": w["frac_mfma"], "traffic": None, "alg_flops_per_step": w["alg_flops"],
+                          "us_per_step": 1e3 * w["ms_per_step"]})
     cpu = None
     if "cpu" in legs:
         log("[bench] CPU oracle on the paper-shaped workload ...")
@@ -470,6 +583,14 @@ def main():
                "value_1thread": o["one"]["steps_per_s"], "host_cpus": os.cpu_count()}
         log("[bench]   %.1f steps/s on %d threads, %.1f on one" %
             (cpu["value"], cpu["cores"], cpu["value_1thread"]))
+        log("[bench] CPU oracle on the gather sweep, the Tiny workload and the wide workload ...")
+        x = leg_cpu_oracle_extras(synth, cpu["cores"])
+        cpu["gather_sweep"] = x["gather_sweep"]
+        cpu["tiny"] = x["tiny"]
+        cpu["wide"] = x["wide"]
+        for g in x["gather_sweep"]:
+            log("[bench]   gather B=%-6d %10.1f us  %6.2f GB/s" % (g["batch"], g["us_per_call"], g["GBps"]))
+        log("[bench]   Tiny %.0f steps/s; wide %.3f steps/s" % (x["tiny"]["steps_per_s"], x["wide"]["steps_per_s"]))
 
     line = {
         "metric": "replay train steps/sec at B=128, cap 1M; gather GB/s vs HBM peak",
@@ -480,7 +601,14 @@ def main():
                                "burn-in 50,000, 1 append/step from HBM, batch 128, MLP 27-256-256-30, "
                                "Huber, Adam 1e-4, one HIP graph per step",
                    "kernels_per_step": p["kernels_per_step"]},
-        "roofline": roofline, "cpu_baseline": cpu,
+        "roofline": roofline, "rooflines": rooflines, "cpu_baseline": cpu,
+        # context only: another machine, another framework, the paper's own dueling network
+        "paper_context": {"speedup_in_gpu_vs_in_ram_pct": {"16": 30.54, "32": 54.87, "64": 67.08,
+                                                           "128": 114.41, "256": 114.35},
+                          "at_batch_128_pct": 114.41,
+                          "hardware": "one NVIDIA TITAN X (Pascal) 12 GB, TensorFlow, fp32",
+                          "source": "the paper's Table 1 (Results)",
+                          "compare_with": "device_vs_inram[batch 128].speedup_pct"},
     }
     line.update(out)
     print(json.dumps(line), flush=True)

@@ -67,10 +67,11 @@ enum { RP_TRAIN_GRAPH = 1, RP_TRAIN_LAYERED = 2 };
 enum { RP_WITH_REPLACEMENT = 0, RP_DISTINCT = 1 };
 /* train_config.head.  RP_HEAD_PLAIN: the last layer gives Q(s, .) directly.  RP_HEAD_DUELING: the
  * dueling head of the paper's network (Deep Q-Network Model): the second hidden layer is two
- * streams side by side, units 0 .. H/2-1 feed a state value V, units H/2 .. H-1 feed one
- * advantage per action, and Q(s,a) = V(s) + A(s,a) - mean_a' A(s,a').  The last layer then has
- * 1 + num_actions outputs (V first) in every parameter array: W3[H*(1+A)] b3[1+A]; its weights
- * from the other stream's units take no part and never change. */
+ * streams side by side, units 0 .. G/2-1 feed a state value V, units G/2 .. G-1 feed one
+ * advantage per action (G = the second hidden layer's width), and
+ * Q(s,a) = V(s) + A(s,a) - mean_a' A(s,a').  The last layer then has 1 + num_actions outputs
+ * (V first) in every parameter array: W3[G*(1+A)] b3[1+A]; its weights from the other stream's
+ * units take no part and never change. */
 enum { RP_HEAD_PLAIN = 0, RP_HEAD_DUELING = 1 };
 
 typedef struct {
@@ -200,17 +201,21 @@ typedef struct {
                                   that is overwritten with the trained ones after every N-th
                                   update (Deep Q-Network Model: target fixing, N = 10,000)      */
     uint32_t head;             /* RP_HEAD_PLAIN | RP_HEAD_DUELING                              */
+    uint32_t hidden2;          /* G: width of the second hidden layer (multiple of 64); 0 = H.
+                                  The paper's network (Deep Q-Network Model: a shared layer of 128
+                                  units, then a value and an advantage stream of 512 units each)
+                                  is hidden = 128, hidden2 = 1024, head = RP_HEAD_DUELING          */
 } train_config;
 
-/* number of network parameters: D*H + H + H*H + H + H*O + O, O = A (plain head) or 1 + A (dueling) */
+/* number of network parameters: D*H + H + H*G + G + G*O + O, O = A (plain head) or 1 + A (dueling) */
 size_t train_param_count(const train_config* cfg);
 /* Bytes of device workspace train_create needs (0 if the configuration is invalid). */
 size_t train_workspace_bytes(const train_config* cfg);
 
 /*
- * Create a trainer for the network D -> H -> H -> A (ReLU after both hidden
- * layers) on top of a PAIR replay.  host_init_params (host) holds
- * W1[D*H] b1[H] W2[H*H] b2[H] W3[H*A] b3[A], matrices row-major [in x out].
+ * Create a trainer for the network D -> H -> G -> A (ReLU after both hidden
+ * layers; G = hidden2, or H when that is 0) on top of a PAIR replay.  host_init_params (host)
+ * holds W1[D*H] b1[H] W2[H*G] b2[G] W3[G*A] b3[A], matrices row-major [in x out].
  * dev_workspace: device, 256-byte aligned, train_workspace_bytes().  Synchronises.
  */
 rp_status train_create(const train_config* cfg, replay_t* rp, void* dev_workspace, size_t bytes,

@@ -36,7 +36,7 @@ class TrainCfg(C.Structure):
                 ("batch", C.c_uint32), ("loss", C.c_uint32), ("opt", C.c_uint32),
                 ("bf16", C.c_uint32), ("dueling", C.c_uint32), ("lr", C.c_double),
                 ("gamma", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double),
-                ("eps", C.c_double)]
+                ("eps", C.c_double), ("hidden2", C.c_uint32), ("pad_", C.c_uint32)]
 
 
 _lib = None
@@ -72,6 +72,8 @@ def lib():
         L.oracle_bf16_bits.restype = C.c_uint16
         L.oracle_param_count.argtypes = [u32, u32, u32]
         L.oracle_param_count.restype = C.c_size_t
+        L.oracle_param_count2.argtypes = [u32, u32, u32, u32]
+        L.oracle_param_count2.restype = C.c_size_t
         L.oracle_mlp_forward.argtypes = [vp, vp, vp, u32, vp, vp, vp]
         L.oracle_loss_fixed_targets.argtypes = [vp, vp, vp, vp, vp]
         L.oracle_loss_fixed_targets.restype = C.c_double
@@ -208,18 +210,23 @@ class Ring:
 
 
 def make_cfg(state_dim, hidden, num_actions, batch, loss=HUBER, opt=SGD, bf16=0, lr=1e-3,
-             gamma=0.99, beta1=0.9, beta2=0.999, eps=1e-8, dueling=0):
+             gamma=0.99, beta1=0.9, beta2=0.999, eps=1e-8, dueling=0, hidden2=0):
     return TrainCfg(state_dim, hidden, num_actions, batch, loss, opt, bf16, dueling, lr, gamma, beta1,
-                    beta2, eps)
+                    beta2, eps, hidden2, 0)
+
+
+def cfg_hidden2(cfg):
+    return cfg.hidden2 or cfg.hidden
 
 
 def cfg_param_count(cfg):
     """Parameters of the network a configuration describes (the dueling head has one more output)."""
-    return param_count(cfg.state_dim, cfg.hidden, cfg.num_actions + (1 if cfg.dueling else 0))
+    return param_count(cfg.state_dim, cfg.hidden, cfg.num_actions + (1 if cfg.dueling else 0),
+                       cfg_hidden2(cfg))
 
 
-def param_count(D, H, A):
-    return int(lib().oracle_param_count(D, H, A))
+def param_count(D, H, A, H2=None):
+    return int(lib().oracle_param_count2(D, H, H if H2 is None else H2, A))
 
 
 def mlp_forward(cfg, params, X, want_hidden=False):
@@ -228,7 +235,7 @@ def mlp_forward(cfg, params, X, want_hidden=False):
     n = X.shape[0]
     Q = np.empty((n, cfg.num_actions), np.float64)
     h1 = np.empty((n, cfg.hidden), np.float64) if want_hidden else None
-    h2 = np.empty((n, cfg.hidden), np.float64) if want_hidden else None
+    h2 = np.empty((n, cfg_hidden2(cfg)), np.float64) if want_hidden else None
     lib().oracle_mlp_forward(C.byref(cfg), _p(params), _p(X), n, _p(h1), _p(h2), _p(Q))
     return (Q, h1, h2) if want_hidden else Q
 

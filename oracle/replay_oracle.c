@@ -284,12 +284,14 @@ double oracle_round_bf16(double x) {
 }
 
 /* ------------------------------------------------------------------------
- * Q-network: D -> H -> H -> A, ReLU after the two hidden layers, linear out.
+ * Q-network: D -> H -> G -> A, ReLU after the two hidden layers, linear out
+ * (G = cfg->hidden2, or H when that is 0).
  *
  * With cfg->dueling the last layer is the dueling head of the paper (Deep
- * Q-Network Model): the second hidden layer is two streams side by side, units
- * 0 .. H/2-1 feed a scalar state value V and units H/2 .. H-1 feed one
- * advantage per action, and
+ * Q-Network Model: one shared layer, then a value stream and an advantage
+ * stream, 128 and 2 x 512 units in the paper, i.e. H = 128, G = 1024): the
+ * second hidden layer is the two streams side by side, units 0 .. G/2-1 feed a
+ * scalar state value V and units G/2 .. G-1 feed one advantage per action, and
  *     Q(s, a) = V(s) + A(s, a) - mean_a' A(s, a').
  * The last layer then has 1 + A outputs (column 0 = V, column 1 + a = A(., a));
  * its weights from the other stream's units are structurally zero and get no
@@ -298,48 +300,55 @@ double oracle_round_bf16(double x) {
 static uint32_t out_width(const oracle_train_cfg* cfg) {
     return cfg->num_actions + (cfg->dueling ? 1u : 0u);
 }
+/* width of the second hidden layer (hidden2 = 0: as wide as the first) */
+static uint32_t width2(const oracle_train_cfg* cfg) {
+    return cfg->hidden2 ? cfg->hidden2 : cfg->hidden;
+}
 
+size_t oracle_param_count2(uint32_t D, uint32_t H, uint32_t G, uint32_t A) {
+    return (size_t)D * H + H + (size_t)H * G + G + (size_t)G * A + A;
+}
 size_t oracle_param_count(uint32_t D, uint32_t H, uint32_t A) {
-    return (size_t)D * H + H + (size_t)H * H + H + (size_t)H * A + A;
+    return oracle_param_count2(D, H, H, A);
 }
 
 typedef struct {
     const double *W1, *b1, *W2, *b2, *W3, *b3;
 } net_view;
 
-static net_view view_params(const double* p, uint32_t D, uint32_t H, uint32_t A) {
+static net_view view_params(const double* p, uint32_t D, uint32_t H, uint32_t G, uint32_t A) {
     net_view n;
     n.W1 = p;               p += (size_t)D * H;
     n.b1 = p;               p += H;
-    n.W2 = p;               p += (size_t)H * H;
-    n.b2 = p;               p += H;
-    n.W3 = p;               p += (size_t)H * A;
+    n.W2 = p;               p += (size_t)H * G;
+    n.b2 = p;               p += G;
+    n.W3 = p;               p += (size_t)G * A;
     n.b3 = p;
     (void)A;
     return n;
 }
 
-/* 1 where the dueling head has a weight from hidden unit k to output o */
+/* 1 where the dueling head has a weight from unit k of the second hidden layer to output o */
 static int head_connected(const oracle_train_cfg* cfg, uint32_t k, uint32_t o) {
     if (!cfg->dueling) return 1;
-    const int value_stream = k < cfg->hidden / 2;
+    const int value_stream = k < width2(cfg) / 2;
     return o == 0 ? value_stream : !value_stream;
 }
 
 /* the weights the matrix products see: bf16-rounded copies in mixed precision, and the
  * structural zeros of the dueling head */
 static double* effective_params(const oracle_train_cfg* cfg, const double* params) {
-    const uint32_t D = cfg->state_dim, H = cfg->hidden, O = out_width(cfg);
-    size_t n = oracle_param_count(D, H, O);
+    const uint32_t D = cfg->state_dim, H = cfg->hidden, G = width2(cfg), O = out_width(cfg);
+    size_t n = oracle_param_count2(D, H, G, O);
     double* e = (double*)malloc(n * sizeof(double));
     memcpy(e, params, n * sizeof(double));
-    size_t oW1 = 0, oW2 = (size_t)D * H + H, oW3 = oW2 + (size_t)H * H + H;
+    size_t oW1 = 0, oW2 = (size_t)D * H + H, oW3 = oW2 + (size_t)H * G + G;
     if (cfg->bf16) {
         for (size_t k = 0; k < (size_t)D * H; ++k) e[oW1 + k] = oracle_round_bf16(e[oW1 + k]);
-        for (size_t k = 0; k < (size_t)H * H; ++k) e[oW2 + k] = oracle_round_bf16(e[oW2 + k]);
-        for (size_t k = 0; k < (size_t)H * O; ++k) e[oW3 + k] = oracle_round_bf16(e[oW3 + k]);
+        for (size_t k = 0; k < (size_t)H * G; ++k) e[oW2 + k] = oracle_round_bf16(e[oW2 + k]);
+        for (size_t k = 0; k < (size_t)G * O; ++k) e[oW3 + k] = oracle_round_bf16(e[oW3 + k]);
     }
-    for (uint32_t k = 0; k < H; ++k)
+    for (uint32_t k = 0; k < G; ++k)
         for (uint32_t o = 0; o < O; ++o)
             if (!head_connected(cfg, k, o)) e[oW3 + (size_t)k * O + o] = 0.0;
     return e;
@@ -379,14 +388,14 @@ static void head_combine(const oracle_train_cfg* cfg, const double* z, uint32_t 
 
 static void forward_with(const oracle_train_cfg* cfg, const double* eff, const double* X,
                          uint32_t n, double* h1, double* h2, double* Q) {
-    const uint32_t D = cfg->state_dim, H = cfg->hidden, O = out_width(cfg);
-    net_view w = view_params(eff, D, H, O);
+    const uint32_t D = cfg->state_dim, H = cfg->hidden, G = width2(cfg), O = out_width(cfg);
+    net_view w = view_params(eff, D, H, G, O);
     double* t1 = h1 ? h1 : (double*)malloc((size_t)n * H * sizeof(double));
-    double* t2 = h2 ? h2 : (double*)malloc((size_t)n * H * sizeof(double));
+    double* t2 = h2 ? h2 : (double*)malloc((size_t)n * G * sizeof(double));
     double* z = (double*)malloc((size_t)n * O * sizeof(double));
     dense(X, n, D, w.W1, w.b1, H, 1, (int)cfg->bf16, t1);
-    dense(t1, n, H, w.W2, w.b2, H, 1, (int)cfg->bf16, t2);
-    dense(t2, n, H, w.W3, w.b3, O, 0, 0, z);
+    dense(t1, n, H, w.W2, w.b2, G, 1, (int)cfg->bf16, t2);
+    dense(t2, n, G, w.W3, w.b3, O, 0, 0, z);
     head_combine(cfg, z, n, Q);
     free(z);
     if (!h1) free(t1);
@@ -467,14 +476,14 @@ void oracle_train_step_target(const oracle_train_cfg* cfg, double* params,
                               const double* r, const uint8_t* term, double* Q_out, double* Qn_out,
                               double* y_out, double* delta_out, double* loss_out,
                               double* grads_out) {
-    const uint32_t D = cfg->state_dim, H = cfg->hidden, A = cfg->num_actions, B = cfg->batch;
-    const uint32_t O = out_width(cfg);
-    const size_t P = oracle_param_count(D, H, O);
+    const uint32_t D = cfg->state_dim, H = cfg->hidden, G = width2(cfg), A = cfg->num_actions;
+    const uint32_t B = cfg->batch, O = out_width(cfg);
+    const size_t P = oracle_param_count2(D, H, G, O);
     double* eff = effective_params(cfg, params);
-    net_view w = view_params(eff, D, H, O);
+    net_view w = view_params(eff, D, H, G, O);
 
     double* h1 = (double*)malloc((size_t)B * H * sizeof(double));
-    double* h2 = (double*)malloc((size_t)B * H * sizeof(double));
+    double* h2 = (double*)malloc((size_t)B * G * sizeof(double));
     double* Q  = (double*)malloc((size_t)B * A * sizeof(double));
     double* Qn = (double*)malloc((size_t)B * A * sizeof(double));
     forward_with(cfg, eff, S, B, h1, h2, Q);
@@ -521,39 +530,39 @@ void oracle_train_step_target(const oracle_train_cfg* cfg, double* params,
     double* gW1 = g;
     double* gb1 = gW1 + (size_t)D * H;
     double* gW2 = gb1 + H;
-    double* gb2 = gW2 + (size_t)H * H;
-    double* gW3 = gb2 + H;
-    double* gb3 = gW3 + (size_t)H * O;
+    double* gb2 = gW2 + (size_t)H * G;
+    double* gW3 = gb2 + G;
+    double* gb3 = gW3 + (size_t)G * O;
 
     /* output layer: dW3 = h2^T dz3 where the head has a weight, db3 = column sums of dz3 */
 #pragma omp parallel for schedule(static)
-    for (int64_t k = 0; k < (int64_t)H; ++k)
+    for (int64_t k = 0; k < (int64_t)G; ++k)
         for (uint32_t i = 0; i < B; ++i)
             for (uint32_t o = 0; o < O; ++o)
                 if (head_connected(cfg, (uint32_t)k, o))
-                    gW3[(size_t)k * O + o] += h2[(size_t)i * H + k] * dz3[(size_t)i * O + o];
+                    gW3[(size_t)k * O + o] += h2[(size_t)i * G + k] * dz3[(size_t)i * O + o];
     for (uint32_t i = 0; i < B; ++i)
         for (uint32_t o = 0; o < O; ++o) gb3[o] += dz3[(size_t)i * O + o];
 
     /* dz2 = (dz3 W3^T) masked by the second ReLU */
-    double* dz2 = (double*)malloc((size_t)B * H * sizeof(double));
+    double* dz2 = (double*)malloc((size_t)B * G * sizeof(double));
 #pragma omp parallel for schedule(static)
     for (int64_t i = 0; i < (int64_t)B; ++i)
-        for (uint32_t k = 0; k < H; ++k) {
+        for (uint32_t k = 0; k < G; ++k) {
             double acc = 0.0;
             for (uint32_t o = 0; o < O; ++o) acc += dz3[(size_t)i * O + o] * w.W3[(size_t)k * O + o];
-            if (!(h2[(size_t)i * H + k] > 0.0)) acc = 0.0;
-            dz2[(size_t)i * H + k] = cfg->bf16 ? oracle_round_bf16(acc) : acc;
+            if (!(h2[(size_t)i * G + k] > 0.0)) acc = 0.0;
+            dz2[(size_t)i * G + k] = cfg->bf16 ? oracle_round_bf16(acc) : acc;
         }
 
     /* dW2 = h1^T dz2, db2 = column sums of dz2 */
 #pragma omp parallel for schedule(static)
     for (int64_t j = 0; j < (int64_t)H; ++j)
         for (uint32_t i = 0; i < B; ++i)
-            for (uint32_t k = 0; k < H; ++k)
-                gW2[(size_t)j * H + k] += h1[(size_t)i * H + j] * dz2[(size_t)i * H + k];
+            for (uint32_t k = 0; k < G; ++k)
+                gW2[(size_t)j * G + k] += h1[(size_t)i * H + j] * dz2[(size_t)i * G + k];
     for (uint32_t i = 0; i < B; ++i)
-        for (uint32_t k = 0; k < H; ++k) gb2[k] += dz2[(size_t)i * H + k];
+        for (uint32_t k = 0; k < G; ++k) gb2[k] += dz2[(size_t)i * G + k];
 
     /* dz1 = (dz2 W2^T) masked by the first ReLU */
     double* dz1 = (double*)malloc((size_t)B * H * sizeof(double));
@@ -561,7 +570,7 @@ void oracle_train_step_target(const oracle_train_cfg* cfg, double* params,
     for (int64_t i = 0; i < (int64_t)B; ++i)
         for (uint32_t j = 0; j < H; ++j) {
             double acc = 0.0;
-            for (uint32_t k = 0; k < H; ++k) acc += dz2[(size_t)i * H + k] * w.W2[(size_t)j * H + k];
+            for (uint32_t k = 0; k < G; ++k) acc += dz2[(size_t)i * G + k] * w.W2[(size_t)j * G + k];
             if (!(h1[(size_t)i * H + j] > 0.0)) acc = 0.0;
             dz1[(size_t)i * H + j] = cfg->bf16 ? oracle_round_bf16(acc) : acc;
         }

@@ -86,14 +86,19 @@ typedef struct {
                           has 1 + num_actions outputs (V first), fed by the two halves of the second
                           hidden layer */
     double lr, gamma, beta1, beta2, eps;
+    uint32_t hidden2;  /* width of the second hidden layer; 0 = the same as `hidden`.  With the
+                          dueling head its two halves are the value and the advantage stream
+                          (Deep Q-Network Model: shared layer 128, two streams of 512) */
+    uint32_t pad_;
 } oracle_train_cfg;
 
-/* Parameters are one flat array: W1[D*H] b1[H] W2[H*H] b2[H] W3[H*A] b3[A],
- * every matrix row-major [in x out]; with the dueling head W3 and b3 have 1 + num_actions
- * columns, i.e. the count is oracle_param_count(D, H, num_actions + 1). */
-size_t oracle_param_count(uint32_t D, uint32_t H, uint32_t A);
+/* Parameters are one flat array: W1[D*H] b1[H] W2[H*G] b2[G] W3[G*A] b3[A] (G = the second
+ * hidden width), every matrix row-major [in x out]; with the dueling head W3 and b3 have
+ * 1 + num_actions columns, i.e. the count is oracle_param_count2(D, H, G, num_actions + 1). */
+size_t oracle_param_count(uint32_t D, uint32_t H, uint32_t A);   /* G = H */
+size_t oracle_param_count2(uint32_t D, uint32_t H, uint32_t G, uint32_t A);
 
-/* Q = MLP(X) for n rows of X[n x D]; h1, h2 (post-ReLU, [n x H]) may be NULL. */
+/* Q = MLP(X) for n rows of X[n x D]; h1 [n x H], h2 [n x G] (post-ReLU) may be NULL. */
 void oracle_mlp_forward(const oracle_train_cfg* cfg, const double* params, const double* X,
                         uint32_t n, double* h1, double* h2, double* Q);
 

@@ -46,7 +46,7 @@ class TrainConfig(C.Structure):
                 ("opt", C.c_uint32), ("appends_per_step", C.c_uint32), ("lr", C.c_float),
                 ("gamma", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
                 ("eps", C.c_float), ("flags", C.c_uint32), ("target_sync", C.c_uint32),
-                ("head", C.c_uint32)]
+                ("head", C.c_uint32), ("hidden2", C.c_uint32)]
 
 
 # every symbol include/ingpu_replay.h declares: name -> (restype, argtypes)
@@ -296,12 +296,13 @@ class Trainer:
 
     def __init__(self, replay, hidden, num_actions, batch, param_dtype=RP_F32, loss=RP_HUBER,
                  opt=RP_ADAM, appends_per_step=1, lr=1e-4, gamma=0.99, beta1=0.9, beta2=0.999,
-                 eps=1e-8, use_graph=True, layered=False, target_sync=0, dueling=False, init_params=None):
+                 eps=1e-8, use_graph=True, layered=False, target_sync=0, dueling=False, init_params=None,
+                 hidden2=0):
         self.replay = replay
         self.cfg = TrainConfig(replay.cfg.state_dim, hidden, num_actions, batch, param_dtype, loss,
                                opt, appends_per_step, lr, gamma, beta1, beta2, eps,
                                (RP_TRAIN_GRAPH if use_graph else 0) | (RP_TRAIN_LAYERED if layered else 0),
-                               target_sync, RP_HEAD_DUELING if dueling else RP_HEAD_PLAIN)
+                               target_sync, RP_HEAD_DUELING if dueling else RP_HEAD_PLAIN, hidden2)
         nbytes = int(lib().train_workspace_bytes(C.byref(self.cfg)))
         if nbytes == 0:
             raise ReplayError(RP_EINVAL, "invalid train configuration")

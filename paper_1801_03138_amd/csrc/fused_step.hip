@@ -1026,6 +1026,7 @@ bool fused_step_supported(const train_config& cfg, const replay* rp_) {
     // registers: hidden width up to 256, states and action sets up to 64 wide
     if (cfg.hidden % 64 != 0 || cfg.hidden > 256 || cfg.state_dim > 64 || cfg.num_actions > 64)
         return false;
+    if (cfg.hidden2 != 0 && cfg.hidden2 != cfg.hidden) return false;   // two layers of one width
     if (cfg.batch > 8192 || cfg.appends_per_step > 8192) return false;
     const unsigned int Dp = (unsigned int)align_up(cfg.state_dim, 32);
     const unsigned int Ap = (unsigned int)align_up(cfg.num_actions, 32);
@@ -1113,8 +1114,18 @@ hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* bat
                         row_kernel_lds(t->Dp, t->H, t->Ap), st);
     if (e != hipSuccess) return e;
 
+    bool folded = false;
+    e = enqueue_weights_update(t, st, &folded);
+    if (e != hipSuccess) return e;
+    unsigned int nh = 0;
+    if (!folded) e = enqueue_head_update(t, st, &nh);
+    if (count) *count = 2 + nh;
+    return e;
+}
+
+hipError_t enqueue_weights_update(trainer* t, hipStream_t st, bool* folded_head) {
     WArgs w;
-    const unsigned int H = t->H;
+    const unsigned int H = t->H, G = t->Hb;
     auto set = [&](int j, const float* act, unsigned int lda, const float* err, unsigned int ldb,
                    unsigned int M, unsigned int N, size_t w_off, size_t b_off, float* wT,
                    unsigned int begin) {
@@ -1126,9 +1137,12 @@ hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* bat
         return begin + jb.tiles_n * ((M + kTM - 1) / kTM);
     };
     unsigned int nt = 0;
-    nt = set(0, a.H1, H, a.dZ2, H, H, H, t->oW2, t->ob2, t->w2t, nt);
-    nt = set(1, a.X, t->Dp, a.dZ1, H, t->Dp, H, t->oW1, t->ob1, nullptr, nt);
-    nt = set(2, a.H2, H, t->dQ, t->Ap, H, t->Ap, t->oW3, t->ob3, nullptr, nt);
+    // (only the two-kernel step reads the transposed copy of W2)
+    nt = set(0, static_cast<const float*>(t->H1), H, static_cast<const float*>(t->dZ2), G, H, G, t->oW2,
+             t->ob2, t->fused ? t->w2t : nullptr, nt);
+    nt = set(1, static_cast<const float*>(t->X), t->Dp, static_cast<const float*>(t->dZ1), H, t->Dp, H,
+             t->oW1, t->ob1, nullptr, nt);
+    nt = set(2, static_cast<const float*>(t->H2), G, t->dQ, t->Ap, G, t->Ap, t->oW3, t->ob3, nullptr, nt);
     w.B = t->B; w.n_tiles = nt;
     w.w = t->w; w.g = t->g; w.m = t->m; w.v = t->v;
     w.opt = t->cfg.opt; w.lr = t->cfg.lr; w.beta1 = t->cfg.beta1; w.beta2 = t->cfg.beta2;
@@ -1145,12 +1159,8 @@ hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* bat
         hipLaunchKernelGGL(fused_weights_kernel<true>, dim3(nt), dim3(kThreads), 0, st, w);
     else
         hipLaunchKernelGGL(fused_weights_kernel<false>, dim3(nt), dim3(kThreads), 0, st, w);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    unsigned int nh = 0;
-    if (!fold) e = enqueue_head_update(t, st, &nh);
-    if (count) *count = 2 + nh;
-    return e;
+    if (folded_head) *folded_head = fold;
+    return hipGetLastError();
 }
 
 }  // namespace rp

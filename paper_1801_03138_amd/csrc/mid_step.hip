@@ -1,0 +1,299 @@
+// fp32 train step on MFMA for networks the two-kernel step does not take: hidden layers wider
+// than 256 units, two hidden layers of different widths (the paper's own network: a shared layer
+// of 128 units, then a value and an advantage stream of 512 units each), wide states or action
+// sets.  One dense product per kernel, fp32 16x16x4 MFMA, operands straight from global memory
+// into the registers the instruction reads; the weight gradients and the optimizer are the
+// second kernel of the two-kernel step, which takes any whole number of 32 x 32 tiles.
+//
+// At the batch sizes of the paper (16 .. 256) every one of these products is a fraction of a
+// microsecond of arithmetic: what counts is that each kernel spreads over many compute units,
+// requests all its operands before the first multiply, and that there are few kernels.
+//
+// Paper: Deep Q-Network Model (the network and the update equation), Integration with
+// Reinforcement Learning Algorithm (train step with no host inputs).
+#include "replay_kernels.hpp"
+#include "trainer.hpp"
+
+namespace rp {
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef const __attribute__((address_space(1))) char* gbytes;   // global memory, byte-addressed
+
+constexpr unsigned int kMmThreads = 256;
+
+enum { MM_BIAS_RELU = 0, MM_BIAS = 1, MM_MASK = 2 };
+
+// C = A B (+ epilogue).  A is [M x K] with K contiguous.  NT: B is [N x K], K contiguous;
+// otherwise B is [K x N], N contiguous.  The M rows come in `parts` equal parts (1, or 2: the
+// rows of s and the rows of s'); a tile never straddles two parts, and the tiles of part 1 take
+// B_hi and bias_hi (the frozen target network's layer) instead of B and bias.
+struct MmArgs {
+    const float* A;
+    unsigned int lda;
+    const float* B;
+    const float* B_hi;
+    unsigned int ldb;
+    const float* bias;
+    const float* bias_hi;
+    const float* mask;       // MM_MASK: [M x N], the output is kept where mask > 0
+    unsigned int ldmask;
+    float* C;
+    unsigned int ldc;
+    unsigned int rows_per_part, parts, tiles_per_part;
+    unsigned int N, K;
+};
+
+// One wavefront's 16 x 16 tile of C over the K range [k_lo, k_lo + 16 * ngroups).
+// Lane l = 16 q + c of a 16x16x4 MFMA supplies A[row c][k slot q] and B[k slot q][column c] and
+// receives C[rows 4 q .. 4 q + 3][column c].  A group is 16 consecutive k: MFMA j of a group
+// takes k = 16 g + 4 q + j in slot q, so that a lane's share of A (and of B when it is K
+// contiguous) for a whole group is one 16-byte load.  P groups are in flight at a time: the
+// loads of group g + P are requested as soon as group g has been multiplied.  Loads never
+// branch: a group past the end re-reads the last one and is multiplied by zero.
+template <bool NT, int P>
+__device__ __forceinline__ f32x4 mm_tile(const float* __restrict__ A, unsigned int lda, unsigned int arow,
+                                         const float* __restrict__ B, unsigned int ldb, unsigned int bcol,
+                                         unsigned int k_lo, unsigned int ngroups, unsigned int lane) {
+    const unsigned int q = lane >> 4;
+    const gbytes ap = (gbytes)reinterpret_cast<const char*>(A) + ((size_t)arow * lda + k_lo + 4u * q) * 4u;
+    const gbytes bp = NT ? (gbytes)reinterpret_cast<const char*>(B) + ((size_t)bcol * ldb + k_lo + 4u * q) * 4u
+                         : (gbytes)reinterpret_cast<const char*>(B) + ((size_t)(k_lo + 4u * q) * ldb + bcol) * 4u;
+    f32x4 a[P], b[P];
+    auto load = [&](int s, unsigned int g) {
+        const unsigned int gc = g < ngroups ? g : ngroups - 1u;
+        a[s] = *(const __attribute__((address_space(1))) f32x4*)(ap + (size_t)gc * 64u);
+        if (NT) {
+            b[s] = *(const __attribute__((address_space(1))) f32x4*)(bp + (size_t)gc * 64u);
+        } else {
+            const gbytes rb = bp + (size_t)gc * 16u * ldb * 4u;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                b[s][j] = *(const __attribute__((address_space(1))) float*)(rb + (size_t)j * ldb * 4u);
+        }
+    };
+#pragma unroll
+    for (int s = 0; s < P; ++s) load(s, (unsigned int)s);
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (unsigned int g0 = 0; g0 < ngroups; g0 += P) {
+#pragma unroll
+        for (int s = 0; s < P; ++s) {
+            const bool live = g0 + s < ngroups;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(live ? a[s][j] : 0.f, b[s][j], acc, 0, 0, 0);
+            load(s, g0 + s + P);
+        }
+    }
+    return acc;
+}
+
+// Tiles of 32 x 32 per workgroup, a 16 x 16 quarter per wavefront over the whole K (KSPLIT
+// false), or 16 x 16 per workgroup with K split over its four wavefronts, summed through LDS
+// in a fixed order (KSPLIT true: long K, few tiles).
+template <bool NT, int EPI, bool KSPLIT, int P>
+__global__ __launch_bounds__(kMmThreads) void mm_f32_kernel(MmArgs p) {
+    __shared__ float part[3][64][4];
+    const unsigned int lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const unsigned int c = lane & 15u, q = lane >> 4;
+    constexpr unsigned int TM = KSPLIT ? 16u : 32u;
+    const unsigned int part_id = blockIdx.y / p.tiles_per_part;
+    const unsigned int m_begin = part_id * p.rows_per_part, m_end = m_begin + p.rows_per_part;
+    const unsigned int m0 = m_begin + (blockIdx.y - part_id * p.tiles_per_part) * TM + (KSPLIT ? 0u : 16u * (wave >> 1));
+    const unsigned int n0 = blockIdx.x * TM + (KSPLIT ? 0u : 16u * (wave & 1u));
+    const float* Bm = part_id ? p.B_hi : p.B;
+    const float* bias = part_id ? p.bias_hi : p.bias;
+    // rows past the part's end re-read its last row; they are not stored
+    const unsigned int arow = min(m0 + c, m_end - 1u);
+    const unsigned int groups = p.K >> 4;
+    const unsigned int ng = KSPLIT ? groups >> 2 : groups;
+    const unsigned int k_lo = KSPLIT ? wave * ng * 16u : 0u;
+    f32x4 acc = mm_tile<NT, P>(p.A, p.lda, arow, Bm, p.ldb, n0 + c, k_lo, ng, lane);
+    if (KSPLIT) {
+        if (wave) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) part[wave - 1u][lane][v] = acc[v];
+        }
+        __syncthreads();
+        if (wave) return;
+#pragma unroll
+        for (unsigned int w = 0; w < 3; ++w)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[v] += part[w][lane][v];
+    }
+    const unsigned int n = n0 + c;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const unsigned int m = m0 + 4u * q + v;
+        if (m >= m_end) continue;
+        float x = acc[v];
+        if (EPI == MM_BIAS_RELU) {
+            x += bias[n];
+            x = x > 0.f ? x : 0.f;
+        } else if (EPI == MM_BIAS) {
+            x += bias[n];
+        } else {
+            if (!(p.mask[(size_t)m * p.ldmask + n] > 0.f)) x = 0.f;
+        }
+        p.C[(size_t)m * p.ldc + n] = x;
+    }
+}
+
+// K is split over a workgroup's wavefronts when a product has few tiles and a long contraction.
+bool want_ksplit(unsigned int M, unsigned int N, unsigned int K) {
+    const unsigned int tiles32 = ((M + 31u) / 32u) * (N / 32u);
+    return K >= 256u && K % 64u == 0 && tiles32 < 256u;
+}
+
+template <bool NT, int EPI>
+hipError_t launch_mm(hipStream_t st, const MmArgs& a, unsigned int M_total) {
+    const bool ks = want_ksplit(M_total, a.N, a.K);
+    const unsigned int TM = ks ? 16u : 32u;
+    MmArgs p = a;
+    p.tiles_per_part = (a.rows_per_part + TM - 1u) / TM;
+    const dim3 grid(a.N / TM, p.tiles_per_part * a.parts), block(kMmThreads);
+    const unsigned int ng = (a.K >> 4) >> (ks ? 2 : 0);
+    if (ks) {
+        if (ng >= 8) hipLaunchKernelGGL((mm_f32_kernel<NT, EPI, true, 8>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((mm_f32_kernel<NT, EPI, true, 4>), grid, block, 0, st, p);
+    } else {
+        if (ng >= 8) hipLaunchKernelGGL((mm_f32_kernel<NT, EPI, false, 8>), grid, block, 0, st, p);
+        else if (ng >= 4) hipLaunchKernelGGL((mm_f32_kernel<NT, EPI, false, 4>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((mm_f32_kernel<NT, EPI, false, 2>), grid, block, 0, st, p);
+    }
+    return hipGetLastError();
+}
+
+// ----------------------------------------------------------------------------------------
+// TD target, loss and the gradient at the second hidden layer's pre-activation, one wavefront
+// per experience i:  y_i = r_i + gamma (1 - term_i) max_a Q[B + i][a],  delta_i = y_i - Q[i][a_i],
+// the loss term, the one non-zero of dL/dQ in row i, and
+//   dZ2[i][k] = dL/dQ[i][a_i] * W3[k][a_i] * 1[H2[i][k] > 0].
+// Thread 0 of block 0 also advances Adam's step count and its bias corrections.
+// ----------------------------------------------------------------------------------------
+struct MidTdArgs {
+    unsigned int B, G, A, Ap;
+    const float* Q;
+    const int* act;
+    const float* rew;
+    const unsigned char* term;
+    float gamma;
+    unsigned int loss_kind;
+    float beta1, beta2;
+    float *y, *delta, *lossi, *dQ;
+    const float* W3;     // [G x Ap]
+    const float* H2;     // [2B x G]
+    float* dZ2;          // [B x G]
+    TrainCounters* ctr;
+};
+
+__global__ __launch_bounds__(256) void mid_td_kernel(MidTdArgs p) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        const unsigned long long t = p.ctr->adam_t + 1;
+        p.ctr->adam_t = t;
+        p.ctr->c1 = (float)(1.0 - pow((double)p.beta1, (double)t));
+        p.ctr->c2 = (float)(1.0 - pow((double)p.beta2, (double)t));
+    }
+    const unsigned int lane = threadIdx.x & 63u;
+    const unsigned int i = blockIdx.x * 4u + (threadIdx.x >> 6);
+    if (i >= p.B) return;
+    const float* qn = p.Q + (size_t)(p.B + i) * p.Ap;
+    float best = -INFINITY;
+    for (unsigned int k = lane; k < p.A; k += 64) best = fmaxf(best, qn[k]);
+    best = wave_max(best);
+    unsigned int ai = (unsigned int)p.act[i];
+    if (ai >= p.A) ai = p.A - 1;  // an out-of-range action must not turn into a wild address
+    const float q = p.Q[(size_t)i * p.Ap + ai];
+    const float y = p.rew[i] + (p.term[i] ? 0.f : p.gamma * best);
+    const float d = y - q;
+    float li, slope;
+    if (p.loss_kind == RP_MSE || fabsf(d) <= 1.f) {
+        li = 0.5f * d * d;
+        slope = d;
+    } else {
+        li = fabsf(d) - 0.5f;
+        slope = d > 0.f ? 1.f : -1.f;
+    }
+    const float g = -slope / (float)p.B;
+    for (unsigned int k = lane; k < p.Ap; k += 64) p.dQ[(size_t)i * p.Ap + k] = (k == ai) ? g : 0.f;
+    if (lane == 0) {
+        p.y[i] = y;
+        p.delta[i] = d;
+        p.lossi[i] = li;
+    }
+    const float* h2 = p.H2 + (size_t)i * p.G;
+    float* dz = p.dZ2 + (size_t)i * p.G;
+    for (unsigned int k = lane; k < p.G; k += 64)
+        dz[k] = h2[k] > 0.f ? g * p.W3[(size_t)k * p.Ap + ai] : 0.f;
+}
+
+}  // namespace
+
+bool mid_step_supported(const train_config& cfg, const replay* rp_) {
+    // fp32 states and parameters; every matrix a whole number of 32 x 32 tiles (hidden widths are
+    // multiples of 64, states and action sets are padded to multiples of 32 in the workspace)
+    return cfg.param_dtype == RP_F32 && rp_->cfg.state_dtype == RP_F32 && rp_->cfg.layout == RP_PAIR &&
+           cfg.hidden % 64 == 0 && cfg.hidden2 % 64 == 0;
+}
+
+// Enqueue the step's kernels from the gathered batch on (X = [S ; S'], the per-row fields).
+hipError_t enqueue_mid_step(trainer* t, hipStream_t st, unsigned int* count) {
+    const unsigned int B = t->B, H = t->H, G = t->Hb, Dp = t->Dp, Ap = t->Ap;
+    const float* X = static_cast<const float*>(t->X);
+    float* H1 = static_cast<float*>(t->H1);
+    float* H2 = static_cast<float*>(t->H2);
+    float* dZ2 = static_cast<float*>(t->dZ2);
+    float* dZ1 = static_cast<float*>(t->dZ1);
+    const float* w = t->w;
+    const float* wt = t->wt ? t->wt : t->w;   // the network that evaluates s'
+    unsigned int n = 0;
+    // forward: the rows of s through the trained network, the rows of s' through the target's
+    // (the same when there is none: then the 2B rows are one part)
+    const unsigned int parts = t->wt ? 2u : 1u, rows = t->wt ? B : 2u * B;
+    MmArgs a;
+    a.mask = nullptr; a.ldmask = 0; a.rows_per_part = rows; a.parts = parts; a.tiles_per_part = 0;
+    a.A = X; a.lda = Dp; a.B = w + t->oW1; a.B_hi = wt + t->oW1; a.ldb = H;
+    a.bias = w + t->ob1; a.bias_hi = wt + t->ob1; a.C = H1; a.ldc = H; a.N = H; a.K = Dp;
+    hipError_t e = launch_mm<false, MM_BIAS_RELU>(st, a, 2u * B);
+    if (e != hipSuccess) return e;
+    ++n;
+    a.A = H1; a.lda = H; a.B = w + t->oW2; a.B_hi = wt + t->oW2; a.ldb = G;
+    a.bias = w + t->ob2; a.bias_hi = wt + t->ob2; a.C = H2; a.ldc = G; a.N = G; a.K = H;
+    e = launch_mm<false, MM_BIAS_RELU>(st, a, 2u * B);
+    if (e != hipSuccess) return e;
+    ++n;
+    a.A = H2; a.lda = G; a.B = w + t->oW3; a.B_hi = wt + t->oW3; a.ldb = Ap;
+    a.bias = w + t->ob3; a.bias_hi = wt + t->ob3; a.C = t->Q; a.ldc = Ap; a.N = Ap; a.K = G;
+    e = launch_mm<false, MM_BIAS>(st, a, 2u * B);
+    if (e != hipSuccess) return e;
+    ++n;
+    {
+        MidTdArgs d;
+        d.B = B; d.G = G; d.A = t->cfg.num_actions; d.Ap = Ap;
+        d.Q = t->Q; d.act = t->act; d.rew = t->rew; d.term = t->term;
+        d.gamma = t->cfg.gamma; d.loss_kind = t->cfg.loss; d.beta1 = t->cfg.beta1; d.beta2 = t->cfg.beta2;
+        d.y = t->y; d.delta = t->delta; d.lossi = t->lossi; d.dQ = t->dQ;
+        d.W3 = w + t->oW3; d.H2 = H2; d.dZ2 = dZ2; d.ctr = t->ctr;
+        hipLaunchKernelGGL(mid_td_kernel, dim3((B + 3) / 4), dim3(256), 0, st, d);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        ++n;
+    }
+    // dZ1 = (dZ2 W2^T) masked by the first ReLU: W2 is [H x G], i.e. K contiguous as it stands
+    a.rows_per_part = B; a.parts = 1;
+    a.A = dZ2; a.lda = G; a.B = w + t->oW2; a.B_hi = a.B; a.ldb = G; a.bias = nullptr; a.bias_hi = nullptr;
+    a.mask = H1; a.ldmask = H; a.C = dZ1; a.ldc = H; a.N = H; a.K = G;
+    e = launch_mm<true, MM_MASK>(st, a, B);
+    if (e != hipSuccess) return e;
+    ++n;
+    bool folded = false;
+    e = enqueue_weights_update(t, st, &folded);
+    if (e != hipSuccess) return e;
+    ++n;
+    unsigned int nh = 0;
+    if (!folded) e = enqueue_head_update(t, st, &nh);
+    if (count) *count = n + nh;
+    return e;
+}
+
+}  // namespace rp

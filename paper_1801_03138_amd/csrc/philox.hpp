@@ -81,6 +81,7 @@ __device__ __forceinline__ unsigned int distinct_rounds(unsigned int choices) {
     return 2u * bitlen + 8u;
 }
 constexpr unsigned int kMaxDistinctRounds = 72;   // 2 * 32 + 8
+constexpr unsigned int kDistinctTableWords = 80;  // the table's size: readers fetch a few entries past `rounds`
 
 // The round constants K_r of one sampling step, r = 0 .. rounds-1, into a table of
 // kMaxDistinctRounds words: lane l (l < rounds / 4, rounded up) fills entries 4 l .. 4 l + 3.
@@ -107,14 +108,24 @@ __device__ __forceinline__ unsigned int swap_bit(unsigned long long seed, unsign
                          (unsigned int)seed, (unsigned int)(seed >> 32)).x & 1u;
 }
 
-// distinct_draw with the round constants taken from a table (one lane, one draw).
+// distinct_draw with the round constants taken from a table (one lane, one draw).  The table
+// holds kMaxDistinctRounds words (entries past `rounds` are never used for a decision), and the
+// constants of four rounds are fetched at a time, ahead of the chain of dependent blocks.
 __device__ __forceinline__ unsigned int distinct_draw_serial(unsigned long long seed, unsigned long long step,
                                                              unsigned int i, unsigned int choices,
                                                              unsigned int rounds, const unsigned int* table) {
     unsigned int x = i;
-    for (unsigned int r = 0; r < rounds; ++r) {
-        const unsigned int partner = swap_partner(table[r], x, choices);
-        if (swap_bit(seed, step, r, partner > x ? partner : x)) x = partner;
+    for (unsigned int r0 = 0; r0 < rounds; r0 += 4u) {
+        unsigned int k[4];
+#pragma unroll
+        for (unsigned int j = 0; j < 4u; ++j) k[j] = table[r0 + j];
+#pragma unroll
+        for (unsigned int j = 0; j < 4u; ++j) {
+            if (r0 + j < rounds) {
+                const unsigned int partner = swap_partner(k[j], x, choices);
+                if (swap_bit(seed, step, r0 + j, partner > x ? partner : x)) x = partner;
+            }
+        }
     }
     return x;
 }
@@ -126,7 +137,8 @@ __device__ __forceinline__ unsigned int distinct_draw_serial(unsigned long long 
 // children 2v = "not swapped" and 2v + 1 = "swapped") takes the round at its depth d for the
 // position reached by the decisions its number spells, and computes that round's bit.  The
 // 2^G - 1 bits of a group then resolve in G cheap steps.  All lanes of a team return the draw;
-// i must be uniform over the team.
+// i must be uniform over the team.  The group's round constants are fetched into registers
+// first, so that the two short chains around the Philox block are arithmetic only.
 template <int G>
 __device__ __forceinline__ unsigned int distinct_draw_team(unsigned long long seed, unsigned long long step,
                                                            unsigned int i, unsigned int choices,
@@ -138,16 +150,24 @@ __device__ __forceinline__ unsigned int distinct_draw_team(unsigned long long se
     const unsigned int team_shift = lane & ~(T - 1u) & 63u;
     unsigned int x = i;
     for (unsigned int r0 = 0; r0 < rounds; r0 += G) {
-        // this member's position: x moved by the decisions its number spells (most significant first)
-        unsigned int xc = x;
+        // (the table has room for every index read here: r0 + G - 1 < kMaxDistinctRounds + G)
+        unsigned int k[G];
 #pragma unroll
-        for (unsigned int j = 0; j + 1u < (unsigned int)G; ++j)
-            if (j < d && ((v >> (d - 1u - j)) & 1u) && r0 + j < rounds)
-                xc = swap_partner(table[r0 + j], xc, choices);
+        for (unsigned int j = 0; j < (unsigned int)G; ++j) k[j] = r0 + j < rounds ? table[r0 + j] : 0u;
+        // this member's position: x moved by the decisions its number spells (most significant
+        // first), and the constant of the round at its depth
+        unsigned int xc = x, kd = k[0];
+#pragma unroll
+        for (unsigned int j = 0; j + 1u < (unsigned int)G; ++j) {
+            if (j < d) {
+                if ((v >> (d - 1u - j)) & 1u) xc = swap_partner(k[j], xc, choices);
+                kd = k[j + 1u];
+            }
+        }
         unsigned int bit = 0;
         const unsigned int r = r0 + d;
         if (v && r < rounds) {
-            const unsigned int partner = swap_partner(table[r], xc, choices);
+            const unsigned int partner = swap_partner(kd, xc, choices);
             bit = swap_bit(seed, step, r, partner > xc ? partner : xc);
         }
         const unsigned long long bits = __ballot(bit) >> team_shift;
@@ -156,7 +176,7 @@ __device__ __forceinline__ unsigned int distinct_draw_team(unsigned long long se
         for (unsigned int j = 0; j < (unsigned int)G; ++j) {
             if (r0 + j < rounds) {
                 const unsigned int b = (unsigned int)(bits >> node) & 1u;
-                if (b) x = swap_partner(table[r0 + j], x, choices);
+                if (b) x = swap_partner(k[j], x, choices);
                 node = 2u * node + b;
             }
         }

@@ -410,8 +410,9 @@ __global__ __launch_bounds__(64) void distinct_draw_kernel(
     RingGeom g, unsigned long long seed, unsigned long long step_value,
     const unsigned long long* __restrict__ step_ptr, unsigned int size_value,
     unsigned long long head_value, unsigned int batch, unsigned int* __restrict__ out) {
-    __shared__ unsigned int keys[kMaxDistinctRounds];
+    __shared__ unsigned int keys[kDistinctTableWords];
     const unsigned int lane = threadIdx.x;
+    if (lane < kDistinctTableWords - 64u) keys[64u + lane] = 0u;   // entries no lane computes
     const unsigned long long step = step_ptr ? *step_ptr : step_value;
     const unsigned long long size = size_value ? size_value : g.state->size;
     const unsigned long long head = size_value ? head_value : g.state->head;

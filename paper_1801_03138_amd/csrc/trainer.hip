@@ -267,23 +267,26 @@ struct WsLayout {
 
 bool ws_layout(const train_config* c, WsLayout* L) {
     if (!c || c->state_dim == 0 || c->state_dim > 4096 || c->hidden == 0 || c->hidden % 64 != 0 ||
-        c->hidden > 8192 || c->num_actions == 0 || c->num_actions > 4096 || c->batch == 0 ||
+        c->hidden > 8192 || c->hidden2 % 64 != 0 || c->hidden2 > 8192 || c->num_actions == 0 ||
+        c->num_actions > 4096 || c->batch == 0 ||
         c->batch > (1u << 20) || (c->param_dtype != RP_F32 && c->param_dtype != RP_BF16) ||
         c->loss > RP_MSE || c->opt > RP_ADAM || c->head > RP_HEAD_DUELING)
         return false;
-    const size_t D = c->state_dim, H = c->hidden, A = c->num_actions, B = c->batch;
+    // H, G: widths of the first and the second hidden layer
+    const size_t D = c->state_dim, H = c->hidden, G = c->hidden2 ? c->hidden2 : c->hidden;
+    const size_t A = c->num_actions, B = c->batch;
     L->Dp = (unsigned int)align_up(D, 32);
     L->Ap = (unsigned int)align_up(A, 32);
     L->elem = c->param_dtype == RP_BF16 ? 2 : 4;
     const size_t O = c->head == RP_HEAD_DUELING ? A + 1 : A;   // outputs of the last layer
-    L->n_params = D * H + H + H * H + H + H * O + O;
-    L->n_head = c->head == RP_HEAD_DUELING ? (H + 1) * O : 0;
+    L->n_params = D * H + H + H * G + G + G * O + O;
+    L->n_head = c->head == RP_HEAD_DUELING ? (G + 1) * O : 0;
     L->oW1 = 0;
     L->ob1 = L->oW1 + (size_t)L->Dp * H;
     L->oW2 = L->ob1 + H;
-    L->ob2 = L->oW2 + H * H;
-    L->oW3 = L->ob2 + H;
-    L->ob3 = L->oW3 + H * L->Ap;
+    L->ob2 = L->oW2 + H * G;
+    L->oW3 = L->ob2 + G;
+    L->ob3 = L->oW3 + G * L->Ap;
     L->n_padded = L->ob3 + L->Ap;
     size_t o = 0;
     auto take = [&](size_t bytes) {
@@ -298,7 +301,7 @@ bool ws_layout(const train_config* c, WsLayout* L) {
     L->m = take(n_dev * 4);
     L->v = take(n_dev * 4);
     L->wt = take(c->target_sync ? n_dev * 4 : 0);
-    L->w2t = take(c->param_dtype == RP_F32 ? H * H * 4 : 0);
+    L->w2t = take(c->param_dtype == RP_F32 ? G * H * 4 : 0);
     L->wb = take(c->param_dtype == RP_BF16 ? L->n_padded * 2 : 0);
     L->wbt = take(c->param_dtype == RP_BF16 && c->target_sync ? L->n_padded * 2 : 0);
     L->X = take(2 * B * L->Dp * L->elem);
@@ -307,16 +310,17 @@ bool ws_layout(const train_config* c, WsLayout* L) {
     L->term = take(B);
     L->idx = take(B * 4);
     L->H1 = take(2 * B * H * L->elem);
-    L->H2 = take(2 * B * H * L->elem);
+    L->H2 = take(2 * B * G * L->elem);
     L->Q = take(2 * B * L->Ap * 4);
     L->y = take(B * 4);
     L->delta = take(B * 4);
     L->lossi = take(B * 4);
     L->dQ = take(B * L->Ap * 4);
-    L->dZ2 = take(B * H * L->elem);
+    L->dZ2 = take(B * G * L->elem);
     L->dZ1 = take(B * H * L->elem);
     L->pre = take(2 * (4 + B) * 4);
-    const bool mixed = c->param_dtype == RP_BF16;
+    // the MFMA mixed-precision step exists for two hidden layers of one width
+    const bool mixed = c->param_dtype == RP_BF16 && H == G;
     const size_t Bp = align_up(B, 128), Dx = align_up(D + 1, 32);
     L->Bp = (unsigned int)Bp;
     L->W1T = take(mixed ? H * L->Dp * 2 : 0);
@@ -346,48 +350,48 @@ bool ws_layout(const train_config* c, WsLayout* L) {
 // and, for the dueling head, its own parameters behind them.  `weights`: also fill positions
 // W3 / b3 of the padded part with the plain output layer the dueling head amounts to.
 void pad_params(const trainer* t, const float* ext, std::vector<float>& pad, bool weights = true) {
-    const size_t D = t->cfg.state_dim, H = t->H, A = t->cfg.num_actions, Ap = t->Ap;
+    const size_t D = t->cfg.state_dim, H = t->H, G = t->Hb, A = t->cfg.num_actions, Ap = t->Ap;
     pad.assign(t->n_dev, 0.f);
     const float* p = ext;
     memcpy(&pad[t->oW1], p, D * H * 4); p += D * H;
     memcpy(&pad[t->ob1], p, H * 4);     p += H;
-    memcpy(&pad[t->oW2], p, H * H * 4); p += H * H;
-    memcpy(&pad[t->ob2], p, H * 4);     p += H;
+    memcpy(&pad[t->oW2], p, H * G * 4); p += H * G;
+    memcpy(&pad[t->ob2], p, G * 4);     p += G;
     if (!t->dueling) {
-        for (size_t k = 0; k < H; ++k) memcpy(&pad[t->oW3 + k * Ap], p + k * A, A * 4);
-        p += H * A;
+        for (size_t k = 0; k < G; ++k) memcpy(&pad[t->oW3 + k * Ap], p + k * A, A * 4);
+        p += G * A;
         memcpy(&pad[t->ob3], p, A * 4);
         return;
     }
     const size_t O = A + 1;
     float* head = &pad[t->n_padded];
-    memcpy(head, p, (H + 1) * O * 4);          // W3[H x O] followed by b3[O] = [(H+1) x O]
+    memcpy(head, p, (G + 1) * O * 4);          // W3[G x O] followed by b3[O] = [(G+1) x O]
     if (!weights) return;
-    for (size_t k = 0; k <= H; ++k) {
+    for (size_t k = 0; k <= G; ++k) {
         const float* row = head + k * O;
-        const float v = head_connected((unsigned int)H, (unsigned int)k, 0) ? row[0] : 0.f;
-        const bool adv_on = head_connected((unsigned int)H, (unsigned int)k, 1);
+        const float v = head_connected((unsigned int)G, (unsigned int)k, 0) ? row[0] : 0.f;
+        const bool adv_on = head_connected((unsigned int)G, (unsigned int)k, 1);
         float sum = 0.f;
         for (size_t a = 0; a < A; ++a) sum += adv_on ? row[1 + a] : 0.f;
         const float mean = sum / (float)A;
-        float* dst = k < H ? &pad[t->oW3 + k * Ap] : &pad[t->ob3];
+        float* dst = k < G ? &pad[t->oW3 + k * Ap] : &pad[t->ob3];
         for (size_t a = 0; a < A; ++a) dst[a] = v + (adv_on ? row[1 + a] : 0.f) - mean;
     }
 }
 
 void unpad_params(const trainer* t, const std::vector<float>& pad, float* ext) {
-    const size_t D = t->cfg.state_dim, H = t->H, A = t->cfg.num_actions, Ap = t->Ap;
+    const size_t D = t->cfg.state_dim, H = t->H, G = t->Hb, A = t->cfg.num_actions, Ap = t->Ap;
     float* p = ext;
     memcpy(p, &pad[t->oW1], D * H * 4); p += D * H;
     memcpy(p, &pad[t->ob1], H * 4);     p += H;
-    memcpy(p, &pad[t->oW2], H * H * 4); p += H * H;
-    memcpy(p, &pad[t->ob2], H * 4);     p += H;
+    memcpy(p, &pad[t->oW2], H * G * 4); p += H * G;
+    memcpy(p, &pad[t->ob2], G * 4);     p += G;
     if (t->dueling) {
-        memcpy(p, &pad[t->n_padded], (H + 1) * (A + 1) * 4);
+        memcpy(p, &pad[t->n_padded], (G + 1) * (A + 1) * 4);
         return;
     }
-    for (size_t k = 0; k < H; ++k) memcpy(p + k * A, &pad[t->oW3 + k * Ap], A * 4);
-    p += H * A;
+    for (size_t k = 0; k < G; ++k) memcpy(p + k * A, &pad[t->oW3 + k * Ap], A * 4);
+    p += G * A;
     memcpy(p, &pad[t->ob3], A * 4);
 }
 
@@ -477,7 +481,8 @@ void gemm(hipStream_t st, int M, int N, int K, const void* A, int lda, const voi
 // type of activations and of the matrices the products read.
 template <typename E>
 hipError_t enqueue_step(trainer* t, hipStream_t st, unsigned int* count, bool sample) {
-    const int B = (int)t->B, H = (int)t->H, Dp = (int)t->Dp, Ap = (int)t->Ap;
+    // H, G: widths of the first and the second hidden layer
+    const int B = (int)t->B, H = (int)t->H, G = (int)t->Hb, Dp = (int)t->Dp, Ap = (int)t->Ap;
     const unsigned int A = t->cfg.num_actions;
     const bool mixed = t->cfg.param_dtype == RP_BF16;
     const unsigned char* wsrc = mixed ? reinterpret_cast<const unsigned char*>(t->wb)
@@ -504,9 +509,9 @@ hipError_t enqueue_step(trainer* t, hipStream_t st, unsigned int* count, bool sa
     if (!t->wt) {
         gemm<E, E, E, false, false, EPI_BIAS_RELU>(st, 2 * B, H, Dp, t->X, Dp, W1, H, t->H1, H,
                                                    t->w + t->ob1, nullptr, 0); ++n;
-        gemm<E, E, E, false, false, EPI_BIAS_RELU>(st, 2 * B, H, H, t->H1, H, W2, H, t->H2, H,
+        gemm<E, E, E, false, false, EPI_BIAS_RELU>(st, 2 * B, G, H, t->H1, H, W2, G, t->H2, G,
                                                    t->w + t->ob2, nullptr, 0); ++n;
-        gemm<E, E, float, false, false, EPI_BIAS>(st, 2 * B, Ap, H, t->H2, H, W3, Ap, t->Q, Ap,
+        gemm<E, E, float, false, false, EPI_BIAS>(st, 2 * B, Ap, G, t->H2, G, W3, Ap, t->Q, Ap,
                                                   t->w + t->ob3, nullptr, 0); ++n;
     } else {
         const unsigned char* tsrc = mixed ? reinterpret_cast<const unsigned char*>(t->wbt)
@@ -521,10 +526,10 @@ hipError_t enqueue_step(trainer* t, hipStream_t st, unsigned int* count, bool sa
             gemm<E, E, E, false, false, EPI_BIAS_RELU>(st, B, H, Dp, Xb + r0 * Dp * eb, Dp,
                                                        ws_ + t->oW1 * eb, H, H1b + r0 * H * eb, H,
                                                        bias + t->ob1, nullptr, 0); ++n;
-            gemm<E, E, E, false, false, EPI_BIAS_RELU>(st, B, H, H, H1b + r0 * H * eb, H,
-                                                       ws_ + t->oW2 * eb, H, H2b + r0 * H * eb, H,
+            gemm<E, E, E, false, false, EPI_BIAS_RELU>(st, B, G, H, H1b + r0 * H * eb, H,
+                                                       ws_ + t->oW2 * eb, G, H2b + r0 * G * eb, G,
                                                        bias + t->ob2, nullptr, 0); ++n;
-            gemm<E, E, float, false, false, EPI_BIAS>(st, B, Ap, H, H2b + r0 * H * eb, H,
+            gemm<E, E, float, false, false, EPI_BIAS>(st, B, Ap, G, H2b + r0 * G * eb, G,
                                                       ws_ + t->oW3 * eb, Ap, t->Q + r0 * Ap, Ap,
                                                       bias + t->ob3, nullptr, 0); ++n;
         }
@@ -534,20 +539,20 @@ hipError_t enqueue_step(trainer* t, hipStream_t st, unsigned int* count, bool sa
                        t->Q, t->act, t->rew, t->term, t->cfg.gamma, t->cfg.loss, t->y, t->delta,
                        t->lossi, t->dQ, t->ctr, t->cfg.beta1, t->cfg.beta2); ++n;
     // output layer
-    gemm<E, float, float, true, false, EPI_NONE>(st, H, Ap, B, t->H2, H, t->dQ, Ap,
+    gemm<E, float, float, true, false, EPI_NONE>(st, G, Ap, B, t->H2, G, t->dQ, Ap,
                                                  t->g + t->oW3, Ap, nullptr, nullptr, 0); ++n;
     hipLaunchKernelGGL(colsum_kernel<float>, dim3((Ap + kThreads - 1) / kThreads), dim3(kThreads),
                        0, st, B, Ap, t->dQ, Ap, t->g + t->ob3); ++n;
-    hipLaunchKernelGGL(dz_out_kernel<E>, dim3(((size_t)B * H + kThreads - 1) / kThreads),
-                       dim3(kThreads), 0, st, t->B, t->H, A, t->Ap, t->dQ, t->act,
+    hipLaunchKernelGGL(dz_out_kernel<E>, dim3(((size_t)B * G + kThreads - 1) / kThreads),
+                       dim3(kThreads), 0, st, t->B, t->Hb, A, t->Ap, t->dQ, t->act,
                        static_cast<const E*>(W3), static_cast<const E*>(t->H2),
                        static_cast<E*>(t->dZ2)); ++n;
     // second hidden layer
-    gemm<E, E, float, true, false, EPI_NONE>(st, H, H, B, t->H1, H, t->dZ2, H, t->g + t->oW2, H,
+    gemm<E, E, float, true, false, EPI_NONE>(st, H, G, B, t->H1, H, t->dZ2, G, t->g + t->oW2, G,
                                              nullptr, nullptr, 0); ++n;
-    hipLaunchKernelGGL(colsum_kernel<E>, dim3((H + kThreads - 1) / kThreads), dim3(kThreads), 0, st,
-                       B, H, static_cast<const E*>(t->dZ2), H, t->g + t->ob2); ++n;
-    gemm<E, E, E, false, true, EPI_MASK>(st, B, H, H, t->dZ2, H, W2, H, t->dZ1, H, nullptr, t->H1,
+    hipLaunchKernelGGL(colsum_kernel<E>, dim3((G + kThreads - 1) / kThreads), dim3(kThreads), 0, st,
+                       B, G, static_cast<const E*>(t->dZ2), G, t->g + t->ob2); ++n;
+    gemm<E, E, E, false, true, EPI_MASK>(st, B, H, G, t->dZ2, G, W2, G, t->dZ1, H, nullptr, t->H1,
                                          H); ++n;
     // first hidden layer
     gemm<E, E, float, true, false, EPI_NONE>(st, Dp, H, B, t->X, Dp, t->dZ1, H, t->g + t->oW1, H,
@@ -574,14 +579,15 @@ hipError_t enqueue_append_and_step(trainer* t, const Payload& src, hipStream_t s
     if (t->fused) return enqueue_fused_step(t, src, nullptr, st, count);
     unsigned int n = 0, k = 0;
     replay* r = t->rp_;
-    if (t->cfg.appends_per_step && t->wide) {
+    if (t->cfg.appends_per_step && (t->wide || t->mid)) {
         // append, sample and gather in one launch; the step then starts from the gathered batch
         const unsigned int Dp = t->Dp;
-        unsigned short* X = static_cast<unsigned short*>(t->X);
+        unsigned char* X = static_cast<unsigned char*>(t->X);
         t->append_args = make_append_gather_args(
             r->geom, RingPos{r->head, r->size, r->total}, t->cfg.appends_per_step, src, r->cfg.seed,
             &t->ctr->step, t->B,
-            GatherOut{X, X + (size_t)t->B * Dp, Dp, t->act, t->rew, t->term, t->idx, t->wd.XT, t->Bp});
+            GatherOut{X, X + (size_t)t->B * Dp * t->elem, Dp, t->act, t->rew, t->term, t->idx,
+                      t->wide ? t->wd.XT : nullptr, t->Bp});
         unsigned int blocks;
         size_t lds;
         append_gather_shape(t->append_args, &blocks, &lds);
@@ -589,7 +595,7 @@ hipError_t enqueue_append_and_step(trainer* t, const Payload& src, hipStream_t s
         hipError_t e = hipLaunchKernel(append_gather_func(r->geom), dim3(blocks), dim3(kThreads), kargs,
                                        lds, st);
         if (e != hipSuccess) return e;
-        e = enqueue_wide_step(t, st, &k, false);
+        e = t->wide ? enqueue_wide_step(t, st, &k, false) : enqueue_mid_step(t, st, &k);
         if (count) *count = 1 + k;
         return e;
     }
@@ -601,6 +607,18 @@ hipError_t enqueue_append_and_step(trainer* t, const Payload& src, hipStream_t s
                                        dim3(kThreads), kargs, 0, st);
         if (e != hipSuccess) return e;
         ++n;
+    }
+    if (t->mid) {
+        // (no new experiences per step: sample and gather on their own, then the step)
+        unsigned int launched = 0;
+        hipError_t e = launch_sample_gather(r->geom, r->cfg.seed, 0, &t->ctr->step, t->B, t->X,
+                                            static_cast<unsigned char*>(t->X) + (size_t)t->B * t->Dp * 4, t->Dp,
+                                            t->act, t->rew, t->term, t->idx, st, nullptr, 0, 0, 0,
+                                            r->draw_scratch, &launched);
+        if (e != hipSuccess) return e;
+        e = enqueue_mid_step(t, st, &k);
+        if (count) *count = n + launched + k;
+        return e;
     }
     hipError_t e = t->wide ? enqueue_wide_step(t, st, &k, true)
                    : t->cfg.param_dtype == RP_BF16 ? enqueue_step<bf16_t>(t, st, &k, true)
@@ -630,7 +648,8 @@ hipError_t enqueue_batch_step(trainer* t, const Payload& batch, hipStream_t st) 
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    return t->wide ? enqueue_wide_step(t, st, nullptr, false)
+    return t->wide  ? enqueue_wide_step(t, st, nullptr, false)
+           : t->mid ? enqueue_mid_step(t, st, nullptr)
            : t->cfg.param_dtype == RP_BF16 ? enqueue_step<bf16_t>(t, st, nullptr, false)
                                            : enqueue_step<float>(t, st, nullptr, false);
 }
@@ -708,7 +727,7 @@ hipError_t enqueue_head_update(trainer* t, hipStream_t st, unsigned int* count) 
     if (count) *count = 0;
     if (!t->dueling) return hipSuccess;
     HeadArgs a;
-    a.H = t->H; a.A = t->cfg.num_actions; a.Ap = t->Ap;
+    a.H = t->Hb; a.A = t->cfg.num_actions; a.Ap = t->Ap;
     a.oW3 = t->oW3; a.ob3 = t->ob3; a.n_padded = t->n_padded;
     a.w = t->w; a.g = t->g; a.m = t->m; a.v = t->v; a.wt = t->wt;
     a.opt = t->cfg.opt; a.sync_every = t->cfg.target_sync;
@@ -718,7 +737,7 @@ hipError_t enqueue_head_update(trainer* t, hipStream_t st, unsigned int* count) 
     a.W3T_t = t->wide && t->wt ? t->wd.W3T_t : nullptr;
     a.wb = t->wide ? nullptr : t->wb;
     a.wbt = t->wide ? nullptr : t->wbt;
-    hipLaunchKernelGGL(dueling_head_kernel, dim3(t->H + 1), dim3(64),
+    hipLaunchKernelGGL(dueling_head_kernel, dim3(t->Hb + 1), dim3(64),
                        (t->cfg.num_actions + 1) * sizeof(float), st, a);
     if (count) *count = 1;
     return hipGetLastError();
@@ -784,8 +803,8 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
     RP_REQUIRE(cfg && rp_ && dev_workspace && host_init_params && out, "train_create: null argument");
     rp::WsLayout L;
     RP_REQUIRE(rp::ws_layout(cfg, &L),
-               "train_create: invalid configuration (hidden must be a multiple of 64; batch, "
-               "state_dim, num_actions >= 1)");
+               "train_create: invalid configuration (hidden and hidden2 must be multiples of 64; "
+               "batch, state_dim, num_actions >= 1)");
     RP_REQUIRE(rp_->cfg.layout == RP_PAIR, "train_create: the trainer needs a PAIR replay");
     RP_REQUIRE(rp_->cfg.state_dim == cfg->state_dim, "train_create: state_dim %u != replay's %u",
                cfg->state_dim, rp_->cfg.state_dim);
@@ -810,6 +829,7 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
     t->cfg = *cfg;
     t->rp_ = rp_;
     t->Dp = L.Dp; t->Ap = L.Ap; t->H = cfg->hidden; t->B = cfg->batch; t->Bp = L.Bp;
+    t->Hb = cfg->hidden2 ? cfg->hidden2 : cfg->hidden;
     t->n_params = L.n_params; t->n_padded = L.n_padded; t->elem = L.elem;
     t->dueling = cfg->head == RP_HEAD_DUELING;
     t->n_head = L.n_head;
@@ -828,6 +848,7 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
     t->w2t = cfg->param_dtype == RP_F32 ? reinterpret_cast<float*>(ws + L.w2t) : nullptr;
     t->fused = !(cfg->flags & RP_TRAIN_LAYERED) && rp::fused_step_supported(*cfg, rp_);
     t->wide = !(cfg->flags & RP_TRAIN_LAYERED) && rp::wide_step_supported(*cfg, rp_);
+    t->mid = !(cfg->flags & RP_TRAIN_LAYERED) && !t->fused && rp::mid_step_supported(*cfg, rp_);
     {
         auto at = [&](size_t off) { return reinterpret_cast<unsigned short*>(ws + off); };
         t->wd = rp::WideBuffers{at(L.W1T), at(L.W2b), at(L.W2T), at(L.W3T), at(L.W1Tt), at(L.W2Tt),
@@ -917,9 +938,9 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
         }
         t->pin_dev = static_cast<unsigned char*>(dp);
     }
-    t->payload_func = t->fused  ? rp::fused_rows_func(t->wt != nullptr, t->Dp, t->B)
-                      : t->wide ? rp::append_gather_func(rp_->geom)
-                                : rp::append_pair_func(rp_->geom);
+    t->payload_func = t->fused               ? rp::fused_rows_func(t->wt != nullptr, t->Dp, t->B)
+                      : (t->wide || t->mid) ? rp::append_gather_func(rp_->geom)
+                                            : rp::append_pair_func(rp_->geom);
     t->payload_kargs[0] = t->fused ? static_cast<void*>(&t->row_args) : static_cast<void*>(&t->append_args);
     t->payload_node[0] = nullptr;
     t->multi_graph = nullptr;
@@ -963,10 +984,13 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
         // (a batch without duplicates is drawn by a kernel of its own wherever the step samples
         // through the replay's stand-alone gather)
         const bool own_draw = rp_->cfg.sampling == RP_DISTINCT && !t->fused &&
-                              !(t->wide && cfg->appends_per_step);
+                              !((t->wide || t->mid) && cfg->appends_per_step);
+        // the head's update is folded into the weights kernel when the action set fits one tile
+        const bool folded_head = t->dueling && (t->fused || t->mid) && t->Ap == 32;
         t->kernels_per_step =
-            (t->dueling ? 1u : 0u) + (own_draw ? 1u : 0u) +
-            (t->fused ? (t->wt ? 3u : 2u)
+            (t->dueling && !folded_head ? 1u : 0u) + (own_draw ? 1u : 0u) +
+            (t->fused ? 2u
+             : t->mid ? 7u
                       : (cfg->appends_per_step ? 1u : 0u) +
                             (t->wide ? (t->wt && cfg->batch % 128 ? 13u : 10u) : (t->wt ? 17u : 14u)));
     }
@@ -1193,11 +1217,11 @@ rp_status train_set_state(trainer_t* t, const float* params, const float* m, con
     RP_CHECK_HIP(hipMemcpy(t->w, pad.data(), t->n_dev * 4, hipMemcpyHostToDevice));
     if (t->wide) RP_CHECK_HIP(rp::wide_set_weights(t, pad.data(), false));
     if (t->w2t) {
-        const size_t H = t->H;
-        std::vector<float> tr(H * H);
+        const size_t H = t->H, G = t->Hb;
+        std::vector<float> tr(G * H);
         for (size_t j = 0; j < H; ++j)
-            for (size_t k = 0; k < H; ++k) tr[k * H + j] = pad[t->oW2 + j * H + k];
-        RP_CHECK_HIP(hipMemcpy(t->w2t, tr.data(), H * H * 4, hipMemcpyHostToDevice));
+            for (size_t k = 0; k < G; ++k) tr[k * H + j] = pad[t->oW2 + j * G + k];
+        RP_CHECK_HIP(hipMemcpy(t->w2t, tr.data(), G * H * 4, hipMemcpyHostToDevice));
     }
     if (m) {
         rp::pad_params(t, m, pad, false);

@@ -43,8 +43,9 @@ struct TrainCounters {
 static_assert(sizeof(TrainCounters) == 64, "one line");
 
 
-// Whether the dueling head has a weight from hidden unit k (k = H: the bias) to output o
-// (0 = state value, fed by units 0 .. H/2-1; 1 + a = advantage of action a, fed by the rest).
+// Whether the dueling head has a weight from unit k of the second hidden layer (H units; k = H:
+// the bias) to output o (0 = state value, fed by units 0 .. H/2-1; 1 + a = advantage of action a,
+// fed by the rest).
 __host__ __device__ inline bool head_connected(unsigned int H, unsigned int k, unsigned int o) {
     if (k >= H) return true;
     return o == 0 ? k < H / 2 : k >= H / 2;
@@ -130,7 +131,8 @@ constexpr unsigned int kPinGroup = 16;       // slots per completion event
 struct trainer {
     train_config cfg;
     replay* rp_;
-    unsigned int Dp, Ap, H, B, Bp;
+    unsigned int Dp, Ap, H, B, Bp;   // H: width of the first hidden layer
+    unsigned int Hb;                 // width of the second hidden layer (= H unless cfg.hidden2 says otherwise)
     size_t n_params, n_padded;       // external / padded parameter counts
     // Dueling head: the arrays w, g, m, v, wt each continue past their n_padded entries with the
     // head's own parameters [(H+1) x (1+A)] (row H = biases); positions oW3.. / ob3.. of w then
@@ -144,7 +146,7 @@ struct trainer {
     rp::TrainCounters* ctr;
     float *w, *g, *m, *v;
     float* wt;                       // frozen target network (padded, as w); null without one
-    float* w2t;                      // fused path: W2 transposed, [H x H]
+    float* w2t;                      // fp32 steps: W2 transposed, [Hb x H]
     rp::bf16_t* wb;
     rp::bf16_t* wbt;                 // layered mixed precision: bf16 copy of the target network
     void* X;                         // [2B x Dp]
@@ -152,13 +154,14 @@ struct trainer {
     float* rew;
     unsigned char* term;
     unsigned int* idx;
-    void *H1, *H2;                   // [2B x H]
+    void *H1, *H2;                   // [2B x H], [2B x Hb]
     float* Q;                        // [2B x Ap]
     float *y, *delta, *lossi, *dQ;   // [B], [B], [B], [B x Ap]
-    void *dZ2, *dZ1;                 // [B x H]
+    void *dZ2, *dZ1;                 // [B x Hb], [B x H]
     unsigned int* pre;               // slots drawn ahead, 2 x (4 + B) words
     bool fused;                      // two-kernel step for small fp32 networks
     bool wide;                       // mixed-precision step on MFMA
+    bool mid;                        // fp32 step on MFMA, one product per kernel
     rp::WideBuffers wd;
     hipGraph_t graph;
     hipGraphExec_t graph_exec;
@@ -205,6 +208,14 @@ void* fused_rows_func(bool target_network, unsigned int Dp, unsigned int B);   /
 // Dueling head: turn the gradient of the equivalent plain output layer (in g) into the head's
 // update and refresh that layer (and its bf16 / target copies).  No-op for a plain head.
 hipError_t enqueue_head_update(trainer* t, hipStream_t st, unsigned int* count);
+// The second kernel of the fused step on its own: weight gradients of all three layers from the
+// activations and pre-activation gradients in the workspace, optimizer, mean loss, step counter;
+// a dueling head of up to 32 actions is updated by it too (*folded_head says so).
+hipError_t enqueue_weights_update(trainer* t, hipStream_t st, bool* folded_head);
+// fp32 step on MFMA for shapes the two-kernel step does not take (wider layers, two different
+// hidden widths): one product per kernel.
+bool mid_step_supported(const train_config& cfg, const replay* rp_);
+hipError_t enqueue_mid_step(trainer* t, hipStream_t st, unsigned int* count);
 // Mixed-precision step on MFMA (bf16 replay states and matrix operands).
 bool wide_step_supported(const train_config& cfg, const replay* rp_);
 unsigned int square_splits(unsigned int Bp, unsigned int H);   // K splits of the dW2 product

@@ -852,7 +852,8 @@ unsigned int square_splits(unsigned int Bp, unsigned int H) { return square_spli
 
 bool wide_step_supported(const train_config& cfg, const replay* rp_) {
     return cfg.param_dtype == RP_BF16 && rp_->cfg.state_dtype == RP_BF16 &&
-           rp_->cfg.layout == RP_PAIR && cfg.hidden % 64 == 0;
+           rp_->cfg.layout == RP_PAIR && cfg.hidden % 64 == 0 &&
+           (cfg.hidden2 == 0 || cfg.hidden2 == cfg.hidden);   // two hidden layers of one width
 }
 
 // Allow the products' LDS sizes and fill the ones rows of the transposed activation buffers

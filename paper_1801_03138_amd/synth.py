@@ -64,23 +64,26 @@ def take(rows, lo, hi):
     return {k: (None if v is None else v[lo:hi]) for k, v in rows.items()}
 
 
-def init_params(state_dim, hidden, num_actions, seed=0):
-    """Flat float32 [W1 b1 W2 b2 W3 b3], each ~ U(-1/sqrt(fan_in), 1/sqrt(fan_in)); W row-major [in x out]."""
+def init_params(state_dim, hidden, num_actions, seed=0, hidden2=None):
+    """Flat float32 [W1 b1 W2 b2 W3 b3], each ~ U(-1/sqrt(fan_in), 1/sqrt(fan_in)); W row-major [in x out].
+    hidden2: width of the second hidden layer (default: the same as the first)."""
     g = np.random.Generator(np.random.PCG64(seed + 1))
+    h2 = hidden if hidden2 is None else hidden2
     parts = []
-    for fan_in, fan_out in ((state_dim, hidden), (hidden, hidden), (hidden, num_actions)):
+    for fan_in, fan_out in ((state_dim, hidden), (hidden, h2), (h2, num_actions)):
         bound = 1.0 / np.sqrt(fan_in)
         parts.append(g.uniform(-bound, bound, size=fan_in * fan_out).astype(np.float32))
         parts.append(g.uniform(-bound, bound, size=fan_out).astype(np.float32))
     return np.concatenate(parts)
 
 
-def split_params(flat, state_dim, hidden, num_actions):
-    """Views W1[D,H], b1[H], W2[H,H], b2[H], W3[H,A], b3[A] into a flat parameter array."""
+def split_params(flat, state_dim, hidden, num_actions, hidden2=None):
+    """Views W1[D,H], b1[H], W2[H,G], b2[G], W3[G,A], b3[A] into a flat parameter array (G = hidden2 or H)."""
     D, H, A = state_dim, hidden, num_actions
+    G = H if hidden2 is None else hidden2
     o = 0
     out = []
-    for shape in ((D, H), (H,), (H, H), (H,), (H, A), (A,)):
+    for shape in ((D, H), (H,), (H, G), (G,), (G, A), (A,)):
         n = int(np.prod(shape))
         out.append(flat[o:o + n].reshape(shape))
         o += n

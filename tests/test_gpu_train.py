@@ -81,8 +81,9 @@ class Pair:
 
     def __init__(self, B, *, capacity, D, H, A, batch, burn_in, seed, dtype="f32", loss="huber",
                  opt="adam", lr=1e-4, appends=1, use_graph=True, max_append=4096, layered=False,
-                 target_sync=0, distinct=False, dueling=False):
+                 target_sync=0, distinct=False, dueling=False, H2=0):
         self.B, self.D, self.H, self.A, self.batch, self.seed = B, D, H, A, batch, seed
+        self.H2 = H2 or H                       # width of the second hidden layer
         self.bf16 = dtype == "bf16"
         self.target_sync = target_sync
         self.distinct = distinct
@@ -91,18 +92,19 @@ class Pair:
                                  max_append=max_append, distinct=distinct)
         self.ref_ring = oracle.Ring(capacity, D, oracle.BF16 if self.bf16 else oracle.F32,
                                     oracle.PAIR, burn_in=burn_in)
-        self.p0 = synth.init_params(D, H, A + (1 if dueling else 0), seed)
+        self.p0 = synth.init_params(D, H, A + (1 if dueling else 0), seed, hidden2=self.H2)
         f = np.float32
         self.hyper = dict(lr=f(lr), gamma=f(0.99), beta1=f(0.9), beta2=f(0.999), eps=f(1e-8))
         self.trainer = B.Trainer(self.gpu_ring, H, A, batch, param_dtype=sd,
                                  loss=B.RP_HUBER if loss == "huber" else B.RP_MSE,
                                  opt=B.RP_ADAM if opt == "adam" else B.RP_SGD,
                                  appends_per_step=appends, use_graph=use_graph, layered=layered,
-                                 target_sync=target_sync, dueling=dueling, init_params=self.p0, **{k: float(v) for k, v in self.hyper.items()})
+                                 target_sync=target_sync, dueling=dueling, init_params=self.p0, hidden2=H2,
+                                 **{k: float(v) for k, v in self.hyper.items()})
         self.cfg = oracle.make_cfg(D, H, A, batch,
                                    loss=oracle.HUBER if loss == "huber" else oracle.MSE,
                                    opt=oracle.ADAM if opt == "adam" else oracle.SGD,
-                                   bf16=int(self.bf16), dueling=int(dueling),
+                                   bf16=int(self.bf16), dueling=int(dueling), hidden2=H2,
                                    **{k: float(v) for k, v in self.hyper.items()})
         self.rtol = BF16_RTOL if self.bf16 else F32_RTOL
         self.kink_steps = 0
@@ -114,12 +116,12 @@ class Pair:
         """Boolean mask over the parameter vector: the gradient entries that a hidden unit lying
         within its fp32 rounding error of the ReLU kink (from parameters p on states S, float64)
         can change; None when there is no such unit."""
-        D, H = self.D, self.H
+        D, H, G = self.D, self.H, self.H2
         O = self.A + (1 if self.dueling else 0)
         p = np.asarray(p, np.float64)
         W1, b1 = p[:D * H].reshape(D, H), p[D * H:D * H + H]
         o = D * H + H
-        W2, b2 = p[o:o + H * H].reshape(H, H), p[o + H * H:o + H * H + H]
+        W2, b2 = p[o:o + H * G].reshape(H, G), p[o + H * G:o + H * G + G]
         u = 16.0 * 2.0 ** -24
         z1 = S @ W1 + b1
         k1 = (np.abs(z1) <= u * (np.abs(S) @ np.abs(W1) + np.abs(b1))).any(axis=0)
@@ -129,14 +131,14 @@ class Pair:
         if not k1.any() and not k2.any():
             return None
         mW1, mb1 = np.zeros((D, H), bool), np.zeros(H, bool)
-        mW2, mb2 = np.zeros((H, H), bool), np.zeros(H, bool)
+        mW2, mb2 = np.zeros((H, G), bool), np.zeros(G, bool)
         mW1[:, k1] = True
         mb1[k1] = True
         if k2.any():
             mW2[:, k2] = True
             mb2[k2] = True
             mW1[:], mb1[:] = True, True
-        return np.concatenate([mW1.ravel(), mb1, mW2.ravel(), mb2, np.zeros(H * O + O, bool)])
+        return np.concatenate([mW1.ravel(), mb1, mW2.ravel(), mb2, np.zeros(G * O + O, bool)])
 
     def append_only(self, part, device_src=True):
         self.ref_ring.append(part["s"], part["s_next"], part["a"], part["r"], part["term"])
@@ -367,10 +369,10 @@ def test_steps_in_flight_equal_steps_synchronised_one_by_one(B, dtype, H, layere
     assert all(np.array_equal(x.view(np.uint8), y.view(np.uint8)) for x, y in zip(a[7], b[7]))
 
 
-@pytest.mark.parametrize("H,layered,kernels", [(192, False, 2), (320, False, 15), (320, True, 15)])
+@pytest.mark.parametrize("H,layered,kernels", [(192, False, 2), (320, False, 7), (320, True, 15)])
 def test_other_widths_agree_with_oracle(B, H, layered, kernels):
-    """Widths that leave lanes idle in the row kernel (192) or exceed it (320, one kernel per
-    layer, tiles with ragged edges); batch 130, ring that wraps."""
+    """Widths that leave lanes idle in the row kernel (192) or exceed it (320: one MFMA product
+    per kernel, or one plain kernel per layer, tiles with ragged edges); batch 130, ring that wraps."""
     rows = synth.experiences(900, 27, 30, 0.05, seed=12)
     pr = Pair(B, capacity=500, D=27, H=H, A=30, batch=130, burn_in=300, seed=4, appends=2,
               layered=layered)
@@ -398,8 +400,8 @@ def test_batches_beyond_one_workgroup_per_compute_unit(B, D, H, A, batch, target
 
 
 def test_wide_state_and_action_sets(B):
-    """D = 60 and A = 64 fill the row kernel's 64-wide limits; D = 70 goes layer by layer."""
-    for D, A, kernels in ((60, 64, 2), (70, 40, 15)):
+    """D = 60 and A = 64 fill the row kernel's 64-wide limits; D = 70 takes one product per kernel."""
+    for D, A, kernels in ((60, 64, 2), (70, 40, 7)):
         rows = synth.experiences(400, D, A, 0.05, seed=13)
         pr = Pair(B, capacity=300, D=D, H=128, A=A, batch=37, burn_in=50, seed=6, appends=1)
         assert pr.trainer.kernels_per_step() == kernels
@@ -650,6 +652,75 @@ def test_dueling_head(B, dtype, H, batch, layered, target_sync, kernels, A):
     assert not np.array_equal(W3a[:H // 2, 0], W3b[:H // 2, 0])
 
 
+@pytest.mark.parametrize("D,H,H2,A,batch,target_sync,dueling,opt,loss,kernels", [
+    (27, 128, 1024, 30, 128, 6, True, "adam", "huber", 7),     # the paper's network
+    (27, 128, 1024, 30, 130, 4, True, "adam", "huber", 7),     # ... on a batch that ends inside a tile
+    (27, 128, 512, 30, 64, 0, False, "sgd", "mse", 7),
+    (27, 64, 192, 40, 33, 3, True, "adam", "mse", 8),          # head wider than one tile: a kernel of its own
+    (70, 320, 64, 5, 50, 0, False, "adam", "huber", 7),
+    (27, 512, 512, 30, 256, 5, False, "adam", "huber", 7),
+    (9, 1024, 128, 3, 17, 0, True, "sgd", "huber", 7),
+])
+def test_two_hidden_widths_on_mfma(B, D, H, H2, A, batch, target_sync, dueling, opt, loss, kernels):
+    """fp32 networks the two-kernel step does not take, one MFMA product per kernel: two hidden
+    layers of different widths, foremost the paper's own network (Deep Q-Network Model: shared
+    layer 128, value and advantage stream 512 each, i.e. 27-128-1024-(1+30), frozen target
+    network), wide layers, wide states, K splits (contractions of 256 and more) and ragged batches."""
+    rows = synth.experiences(700, D, A, 0.05, seed=61)
+    pr = Pair(B, capacity=400, D=D, H=H, H2=H2, A=A, batch=batch, burn_in=300, seed=7, appends=2,
+              target_sync=target_sync, dueling=dueling, opt=opt, loss=loss, lr=1e-3)
+    assert pr.trainer.kernels_per_step() == kernels
+    n_params = D * H + H + H * H2 + H2 + H2 * (A + dueling) + A + dueling
+    assert len(pr.trainer.params()) == n_params
+    for lo in (0, 250):                       # 500 experiences into 400 slots: the ring wraps
+        pr.append_only(synth.take(rows, lo, lo + 250))
+    for k in range(500, 700, 2):
+        assert pr.step(synth.take(rows, k, k + 2), compare=(k % 20 == 0) or k >= 690) == 0
+    assert pr.gpu_ring.state() == pr.ref_ring.state()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_two_hidden_widths_layer_by_layer(B, dtype):
+    """The plain one-kernel-per-layer step takes two widths as well (fp32 behind RP_TRAIN_LAYERED;
+    in mixed precision it is the step for two different widths)."""
+    rows = synth.experiences(300, 27, 30, 0.05, seed=62, state_dtype=dtype)
+    pr = Pair(B, capacity=256, D=27, H=64, H2=128, A=30, batch=40, burn_in=100, seed=3, dtype=dtype,
+              appends=2, layered=dtype == "f32", target_sync=5, dueling=True, lr=1e-3)
+    assert pr.trainer.kernels_per_step() == 19
+    for k in range(0, 300, 2):
+        pr.step(synth.take(rows, k, k + 2), compare=(k % 30 == 0) or k >= 290)
+
+
+def test_paper_network_step_on_a_given_batch_and_without_appends(B):
+    """The paper's network with no new experiences per step (sample and gather in a kernel of
+    their own) and on a caller-provided batch."""
+    D, H, H2, A, batch = 27, 128, 1024, 30, 70
+    rows = synth.experiences(400, D, A, 0.1, seed=63)
+    pr = Pair(B, capacity=300, D=D, H=H, H2=H2, A=A, batch=batch, burn_in=0, seed=1, appends=0,
+              dueling=True, target_sync=2, lr=1e-3)
+    assert pr.trainer.kernels_per_step() == 7
+    pr.append_only(synth.take(rows, 0, 300))
+    empty = synth.take(rows, 0, 0)
+    for k in range(4):
+        assert pr.step(empty, compare=True) == 0
+    tr = pr.trainer
+    d = {k: torch.from_numpy(v).cuda() for k, v in synth.take(rows, 300, 300 + batch).items()}
+    part = synth.take(rows, 300, 300 + batch)
+    for k in range(3):
+        p, (m, v, t, step), tgt = tr.params(), tr.opt_state(), tr.target()
+        assert tr.step_batch(d["s"], d["s_next"], d["a"], d["r"], d["term"]) == 0
+        ref = oracle.train_step(pr.cfg, p, m, v, t, part["s"].astype(np.float64),
+                                part["s_next"].astype(np.float64), part["a"], part["r"], part["term"],
+                                target=tgt)
+        last = tr.last()
+        assert_close(last["Q"], ref.Q, pr.rtol, "Q(s,.)")
+        assert_close(last["Qn"], ref.Qn, pr.rtol, "Q(s',.)")
+        assert_close([last["loss"]], [ref.loss], pr.rtol, "loss")
+        own_p, _, _, _ = oracle.opt_apply(pr.cfg, p, m, v, t, tr.grads())
+        assert_close(tr.params(), own_p, F32_RTOL, "update rule applied to the GPU's own gradient")
+        assert_close(tr.grads(), ref.grads, 10 * pr.rtol, "gradients")
+
+
 def _random_configs(n, seed):
     """Seeded draw of step configurations: every kind of step (two-kernel fp32, MFMA mixed
     precision, layered), shapes on and off the tile sizes, both losses and optimizers, with and
@@ -661,13 +732,14 @@ def _random_configs(n, seed):
         H = int(rng.choice([64, 128, 192, 256, 320]))
         if dtype == "bf16":
             H = int(rng.choice([64, 128, 192]))
+        H2 = int(rng.choice([0, 0, 64, 128, 320])) if dtype == "f32" else 0
         D = int(rng.integers(1, 70))
         A = int(rng.integers(1, 70))
         batch = int(rng.choice([1, 2, 5, 31, 64, 100, 128, 129, 257]))
         appends = int(rng.choice([0, 1, 3, 17]))
         capacity = int(rng.choice([300, 512, 1000]))
         distinct = bool(rng.random() < 0.3) and batch <= 128
-        out.append(dict(dtype=dtype, H=H, D=D, A=A, batch=batch, appends=appends, capacity=capacity,
+        out.append(dict(dtype=dtype, H=H, H2=H2, D=D, A=A, batch=batch, appends=appends, capacity=capacity,
                         loss=str(rng.choice(["huber", "mse"])), opt=str(rng.choice(["adam", "sgd"])),
                         layered=bool(rng.random() < 0.25), target_sync=int(rng.choice([0, 0, 3])),
                         dueling=bool(rng.random() < 0.3) and A >= 2, distinct=distinct,
@@ -676,14 +748,14 @@ def _random_configs(n, seed):
 
 
 @pytest.mark.parametrize("c", _random_configs(64, 20261127), ids=lambda c: "-".join(
-    "%s" % c[k] for k in ("dtype", "D", "H", "A", "batch", "appends", "opt", "loss")))
+    "%s" % c[k] for k in ("dtype", "D", "H", "H2", "A", "batch", "appends", "opt", "loss")))
 def test_random_configurations(B, c):
     """Twelve teacher-forced steps of a randomly drawn configuration, after a prefill that wraps
     the ring when the capacity is small."""
     n_pre = c["capacity"] + 57
     rows = synth.experiences(n_pre + 12 * max(1, c["appends"]), c["D"], c["A"], 0.05, seed=c["seed"],
                              state_dtype=c["dtype"])
-    pr = Pair(B, capacity=c["capacity"], D=c["D"], H=c["H"], A=c["A"], batch=c["batch"], burn_in=40,
+    pr = Pair(B, capacity=c["capacity"], D=c["D"], H=c["H"], H2=c["H2"], A=c["A"], batch=c["batch"], burn_in=40,
               seed=c["seed"], dtype=c["dtype"], loss=c["loss"], opt=c["opt"], lr=1e-3,
               appends=c["appends"], layered=c["layered"], target_sync=c["target_sync"],
               distinct=c["distinct"], dueling=c["dueling"])

@@ -524,3 +524,73 @@ def test_dueling_with_one_action_is_the_value_stream_alone():
     q = np.concatenate([p[:oW3], w_plain, p[oW3 + 2 * H:oW3 + 2 * H + 1]])
     assert np.allclose(oracle.mlp_forward(cfg, p, rows["s"]), oracle.mlp_forward(plain, q, rows["s"]),
                        rtol=1e-13, atol=1e-15)
+
+
+# ---------------------------------------------------------------- two hidden widths
+def _two_width_problem(D, H, G, A, n, seed, dueling):
+    rows = synth.experiences(n, D, A, 0.2, seed=seed)
+    p = synth.init_params(D, H, A + (1 if dueling else 0), seed, hidden2=G).astype(np.float64)
+    return p, rows
+
+
+def test_two_widths_forward_against_library_network():
+    """D -> H -> G -> A with H != G: torch.nn.functional in float64 (library routine), and the
+    hidden activations have the two different widths."""
+    D, H, G, A, n = 7, 8, 12, 3, 25
+    p, rows = _two_width_problem(D, H, G, A, n, 3, False)
+    w1, b1, w2, b2, w3, b3 = [torch.from_numpy(np.array(x)) for x in synth.split_params(p, D, H, A, hidden2=G)]
+    F = torch.nn.functional
+    x = torch.from_numpy(rows["s"].astype(np.float64))
+    want = F.linear(F.relu(F.linear(F.relu(F.linear(x, w1.T, b1)), w2.T, b2)), w3.T, b3).numpy()
+    cfg = oracle.make_cfg(D, H, A, n, hidden2=G)
+    got, h1, h2 = oracle.mlp_forward(cfg, p, rows["s"], want_hidden=True)
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-14)
+    assert h1.shape == (n, H) and h2.shape == (n, G)
+    assert oracle.cfg_param_count(cfg) == D * H + H + H * G + G + G * A + A == p.size
+    # hidden2 equal to hidden is the same network as hidden2 = 0
+    q = synth.init_params(D, H, A, 5).astype(np.float64)
+    a = oracle.mlp_forward(oracle.make_cfg(D, H, A, n), q, rows["s"])
+    b = oracle.mlp_forward(oracle.make_cfg(D, H, A, n, hidden2=H), q, rows["s"])
+    assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("dueling", [0, 1])
+def test_two_widths_gradients_match_finite_differences(dueling):
+    """Every parameter of a D-H-G-A network with H != G (plain and dueling head) against central
+    differences of the frozen-target loss; then the SGD step is -lr times that gradient."""
+    D, H, G, A, n = 5, 4, 6, 3, 20
+    p, rows = _two_width_problem(D, H, G, A, n, 21, dueling)
+    cfg = oracle.make_cfg(D, H, A, n, loss=oracle.HUBER, opt=oracle.SGD, lr=1e-2, dueling=dueling, hidden2=G)
+    out = oracle.train_step(cfg, p, None, None, 0, rows["s"], rows["s_next"], rows["a"], rows["r"], rows["term"])
+    assert np.allclose(out.params, p - 1e-2 * out.grads, rtol=0, atol=1e-18)
+    assert np.abs(np.abs(out.delta) - 1).min() > 1e-4
+    w1, b1, w2, b2, _, _ = synth.split_params(p, D, H, A + dueling, hidden2=G)
+    z1 = rows["s"] @ w1 + b1
+    assert min(np.abs(z1).min(), np.abs(np.maximum(z1, 0) @ w2 + b2).min()) > 1e-4
+    h = 1e-6
+    for k in range(len(p)):
+        e = np.zeros_like(p); e[k] = h
+        fd = (oracle.loss_fixed_targets(cfg, p + e, rows["s"], rows["a"], out.y) -
+              oracle.loss_fixed_targets(cfg, p - e, rows["s"], rows["a"], out.y)) / (2 * h)
+        assert abs(fd - out.grads[k]) <= 2e-7 * max(1.0, abs(fd)), k
+
+
+def test_two_widths_dueling_streams_split_the_second_layer():
+    """The paper's shape in small: shared layer H, then a value stream and an advantage stream of
+    G/2 units each (Deep Q-Network Model).  Library matmuls stream by stream; mean_a Q = V."""
+    D, H, G, A, n = 6, 4, 10, 5, 30
+    p, rows = _two_width_problem(D, H, G, A, n, 8, True)
+    W1, b1, W2, b2, W3, b3 = synth.split_params(p, D, H, A + 1, hidden2=G)
+    h1 = np.maximum(rows["s"].astype(np.float64) @ W1 + b1, 0)
+    hv = np.maximum(h1 @ W2[:, :G // 2] + b2[:G // 2], 0)
+    ha = np.maximum(h1 @ W2[:, G // 2:] + b2[G // 2:], 0)
+    V = hv @ W3[:G // 2, 0] + b3[0]
+    Adv = ha @ W3[G // 2:, 1:] + b3[1:]
+    want = V[:, None] + Adv - Adv.mean(1, keepdims=True)
+    cfg = oracle.make_cfg(D, H, A, n, dueling=1, hidden2=G)
+    Q = oracle.mlp_forward(cfg, p, rows["s"])
+    assert np.allclose(Q, want, rtol=1e-13, atol=1e-13) and np.allclose(Q.mean(1), V, rtol=1e-13, atol=1e-13)
+    out = oracle.train_step(cfg, p, None, None, 0, rows["s"], rows["s_next"], rows["a"], rows["r"], rows["term"])
+    g3 = synth.split_params(out.grads, D, H, A + 1, hidden2=G)[4]
+    assert not g3[G // 2:, 0].any() and not g3[:G // 2, 1:].any()
+    assert g3[:G // 2, 0].any() and g3[G // 2:, 1:].any()
