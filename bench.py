@@ -433,7 +433,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10_000)
     ap.add_argument("--warmup", type=int, default=500)
-    ap.add_argument("--legs", default="p,psteady,pfull,phost,pmodel,inram,gather,append,copy,large,wide,cpu")
+    ap.add_argument("--legs", default="p,psteady,pfull,phost,pmodel,pnet,inram,gather,append,copy,large,wide,cpu")
     ap.add_argument("--gather-reps", type=int, default=1000)
     ap.add_argument("--wide-steps", type=int, default=2000)
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
@@ -480,15 +480,19 @@ def main():
             B, synth, args.steps, args.warmup, False, target_sync=10_000, dueling=True)
         out["paper_shaped_without_duplicates"] = leg_paper_shaped(B, synth, args.steps, args.warmup, False,
                                                                   distinct=True)
-        # the paper's own network: shared layer 128, value and advantage stream 512 each, dueling
-        # head, frozen target network synced every 10,000 updates (Deep Q-Network Model), fp32
-        out["paper_network_27_128_1024_dueling_target"] = leg_paper_shaped(
-            B, synth, args.steps, args.warmup, False, target_sync=10_000, dueling=True, widths=(128, 1024))
-        out["paper_network_27_128_1024_dueling_target"]["network"] = "27-128-(512+512)-(1+30), fp32"
         for k in ("paper_shaped_target_network", "paper_shaped_dueling", "paper_shaped_dueling_target_network",
-                  "paper_shaped_without_duplicates", "paper_network_27_128_1024_dueling_target"):
+                  "paper_shaped_without_duplicates"):
             log("[bench]   %-42s %8.0f steps/s, %d kernels/step" %
                 (k, out[k]["steps_per_s"], out[k]["kernels_per_step"]))
+    if "pnet" in legs:
+        # the paper's own network: shared layer 128, value and advantage stream 512 each, dueling
+        # head, frozen target network synced every 10,000 updates (Deep Q-Network Model), fp32
+        log("[bench] paper-shaped replay with the paper's own network 27-128-(512+512)-(1+30) ...")
+        k = "paper_network_27_128_1024_dueling_target"
+        out[k] = leg_paper_shaped(B, synth, args.steps, args.warmup, False, target_sync=10_000,
+                                  dueling=True, widths=(128, 1024))
+        out[k]["network"] = "27-128-(512+512)-(1+30), fp32, dueling head, target network"
+        log("[bench]   %.0f steps/s, %d kernels/step" % (out[k]["steps_per_s"], out[k]["kernels_per_step"]))
     if "inram" in legs:
         log("[bench] device-resident replay vs in-RAM replay with a per-step batch copy ...")
         out["device_vs_inram"] = leg_device_vs_inram(B, synth, min(args.steps, 4000), 200)

@@ -165,11 +165,15 @@ hipError_t launch_mm(hipStream_t st, const MmArgs& a, unsigned int M_total) {
 }
 
 // ----------------------------------------------------------------------------------------
-// TD target, loss and the gradient at the second hidden layer's pre-activation, one wavefront
+// TD target, loss and the gradient at the second hidden layer's pre-activation, one workgroup
 // per experience i:  y_i = r_i + gamma (1 - term_i) max_a Q[B + i][a],  delta_i = y_i - Q[i][a_i],
-// the loss term, the one non-zero of dL/dQ in row i, and
-//   dZ2[i][k] = dL/dQ[i][a_i] * W3[k][a_i] * 1[H2[i][k] > 0].
-// Thread 0 of block 0 also advances Adam's step count and its bias corrections.
+// the loss term, the one non-zero of dL/dQ in row i (every wavefront works these out for
+// itself: a few loads, no exchange), and
+//   dZ2[i][k] = dL/dQ[i][a_i] * W3[k][a_i] * 1[H2[i][k] > 0],
+// a few k per thread with all loads requested at once (a load that misses the local L2 takes
+// microseconds here, so a loop of dependent iterations would pay that once per iteration).
+// Thread 0 of block 0 also advances Adam's step count and its bias corrections 1 - beta^t, from
+// running products beta^t kept in double precision (no power function on the device).
 // ----------------------------------------------------------------------------------------
 struct MidTdArgs {
     unsigned int B, G, A, Ap;
@@ -188,21 +192,38 @@ struct MidTdArgs {
 };
 
 __global__ __launch_bounds__(256) void mid_td_kernel(MidTdArgs p) {
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        const unsigned long long t = p.ctr->adam_t + 1;
-        p.ctr->adam_t = t;
-        p.ctr->c1 = (float)(1.0 - pow((double)p.beta1, (double)t));
-        p.ctr->c2 = (float)(1.0 - pow((double)p.beta2, (double)t));
+    const unsigned int tid = threadIdx.x, lane = tid & 63u;
+    const unsigned int i = blockIdx.x;
+    // this thread's hidden units and their activations: requested before anything else
+    constexpr unsigned int KU = 4;
+    const float* h2 = p.H2 + (size_t)i * p.G;
+    float hv[KU];
+#pragma unroll
+    for (unsigned int u = 0; u < KU; ++u) {
+        const unsigned int k = tid + 256u * u;
+        hv[u] = k < p.G ? h2[k] : 0.f;
     }
-    const unsigned int lane = threadIdx.x & 63u;
-    const unsigned int i = blockIdx.x * 4u + (threadIdx.x >> 6);
-    if (i >= p.B) return;
+    if (i == 0 && tid == 0) {
+        const unsigned long long t = p.ctr->adam_t + 1;
+        const double pw1 = p.ctr->pw1 * (double)p.beta1, pw2 = p.ctr->pw2 * (double)p.beta2;
+        p.ctr->adam_t = t;
+        p.ctr->pw1 = pw1;
+        p.ctr->pw2 = pw2;
+        p.ctr->c1 = (float)(1.0 - pw1);
+        p.ctr->c2 = (float)(1.0 - pw2);
+    }
     const float* qn = p.Q + (size_t)(p.B + i) * p.Ap;
     float best = -INFINITY;
     for (unsigned int k = lane; k < p.A; k += 64) best = fmaxf(best, qn[k]);
     best = wave_max(best);
     unsigned int ai = (unsigned int)p.act[i];
     if (ai >= p.A) ai = p.A - 1;  // an out-of-range action must not turn into a wild address
+    float w3[KU];
+#pragma unroll
+    for (unsigned int u = 0; u < KU; ++u) {
+        const unsigned int k = tid + 256u * u;
+        w3[u] = k < p.G ? p.W3[(size_t)k * p.Ap + ai] : 0.f;
+    }
     const float q = p.Q[(size_t)i * p.Ap + ai];
     const float y = p.rew[i] + (p.term[i] ? 0.f : p.gamma * best);
     const float d = y - q;
@@ -215,15 +236,20 @@ __global__ __launch_bounds__(256) void mid_td_kernel(MidTdArgs p) {
         slope = d > 0.f ? 1.f : -1.f;
     }
     const float g = -slope / (float)p.B;
-    for (unsigned int k = lane; k < p.Ap; k += 64) p.dQ[(size_t)i * p.Ap + k] = (k == ai) ? g : 0.f;
-    if (lane == 0) {
+    for (unsigned int k = tid; k < p.Ap; k += 256) p.dQ[(size_t)i * p.Ap + k] = (k == ai) ? g : 0.f;
+    if (tid == 0) {
         p.y[i] = y;
         p.delta[i] = d;
         p.lossi[i] = li;
     }
-    const float* h2 = p.H2 + (size_t)i * p.G;
     float* dz = p.dZ2 + (size_t)i * p.G;
-    for (unsigned int k = lane; k < p.G; k += 64)
+#pragma unroll
+    for (unsigned int u = 0; u < KU; ++u) {
+        const unsigned int k = tid + 256u * u;
+        if (k < p.G) dz[k] = hv[u] > 0.f ? g * w3[u] : 0.f;
+    }
+    // (layers wider than 256 * KU units: the rest, one unit at a time)
+    for (unsigned int k = tid + 256u * KU; k < p.G; k += 256)
         dz[k] = h2[k] > 0.f ? g * p.W3[(size_t)k * p.Ap + ai] : 0.f;
 }
 
@@ -274,7 +300,7 @@ hipError_t enqueue_mid_step(trainer* t, hipStream_t st, unsigned int* count) {
         d.gamma = t->cfg.gamma; d.loss_kind = t->cfg.loss; d.beta1 = t->cfg.beta1; d.beta2 = t->cfg.beta2;
         d.y = t->y; d.delta = t->delta; d.lossi = t->lossi; d.dQ = t->dQ;
         d.W3 = w + t->oW3; d.H2 = H2; d.dZ2 = dZ2; d.ctr = t->ctr;
-        hipLaunchKernelGGL(mid_td_kernel, dim3((B + 3) / 4), dim3(256), 0, st, d);
+        hipLaunchKernelGGL(mid_td_kernel, dim3(B), dim3(256), 0, st, d);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         ++n;

@@ -119,10 +119,13 @@ __global__ __launch_bounds__(kThreads) void td_loss_kernel(
     float* __restrict__ y_out, float* __restrict__ delta_out, float* __restrict__ lossi,
     float* __restrict__ dQ, TrainCounters* __restrict__ ctr, float beta1, float beta2) {
     if (blockIdx.x == 0 && threadIdx.x == 0) {
-        const unsigned long long t = ctr->adam_t + 1;
-        ctr->adam_t = t;
-        ctr->c1 = (float)(1.0 - pow((double)beta1, (double)t));
-        ctr->c2 = (float)(1.0 - pow((double)beta2, (double)t));
+        // (running products beta^t in double precision: no power function on the device)
+        const double pw1 = ctr->pw1 * (double)beta1, pw2 = ctr->pw2 * (double)beta2;
+        ctr->adam_t = ctr->adam_t + 1;
+        ctr->pw1 = pw1;
+        ctr->pw2 = pw2;
+        ctr->c1 = (float)(1.0 - pw1);
+        ctr->c2 = (float)(1.0 - pw2);
     }
     const unsigned int lane = threadIdx.x & 63u;
     const unsigned int i = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
@@ -1235,6 +1238,8 @@ rp_status train_set_state(trainer_t* t, const float* params, const float* m, con
     RP_CHECK_HIP(hipMemcpy(&c, t->ctr, sizeof(c), hipMemcpyDeviceToHost));
     c.adam_t = adam_t;
     c.step = step;
+    c.pw1 = std::pow((double)t->cfg.beta1, (double)adam_t);
+    c.pw2 = std::pow((double)t->cfg.beta2, (double)adam_t);
     RP_CHECK_HIP(hipMemcpy(t->ctr, &c, sizeof(c), hipMemcpyHostToDevice));
     t->host_step = step;
     t->host_adam_t = adam_t;

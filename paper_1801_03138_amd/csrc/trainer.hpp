@@ -38,7 +38,9 @@ struct TrainCounters {
     unsigned long long adam_t;  // Adam steps taken
     float c1, c2;               // Adam bias corrections 1 - beta^t of the current step
     float loss;                 // mean loss of the last step
-    unsigned int pad_[9];
+    unsigned int pad0_;
+    double pw1, pw2;            // beta1^t, beta2^t for t = adam_t (kept by the steps that advance t on the device)
+    unsigned int pad_[4];
 };
 static_assert(sizeof(TrainCounters) == 64, "one line");
 

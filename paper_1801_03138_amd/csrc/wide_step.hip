@@ -527,10 +527,13 @@ __global__ __launch_bounds__(256) void td_dz_kernel(TdArgs p) {
     const unsigned int tid = threadIdx.x;
     const unsigned int i0 = blockIdx.x * 64u, k0 = blockIdx.y * 64u;
     if (blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) {
-        const unsigned long long t = p.ctr->adam_t + 1;
-        p.ctr->adam_t = t;
-        p.ctr->c1 = (float)(1.0 - pow((double)p.beta1, (double)t));
-        p.ctr->c2 = (float)(1.0 - pow((double)p.beta2, (double)t));
+        // (running products beta^t in double precision: no power function on the device)
+        const double pw1 = p.ctr->pw1 * (double)p.beta1, pw2 = p.ctr->pw2 * (double)p.beta2;
+        p.ctr->adam_t = p.ctr->adam_t + 1;
+        p.ctr->pw1 = pw1;
+        p.ctr->pw2 = pw2;
+        p.ctr->c1 = (float)(1.0 - pw1);
+        p.ctr->c2 = (float)(1.0 - pw2);
     }
     {
         const unsigned int r = tid >> 2, part = tid & 3u, i = i0 + r;
