@@ -14,6 +14,8 @@
 //
 // Paper: Integration with Reinforcement Learning Algorithm (train step with no host inputs),
 // Deep Q-Network Model (update equation).
+#include <algorithm>
+#include <type_traits>
 #include <vector>
 
 #include "replay_kernels.hpp"
@@ -182,11 +184,12 @@ struct GemmArgs {
     unsigned int ldb;
     unsigned int M, N, K;          // K: columns one workgroup contracts over
     unsigned int tiles_m, tiles_n, splits;
+    unsigned int band;             // tiles are numbered band by band: `band` tile columns at a time, rows fastest after that
 };
 
-template <int BM, int BN, int BK, int WGM, int WGN>
+template <int BM, int BN, int BK, int WGM, int WGN, int NSTAGE = 2>
 constexpr size_t gemm_lds_bytes() {
-    const size_t slices = 2 * (size_t)(BM + BN) * BK * 2;
+    const size_t slices = NSTAGE * (size_t)(BM + BN) * BK * 2;
     // staged epilogues park every wavefront's bf16 tile, rows padded by 16 bytes
     const size_t parked = 4 * (size_t)(BM / WGM) * ((BN / WGN) * 2 + 16);
     return slices > parked ? slices : parked;
@@ -195,9 +198,10 @@ constexpr size_t gemm_lds_bytes() {
 #define RP_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 #define RP_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 
-template <int BM, int BN, int BK, int WGM, int WGN, class Epi>
+template <int BM, int BN, int BK, int WGM, int WGN, int NSTAGE = 2, class Epi>
 __device__ __forceinline__ void gemm_nt_block(const GemmArgs& p, const Epi& epi, unsigned int block) {
     static_assert(WGM * WGN == 4, "four wavefronts");
+    static_assert(NSTAGE >= 2 && NSTAGE <= 4, "slices in flight");
     static_assert(BK == 32 || BK == 64, "slice width");
     constexpr int RB = BK * 2;                             // bytes per LDS row
     constexpr int CPR = RB / 16;                           // 16-byte pieces per row
@@ -212,13 +216,17 @@ __device__ __forceinline__ void gemm_nt_block(const GemmArgs& p, const Epi& epi,
     unsigned char* smem = reinterpret_cast<unsigned char*>(gemm_smem);
 
     // Workgroups are dealt to the eight XCDs round-robin; each XCD gets a contiguous range of
-    // tiles (N fastest), so the workgroups that share an L2 also share operand panels.
+    // tile numbers, and tiles are numbered so that such a range is a compact block of the output
+    // (bands of `band` tile columns, within a band row by row): the workgroups that share an L2
+    // then share as few operand panels as possible, and each panel is fetched by few XCDs.
     const unsigned int per_split = p.tiles_m * p.tiles_n, n_tiles = per_split * p.splits;
     const unsigned int per_xcd = (n_tiles + 7u) / 8u;
     const unsigned int tile_s = (block & 7u) * per_xcd + (block >> 3);
     if (tile_s >= n_tiles) return;
     const unsigned int split = tile_s / per_split, tile = tile_s % per_split;
-    const unsigned int m0 = (tile / p.tiles_n) * BM, n0 = (tile % p.tiles_n) * BN;
+    const unsigned int band_tiles = p.tiles_m * p.band, band_id = tile / band_tiles, in_band = tile % band_tiles;
+    const unsigned int width = min(p.band, p.tiles_n - band_id * p.band);
+    const unsigned int m0 = (in_band / width) * BM, n0 = (band_id * p.band + in_band % width) * BN;
     const unsigned int k_base = split * p.K;
 
     const unsigned int tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
@@ -230,32 +238,47 @@ __device__ __forceinline__ void gemm_nt_block(const GemmArgs& p, const Epi& epi,
 
     // loader: wavefront w moves row groups w*GA.. of A and w*GB.. of B; a lane's piece lands at
     // LDS position `lane` of the group, so the lane fetches the piece that belongs there
+    // A request's address is a wavefront-uniform base (the operand, advanced by the slice's
+    // column: scalar registers) plus a per-lane byte offset that never changes (one 32-bit
+    // register per request, at most a tile's rows away from row 0 of the operand, which must
+    // therefore stay below 4 GiB), and its LDS destination is uniform as well: issuing a request
+    // then costs two scalar instructions and the load itself, no vector arithmetic.
     const unsigned int lr = lane / CPR, lc = lane % CPR;
-    const bf16_bits* a_ptr[GA];
-    const bf16_bits* b_ptr[GB];
+    const unsigned int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    unsigned int a_off[GA], b_off[GB];
 #pragma unroll
     for (int u = 0; u < GA; ++u) {
         const unsigned int r = (wave * GA + u) * RPI + lr;
         unsigned int gm = m0 + r;
         gm = gm < p.M ? gm : p.M - 1;
-        a_ptr[u] = p.A + (size_t)gm * p.lda + k_base + (lc ^ swz(r)) * 8u;
+        a_off[u] = (gm * p.lda + (lc ^ swz(r)) * 8u) * 2u;
     }
 #pragma unroll
     for (int u = 0; u < GB; ++u) {
         const unsigned int r = (wave * GB + u) * RPI + lr;
         unsigned int gn = n0 + r;
         gn = gn < p.N ? gn : p.N - 1;
-        b_ptr[u] = (m0 >= p.m_split ? p.Bt_hi : p.Bt) + (size_t)gn * p.ldb + k_base + (lc ^ swz(r)) * 8u;
+        b_off[u] = (gn * p.ldb + (lc ^ swz(r)) * 8u) * 2u;
     }
+    typedef const __attribute__((address_space(1))) char* gchar;
+    const gchar a_base = (gchar)reinterpret_cast<const char*>(p.A + k_base);
+    const gchar b_base = (gchar)reinterpret_cast<const char*>((m0 >= p.m_split ? p.Bt_hi : p.Bt) + k_base);
+    // request u (0 .. GA + GB - 1) of a slice: one wavefront-wide 16-byte-per-lane load into LDS
+    constexpr int L = GA + GB;                              // loads per wavefront and slice
+    auto fetch_one = [&](int u, unsigned int buf, unsigned int k0) {
+        if (u < GA) {
+            unsigned char* sa = smem + buf * STAGE + (wave_u * GA) * 1024u;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a_base + (size_t)k0 * 2u + a_off[u < GA ? u : 0]),
+                                             RP_LDS_PTR(sa + u * 1024), 16, 0, 0);
+        } else {
+            unsigned char* sb = smem + buf * STAGE + A_BYTES + (wave_u * GB) * 1024u;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(b_base + (size_t)k0 * 2u + b_off[u >= GA ? u - GA : 0]),
+                                             RP_LDS_PTR(sb + (u - GA) * 1024), 16, 0, 0);
+        }
+    };
     auto fetch = [&](unsigned int buf, unsigned int k0) {
-        unsigned char* sa = smem + buf * STAGE + (wave * GA) * 1024u;
-        unsigned char* sb = smem + buf * STAGE + A_BYTES + (wave * GB) * 1024u;
 #pragma unroll
-        for (int u = 0; u < GA; ++u)
-            __builtin_amdgcn_global_load_lds(RP_GLOBAL_PTR(a_ptr[u] + k0), RP_LDS_PTR(sa + u * 1024), 16, 0, 0);
-#pragma unroll
-        for (int u = 0; u < GB; ++u)
-            __builtin_amdgcn_global_load_lds(RP_GLOBAL_PTR(b_ptr[u] + k0), RP_LDS_PTR(sb + u * 1024), 16, 0, 0);
+        for (int u = 0; u < L; ++u) fetch_one(u, buf, k0);
     };
 
     f32x16 acc[TM][TN];
@@ -269,39 +292,80 @@ __device__ __forceinline__ void gemm_nt_block(const GemmArgs& p, const Epi& epi,
     const unsigned int a_row = (wm * TM * 32u + (lane & 31u)) * RB;
     const unsigned int b_row = (wn * TN * 32u + (lane & 31u)) * RB;
     const unsigned int sw = swz(lane & 31u), half = lane >> 5;
-    auto multiply = [&](unsigned int buf) {
+    // One slice's multiply.  A wavefront issues in order, and it is alone on its SIMD when the
+    // workgroup has the compute unit to itself, so everything that has to happen during a
+    // slice is interleaved with its MFMAs by hand: the LDS reads of step s + 1 are issued before
+    // the MFMAs of step s (two sets of fragment registers), and the global -> LDS requests of a
+    // later slice (FETCH) are spread out between the MFMAs, one at a time, instead of being
+    // issued in a burst during which no MFMA could start.  The scheduling barriers keep the
+    // compiler from regrouping them.
+    auto multiply = [&](unsigned int buf, auto fetch_flag, unsigned int fbuf, unsigned int fk0) {
+        constexpr bool FETCH = decltype(fetch_flag)::value;
         const unsigned char* as = smem + buf * STAGE + a_row;
         const unsigned char* bs = smem + buf * STAGE + A_BYTES + b_row;
-#pragma unroll
-        for (int s = 0; s < BK / 16; ++s) {
+        constexpr int STEPS = BK / 16, NM = STEPS * TM * TN;
+        u32x4 a[2][TM], b[2][TN];
+        auto request = [&](int s, int set) {
             const unsigned int ko = ((2u * s + half) ^ sw) * 16u;   // where this 16-deep step's piece sits
-            bf16x8 a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[set][i] = *reinterpret_cast<const u32x4*>(as + i * 32 * RB + ko);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[set][j] = *reinterpret_cast<const u32x4*>(bs + j * 32 * RB + ko);
+        };
+        request(0, 0);
+#pragma unroll
+        for (int s = 0; s < STEPS; ++s) {
+            if (s + 1 < STEPS) request(s + 1, (s + 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
-                a[i] = as_bf16x8(*reinterpret_cast<const u32x4*>(as + i * 32 * RB + ko));
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
-                b[j] = as_bf16x8(*reinterpret_cast<const u32x4*>(bs + j * 32 * RB + ko));
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
+                for (int j = 0; j < TN; ++j) {
                     acc[i][j] = Epi::kStaged
-                                    ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0)
-                                    : __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+                                    ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(b[s & 1][j]), as_bf16x8(a[s & 1][i]), acc[i][j], 0, 0, 0)
+                                    : __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a[s & 1][i]), as_bf16x8(b[s & 1][j]), acc[i][j], 0, 0, 0);
+                    if (FETCH) {
+                        const int m = (s * TM + i) * TN + j;          // this MFMA's number within the slice
+#pragma unroll
+                        for (int u = m * L / NM; u < (m + 1) * L / NM; ++u) fetch_one(u, fbuf, fk0);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
-    // Slice kt is awaited (every wavefront waits for its own loads, the barrier covers the
-    // others'); after the barrier nobody reads the other buffer any more, so slice kt+1 is
-    // requested into it and travels while slice kt is multiplied.
+    // NSTAGE slices deep: slice kt is awaited (every wavefront waits for its own loads, the barrier
+    // covers the others'); after the barrier nobody reads the buffer of slice kt - 1 any more, so
+    // slice kt + NSTAGE - 1 is requested into it and travels while slices kt .. are multiplied.
+    // With two workgroups on a compute unit two slices are enough (the other workgroup computes
+    // while this one waits); a workgroup that has a compute unit to itself needs its requests
+    // further ahead than one slice's multiply time.
+    auto wait_vm = [](auto n) {                             // s_waitcnt vmcnt(n), nothing else
+        constexpr unsigned int N = decltype(n)::value;
+        __builtin_amdgcn_s_waitcnt((N & 0xFu) | ((N >> 4) << 14) | 0x0F70u);
+    };
     const unsigned int nk = p.K / BK;
-    fetch(0, 0);
-    for (unsigned int kt = 0; kt < nk; ++kt) {
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's loads have landed in LDS
+#pragma unroll
+    for (unsigned int s0 = 0; s0 + 1 < (unsigned int)NSTAGE; ++s0)
+        if (s0 < nk) fetch(s0, s0 * BK);
+    // steady state: slices kt + 1 .. kt + NSTAGE - 2 may still be in flight while slice kt is awaited
+    // (two loops, so that each has one straight-line body: with both kinds of multiply in one loop
+    // the compiler moved all accumulators between register files on every iteration)
+    unsigned int kt = 0;
+    for (; kt + NSTAGE - 1 < nk; ++kt) {
+        wait_vm(std::integral_constant<unsigned int, (NSTAGE - 2) * L>{});
         __syncthreads();
-        if (kt + 1 < nk) fetch((kt + 1) & 1u, (kt + 1) * BK);
-        multiply(kt & 1u);
+        multiply(kt % NSTAGE, std::true_type{}, (kt + NSTAGE - 1) % NSTAGE, (kt + NSTAGE - 1) * BK);
+    }
+    // the last NSTAGE - 1 slices: nothing left to request
+    for (; kt < nk; ++kt) {
+        const unsigned int later = nk - 1u - kt;
+        if (NSTAGE >= 4 && later == 2u) wait_vm(std::integral_constant<unsigned int, 2 * L>{});
+        else if (NSTAGE >= 3 && later == 1u) wait_vm(std::integral_constant<unsigned int, L>{});
+        else wait_vm(std::integral_constant<unsigned int, 0>{});
+        __syncthreads();
+        multiply(kt % NSTAGE, std::false_type{}, 0u, 0u);
     }
 
     if constexpr (Epi::kStaged) {
@@ -311,7 +375,7 @@ __device__ __forceinline__ void gemm_nt_block(const GemmArgs& p, const Epi& epi,
         constexpr int TSTRIDE = TN * 64 + 16;                // bytes per parked row
         constexpr int CR = TN * 4;                           // 16-byte pieces per row
         constexpr int RP = 64 / CR;                          // rows per pass of the wavefront
-        static_assert(4 * TM * 32 * TSTRIDE <= (int)gemm_lds_bytes<BM, BN, BK, WGM, WGN>(), "parked tiles fit");
+        static_assert(4 * TM * 32 * TSTRIDE <= (int)gemm_lds_bytes<BM, BN, BK, WGM, WGN, NSTAGE>(), "parked tiles fit");
         __syncthreads();
         unsigned char* park = smem + wave * (TM * 32 * TSTRIDE);
         const unsigned int wm0 = m0 + wm * TM * 32u, wn0 = n0 + wn * TN * 32u;
@@ -347,9 +411,9 @@ __device__ __forceinline__ void gemm_nt_block(const GemmArgs& p, const Epi& epi,
     }
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, class Epi>
+template <int BM, int BN, int BK, int WGM, int WGN, int NSTAGE, class Epi>
 __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(GemmArgs p, Epi epi) {
-    gemm_nt_block<BM, BN, BK, WGM, WGN>(p, epi, blockIdx.x);
+    gemm_nt_block<BM, BN, BK, WGM, WGN, NSTAGE>(p, epi, blockIdx.x);
 }
 
 // The three weight-gradient products of a step in one launch (each writes K-split partials):
@@ -375,12 +439,12 @@ __global__ __launch_bounds__(kGemmThreads) void grad_products_kernel(GemmArgs p2
 
 // The dynamic LDS size of each kernel (up to 64 KB) is announced per kernel before the first
 // launch (done at trainer creation, outside any stream capture).
-template <int BM, int BN, int BK, int WGM, int WGN, class Epi>
+template <int BM, int BN, int BK, int WGM, int WGN, class Epi, int NSTAGE = 2>
 hipError_t configure_gemm() {
-    auto kernel = gemm_nt_kernel<BM, BN, BK, WGM, WGN, Epi>;
+    auto kernel = gemm_nt_kernel<BM, BN, BK, WGM, WGN, NSTAGE, Epi>;
     return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                hipFuncAttributeMaxDynamicSharedMemorySize,
-                               (int)gemm_lds_bytes<BM, BN, BK, WGM, WGN>());
+                               (int)gemm_lds_bytes<BM, BN, BK, WGM, WGN, NSTAGE>());
 }
 
 template <bool NARROW3, bool NARROW1>
@@ -408,10 +472,33 @@ bool gemm_args(const bf16_bits* A, unsigned int lda, const bf16_bits* Bt, unsign
     a->splits = splits;
     const unsigned int n_tiles = a->tiles_m * a->tiles_n * splits;
     *blocks = 8u * ((n_tiles + 7u) / 8u);
+    // band width: the one for which an XCD's share of the tiles (a block of about per_xcd / band
+    // tile rows by `band` tile columns) touches the fewest operand rows
+    const unsigned int per_xcd = std::min((n_tiles + 7u) / 8u, a->tiles_m * a->tiles_n);
+    unsigned int best = a->tiles_n;
+    size_t best_cost = ~(size_t)0;
+    // (first among the widths whose bands line up with the XCDs' ranges, so that a range does not
+    // straddle two bands; any width if there is none)
+    for (int aligned = 1; aligned >= 0 && best_cost == ~(size_t)0; --aligned)
+        for (unsigned int w = 1; w <= a->tiles_n; ++w) {
+            const unsigned int band_tiles = a->tiles_m * w;
+            if (aligned && band_tiles % per_xcd != 0 && per_xcd % band_tiles != 0) continue;
+            // a range of per_xcd tile numbers covers whole bands when it is longer than one
+            const unsigned int rows = per_xcd >= band_tiles ? a->tiles_m : std::min(a->tiles_m, (per_xcd + w - 1) / w);
+            const unsigned int cols = per_xcd >= band_tiles
+                                          ? std::min(a->tiles_n, w * ((per_xcd + band_tiles - 1) / band_tiles))
+                                          : w;
+            const size_t cost = (size_t)rows * BM + (size_t)cols * BN;
+            if (cost < best_cost) {
+                best_cost = cost;
+                best = w;
+            }
+        }
+    a->band = best;
     return true;
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, class Epi>
+template <int BM, int BN, int BK, int WGM, int WGN, int NSTAGE = 2, class Epi>
 hipError_t launch_gemm(hipStream_t st, const bf16_bits* A, unsigned int lda, const bf16_bits* Bt,
                        unsigned int ldb, unsigned int M, unsigned int N, unsigned int K,
                        const Epi& epi, unsigned int splits = 1, const bf16_bits* Bt_hi = nullptr,
@@ -420,8 +507,8 @@ hipError_t launch_gemm(hipStream_t st, const bf16_bits* A, unsigned int lda, con
     unsigned int blocks;
     if (!gemm_args<BM, BN, BK>(A, lda, Bt, ldb, M, N, K, splits, Bt_hi, m_split, &a, &blocks))
         return hipErrorInvalidValue;
-    constexpr size_t lds = gemm_lds_bytes<BM, BN, BK, WGM, WGN>();
-    hipLaunchKernelGGL((gemm_nt_kernel<BM, BN, BK, WGM, WGN, Epi>), dim3(blocks),
+    constexpr size_t lds = gemm_lds_bytes<BM, BN, BK, WGM, WGN, NSTAGE>();
+    hipLaunchKernelGGL((gemm_nt_kernel<BM, BN, BK, WGM, WGN, NSTAGE, Epi>), dim3(blocks),
                        dim3(kGemmThreads), lds, st, a, epi);
     return hipGetLastError();
 }
