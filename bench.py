@@ -32,14 +32,17 @@ P_CFG = dict(capacity=1_000_000, D=27, A=30, B=128, H=256, burn_in=50_000, p_ter
 W_CFG = dict(capacity=4_000_000, D=27, A=30, B=4096, H=1024, p_term=0.005, lr=1e-4, appends=64)
 L_CFG = dict(capacity=200_000, D=84 * 84 * 4, p_term=0.001)
 GATHER_BATCHES = [32, 128, 512, 2048, 8192, 65536]
-# HBM bytes per launch of sample_gather_pair_kernel<4, 1, false> at batch 65,536 from rocprofv3 PMC runs
-# (FETCH_SIZE 8,182.8 KiB x 2.000 + WRITE_SIZE 14,720.0 KiB x 1.000, the factors being what the
+# HBM bytes per launch of sample_gather_pair_kernel<4, 1, 0> at batch 65,536 from rocprofv3 PMC runs
+# (FETCH_SIZE 8,180.7 KiB x 2.000 + WRITE_SIZE 14,720.0 KiB x 1.000, the factors being what the
 # same counters read for the 256 MiB plain copy of the copy_calibration leg); the runs and the
 # table are in profiles/gather_kernels_hbm_traffic_pmc.txt.  Set to None when that kernel changes.
-GATHER_65536_HBM_BYTES = (8182.8 * 2.000 + 14720.0 * 1.000) * 1024
+GATHER_65536_HBM_BYTES = (8180.7 * 2.000 + 14720.0 * 1.000) * 1024
+GATHER_8M_65536_HBM_BYTES = (8209.9 * 2.000 + 14720.0 * 1.000) * 1024
 GATHER_KERNEL = "sample_gather_pair_kernel<4, 1, 0>"
-# the same for sample_gather_chain_kernel<1, 0> at batch 256 (None: not taken for this kernel build)
-LARGE_256_HBM_BYTES = None
+# the same for sample_gather_chain_kernel<1, 0> at batch 256
+LARGE_256_HBM_BYTES = (7157.6 * 2.000 + 56461.2 * 1.000) * 1024
+# and for append_pair_bulk_kernel<unsigned int> at 65,536 rows (profiles/append_bulk_kernel_hbm_traffic_pmc.txt)
+APPEND_65536_HBM_BYTES = (7314.5 * 2.000 + 16384.0 * 1.000) * 1024
 
 
 def log(*a):
@@ -523,7 +526,7 @@ def main():
         rooflines.append({"kernel": GATHER_KERNEL, "workload": "gather, batch 65536, capacity 8,000,000 "
                           "(2 GB ring, eight times the last-level cache), 27 fp32 per state",
                           "bound": "hbm", "achieved": big["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                          "frac": big["GBps"] / HBM_PEAK_GBS, "traffic": None,
+                          "frac": big["GBps"] / HBM_PEAK_GBS, "traffic": GATHER_8M_65536_HBM_BYTES,
                           "alg_bytes_per_launch": big["alg_bytes"], "us_per_launch": big["us_per_call"]})
     if "gather" in legs:
         out["gather_sweep_without_duplicates"] = leg_gather_sweep(B, synth, max(100, args.gather_reps // 4),
@@ -539,6 +542,13 @@ def main():
                 "%9.4f us/exp" % (g["update_size"], g["device_src_us_per_call"],
                                   g["device_src_us_per_experience"], g["device_src_GBps"],
                                   g["host_src_us_per_call"], g["host_src_us_per_experience"]))
+        g = out["append_sweep"][-1]
+        rooflines.append({"kernel": "append_pair_bulk_kernel<unsigned int>", "workload": "append %d experiences "
+                          "from device arrays into the 1M-row ring, 27 fp32 per state" % g["update_size"],
+                          "bound": "hbm", "achieved": g["device_src_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                          "frac": g["device_src_GBps"] / HBM_PEAK_GBS, "traffic": APPEND_65536_HBM_BYTES,
+                          "alg_bytes_per_launch": g["update_size"] * 2 * (2 * P_CFG["D"] + 3) * 4,
+                          "us_per_launch": g["device_src_us_per_call"]})
     if "copy" in legs:
         log("[bench] plain device-to-device copy, 256 MiB ...")
         out["copy_calibration"] = leg_copy_calibration(20)
