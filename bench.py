@@ -43,6 +43,8 @@ GATHER_KERNEL = "sample_gather_pair_kernel<4, 1, 0>"
 LARGE_256_HBM_BYTES = (7157.6 * 2.000 + 56461.2 * 1.000) * 1024
 # and for append_pair_bulk_kernel<unsigned int> at 65,536 rows (profiles/append_bulk_kernel_hbm_traffic_pmc.txt)
 APPEND_65536_HBM_BYTES = (7314.5 * 2.000 + 16384.0 * 1.000) * 1024
+# and summed over the eight kernels of one wide step (profiles/wide_step_kernels_hbm_traffic_pmc.txt)
+WIDE_STEP_HBM_BYTES = (90907.4 * 2.000 + 120678.2 * 1.000) * 1024
 
 
 def log(*a):
@@ -584,7 +586,7 @@ def main():
                           "workload": "wide fused step: batch 4096, 27-1024-1024-30, bf16 operands, fp32 "
                                       "accumulation, Adam, 64 appends per step", "bound": "mfma",
                           "achieved": w["TFLOPs"], "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                          "frac": w["frac_mfma"], "traffic": None, "alg_flops_per_step": w["alg_flops"],
+                          "frac": w["frac_mfma"], "traffic": WIDE_STEP_HBM_BYTES, "alg_flops_per_step": w["alg_flops"],
                           "us_per_step": 1e3 * w["ms_per_step"]})
     cpu = None
     if "cpu" in legs:
