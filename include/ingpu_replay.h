@@ -260,7 +260,11 @@ rp_status train_steps(trainer_t* tr, uint64_t count, const void* s, const void* 
 rp_status train_step_batch(trainer_t* tr, const void* s, const void* s_next, const int32_t* a,
                            const float* r, const uint8_t* term, void* hip_stream);
 
-/* Test / inspection calls; host destinations, any may be NULL; all synchronise. */
+/* Test / inspection calls; host destinations, any may be NULL; all synchronise.
+ * train_get_opt_state and train_get_last return RP_ESTATE (outputs filled all the same) if a
+ * train step with a target network has run whose workgroups did not receive the target
+ * network's values from their partner workgroups within the kernel's time limit (the step then
+ * used zeros): the trainer's weights are not to be trusted from that step on. */
 rp_status train_get_params(trainer_t* tr, float* params);             /* fp32 master weights */
 rp_status train_get_grads(trainer_t* tr, float* grads);               /* of the last step    */
 rp_status train_get_opt_state(trainer_t* tr, float* m, float* v, uint64_t* t, uint64_t* step);

@@ -34,6 +34,14 @@ void set_error(const char* fmt, ...);
         }                               \
     } while (0)
 
+#define RP_REQUIRE_STATE(cond, ...)     \
+    do {                                \
+        if (!(cond)) {                  \
+            rp::set_error(__VA_ARGS__); \
+            return RP_ESTATE;           \
+        }                               \
+    } while (0)
+
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // Device-resident replay state.  Kernels read and advance it, so that a

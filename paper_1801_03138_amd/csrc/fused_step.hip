@@ -6,7 +6,8 @@
 // backward pass down to the pre-activation gradients.  Kernel 1 does all of that for two or four
 // experiences per workgroup, keeping activations in LDS and streaming the weights through
 // 4x4x1 fp32 MFMA (four rows per instruction, so a four-row tile is not padded).  It also
-// appends the step's new experiences.  Only the weight gradients reduce over the batch:
+// appends the step's new experiences.  A frozen target network gets workgroups of its own in
+// the same launch, which hand max_a Q_target(s', a) over to the workgroups that hold s.  Only the weight gradients reduce over the batch:
 // kernel 2 forms them tile by tile and applies the optimizer to each tile as soon as it is
 // complete, so gradients never make a round trip through HBM before the update.
 //
@@ -26,6 +27,8 @@ constexpr unsigned int kSmallBatch = 512;  // ... and 2 for batches up to this s
 constexpr unsigned int kChunk = 256;       // output columns the workgroup covers per pass
 constexpr size_t kRowLdsMax = 160 * 1024;  // dynamic LDS the row kernel may ask for (all of a CU's)
 constexpr unsigned int kPadK = 4;          // LDS row padding (floats) against bank conflicts
+constexpr long long kHandoffTicks = 5000000;   // longest wait for the other workgroup of a pair: 50 ms
+                                               // of the 100 MHz wall clock
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
@@ -109,9 +112,8 @@ __device__ __forceinline__ void load_cols(float (&wr)[NR], const float* __restri
     }
 }
 
-// The same for the wide split: wr[u] = W[kbeg + u][col .. col+3], col a multiple of 4, for
-// u = U0 .. U1-1 (a lane's share can be requested in parts).
-template <int NR, int U0 = 0, int U1 = NR>
+// The same for the wide split: wr[u] = W[kbeg + u][col .. col+3], col a multiple of 4.
+template <int NR>
 __device__ __forceinline__ void load_cols4(f32x4 (&wr)[NR], const float* __restrict__ W,
                                            unsigned int N, unsigned int col, unsigned int kbeg,
                                            unsigned int kcount) {
@@ -120,7 +122,7 @@ __device__ __forceinline__ void load_cols4(f32x4 (&wr)[NR], const float* __restr
     const unsigned int cb = (col + 3u < N ? col : N - 4u) * 4u;
     const gbytes base = (gbytes)reinterpret_cast<const char*>(W) + (size_t)kb * N * 4u;
 #pragma unroll
-    for (int u = U0; u < U1; ++u) {
+    for (int u = 0; u < NR; ++u) {
         const unsigned int uu = (unsigned int)u < kc ? (unsigned int)u : kc - 1u;
         gbytes rb = base + (size_t)uu * N * 4u;
         asm volatile("" : "+s"(rb));
@@ -150,47 +152,6 @@ __device__ __forceinline__ void mma_cols(f32x4 (&acc)[MG], const float* act, uns
     }
 }
 
-// The same product, and as soon as a group of four weight registers has been consumed it is
-// refilled from the next matrix (Wn, [.. x Nn], rows kbeg_n..): the loads of the next layer's
-// weights overlap this layer's MFMAs instead of queueing up behind them.
-template <int MG, int NR>
-__device__ __forceinline__ void mma_cols_reload(f32x4 (&acc)[MG], const float* act,
-                                                unsigned int ldk, unsigned int kbeg,
-                                                unsigned int kcount, float (&wr)[NR],
-                                                const float* __restrict__ Wn, unsigned int Nn,
-                                                unsigned int col_n, unsigned int kbeg_n,
-                                                unsigned int kcount_n) {
-    const float* ap = act + (threadIdx.x & 3u) * ldk + kbeg;
-    // (unconditional loads from a scalar row address, as in load_cols)
-    const unsigned int kbn = __builtin_amdgcn_readfirstlane(kbeg_n);
-    const unsigned int kcn = __builtin_amdgcn_readfirstlane(kcount_n);
-    const unsigned int cbn = (col_n < Nn ? col_n : Nn - 1u) * 4u;
-    const gbytes base_n = (gbytes)reinterpret_cast<const char*>(Wn) + (size_t)kbn * Nn * 4u;
-#pragma unroll
-    for (int mg = 0; mg < MG; ++mg) acc[mg] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int u4 = 0; u4 < NR; u4 += 4) {
-        if ((unsigned int)u4 < kcount) {
-#pragma unroll
-            for (int mg = 0; mg < MG; ++mg) {
-                const f32x4 a = *reinterpret_cast<const f32x4*>(ap + (size_t)mg * 4 * ldk + u4);
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    acc[mg] = __builtin_amdgcn_mfma_f32_4x4x1f32(a[u], wr[u4 + u], acc[mg], 0, 0, 0);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const unsigned int uu = (unsigned int)(u4 + u) < kcn ? (unsigned int)(u4 + u) : kcn - 1u;
-            gbytes rb = base_n + (size_t)uu * Nn * 4u;
-            asm volatile("" : "+s"(rb));
-            wr[u4 + u] = *(const __attribute__((address_space(1))) float*)(rb + cbn);
-        }
-    }
-}
-
-// Wide split: acc[mg][j][v] += sum_{u < kcount} act[mg*4 + v][kbeg + u] * wr[u][j], j = 0..3.  The activations are read VEC (2 or 4) consecutive k at a time; kcount is a
-// multiple of VEC.
 template <int VEC> struct ActVec;
 template <> struct ActVec<2> { typedef float type __attribute__((ext_vector_type(2))); };
 template <> struct ActVec<4> { typedef f32x4 type; };
@@ -218,50 +179,6 @@ __device__ __forceinline__ void mma_cols4(f32x4 (&acc)[MG][4], const float* act,
                     for (int j = 0; j < 4; ++j)
                         acc[mg][j] = __builtin_amdgcn_mfma_f32_4x4x1f32(a[u], wr[u0 + u][j], acc[mg][j], 0, 0, 0);
             }
-        }
-    }
-}
-
-// ... refilling each group of VEC weight registers from the next matrix (Wn, [.. x Nn], rows
-// kbeg_n..) as soon as it has been consumed: the loads of the next layer's weights overlap this
-// layer's MFMAs instead of queueing up behind them.
-template <int MG, int NR, int VEC>
-__device__ __forceinline__ void mma_cols4_reload(f32x4 (&acc)[MG][4], const float* act,
-                                                 unsigned int ldk, unsigned int kbeg,
-                                                 unsigned int kcount, f32x4 (&wr)[NR],
-                                                 const float* __restrict__ Wn, unsigned int Nn,
-                                                 unsigned int col_n, unsigned int kbeg_n,
-                                                 unsigned int kcount_n) {
-    // MG groups of four activation rows (rows mg*4 .. mg*4+3 of act) share the weights
-    typedef typename ActVec<VEC>::type avec;
-    const float* ap = act + (threadIdx.x & 3u) * ldk + kbeg;
-    const unsigned int kbn = __builtin_amdgcn_readfirstlane(kbeg_n);
-    const unsigned int kcn = __builtin_amdgcn_readfirstlane(kcount_n);
-    const unsigned int cbn = (col_n + 3u < Nn ? col_n : Nn - 4u) * 4u;
-    const gbytes base_n = (gbytes)reinterpret_cast<const char*>(Wn) + (size_t)kbn * Nn * 4u;
-#pragma unroll
-    for (int mg = 0; mg < MG; ++mg)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[mg][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int u0 = 0; u0 < NR; u0 += VEC) {
-        if ((unsigned int)u0 < kcount) {
-#pragma unroll
-            for (int mg = 0; mg < MG; ++mg) {
-                const avec a = *reinterpret_cast<const avec*>(ap + (size_t)mg * 4 * ldk + u0);
-#pragma unroll
-                for (int u = 0; u < VEC; ++u)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        acc[mg][j] = __builtin_amdgcn_mfma_f32_4x4x1f32(a[u], wr[u0 + u][j], acc[mg][j], 0, 0, 0);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < VEC; ++u) {
-            const unsigned int uu = (unsigned int)(u0 + u) < kcn ? (unsigned int)(u0 + u) : kcn - 1u;
-            gbytes rb = base_n + (size_t)uu * Nn * 4u;
-            asm volatile("" : "+s"(rb));
-            wr[u0 + u] = *(const __attribute__((address_space(1))) f32x4*)(rb + cbn);
         }
     }
 }
@@ -295,20 +212,29 @@ __device__ __forceinline__ float sum_part(const float* part, unsigned int slices
     return v;
 }
 
-// BOTH: a frozen target network evaluates s'.  NR1: rows of W1 a lane holds (Dp / 4, 8 or 16).
+// NR1: rows of W1 a lane holds (Dp / 4, 8 or 16).
 // R: experiences per workgroup, 4 or 2.  A workgroup's 2 R rows (R states s, then R states s')
 // form R / 2 groups of four MFMA rows.  Every workgroup fetches all the weights whatever R is,
 // so R = 2 halves a workgroup's products at twice the workgroups: the choice for batches that
-// leave most compute units idle anyway.  (With a target network s and s' cannot share a group.)
-template <bool BOTH, int NR1, int R>
+// leave most compute units idle anyway.
+//
+// SPLIT: the frozen target network in workgroups of its own.  Workgroups come in pairs for four
+// experiences: the even one (lower number, so dispatched first) sends the four states s' through
+// the target network and hands max_a Q_target(s', a) to the odd one, which does everything else
+// for the four states s.  Both then fetch one network's weights and multiply one group of four
+// rows, like a workgroup of the step without a target network, and run side by side on
+// different compute units; the odd one waits (a bounded time) where it needs the maxima.
+template <bool SPLIT, int NR1, int R>
 __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
-    static_assert(R == 4 || (R == 2 && !BOTH), "rows per workgroup");
-    constexpr int MG = R / 2;            // groups of four rows
-    constexpr unsigned int NRW = 2 * R;  // rows of a workgroup
-    constexpr unsigned int PR = NRW;     // rows of its MFMA groups
+    static_assert(R == 4 || (R == 2 && !SPLIT), "experiences per workgroup (split: per pair of workgroups)");
+    constexpr unsigned int NRW = SPLIT ? 4 : 2 * R;  // rows of a workgroup
+    constexpr int MG = NRW / 4;                      // groups of four rows
+    constexpr unsigned int PR = NRW;                 // rows of its MFMA groups
     extern __shared__ float lds[];
     touch_kernel_args<RowArgs>();
-    if (blockIdx.x * R >= p.B) {
+    const unsigned int wg = SPLIT ? blockIdx.x >> 1 : blockIdx.x;
+    const bool target_side = SPLIT && !(blockIdx.x & 1u);   // (uniform over the workgroup)
+    if (wg * R >= p.B) {
         // the extra workgroup of a replay that samples without duplicates: the next step's slots
         const unsigned long long ns = p.step + 1;
         unsigned int* dst = p.pre + ((ns & 1u) ? p.pre_stride : 0u);
@@ -333,19 +259,13 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     float* b1s = part + 16 * 8 * kChunk;  // [H]   (layer 1's biases stay in registers: unused)
     float* b2s = b1s + H;                 // [H]
     float* b3s = b2s + H;                 // [Ap]
-    float* b1ts = b3s + Ap;               // [H]   the frozen target network's biases
-    float* b2ts = b1ts + H;               // [H]
-    float* b3ts = b2ts + H;               // [Ap]
-    unsigned int* meta = reinterpret_cast<unsigned int*>(b3ts + Ap);  // [4][4]
+    unsigned int* meta = reinterpret_cast<unsigned int*>(b3s + Ap);   // [4][4]
     float* gs = reinterpret_cast<float*>(meta + 16);                 // [4]
 
-    const float* W1 = p.w + p.oW1;
-    const float* W2 = p.w + p.oW2;
-    const float* W3 = p.w + p.oW3;
-    // Frozen target network: rows 4..7 (the new states) go through its weights instead.  The lane's
-    // registers take the trained network's share of a layer first (rows 0..3: R = 4 then) and are refilled
-    // with the target's during those MFMAs.
-    constexpr bool both = BOTH;
+    const float* wsrc = target_side ? p.wt : p.w;
+    const float* W1 = wsrc + p.oW1;
+    const float* W2 = wsrc + p.oW2;
+    const float* W3 = wsrc + p.oW3;
     // wide split (layer 2 and backward): K sixteenths
     const unsigned int cc = 4u * lane, ks = wave;
     const unsigned int q2 = H >> 4;
@@ -362,16 +282,17 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     f32x4 acc2[MG];
     // layer 3's weights can be requested with W2 by the wavefronts that have no part in
     // layer 1 (two experiences per workgroup: the registers hold them next to layer 2's sums)
-    constexpr bool W3_EARLY = R == 2 || BOTH;   // (four experiences without a target network: no room)
-    constexpr unsigned int NL1 = BOTH ? 8u : 4u;   // wavefronts in layer 1
+    constexpr bool W3_EARLY = MG == 1;          // (two groups of rows: no room)
+    constexpr unsigned int NL1 = 4u;            // wavefronts in layer 1
     const unsigned long long cap = p.g.capacity;
     const unsigned long long head = p.head;
     const unsigned long long step = p.step;
     const unsigned long long n = p.n_append;
     const unsigned int size = p.size_after;
-    const unsigned int i0 = blockIdx.x * R;
+    const unsigned int i0 = wg * R;
     const unsigned int nrows = min((unsigned int)R, p.B - i0);
-    const unsigned int words = 2 * D + 3;
+    // words of a sampled row this workgroup needs: all 2 D + 3, or s and (a, r, terminal), or s'
+    const unsigned int words = SPLIT ? (target_side ? D : D + 3u) : 2 * D + 3;
 
     // The state that follows this step is known up front (the host mirrors it exactly): one
     // thread stores it for the kernels and calls that read it later, off everyone's critical path.
@@ -393,9 +314,8 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
         // queueing their requests for W2.  Each of the four draws and gathers the (few) sampled
         // words itself, and they share publishing them: wavefront 1 the action / reward / terminal
         // words, the others the states, a pass each.
-        // With a target network wavefronts 4..7 do the same for the rows s' with its W1 and b1.
-        constexpr int MGF = BOTH ? 1 : MG;              // groups of four rows each of them takes
-        const unsigned int grp = BOTH ? __builtin_amdgcn_readfirstlane(wave >> 2) : 0u, wq = wave & 3u;
+        constexpr int MGF = MG;                         // groups of four rows each of them takes
+        const unsigned int wq = wave & 3u;
         if (wave < NL1) {
             // one draw per row, in the lane of that row: first of all, the sampled words take
             // longest to arrive
@@ -412,12 +332,17 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
                         myslot = batch_draw(p.g.sampling, p.seed, step, i0 + lane, size);
                 }
             }
-            constexpr int NPASS = (R * (8 * NR1 + 3) + 63) / 64;   // 2 D + 3 <= 8 NR1 + 3 words per row
+            // D <= 4 NR1: at most 8 NR1 + 3 words per row (split: 4 NR1 + 3)
+            constexpr int NPASS = (R * ((SPLIT ? 4 : 8) * NR1 + 3) + 63) / 64;
             unsigned int gv[NPASS], gsl[NPASS];
+            // word `wl` of this workgroup's share of a row -> word of the row [s | s' | a r terminal]
+            auto row_word = [&](unsigned int wl) {
+                return !SPLIT ? wl : target_side ? wl + D : wl < D ? wl : wl + D;
+            };
 #pragma unroll
             for (int pass = 0; pass < NPASS; ++pass) {
                 const unsigned int e = lane + 64u * pass;
-                const unsigned int r = min(e / words, (unsigned int)R - 1u), w = e - r * words;
+                const unsigned int r = min(e / words, (unsigned int)R - 1u), w = row_word(e - r * words);
                 const unsigned int slot = __shfl(myslot, (int)r, 64);
                 gv[pass] = 0u;
                 gsl[pass] = slot;
@@ -443,7 +368,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
             f32x4 w1x[NR1];
             {
                 const unsigned int loff = (((unsigned int)NR1 * kq) * H + (colf ? ccf : H - 4u)) * 4u;
-                const gbytes base = (gbytes)reinterpret_cast<const char*>(BOTH && grp ? p.wt + p.oW1 : W1);
+                const gbytes base = (gbytes)reinterpret_cast<const char*>(W1);
 #pragma unroll
                 for (int u = 0; u < NR1; ++u) {
                     gbytes rb = base + (size_t)u * H * 4u;
@@ -451,7 +376,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
                     w1x[u] = *(const __attribute__((address_space(1))) f32x4*)(rb + loff);
                 }
             }
-            const f32x4 b1f = *reinterpret_cast<const f32x4*>((BOTH && grp ? p.wt : p.w) + p.ob1 + (colf ? ccf : H - 4u));
+            const f32x4 b1f = *reinterpret_cast<const f32x4*>(wsrc + p.ob1 + (colf ? ccf : H - 4u));
             // the private copy (in the partial-sum buffer, which nothing uses before layer 2)
             float* Xp = part + wave * (PR * ldx);
             for (unsigned int e = lane; e < PR * ldx; e += 64u) Xp[e] = 0.f;
@@ -460,7 +385,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
             for (int pass = 0; pass < NPASS; ++pass) {
                 const unsigned int e = lane + 64u * pass;
                 if (e < nrows * words) {
-                    const unsigned int r = e / words, w = e - r * words;
+                    const unsigned int r = e / words, w = row_word(e - r * words);
                     const unsigned int i = i0 + r;
                     const unsigned int val = gv[pass];
                     if (w < D) {
@@ -468,7 +393,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
                         if (wave == (pass % 3 == 0 ? 0u : pass % 3 == 1 ? 2u : 3u))
                             p.X[(size_t)i * Dp + w] = __uint_as_float(val);
                     } else if (w < 2 * D) {
-                        Xp[(R + r) * ldx + w - D] = __uint_as_float(val);
+                        Xp[((SPLIT ? 0u : (unsigned int)R) + r) * ldx + w - D] = __uint_as_float(val);
                     } else if (wave == 1) {
                         meta[r * 4 + (w - 2 * D)] = val;
                         if (w == 2 * D) {
@@ -486,7 +411,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             f32x4 accf[MGF][4];
             {
-                const float* ap = Xp + (4u * grp + (lane & 3u)) * ldx + (unsigned int)NR1 * kq;
+                const float* ap = Xp + (lane & 3u) * ldx + (unsigned int)NR1 * kq;
 #pragma unroll
                 for (int mg = 0; mg < MGF; ++mg)
 #pragma unroll
@@ -519,10 +444,11 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
                     }
 #pragma unroll
                 for (int j = 0; j < 4; ++j) hv[j] = hv[j] > 0.f ? hv[j] : 0.f;
-                const unsigned int row = (mg + grp) * 4 + kq;
+                const unsigned int row = mg * 4 + kq;
                 if (colf) {
                     *reinterpret_cast<f32x4*>(H1s + row * ldh + ccf) = hv;
-                    if (row < nrows) *reinterpret_cast<f32x4*>(p.H1 + (size_t)(i0 + row) * H + ccf) = hv;
+                    if (row < nrows && !target_side)
+                        *reinterpret_cast<f32x4*>(p.H1 + (size_t)(i0 + row) * H + ccf) = hv;
                 }
             }
             load_cols4<16>(w2r, W2, H, cc, ks * q2, q2);
@@ -531,17 +457,13 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
             if constexpr (W3_EARLY) load_cols<16>(w3r, W3, Ap, lane, wave * s3, s3);
             // the other biases: the four wavefronts after layer 1's
             const unsigned int t4 = tid - 64u * NL1;
-            if (t4 < H) b2s[t4] = p.w[p.ob2 + t4];
-            if (t4 < Ap) b3s[t4] = p.w[p.ob3 + t4];
-            if constexpr (BOTH) {
-                if (t4 < H) b2ts[t4] = p.wt[p.ob2 + t4];
-                if (t4 < Ap) b3ts[t4] = p.wt[p.ob3 + t4];
-            }
+            if (t4 < H) b2s[t4] = wsrc[p.ob2 + t4];
+            if (t4 < Ap) b3s[t4] = wsrc[p.ob3 + t4];
         }
         // The last workgroup also writes the new experiences into the ring.  No workgroup reads
         // those slots from the ring in this launch (see above), so this can go out right away and
         // its latency is hidden behind the rest of the kernel.
-        if (i0 + R >= p.B && n) {
+        if (i0 + R >= p.B && n && !target_side) {
             const unsigned int rw = p.g.row_bytes >> 2;
             for (unsigned long long e = tid; e < n * rw; e += kRowThreads) {
                 const unsigned long long k = e / rw;
@@ -559,17 +481,11 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     // half a microsecond while its SIMD's load path is busy, so each wavefront does it in a
     // phase in which the others have all the work: wavefronts 8..15 during layer 2's sums
     // (wavefronts 0..7), wavefronts 0..7 during layer 3's sums and the TD phase (12..15).
-    if constexpr (!BOTH) {
+    {
         f32x4 acc8[MG][4];
         mma_cols4<MG, 16, 4>(acc8, H1s, ldh, ks * q2, q2, w2r);
 #pragma unroll
         for (int mg = 0; mg < MG; ++mg) store_part4(part, ks, NRW, 4 * mg, kChunk, cc, acc8[mg]);
-    } else {
-        f32x4 acc4[1][4];
-        mma_cols4_reload<1, 16, 4>(acc4, H1s, ldh, ks * q2, q2, w2r, p.wt + p.oW2, H, cc, ks * q2, q2);
-        store_part4(part, ks, 8, 0, kChunk, cc, acc4[0]);
-        mma_cols4<1, 16, 4>(acc4, H1s + 4 * ldh, ldh, ks * q2, q2, w2r);
-        store_part4(part, ks, 8, 4, kChunk, cc, acc4[0]);
     }
     // The accumulators are free: layer 3's weights are requested, and ...
     if (!W3_EARLY || wave < NL1) load_cols<16>(w3r, W3, Ap, lane, wave * s3, s3);
@@ -577,7 +493,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     float w3sel = 0.f;
     {
         const unsigned int r = tid / H, k = tid - r * H;
-        if (r < nrows) {
+        if (r < nrows && !target_side) {
             unsigned int ai = meta[r * 4 + 0];
             if (ai >= A) ai = A - 1;  // an out-of-range action must not turn into a wild address
             w3sel = W3[(size_t)k * Ap + ai];
@@ -588,37 +504,22 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
         // four adjacent columns of one row per thread, 16-byte LDS accesses
         for (unsigned int e = tid; e < NRW * (H >> 2); e += 512u) {
             const unsigned int row = e / (H >> 2), c = (e - row * (H >> 2)) * 4u;
-            f32x4 v = *reinterpret_cast<const f32x4*>((both && row >= R ? b2ts : b2s) + c);
+            f32x4 v = *reinterpret_cast<const f32x4*>(b2s + c);
             for (unsigned int sl = 0; sl < 16; ++sl)
                 v += *reinterpret_cast<const f32x4*>(part + ((size_t)(sl * NRW + row)) * kChunk + c);
 #pragma unroll
             for (int j = 0; j < 4; ++j) v[j] = v[j] > 0.f ? v[j] : 0.f;
             *reinterpret_cast<f32x4*>(H2s + row * ldh + c) = v;
-            if (row < nrows) *reinterpret_cast<f32x4*>(p.H2 + (size_t)(i0 + row) * H + c) = v;
+            if (row < nrows && !target_side) *reinterpret_cast<f32x4*>(p.H2 + (size_t)(i0 + row) * H + c) = v;
         }
-    } else {
-        load_cols4<16, 0, BOTH ? 12 : 16>(w2r, p.w2t, H, cc, ks * q2, q2);
+    } else if (!target_side) {
+        load_cols4<16>(w2r, p.w2t, H, cc, ks * q2, q2);
     }
     lds_barrier();
 
     // ---- layer 3 (narrow split: 16 K slices, columns 0..63)
-    if constexpr (!BOTH) {
-        mma_cols<MG, 16>(acc2, H2s, ldh, wave * s3, s3, w3r);
-    } else {
-        f32x4 lo[1], hi[1];
-        mma_cols_reload<1, 16>(lo, H2s, ldh, wave * s3, s3, w3r, p.wt + p.oW3, Ap, lane, wave * s3, s3);
-        mma_cols<1, 16>(hi, H2s + 4 * ldh, ldh, wave * s3, s3, w3r);
-        acc2[0] = lo[0];
-        acc2[1] = hi[0];
-    }
+    mma_cols<MG, 16>(acc2, H2s, ldh, wave * s3, s3, w3r);
     store_part<MG>(part, wave, 64, lane, acc2);
-    // (with a target network: a few rows of W2^T per wavefront here, so that the two phases around
-    // this one, whose length is that of their requests, get shorter; measured a gain there, a small
-    // loss without the target network)
-    if constexpr (BOTH) {
-        if (wave < 8) load_cols4<16, 0, 4>(w2r, p.w2t, H, cc, ks * q2, q2);
-        else load_cols4<16, 12, 16>(w2r, p.w2t, H, cc, ks * q2, q2);
-    }
     lds_barrier();
 
     // ---- Q values (sums of the partial products), TD target, loss term, dL/dQ: wavefront
@@ -631,10 +532,42 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
         const unsigned int r = wave - 12u;
         if (r < (unsigned int)R && lane < Ap) {
             td_qs = sum_part(part, 16, NRW, 64, r, lane) + b3s[lane];
-            td_qn = sum_part(part, 16, NRW, 64, R + r, lane) + (both ? b3ts : b3s)[lane];
+            if constexpr (!SPLIT) td_qn = sum_part(part, 16, NRW, 64, R + r, lane) + b3s[lane];
         }
-        if (r < nrows) {
-            const float best = wave_max(lane < A ? td_qn : -INFINITY);
+        if (SPLIT && target_side) {
+            // Q_target(s', .) of this row and its maximum, handed over in one 8-byte word that
+            // carries this launch's number (value and tag arrive together or not at all)
+            if (r < nrows) {
+                const unsigned int i = i0 + r;
+                const float best = wave_max(lane < A ? td_qs : -INFINITY);
+                if (lane < Ap) p.Q[((size_t)p.B + i) * Ap + lane] = td_qs;
+                if (lane == 0)
+                    __hip_atomic_store(p.handoff + i, ((unsigned long long)p.seq << 32) | __float_as_uint(best),
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        } else if (r < nrows) {
+            float best;
+            if constexpr (SPLIT) {
+                // wait for the other workgroup of the pair: it was dispatched before this one and
+                // waits for nothing, so the word arrives; the time limit only guards against a
+                // launch that breaks that order (then the step is marked as failed)
+                unsigned long long word = 0;
+                if (lane == 0) {
+                    const long long t0 = wall_clock64();
+                    bool there;
+                    do {
+                        word = __hip_atomic_load(p.handoff + i0 + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        there = (unsigned int)(word >> 32) == p.seq;
+                    } while (!there && wall_clock64() - t0 < kHandoffTicks);
+                    if (!there) {
+                        p.ctr->handoff_missed = 1u;
+                        word = 0;
+                    }
+                }
+                best = __uint_as_float((unsigned int)__shfl(word, 0, 64));
+            } else {
+                best = wave_max(lane < A ? td_qn : -INFINITY);
+            }
             td_ai = meta[r * 4 + 0];
             if (td_ai >= A) td_ai = A - 1;
             const float q = __shfl(td_qs, (int)td_ai, 64);
@@ -651,15 +584,16 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
             td_gr = -slope / (float)p.B;
             if (lane == 0) gs[r] = td_gr;
         }
-    } else if (wave < 8) {
-        load_cols4<16, BOTH ? 4 : 0, 16>(w2r, p.w2t, H, cc, ks * q2, q2);
+    } else if (wave < 8 && !target_side) {
+        load_cols4<16>(w2r, p.w2t, H, cc, ks * q2, q2);
     }
+    if (target_side) return;   // (the whole workgroup: nothing after this concerns s')
     lds_barrier();
     if (wave >= 12 && wave - 12u < nrows) {
         const unsigned int i = i0 + wave - 12u;
         if (lane < Ap) {
             p.Q[(size_t)i * Ap + lane] = td_qs;
-            p.Q[((size_t)p.B + i) * Ap + lane] = td_qn;
+            if constexpr (!SPLIT) p.Q[((size_t)p.B + i) * Ap + lane] = td_qn;
             p.dQ[(size_t)i * Ap + lane] = lane == td_ai ? td_gr : 0.f;
         }
         if (lane == 0) {
@@ -1013,7 +947,7 @@ __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
 
 size_t row_kernel_lds(unsigned int Dp, unsigned int H, unsigned int Ap) {
     const size_t ldx = Dp + kPadK, ldh = H + kPadK, ldq = Ap + kPadK;
-    return (8 * ldx + 8 * ldh * 2 + 8 * ldq + 4 * ldh + 16 * 8 * kChunk + 2 * (2 * H + Ap) + 16 + 4) *
+    return (8 * ldx + 8 * ldh * 2 + 8 * ldq + 4 * ldh + 16 * 8 * kChunk + (2 * H + Ap) + 16 + 4) *
            sizeof(float);
 }
 
@@ -1050,7 +984,8 @@ hipError_t fused_init() {
 }
 
 // Experiences per workgroup of the row kernel: two while that still leaves compute units idle
-// (every workgroup fetches all the weights, so more workgroups than that only add traffic).
+// (every workgroup fetches all the weights, so more workgroups than that only add traffic); with
+// a target network four per pair of workgroups.
 unsigned int fused_rows_per_group(bool target_network, unsigned int B) {
     return !target_network && B <= kSmallBatch ? 2u : kRows;
 }
@@ -1087,6 +1022,8 @@ hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* bat
         a.total_after = r->total + a.n_append;
         set_adam_step(a, t->host_adam_t + 1, t->cfg.beta1, t->cfg.beta2);
     }
+    a.handoff = t->handoff;
+    a.seq = next_launch_seq(t);
     a.ctr = t->ctr;
     a.w = t->w;
     a.wt = t->wt;
@@ -1107,7 +1044,8 @@ hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* bat
     a.pre = ahead ? t->pre : nullptr;
     a.pre_stride = 4u + t->B;
     const unsigned int per = fused_rows_per_group(t->wt != nullptr, t->B);
-    const unsigned int blocks = (t->B + per - 1) / per + (ahead ? 1u : 0u);
+    // (with a target network: a pair of workgroups for every four experiences)
+    const unsigned int blocks = (t->B + per - 1) / per * (t->wt ? 2u : 1u) + (ahead ? 1u : 0u);
     hipError_t e = hipSuccess;
     void* kargs[] = {&a};
     e = hipLaunchKernel(fused_rows_func(t->wt != nullptr, t->Dp, t->B), dim3(blocks), dim3(kRowThreads), kargs,

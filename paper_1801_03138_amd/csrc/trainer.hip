@@ -260,7 +260,7 @@ namespace {
 
 struct WsLayout {
     size_t ctr, w, g, m, v, wt, w2t, wb, wbt, X, act, rew, term, idx, H1, H2, Q, y, delta, lossi, dQ, dZ2, dZ1,
-        pre, total;
+        pre, handoff, total;
     // mixed-precision step on MFMA
     size_t W1T, W2b, W2T, W3T, W1Tt, W2Tt, W3Tt, XT, H1T, H2T, dQTh, dQTl, dZ2T, dZ1T, part3, part1, part2;
     unsigned int Dp, Ap, Bp;
@@ -322,6 +322,7 @@ bool ws_layout(const train_config* c, WsLayout* L) {
     L->dZ2 = take(B * G * L->elem);
     L->dZ1 = take(B * H * L->elem);
     L->pre = take(2 * (4 + B) * 4);
+    L->handoff = take(c->target_sync ? B * 8 : 0);
     // the MFMA mixed-precision step exists for two hidden layers of one width
     const bool mixed = c->param_dtype == RP_BF16 && H == G;
     const size_t Bp = align_up(B, 128), Dx = align_up(D + 1, 32);
@@ -717,6 +718,7 @@ void set_payload_args(trainer* t, const Payload& src, unsigned int k) {
         t->row_args.size_after = (unsigned int)(size + n > cap ? cap : size + n);
         t->row_args.next_size = (unsigned int)(size + 2 * n > cap ? cap : size + 2 * n);
         t->row_args.total_after = total + n;
+        t->row_args.seq = rp::next_launch_seq(t);
         rp::set_adam_step(t->row_args, t->host_adam_t + k + 1, t->cfg.beta1, t->cfg.beta2);
     } else {
         t->append_args.src = src;
@@ -877,6 +879,8 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
     t->dZ2 = ws + L.dZ2;
     t->dZ1 = ws + L.dZ1;
     t->pre = reinterpret_cast<unsigned int*>(ws + L.pre);
+    t->handoff = reinterpret_cast<unsigned long long*>(ws + L.handoff);
+    t->launch_seq = 0;
     t->graph = nullptr;
     t->graph_exec = nullptr;
     t->capture_stream = nullptr;
@@ -1077,6 +1081,7 @@ rp_status train_step_batch(trainer_t* t, const void* s, const void* s_next, cons
         t->row_args.step = t->host_step;
         t->row_args.size_after = (unsigned int)rpl->size;
         t->row_args.total_after = rpl->total;
+        t->row_args.seq = rp::next_launch_seq(t);
         rp::set_adam_step(t->row_args, t->host_adam_t + 1, t->cfg.beta1, t->cfg.beta2);
         RP_CHECK_HIP(hipGraphExecKernelNodeSetParams(t->graph_exec, t->payload_node[0],
                                                      &t->payload_np[0]));
@@ -1208,6 +1213,7 @@ rp_status train_get_opt_state(trainer_t* t, float* m, float* v, uint64_t* adam_t
     RP_CHECK_HIP(hipMemcpy(&c, t->ctr, sizeof(c), hipMemcpyDeviceToHost));
     if (adam_t) *adam_t = c.adam_t;
     if (step) *step = c.step;
+    RP_REQUIRE_STATE(!c.handoff_missed, "train_get_opt_state: a train step's workgroups missed a hand-over");
     return RP_OK;
 }
 
@@ -1268,11 +1274,10 @@ rp_status train_get_last(trainer_t* t, float* q, float* q_next, float* y, float*
     if (y) RP_CHECK_HIP(hipMemcpy(y, t->y, B * 4, hipMemcpyDeviceToHost));
     if (delta) RP_CHECK_HIP(hipMemcpy(delta, t->delta, B * 4, hipMemcpyDeviceToHost));
     if (idx) RP_CHECK_HIP(hipMemcpy(idx, t->idx, B * 4, hipMemcpyDeviceToHost));
-    if (loss) {
-        TrainCounters c;
-        RP_CHECK_HIP(hipMemcpy(&c, t->ctr, sizeof(c), hipMemcpyDeviceToHost));
-        *loss = c.loss;
-    }
+    TrainCounters c;
+    RP_CHECK_HIP(hipMemcpy(&c, t->ctr, sizeof(c), hipMemcpyDeviceToHost));
+    if (loss) *loss = c.loss;
+    RP_REQUIRE_STATE(!c.handoff_missed, "train_get_last: a train step's workgroups missed a hand-over");
     return RP_OK;
 }
 

@@ -38,7 +38,7 @@ struct TrainCounters {
     unsigned long long adam_t;  // Adam steps taken
     float c1, c2;               // Adam bias corrections 1 - beta^t of the current step
     float loss;                 // mean loss of the last step
-    unsigned int pad0_;
+    unsigned int handoff_missed;   // set when a workgroup's bounded wait for another one ran out
     double pw1, pw2;            // beta1^t, beta2^t for t = adam_t (kept by the steps that advance t on the device)
     unsigned int pad_[4];
 };
@@ -86,6 +86,11 @@ struct RowArgs {
     unsigned int* pre;           // null: no extra workgroup, no look-up
     unsigned int pre_stride;
     unsigned int next_size;      // experiences held after the next step's append
+    // Target network in workgroups of its own: max_a Q_target(s'_i, a) travels from one workgroup to
+    // another inside the launch as handoff[i] = (seq << 32) | float bits; seq differs from launch
+    // to launch, so a word left by an earlier launch is never taken for this one's.
+    unsigned long long* handoff; // [B]
+    unsigned int seq;
     TrainCounters* ctr;
     const float* w;       // padded parameters
     const float* wt;      // the frozen target network's (Q(s', .) is computed with them), or null
@@ -161,6 +166,8 @@ struct trainer {
     float *y, *delta, *lossi, *dQ;   // [B], [B], [B], [B x Ap]
     void *dZ2, *dZ1;                 // [B x Hb], [B x H]
     unsigned int* pre;               // slots drawn ahead, 2 x (4 + B) words
+    unsigned long long* handoff;     // [B] words one workgroup of the row kernel hands to another
+    unsigned int launch_seq;         // number of the last row-kernel launch prepared (never 0)
     bool fused;                      // two-kernel step for small fp32 networks
     bool wide;                       // mixed-precision step on MFMA
     bool mid;                        // fp32 step on MFMA, one product per kernel
@@ -206,6 +213,12 @@ bool fused_step_supported(const train_config& cfg, const replay* rp_);
 hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* batch, hipStream_t st,
                               unsigned int* count);
 hipError_t fused_init();                      // once, at trainer creation
+// The number that tells one launch of the row kernel from the others (never 0, the value of a
+// cleared hand-over word).
+inline unsigned int next_launch_seq(trainer* t) {
+    if (++t->launch_seq == 0) ++t->launch_seq;
+    return t->launch_seq;
+}
 void* fused_rows_func(bool target_network, unsigned int Dp, unsigned int B);   // the row kernel variant for a configuration
 // Dueling head: turn the gradient of the equivalent plain output layer (in g) into the head's
 // update and refresh that layer (and its bf16 / target copies).  No-op for a plain head.

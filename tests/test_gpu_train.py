@@ -557,7 +557,7 @@ def test_in_ram_replay_trains_on_the_same_batches_as_the_device_replay(B):
     ("bf16", 128, 200, False, 11), ("bf16", 64, 256, False, 8), ("bf16", 128, 96, True, 18)])
 def test_frozen_target_network(B, dtype, H, batch, layered, kernels):
     """Q(s', .) from a frozen copy of the weights, synced every 7th update (Deep Q-Network Model):
-    the small fp32 step with a target pass of its row kernel first, the layered step, and the
+    the small fp32 step with the target's forward pass in workgroups of its own, the layered step, and the
     MFMA step with the S' rows in the same launches (batch 256) or in launches of their own
     (batch 200)."""
     rows = synth.experiences(400, 27, 30, 0.05, seed=23, state_dtype=dtype)
@@ -576,6 +576,39 @@ def test_frozen_target_network(B, dtype, H, batch, layered, kernels):
     pr.trainer.set_target(other)
     assert np.array_equal(pr.trainer.target(), other)
     pr.step(synth.experiences(2, 27, 30, 0.05, seed=24, state_dtype=dtype), compare=True)
+
+
+@pytest.mark.parametrize("D,H,A,batch,distinct,dueling", [
+    (27, 256, 30, 128, False, False),    # the paper-shaped step
+    (60, 128, 9, 1030, False, False),    # wide states, 258 pairs of workgroups (more than compute units), ragged
+    (27, 64, 30, 131, True, True),       # the extra workgroup that draws the next step's slots, ragged; dueling head
+    (5, 192, 64, 3, False, False),       # one pair only, three of its four rows; widest action set
+])
+def test_target_network_in_workgroups_of_its_own(B, D, H, A, batch, distinct, dueling):
+    """Two-kernel step with a frozen target network: the states s' go through the target
+    network in workgroups of their own, which hand max_a Q_target(s', a) over to the workgroups
+    that hold s inside the same launch.  Q(s', .), targets, TD errors and the update against the
+    oracle on every step, across several syncs; then a batch given by the caller."""
+    rows = synth.experiences(1700, D, A, 0.1, seed=61)
+    pr = Pair(B, capacity=1500, D=D, H=H, A=A, batch=batch, burn_in=1100, seed=13, appends=4,
+              target_sync=3, distinct=distinct, dueling=dueling, lr=1e-3)
+    assert pr.trainer.kernels_per_step() == 2
+    pr.append_only(synth.take(rows, 0, 1200))
+    for k in range(12):
+        assert pr.step(synth.take(rows, 1200 + 4 * k, 1204 + 4 * k), compare=True) == 0
+    assert pr.gpu_ring.state() == pr.ref_ring.state()
+    tr = pr.trainer
+    given = synth.experiences(batch, D, A, 0.1, seed=62)
+    d = {k: torch.from_numpy(v).cuda() for k, v in given.items()}
+    p, (m, v, t, step), tgt = tr.params(), tr.opt_state(), tr.target()
+    assert tr.step_batch(d["s"], d["s_next"], d["a"], d["r"], d["term"]) == 0
+    ref = oracle.train_step(pr.cfg, p, m, v, t, pr.states_f64(given["s"]), pr.states_f64(given["s_next"]),
+                            given["a"], given["r"], given["term"], target=tgt)
+    last = tr.last()
+    assert_close(last["Q"], ref.Q, pr.rtol, "Q(s,.)")
+    assert_close(last["Qn"], ref.Qn, pr.rtol, "Q_target(s',.)")
+    assert_close(last["y"], ref.y, pr.rtol, "targets")
+    assert_close([last["loss"]], [ref.loss], pr.rtol, "loss")
 
 
 @pytest.mark.parametrize("dtype,H,layered", [("f32", 64, False), ("f32", 64, True), ("bf16", 128, False)])
