@@ -280,6 +280,13 @@ rp_status train_set_state(trainer_t* tr, const float* params, const float* m, co
  * sampled slot numbers idx[B]. */
 rp_status train_get_last(trainer_t* tr, float* q, float* q_next, float* y, float* delta,
                          float* loss, uint32_t* idx);
+/* Test call for the bounded wait above.  ticks: the longest a workgroup waits for its partner, in
+ * ticks of the GPU's 100 MHz wall clock (0 = the default, 50 ms; at most 2^40).  break_pairing
+ * != 0 makes the waiting workgroups of later steps look for a launch number that no workgroup
+ * sends, so every wait runs out after `ticks`: the kernels end normally, the steps compute with
+ * zeros in place of the target network's values, and the read-back calls return RP_ESTATE until
+ * train_set_state (which clears the mark) is called.  Takes effect from the next step enqueued. */
+rp_status train_set_handoff_wait(trainer_t* tr, uint64_t ticks, int break_pairing);
 /* Number of GPU kernels one executed train step launches (graph nodes). */
 rp_status train_kernels_per_step(trainer_t* tr, uint32_t* n);
 

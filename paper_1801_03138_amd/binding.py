@@ -83,6 +83,7 @@ SYMBOLS = {
     "train_get_target": (_int, [_vp, _vp]),
     "train_set_target": (_int, [_vp, _vp]),
     "train_kernels_per_step": (_int, [_vp, _vp]),
+    "train_set_handoff_wait": (_int, [_vp, _u64, _int]),
     "rp_last_error": (C.c_char_p, []),
     "rp_version": (C.c_char_p, []),
 }
@@ -409,6 +410,9 @@ class Trainer:
         _check(lib().train_get_last(self._h, _host(q), _host(qn), _host(y), _host(d), _host(loss),
                                     _host(idx)))
         return {"Q": q, "Qn": qn, "y": y, "delta": d, "loss": float(loss[0]), "idx": idx}
+
+    def set_handoff_wait(self, ticks=0, break_pairing=False):
+        _check(lib().train_set_handoff_wait(self._h, int(ticks), int(bool(break_pairing))))
 
     def kernels_per_step(self):
         n = C.c_uint32()

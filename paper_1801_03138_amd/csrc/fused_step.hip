@@ -27,8 +27,6 @@ constexpr unsigned int kSmallBatch = 512;  // ... and 2 for batches up to this s
 constexpr unsigned int kChunk = 256;       // output columns the workgroup covers per pass
 constexpr size_t kRowLdsMax = 160 * 1024;  // dynamic LDS the row kernel may ask for (all of a CU's)
 constexpr unsigned int kPadK = 4;          // LDS row padding (floats) against bank conflicts
-constexpr long long kHandoffTicks = 5000000;   // longest wait for the other workgroup of a pair: 50 ms
-                                               // of the 100 MHz wall clock
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
@@ -557,8 +555,8 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
                     bool there;
                     do {
                         word = __hip_atomic_load(p.handoff + i0 + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        there = (unsigned int)(word >> 32) == p.seq;
-                    } while (!there && wall_clock64() - t0 < kHandoffTicks);
+                        there = (unsigned int)(word >> 32) == p.seq_wait;
+                    } while (!there && wall_clock64() - t0 < p.handoff_ticks);
                     if (!there) {
                         p.ctr->handoff_missed = 1u;
                         word = 0;
@@ -1023,7 +1021,7 @@ hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* bat
         set_adam_step(a, t->host_adam_t + 1, t->cfg.beta1, t->cfg.beta2);
     }
     a.handoff = t->handoff;
-    a.seq = next_launch_seq(t);
+    stamp_launch(t, a);
     a.ctr = t->ctr;
     a.w = t->w;
     a.wt = t->wt;

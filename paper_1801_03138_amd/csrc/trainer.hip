@@ -718,7 +718,7 @@ void set_payload_args(trainer* t, const Payload& src, unsigned int k) {
         t->row_args.size_after = (unsigned int)(size + n > cap ? cap : size + n);
         t->row_args.next_size = (unsigned int)(size + 2 * n > cap ? cap : size + 2 * n);
         t->row_args.total_after = total + n;
-        t->row_args.seq = rp::next_launch_seq(t);
+        rp::stamp_launch(t, t->row_args);
         rp::set_adam_step(t->row_args, t->host_adam_t + k + 1, t->cfg.beta1, t->cfg.beta2);
     } else {
         t->append_args.src = src;
@@ -881,6 +881,8 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
     t->pre = reinterpret_cast<unsigned int*>(ws + L.pre);
     t->handoff = reinterpret_cast<unsigned long long*>(ws + L.handoff);
     t->launch_seq = 0;
+    t->handoff_ticks = rp::kHandoffTicks;
+    t->handoff_break = false;
     t->graph = nullptr;
     t->graph_exec = nullptr;
     t->capture_stream = nullptr;
@@ -1081,7 +1083,7 @@ rp_status train_step_batch(trainer_t* t, const void* s, const void* s_next, cons
         t->row_args.step = t->host_step;
         t->row_args.size_after = (unsigned int)rpl->size;
         t->row_args.total_after = rpl->total;
-        t->row_args.seq = rp::next_launch_seq(t);
+        rp::stamp_launch(t, t->row_args);
         rp::set_adam_step(t->row_args, t->host_adam_t + 1, t->cfg.beta1, t->cfg.beta2);
         RP_CHECK_HIP(hipGraphExecKernelNodeSetParams(t->graph_exec, t->payload_node[0],
                                                      &t->payload_np[0]));
@@ -1244,6 +1246,7 @@ rp_status train_set_state(trainer_t* t, const float* params, const float* m, con
     RP_CHECK_HIP(hipMemcpy(&c, t->ctr, sizeof(c), hipMemcpyDeviceToHost));
     c.adam_t = adam_t;
     c.step = step;
+    c.handoff_missed = 0;
     c.pw1 = std::pow((double)t->cfg.beta1, (double)adam_t);
     c.pw2 = std::pow((double)t->cfg.beta2, (double)adam_t);
     RP_CHECK_HIP(hipMemcpy(t->ctr, &c, sizeof(c), hipMemcpyHostToDevice));
@@ -1278,6 +1281,14 @@ rp_status train_get_last(trainer_t* t, float* q, float* q_next, float* y, float*
     RP_CHECK_HIP(hipMemcpy(&c, t->ctr, sizeof(c), hipMemcpyDeviceToHost));
     if (loss) *loss = c.loss;
     RP_REQUIRE_STATE(!c.handoff_missed, "train_get_last: a train step's workgroups missed a hand-over");
+    return RP_OK;
+}
+
+rp_status train_set_handoff_wait(trainer_t* t, uint64_t ticks, int break_pairing) {
+    RP_REQUIRE(t, "train_set_handoff_wait: null handle");
+    RP_REQUIRE(ticks <= (uint64_t)1 << 40, "train_set_handoff_wait: limit beyond 2^40 ticks");
+    t->handoff_ticks = ticks ? (long long)ticks : rp::kHandoffTicks;
+    t->handoff_break = break_pairing != 0;
     return RP_OK;
 }
 

@@ -90,7 +90,9 @@ struct RowArgs {
     // another inside the launch as handoff[i] = (seq << 32) | float bits; seq differs from launch
     // to launch, so a word left by an earlier launch is never taken for this one's.
     unsigned long long* handoff; // [B]
-    unsigned int seq;
+    unsigned int seq;            // what the sending workgroups stamp their words with
+    unsigned int seq_wait;       // what the waiting ones look for (the same, except in a test of the time limit)
+    long long handoff_ticks;     // longest wait, in ticks of the 100 MHz wall clock
     TrainCounters* ctr;
     const float* w;       // padded parameters
     const float* wt;      // the frozen target network's (Q(s', .) is computed with them), or null
@@ -168,6 +170,8 @@ struct trainer {
     unsigned int* pre;               // slots drawn ahead, 2 x (4 + B) words
     unsigned long long* handoff;     // [B] words one workgroup of the row kernel hands to another
     unsigned int launch_seq;         // number of the last row-kernel launch prepared (never 0)
+    long long handoff_ticks;         // longest wait of a workgroup for its partner (wall-clock ticks)
+    bool handoff_break;              // test of that limit: the waiting side expects a number nobody sends
     bool fused;                      // two-kernel step for small fp32 networks
     bool wide;                       // mixed-precision step on MFMA
     bool mid;                        // fp32 step on MFMA, one product per kernel
@@ -215,10 +219,13 @@ hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* bat
 hipError_t fused_init();                      // once, at trainer creation
 // The number that tells one launch of the row kernel from the others (never 0, the value of a
 // cleared hand-over word).
-inline unsigned int next_launch_seq(trainer* t) {
+inline void stamp_launch(trainer* t, RowArgs& a) {
     if (++t->launch_seq == 0) ++t->launch_seq;
-    return t->launch_seq;
+    a.seq = t->launch_seq;
+    a.seq_wait = t->handoff_break ? ~a.seq : a.seq;
+    a.handoff_ticks = t->handoff_ticks;
 }
+constexpr long long kHandoffTicks = 5000000;   // default limit: 50 ms
 void* fused_rows_func(bool target_network, unsigned int Dp, unsigned int B);   // the row kernel variant for a configuration
 // Dueling head: turn the gradient of the equivalent plain output layer (in g) into the head's
 // update and refresh that layer (and its bf16 / target copies).  No-op for a plain head.

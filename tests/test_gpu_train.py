@@ -611,6 +611,36 @@ def test_target_network_in_workgroups_of_its_own(B, D, H, A, batch, distinct, du
     assert_close([last["loss"]], [ref.loss], pr.rtol, "loss")
 
 
+def test_a_hand_over_that_never_arrives_ends_the_wait_and_is_reported(B):
+    """The wait of a workgroup for its partner is bounded.  With the waiting side told to look for
+    a launch number that nobody sends (a host-side switch: every kernel still runs to its end)
+    and a limit of 20 microseconds, the steps finish, the read-back calls report RP_ESTATE, and
+    after train_set_state and with the pairing restored the trainer agrees with the oracle again."""
+    rows = synth.experiences(400, 27, 30, 0.1, seed=71)
+    pr = Pair(B, capacity=300, D=27, H=64, A=30, batch=50, burn_in=100, seed=2, appends=2, target_sync=5)
+    tr = pr.trainer
+    pr.append_only(synth.take(rows, 0, 200))
+    assert pr.step(synth.take(rows, 200, 202), compare=True) == 0
+    p, (m, v, t, step) = tr.params(), tr.opt_state()
+    tr.set_handoff_wait(ticks=2000, break_pairing=True)
+    d = {k: torch.from_numpy(x).cuda() for k, x in synth.take(rows, 202, 210).items()}
+    assert tr.steps(4, d["s"], d["s_next"], d["a"], d["r"], d["term"]) == 4
+    torch.cuda.synchronize()
+    with pytest.raises(B.ReplayError) as err:
+        tr.last()
+    assert err.value.status == B.RP_ESTATE and "hand-over" in str(err.value)
+    with pytest.raises(B.ReplayError):
+        tr.opt_state()
+    # back to a known state (the ring took the eight rows; the oracle's ring follows)
+    part = synth.take(rows, 202, 210)
+    pr.ref_ring.append(part["s"], part["s_next"], part["a"], part["r"], part["term"])
+    tr.set_handoff_wait(ticks=0, break_pairing=False)
+    tr.set_state(p, m, v, t, step + 4)
+    tr.last()
+    for k in range(210, 230, 2):
+        assert pr.step(synth.take(rows, k, k + 2), compare=True) == 0
+
+
 @pytest.mark.parametrize("dtype,H,layered", [("f32", 64, False), ("f32", 64, True), ("bf16", 128, False)])
 def test_train_step_with_batches_without_duplicates(B, dtype, H, layered):
     """RP_DISTINCT replay under each kind of train step; with burn-in 10 and batch 40 the first
