@@ -287,6 +287,10 @@ rp_status train_get_last(trainer_t* tr, float* q, float* q_next, float* y, float
  * zeros in place of the target network's values, and the read-back calls return RP_ESTATE until
  * train_set_state (which clears the mark) is called.  Takes effect from the next step enqueued. */
 rp_status train_set_handoff_wait(trainer_t* tr, uint64_t ticks, int break_pairing);
+/* Test call.  Two-kernel step with a target network: whether the last executed step took
+ * max_a Q_target(s', a) of its experience 0 from the table that the step before it filled
+ * (*from_table = 1) or had it computed inside its own launch (0).  Synchronises. */
+rp_status train_get_target_source(trainer_t* tr, uint32_t* from_table);
 /* Number of GPU kernels one executed train step launches (graph nodes). */
 rp_status train_kernels_per_step(trainer_t* tr, uint32_t* n);
 

@@ -84,6 +84,7 @@ SYMBOLS = {
     "train_set_target": (_int, [_vp, _vp]),
     "train_kernels_per_step": (_int, [_vp, _vp]),
     "train_set_handoff_wait": (_int, [_vp, _u64, _int]),
+    "train_get_target_source": (_int, [_vp, _vp]),
     "rp_last_error": (C.c_char_p, []),
     "rp_version": (C.c_char_p, []),
 }
@@ -413,6 +414,11 @@ class Trainer:
 
     def set_handoff_wait(self, ticks=0, break_pairing=False):
         _check(lib().train_set_handoff_wait(self._h, int(ticks), int(bool(break_pairing))))
+
+    def target_from_table(self):
+        n = C.c_uint32()
+        _check(lib().train_get_target_source(self._h, C.byref(n)))
+        return bool(n.value)
 
     def kernels_per_step(self):
         n = C.c_uint32()

@@ -24,6 +24,7 @@ constexpr unsigned int kRowThreads = 1024;         // row kernel: 16 wavefronts
 constexpr unsigned int kRows = 4;          // experiences per workgroup of the row kernel ...
 constexpr unsigned int kSmallBatch = 512;  // ... and 2 for batches up to this size (no target network):
                                            // measured faster while the workgroups fit the 256 compute units
+constexpr unsigned int kSmallBatchSplit = 168;   // the same with a target network (three workgroups per group)
 constexpr unsigned int kChunk = 256;       // output columns the workgroup covers per pass
 constexpr size_t kRowLdsMax = 160 * 1024;  // dynamic LDS the row kernel may ask for (all of a CU's)
 constexpr unsigned int kPadK = 4;          // LDS row padding (floats) against bank conflicts
@@ -216,22 +217,37 @@ __device__ __forceinline__ float sum_part(const float* part, unsigned int slices
 // so R = 2 halves a workgroup's products at twice the workgroups: the choice for batches that
 // leave most compute units idle anyway.
 //
-// SPLIT: the frozen target network in workgroups of its own.  Workgroups come in pairs for four
-// experiences: the even one (lower number, so dispatched first) sends the four states s' through
-// the target network and hands max_a Q_target(s', a) to the odd one, which does everything else
-// for the four states s.  Both then fetch one network's weights and multiply one group of four
-// rows, like a workgroup of the step without a target network, and run side by side on
-// different compute units; the odd one waits (a bounded time) where it needs the maxima.
+// SPLIT: the frozen target network in workgroups of its own.  Workgroups come in threes for R
+// experiences (numbers 3 j, 3 j + 1, 3 j + 2; lower numbers are dispatched first):
+//   3 j      ends at once when a table that the previous launch filled holds this step's
+//            max_a Q_target(s', a) for all of its experiences; otherwise it sends their states s'
+//            through the target network now and hands the maxima over;
+//   3 j + 1  does everything for the states s of THIS step, and takes the maxima from the table
+//            or, for entries that are not valid for this step, from workgroup 3 j, for which it
+//            waits (a bounded time);
+//   3 j + 2  sends the states s' of the NEXT step's sample (a function of seed, step and ring
+//            size alone) through the target network and fills the table for the next launch,
+//            when the host says the target network stays as it is until then.
+// Each workgroup then fetches one network's weights and multiplies one group of four rows, like
+// a workgroup of the step without a target network, and they run side by side on different
+// compute units.  A table entry carries what it was computed for (sampling step, experiences ever
+// added, Adam steps, a count of calls that changed weights from outside): it is valid when those
+// are this step's.  Its row was read from the ring as it will be at that step: rows this step
+// appends come from the payload, rows the next step will overwrite make the entry invalid.
+constexpr unsigned int kNowSide = 0, kMainSide = 1, kAheadSide = 2;
+constexpr unsigned int kAheadWords = 8;   // step, total, Adam steps (two words each), outside changes, maximum
 template <bool SPLIT, int NR1, int R>
 __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
-    static_assert(R == 4 || (R == 2 && !SPLIT), "experiences per workgroup (split: per pair of workgroups)");
+    static_assert(R == 4 || R == 2, "experiences per workgroup (split: per three workgroups)");
     constexpr unsigned int NRW = SPLIT ? 4 : 2 * R;  // rows of a workgroup
     constexpr int MG = NRW / 4;                      // groups of four rows
     constexpr unsigned int PR = NRW;                 // rows of its MFMA groups
     extern __shared__ float lds[];
     touch_kernel_args<RowArgs>();
-    const unsigned int wg = SPLIT ? blockIdx.x >> 1 : blockIdx.x;
-    const bool target_side = SPLIT && !(blockIdx.x & 1u);   // (uniform over the workgroup)
+    const unsigned int wg = SPLIT ? blockIdx.x / 3u : blockIdx.x;
+    const unsigned int side = SPLIT ? blockIdx.x - 3u * wg : kMainSide;   // (uniform over the workgroup)
+    const bool target_side = side != kMainSide;
+    const bool ahead_side = SPLIT && side == kAheadSide;
     if (wg * R >= p.B) {
         // the extra workgroup of a replay that samples without duplicates: the next step's slots
         const unsigned long long ns = p.step + 1;
@@ -259,6 +275,9 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     float* b3s = b2s + H;                 // [Ap]
     unsigned int* meta = reinterpret_cast<unsigned int*>(b3s + Ap);   // [4][4]
     float* gs = reinterpret_cast<float*>(meta + 16);                 // [4]
+    unsigned int* ahead_s = reinterpret_cast<unsigned int*>(gs + 4); // [4][8]  split: this step's table entries
+    float* qn_s = reinterpret_cast<float*>(ahead_s + 4 * kAheadWords);   // [4][64] and their rows Q_target(s', .)
+    unsigned int* idle_s = reinterpret_cast<unsigned int*>(qn_s + 4 * 64);   // [1]  split: nothing to do for this workgroup
 
     const float* wsrc = target_side ? p.wt : p.w;
     const float* W1 = wsrc + p.oW1;
@@ -284,21 +303,49 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     constexpr unsigned int NL1 = 4u;            // wavefronts in layer 1
     const unsigned long long cap = p.g.capacity;
     const unsigned long long head = p.head;
-    const unsigned long long step = p.step;
+    const unsigned long long step = p.step + (ahead_side ? 1u : 0u);   // the step whose sample this workgroup takes
     const unsigned long long n = p.n_append;
-    const unsigned int size = p.size_after;
+    const unsigned int size = ahead_side ? p.next_size : p.size_after;
     const unsigned int i0 = wg * R;
     const unsigned int nrows = min((unsigned int)R, p.B - i0);
+    // word j of the table entry that is valid for this step (next: for the step after it)
+    auto key_word = [&](unsigned int j, bool next) {
+        const unsigned long long st = p.step + (next ? 1u : 0u), tot = next ? p.next_total_after : p.total_after,
+                                 ad = p.adam_t_after + (next ? 1u : 0u);
+        return j == 0 ? (unsigned int)st : j == 1 ? (unsigned int)(st >> 32) : j == 2 ? (unsigned int)tot
+             : j == 3 ? (unsigned int)(tot >> 32) : j == 4 ? (unsigned int)ad : j == 5 ? (unsigned int)(ad >> 32)
+             : p.epoch;
+    };
+    if constexpr (SPLIT) {
+        if (ahead_side && !p.ahead_on) return;
+        if (side == kNowSide) {
+            // nothing to do when the table holds this step's values for all of this workgroup's rows
+            // (the first wavefront holds all 8 x 4 words)
+            if (wave == 0) {
+                bool ok = !p.from_batch;
+                if (ok && lane < kAheadWords * nrows) {
+                    const unsigned int j = lane & (kAheadWords - 1u);
+                    const unsigned int word =
+                        p.ahead[((size_t)(p.step & 1u) * p.B + i0 + lane / kAheadWords) * kAheadWords + j];
+                    ok = j == kAheadWords - 1u || word == key_word(j, false);
+                }
+                const bool all = __ballot(ok) == ~0ull;
+                if (lane == 0) *idle_s = all ? 1u : 0u;
+            }
+            __syncthreads();
+            if (*idle_s) return;
+        }
+    }
     // words of a sampled row this workgroup needs: all 2 D + 3, or s and (a, r, terminal), or s'
     const unsigned int words = SPLIT ? (target_side ? D : D + 3u) : 2 * D + 3;
 
     // The state that follows this step is known up front (the host mirrors it exactly): one
     // thread stores it for the kernels and calls that read it later, off everyone's critical path.
-    if (blockIdx.x == 0 && tid == kRowThreads - 1) {
+    if (wg == 0 && side == kMainSide && tid == kRowThreads - 1) {
         unsigned long long h = head + n;
         if (h >= cap) h -= cap;
         p.g.state->head = h;
-        p.g.state->size = size;
+        p.g.state->size = p.size_after;
         p.g.state->total = p.total_after;
         p.ctr->adam_t = p.adam_t_after;
         p.ctr->c1 = p.c1_after;
@@ -322,6 +369,8 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
                 if (p.from_batch) {
                     myslot = i0 + lane;
                 } else {
+                    // (slots drawn a step ahead: only for replays that sample without duplicates,
+                    // which have no table of target values a step ahead)
                     const unsigned int* ahead = p.pre ? p.pre + ((step & 1u) ? p.pre_stride : 0u) : nullptr;
                     if (ahead && ahead[0] == (unsigned int)step && ahead[1] == (unsigned int)(step >> 32) &&
                         ahead[2] == size)
@@ -378,7 +427,15 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
             // the private copy (in the partial-sum buffer, which nothing uses before layer 2)
             float* Xp = part + wave * (PR * ldx);
             for (unsigned int e = lane; e < PR * ldx; e += 64u) Xp[e] = 0.f;
-            if (wave == 1 && lane < 16 && ((lane >> 2) >= nrows || (lane & 3u) == 3u)) meta[lane] = 0;
+            // (word 3 of a row's four: for the step after this one, whether the next step's
+            // append overwrites the row, so that its content is not known yet)
+            unsigned int unknown = 0;
+            if constexpr (SPLIT) {
+                unsigned long long off = (unsigned long long)__shfl(myslot, (int)((lane >> 2) & 3u), 64) + cap - head;
+                if (off >= cap) off -= cap;
+                unknown = ahead_side && (lane >> 2) < nrows && off >= n && off - n < n;
+            }
+            if (wave == 1 && lane < 16 && ((lane >> 2) >= nrows || (lane & 3u) == 3u)) meta[lane] = unknown;
 #pragma unroll
             for (int pass = 0; pass < NPASS; ++pass) {
                 const unsigned int e = lane + 64u * pass;
@@ -451,8 +508,22 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
             }
             load_cols4<16>(w2r, W2, H, cc, ks * q2, q2);
         } else {
+            // (main side, the four wavefronts of the TD phase: this step's table entries and rows,
+            // requested ahead of everything else and parked in LDS once they are there)
+            unsigned int aw = 0;
+            float aq = 0.f;
+            const bool looks_up = SPLIT && !target_side && wave >= 12 && wave - 12u < nrows && !p.from_batch;
+            if (looks_up) {
+                const size_t e = (size_t)(p.step & 1u) * p.B + i0 + (wave - 12u);
+                aw = p.ahead[e * kAheadWords + (lane & (kAheadWords - 1u))];
+                if (lane < Ap) aq = p.qn_ahead[e * Ap + lane];
+            }
             load_cols4<16>(w2r, W2, H, cc, ks * q2, q2);
             if constexpr (W3_EARLY) load_cols<16>(w3r, W3, Ap, lane, wave * s3, s3);
+            if (SPLIT && wave >= 12) {
+                if (lane < kAheadWords) ahead_s[(wave - 12u) * kAheadWords + lane] = looks_up ? aw : ~0u;
+                qn_s[(wave - 12u) * 64u + lane] = aq;
+            }
             // the other biases: the four wavefronts after layer 1's
             const unsigned int t4 = tid - 64u * NL1;
             if (t4 < H) b2s[t4] = wsrc[p.ob2 + t4];
@@ -526,6 +597,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     // the other wavefronts' requests and a store would queue up behind them.
     float td_qs = 0.f, td_qn = 0.f, td_y = 0.f, td_d = 0.f, td_li = 0.f, td_gr = 0.f;
     unsigned int td_ai = 0;
+    bool td_hit = false;   // split: the table held this step's value for the row
     if (wave >= 12) {
         const unsigned int r = wave - 12u;
         if (r < (unsigned int)R && lane < Ap) {
@@ -533,19 +605,36 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
             if constexpr (!SPLIT) td_qn = sum_part(part, 16, NRW, 64, R + r, lane) + b3s[lane];
         }
         if (SPLIT && target_side) {
-            // Q_target(s', .) of this row and its maximum, handed over in one 8-byte word that
-            // carries this launch's number (value and tag arrive together or not at all)
             if (r < nrows) {
                 const unsigned int i = i0 + r;
                 const float best = wave_max(lane < A ? td_qs : -INFINITY);
-                if (lane < Ap) p.Q[((size_t)p.B + i) * Ap + lane] = td_qs;
-                if (lane == 0)
-                    __hip_atomic_store(p.handoff + i, ((unsigned long long)p.seq << 32) | __float_as_uint(best),
-                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (ahead_side) {
+                    // Q_target(s', .) of this row and its maximum for the next step, with what they hold for
+                    const size_t e = (size_t)(step & 1u) * p.B + i;
+                    const bool known = meta[r * 4 + 3] == 0u;
+                    if (lane < Ap) p.qn_ahead[e * Ap + lane] = td_qs;
+                    if (lane < kAheadWords)
+                        p.ahead[e * kAheadWords + lane] = lane == kAheadWords - 1u ? __float_as_uint(best)
+                                                          : known ? key_word(lane, true) : ~0u;
+                } else {
+                    // ... for this step, handed over in one 8-byte word that carries this launch's
+                    // number (value and tag arrive together or not at all)
+                    if (lane < Ap) p.Q[((size_t)p.B + i) * Ap + lane] = td_qs;
+                    if (lane == 0)
+                        __hip_atomic_store(p.handoff + i, ((unsigned long long)p.seq << 32) | __float_as_uint(best),
+                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
             }
         } else if (r < nrows) {
             float best;
             if constexpr (SPLIT) {
+                const unsigned int j = lane & (kAheadWords - 1u);
+                td_hit = __ballot(j == kAheadWords - 1u || ahead_s[r * kAheadWords + j] == key_word(j, false)) == ~0ull;
+            }
+            if (SPLIT && td_hit) {
+                best = __uint_as_float(ahead_s[r * kAheadWords + kAheadWords - 1u]);
+                td_qn = qn_s[r * 64u + lane];
+            } else if constexpr (SPLIT) {
                 // wait for the other workgroup of the pair: it was dispatched before this one and
                 // waits for nothing, so the word arrives; the time limit only guards against a
                 // launch that breaks that order (then the step is marked as failed)
@@ -591,10 +680,11 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
         const unsigned int i = i0 + wave - 12u;
         if (lane < Ap) {
             p.Q[(size_t)i * Ap + lane] = td_qs;
-            if constexpr (!SPLIT) p.Q[((size_t)p.B + i) * Ap + lane] = td_qn;
+            if (!SPLIT || td_hit) p.Q[((size_t)p.B + i) * Ap + lane] = td_qn;
             p.dQ[(size_t)i * Ap + lane] = lane == td_ai ? td_gr : 0.f;
         }
         if (lane == 0) {
+            if (SPLIT && i == 0) p.ctr->from_table = td_hit ? 1u : 0u;
             p.y[i] = td_y;
             p.delta[i] = td_d;
             p.lossi[i] = td_li;
@@ -945,7 +1035,8 @@ __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
 
 size_t row_kernel_lds(unsigned int Dp, unsigned int H, unsigned int Ap) {
     const size_t ldx = Dp + kPadK, ldh = H + kPadK, ldq = Ap + kPadK;
-    return (8 * ldx + 8 * ldh * 2 + 8 * ldq + 4 * ldh + 16 * 8 * kChunk + (2 * H + Ap) + 16 + 4) *
+    return (8 * ldx + 8 * ldh * 2 + 8 * ldq + 4 * ldh + 16 * 8 * kChunk + (2 * H + Ap) + 16 + 4 +
+            4 * kAheadWords + 4 * 64 + 4) *
            sizeof(float);
 }
 
@@ -973,7 +1064,9 @@ hipError_t fused_init() {
                              reinterpret_cast<const void*>(fused_rows_kernel<false, 8, 2>),
                              reinterpret_cast<const void*>(fused_rows_kernel<false, 16, 2>),
                              reinterpret_cast<const void*>(fused_rows_kernel<true, 8, 4>),
-                             reinterpret_cast<const void*>(fused_rows_kernel<true, 16, 4>)};
+                             reinterpret_cast<const void*>(fused_rows_kernel<true, 16, 4>),
+                             reinterpret_cast<const void*>(fused_rows_kernel<true, 8, 2>),
+                             reinterpret_cast<const void*>(fused_rows_kernel<true, 16, 2>)};
     for (const void* k : kernels) {
         hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kRowLdsMax);
         if (e != hipSuccess) return e;
@@ -985,14 +1078,18 @@ hipError_t fused_init() {
 // (every workgroup fetches all the weights, so more workgroups than that only add traffic); with
 // a target network four per pair of workgroups.
 unsigned int fused_rows_per_group(bool target_network, unsigned int B) {
-    return !target_network && B <= kSmallBatch ? 2u : kRows;
+    return B <= (target_network ? kSmallBatchSplit : kSmallBatch) ? 2u : kRows;
 }
 
 void* fused_rows_func(bool target_network, unsigned int Dp, unsigned int B) {
     const bool narrow = Dp <= 32;
-    if (target_network)
+    if (target_network) {
+        if (fused_rows_per_group(true, B) == 2)
+            return narrow ? reinterpret_cast<void*>(fused_rows_kernel<true, 8, 2>)
+                          : reinterpret_cast<void*>(fused_rows_kernel<true, 16, 2>);
         return narrow ? reinterpret_cast<void*>(fused_rows_kernel<true, 8, 4>)
                       : reinterpret_cast<void*>(fused_rows_kernel<true, 16, 4>);
+    }
     if (fused_rows_per_group(false, B) == 2)
         return narrow ? reinterpret_cast<void*>(fused_rows_kernel<false, 8, 2>)
                       : reinterpret_cast<void*>(fused_rows_kernel<false, 16, 2>);
@@ -1020,7 +1117,6 @@ hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* bat
         a.total_after = r->total + a.n_append;
         set_adam_step(a, t->host_adam_t + 1, t->cfg.beta1, t->cfg.beta2);
     }
-    a.handoff = t->handoff;
     stamp_launch(t, a);
     a.ctr = t->ctr;
     a.w = t->w;
@@ -1042,8 +1138,8 @@ hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* bat
     a.pre = ahead ? t->pre : nullptr;
     a.pre_stride = 4u + t->B;
     const unsigned int per = fused_rows_per_group(t->wt != nullptr, t->B);
-    // (with a target network: a pair of workgroups for every four experiences)
-    const unsigned int blocks = (t->B + per - 1) / per * (t->wt ? 2u : 1u) + (ahead ? 1u : 0u);
+    // (with a target network: three workgroups for every four experiences)
+    const unsigned int blocks = (t->B + per - 1) / per * (t->wt ? 3u : 1u) + (ahead ? 1u : 0u);
     hipError_t e = hipSuccess;
     void* kargs[] = {&a};
     e = hipLaunchKernel(fused_rows_func(t->wt != nullptr, t->Dp, t->B), dim3(blocks), dim3(kRowThreads), kargs,

@@ -260,7 +260,7 @@ namespace {
 
 struct WsLayout {
     size_t ctr, w, g, m, v, wt, w2t, wb, wbt, X, act, rew, term, idx, H1, H2, Q, y, delta, lossi, dQ, dZ2, dZ1,
-        pre, handoff, total;
+        pre, handoff, ahead, qn_ahead, total;
     // mixed-precision step on MFMA
     size_t W1T, W2b, W2T, W3T, W1Tt, W2Tt, W3Tt, XT, H1T, H2T, dQTh, dQTl, dZ2T, dZ1T, part3, part1, part2;
     unsigned int Dp, Ap, Bp;
@@ -323,6 +323,8 @@ bool ws_layout(const train_config* c, WsLayout* L) {
     L->dZ1 = take(B * H * L->elem);
     L->pre = take(2 * (4 + B) * 4);
     L->handoff = take(c->target_sync ? B * 8 : 0);
+    L->ahead = take(c->target_sync ? 2 * B * 8 * 4 : 0);
+    L->qn_ahead = take(c->target_sync ? 2 * B * L->Ap * 4 : 0);
     // the MFMA mixed-precision step exists for two hidden layers of one width
     const bool mixed = c->param_dtype == RP_BF16 && H == G;
     const size_t Bp = align_up(B, 128), Dx = align_up(D + 1, 32);
@@ -718,8 +720,8 @@ void set_payload_args(trainer* t, const Payload& src, unsigned int k) {
         t->row_args.size_after = (unsigned int)(size + n > cap ? cap : size + n);
         t->row_args.next_size = (unsigned int)(size + 2 * n > cap ? cap : size + 2 * n);
         t->row_args.total_after = total + n;
-        rp::stamp_launch(t, t->row_args);
         rp::set_adam_step(t->row_args, t->host_adam_t + k + 1, t->cfg.beta1, t->cfg.beta2);
+        rp::stamp_launch(t, t->row_args);
     } else {
         t->append_args.src = src;
         t->append_args.pos = RingPos{head, size, total};
@@ -880,6 +882,9 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
     t->dZ1 = ws + L.dZ1;
     t->pre = reinterpret_cast<unsigned int*>(ws + L.pre);
     t->handoff = reinterpret_cast<unsigned long long*>(ws + L.handoff);
+    t->ahead = reinterpret_cast<unsigned int*>(ws + L.ahead);
+    t->qn_ahead = reinterpret_cast<float*>(ws + L.qn_ahead);
+    t->epoch = 1;
     t->launch_seq = 0;
     t->handoff_ticks = rp::kHandoffTicks;
     t->handoff_break = false;
@@ -1083,8 +1088,8 @@ rp_status train_step_batch(trainer_t* t, const void* s, const void* s_next, cons
         t->row_args.step = t->host_step;
         t->row_args.size_after = (unsigned int)rpl->size;
         t->row_args.total_after = rpl->total;
-        rp::stamp_launch(t, t->row_args);
         rp::set_adam_step(t->row_args, t->host_adam_t + 1, t->cfg.beta1, t->cfg.beta2);
+        rp::stamp_launch(t, t->row_args);
         RP_CHECK_HIP(hipGraphExecKernelNodeSetParams(t->graph_exec, t->payload_node[0],
                                                      &t->payload_np[0]));
         RP_CHECK_HIP(hipGraphLaunch(t->graph_exec, st));
@@ -1176,6 +1181,7 @@ rp_status train_get_target(trainer_t* t, float* params) {
 rp_status train_set_target(trainer_t* t, const float* params) {
     RP_REQUIRE(t && params, "train_set_target: null argument");
     RP_REQUIRE(t->wt, "train_set_target: this trainer has no target network (target_sync = 0)");
+    if (++t->epoch == 0) ++t->epoch;   // target values computed a step ahead no longer hold
     std::vector<float> pad;
     RP_CHECK_HIP(hipDeviceSynchronize());
     rp::pad_params(t, params, pad);
@@ -1222,6 +1228,7 @@ rp_status train_get_opt_state(trainer_t* t, float* m, float* v, uint64_t* adam_t
 rp_status train_set_state(trainer_t* t, const float* params, const float* m, const float* v,
                           uint64_t adam_t, uint64_t step) {
     RP_REQUIRE(t && params, "train_set_state: null argument");
+    if (++t->epoch == 0) ++t->epoch;
     std::vector<float> pad;
     RP_CHECK_HIP(hipDeviceSynchronize());
     rp::pad_params(t, params, pad);
@@ -1289,6 +1296,15 @@ rp_status train_set_handoff_wait(trainer_t* t, uint64_t ticks, int break_pairing
     RP_REQUIRE(ticks <= (uint64_t)1 << 40, "train_set_handoff_wait: limit beyond 2^40 ticks");
     t->handoff_ticks = ticks ? (long long)ticks : rp::kHandoffTicks;
     t->handoff_break = break_pairing != 0;
+    return RP_OK;
+}
+
+rp_status train_get_target_source(trainer_t* t, uint32_t* from_table) {
+    RP_REQUIRE(t && from_table, "train_get_target_source: null argument");
+    RP_CHECK_HIP(hipDeviceSynchronize());
+    TrainCounters c;
+    RP_CHECK_HIP(hipMemcpy(&c, t->ctr, sizeof(c), hipMemcpyDeviceToHost));
+    *from_table = c.from_table;
     return RP_OK;
 }
 

@@ -40,7 +40,8 @@ struct TrainCounters {
     float loss;                 // mean loss of the last step
     unsigned int handoff_missed;   // set when a workgroup's bounded wait for another one ran out
     double pw1, pw2;            // beta1^t, beta2^t for t = adam_t (kept by the steps that advance t on the device)
-    unsigned int pad_[4];
+    unsigned int from_table;    // last step, experience 0: target value taken from the table filled a step ahead
+    unsigned int pad_[3];
 };
 static_assert(sizeof(TrainCounters) == 64, "one line");
 
@@ -93,6 +94,15 @@ struct RowArgs {
     unsigned int seq;            // what the sending workgroups stamp their words with
     unsigned int seq_wait;       // what the waiting ones look for (the same, except in a test of the time limit)
     long long handoff_ticks;     // longest wait, in ticks of the 100 MHz wall clock
+    // ... and from one launch to the next: table[parity of the step][i] = eight words (the step the
+    // entry holds for: sampling step, experiences ever added, Adam steps, each after that step, two
+    // words each; count of calls that changed weights from outside; the maximum), with the rows
+    // Q_target(s'_i, .) beside it.
+    unsigned int* ahead;         // [2][B][8]
+    float* qn_ahead;             // [2][B][Ap]
+    unsigned int ahead_on;       // fill the table for the next step (the target network stays as it is until then)
+    unsigned int epoch;          // calls that changed weights or counters from outside, so far
+    unsigned long long next_total_after;   // experiences ever added, after the next step's append
     TrainCounters* ctr;
     const float* w;       // padded parameters
     const float* wt;      // the frozen target network's (Q(s', .) is computed with them), or null
@@ -171,6 +181,9 @@ struct trainer {
     unsigned long long* handoff;     // [B] words one workgroup of the row kernel hands to another
     unsigned int launch_seq;         // number of the last row-kernel launch prepared (never 0)
     long long handoff_ticks;         // longest wait of a workgroup for its partner (wall-clock ticks)
+    unsigned int* ahead;             // target values a step ahead, 2 x B x 8 words ...
+    float* qn_ahead;                 // ... and 2 x B x Ap
+    unsigned int epoch;              // calls that changed weights or counters from outside (never 0)
     bool handoff_break;              // test of that limit: the waiting side expects a number nobody sends
     bool fused;                      // two-kernel step for small fp32 networks
     bool wide;                       // mixed-precision step on MFMA
@@ -219,11 +232,21 @@ hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* bat
 hipError_t fused_init();                      // once, at trainer creation
 // The number that tells one launch of the row kernel from the others (never 0, the value of a
 // cleared hand-over word).
+// ... and what the target network's workgroups need to know about the step after this one.
+// Call with the step's other fields (n_append, from_batch, total_after, adam_t_after) in place.
 inline void stamp_launch(trainer* t, RowArgs& a) {
     if (++t->launch_seq == 0) ++t->launch_seq;
     a.seq = t->launch_seq;
     a.seq_wait = t->handoff_break ? ~a.seq : a.seq;
     a.handoff_ticks = t->handoff_ticks;
+    a.handoff = t->handoff;
+    a.ahead = t->ahead;
+    a.qn_ahead = t->qn_ahead;
+    a.epoch = t->epoch;
+    a.next_total_after = a.total_after + a.n_append;
+    // the next step finds the target network as this launch does unless this step's update syncs it
+    a.ahead_on = t->wt && !a.from_batch && t->rp_->cfg.sampling == RP_WITH_REPLACEMENT &&
+                 a.adam_t_after % t->cfg.target_sync != 0;
 }
 constexpr long long kHandoffTicks = 5000000;   // default limit: 50 ms
 void* fused_rows_func(bool target_network, unsigned int Dp, unsigned int B);   // the row kernel variant for a configuration

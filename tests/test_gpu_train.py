@@ -580,15 +580,16 @@ def test_frozen_target_network(B, dtype, H, batch, layered, kernels):
 
 @pytest.mark.parametrize("D,H,A,batch,distinct,dueling", [
     (27, 256, 30, 128, False, False),    # the paper-shaped step
-    (60, 128, 9, 1030, False, False),    # wide states, 258 pairs of workgroups (more than compute units), ragged
+    (60, 128, 9, 1030, False, False),    # wide states, 258 threes of workgroups (more than compute units), ragged
     (27, 64, 30, 131, True, True),       # the extra workgroup that draws the next step's slots, ragged; dueling head
-    (5, 192, 64, 3, False, False),       # one pair only, three of its four rows; widest action set
+    (5, 192, 64, 3, False, False),       # two groups of workgroups, the second with one row; widest action set
 ])
 def test_target_network_in_workgroups_of_its_own(B, D, H, A, batch, distinct, dueling):
     """Two-kernel step with a frozen target network: the states s' go through the target
-    network in workgroups of their own, which hand max_a Q_target(s', a) over to the workgroups
-    that hold s inside the same launch.  Q(s', .), targets, TD errors and the update against the
-    oracle on every step, across several syncs; then a batch given by the caller."""
+    network in workgroups of their own, which pass max_a Q_target(s', a) to the workgroups that
+    hold s (through a table filled a step ahead, or inside the same launch).  Q(s', .), targets,
+    TD errors and the update against the oracle on every step, across several syncs; then a batch
+    given by the caller."""
     rows = synth.experiences(1700, D, A, 0.1, seed=61)
     pr = Pair(B, capacity=1500, D=D, H=H, A=A, batch=batch, burn_in=1100, seed=13, appends=4,
               target_sync=3, distinct=distinct, dueling=dueling, lr=1e-3)
@@ -609,6 +610,51 @@ def test_target_network_in_workgroups_of_its_own(B, D, H, A, batch, distinct, du
     assert_close(last["Qn"], ref.Qn, pr.rtol, "Q_target(s',.)")
     assert_close(last["y"], ref.y, pr.rtol, "targets")
     assert_close([last["loss"]], [ref.loss], pr.rtol, "loss")
+
+
+@pytest.mark.parametrize("capacity", [5000, 70])
+def test_target_values_computed_a_step_ahead(B, capacity):
+    """Two-kernel step with a target network: workgroups of a step's launch send the NEXT step's
+    sampled states s' through the target network and leave max_a Q_target(s', a) in a table; the
+    next step takes them from there unless something changed in between.  Every step against the
+    oracle, and for experience 0 of each step where its value came from: the table, except after
+    a step that synced the target network, for a row that the step's own append wrote, after an
+    append from outside, after train_set_target, after a step on a given batch, and on the first
+    step.  With 70 slots for batches of 64 most groups of four mix both sources."""
+    D, H, A, batch, per, sync = 27, 64, 30, 64, 2, 6
+    rows = synth.experiences(400, D, A, 0.1, seed=81)
+    pr = Pair(B, capacity=capacity, D=D, H=H, A=A, batch=batch, burn_in=64, seed=17, appends=per,
+              target_sync=sync, lr=1e-3)
+    tr = pr.trainer
+    pr.append_only(synth.take(rows, 0, 64))
+    at = [64]
+
+    def step_and_source(expect_table):
+        head = pr.gpu_ring.state()[0]
+        assert pr.step(synth.take(rows, at[0], at[0] + per), compare=True) == 0
+        at[0] += per
+        slot0 = int(tr.last()["idx"][0])
+        own_append = (slot0 - head) % capacity < per
+        t_after = tr.opt_state()[2]
+        assert tr.target_from_table() == (expect_table and not own_append), (at[0], slot0, head)
+        return t_after % sync != 0       # whether the step after this one may use the table
+
+    ok = step_and_source(False)                      # first step: nothing in the table
+    for _ in range(20):                              # three syncs on the way
+        ok = step_and_source(ok)
+    pr.append_only(synth.take(rows, at[0], at[0] + 3)); at[0] += 3
+    ok = step_and_source(False)                      # experiences added from outside
+    ok = step_and_source(ok)
+    tr.set_target(synth.init_params(D, H, A, 77))
+    ok = step_and_source(False)                      # target network replaced from outside
+    ok = step_and_source(ok)
+    given = synth.experiences(batch, D, A, 0.1, seed=82)
+    d = {k: torch.from_numpy(v).cuda() for k, v in given.items()}
+    assert tr.step_batch(d["s"], d["s_next"], d["a"], d["r"], d["term"]) == 0
+    ok = step_and_source(False)                      # a step on a given batch in between
+    for _ in range(8):
+        ok = step_and_source(ok)
+    assert pr.gpu_ring.state() == pr.ref_ring.state()
 
 
 def test_a_hand_over_that_never_arrives_ends_the_wait_and_is_reported(B):
