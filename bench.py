@@ -32,15 +32,15 @@ P_CFG = dict(capacity=1_000_000, D=27, A=30, B=128, H=256, burn_in=50_000, p_ter
 W_CFG = dict(capacity=4_000_000, D=27, A=30, B=4096, H=1024, p_term=0.005, lr=1e-4, appends=64)
 L_CFG = dict(capacity=200_000, D=84 * 84 * 4, p_term=0.001)
 GATHER_BATCHES = [32, 128, 512, 2048, 8192, 65536]
-# HBM bytes per launch of sample_gather_pair_kernel<4, 1, 0> at batch 65,536 from rocprofv3 PMC runs
-# (FETCH_SIZE 8,180.7 KiB x 2.000 + WRITE_SIZE 14,720.0 KiB x 1.000, the factors being what the
+# HBM bytes per launch of sample_gather_pair_kernel<4, 2, 0> at batch 65,536 from rocprofv3 PMC runs
+# (FETCH_SIZE 8,186.3 KiB x 2.000 + WRITE_SIZE 14,656.5 KiB x 1.000, the factors being what the
 # same counters read for the 256 MiB plain copy of the copy_calibration leg); the runs and the
 # table are in profiles/gather_kernels_hbm_traffic_pmc.txt.  Set to None when that kernel changes.
-GATHER_65536_HBM_BYTES = (8180.7 * 2.000 + 14720.0 * 1.000) * 1024
-GATHER_8M_65536_HBM_BYTES = (8209.9 * 2.000 + 14720.0 * 1.000) * 1024
-GATHER_KERNEL = "sample_gather_pair_kernel<4, 1, 0>"
+GATHER_65536_HBM_BYTES = (8186.3 * 2.000 + 14656.5 * 1.000) * 1024
+GATHER_8M_65536_HBM_BYTES = (8215.9 * 2.000 + 14657.0 * 1.000) * 1024
+GATHER_KERNEL = "sample_gather_pair_kernel<4, 2, 0>"
 # the same for sample_gather_chain_kernel<1, 0> at batch 256
-LARGE_256_HBM_BYTES = (7157.6 * 2.000 + 56461.2 * 1.000) * 1024
+LARGE_256_HBM_BYTES = (7154.9 * 2.000 + 56461.1 * 1.000) * 1024
 # and for append_pair_bulk_kernel<unsigned int> at 65,536 rows (profiles/append_bulk_kernel_hbm_traffic_pmc.txt)
 APPEND_65536_HBM_BYTES = (7314.5 * 2.000 + 16384.0 * 1.000) * 1024
 # and summed over the eight kernels of one wide step (profiles/wide_step_kernels_hbm_traffic_pmc.txt)

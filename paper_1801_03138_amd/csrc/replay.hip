@@ -34,6 +34,7 @@ void set_error(const char* fmt, ...) {
 namespace {
 
 constexpr unsigned int kThreads = 256;
+constexpr unsigned int kResidentBlocks = 8 * 256;   // blocks of kThreads the chip's 256 compute units hold at once
 constexpr unsigned int kMaxPairRowBytes = 32768;  // a gathered PAIR row is staged through LDS
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
@@ -739,9 +740,14 @@ hipError_t launch_sample_gather(const RingGeom& g, unsigned long long seed,
     if (g.layout == RP_PAIR) {
         const unsigned int lane_shift = pair_lane_shift(g);
         const unsigned int rows_per_pass = kThreads >> lane_shift;
-        // rows per thread: 1, 2 and 4 were tried on 256-byte rows at batches 2,048 to 65,536;
-        // 1 (sixteen rows per block, eight blocks resident per CU) was fastest throughout
-        const unsigned int U = 1;
+        // rows per thread: one while all blocks are resident at once (eight per compute unit;
+        // measured on 256-byte rows: a second row adds 0.7 us to a block's chain of draw, load
+        // and store, which is all a small batch's launch consists of), more for batches that
+        // would otherwise come in several waves of blocks (65,536 rows: 8.0 us against 8.5)
+        unsigned int U = 1;
+        while (U < 4 && (batch + U * rows_per_pass - 1) / (U * rows_per_pass) > kResidentBlocks &&
+               (size_t)2 * U * rows_per_pass * g.row_bytes <= 32 * 1024)   // (the rows wait in LDS)
+            U *= 2;
         const unsigned int R = U * rows_per_pass;
         const unsigned int blocks = (batch + R - 1) / R;
         const int mode = drawn ? kDrawGiven : distinct ? kDrawDistinct : kDrawUniform;
@@ -750,11 +756,17 @@ hipError_t launch_sample_gather(const RingGeom& g, unsigned long long seed,
 #define RP_LAUNCH_PAIR(E, UU, MM)                                                                  \
     hipLaunchKernelGGL((sample_gather_pair_kernel<E, UU, MM>), dim3(blocks), dim3(kThreads), lds,   \
                        stream, g, seed, step_value, step_ptr, size_value, batch, lane_shift, out, drawn)
+#define RP_LAUNCH_PAIR_U(E, UU)                                             \
+    do {                                                                   \
+        if (mode == kDrawGiven) RP_LAUNCH_PAIR(E, UU, kDrawGiven);         \
+        else if (mode == kDrawDistinct) RP_LAUNCH_PAIR(E, UU, kDrawDistinct); \
+        else RP_LAUNCH_PAIR(E, UU, kDrawUniform);                          \
+    } while (0)
 #define RP_LAUNCH_PAIR_E(E)                                                \
     do {                                                                   \
-        if (mode == kDrawGiven) RP_LAUNCH_PAIR(E, 1, kDrawGiven);          \
-        else if (mode == kDrawDistinct) RP_LAUNCH_PAIR(E, 1, kDrawDistinct); \
-        else RP_LAUNCH_PAIR(E, 1, kDrawUniform);                           \
+        if (U == 1) RP_LAUNCH_PAIR_U(E, 1);                                \
+        else if (U == 2) RP_LAUNCH_PAIR_U(E, 2);                           \
+        else RP_LAUNCH_PAIR_U(E, 4);                                       \
     } while (0)
         if (g.elem_bytes == 4)
             RP_LAUNCH_PAIR_E(4);
@@ -763,6 +775,7 @@ hipError_t launch_sample_gather(const RingGeom& g, unsigned long long seed,
         else
             RP_LAUNCH_PAIR_E(1);
 #undef RP_LAUNCH_PAIR_E
+#undef RP_LAUNCH_PAIR_U
 #undef RP_LAUNCH_PAIR
     } else {
         const unsigned int vectors = (g.state_bytes + 15u) >> 4;

@@ -234,7 +234,8 @@ def test_paper_shaped_ring_full_size(B):
     for p in probe:
         g, o = gpu.read_rows(p, 1), ref.read(p, 1)
         assert all(np.array_equal(x.view(np.uint8), y.view(np.uint8)) for x, y in zip(g, o))
-    for step, batch in enumerate([32, 128, 512, 2048, 8192, 65536]):
+    # (from 32,769 rows on a thread of the gather takes two rows, from 65,537 four: ragged on both sides)
+    for step, batch in enumerate([32, 128, 512, 2048, 8192, 32768, 32769, 65536, 65537, 150_001]):
         st, out = gpu.sample_gather(step, batch)
         assert st == 0
         _assert_batch_equal(out, ref, ref.sample(0, step, batch))
