@@ -5,9 +5,10 @@
 // batch: its slot draw, its gather, the forward pass on s and s', the TD target, and the
 // backward pass down to the pre-activation gradients.  Kernel 1 does all of that for two or four
 // experiences per workgroup, keeping activations in LDS and streaming the weights through
-// 4x4x1 fp32 MFMA (four rows per instruction, so a four-row tile is not padded).  It also
-// appends the step's new experiences.  A frozen target network gets workgroups of its own in
-// the same launch, which hand max_a Q_target(s', a) over to the workgroups that hold s.  Only the weight gradients reduce over the batch:
+// 4x4x1 fp32 MFMA (four rows per instruction, so a four-row tile is not padded).  One more
+// workgroup of the launch appends the step's new experiences, and a frozen target network gets
+// workgroups of its own, which compute max_a Q_target(s', a) a step ahead of the workgroups
+// that hold s.  Only the weight gradients reduce over the batch:
 // kernel 2 forms them tile by tile and applies the optimizer to each tile as soon as it is
 // complete, so gradients never make a round trip through HBM before the update.
 //
@@ -249,7 +250,25 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
     const bool target_side = side != kMainSide;
     const bool ahead_side = SPLIT && side == kAheadSide;
     if (wg * R >= p.B) {
-        // the extra workgroup of a replay that samples without duplicates: the next step's slots
+        // Extra workgroups, after those of the batch.  First (when the trainer appends at all): the
+        // one that writes the step's new experiences into the ring.  No workgroup reads those
+        // slots from the ring in this launch (they take such rows from the payload), so nothing
+        // waits for it; it has compute units to itself, and a payload in host memory, which takes
+        // microseconds to arrive, holds up none of the batch's workgroups.
+        const unsigned int extra = blockIdx.x - (SPLIT ? 3u : 1u) * ((p.B + R - 1u) / R);
+        if (p.append_group && extra == 0) {
+            const unsigned long long cap = p.g.capacity, n = p.n_append;
+            const unsigned int rw = p.g.row_bytes >> 2;
+            for (unsigned long long e = threadIdx.x; e < n * rw; e += kRowThreads) {
+                const unsigned long long k = e / rw;
+                const unsigned int w = (unsigned int)(e - k * rw);
+                unsigned long long slot = p.head + k;
+                if (slot >= cap) slot -= cap;
+                reinterpret_cast<unsigned int*>(p.g.rows + slot * p.g.row_bytes)[w] = staged_word(p, k, w);
+            }
+            return;
+        }
+        // then that of a replay that samples without duplicates: the next step's slots
         const unsigned long long ns = p.step + 1;
         unsigned int* dst = p.pre + ((ns & 1u) ? p.pre_stride : 0u);
         for (unsigned int i = threadIdx.x; i < p.B; i += kRowThreads)
@@ -528,19 +547,6 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
             const unsigned int t4 = tid - 64u * NL1;
             if (t4 < H) b2s[t4] = wsrc[p.ob2 + t4];
             if (t4 < Ap) b3s[t4] = wsrc[p.ob3 + t4];
-        }
-        // The last workgroup also writes the new experiences into the ring.  No workgroup reads
-        // those slots from the ring in this launch (see above), so this can go out right away and
-        // its latency is hidden behind the rest of the kernel.
-        if (i0 + R >= p.B && n && !target_side) {
-            const unsigned int rw = p.g.row_bytes >> 2;
-            for (unsigned long long e = tid; e < n * rw; e += kRowThreads) {
-                const unsigned long long k = e / rw;
-                const unsigned int w = (unsigned int)(e - k * rw);
-                unsigned long long slot = head + k;
-                if (slot >= cap) slot -= cap;
-                reinterpret_cast<unsigned int*>(p.g.rows + slot * p.g.row_bytes)[w] = staged_word(p, k, w);
-            }
         }
         lds_barrier();
     }
@@ -1139,7 +1145,8 @@ hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* bat
     a.pre_stride = 4u + t->B;
     const unsigned int per = fused_rows_per_group(t->wt != nullptr, t->B);
     // (with a target network: three workgroups for every four experiences)
-    const unsigned int blocks = (t->B + per - 1) / per * (t->wt ? 3u : 1u) + (ahead ? 1u : 0u);
+    a.append_group = t->cfg.appends_per_step ? 1u : 0u;
+    const unsigned int blocks = (t->B + per - 1) / per * (t->wt ? 3u : 1u) + a.append_group + (ahead ? 1u : 0u);
     hipError_t e = hipSuccess;
     void* kargs[] = {&a};
     e = hipLaunchKernel(fused_rows_func(t->wt != nullptr, t->Dp, t->B), dim3(blocks), dim3(kRowThreads), kargs,

@@ -71,6 +71,7 @@ struct RowArgs {
     RingGeom g;
     unsigned long long seed;
     unsigned int n_append;
+    unsigned int append_group;   // the launch has a workgroup for the append (trainers that append at all)
     Payload src;          // this step's new experiences
     Payload batch;        // from_batch: the batch itself, given by the caller instead of sampled
     unsigned int from_batch;
