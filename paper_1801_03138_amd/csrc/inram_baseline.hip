@@ -28,6 +28,7 @@ inline void philox4x32_10_host(uint32_t c[4], uint32_t k0, uint32_t k1) {
 }
 
 constexpr unsigned int kSlots = 16;   // pinned staging batches in flight
+constexpr size_t kCopyPiece = 16 * 1024;   // bytes per host-to-device copy call
 
 }  // namespace
 
@@ -171,7 +172,16 @@ rp_status inram_train_step(inram_replay_t* h, trainer_t* tr, void* hip_stream) {
             pt[i] = h->term[idx];
         }
     }
-    RP_CHECK_HIP(hipMemcpyAsync(h->dev, p, h->slot_bytes, hipMemcpyHostToDevice, st));
+    // The runtime copies up to 16 KB with a kernel on the stream itself (4 us per call); larger
+    // transfers take another path that costs 10 us and orders itself against the stream's
+    // kernels far more slowly (measured: 65 us per step at batch 128 with one 29 KB copy, 41 us
+    // with two copies of half the size; at batch 256, 58 KB, one copy is the faster way, 54 us
+    // against 61 us in four).  The comparison system gets the faster way at every size.
+    const size_t piece = h->slot_bytes <= 2 * kCopyPiece ? kCopyPiece : h->slot_bytes;
+    for (size_t at = 0; at < h->slot_bytes; at += piece) {
+        const size_t len = h->slot_bytes - at < piece ? h->slot_bytes - at : piece;
+        RP_CHECK_HIP(hipMemcpyAsync(h->dev + at, p + at, len, hipMemcpyHostToDevice, st));
+    }
     RP_CHECK_HIP(hipEventRecord(h->copied[slot], st));
     h->live[slot] = true;
     h->next_slot += 1;
