@@ -657,6 +657,51 @@ def test_target_values_computed_a_step_ahead(B, capacity):
     assert pr.gpu_ring.state() == pr.ref_ring.state()
 
 
+@pytest.mark.parametrize("seed,distinct,dueling", [(1, False, False), (2, False, True), (3, True, False)])
+def test_target_network_under_a_random_sequence_of_calls(B, seed, distinct, dueling):
+    """Whatever happens between two train steps, the step after it must use the target network
+    and the rows as they are then: a seeded random sequence of train steps, steps on given
+    batches, appends from outside, new target networks, rewound counters and runs of steps
+    queued without a synchronisation, every compared step against the oracle (ring of 90
+    slots, batch 37: ragged groups, rows that the steps' own appends overwrite)."""
+    D, H, A, batch, per, cap = 27, 64, 30, 37, 3, 90
+    rng = np.random.default_rng(1000 + seed)
+    rows = synth.experiences(4000, D, A, 0.1, seed=90 + seed)
+    pr = Pair(B, capacity=cap, D=D, H=H, A=A, batch=batch, burn_in=40, seed=seed, appends=per,
+              target_sync=int(rng.choice([2, 4, 7])), distinct=distinct, dueling=dueling, lr=1e-3)
+    tr = pr.trainer
+    at = [0]
+
+    def take(n):
+        part = synth.take(rows, at[0], at[0] + n)
+        at[0] += n
+        return part
+
+    pr.append_only(take(60))
+    for _ in range(70):
+        op = rng.choice(["step", "step", "step", "batch", "append", "target", "rewind", "run"])
+        if op == "step":
+            assert pr.step(take(per), compare=True) == 0
+        elif op == "batch":
+            given = synth.experiences(batch, D, A, 0.1, seed=int(rng.integers(1 << 30)))
+            d = {k: torch.from_numpy(v).cuda() for k, v in given.items()}
+            assert tr.step_batch(d["s"], d["s_next"], d["a"], d["r"], d["term"]) == 0
+        elif op == "append":
+            pr.append_only(take(int(rng.integers(1, 8))))
+        elif op == "target":
+            tr.set_target(synth.init_params(D, H, A + (1 if dueling else 0), int(rng.integers(1 << 30))))
+        elif op == "rewind":
+            p, (m, v, t, step) = tr.params(), tr.opt_state()
+            tr.set_state(p, m, v, max(0, t - int(rng.integers(0, 3))), step + int(rng.integers(0, 3)))
+        else:
+            n = int(rng.integers(2, 12))
+            part = take(n * per)
+            pr.ref_ring.append(part["s"], part["s_next"], part["a"], part["r"], part["term"])
+            assert tr.steps(n, part["s"], part["s_next"], part["a"], part["r"], part["term"]) == n
+    assert pr.step(take(per), compare=True) == 0
+    assert pr.gpu_ring.state() == pr.ref_ring.state()
+
+
 def test_a_hand_over_that_never_arrives_ends_the_wait_and_is_reported(B):
     """The wait of a workgroup for its partner is bounded.  With the waiting side told to look for
     a launch number that nobody sends (a host-side switch: every kernel still runs to its end)
