@@ -959,6 +959,8 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
     t->payload_node[0] = nullptr;
     t->multi_graph = nullptr;
     t->multi_exec = nullptr;
+    t->long_graph = nullptr;
+    t->long_exec = nullptr;
 
     if (cfg->flags & RP_TRAIN_GRAPH) {
         // recorded once with the replay's staging area as a stand-in payload; the payload
@@ -989,6 +991,18 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
             e = rp::find_payload_nodes(t, t->multi_graph, rp::kGraphSteps,
                                        t->multi_node, t->multi_np);
         if (e == hipSuccess) e = hipGraphInstantiate(&t->multi_exec, t->multi_graph, nullptr, nullptr, 0);
+        // ... and for kGraphStepsLong
+        if (e == hipSuccess) e = hipStreamBeginCapture(t->capture_stream, hipStreamCaptureModeThreadLocal);
+        if (e == hipSuccess) {
+            hipError_t ek = hipSuccess;
+            for (unsigned int k = 0; k < rp::kGraphStepsLong && ek == hipSuccess; ++k)
+                ek = rp::enqueue_append_and_step(t, stand_in, t->capture_stream, nullptr);
+            e = hipStreamEndCapture(t->capture_stream, &t->long_graph);
+            if (ek != hipSuccess) e = ek;
+        }
+        if (e == hipSuccess && rp::has_payload_node(t))
+            e = rp::find_payload_nodes(t, t->long_graph, rp::kGraphStepsLong, t->long_node, t->long_np);
+        if (e == hipSuccess) e = hipGraphInstantiate(&t->long_exec, t->long_graph, nullptr, nullptr, 0);
         if (e != hipSuccess) {
             rp::set_error("train_create: recording the step graph failed: %s", hipGetErrorString(e));
             return fail(RP_EHIP);
@@ -1018,6 +1032,8 @@ rp_status train_destroy(trainer_t* t) {
     if (t->graph) (void)hipGraphDestroy(t->graph);
     if (t->multi_exec) (void)hipGraphExecDestroy(t->multi_exec);
     if (t->multi_graph) (void)hipGraphDestroy(t->multi_graph);
+    if (t->long_exec) (void)hipGraphExecDestroy(t->long_exec);
+    if (t->long_graph) (void)hipGraphDestroy(t->long_graph);
     if (t->capture_stream) (void)hipStreamDestroy(t->capture_stream);
     for (auto& ev : t->pin_event)
         if (ev) (void)hipEventDestroy(ev);
@@ -1106,7 +1122,7 @@ rp_status train_steps(trainer_t* t, uint64_t count, const void* s, const void* s
                       void* hip_stream, uint64_t* executed) {
     RP_REQUIRE(t, "train_steps: null handle");
     replay* rpl = t->rp_;
-    const uint64_t n = t->cfg.appends_per_step, K = rp::kGraphSteps;
+    const uint64_t n = t->cfg.appends_per_step;
     const size_t sb = rpl->geom.state_bytes;
     RP_REQUIRE(n == 0 || (s && s_next && a && r && term), "train_steps: null field array for the append");
     uint64_t done = 0;
@@ -1115,7 +1131,13 @@ rp_status train_steps(trainer_t* t, uint64_t count, const void* s, const void* s
         // kGraphSteps steps in one graph launch when all of them train (new experiences in host
         // memory go through one pinned slot per step)
         const bool host_src = n && !src_is_device;
-        if (t->multi_exec && count - k >= K && (!host_src || rp::has_payload_node(t)) &&
+        // (the longer graph when the new experiences need no staging)
+        const bool longer = t->long_exec && !host_src && count - k >= rp::kGraphStepsLong;
+        const uint64_t K = longer ? rp::kGraphStepsLong : rp::kGraphSteps;
+        hipGraphExec_t const run_exec = longer ? t->long_exec : t->multi_exec;
+        hipGraphNode_t* const run_node = longer ? t->long_node : t->multi_node;
+        hipKernelNodeParams* const run_np = longer ? t->long_np : t->multi_np;
+        if (run_exec && count - k >= K && (!host_src || rp::has_payload_node(t)) &&
             rpl->total + n >= rpl->cfg.burn_in &&
             rpl->size + n >= (rpl->cfg.sampling == RP_DISTINCT ? t->cfg.batch : 1u)) {
             for (unsigned int j = 0; j < K && rp::has_payload_node(t); ++j) {
@@ -1128,10 +1150,9 @@ rp_status train_steps(trainer_t* t, uint64_t count, const void* s, const void* s
                 if (host_src)
                     RP_CHECK_HIP(rp::stage_host_payload(t, j, n, src.s, src.s_next, src.a, src.r, src.term, &src));
                 rp::set_payload_args(t, src, j);
-                RP_CHECK_HIP(hipGraphExecKernelNodeSetParams(t->multi_exec, t->multi_node[j],
-                                                             &t->multi_np[j]));
+                RP_CHECK_HIP(hipGraphExecKernelNodeSetParams(run_exec, run_node[j], &run_np[j]));
             }
-            RP_CHECK_HIP(hipGraphLaunch(t->multi_exec, static_cast<hipStream_t>(hip_stream)));
+            RP_CHECK_HIP(hipGraphLaunch(run_exec, static_cast<hipStream_t>(hip_stream)));
             if (host_src)
                 RP_CHECK_HIP(rp::commit_host_slots(t, (unsigned int)K, static_cast<hipStream_t>(hip_stream)));
             const uint64_t cap = rpl->cfg.capacity;

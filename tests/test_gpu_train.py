@@ -331,7 +331,7 @@ def test_many_steps_in_flight(B, dtype, layered, device_src):
 def test_steps_in_flight_equal_steps_synchronised_one_by_one(B, dtype, H, layered, device_src):
     """The argument block of the kernel that consumes a step's new experiences is rewritten in
     the recorded graph before every launch, while earlier launches of the same graph may still be
-    running.  2,000 steps queued without any synchronisation (eight steps per graph launch) must
+    running.  2,000 steps queued without any synchronisation (32 or 8 steps per graph launch) must
     leave exactly the state that the same 2,000 steps leave when the device is synchronised after
     every single step (one step per graph launch): ring, weights, moments, counters and the last
     step's sampled slots, bit for bit.  Two-kernel step (device and host arrays), MFMA step,
