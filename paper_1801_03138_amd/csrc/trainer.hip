@@ -957,10 +957,10 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
                                             : rp::append_pair_func(rp_->geom);
     t->payload_kargs[0] = t->fused ? static_cast<void*>(&t->row_args) : static_cast<void*>(&t->append_args);
     t->payload_node[0] = nullptr;
-    t->multi_graph = nullptr;
-    t->multi_exec = nullptr;
-    t->long_graph = nullptr;
-    t->long_exec = nullptr;
+    for (auto& run : t->runs) {
+        run.graph = nullptr;
+        run.exec = nullptr;
+    }
 
     if (cfg->flags & RP_TRAIN_GRAPH) {
         // recorded once with the replay's staging area as a stand-in payload; the payload
@@ -978,31 +978,20 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
         if (e == hipSuccess && rp::has_payload_node(t))
             e = rp::find_payload_nodes(t, t->graph, 1, t->payload_node, t->payload_np);
         if (e == hipSuccess) e = hipGraphInstantiate(&t->graph_exec, t->graph, nullptr, nullptr, 0);
-        // the same for kGraphSteps steps in a row
-        if (e == hipSuccess) e = hipStreamBeginCapture(t->capture_stream, hipStreamCaptureModeThreadLocal);
-        if (e == hipSuccess) {
+        // the same for runs of several steps
+        for (unsigned int g = 0; g < rp::kRuns && e == hipSuccess; ++g) {
+            trainer::StepRun& run = t->runs[g];
+            e = hipStreamBeginCapture(t->capture_stream, hipStreamCaptureModeThreadLocal);
+            if (e != hipSuccess) break;
             hipError_t ek = hipSuccess;
-            for (unsigned int k = 0; k < rp::kGraphSteps && ek == hipSuccess; ++k)
+            for (unsigned int k = 0; k < rp::kRunSteps[g] && ek == hipSuccess; ++k)
                 ek = rp::enqueue_append_and_step(t, stand_in, t->capture_stream, nullptr);
-            e = hipStreamEndCapture(t->capture_stream, &t->multi_graph);
+            e = hipStreamEndCapture(t->capture_stream, &run.graph);
             if (ek != hipSuccess) e = ek;
+            if (e == hipSuccess && rp::has_payload_node(t))
+                e = rp::find_payload_nodes(t, run.graph, rp::kRunSteps[g], run.node, run.np);
+            if (e == hipSuccess) e = hipGraphInstantiate(&run.exec, run.graph, nullptr, nullptr, 0);
         }
-        if (e == hipSuccess && rp::has_payload_node(t))
-            e = rp::find_payload_nodes(t, t->multi_graph, rp::kGraphSteps,
-                                       t->multi_node, t->multi_np);
-        if (e == hipSuccess) e = hipGraphInstantiate(&t->multi_exec, t->multi_graph, nullptr, nullptr, 0);
-        // ... and for kGraphStepsLong
-        if (e == hipSuccess) e = hipStreamBeginCapture(t->capture_stream, hipStreamCaptureModeThreadLocal);
-        if (e == hipSuccess) {
-            hipError_t ek = hipSuccess;
-            for (unsigned int k = 0; k < rp::kGraphStepsLong && ek == hipSuccess; ++k)
-                ek = rp::enqueue_append_and_step(t, stand_in, t->capture_stream, nullptr);
-            e = hipStreamEndCapture(t->capture_stream, &t->long_graph);
-            if (ek != hipSuccess) e = ek;
-        }
-        if (e == hipSuccess && rp::has_payload_node(t))
-            e = rp::find_payload_nodes(t, t->long_graph, rp::kGraphStepsLong, t->long_node, t->long_np);
-        if (e == hipSuccess) e = hipGraphInstantiate(&t->long_exec, t->long_graph, nullptr, nullptr, 0);
         if (e != hipSuccess) {
             rp::set_error("train_create: recording the step graph failed: %s", hipGetErrorString(e));
             return fail(RP_EHIP);
@@ -1030,10 +1019,10 @@ rp_status train_destroy(trainer_t* t) {
     if (!t) return RP_OK;
     if (t->graph_exec) (void)hipGraphExecDestroy(t->graph_exec);
     if (t->graph) (void)hipGraphDestroy(t->graph);
-    if (t->multi_exec) (void)hipGraphExecDestroy(t->multi_exec);
-    if (t->multi_graph) (void)hipGraphDestroy(t->multi_graph);
-    if (t->long_exec) (void)hipGraphExecDestroy(t->long_exec);
-    if (t->long_graph) (void)hipGraphDestroy(t->long_graph);
+    for (auto& run : t->runs) {
+        if (run.exec) (void)hipGraphExecDestroy(run.exec);
+        if (run.graph) (void)hipGraphDestroy(run.graph);
+    }
     if (t->capture_stream) (void)hipStreamDestroy(t->capture_stream);
     for (auto& ev : t->pin_event)
         if (ev) (void)hipEventDestroy(ev);
@@ -1128,16 +1117,23 @@ rp_status train_steps(trainer_t* t, uint64_t count, const void* s, const void* s
     uint64_t done = 0;
     for (uint64_t k = 0; k < count;) {
         const uint64_t o = k * n;
-        // kGraphSteps steps in one graph launch when all of them train (new experiences in host
+        // several steps in one graph launch when all of them train (new experiences in host
         // memory go through one pinned slot per step)
         const bool host_src = n && !src_is_device;
-        // (the longer graph when the new experiences need no staging)
-        const bool longer = t->long_exec && !host_src && count - k >= rp::kGraphStepsLong;
-        const uint64_t K = longer ? rp::kGraphStepsLong : rp::kGraphSteps;
-        hipGraphExec_t const run_exec = longer ? t->long_exec : t->multi_exec;
-        hipGraphNode_t* const run_node = longer ? t->long_node : t->multi_node;
-        hipKernelNodeParams* const run_np = longer ? t->long_np : t->multi_np;
-        if (run_exec && count - k >= K && (!host_src || rp::has_payload_node(t)) &&
+        // the longest recorded run that fits what is left (and the staging area, for host arrays)
+        trainer::StepRun* run = nullptr;
+        uint64_t K = 0;
+        for (unsigned int g = 0; g < rp::kRuns && !run; ++g) {
+            const uint64_t steps = rp::kRunSteps[g];
+            if (t->runs[g].exec && steps <= count - k && (!host_src || steps <= rp::kRunStepsHostPayload)) {
+                run = &t->runs[g];
+                K = steps;
+            }
+        }
+        hipGraphExec_t const run_exec = run ? run->exec : nullptr;
+        hipGraphNode_t* const run_node = run ? run->node : nullptr;
+        hipKernelNodeParams* const run_np = run ? run->np : nullptr;
+        if (run_exec && (!host_src || rp::has_payload_node(t)) &&
             rpl->total + n >= rpl->cfg.burn_in &&
             rpl->size + n >= (rpl->cfg.sampling == RP_DISTINCT ? t->cfg.batch : 1u)) {
             for (unsigned int j = 0; j < K && rp::has_payload_node(t); ++j) {

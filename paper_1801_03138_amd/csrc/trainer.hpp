@@ -142,11 +142,13 @@ struct WideBuffers {
     float* part2;                            // K-split partials [splits][H+1][H] of [dW2 ; db2]
 };
 
-constexpr unsigned int kGraphSteps = 8;       // train steps per launch of the multi-step graph ...
-constexpr unsigned int kGraphStepsLong = 32;  // ... and of the longer one, for new experiences that are in device
-                                              // memory already.  A graph launch costs about 5 us of GPU idle time:
-                                              // measured 59.8k / 61.5k / 62.0k steps/s with 8 / 16 / 32 steps per
-                                              // launch; per-step payloads staged from host memory lost 17 % with 16.
+// train_steps runs several steps per graph launch (a launch costs about 5 us of GPU idle time:
+// measured 59.8k / 61.5k / 62.0k steps/s with 8 / 16 / 32 steps per launch): graphs of these many
+// steps are recorded, longest first, and a run of steps takes the longest that still fits.
+// New experiences staged from host memory go 8 at most per launch (16 lost 17 % there).
+constexpr unsigned int kRunSteps[] = {32, 16, 8, 4, 2};
+constexpr unsigned int kRuns = sizeof(kRunSteps) / sizeof(kRunSteps[0]);
+constexpr unsigned int kRunStepsMax = 32, kRunStepsHostPayload = 8;
 constexpr unsigned int kPinSlots = 64;       // pinned host slots for host-sourced payloads
 constexpr unsigned int kPinGroup = 16;       // slots per completion event
 
@@ -209,16 +211,14 @@ struct trainer {
     void* payload_kargs[1];          // -> row_args / append_args
     hipGraphNode_t payload_node[1];
     hipKernelNodeParams payload_np[1];
-    // kGraphSteps consecutive steps recorded as one graph, for train_steps: one launch (and one
-    // launch gap on the GPU) per kGraphSteps steps; each step's payload kernel has its own node.
-    hipGraph_t multi_graph;
-    hipGraphExec_t multi_exec;
-    hipGraphNode_t multi_node[rp::kGraphSteps];
-    hipKernelNodeParams multi_np[rp::kGraphSteps];
-    hipGraph_t long_graph;
-    hipGraphExec_t long_exec;
-    hipGraphNode_t long_node[rp::kGraphStepsLong];
-    hipKernelNodeParams long_np[rp::kGraphStepsLong];
+    // Runs of consecutive steps recorded as one graph each, for train_steps: one launch (and one
+    // launch gap on the GPU) per run; each step's payload kernel has its own node.
+    struct StepRun {
+        hipGraph_t graph;
+        hipGraphExec_t exec;
+        hipGraphNode_t node[rp::kRunStepsMax];
+        hipKernelNodeParams np[rp::kRunStepsMax];
+    } runs[rp::kRuns];
     // Host-sourced payloads are copied into a ring of pinned, device-mapped host slots that the
     // kernel reads directly; an event per group of slots tells when a group may be reused.
     unsigned char* pin_host;
