@@ -114,7 +114,8 @@ struct GatherOut {
 // starts with the append kernel's block, so one object can feed either kernel.
 struct AppendGatherArgs : AppendArgs {
     unsigned long long seed;
-    const unsigned long long* step_ptr;   // sampling step (device)
+    const unsigned long long* step_ptr;   // sampling step (device), or null: step_value then
+    unsigned long long step_value;        // (callers that mirror the step pass it by value: no dependent load)
     unsigned int batch, lane_shift;
     GatherOut out;
 };

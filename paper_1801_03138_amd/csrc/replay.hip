@@ -458,7 +458,7 @@ __global__ __launch_bounds__(kThreads) void append_sample_gather_pair_kernel(App
     }
     const unsigned long long sz = p.pos.size + p.n;
     const unsigned int size = (unsigned int)(sz > g.capacity ? g.capacity : sz);
-    gather_pair_block<ELEM, 1, MODE, true>(g, p.seed, *p.step_ptr, size, p.batch, p.lane_shift,
+    gather_pair_block<ELEM, 1, MODE, true>(g, p.seed, p.step_ptr ? *p.step_ptr : p.step_value, size, p.batch, p.lane_shift,
                                            p.out, p.src, p.pos.head, p.n);
 }
 
@@ -630,6 +630,7 @@ AppendGatherArgs make_append_gather_args(const RingGeom& g, const RingPos& pos, 
     static_cast<AppendArgs&>(a) = make_append_args(g, pos, n, src);
     a.seed = seed;
     a.step_ptr = step_ptr;
+    a.step_value = 0;
     a.batch = batch;
     a.lane_shift = pair_lane_shift(g);
     a.out = out;

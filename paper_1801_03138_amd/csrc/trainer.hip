@@ -591,9 +591,10 @@ hipError_t enqueue_append_and_step(trainer* t, const Payload& src, hipStream_t s
         unsigned char* X = static_cast<unsigned char*>(t->X);
         t->append_args = make_append_gather_args(
             r->geom, RingPos{r->head, r->size, r->total}, t->cfg.appends_per_step, src, r->cfg.seed,
-            &t->ctr->step, t->B,
+            nullptr, t->B,
             GatherOut{X, X + (size_t)t->B * Dp * t->elem, Dp, t->act, t->rew, t->term, t->idx,
                       t->wide ? t->wd.XT : nullptr, t->Bp});
+        t->append_args.step_value = t->host_step;   // (the host mirrors the device's counter exactly)
         unsigned int blocks;
         size_t lds;
         append_gather_shape(t->append_args, &blocks, &lds);
@@ -725,6 +726,7 @@ void set_payload_args(trainer* t, const Payload& src, unsigned int k) {
     } else {
         t->append_args.src = src;
         t->append_args.pos = RingPos{head, size, total};
+        t->append_args.step_value = t->host_step + k;
     }
 }
 
