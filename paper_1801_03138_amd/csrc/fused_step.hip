@@ -452,7 +452,10 @@ __global__ __launch_bounds__(kRowThreads) void fused_rows_kernel(RowArgs p) {
             if constexpr (SPLIT) {
                 unsigned long long off = (unsigned long long)__shfl(myslot, (int)((lane >> 2) & 3u), 64) + cap - head;
                 if (off >= cap) off -= cap;
-                unknown = ahead_side && (lane >> 2) < nrows && off >= n && off - n < n;
+                // (position counted from where the next append starts; on a ring shorter than two
+                // appends that range laps into this step's own)
+                const unsigned long long off2 = off >= n ? off - n : off + cap - n;
+                unknown = ahead_side && (lane >> 2) < nrows && off2 < n;
             }
             if (wave == 1 && lane < 16 && ((lane >> 2) >= nrows || (lane & 3u) == 3u)) meta[lane] = unknown;
 #pragma unroll

@@ -657,16 +657,18 @@ def test_target_values_computed_a_step_ahead(B, capacity):
     assert pr.gpu_ring.state() == pr.ref_ring.state()
 
 
-@pytest.mark.parametrize("seed,distinct,dueling", [(1, False, False), (2, False, True), (3, True, False)])
-def test_target_network_under_a_random_sequence_of_calls(B, seed, distinct, dueling):
+@pytest.mark.parametrize("seed,distinct,dueling,cap,per", [
+    (1, False, False, 90, 3), (2, False, True, 90, 3), (3, True, False, 90, 3),
+    (4, False, False, 50, 30)])    # a ring shorter than two appends: the next append laps into this one's rows
+def test_target_network_under_a_random_sequence_of_calls(B, seed, distinct, dueling, cap, per):
     """Whatever happens between two train steps, the step after it must use the target network
     and the rows as they are then: a seeded random sequence of train steps, steps on given
     batches, appends from outside, new target networks, rewound counters and runs of steps
     queued without a synchronisation, every compared step against the oracle (ring of 90
     slots, batch 37: ragged groups, rows that the steps' own appends overwrite)."""
-    D, H, A, batch, per, cap = 27, 64, 30, 37, 3, 90
+    D, H, A, batch = 27, 64, 30, 37
     rng = np.random.default_rng(1000 + seed)
-    rows = synth.experiences(4000, D, A, 0.1, seed=90 + seed)
+    rows = synth.experiences(12000, D, A, 0.1, seed=90 + seed)
     pr = Pair(B, capacity=cap, D=D, H=H, A=A, batch=batch, burn_in=40, seed=seed, appends=per,
               target_sync=int(rng.choice([2, 4, 7])), distinct=distinct, dueling=dueling, lr=1e-3)
     tr = pr.trainer
@@ -677,7 +679,7 @@ def test_target_network_under_a_random_sequence_of_calls(B, seed, distinct, duel
         at[0] += n
         return part
 
-    pr.append_only(take(60))
+    pr.append_only(take(min(60, cap)))
     for _ in range(70):
         op = rng.choice(["step", "step", "step", "batch", "append", "target", "rewind", "run"])
         if op == "step":
@@ -696,7 +698,9 @@ def test_target_network_under_a_random_sequence_of_calls(B, seed, distinct, duel
         else:
             n = int(rng.integers(2, 12))
             part = take(n * per)
-            pr.ref_ring.append(part["s"], part["s_next"], part["a"], part["r"], part["term"])
+            for j in range(n):
+                one = synth.take(part, j * per, (j + 1) * per)
+                pr.ref_ring.append(one["s"], one["s_next"], one["a"], one["r"], one["term"])
             assert tr.steps(n, part["s"], part["s_next"], part["a"], part["r"], part["term"]) == n
     assert pr.step(take(per), compare=True) == 0
     assert pr.gpu_ring.state() == pr.ref_ring.state()
