@@ -22,7 +22,7 @@ typedef const __attribute__((address_space(1))) char* gbytes;   // global memory
 
 constexpr unsigned int kMmThreads = 256;
 
-enum { MM_BIAS_RELU = 0, MM_BIAS = 1, MM_MASK = 2 };
+enum { MM_BIAS_RELU = 0, MM_BIAS = 1, MM_MASK = 2, MM_PARTIAL = 3 };
 
 // C = A B (+ epilogue).  A is [M x K] with K contiguous.  NT: B is [N x K], K contiguous;
 // otherwise B is [K x N], N contiguous.  The M rows come in `parts` equal parts (1, or 2: the
@@ -41,7 +41,10 @@ struct MmArgs {
     float* C;
     unsigned int ldc;
     unsigned int rows_per_part, parts, tiles_per_part;
-    unsigned int N, K;
+    unsigned int N, K;       // K: what one workgroup contracts over
+    // MM_PARTIAL: the contraction is split over gridDim.z workgroups per tile as well, K columns
+    // each; workgroup z stores its partial product (no bias) c_stride elements after the one before.
+    size_t c_stride;
 };
 
 // One wavefront's 16 x 16 tile of C over the K range [k_lo, k_lo + 16 * ngroups).
@@ -107,7 +110,7 @@ __global__ __launch_bounds__(kMmThreads) void mm_f32_kernel(MmArgs p) {
     const unsigned int arow = min(m0 + c, m_end - 1u);
     const unsigned int groups = p.K >> 4;
     const unsigned int ng = KSPLIT ? groups >> 2 : groups;
-    const unsigned int k_lo = KSPLIT ? wave * ng * 16u : 0u;
+    const unsigned int k_lo = (EPI == MM_PARTIAL ? blockIdx.z * p.K : 0u) + (KSPLIT ? wave * ng * 16u : 0u);
     f32x4 acc = mm_tile<NT, P>(p.A, p.lda, arow, Bm, p.ldb, n0 + c, k_lo, ng, lane);
     if (KSPLIT) {
         if (wave) {
@@ -132,10 +135,10 @@ __global__ __launch_bounds__(kMmThreads) void mm_f32_kernel(MmArgs p) {
             x = x > 0.f ? x : 0.f;
         } else if (EPI == MM_BIAS) {
             x += bias[n];
-        } else {
+        } else if (EPI == MM_MASK) {
             if (!(p.mask[(size_t)m * p.ldmask + n] > 0.f)) x = 0.f;
         }
-        p.C[(size_t)m * p.ldc + n] = x;
+        p.C[(EPI == MM_PARTIAL ? blockIdx.z * p.c_stride : 0) + (size_t)m * p.ldc + n] = x;
     }
 }
 
@@ -145,17 +148,29 @@ bool want_ksplit(unsigned int M, unsigned int N, unsigned int K) {
     return K >= 256u && K % 64u == 0 && tiles32 < 256u;
 }
 
+// Workgroups per tile that share a long contraction with few tiles (their partial products are
+// added up by the kernel that reads the result): 1 = none.
+unsigned int want_kgroups(unsigned int M, unsigned int N, unsigned int K) {
+    const unsigned int tiles16 = ((M + 15u) / 16u) * (N / 16u);
+    unsigned int z = 1;
+    while (z < 8u && tiles16 * z < 256u && K % (2u * z * 64u) == 0 && K / (2u * z) >= 128u) z *= 2u;
+    return z;
+}
+
+// kgroups > 1 (MM_PARTIAL only): a.K is the whole contraction, split over that many workgroups per tile.
 template <bool NT, int EPI>
-hipError_t launch_mm(hipStream_t st, const MmArgs& a, unsigned int M_total) {
-    const bool ks = want_ksplit(M_total, a.N, a.K);
-    const unsigned int TM = ks ? 16u : 32u;
+hipError_t launch_mm(hipStream_t st, const MmArgs& a, unsigned int M_total, unsigned int kgroups = 1) {
     MmArgs p = a;
+    p.K = a.K / kgroups;
+    const bool ks = kgroups > 1 || want_ksplit(M_total, a.N, p.K);
+    const unsigned int TM = ks ? 16u : 32u;
     p.tiles_per_part = (a.rows_per_part + TM - 1u) / TM;
-    const dim3 grid(a.N / TM, p.tiles_per_part * a.parts), block(kMmThreads);
-    const unsigned int ng = (a.K >> 4) >> (ks ? 2 : 0);
+    const dim3 grid(a.N / TM, p.tiles_per_part * a.parts, kgroups), block(kMmThreads);
+    const unsigned int ng = (p.K >> 4) >> (ks ? 2 : 0);
     if (ks) {
         if (ng >= 8) hipLaunchKernelGGL((mm_f32_kernel<NT, EPI, true, 8>), grid, block, 0, st, p);
-        else hipLaunchKernelGGL((mm_f32_kernel<NT, EPI, true, 4>), grid, block, 0, st, p);
+        else if (ng >= 4) hipLaunchKernelGGL((mm_f32_kernel<NT, EPI, true, 4>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((mm_f32_kernel<NT, EPI, true, 2>), grid, block, 0, st, p);
     } else {
         if (ng >= 8) hipLaunchKernelGGL((mm_f32_kernel<NT, EPI, false, 8>), grid, block, 0, st, p);
         else if (ng >= 4) hipLaunchKernelGGL((mm_f32_kernel<NT, EPI, false, 4>), grid, block, 0, st, p);
@@ -177,7 +192,14 @@ hipError_t launch_mm(hipStream_t st, const MmArgs& a, unsigned int M_total) {
 // ----------------------------------------------------------------------------------------
 struct MidTdArgs {
     unsigned int B, G, A, Ap;
-    const float* Q;
+    // kz > 1: the output layer's product arrives as kz partial products [2B x Ap], part_stride
+    // elements apart, without the bias; this kernel adds them up (in a fixed order), adds the
+    // bias (b3 for the rows of s, b3_hi for the rows of s') and writes Q
+    unsigned int kz;
+    const float* part;
+    size_t part_stride;
+    const float *b3, *b3_hi;
+    float* Q;
     const int* act;
     const float* rew;
     const unsigned char* term;
@@ -212,19 +234,56 @@ __global__ __launch_bounds__(256) void mid_td_kernel(MidTdArgs p) {
         p.ctr->c1 = (float)(1.0 - pw1);
         p.ctr->c2 = (float)(1.0 - pw2);
     }
-    const float* qn = p.Q + (size_t)(p.B + i) * p.Ap;
-    float best = -INFINITY;
-    for (unsigned int k = lane; k < p.A; k += 64) best = fmaxf(best, qn[k]);
-    best = wave_max(best);
     unsigned int ai = (unsigned int)p.act[i];
     if (ai >= p.A) ai = p.A - 1;  // an out-of-range action must not turn into a wild address
+    float best = -INFINITY, q;
+    if (p.kz > 1) {
+        // (every wavefront for itself; the first one stores the rows)
+        // (all loads requested before the first sum: partial z beyond kz re-reads partial 0 and
+        // counts as zero)
+        constexpr unsigned int KZ = 8;
+        const size_t row_s = (size_t)i * p.Ap, row_n = (size_t)(p.B + i) * p.Ap;
+        float pa[KZ];
+#pragma unroll
+        for (unsigned int z = 0; z < KZ; ++z) pa[z] = p.part[(z < p.kz ? z : 0u) * p.part_stride + row_s + ai];
+        for (unsigned int k = lane; k < p.Ap; k += 64) {
+            float ps[KZ], pn[KZ];
+#pragma unroll
+            for (unsigned int z = 0; z < KZ; ++z) {
+                const size_t at = (z < p.kz ? z : 0u) * p.part_stride;
+                ps[z] = p.part[at + row_s + k];
+                pn[z] = p.part[at + row_n + k];
+            }
+            float qs = 0.f, qn = 0.f;
+#pragma unroll
+            for (unsigned int z = 0; z < KZ; ++z) {
+                qs += z < p.kz ? ps[z] : 0.f;
+                qn += z < p.kz ? pn[z] : 0.f;
+            }
+            qs += p.b3[k];
+            qn += p.b3_hi[k];
+            if (k < p.A) best = fmaxf(best, qn);
+            if (tid < 64) {
+                p.Q[row_s + k] = qs;
+                p.Q[row_n + k] = qn;
+            }
+        }
+        q = 0.f;
+#pragma unroll
+        for (unsigned int z = 0; z < KZ; ++z) q += z < p.kz ? pa[z] : 0.f;
+        q += p.b3[ai];
+    } else {
+        const float* qn = p.Q + (size_t)(p.B + i) * p.Ap;
+        for (unsigned int k = lane; k < p.A; k += 64) best = fmaxf(best, qn[k]);
+        q = p.Q[(size_t)i * p.Ap + ai];
+    }
+    best = wave_max(best);
     float w3[KU];
 #pragma unroll
     for (unsigned int u = 0; u < KU; ++u) {
         const unsigned int k = tid + 256u * u;
         w3[u] = k < p.G ? p.W3[(size_t)k * p.Ap + ai] : 0.f;
     }
-    const float q = p.Q[(size_t)i * p.Ap + ai];
     const float y = p.rew[i] + (p.term[i] ? 0.f : p.gamma * best);
     const float d = y - q;
     float li, slope;
@@ -277,7 +336,7 @@ hipError_t enqueue_mid_step(trainer* t, hipStream_t st, unsigned int* count) {
     // (the same when there is none: then the 2B rows are one part)
     const unsigned int parts = t->wt ? 2u : 1u, rows = t->wt ? B : 2u * B;
     MmArgs a;
-    a.mask = nullptr; a.ldmask = 0; a.rows_per_part = rows; a.parts = parts; a.tiles_per_part = 0;
+    a.mask = nullptr; a.ldmask = 0; a.rows_per_part = rows; a.parts = parts; a.tiles_per_part = 0; a.c_stride = 0;
     a.A = X; a.lda = Dp; a.B = w + t->oW1; a.B_hi = wt + t->oW1; a.ldb = H;
     a.bias = w + t->ob1; a.bias_hi = wt + t->ob1; a.C = H1; a.ldc = H; a.N = H; a.K = Dp;
     hipError_t e = launch_mm<false, MM_BIAS_RELU>(st, a, 2u * B);
@@ -290,12 +349,23 @@ hipError_t enqueue_mid_step(trainer* t, hipStream_t st, unsigned int* count) {
     ++n;
     a.A = H2; a.lda = G; a.B = w + t->oW3; a.B_hi = wt + t->oW3; a.ldb = Ap;
     a.bias = w + t->ob3; a.bias_hi = wt + t->ob3; a.C = t->Q; a.ldc = Ap; a.N = Ap; a.K = G;
-    e = launch_mm<false, MM_BIAS>(st, a, 2u * B);
+    // a long contraction with few tiles: several workgroups per tile, each a stretch of K; the TD
+    // kernel adds their partial products up
+    const unsigned int kz = want_kgroups(2u * B, Ap, G);
+    if (kz > 1) {
+        a.C = t->qpart;
+        a.c_stride = (size_t)2u * B * Ap;
+        e = launch_mm<false, MM_PARTIAL>(st, a, 2u * B, kz);
+    } else {
+        e = launch_mm<false, MM_BIAS>(st, a, 2u * B);
+    }
     if (e != hipSuccess) return e;
     ++n;
     {
         MidTdArgs d;
         d.B = B; d.G = G; d.A = t->cfg.num_actions; d.Ap = Ap;
+        d.kz = kz; d.part = t->qpart; d.part_stride = (size_t)2u * B * Ap;
+        d.b3 = w + t->ob3; d.b3_hi = wt + t->ob3;
         d.Q = t->Q; d.act = t->act; d.rew = t->rew; d.term = t->term;
         d.gamma = t->cfg.gamma; d.loss_kind = t->cfg.loss; d.beta1 = t->cfg.beta1; d.beta2 = t->cfg.beta2;
         d.y = t->y; d.delta = t->delta; d.lossi = t->lossi; d.dQ = t->dQ;

@@ -260,7 +260,7 @@ namespace {
 
 struct WsLayout {
     size_t ctr, w, g, m, v, wt, w2t, wb, wbt, X, act, rew, term, idx, H1, H2, Q, y, delta, lossi, dQ, dZ2, dZ1,
-        pre, handoff, ahead, qn_ahead, total;
+        pre, qpart, handoff, ahead, qn_ahead, total;
     // mixed-precision step on MFMA
     size_t W1T, W2b, W2T, W3T, W1Tt, W2Tt, W3Tt, XT, H1T, H2T, dQTh, dQTl, dZ2T, dZ1T, part3, part1, part2;
     unsigned int Dp, Ap, Bp;
@@ -322,6 +322,8 @@ bool ws_layout(const train_config* c, WsLayout* L) {
     L->dZ2 = take(B * G * L->elem);
     L->dZ1 = take(B * H * L->elem);
     L->pre = take(2 * (4 + B) * 4);
+    // (partial products of the output layer, fp32 step on MFMA: up to 8 per element)
+    L->qpart = take(c->param_dtype == RP_F32 ? 8 * 2 * B * L->Ap * 4 : 0);
     L->handoff = take(c->target_sync ? B * 8 : 0);
     L->ahead = take(c->target_sync ? 2 * B * 8 * 4 : 0);
     L->qn_ahead = take(c->target_sync ? 2 * B * L->Ap * 4 : 0);
@@ -883,6 +885,7 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
     t->dZ2 = ws + L.dZ2;
     t->dZ1 = ws + L.dZ1;
     t->pre = reinterpret_cast<unsigned int*>(ws + L.pre);
+    t->qpart = reinterpret_cast<float*>(ws + L.qpart);
     t->handoff = reinterpret_cast<unsigned long long*>(ws + L.handoff);
     t->ahead = reinterpret_cast<unsigned int*>(ws + L.ahead);
     t->qn_ahead = reinterpret_cast<float*>(ws + L.qn_ahead);

@@ -185,6 +185,7 @@ struct trainer {
     float *y, *delta, *lossi, *dQ;   // [B], [B], [B], [B x Ap]
     void *dZ2, *dZ1;                 // [B x Hb], [B x H]
     unsigned int* pre;               // slots drawn ahead, 2 x (4 + B) words
+    float* qpart;                    // [8][2B x Ap] partial products of the output layer (fp32 step on MFMA)
     unsigned long long* handoff;     // [B] words one workgroup of the row kernel hands to another
     unsigned int launch_seq;         // number of the last row-kernel launch prepared (never 0)
     long long handoff_ticks;         // longest wait of a workgroup for its partner (wall-clock ticks)
