@@ -14,7 +14,9 @@
 //
 // Paper: Integration with Reinforcement Learning Algorithm (train step with no host inputs),
 // Deep Q-Network Model (update equation), Methods (add, sample).
+#include "gather_block.hpp"
 #include "philox.hpp"
+#include "replay_kernels.hpp"
 #include "trainer.hpp"
 
 namespace rp {
@@ -814,11 +816,10 @@ __device__ __forceinline__ float opt_apply(const WArgs& p, unsigned int k, float
 // requested before the first use; nothing passes through LDS and no wavefront waits for another.
 // FOLD: the variant that also updates a dueling head (the tiles of job fold_job).
 template <bool FOLD>
-__global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
+__device__ __forceinline__ void weights_tile(const WArgs& p) {
     const unsigned int tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const unsigned int l16 = lane & 15u, lq = lane >> 4;
     const unsigned int wr = wave >> 1, wc = wave & 1u;
-    touch_kernel_args<WArgs>();
     unsigned int j = 0;
     if (blockIdx.x >= p.job[1].tile_begin) j = 1;
     if (blockIdx.x >= p.job[2].tile_begin) j = 2;
@@ -911,7 +912,7 @@ __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
 
     // the last workgroup (never on a tile row with a bias) also reduces the per-sample losses:
     // fetch them now
-    const bool loss_block = blockIdx.x == gridDim.x - 1;
+    const bool loss_block = blockIdx.x == p.n_tiles - 1;
     float loss_part = 0.f;
     if (loss_block && tid < 64)
         for (unsigned int i = tid; i < p.B; i += 64) loss_part += p.lossi[i];
@@ -1040,6 +1041,26 @@ __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
             p.ctr->step += 1;
         }
     }
+}
+
+template <bool FOLD>
+__global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
+    touch_kernel_args<WArgs>();
+    weights_tile<FOLD>(p);
+}
+
+// The same launch with `next_blocks` more workgroups after the tiles' own, which append, sample
+// and gather for the NEXT train step (fp32 step on MFMA, inside a recorded run of steps): they
+// touch nothing the tiles read or write (the next step's batch goes to a buffer of its own), and
+// they run on compute units the tiles leave idle, so the next step begins with its first layer.
+template <bool FOLD>
+__global__ __launch_bounds__(kThreads) void fused_weights_ahead_kernel(WArgs p, AppendGatherArgs next,
+                                                                       unsigned int next_blocks) {
+    if (blockIdx.x >= p.n_tiles) {
+        append_gather_block<4, kDrawUniform>(next, blockIdx.x - p.n_tiles, next_blocks);
+        return;
+    }
+    weights_tile<FOLD>(p);
 }
 
 size_t row_kernel_lds(unsigned int Dp, unsigned int H, unsigned int Ap) {
@@ -1197,12 +1218,55 @@ hipError_t enqueue_weights_update(trainer* t, hipStream_t st, bool* folded_head)
     w.head_off = (unsigned int)t->n_padded;
     w.wt = t->wt;
     w.sync_every = t->cfg.target_sync;
-    if (fold)
+    if (t->rec_next) {
+        // (recording a run of steps: this launch also gathers the next step's batch; the argument
+        // blocks are kept for the launches that replace the next step's part)
+        if (!t->w_args_host[t->rec_parity]) t->w_args_host[t->rec_parity] = new WArgs;
+        *static_cast<WArgs*>(t->w_args_host[t->rec_parity]) = w;
+        unsigned int nb = 0;
+        size_t lds = 0;
+        append_gather_shape(*t->rec_next, &nb, &lds);
+        if (fold)
+            hipLaunchKernelGGL(fused_weights_ahead_kernel<true>, dim3(nt + nb), dim3(kThreads), lds, st, w,
+                               *t->rec_next, nb);
+        else
+            hipLaunchKernelGGL(fused_weights_ahead_kernel<false>, dim3(nt + nb), dim3(kThreads), lds, st, w,
+                               *t->rec_next, nb);
+    } else if (fold) {
         hipLaunchKernelGGL(fused_weights_kernel<true>, dim3(nt), dim3(kThreads), 0, st, w);
-    else
+    } else {
         hipLaunchKernelGGL(fused_weights_kernel<false>, dim3(nt), dim3(kThreads), 0, st, w);
+    }
     if (folded_head) *folded_head = fold;
     return hipGetLastError();
+}
+
+void* weights_ahead_func(const trainer* t) {
+    const bool fold = t->dueling && t->Ap == kTN;
+    return fold ? reinterpret_cast<void*>(fused_weights_ahead_kernel<true>)
+                : reinterpret_cast<void*>(fused_weights_ahead_kernel<false>);
+}
+
+hipError_t patch_weights_ahead_node(trainer* t, hipGraphExec_t exec, hipGraphNode_t node,
+                                    const hipKernelNodeParams& recorded, unsigned int parity,
+                                    const AppendGatherArgs& next) {
+    WArgs w = *static_cast<const WArgs*>(t->w_args_host[parity]);
+    AppendGatherArgs nx = next;
+    unsigned int nb = 0;
+    size_t lds = 0;
+    append_gather_shape(nx, &nb, &lds);
+    void* kargs[] = {&w, &nx, &nb};
+    hipKernelNodeParams np = recorded;
+    np.kernelParams = kargs;
+    np.extra = nullptr;
+    return hipGraphExecKernelNodeSetParams(exec, node, &np);
+}
+
+void free_weights_args(trainer* t) {
+    for (auto& p : t->w_args_host) {
+        delete static_cast<WArgs*>(p);
+        p = nullptr;
+    }
 }
 
 }  // namespace rp

@@ -260,7 +260,7 @@ namespace {
 
 struct WsLayout {
     size_t ctr, w, g, m, v, wt, w2t, wb, wbt, X, act, rew, term, idx, H1, H2, Q, y, delta, lossi, dQ, dZ2, dZ1,
-        pre, qpart, handoff, ahead, qn_ahead, total;
+        pre, qpart, handoff, ahead, qn_ahead, X2, total;
     // mixed-precision step on MFMA
     size_t W1T, W2b, W2T, W3T, W1Tt, W2Tt, W3Tt, XT, H1T, H2T, dQTh, dQTl, dZ2T, dZ1T, part3, part1, part2;
     unsigned int Dp, Ap, Bp;
@@ -308,6 +308,9 @@ bool ws_layout(const train_config* c, WsLayout* L) {
     L->wb = take(c->param_dtype == RP_BF16 ? L->n_padded * 2 : 0);
     L->wbt = take(c->param_dtype == RP_BF16 && c->target_sync ? L->n_padded * 2 : 0);
     L->X = take(2 * B * L->Dp * L->elem);
+    // (a second batch buffer for the fp32 step on MFMA, whose weights kernel still reads the batch
+    // while its extra workgroups gather the next one)
+    L->X2 = take(c->param_dtype == RP_F32 ? 2 * B * L->Dp * L->elem : 0);
     L->act = take(B * 4);
     L->rew = take(B * 4);
     L->term = take(B);
@@ -601,8 +604,10 @@ hipError_t enqueue_append_and_step(trainer* t, const Payload& src, hipStream_t s
         size_t lds;
         append_gather_shape(t->append_args, &blocks, &lds);
         void* kargs[] = {&t->append_args};
-        hipError_t e = hipLaunchKernel(append_gather_func(r->geom), dim3(blocks), dim3(kThreads), kargs,
-                                       lds, st);
+        // (in a recorded run the step before this one may have gathered this step's batch already)
+        hipError_t e = t->rec_skip_gather ? hipSuccess
+                                          : hipLaunchKernel(append_gather_func(r->geom), dim3(blocks),
+                                                            dim3(kThreads), kargs, lds, st);
         if (e != hipSuccess) return e;
         e = t->wide ? enqueue_wide_step(t, st, &k, false) : enqueue_mid_step(t, st, &k);
         if (count) *count = 1 + k;
@@ -665,8 +670,8 @@ hipError_t enqueue_batch_step(trainer* t, const Payload& batch, hipStream_t st) 
 
 // Find the nodes of the payload-consuming kernel in a recorded graph, in execution order (the
 // graph is a chain: one root, every node one dependent).  Finds `want` of them or fails.
-hipError_t find_payload_nodes(trainer* t, hipGraph_t graph, unsigned int want, hipGraphNode_t* nodes,
-                              hipKernelNodeParams* params) {
+hipError_t find_kernel_nodes(trainer* t, hipGraph_t graph, const void* func, unsigned int want,
+                             hipGraphNode_t* nodes, hipKernelNodeParams* params) {
     size_t n_roots = 0;
     hipError_t e = hipGraphGetRootNodes(graph, nullptr, &n_roots);
     if (e != hipSuccess) return e;
@@ -683,7 +688,7 @@ hipError_t find_payload_nodes(trainer* t, hipGraph_t graph, unsigned int want, h
             hipKernelNodeParams np;
             e = hipGraphKernelNodeGetParams(cur, &np);
             if (e != hipSuccess) return e;
-            if (np.func == t->payload_func && found < want) {
+            if (np.func == func && found < want) {
                 nodes[found] = cur;
                 params[found] = np;
                 params[found].kernelParams = t->payload_kargs;
@@ -702,6 +707,11 @@ hipError_t find_payload_nodes(trainer* t, hipGraph_t graph, unsigned int want, h
         cur = next;
     }
     return found == want ? hipSuccess : hipErrorNotFound;
+}
+
+hipError_t find_payload_nodes(trainer* t, hipGraph_t graph, unsigned int want, hipGraphNode_t* nodes,
+                              hipKernelNodeParams* params) {
+    return find_kernel_nodes(t, graph, t->payload_func, want, nodes, params);
 }
 
 // Whether a recorded step has a node whose argument changes from step to step.
@@ -729,6 +739,12 @@ void set_payload_args(trainer* t, const Payload& src, unsigned int k) {
         t->append_args.src = src;
         t->append_args.pos = RingPos{head, size, total};
         t->append_args.step_value = t->host_step + k;
+        if (t->gather_ahead) {
+            // (the steps of a recorded run alternate between the two batch buffers)
+            unsigned char* X = static_cast<unsigned char*>(t->X_buf[k & 1u]);
+            t->append_args.out.out_s = X;
+            t->append_args.out.out_s_next = X + (size_t)t->B * t->Dp * t->elem;
+        }
     }
 }
 
@@ -871,6 +887,13 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
     }
     t->wb = cfg->param_dtype == RP_BF16 ? reinterpret_cast<bf16_t*>(ws + L.wb) : nullptr;
     t->X = ws + L.X;
+    t->X_buf[0] = ws + L.X;
+    t->X_buf[1] = ws + L.X2;
+    t->gather_ahead = false;
+    t->rec_skip_gather = false;
+    t->rec_next = nullptr;
+    t->rec_parity = 0;
+    t->w_args_host[0] = t->w_args_host[1] = nullptr;
     t->act = reinterpret_cast<int*>(ws + L.act);
     t->rew = reinterpret_cast<float*>(ws + L.rew);
     t->term = ws + L.term;
@@ -973,6 +996,7 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
         const rp::Payload stand_in{rp_->stage_s, rp_->stage_s_next, rp_->stage_a, rp_->stage_r,
                                    rp_->stage_term};
         e = hipStreamCreateWithFlags(&t->capture_stream, hipStreamNonBlocking);
+        t->gather_ahead = t->mid && cfg->appends_per_step && rp_->cfg.sampling == RP_WITH_REPLACEMENT;
         if (e == hipSuccess) e = hipStreamBeginCapture(t->capture_stream, hipStreamCaptureModeThreadLocal);
         if (e == hipSuccess) {
             hipError_t ek = rp::enqueue_append_and_step(t, stand_in, t->capture_stream,
@@ -989,11 +1013,40 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
             e = hipStreamBeginCapture(t->capture_stream, hipStreamCaptureModeThreadLocal);
             if (e != hipSuccess) break;
             hipError_t ek = hipSuccess;
-            for (unsigned int k = 0; k < rp::kRunSteps[g] && ek == hipSuccess; ++k)
+            const unsigned int steps = rp::kRunSteps[g];
+            for (unsigned int k = 0; k < steps && ek == hipSuccess; ++k) {
+                rp::AppendGatherArgs next_gather;
+                if (t->gather_ahead) {
+                    // this step reads batch buffer k mod 2; all but the last also gather the
+                    // next step's batch, into the other buffer, in their weights kernel's launch
+                    t->X = t->X_buf[k & 1u];
+                    t->rec_parity = k & 1u;
+                    t->rec_skip_gather = k > 0;
+                    if (k + 1 < steps) {
+                        unsigned char* Xn = static_cast<unsigned char*>(t->X_buf[(k + 1) & 1u]);
+                        next_gather = rp::make_append_gather_args(
+                            rp_->geom, rp::RingPos{rp_->head, rp_->size, rp_->total}, cfg->appends_per_step,
+                            stand_in, rp_->cfg.seed, nullptr, t->B,
+                            rp::GatherOut{Xn, Xn + (size_t)t->B * t->Dp * t->elem, t->Dp, t->act, t->rew,
+                                          t->term, t->idx, nullptr, t->Bp});
+                        t->rec_next = &next_gather;
+                    }
+                }
                 ek = rp::enqueue_append_and_step(t, stand_in, t->capture_stream, nullptr);
+                t->rec_next = nullptr;
+            }
+            t->rec_skip_gather = false;
+            t->rec_parity = 0;
+            t->X = t->X_buf[0];
             e = hipStreamEndCapture(t->capture_stream, &run.graph);
             if (ek != hipSuccess) e = ek;
-            if (e == hipSuccess && rp::has_payload_node(t))
+            if (e == hipSuccess && t->gather_ahead) {
+                // node 0: the first step's append + gather kernel; node k > 0: step k - 1's weights kernel
+                e = rp::find_payload_nodes(t, run.graph, 1, run.node, run.np);
+                if (e == hipSuccess)
+                    e = rp::find_kernel_nodes(t, run.graph, rp::weights_ahead_func(t), steps - 1, run.node + 1,
+                                              run.np + 1);
+            } else if (e == hipSuccess && rp::has_payload_node(t))
                 e = rp::find_payload_nodes(t, run.graph, rp::kRunSteps[g], run.node, run.np);
             if (e == hipSuccess) e = hipGraphInstantiate(&run.exec, run.graph, nullptr, nullptr, 0);
         }
@@ -1029,6 +1082,7 @@ rp_status train_destroy(trainer_t* t) {
         if (run.graph) (void)hipGraphDestroy(run.graph);
     }
     if (t->capture_stream) (void)hipStreamDestroy(t->capture_stream);
+    rp::free_weights_args(t);
     for (auto& ev : t->pin_event)
         if (ev) (void)hipEventDestroy(ev);
     if (t->pin_host) (void)hipHostFree(t->pin_host);
@@ -1151,7 +1205,11 @@ rp_status train_steps(trainer_t* t, uint64_t count, const void* s, const void* s
                 if (host_src)
                     RP_CHECK_HIP(rp::stage_host_payload(t, j, n, src.s, src.s_next, src.a, src.r, src.term, &src));
                 rp::set_payload_args(t, src, j);
-                RP_CHECK_HIP(hipGraphExecKernelNodeSetParams(run_exec, run_node[j], &run_np[j]));
+                if (t->gather_ahead && j)
+                    RP_CHECK_HIP(rp::patch_weights_ahead_node(t, run_exec, run_node[j], run_np[j], (j - 1u) & 1u,
+                                                              t->append_args));
+                else
+                    RP_CHECK_HIP(hipGraphExecKernelNodeSetParams(run_exec, run_node[j], &run_np[j]));
             }
             RP_CHECK_HIP(hipGraphLaunch(run_exec, static_cast<hipStream_t>(hip_stream)));
             if (host_src)

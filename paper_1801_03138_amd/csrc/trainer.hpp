@@ -220,6 +220,16 @@ struct trainer {
         hipGraphNode_t node[rp::kRunStepsMax];
         hipKernelNodeParams np[rp::kRunStepsMax];
     } runs[rp::kRuns];
+    // fp32 step on MFMA with new experiences every step and sampling with replacement: in a
+    // recorded run only the first step has an append + gather kernel of its own; the gather of
+    // step k + 1 is done by extra workgroups of step k's weights kernel (the run's node k + 1 is
+    // that kernel then), into the batch buffer step k does not use (X_buf, alternating).
+    bool gather_ahead;
+    void* X_buf[2];
+    bool rec_skip_gather;                    // recording: this step's batch was gathered by the step before
+    const rp::AppendGatherArgs* rec_next;    // recording: the next step's gather, for this step's weights kernel
+    unsigned int rec_parity;                 // recording: which batch buffer this step reads
+    void* w_args_host[2];                    // the weights kernel's argument block as recorded, per batch buffer
     // Host-sourced payloads are copied into a ring of pinned, device-mapped host slots that the
     // kernel reads directly; an event per group of slots tells when a group may be reused.
     unsigned char* pin_host;
@@ -267,6 +277,14 @@ hipError_t enqueue_head_update(trainer* t, hipStream_t st, unsigned int* count);
 // activations and pre-activation gradients in the workspace, optimizer, mean loss, step counter;
 // a dueling head of up to 32 actions is updated by it too (*folded_head says so).
 hipError_t enqueue_weights_update(trainer* t, hipStream_t st, bool* folded_head);
+// The weights kernel with the next step's gather in its launch (see trainer::gather_ahead): its
+// __global__ function, replacing the next step's part of a recorded node's arguments, and
+// releasing the recorded argument blocks.
+void* weights_ahead_func(const trainer* t);
+hipError_t patch_weights_ahead_node(trainer* t, hipGraphExec_t exec, hipGraphNode_t node,
+                                    const hipKernelNodeParams& recorded, unsigned int parity,
+                                    const AppendGatherArgs& next);
+void free_weights_args(trainer* t);
 // fp32 step on MFMA for shapes the two-kernel step does not take (wider layers, two different
 // hidden widths): one product per kernel.
 bool mid_step_supported(const train_config& cfg, const replay* rp_);

@@ -327,7 +327,8 @@ def test_many_steps_in_flight(B, dtype, layered, device_src):
 
 
 @pytest.mark.parametrize("dtype,H,layered,device_src", [("f32", 64, False, True), ("f32", 64, False, False),
-                                                        ("bf16", 128, False, True), ("f32", 64, True, True)])
+                                                        ("bf16", 128, False, True), ("f32", 64, True, True),
+                                                        ("f32", 320, False, True), ("f32", 320, False, False)])
 def test_steps_in_flight_equal_steps_synchronised_one_by_one(B, dtype, H, layered, device_src):
     """The argument block of the kernel that consumes a step's new experiences is rewritten in
     the recorded graph before every launch, while earlier launches of the same graph may still be
@@ -335,7 +336,8 @@ def test_steps_in_flight_equal_steps_synchronised_one_by_one(B, dtype, H, layere
     leave exactly the state that the same 2,000 steps leave when the device is synchronised after
     every single step (one step per graph launch): ring, weights, moments, counters and the last
     step's sampled slots, bit for bit.  Two-kernel step (device and host arrays), MFMA step,
-    layered step."""
+    layered step, fp32 MFMA step (whose recorded runs gather a step's batch in the launch of
+    the step before it; device and host arrays)."""
     n_steps, per = 2000, 2
     rows = synth.experiences(n_steps * per, 27, 30, 0.05, seed=51, state_dtype=dtype)
     outs = []
