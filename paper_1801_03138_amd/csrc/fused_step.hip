@@ -14,6 +14,9 @@
 //
 // Paper: Integration with Reinforcement Learning Algorithm (train step with no host inputs),
 // Deep Q-Network Model (update equation), Methods (add, sample).
+#include <cstdlib>
+#include <cstring>
+
 #include "gather_block.hpp"
 #include "philox.hpp"
 #include "replay_kernels.hpp"
@@ -1221,8 +1224,9 @@ hipError_t enqueue_weights_update(trainer* t, hipStream_t st, bool* folded_head)
     if (t->rec_next) {
         // (recording a run of steps: this launch also gathers the next step's batch; the argument
         // blocks are kept for the launches that replace the next step's part)
-        if (!t->w_args_host[t->rec_parity]) t->w_args_host[t->rec_parity] = new WArgs;
-        *static_cast<WArgs*>(t->w_args_host[t->rec_parity]) = w;
+        if (!t->w_args_host[t->rec_parity]) t->w_args_host[t->rec_parity] = malloc(sizeof(WArgs));
+        if (!t->w_args_host[t->rec_parity]) return hipErrorOutOfMemory;
+        memcpy(t->w_args_host[t->rec_parity], &w, sizeof(WArgs));
         unsigned int nb = 0;
         size_t lds = 0;
         append_gather_shape(*t->rec_next, &nb, &lds);
@@ -1250,7 +1254,8 @@ void* weights_ahead_func(const trainer* t) {
 hipError_t patch_weights_ahead_node(trainer* t, hipGraphExec_t exec, hipGraphNode_t node,
                                     const hipKernelNodeParams& recorded, unsigned int parity,
                                     const AppendGatherArgs& next) {
-    WArgs w = *static_cast<const WArgs*>(t->w_args_host[parity]);
+    WArgs w;
+    memcpy(&w, t->w_args_host[parity], sizeof(WArgs));
     AppendGatherArgs nx = next;
     unsigned int nb = 0;
     size_t lds = 0;
@@ -1264,7 +1269,7 @@ hipError_t patch_weights_ahead_node(trainer* t, hipGraphExec_t exec, hipGraphNod
 
 void free_weights_args(trainer* t) {
     for (auto& p : t->w_args_host) {
-        delete static_cast<WArgs*>(p);
+        free(p);
         p = nullptr;
     }
 }

@@ -996,7 +996,8 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
         const rp::Payload stand_in{rp_->stage_s, rp_->stage_s_next, rp_->stage_a, rp_->stage_r,
                                    rp_->stage_term};
         e = hipStreamCreateWithFlags(&t->capture_stream, hipStreamNonBlocking);
-        t->gather_ahead = t->mid && cfg->appends_per_step && rp_->cfg.sampling == RP_WITH_REPLACEMENT;
+        t->gather_ahead = (t->mid || t->wide) && cfg->appends_per_step && rp_->cfg.sampling == RP_WITH_REPLACEMENT;
+        if (t->wide) t->X_buf[1] = t->X_buf[0];   // (its optimizer kernel does not read the batch)
         if (e == hipSuccess) e = hipStreamBeginCapture(t->capture_stream, hipStreamCaptureModeThreadLocal);
         if (e == hipSuccess) {
             hipError_t ek = rp::enqueue_append_and_step(t, stand_in, t->capture_stream,
@@ -1028,7 +1029,7 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
                             rp_->geom, rp::RingPos{rp_->head, rp_->size, rp_->total}, cfg->appends_per_step,
                             stand_in, rp_->cfg.seed, nullptr, t->B,
                             rp::GatherOut{Xn, Xn + (size_t)t->B * t->Dp * t->elem, t->Dp, t->act, t->rew,
-                                          t->term, t->idx, nullptr, t->Bp});
+                                          t->term, t->idx, t->wide ? t->wd.XT : nullptr, t->Bp});
                         t->rec_next = &next_gather;
                     }
                 }
@@ -1044,8 +1045,8 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
                 // node 0: the first step's append + gather kernel; node k > 0: step k - 1's weights kernel
                 e = rp::find_payload_nodes(t, run.graph, 1, run.node, run.np);
                 if (e == hipSuccess)
-                    e = rp::find_kernel_nodes(t, run.graph, rp::weights_ahead_func(t), steps - 1, run.node + 1,
-                                              run.np + 1);
+                    e = rp::find_kernel_nodes(t, run.graph, t->wide ? rp::opt_ahead_func() : rp::weights_ahead_func(t),
+                                              steps - 1, run.node + 1, run.np + 1);
             } else if (e == hipSuccess && rp::has_payload_node(t))
                 e = rp::find_payload_nodes(t, run.graph, rp::kRunSteps[g], run.node, run.np);
             if (e == hipSuccess) e = hipGraphInstantiate(&run.exec, run.graph, nullptr, nullptr, 0);
@@ -1205,7 +1206,9 @@ rp_status train_steps(trainer_t* t, uint64_t count, const void* s, const void* s
                 if (host_src)
                     RP_CHECK_HIP(rp::stage_host_payload(t, j, n, src.s, src.s_next, src.a, src.r, src.term, &src));
                 rp::set_payload_args(t, src, j);
-                if (t->gather_ahead && j)
+                if (t->gather_ahead && j && t->wide)
+                    RP_CHECK_HIP(rp::patch_opt_ahead_node(t, run_exec, run_node[j], run_np[j], t->append_args));
+                else if (t->gather_ahead && j)
                     RP_CHECK_HIP(rp::patch_weights_ahead_node(t, run_exec, run_node[j], run_np[j], (j - 1u) & 1u,
                                                               t->append_args));
                 else

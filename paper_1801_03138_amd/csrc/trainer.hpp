@@ -220,10 +220,12 @@ struct trainer {
         hipGraphNode_t node[rp::kRunStepsMax];
         hipKernelNodeParams np[rp::kRunStepsMax];
     } runs[rp::kRuns];
-    // fp32 step on MFMA with new experiences every step and sampling with replacement: in a
-    // recorded run only the first step has an append + gather kernel of its own; the gather of
-    // step k + 1 is done by extra workgroups of step k's weights kernel (the run's node k + 1 is
-    // that kernel then), into the batch buffer step k does not use (X_buf, alternating).
+    // Steps on MFMA with new experiences every step and sampling with replacement: in a recorded
+    // run only the first step has an append + gather kernel of its own; the gather of step k + 1
+    // is done by extra workgroups of step k's last kernel (the weights kernel of the fp32 step,
+    // the optimizer kernel of the mixed-precision step; the run's node k + 1 is that kernel then).
+    // The fp32 step's weights kernel still reads the batch, so its steps alternate between two
+    // batch buffers (X_buf); the mixed-precision step has one (both entries the same).
     bool gather_ahead;
     void* X_buf[2];
     bool rec_skip_gather;                    // recording: this step's batch was gathered by the step before
@@ -285,6 +287,10 @@ hipError_t patch_weights_ahead_node(trainer* t, hipGraphExec_t exec, hipGraphNod
                                     const hipKernelNodeParams& recorded, unsigned int parity,
                                     const AppendGatherArgs& next);
 void free_weights_args(trainer* t);
+// The same for the mixed-precision step, whose last kernel is the optimizer's.
+void* opt_ahead_func();
+hipError_t patch_opt_ahead_node(trainer* t, hipGraphExec_t exec, hipGraphNode_t node,
+                                const hipKernelNodeParams& recorded, const AppendGatherArgs& next);
 // fp32 step on MFMA for shapes the two-kernel step does not take (wider layers, two different
 // hidden widths): one product per kernel.
 bool mid_step_supported(const train_config& cfg, const replay* rp_);

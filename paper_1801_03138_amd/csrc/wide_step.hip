@@ -15,9 +15,12 @@
 // Paper: Integration with Reinforcement Learning Algorithm (train step with no host inputs),
 // Deep Q-Network Model (update equation).
 #include <algorithm>
+#include <cstdlib>
+#include <cstring>
 #include <type_traits>
 #include <vector>
 
+#include "gather_block.hpp"
 #include "replay_kernels.hpp"
 #include "trainer.hpp"
 
@@ -910,6 +913,29 @@ __global__ __launch_bounds__(256) void opt_kernel(SquareOptArgs sq, SmallOptArgs
         small_opt_block(sm, blockIdx.x - n_square);
 }
 
+// The same launch with `next_blocks` more workgroups after its `own` ones, which append, sample and
+// gather for the NEXT train step (inside a recorded run of steps): nothing the optimizer reads or
+// writes is touched by them, and the next step then begins with its first layer.
+__global__ __launch_bounds__(256) void opt_ahead_kernel(SquareOptArgs sq, SmallOptArgs sm, AppendGatherArgs next,
+                                                        unsigned int own, unsigned int next_blocks) {
+    if (blockIdx.x >= own) {
+        append_gather_block<2, kDrawUniform>(next, blockIdx.x - own, next_blocks);
+        return;
+    }
+    const unsigned int tiles_n = sq.N / 64u, n_square = tiles_n * (sq.R / kSqRows);
+    if (blockIdx.x < n_square)
+        square_opt_block(sq, blockIdx.x % tiles_n, blockIdx.x / tiles_n);
+    else
+        small_opt_block(sm, blockIdx.x - n_square);
+}
+
+// What a recorded opt_ahead_kernel node was launched with, apart from the next step's part.
+struct OptRecorded {
+    SquareOptArgs sq;
+    SmallOptArgs sm;
+    unsigned int own;
+};
+
 // K splits of the narrow layers' gradient products (contraction over the padded batch): as
 // many as leave every workgroup at least 256 columns, in whole 64-wide slices, at most 16.
 unsigned int batch_splits(unsigned int Bp) {
@@ -1132,7 +1158,21 @@ hipError_t enqueue_wide_step(trainer* t, hipStream_t st, unsigned int* count, bo
         a.ctr = t->ctr; a.lossi = t->lossi;
         a.out_grad_only = t->dueling ? 1u : 0u;
         const unsigned int elems = (H + 1) * Ap + H * (D + 1);
-        hipLaunchKernelGGL(opt_kernel, dim3((H / 64) * (H / kSqRows) + (elems + 255) / 256), dim3(256), 0, st, q, a);
+        const unsigned int own = (H / 64) * (H / kSqRows) + (elems + 255) / 256;
+        if (t->rec_next) {
+            // (recording a run of steps: this launch also gathers the next step's batch; the rest of
+            // its arguments is kept for the launches that replace the next step's part)
+            if (!t->w_args_host[0]) t->w_args_host[0] = malloc(sizeof(OptRecorded));
+            if (!t->w_args_host[0]) return hipErrorOutOfMemory;
+            const OptRecorded rec{q, a, own};
+            memcpy(t->w_args_host[0], &rec, sizeof(rec));
+            unsigned int nb = 0;
+            size_t lds = 0;
+            append_gather_shape(*t->rec_next, &nb, &lds);
+            hipLaunchKernelGGL(opt_ahead_kernel, dim3(own + nb), dim3(256), lds, st, q, a, *t->rec_next, own, nb);
+        } else {
+            hipLaunchKernelGGL(opt_kernel, dim3(own), dim3(256), 0, st, q, a);
+        }
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         ++n;
@@ -1143,6 +1183,23 @@ hipError_t enqueue_wide_step(trainer* t, hipStream_t st, unsigned int* count, bo
     }
     if (count) *count = n;
     return hipGetLastError();
+}
+
+void* opt_ahead_func() { return reinterpret_cast<void*>(opt_ahead_kernel); }
+
+hipError_t patch_opt_ahead_node(trainer* t, hipGraphExec_t exec, hipGraphNode_t node,
+                                const hipKernelNodeParams& recorded, const AppendGatherArgs& next) {
+    OptRecorded rec;
+    memcpy(&rec, t->w_args_host[0], sizeof(rec));
+    AppendGatherArgs nx = next;
+    unsigned int nb = 0;
+    size_t lds = 0;
+    append_gather_shape(nx, &nb, &lds);
+    void* kargs[] = {&rec.sq, &rec.sm, &nx, &rec.own, &nb};
+    hipKernelNodeParams np = recorded;
+    np.kernelParams = kargs;
+    np.extra = nullptr;
+    return hipGraphExecKernelNodeSetParams(exec, node, &np);
 }
 
 }  // namespace rp
