@@ -581,8 +581,8 @@ def main():
         w["frac_mfma"] = w["TFLOPs"] / BF16_MFMA_PEAK_TFLOPS
         out["wide_step"] = w
         log("[bench]   %.1f steps/s, %.1f TFLOP/s" % (w["steps_per_s"], w["TFLOPs"]))
-        rooflines.append({"kernel": "whole wide step (%d kernels; the dense products are gemm_nt_kernel)"
-                          % w["kernels_per_step"],
+        rooflines.append({"kernel": "whole wide step (%d kernels step by step, one fewer in the recorded runs "
+                                    "timed here; the dense products are gemm_nt_kernel)" % w["kernels_per_step"],
                           "workload": "wide fused step: batch 4096, 27-1024-1024-30, bf16 operands, fp32 "
                                       "accumulation, Adam, 64 appends per step", "bound": "mfma",
                           "achieved": w["TFLOPs"], "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
