@@ -43,8 +43,8 @@ GATHER_KERNEL = "sample_gather_pair_kernel<4, 2, 0>"
 LARGE_256_HBM_BYTES = (7154.9 * 2.000 + 56461.1 * 1.000) * 1024
 # and for append_pair_bulk_kernel<unsigned int> at 65,536 rows (profiles/append_bulk_kernel_hbm_traffic_pmc.txt)
 APPEND_65536_HBM_BYTES = (7314.5 * 2.000 + 16384.0 * 1.000) * 1024
-# and summed over the eight kernels of one wide step (profiles/wide_step_kernels_hbm_traffic_pmc.txt)
-WIDE_STEP_HBM_BYTES = (90907.4 * 2.000 + 120678.2 * 1.000) * 1024
+# and summed over the seven kernels of one wide step of a recorded run (profiles/wide_step_kernels_hbm_traffic_pmc.txt)
+WIDE_STEP_HBM_BYTES = (90886.2 * 2.000 + 120684.0 * 1.000) * 1024
 
 
 def log(*a):
