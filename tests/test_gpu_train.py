@@ -338,7 +338,11 @@ def test_steps_in_flight_equal_steps_synchronised_one_by_one(B, dtype, H, layere
     step's sampled slots, bit for bit.  Two-kernel step (device and host arrays), MFMA step,
     layered step, fp32 MFMA step (whose recorded runs gather a step's batch in the launch of
     the step before it; device and host arrays)."""
+    # (the queued side makes the 2,000 steps in calls of these lengths, so that recorded runs of
+    # every length, single steps and the hand-over from one run to the next all occur)
     n_steps, per = 2000, 2
+    calls = [1, 2, 3, 5, 7, 13, 31, 33, 64, 70, 24, 56, 15]
+    calls.append(n_steps - sum(calls))
     rows = synth.experiences(n_steps * per, 27, 30, 0.05, seed=51, state_dtype=dtype)
     outs = []
     for one_by_one in (False, True):
@@ -357,7 +361,12 @@ def test_steps_in_flight_equal_steps_synchronised_one_by_one(B, dtype, H, layere
                                 d["term"][lo:hi]) == 0
                 torch.cuda.synchronize()
         else:
-            done = tr.steps(n_steps, d["s"], d["s_next"], d["a"], d["r"], d["term"])
+            done, at = 0, 0
+            for n in calls:
+                lo, hi = at * per, (at + n) * per
+                done += tr.steps(n, d["s"][lo:hi], d["s_next"][lo:hi], d["a"][lo:hi], d["r"][lo:hi],
+                                 d["term"][lo:hi])
+                at += n
         assert done == n_steps - 49
         last = tr.last()
         outs.append((tr.params(), tr.target(), tr.opt_state(), last["idx"], last["loss"], last["Q"],
