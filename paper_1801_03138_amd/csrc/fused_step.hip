@@ -18,6 +18,7 @@
 #include <cstring>
 
 #include "gather_block.hpp"
+#include "mm_f32.hpp"
 #include "philox.hpp"
 #include "replay_kernels.hpp"
 #include "trainer.hpp"
@@ -35,7 +36,6 @@ constexpr unsigned int kChunk = 256;       // output columns the workgroup cover
 constexpr size_t kRowLdsMax = 160 * 1024;  // dynamic LDS the row kernel may ask for (all of a CU's)
 constexpr unsigned int kPadK = 4;          // LDS row padding (floats) against bank conflicts
 
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
 // outstanding global load of the wavefront, which would cancel the register prefetch of the
@@ -89,7 +89,6 @@ __device__ __forceinline__ unsigned int staged_word(const RowArgs& p, unsigned l
 // "narrow" split (N up to 64): a lane owns one column, every wavefront covers columns 0..63
 // and K sixteenth w.
 // ----------------------------------------------------------------------------------------
-typedef const __attribute__((address_space(1))) char* gbytes;   // global memory, byte-addressed
 
 template <int NR>
 __device__ __forceinline__ void load_cols(float (&wr)[NR], const float* __restrict__ W,
@@ -761,6 +760,9 @@ struct WArgs {
     unsigned int fold_job, head_A, head_off;
     float* wt;                    // frozen target network, synced when Adam's t is a multiple of
     unsigned int sync_every;      // sync_every (0: never)
+    // 1: the launch whose last tile writes the step's loss and advances the step count (one
+    // launch per train step; a step's other launch of tiles leaves both alone)
+    unsigned int closes_step;
 };
 
 constexpr unsigned int kTM = 32, kTN = 32, kTK = 128;
@@ -818,16 +820,17 @@ __device__ __forceinline__ float opt_apply(const WArgs& p, unsigned int k, float
 // 4t + l/16 of step t, column l%16 of the quarter -- 64-byte runs), all 64 loads of a pass
 // requested before the first use; nothing passes through LDS and no wavefront waits for another.
 // FOLD: the variant that also updates a dueling head (the tiles of job fold_job).
+// block: the workgroup's number among the launch's tiles.
 template <bool FOLD>
-__device__ __forceinline__ void weights_tile(const WArgs& p) {
+__device__ __forceinline__ void weights_tile(const WArgs& p, unsigned int block) {
     const unsigned int tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const unsigned int l16 = lane & 15u, lq = lane >> 4;
     const unsigned int wr = wave >> 1, wc = wave & 1u;
     unsigned int j = 0;
-    if (blockIdx.x >= p.job[1].tile_begin) j = 1;
-    if (blockIdx.x >= p.job[2].tile_begin) j = 2;
+    if (block >= p.job[1].tile_begin) j = 1;
+    if (block >= p.job[2].tile_begin) j = 2;
     const WJob jb = j == 0 ? p.job[0] : j == 1 ? p.job[1] : p.job[2];
-    const unsigned int tile = blockIdx.x - jb.tile_begin;
+    const unsigned int tile = block - jb.tile_begin;
     const unsigned int m0 = (tile / jb.tiles_n) * kTM, n0 = (tile % jb.tiles_n) * kTN;
     // this lane's outputs: rows mm .. mm+3 of column nn
     const unsigned int nn = n0 + 16u * wc + l16;
@@ -913,9 +916,9 @@ __device__ __forceinline__ void weights_tile(const WArgs& p) {
     const unsigned int kval = !val_lane ? kb : l16 < 4 ? p.head_off + (mm + l16) * O : hbias;
     const float vw_old = ldw(p.w, kval), vm_old = ldw(p.m, kval), vv_old = ldw(p.v, kval);
 
-    // the last workgroup (never on a tile row with a bias) also reduces the per-sample losses:
-    // fetch them now
-    const bool loss_block = blockIdx.x == p.n_tiles - 1;
+    // the last workgroup of the launch that closes the step (never on a tile row with a bias)
+    // also reduces the per-sample losses: fetch them now
+    const bool loss_block = p.closes_step && block == p.n_tiles - 1;
     float loss_part = 0.f;
     if (loss_block && tid < 64)
         for (unsigned int i = tid; i < p.B; i += 64) loss_part += p.lossi[i];
@@ -1049,21 +1052,37 @@ __device__ __forceinline__ void weights_tile(const WArgs& p) {
 template <bool FOLD>
 __global__ __launch_bounds__(kThreads) void fused_weights_kernel(WArgs p) {
     touch_kernel_args<WArgs>();
-    weights_tile<FOLD>(p);
+    weights_tile<FOLD>(p, blockIdx.x);
 }
 
-// The same launch with `next_blocks` more workgroups after the tiles' own, which append, sample
-// and gather for the NEXT train step (fp32 step on MFMA, inside a recorded run of steps): they
-// touch nothing the tiles read or write (the next step's batch goes to a buffer of its own), and
-// they run on compute units the tiles leave idle, so the next step begins with its first layer.
+// The launch of tiles of the fp32 step on MFMA, with two more kinds of workgroup in it:
+//  - the first dz_blocks workgroups compute dZ1 = (dZ2 W2^T) masked by the first ReLU (16 x 16
+//    per workgroup, K over its four wavefronts; dz_nx tiles per tile row).  The tiles of this
+//    launch are then those that do not read dZ1 (the second layer's and the output layer's); the
+//    first layer's follow in a launch of their own.  Product and tiles each fit the compute
+//    units the other leaves idle, so the launch takes as long as the slower of the two alone.
+//    The second layer's tiles update W2 in place, so the product takes W2 from a copy this
+//    launch does not write (dz.B; made earlier in the step).
+//  - after the tiles, next_blocks workgroups append, sample and gather for the NEXT train step
+//    (inside a recorded run of steps): they touch nothing this step reads or writes (the next
+//    step's batch goes to a buffer of its own), so the next step begins with its first layer.
 template <bool FOLD>
-__global__ __launch_bounds__(kThreads) void fused_weights_ahead_kernel(WArgs p, AppendGatherArgs next,
+__global__ __launch_bounds__(kThreads) void fused_weights_ahead_kernel(WArgs p, MmArgs dz, unsigned int dz_nx,
+                                                                       unsigned int dz_blocks,
+                                                                       AppendGatherArgs next,
                                                                        unsigned int next_blocks) {
-    if (blockIdx.x >= p.n_tiles) {
-        append_gather_block<4, kDrawUniform>(next, blockIdx.x - p.n_tiles, next_blocks);
+    __shared__ float part[3][64][4];
+    if (blockIdx.x < dz_blocks) {
+        const unsigned int by = blockIdx.x / dz_nx;
+        mm_f32_block<true, MM_MASK, true, 8>(dz, blockIdx.x - by * dz_nx, by, 0u, part);
         return;
     }
-    weights_tile<FOLD>(p);
+    const unsigned int block = blockIdx.x - dz_blocks;
+    if (block >= p.n_tiles) {
+        append_gather_block<4, kDrawUniform>(next, block - p.n_tiles, next_blocks);
+        return;
+    }
+    weights_tile<FOLD>(p, block);
 }
 
 size_t row_kernel_lds(unsigned int Dp, unsigned int H, unsigned int Ap) {
@@ -1189,13 +1208,23 @@ hipError_t enqueue_fused_step(trainer* t, const Payload& src, const Payload* bat
     return e;
 }
 
-hipError_t enqueue_weights_update(trainer* t, hipStream_t st, bool* folded_head) {
+namespace {
+
+// What a recorded launch of fused_weights_ahead_kernel was given, apart from the next step's gather.
+struct TilesRecorded {
     WArgs w;
+    MmArgs dz;
+    unsigned int dz_nx, dz_blocks;
+};
+
+// The tiles of the layers in `jobs` (bit j: job j; 0 = the second layer, 1 = the first, 2 = the output layer).
+unsigned int set_weight_jobs(const trainer* t, unsigned int jobs, WArgs* w) {
     const unsigned int H = t->H, G = t->Hb;
     auto set = [&](int j, const float* act, unsigned int lda, const float* err, unsigned int ldb,
                    unsigned int M, unsigned int N, size_t w_off, size_t b_off, float* wT,
                    unsigned int begin) {
-        WJob& jb = w.job[j];
+        WJob& jb = w->job[j];
+        if (!(jobs >> j & 1u)) M = 0;
         jb.act = act; jb.lda = lda; jb.err = err; jb.ldb = ldb; jb.M = M; jb.N = N;
         jb.w_off = (unsigned int)w_off; jb.ldw = N; jb.b_off = (unsigned int)b_off; jb.wT = wT;
         jb.tiles_n = (N + kTN - 1) / kTN;
@@ -1209,6 +1238,17 @@ hipError_t enqueue_weights_update(trainer* t, hipStream_t st, bool* folded_head)
     nt = set(1, static_cast<const float*>(t->X), t->Dp, static_cast<const float*>(t->dZ1), H, t->Dp, H,
              t->oW1, t->ob1, nullptr, nt);
     nt = set(2, static_cast<const float*>(t->H2), G, t->dQ, t->Ap, G, t->Ap, t->oW3, t->ob3, nullptr, nt);
+    return nt;
+}
+
+}  // namespace
+
+// dz1 (fp32 step on MFMA): the product dZ1 to compute in the same launch as the tiles that do not
+// read it; the first layer's tiles, which do, then follow in a second launch.
+hipError_t enqueue_weights_update(trainer* t, hipStream_t st, bool* folded_head, const MmArgs* dz1,
+                                  unsigned int* launches) {
+    WArgs w;
+    const unsigned int nt = set_weight_jobs(t, dz1 ? 0x5u : 0x7u, &w);
     w.B = t->B; w.n_tiles = nt;
     w.w = t->w; w.g = t->g; w.m = t->m; w.v = t->v;
     w.opt = t->cfg.opt; w.lr = t->cfg.lr; w.beta1 = t->cfg.beta1; w.beta2 = t->cfg.beta2;
@@ -1221,21 +1261,48 @@ hipError_t enqueue_weights_update(trainer* t, hipStream_t st, bool* folded_head)
     w.head_off = (unsigned int)t->n_padded;
     w.wt = t->wt;
     w.sync_every = t->cfg.target_sync;
-    if (t->rec_next) {
-        // (recording a run of steps: this launch also gathers the next step's batch; the argument
-        // blocks are kept for the launches that replace the next step's part)
-        if (!t->w_args_host[t->rec_parity]) t->w_args_host[t->rec_parity] = malloc(sizeof(WArgs));
-        if (!t->w_args_host[t->rec_parity]) return hipErrorOutOfMemory;
-        memcpy(t->w_args_host[t->rec_parity], &w, sizeof(WArgs));
+    w.closes_step = 1;
+    if (launches) *launches = 1;
+    if (t->rec_next || dz1) {
+        TilesRecorded rec;
+        memset(&rec, 0, sizeof(rec));
+        rec.w = w;
+        if (dz1) {
+            rec.dz = *dz1;
+            rec.dz_nx = dz1->N / 16u;
+            rec.dz_blocks = rec.dz_nx * dz1->tiles_per_part;
+        }
+        AppendGatherArgs next;
+        memset(&next, 0, sizeof(next));
         unsigned int nb = 0;
         size_t lds = 0;
-        append_gather_shape(*t->rec_next, &nb, &lds);
+        if (t->rec_next) {
+            // (recording a run of steps: this launch also gathers the next step's batch; the argument
+            // blocks are kept for the launches that replace the next step's part)
+            if (!t->w_args_host[t->rec_parity]) t->w_args_host[t->rec_parity] = malloc(sizeof(TilesRecorded));
+            if (!t->w_args_host[t->rec_parity]) return hipErrorOutOfMemory;
+            memcpy(t->w_args_host[t->rec_parity], &rec, sizeof(TilesRecorded));
+            next = *t->rec_next;
+            append_gather_shape(next, &nb, &lds);
+        }
+        const dim3 grid(rec.dz_blocks + nt + nb);
         if (fold)
-            hipLaunchKernelGGL(fused_weights_ahead_kernel<true>, dim3(nt + nb), dim3(kThreads), lds, st, w,
-                               *t->rec_next, nb);
+            hipLaunchKernelGGL(fused_weights_ahead_kernel<true>, grid, dim3(kThreads), lds, st, w, rec.dz,
+                               rec.dz_nx, rec.dz_blocks, next, nb);
         else
-            hipLaunchKernelGGL(fused_weights_ahead_kernel<false>, dim3(nt + nb), dim3(kThreads), lds, st, w,
-                               *t->rec_next, nb);
+            hipLaunchKernelGGL(fused_weights_ahead_kernel<false>, grid, dim3(kThreads), lds, st, w, rec.dz,
+                               rec.dz_nx, rec.dz_blocks, next, nb);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        if (dz1) {
+            WArgs w1 = w;
+            w1.n_tiles = set_weight_jobs(t, 0x2u, &w1);
+            w1.grad_only_job = ~0u;
+            w1.fold_job = ~0u;
+            w1.closes_step = 0;
+            hipLaunchKernelGGL(fused_weights_kernel<false>, dim3(w1.n_tiles), dim3(kThreads), 0, st, w1);
+            if (launches) *launches = 2;
+        }
     } else if (fold) {
         hipLaunchKernelGGL(fused_weights_kernel<true>, dim3(nt), dim3(kThreads), 0, st, w);
     } else {
@@ -1254,13 +1321,13 @@ void* weights_ahead_func(const trainer* t) {
 hipError_t patch_weights_ahead_node(trainer* t, hipGraphExec_t exec, hipGraphNode_t node,
                                     const hipKernelNodeParams& recorded, unsigned int parity,
                                     const AppendGatherArgs& next) {
-    WArgs w;
-    memcpy(&w, t->w_args_host[parity], sizeof(WArgs));
+    TilesRecorded rec;
+    memcpy(&rec, t->w_args_host[parity], sizeof(TilesRecorded));
     AppendGatherArgs nx = next;
     unsigned int nb = 0;
     size_t lds = 0;
     append_gather_shape(nx, &nb, &lds);
-    void* kargs[] = {&w, &nx, &nb};
+    void* kargs[] = {&rec.w, &rec.dz, &rec.dz_nx, &rec.dz_blocks, &nx, &nb};
     hipKernelNodeParams np = recorded;
     np.kernelParams = kargs;
     np.extra = nullptr;

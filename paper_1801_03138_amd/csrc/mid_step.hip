@@ -11,141 +11,46 @@
 //
 // Paper: Deep Q-Network Model (the network and the update equation), Integration with
 // Reinforcement Learning Algorithm (train step with no host inputs).
+#include "mm_f32.hpp"
 #include "replay_kernels.hpp"
 #include "trainer.hpp"
 
 namespace rp {
 namespace {
 
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef const __attribute__((address_space(1))) char* gbytes;   // global memory, byte-addressed
-
-constexpr unsigned int kMmThreads = 256;
-
-enum { MM_BIAS_RELU = 0, MM_BIAS = 1, MM_MASK = 2, MM_PARTIAL = 3 };
-
-// C = A B (+ epilogue).  A is [M x K] with K contiguous.  NT: B is [N x K], K contiguous;
-// otherwise B is [K x N], N contiguous.  The M rows come in `parts` equal parts (1, or 2: the
-// rows of s and the rows of s'); a tile never straddles two parts, and the tiles of part 1 take
-// B_hi and bias_hi (the frozen target network's layer) instead of B and bias.
-struct MmArgs {
-    const float* A;
-    unsigned int lda;
-    const float* B;
-    const float* B_hi;
-    unsigned int ldb;
-    const float* bias;
-    const float* bias_hi;
-    const float* mask;       // MM_MASK: [M x N], the output is kept where mask > 0
-    unsigned int ldmask;
-    float* C;
-    unsigned int ldc;
-    unsigned int rows_per_part, parts, tiles_per_part;
-    unsigned int N, K;       // K: what one workgroup contracts over
-    // MM_PARTIAL: the contraction is split over gridDim.z workgroups per tile as well, K columns
-    // each; workgroup z stores its partial product (no bias) c_stride elements after the one before.
-    size_t c_stride;
-};
-
-// One wavefront's 16 x 16 tile of C over the K range [k_lo, k_lo + 16 * ngroups).
-// Lane l = 16 q + c of a 16x16x4 MFMA supplies A[row c][k slot q] and B[k slot q][column c] and
-// receives C[rows 4 q .. 4 q + 3][column c].  A group is 16 consecutive k: MFMA j of a group
-// takes k = 16 g + 4 q + j in slot q, so that a lane's share of A (and of B when it is K
-// contiguous) for a whole group is one 16-byte load.  P groups are in flight at a time: the
-// loads of group g + P are requested as soon as group g has been multiplied.  Loads never
-// branch: a group past the end re-reads the last one and is multiplied by zero.
-template <bool NT, int P>
-__device__ __forceinline__ f32x4 mm_tile(const float* __restrict__ A, unsigned int lda, unsigned int arow,
-                                         const float* __restrict__ B, unsigned int ldb, unsigned int bcol,
-                                         unsigned int k_lo, unsigned int ngroups, unsigned int lane) {
-    const unsigned int q = lane >> 4;
-    const gbytes ap = (gbytes)reinterpret_cast<const char*>(A) + ((size_t)arow * lda + k_lo + 4u * q) * 4u;
-    const gbytes bp = NT ? (gbytes)reinterpret_cast<const char*>(B) + ((size_t)bcol * ldb + k_lo + 4u * q) * 4u
-                         : (gbytes)reinterpret_cast<const char*>(B) + ((size_t)(k_lo + 4u * q) * ldb + bcol) * 4u;
-    f32x4 a[P], b[P];
-    auto load = [&](int s, unsigned int g) {
-        const unsigned int gc = g < ngroups ? g : ngroups - 1u;
-        a[s] = *(const __attribute__((address_space(1))) f32x4*)(ap + (size_t)gc * 64u);
-        if (NT) {
-            b[s] = *(const __attribute__((address_space(1))) f32x4*)(bp + (size_t)gc * 64u);
-        } else {
-            const gbytes rb = bp + (size_t)gc * 16u * ldb * 4u;
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                b[s][j] = *(const __attribute__((address_space(1))) float*)(rb + (size_t)j * ldb * 4u);
-        }
-    };
-#pragma unroll
-    for (int s = 0; s < P; ++s) load(s, (unsigned int)s);
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (unsigned int g0 = 0; g0 < ngroups; g0 += P) {
-#pragma unroll
-        for (int s = 0; s < P; ++s) {
-            const bool live = g0 + s < ngroups;
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(live ? a[s][j] : 0.f, b[s][j], acc, 0, 0, 0);
-            load(s, g0 + s + P);
-        }
-    }
-    return acc;
-}
-
-// Tiles of 32 x 32 per workgroup, a 16 x 16 quarter per wavefront over the whole K (KSPLIT
-// false), or 16 x 16 per workgroup with K split over its four wavefronts, summed through LDS
-// in a fixed order (KSPLIT true: long K, few tiles).
 template <bool NT, int EPI, bool KSPLIT, int P>
 __global__ __launch_bounds__(kMmThreads) void mm_f32_kernel(MmArgs p) {
     __shared__ float part[3][64][4];
-    const unsigned int lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-    const unsigned int c = lane & 15u, q = lane >> 4;
-    constexpr unsigned int TM = KSPLIT ? 16u : 32u;
-    const unsigned int part_id = blockIdx.y / p.tiles_per_part;
-    const unsigned int m_begin = part_id * p.rows_per_part, m_end = m_begin + p.rows_per_part;
-    const unsigned int m0 = m_begin + (blockIdx.y - part_id * p.tiles_per_part) * TM + (KSPLIT ? 0u : 16u * (wave >> 1));
-    const unsigned int n0 = blockIdx.x * TM + (KSPLIT ? 0u : 16u * (wave & 1u));
-    const float* Bm = part_id ? p.B_hi : p.B;
-    const float* bias = part_id ? p.bias_hi : p.bias;
-    // rows past the part's end re-read its last row; they are not stored
-    const unsigned int arow = min(m0 + c, m_end - 1u);
-    const unsigned int groups = p.K >> 4;
-    const unsigned int ng = KSPLIT ? groups >> 2 : groups;
-    const unsigned int k_lo = (EPI == MM_PARTIAL ? blockIdx.z * p.K : 0u) + (KSPLIT ? wave * ng * 16u : 0u);
-    f32x4 acc = mm_tile<NT, P>(p.A, p.lda, arow, Bm, p.ldb, n0 + c, k_lo, ng, lane);
-    if (KSPLIT) {
-        if (wave) {
-#pragma unroll
-            for (int v = 0; v < 4; ++v) part[wave - 1u][lane][v] = acc[v];
-        }
-        __syncthreads();
-        if (wave) return;
-#pragma unroll
-        for (unsigned int w = 0; w < 3; ++w)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) acc[v] += part[w][lane][v];
-    }
-    const unsigned int n = n0 + c;
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-        const unsigned int m = m0 + 4u * q + v;
-        if (m >= m_end) continue;
-        float x = acc[v];
-        if (EPI == MM_BIAS_RELU) {
-            x += bias[n];
-            x = x > 0.f ? x : 0.f;
-        } else if (EPI == MM_BIAS) {
-            x += bias[n];
-        } else if (EPI == MM_MASK) {
-            if (!(p.mask[(size_t)m * p.ldmask + n] > 0.f)) x = 0.f;
-        }
-        p.C[(EPI == MM_PARTIAL ? blockIdx.z * p.c_stride : 0) + (size_t)m * p.ldc + n] = x;
-    }
+    mm_f32_block<NT, EPI, KSPLIT, P>(p, blockIdx.x, blockIdx.y, blockIdx.z, part);
 }
 
-// K is split over a workgroup's wavefronts when a product has few tiles and a long contraction.
-bool want_ksplit(unsigned int M, unsigned int N, unsigned int K) {
-    const unsigned int tiles32 = ((M + 31u) / 32u) * (N / 32u);
-    return K >= 256u && K % 64u == 0 && tiles32 < 256u;
+// The same launch with more rows of workgroups after the product's tiles_y, which copy n4
+// 16-byte pieces from src to dst (up to four per thread, all requested before the first store).
+struct CopyArgs {
+    const f32x4* src;
+    f32x4* dst;
+    unsigned int n4;
+};
+
+template <bool NT, int EPI, bool KSPLIT, int P>
+__global__ __launch_bounds__(kMmThreads) void mm_f32_copy_kernel(MmArgs p, unsigned int tiles_y, CopyArgs c) {
+    __shared__ float part[3][64][4];
+    if (blockIdx.y >= tiles_y) {
+        const unsigned int i0 = (((blockIdx.y - tiles_y) * gridDim.x + blockIdx.x) * 4u) * kMmThreads + threadIdx.x;
+        f32x4 x[4];
+#pragma unroll
+        for (unsigned int u = 0; u < 4; ++u) {
+            const unsigned int i = i0 + u * kMmThreads;
+            x[u] = c.src[i < c.n4 ? i : c.n4 - 1u];
+        }
+#pragma unroll
+        for (unsigned int u = 0; u < 4; ++u) {
+            const unsigned int i = i0 + u * kMmThreads;
+            if (i < c.n4) c.dst[i] = x[u];
+        }
+        return;
+    }
+    mm_f32_block<NT, EPI, KSPLIT, P>(p, blockIdx.x, blockIdx.y, blockIdx.z, part);
 }
 
 // Workgroups per tile that share a long contraction with few tiles (their partial products are
@@ -158,15 +63,36 @@ unsigned int want_kgroups(unsigned int M, unsigned int N, unsigned int K) {
 }
 
 // kgroups > 1 (MM_PARTIAL only): a.K is the whole contraction, split over that many workgroups per tile.
+// copy (kgroups 1 only): the launch also copies copy->n4 16-byte pieces, in workgroups of its own.
 template <bool NT, int EPI>
-hipError_t launch_mm(hipStream_t st, const MmArgs& a, unsigned int M_total, unsigned int kgroups = 1) {
+hipError_t launch_mm(hipStream_t st, const MmArgs& a, unsigned int M_total, unsigned int kgroups = 1,
+                     const CopyArgs* copy = nullptr) {
     MmArgs p = a;
     p.K = a.K / kgroups;
     const bool ks = kgroups > 1 || want_ksplit(M_total, a.N, p.K);
     const unsigned int TM = ks ? 16u : 32u;
     p.tiles_per_part = (a.rows_per_part + TM - 1u) / TM;
-    const dim3 grid(a.N / TM, p.tiles_per_part * a.parts, kgroups), block(kMmThreads);
+    const unsigned int tiles_y = p.tiles_per_part * a.parts;
+    const dim3 block(kMmThreads);
     const unsigned int ng = (p.K >> 4) >> (ks ? 2 : 0);
+    if constexpr (!NT && EPI == MM_BIAS_RELU) if (copy) {
+        const unsigned int cb = (copy->n4 + 4u * kMmThreads - 1u) / (4u * kMmThreads), nx = a.N / TM;
+        const dim3 grid(nx, tiles_y + (cb + nx - 1u) / nx, 1);
+#define RP_MM_COPY(KS, P_) \
+    hipLaunchKernelGGL((mm_f32_copy_kernel<NT, EPI, KS, P_>), grid, block, 0, st, p, tiles_y, *copy)
+        if (ks) {
+            if (ng >= 8) RP_MM_COPY(true, 8);
+            else if (ng >= 4) RP_MM_COPY(true, 4);
+            else RP_MM_COPY(true, 2);
+        } else {
+            if (ng >= 8) RP_MM_COPY(false, 8);
+            else if (ng >= 4) RP_MM_COPY(false, 4);
+            else RP_MM_COPY(false, 2);
+        }
+#undef RP_MM_COPY
+        return hipGetLastError();
+    }
+    const dim3 grid(a.N / TM, tiles_y, kgroups);
     if (ks) {
         if (ng >= 8) hipLaunchKernelGGL((mm_f32_kernel<NT, EPI, true, 8>), grid, block, 0, st, p);
         else if (ng >= 4) hipLaunchKernelGGL((mm_f32_kernel<NT, EPI, true, 4>), grid, block, 0, st, p);
@@ -339,7 +265,12 @@ hipError_t enqueue_mid_step(trainer* t, hipStream_t st, unsigned int* count) {
     a.mask = nullptr; a.ldmask = 0; a.rows_per_part = rows; a.parts = parts; a.tiles_per_part = 0; a.c_stride = 0;
     a.A = X; a.lda = Dp; a.B = w + t->oW1; a.B_hi = wt + t->oW1; a.ldb = H;
     a.bias = w + t->ob1; a.bias_hi = wt + t->ob1; a.C = H1; a.ldc = H; a.N = H; a.K = Dp;
-    hipError_t e = launch_mm<false, MM_BIAS_RELU>(st, a, 2u * B);
+    // (when dZ1's product will run beside the second layer's tiles, which update W2 in place, it
+    // takes W2 from a copy: made here, by workgroups of the first layer's launch)
+    const bool dz1_beside_tiles = dz1_rides_with_tiles(B, H, G);
+    const CopyArgs w2_copy{reinterpret_cast<const f32x4*>(w + t->oW2), reinterpret_cast<f32x4*>(t->w2t),
+                           H * G / 4u};
+    hipError_t e = launch_mm<false, MM_BIAS_RELU>(st, a, 2u * B, 1, dz1_beside_tiles ? &w2_copy : nullptr);
     if (e != hipSuccess) return e;
     ++n;
     a.A = H1; a.lda = H; a.B = w + t->oW2; a.B_hi = wt + t->oW2; a.ldb = G;
@@ -379,13 +310,22 @@ hipError_t enqueue_mid_step(trainer* t, hipStream_t st, unsigned int* count) {
     a.rows_per_part = B; a.parts = 1;
     a.A = dZ2; a.lda = G; a.B = w + t->oW2; a.B_hi = a.B; a.ldb = G; a.bias = nullptr; a.bias_hi = nullptr;
     a.mask = H1; a.ldmask = H; a.C = dZ1; a.ldc = H; a.N = H; a.K = G;
-    e = launch_mm<true, MM_MASK>(st, a, B);
-    if (e != hipSuccess) return e;
-    ++n;
     bool folded = false;
-    e = enqueue_weights_update(t, st, &folded);
-    if (e != hipSuccess) return e;
-    ++n;
+    if (dz1_beside_tiles) {
+        a.B = t->w2t; a.B_hi = a.B;
+        a.tiles_per_part = (B + 15u) / 16u;
+        unsigned int launches = 0;
+        e = enqueue_weights_update(t, st, &folded, &a, &launches);
+        if (e != hipSuccess) return e;
+        n += launches;
+    } else {
+        e = launch_mm<true, MM_MASK>(st, a, B);
+        if (e != hipSuccess) return e;
+        ++n;
+        e = enqueue_weights_update(t, st, &folded);
+        if (e != hipSuccess) return e;
+        ++n;
+    }
     unsigned int nh = 0;
     if (!folded) e = enqueue_head_update(t, st, &nh);
     if (count) *count = n + nh;

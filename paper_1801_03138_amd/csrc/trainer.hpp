@@ -278,7 +278,9 @@ hipError_t enqueue_head_update(trainer* t, hipStream_t st, unsigned int* count);
 // The second kernel of the fused step on its own: weight gradients of all three layers from the
 // activations and pre-activation gradients in the workspace, optimizer, mean loss, step counter;
 // a dueling head of up to 32 actions is updated by it too (*folded_head says so).
-hipError_t enqueue_weights_update(trainer* t, hipStream_t st, bool* folded_head);
+struct MmArgs;
+hipError_t enqueue_weights_update(trainer* t, hipStream_t st, bool* folded_head, const MmArgs* dz1 = nullptr,
+                                  unsigned int* launches = nullptr);
 // The weights kernel with the next step's gather in its launch (see trainer::gather_ahead): its
 // __global__ function, replacing the next step's part of a recorded node's arguments, and
 // releasing the recorded argument blocks.

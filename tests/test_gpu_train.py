@@ -326,10 +326,11 @@ def test_many_steps_in_flight(B, dtype, layered, device_src):
     assert pr.step(extra, compare=True) == 0
 
 
-@pytest.mark.parametrize("dtype,H,layered,device_src", [("f32", 64, False, True), ("f32", 64, False, False),
-                                                        ("bf16", 128, False, True), ("f32", 64, True, True),
-                                                        ("f32", 320, False, True), ("f32", 320, False, False)])
-def test_steps_in_flight_equal_steps_synchronised_one_by_one(B, dtype, H, layered, device_src):
+@pytest.mark.parametrize("dtype,H,H2,layered,device_src", [
+    ("f32", 64, 0, False, True), ("f32", 64, 0, False, False), ("bf16", 128, 0, False, True),
+    ("f32", 64, 0, True, True), ("f32", 320, 0, False, True), ("f32", 320, 0, False, False),
+    ("f32", 128, 1024, False, True)])
+def test_steps_in_flight_equal_steps_synchronised_one_by_one(B, dtype, H, H2, layered, device_src):
     """The argument block of the kernel that consumes a step's new experiences is rewritten in
     the recorded graph before every launch, while earlier launches of the same graph may still be
     running.  2,000 steps queued without any synchronisation (32 or 8 steps per graph launch) must
@@ -337,7 +338,8 @@ def test_steps_in_flight_equal_steps_synchronised_one_by_one(B, dtype, H, layere
     every single step (one step per graph launch): ring, weights, moments, counters and the last
     step's sampled slots, bit for bit.  Two-kernel step (device and host arrays), MFMA step,
     layered step, fp32 MFMA step (whose recorded runs gather a step's batch in the launch of
-    the step before it; device and host arrays)."""
+    the step before it; device and host arrays), and the paper's network with a dueling head on
+    that step (where the same launch also holds the product dZ1)."""
     # (the queued side makes the 2,000 steps in calls of these lengths, so that recorded runs of
     # every length, single steps and the hand-over from one run to the next all occur)
     n_steps, per = 2000, 2
@@ -346,8 +348,8 @@ def test_steps_in_flight_equal_steps_synchronised_one_by_one(B, dtype, H, layere
     rows = synth.experiences(n_steps * per, 27, 30, 0.05, seed=51, state_dtype=dtype)
     outs = []
     for one_by_one in (False, True):
-        pr = Pair(B, capacity=1500, D=27, H=H, A=30, batch=64, burn_in=100, seed=5, appends=per,
-                  layered=layered, dtype=dtype, target_sync=9)
+        pr = Pair(B, capacity=1500, D=27, H=H, H2=H2, A=30, batch=64, burn_in=100, seed=5, appends=per,
+                  layered=layered, dtype=dtype, target_sync=9, dueling=H2 != 0)
         d = rows
         if device_src:
             d = {k: torch.from_numpy(v.view(np.int16) if v.dtype == np.uint16 else v).cuda()
