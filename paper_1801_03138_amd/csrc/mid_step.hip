@@ -32,25 +32,147 @@ struct CopyArgs {
     unsigned int n4;
 };
 
+__device__ __forceinline__ void copy_block(const CopyArgs& c, unsigned int block) {
+    const unsigned int i0 = block * 4u * kMmThreads + threadIdx.x;
+    f32x4 x[4];
+#pragma unroll
+    for (unsigned int u = 0; u < 4; ++u) {
+        const unsigned int i = i0 + u * kMmThreads;
+        x[u] = c.src[i < c.n4 ? i : c.n4 - 1u];
+    }
+#pragma unroll
+    for (unsigned int u = 0; u < 4; ++u) {
+        const unsigned int i = i0 + u * kMmThreads;
+        if (i < c.n4) c.dst[i] = x[u];
+    }
+}
+
 template <bool NT, int EPI, bool KSPLIT, int P>
 __global__ __launch_bounds__(kMmThreads) void mm_f32_copy_kernel(MmArgs p, unsigned int tiles_y, CopyArgs c) {
     __shared__ float part[3][64][4];
     if (blockIdx.y >= tiles_y) {
-        const unsigned int i0 = (((blockIdx.y - tiles_y) * gridDim.x + blockIdx.x) * 4u) * kMmThreads + threadIdx.x;
-        f32x4 x[4];
-#pragma unroll
-        for (unsigned int u = 0; u < 4; ++u) {
-            const unsigned int i = i0 + u * kMmThreads;
-            x[u] = c.src[i < c.n4 ? i : c.n4 - 1u];
-        }
-#pragma unroll
-        for (unsigned int u = 0; u < 4; ++u) {
-            const unsigned int i = i0 + u * kMmThreads;
-            if (i < c.n4) c.dst[i] = x[u];
-        }
+        copy_block(c, (blockIdx.y - tiles_y) * gridDim.x + blockIdx.x);
         return;
     }
     mm_f32_block<NT, EPI, KSPLIT, P>(p, blockIdx.x, blockIdx.y, blockIdx.z, part);
+}
+
+// The first two layers in one launch, for a narrow first layer (H = 32 TPW <= 128 units over
+// Dp = 16 NG1 <= 64 inputs): H2 = relu(relu(X W1 + b1) W2 + b2).  A workgroup owns a 32 x 32 tile
+// of H2.  It first works out the 32 x H block of H1 its rows need (every workgroup of a tile row
+// repeats that small product; the one in tile column 0 also stores the block, which the backward
+// pass reads), leaves it in LDS, and contracts it with its 32 columns of W2, whose loads it
+// requested before anything else: the launch takes about as long as the second layer's alone.
+// Operand layout of the MFMA as in mm_tile: lane 16 q + c gives A[row c][k = 16 g + 4 q + j]
+// and B[that k][column c] to MFMA j of group g and receives C[rows 4 q .. 4 q + 3][column c].
+// l1, l2: the two products as a launch of their own would get them (l2.tiles_per_part for
+// 32-row tiles); rows past a part's end repeat its last row and are not stored.
+template <int TPW, int NG1>
+__global__ __launch_bounds__(kMmThreads) void mm_f32_two_layers_kernel(MmArgs l1, MmArgs l2, unsigned int tiles_y,
+                                                                       CopyArgs cp) {
+    constexpr unsigned int H = 32u * TPW, NG2 = H / 16u, LD = H + 4u;
+    __shared__ __attribute__((aligned(16))) float h1s[32][LD];
+    if (blockIdx.y >= tiles_y) {
+        copy_block(cp, (blockIdx.y - tiles_y) * gridDim.x + blockIdx.x);
+        return;
+    }
+    const unsigned int lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const unsigned int c = lane & 15u, q = lane >> 4;
+    const unsigned int part_id = blockIdx.y / l2.tiles_per_part;
+    const unsigned int m_begin = part_id * l2.rows_per_part, m_end = m_begin + l2.rows_per_part;
+    const unsigned int m_tile = m_begin + (blockIdx.y - part_id * l2.tiles_per_part) * 32u;
+    const float* W1 = part_id ? l1.B_hi : l1.B;
+    const float* W2 = part_id ? l2.B_hi : l2.B;
+    const float* bias1 = part_id ? l1.bias_hi : l1.bias;
+    const float* bias2 = part_id ? l2.bias_hi : l2.bias;
+    // second product: this wavefront's quarter (wave >> 1, wave & 1) of the tile; its share of W2
+    const unsigned int n2 = blockIdx.x * 32u + 16u * (wave & 1u) + c;
+    f32x4 b2[NG2];
+#pragma unroll
+    for (unsigned int g = 0; g < NG2; ++g)
+#pragma unroll
+        for (unsigned int j = 0; j < 4; ++j) b2[g][j] = W2[(size_t)(16u * g + 4u * q + j) * l2.ldb + n2];
+    const float bias2_n = bias2[n2];
+    // first product: rows 16 (wave & 1) .., column blocks TPW (wave >> 1) .. + TPW of the H1 block
+    const unsigned int rb = wave & 1u, cb0 = (wave >> 1) * TPW;
+    const unsigned int arow = min(m_tile + 16u * rb + c, m_end - 1u);
+    f32x4 a1[NG1];
+#pragma unroll
+    for (unsigned int g = 0; g < NG1; ++g)
+        a1[g] = *reinterpret_cast<const f32x4*>(l1.A + (size_t)arow * l1.lda + 16u * g + 4u * q);
+    f32x4 b1[TPW][NG1];
+    float bias1_n[TPW];
+#pragma unroll
+    for (unsigned int i = 0; i < TPW; ++i) {
+        const unsigned int n1 = (cb0 + i) * 16u + c;
+#pragma unroll
+        for (unsigned int g = 0; g < NG1; ++g)
+#pragma unroll
+            for (unsigned int j = 0; j < 4; ++j) b1[i][g][j] = W1[(size_t)(16u * g + 4u * q + j) * l1.ldb + n1];
+        bias1_n[i] = bias1[n1];
+    }
+#pragma unroll
+    for (unsigned int i = 0; i < TPW; ++i) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (unsigned int g = 0; g < NG1; ++g)
+#pragma unroll
+            for (unsigned int j = 0; j < 4; ++j)
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a1[g][j], b1[i][g][j], acc, 0, 0, 0);
+        const unsigned int n1 = (cb0 + i) * 16u + c;
+#pragma unroll
+        for (unsigned int v = 0; v < 4; ++v) {
+            float x = acc[v] + bias1_n[i];
+            x = x > 0.f ? x : 0.f;
+            const unsigned int r = 16u * rb + 4u * q + v;
+            h1s[r][n1] = x;
+            if (blockIdx.x == 0 && m_tile + r < m_end) l1.C[(size_t)(m_tile + r) * l1.ldc + n1] = x;
+        }
+    }
+    __syncthreads();
+    const unsigned int r2 = 16u * (wave >> 1);
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (unsigned int g = 0; g < NG2; ++g) {
+        const f32x4 a = *reinterpret_cast<const f32x4*>(&h1s[r2 + c][16u * g + 4u * q]);
+#pragma unroll
+        for (unsigned int j = 0; j < 4; ++j)
+            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[j], b2[g][j], acc, 0, 0, 0);
+    }
+#pragma unroll
+    for (unsigned int v = 0; v < 4; ++v) {
+        const unsigned int m = m_tile + r2 + 4u * q + v;
+        if (m >= m_end) continue;
+        const float x = acc[v] + bias2_n;
+        l2.C[(size_t)m * l2.ldc + n2] = x > 0.f ? x : 0.f;
+    }
+}
+
+// Whether the first two layers run in one launch (mm_f32_two_layers_kernel's shapes).
+bool two_layers_in_one_launch(unsigned int Dp, unsigned int H) { return (Dp == 32u || Dp == 64u) && (H == 64u || H == 128u); }
+
+hipError_t launch_two_layers(hipStream_t st, const MmArgs& l1, const MmArgs& l2, const CopyArgs* copy) {
+    MmArgs p1 = l1, p2 = l2;
+    p2.tiles_per_part = (l2.rows_per_part + 31u) / 32u;
+    p1.tiles_per_part = p2.tiles_per_part;
+    const unsigned int tiles_y = p2.tiles_per_part * l2.parts, nx = l2.N / 32u;
+    CopyArgs c{nullptr, nullptr, 0u};
+    unsigned int cb = 0;
+    if (copy) {
+        c = *copy;
+        cb = (c.n4 + 4u * kMmThreads - 1u) / (4u * kMmThreads);
+    }
+    const dim3 grid(nx, tiles_y + (cb + nx - 1u) / nx, 1), block(kMmThreads);
+    const unsigned int H = l1.N, Dp = l1.K;
+#define RP_TWO_LAYERS(TPW, NG1) \
+    hipLaunchKernelGGL((mm_f32_two_layers_kernel<TPW, NG1>), grid, block, 0, st, p1, p2, tiles_y, c)
+    if (H == 128u && Dp == 32u) RP_TWO_LAYERS(4, 2);
+    else if (H == 128u && Dp == 64u) RP_TWO_LAYERS(4, 4);
+    else if (H == 64u && Dp == 32u) RP_TWO_LAYERS(2, 2);
+    else if (H == 64u && Dp == 64u) RP_TWO_LAYERS(2, 4);
+    else return hipErrorInvalidValue;
+#undef RP_TWO_LAYERS
+    return hipGetLastError();
 }
 
 // Workgroups per tile that share a long contraction with few tiles (their partial products are
@@ -247,6 +369,8 @@ bool mid_step_supported(const train_config& cfg, const replay* rp_) {
            cfg.hidden % 64 == 0 && cfg.hidden2 % 64 == 0;
 }
 
+unsigned int mid_step_kernels(const trainer* t) { return two_layers_in_one_launch(t->Dp, t->H) ? 6u : 7u; }
+
 // Enqueue the step's kernels from the gathered batch on (X = [S ; S'], the per-row fields).
 hipError_t enqueue_mid_step(trainer* t, hipStream_t st, unsigned int* count) {
     const unsigned int B = t->B, H = t->H, G = t->Hb, Dp = t->Dp, Ap = t->Ap;
@@ -270,14 +394,24 @@ hipError_t enqueue_mid_step(trainer* t, hipStream_t st, unsigned int* count) {
     const bool dz1_beside_tiles = dz1_rides_with_tiles(B, H, G);
     const CopyArgs w2_copy{reinterpret_cast<const f32x4*>(w + t->oW2), reinterpret_cast<f32x4*>(t->w2t),
                            H * G / 4u};
-    hipError_t e = launch_mm<false, MM_BIAS_RELU>(st, a, 2u * B, 1, dz1_beside_tiles ? &w2_copy : nullptr);
-    if (e != hipSuccess) return e;
-    ++n;
-    a.A = H1; a.lda = H; a.B = w + t->oW2; a.B_hi = wt + t->oW2; a.ldb = G;
-    a.bias = w + t->ob2; a.bias_hi = wt + t->ob2; a.C = H2; a.ldc = G; a.N = G; a.K = H;
-    e = launch_mm<false, MM_BIAS_RELU>(st, a, 2u * B);
-    if (e != hipSuccess) return e;
-    ++n;
+    hipError_t e;
+    if (two_layers_in_one_launch(Dp, H)) {
+        MmArgs a2 = a;
+        a2.A = H1; a2.lda = H; a2.B = w + t->oW2; a2.B_hi = wt + t->oW2; a2.ldb = G;
+        a2.bias = w + t->ob2; a2.bias_hi = wt + t->ob2; a2.C = H2; a2.ldc = G; a2.N = G; a2.K = H;
+        e = launch_two_layers(st, a, a2, dz1_beside_tiles ? &w2_copy : nullptr);
+        if (e != hipSuccess) return e;
+        ++n;
+    } else {
+        e = launch_mm<false, MM_BIAS_RELU>(st, a, 2u * B, 1, dz1_beside_tiles ? &w2_copy : nullptr);
+        if (e != hipSuccess) return e;
+        ++n;
+        a.A = H1; a.lda = H; a.B = w + t->oW2; a.B_hi = wt + t->oW2; a.ldb = G;
+        a.bias = w + t->ob2; a.bias_hi = wt + t->ob2; a.C = H2; a.ldc = G; a.N = G; a.K = H;
+        e = launch_mm<false, MM_BIAS_RELU>(st, a, 2u * B);
+        if (e != hipSuccess) return e;
+        ++n;
+    }
     a.A = H2; a.lda = G; a.B = w + t->oW3; a.B_hi = wt + t->oW3; a.ldb = Ap;
     a.bias = w + t->ob3; a.bias_hi = wt + t->ob3; a.C = t->Q; a.ldc = Ap; a.N = Ap; a.K = G;
     // a long contraction with few tiles: several workgroups per tile, each a stretch of K; the TD

@@ -1066,7 +1066,7 @@ rp_status train_create(const train_config* cfg, replay_t* rp_, void* dev_workspa
         t->kernels_per_step =
             (t->dueling && !folded_head ? 1u : 0u) + (own_draw ? 1u : 0u) +
             (t->fused ? 2u
-             : t->mid ? 7u
+             : t->mid ? rp::mid_step_kernels(t)
                       : (cfg->appends_per_step ? 1u : 0u) +
                             (t->wide ? (t->wt && cfg->batch % 128 ? 13u : 10u) : (t->wt ? 17u : 14u)));
     }

@@ -297,6 +297,7 @@ hipError_t patch_opt_ahead_node(trainer* t, hipGraphExec_t exec, hipGraphNode_t 
 // hidden widths): one product per kernel.
 bool mid_step_supported(const train_config& cfg, const replay* rp_);
 hipError_t enqueue_mid_step(trainer* t, hipStream_t st, unsigned int* count);
+unsigned int mid_step_kernels(const trainer* t);   // launches per step, the append + gather kernel included
 // Mixed-precision step on MFMA (bf16 replay states and matrix operands).
 bool wide_step_supported(const train_config& cfg, const replay* rp_);
 unsigned int square_splits(unsigned int Bp, unsigned int H);   // K splits of the dW2 product

@@ -824,10 +824,11 @@ def test_dueling_head(B, dtype, H, batch, layered, target_sync, kernels, A):
 
 
 @pytest.mark.parametrize("D,H,H2,A,batch,target_sync,dueling,opt,loss,kernels", [
-    (27, 128, 1024, 30, 128, 6, True, "adam", "huber", 7),     # the paper's network
-    (27, 128, 1024, 30, 130, 4, True, "adam", "huber", 7),     # ... on a batch that ends inside a tile
-    (27, 128, 512, 30, 64, 0, False, "sgd", "mse", 7),
-    (27, 64, 192, 40, 33, 3, True, "adam", "mse", 8),          # head wider than one tile: a kernel of its own
+    (27, 128, 1024, 30, 128, 6, True, "adam", "huber", 6),     # the paper's network
+    (27, 128, 1024, 30, 130, 4, True, "adam", "huber", 6),     # ... on a batch that ends inside a tile
+    (27, 128, 512, 30, 64, 0, False, "sgd", "mse", 6),
+    (40, 64, 512, 30, 77, 3, False, "adam", "huber", 6),       # 64 inputs after padding, first layer of 64
+    (27, 64, 192, 40, 33, 3, True, "adam", "mse", 7),          # head wider than one tile: a kernel of its own
     (70, 320, 64, 5, 50, 0, False, "adam", "huber", 7),
     (27, 512, 512, 30, 256, 5, False, "adam", "huber", 7),
     (9, 1024, 128, 3, 17, 0, True, "sgd", "huber", 7),
@@ -869,7 +870,7 @@ def test_paper_network_step_on_a_given_batch_and_without_appends(B):
     rows = synth.experiences(400, D, A, 0.1, seed=63)
     pr = Pair(B, capacity=300, D=D, H=H, H2=H2, A=A, batch=batch, burn_in=0, seed=1, appends=0,
               dueling=True, target_sync=2, lr=1e-3)
-    assert pr.trainer.kernels_per_step() == 7
+    assert pr.trainer.kernels_per_step() == 6
     pr.append_only(synth.take(rows, 0, 300))
     empty = synth.take(rows, 0, 0)
     for k in range(4):
