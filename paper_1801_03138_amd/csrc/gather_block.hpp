@@ -103,23 +103,21 @@ __device__ __forceinline__ float unit_from_u8(unsigned int b) {
 // kDrawGiven: read from `drawn`, which an earlier kernel filled (see distinct_draw_kernel).
 enum { kDrawUniform = 0, kDrawDistinct = 1, kDrawGiven = 2 };
 
+// gather_pair_rows: batch rows i0 .. i0 + nrows - 1 (nrows <= R); with kDrawGiven, row i0 + rr
+// takes slot number drawn[drawn_at + rr].
 template <int ELEM, int U, int MODE, bool FRESH>
-__device__ __forceinline__ void gather_pair_block(const RingGeom& g, unsigned long long seed,
-                                                  unsigned long long step, unsigned int size,
-                                                  unsigned int batch, unsigned int lane_shift,
-                                                  const GatherOut& o, const Payload& fresh,
-                                                  unsigned long long head, unsigned long long n_fresh,
-                                                  const unsigned int* __restrict__ drawn = nullptr,
-                                                  unsigned int block = blockIdx.x) {
+__device__ __forceinline__ void gather_pair_rows(const RingGeom& g, unsigned long long seed,
+                                                 unsigned long long step, unsigned int size,
+                                                 unsigned int lane_shift, const GatherOut& o,
+                                                 const Payload& fresh, unsigned long long head,
+                                                 unsigned long long n_fresh, const unsigned int* drawn,
+                                                 unsigned int drawn_at, unsigned int i0, unsigned int nrows) {
     constexpr bool DISTINCT = MODE == kDrawDistinct;
     extern __shared__ uint4 smem[];
     unsigned int* idx_s = reinterpret_cast<unsigned int*>(smem);   // distinct mode: R slot numbers
     unsigned char* rows_s = reinterpret_cast<unsigned char*>(smem) + (DISTINCT ? 4 * U * kGatherThreads : 0);
 
     const unsigned int rows_per_pass = kGatherThreads >> lane_shift;
-    const unsigned int R = U * rows_per_pass;
-    const unsigned int i0 = block * R;
-    const unsigned int nrows = min(R, batch - i0);
 
     {
         const unsigned int V = g.row_bytes >> 4;             // 16-byte vectors per row
@@ -140,7 +138,7 @@ __device__ __forceinline__ void gather_pair_block(const RingGeom& g, unsigned lo
         for (int u = 0; u < U; ++u) {
             unsigned int rr = rsub + u * rows_per_pass;
             rr = rr < nrows ? rr : 0u;   // a row past the end re-reads row 0; not stored
-            const unsigned int p = MODE == kDrawGiven ? drawn[i0 + rr]
+            const unsigned int p = MODE == kDrawGiven ? drawn[drawn_at + rr]
                                    : DISTINCT         ? idx_s[rr]
                                                       : uniform_draw(seed, step, i0 + rr, size);
             src[u] = g.rows + (unsigned long long)p * g.row_bytes;
@@ -204,6 +202,20 @@ __device__ __forceinline__ void gather_pair_block(const RingGeom& g, unsigned lo
         if (o.out_r) o.out_r[i] = __uint_as_float(meta[1]);
         if (o.out_term) o.out_term[i] = (unsigned char)meta[2];
     }
+}
+
+template <int ELEM, int U, int MODE, bool FRESH>
+__device__ __forceinline__ void gather_pair_block(const RingGeom& g, unsigned long long seed,
+                                                  unsigned long long step, unsigned int size,
+                                                  unsigned int batch, unsigned int lane_shift,
+                                                  const GatherOut& o, const Payload& fresh,
+                                                  unsigned long long head, unsigned long long n_fresh,
+                                                  const unsigned int* __restrict__ drawn = nullptr,
+                                                  unsigned int block = blockIdx.x) {
+    const unsigned int R = U * (kGatherThreads >> lane_shift);
+    const unsigned int i0 = block * R;
+    gather_pair_rows<ELEM, U, MODE, FRESH>(g, seed, step, size, lane_shift, o, fresh, head, n_fresh, drawn, i0,
+                                           i0, min(R, batch - i0));
 }
 
 

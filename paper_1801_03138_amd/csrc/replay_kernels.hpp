@@ -46,6 +46,6 @@ hipError_t launch_sample_gather(const RingGeom& g, unsigned long long seed,
                                 hipStream_t stream, void* out_s_t = nullptr,
                                 unsigned int out_t_ld = 0, unsigned int size_value = 0,
                                 unsigned long long head_value = 0, unsigned int* draw_scratch = nullptr,
-                                unsigned int* launched = nullptr);
+                                unsigned int* launched = nullptr, bool draw_in_gather = false);
 
 }  // namespace rp

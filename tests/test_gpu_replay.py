@@ -307,8 +307,8 @@ def test_sampling_without_duplicates_every_draw_shape(B, chain):
 
 
 def test_sampling_without_duplicates_at_paper_size(B):
-    """1,000,000 experiences, batch 65,536: the launch shape the bench times; every slot number
-    against the oracle on a sample of positions, all of them distinct."""
+    """1,000,000 experiences, batch 65,536 and the smaller ones: the launch shapes the bench times;
+    every slot number against the oracle on a sample of positions, all of them distinct."""
     C, D = 1_000_000, 27
     gpu = B.Replay(C, D, seed=3, max_append=4096, distinct=True)
     rows = synth.experiences(100_000, D, 30, 0.005, seed=0)
@@ -325,6 +325,18 @@ def test_sampling_without_duplicates_at_paper_size(B):
     # the gathered rows are those slots' rows (the ring holds the 100,000 source rows ten times)
     s = out[0].cpu().numpy()
     assert np.array_equal(s.view(np.uint32), rows["s"][idx % 100_000].view(np.uint32))
+    # the smaller batches the bench times, which draw inside the gather's launch
+    for step, batch in ((8, 128), (9, 2048), (10, 8192)):
+        st, out = gpu.sample_gather(step, batch)
+        assert st == 0
+        torch.cuda.synchronize()
+        idx = out[5].cpu().numpy().view(np.uint32)
+        assert len(np.unique(idx)) == batch
+        for i in list(range(0, batch, 61)) + [batch - 1]:
+            assert idx[i] == oracle.distinct_index(3, step, i, C)
+        s, sn = out[0].cpu().numpy(), out[1].cpu().numpy()
+        assert np.array_equal(s.view(np.uint32), rows["s"][idx % 100_000].view(np.uint32))
+        assert np.array_equal(sn.view(np.uint32), rows["s_next"][idx % 100_000].view(np.uint32))
 
 
 def _random_rings(n, seed):
