@@ -827,6 +827,7 @@ def test_dueling_head(B, dtype, H, batch, layered, target_sync, kernels, A):
     (27, 128, 1024, 30, 128, 6, True, "adam", "huber", 6),     # the paper's network
     (27, 128, 1024, 30, 130, 4, True, "adam", "huber", 6),     # ... on a batch that ends inside a tile
     (27, 128, 512, 30, 64, 0, False, "sgd", "mse", 6),
+    (50, 128, 192, 6, 40, 0, False, "adam", "mse", 6),          # 64 padded inputs into 128 units
     (40, 64, 512, 30, 77, 3, False, "adam", "huber", 6),       # 64 inputs after padding, first layer of 64
     (27, 64, 192, 40, 33, 3, True, "adam", "mse", 7),          # head wider than one tile: a kernel of its own
     (70, 320, 64, 5, 50, 0, False, "adam", "huber", 7),
