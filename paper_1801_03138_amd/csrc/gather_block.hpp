@@ -124,11 +124,26 @@ __device__ __forceinline__ void gather_pair_rows(const RingGeom& g, unsigned lon
         const unsigned int lanes = 1u << lane_shift;         // lanes per row (power of two)
         const unsigned int part0 = threadIdx.x & (lanes - 1u);
         const unsigned int rsub = threadIdx.x >> lane_shift;
-        // A draw without duplicates takes some sixty Philox blocks: one lane per row makes
-        // it and the others pick it up from LDS.
-        if (DISTINCT) {
-            for (unsigned int rr = threadIdx.x; rr < nrows; rr += kGatherThreads)
-                idx_s[rr] = distinct_draw(seed, step, i0 + rr, size);
+        // A draw without duplicates takes some sixty dependent Philox blocks.  Where a row has
+        // sixteen lanes and a thread one row, they make the draw as a team, four rounds at a
+        // time (distinct_draw_team); otherwise one lane per row makes it.  The others pick it
+        // up from LDS.
+        if constexpr (DISTINCT) {
+            if (U == 1 && lane_shift == 4) {
+                __shared__ unsigned int keys[kDistinctTableWords];
+                const unsigned int rounds = distinct_rounds(size);
+                if (threadIdx.x < 64u) {
+                    if (threadIdx.x < kDistinctTableWords - 64u) keys[64u + threadIdx.x] = 0u;
+                    distinct_round_keys(seed, step, size, rounds, threadIdx.x, keys);
+                }
+                __syncthreads();
+                const unsigned int u = distinct_draw_team<4>(seed, step, i0 + (rsub < nrows ? rsub : 0u), size,
+                                                             rounds, keys, threadIdx.x & 63u);
+                if (part0 == 0) idx_s[rsub] = u;
+            } else {
+                for (unsigned int rr = threadIdx.x; rr < nrows; rr += kGatherThreads)
+                    idx_s[rr] = distinct_draw(seed, step, i0 + rr, size);
+            }
             __syncthreads();
         }
         const unsigned char* src[U];

@@ -749,10 +749,13 @@ def test_a_hand_over_that_never_arrives_ends_the_wait_and_is_reported(B):
         assert pr.step(synth.take(rows, k, k + 2), compare=True) == 0
 
 
-@pytest.mark.parametrize("dtype,H,layered", [("f32", 64, False), ("f32", 64, True), ("bf16", 128, False)])
+@pytest.mark.parametrize("dtype,H,layered", [("f32", 64, False), ("f32", 64, True), ("bf16", 128, False),
+                                             ("f32", 320, False)])
 def test_train_step_with_batches_without_duplicates(B, dtype, H, layered):
-    """RP_DISTINCT replay under each kind of train step; with burn-in 10 and batch 40 the first
-    steps are refused until 40 experiences are held."""
+    """RP_DISTINCT replay under each kind of train step (two-kernel, layered, MFMA mixed precision,
+    fp32 MFMA: the last two draw inside their append + gather kernel, one lane per row or, with
+    sixteen lanes per row, as a team); with burn-in 10 and batch 40 the first steps are refused
+    until 40 experiences are held."""
     rows = synth.experiences(300, 27, 30, 0.05, seed=29, state_dtype=dtype)
     pr = Pair(B, capacity=128, D=27, H=H, A=30, batch=40, burn_in=10, seed=8, dtype=dtype,
               appends=2, layered=layered, distinct=True)
