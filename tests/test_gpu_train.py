@@ -833,6 +833,7 @@ def test_dueling_head(B, dtype, H, batch, layered, target_sync, kernels, A):
     (50, 128, 192, 6, 40, 0, False, "adam", "mse", 6),          # 64 padded inputs into 128 units
     (40, 64, 512, 30, 77, 3, False, "adam", "huber", 6),       # 64 inputs after padding, first layer of 64
     (27, 64, 192, 40, 33, 3, True, "adam", "mse", 7),          # head wider than one tile: a kernel of its own
+    (27, 128, 512, 40, 48, 3, True, "adam", "huber", 7),       # ... after the launch that holds the dZ1 product
     (70, 320, 64, 5, 50, 0, False, "adam", "huber", 7),
     (27, 512, 512, 30, 256, 5, False, "adam", "huber", 7),
     (9, 1024, 128, 3, 17, 0, True, "sgd", "huber", 7),
