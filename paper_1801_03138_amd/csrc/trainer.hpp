@@ -172,7 +172,9 @@ struct trainer {
     rp::TrainCounters* ctr;
     float *w, *g, *m, *v;
     float* wt;                       // frozen target network (padded, as w); null without one
-    float* w2t;                      // fp32 steps: W2 transposed, [Hb x H]
+    float* w2t;                      // two-kernel step: W2 transposed, [Hb x H]; fp32 step on MFMA: the copy of W2
+                                     // ([H x Hb], made anew in every step) that the dZ1 product reads while
+                                     // the second layer's tiles update W2 in place
     rp::bf16_t* wb;
     rp::bf16_t* wbt;                 // layered mixed precision: bf16 copy of the target network
     void* X;                         // [2B x Dp]
