@@ -329,7 +329,7 @@ def test_many_steps_in_flight(B, dtype, layered, device_src):
 @pytest.mark.parametrize("dtype,H,H2,layered,device_src", [
     ("f32", 64, 0, False, True), ("f32", 64, 0, False, False), ("bf16", 128, 0, False, True),
     ("f32", 64, 0, True, True), ("f32", 320, 0, False, True), ("f32", 320, 0, False, False),
-    ("f32", 128, 1024, False, True)])
+    ("f32", 128, 1024, False, True), ("f32", 128, 1024, False, False)])
 def test_steps_in_flight_equal_steps_synchronised_one_by_one(B, dtype, H, H2, layered, device_src):
     """The argument block of the kernel that consumes a step's new experiences is rewritten in
     the recorded graph before every launch, while earlier launches of the same graph may still be
