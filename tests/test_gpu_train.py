@@ -945,6 +945,54 @@ def test_random_configurations(B, c):
         assert pr.step(part, compare=True) == 0
 
 
+def test_paper_network_free_running_through_recorded_runs(B, capsys):
+    """The paper's network (27-128-(512+512)-(1+30), dueling head, target network synced every 20
+    updates) for 50 consecutive steps made by ONE train_steps call, i.e. in recorded runs of 32,
+    16 and 2 steps, whose steps gather the next step's batch in their own launches: no teacher
+    forcing, the oracle (fp64) carries its own weights, moments and target network from the same
+    start.  Sampled slots of the last step, step counts and the sync schedule must agree exactly,
+    the weights and the target network within a loose drift bound (see the test below)."""
+    D, H, H2, A, batch, n_steps, sync = 27, 128, 1024, 30, 128, 50, 20
+    oracle.set_threads(16)
+    try:
+        rows = synth.experiences(2000 + n_steps, D, A, 0.01, seed=5)
+        pr = Pair(B, capacity=4096, D=D, H=H, H2=H2, A=A, batch=batch, burn_in=1000, seed=3,
+                  target_sync=sync, dueling=True, lr=1e-4)
+        pr.append_only(synth.take(rows, 0, 2000))
+        tr = pr.trainer
+        assert tr.kernels_per_step() == 6
+        p = tr.params().astype(np.float64)
+        tgt = tr.target().astype(np.float64)
+        m, v, t, step = tr.opt_state()
+        m, v = np.asarray(m, np.float64), np.asarray(v, np.float64)
+        new = synth.take(rows, 2000, 2000 + n_steps)
+        d = {k: torch.from_numpy(x).cuda() for k, x in new.items()}
+        assert tr.steps(n_steps, d["s"], d["s_next"], d["a"], d["r"], d["term"]) == n_steps
+        for k in range(n_steps):
+            part = synth.take(rows, 2000 + k, 2001 + k)
+            pr.ref_ring.append(part["s"], part["s_next"], part["a"], part["r"], part["term"])
+            idx = pr.ref_ring.sample(pr.seed, step + k, batch)
+            s_, sn_, a_, r_, term_ = pr.ref_ring.gather(idx)
+            ref = oracle.train_step(pr.cfg, p, m, v, t + k, s_.astype(np.float64), sn_.astype(np.float64),
+                                    a_, r_, term_, target=tgt)
+            p, m, v = ref.params, ref.m, ref.v
+            tgt = oracle.target_after_step(tgt, p, t + k + 1, sync)
+        assert pr.gpu_ring.state() == pr.ref_ring.state()
+        assert np.array_equal(tr.last()["idx"], idx)
+        assert tr.opt_state()[2:] == (t + n_steps, step + n_steps)
+        scale = np.abs(p).max()
+        drift = float(np.abs(tr.params().astype(np.float64) - p).max() / scale)
+        drift_t = float(np.abs(tr.target().astype(np.float64) - tgt).max() / scale)
+        with capsys.disabled():
+            print("\npaper network, 50 free-running steps in recorded runs: max |w_gpu - w_oracle| / max |w| = "
+                  "%.2e (target network %.2e)" % (drift, drift_t))
+        assert drift <= 1e-4 and drift_t <= 1e-4
+        # the target network is the weights as they were after update 40, not the current ones
+        assert np.abs(tr.target() - tr.params()).max() > 0
+    finally:
+        oracle.set_threads(1)
+
+
 def test_paper_shaped_free_running_drift(B, capsys):
     """100 consecutive steps with no teacher forcing: the GPU (fp32) and the oracle (fp64) each
     carry their own weights and Adam moments from the same start.  The drift of the weights is
