@@ -297,6 +297,28 @@ def test_paper_shaped_config_sampled_steps(B):
     assert all(np.array_equal(x.view(np.uint8), y.view(np.uint8)) for x, y in zip(g, o))
 
 
+def test_paper_network_at_paper_size(B):
+    """The paper's own network (27-128-(512+512)-(1+30), dueling head, target network synced every
+    10,000 updates) on the paper-shaped replay (capacity 1e6, batch 128, burn-in 50,000), the
+    configuration the bench times: a compared step, 1,000 steps queued by one call (recorded runs),
+    then two more compared steps; ring and counters exact."""
+    rows = synth.experiences(52_000, 27, 30, 0.005, seed=0)
+    pr = Pair(B, capacity=1_000_000, D=27, H=128, H2=1024, A=30, batch=128, burn_in=50_000, seed=0,
+              dueling=True, target_sync=10_000)
+    tr = pr.trainer
+    pr.append_only(synth.take(rows, 0, 49_999))
+    assert pr.step(synth.take(rows, 49_999, 50_000), compare=True) == 0
+    new = synth.take(rows, 50_000, 51_000)
+    d = {k: torch.from_numpy(x).cuda() for k, x in new.items()}
+    assert tr.steps(1000, d["s"], d["s_next"], d["a"], d["r"], d["term"]) == 1000
+    pr.ref_ring.append(new["s"], new["s_next"], new["a"], new["r"], new["term"])
+    for k in (51_000, 51_001):
+        assert pr.step(synth.take(rows, k, k + 1), compare=True) == 0
+    assert tr.opt_state()[2:] == (1003, 1003)
+    assert pr.gpu_ring.state() == pr.ref_ring.state() == (51_002, 51_002, 51_002)
+    assert tr.kernels_per_step() == 6
+
+
 @pytest.mark.parametrize("dtype,layered,device_src", [("f32", False, True), ("f32", True, True),
                                                       ("bf16", False, True), ("f32", False, False),
                                                       ("bf16", False, False), ("f32", True, False)])
