@@ -1180,12 +1180,19 @@ rp_status train_steps(trainer_t* t, uint64_t count, const void* s, const void* s
         // several steps in one graph launch when all of them train (new experiences in host
         // memory go through one pinned slot per step)
         const bool host_src = n && !src_is_device;
-        // the longest recorded run that fits what is left (and the staging area, for host arrays)
+        // What is left is made in recorded runs, the short ones first: the longest run (the
+        // longest the staging area takes, for host arrays) as often as it fits, and before
+        // those the powers of two that make up the rest, smallest first.  The GPU then starts
+        // on a call's first steps after few nodes' arguments have been replaced, and the long
+        // runs are prepared while it works.
+        const uint64_t longest = host_src ? rp::kRunStepsHostPayload : rp::kRunStepsMax;
+        const uint64_t rest = (count - k) % longest;
+        const uint64_t want = rest ? (rest & (~rest + 1)) : longest;
         trainer::StepRun* run = nullptr;
         uint64_t K = 0;
         for (unsigned int g = 0; g < rp::kRuns && !run; ++g) {
             const uint64_t steps = rp::kRunSteps[g];
-            if (t->runs[g].exec && steps <= count - k && (!host_src || steps <= rp::kRunStepsHostPayload)) {
+            if (t->runs[g].exec && steps <= want) {
                 run = &t->runs[g];
                 K = steps;
             }
